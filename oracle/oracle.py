@@ -1,0 +1,234 @@
+"""ctypes front end of the plain-C oracle (oracle/strads_oracle.c).
+
+Test infrastructure: only tests/, the smoke check and the benchmark's
+cpu_baseline leg may import this.  Nothing here touches the HIP library.
+All arithmetic lives in the C file; this module marshals numpy arrays and
+keeps the solver state (beta, dbeta, r, round counter) between rounds.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "strads_oracle.c")
+_LIB = os.path.join(_HERE, "libstrads_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  -ffp-contract=off keeps every fp32
+    operation of the specified key arithmetic separately rounded."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Problem(C.Structure):
+    _fields_ = [("N", C.c_int64), ("J", C.c_int64), ("X", C.c_void_p), ("row_idx", C.c_void_p),
+                ("col_ptr", C.c_void_p), ("lam", C.c_float), ("rho", C.c_float), ("eta", C.c_float),
+                ("l_prime", C.c_int32), ("p_max", C.c_int32), ("seed", C.c_uint64)]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        vp, i32, i64, u64, f32, f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float, C.c_double
+        L.oracle_philox4x32_10.argtypes = [vp, vp, vp]
+        L.oracle_philox4x32_10.restype = None
+        L.oracle_uniform.argtypes = [u64, u64, u64]
+        L.oracle_uniform.restype = f32
+        L.oracle_log2_spec.argtypes = [f32]
+        L.oracle_log2_spec.restype = f32
+        L.oracle_priority_key.argtypes = [f32, f32, u64, u64, u64]
+        L.oracle_priority_key.restype = f32
+        L.oracle_priority_keys.argtypes = [i64, vp, f32, u64, u64, vp]
+        L.oracle_priority_keys.restype = None
+        L.oracle_draw.argtypes = [i64, vp, i32, vp]
+        L.oracle_draw.restype = i32
+        L.oracle_gram_dense.argtypes = [i64, vp, vp, i32, vp]
+        L.oracle_gram_dense.restype = None
+        L.oracle_gram_csc.argtypes = [vp, vp, vp, vp, i32, vp]
+        L.oracle_gram_csc.restype = None
+        L.oracle_filter.argtypes = [i32, vp, f32, i32, vp]
+        L.oracle_filter.restype = i32
+        L.oracle_dots_dense.argtypes = [i64, vp, vp, i32, vp, vp]
+        L.oracle_dots_dense.restype = None
+        L.oracle_dots_csc.argtypes = [vp, vp, vp, vp, i32, vp, vp]
+        L.oracle_dots_csc.restype = None
+        L.oracle_soft_threshold.argtypes = [f64, f64]
+        L.oracle_soft_threshold.restype = f64
+        L.oracle_update.argtypes = [i32, vp, vp, f32, vp, vp, vp]
+        L.oracle_update.restype = None
+        L.oracle_residual_dense.argtypes = [i64, vp, vp, i32, vp, vp]
+        L.oracle_residual_dense.restype = None
+        L.oracle_residual_csc.argtypes = [i64, vp, vp, vp, vp, i32, vp, vp]
+        L.oracle_residual_csc.restype = None
+        L.oracle_objective.argtypes = [i64, vp, i64, vp, f32]
+        L.oracle_objective.restype = f64
+        L.oracle_kkt_dense.argtypes = [i64, i64, vp, vp, vp, f32, vp]
+        L.oracle_kkt_dense.restype = f64
+        L.oracle_kkt_csc.argtypes = [i64, vp, vp, vp, vp, vp, f32, vp]
+        L.oracle_kkt_csc.restype = f64
+        L.oracle_round.argtypes = [C.POINTER(_Problem), u64, vp, vp, vp, vp, i32, vp, i32,
+                                   vp, C.POINTER(i32), vp, vp, vp, vp, vp]
+        L.oracle_round.restype = i32
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data
+
+
+def _arr(a, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+# -- thin stage-level wrappers (used by the pin tests and stage-isolated parity) --------------
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c, k = _arr(ctr, np.uint32), _arr(key, np.uint32)
+    out = np.zeros(4, np.uint32)
+    lib().oracle_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def uniform(seed: int, t: int, j: int) -> float:
+    return float(lib().oracle_uniform(seed, t, j))
+
+
+def log2_spec(x: float) -> float:
+    return float(lib().oracle_log2_spec(np.float32(x)))
+
+
+def priority_keys(dbeta, eta, seed, t) -> np.ndarray:
+    d = _arr(dbeta, np.float32)
+    keys = np.empty(d.shape[0], np.float32)
+    lib().oracle_priority_keys(d.shape[0], _p(d), np.float32(eta), seed, t, _p(keys))
+    return keys
+
+
+def draw(keys, l_prime) -> np.ndarray:
+    k = _arr(keys, np.float32)
+    cand = np.empty(max(1, min(int(l_prime), k.shape[0])), np.int32)
+    n = lib().oracle_draw(k.shape[0], _p(k), int(l_prime), _p(cand))
+    if n < 0:
+        raise MemoryError
+    return cand[:n].copy()
+
+
+def gram_dense(x_cols, cand) -> np.ndarray:
+    """x_cols: (J, N) fp32, row j = covariate x_j."""
+    x, c = _arr(x_cols, np.float32), _arr(cand, np.int32)
+    L = c.shape[0]
+    G = np.empty((L, L), np.float32)
+    lib().oracle_gram_dense(x.shape[1], _p(x), _p(c), L, _p(G))
+    return G
+
+
+def gram_csc(values, row_idx, col_ptr, cand) -> np.ndarray:
+    v, ri, cp, c = _arr(values, np.float32), _arr(row_idx, np.int32), _arr(col_ptr, np.int64), _arr(cand, np.int32)
+    L = c.shape[0]
+    G = np.empty((L, L), np.float32)
+    lib().oracle_gram_csc(_p(v), _p(ri), _p(cp), _p(c), L, _p(G))
+    return G
+
+
+def greedy_filter(G, rho, p_max=0) -> np.ndarray:
+    g = _arr(G, np.float32)
+    L = g.shape[0]
+    kept = np.empty(max(L, 1), np.int32)
+    k = lib().oracle_filter(L, _p(g), np.float32(rho), int(p_max), _p(kept))
+    return kept[:k].copy()
+
+
+def soft_threshold(a: float, lam: float) -> float:
+    return float(lib().oracle_soft_threshold(float(a), float(lam)))
+
+
+def objective(r, beta, lam) -> float:
+    rr, b = _arr(r, np.float32), _arr(beta, np.float32)
+    return float(lib().oracle_objective(rr.shape[0], _p(rr), b.shape[0], _p(b), np.float32(lam)))
+
+
+class OracleLasso:
+    """State + rounds of Algorithm 1 on the CPU.  Dense: pass x of shape (J, N)
+    (row j = covariate j).  CSC: pass values,row_idx,col_ptr and n."""
+
+    def __init__(self, y, lam, rho, eta, l_prime, seed=0, p_max=0, c_init=1e6, x=None,
+                 values=None, row_idx=None, col_ptr=None, n=None):
+        self.y = _arr(y, np.float32)
+        if x is not None:
+            self.x = _arr(x, np.float32)
+            self.J, self.N = self.x.shape
+            self.csc = False
+            self.row_idx = self.col_ptr = None
+        else:
+            self.x = _arr(values, np.float32)
+            self.row_idx = _arr(row_idx, np.int32)
+            self.col_ptr = _arr(col_ptr, np.int64)
+            self.J, self.N = self.col_ptr.shape[0] - 1, int(n)
+            self.csc = True
+        assert self.y.shape[0] == self.N
+        self.lam, self.rho, self.eta = np.float32(lam), np.float32(rho), np.float32(eta)
+        self.l_prime, self.p_max, self.seed = min(int(l_prime), self.J), int(p_max), int(seed)
+        # Algorithm 1 initialisation: beta^(t-1) = 0, beta^(t-2) = C  =>  delta beta_j = C for all j
+        self.beta = np.zeros(self.J, np.float32)
+        self.dbeta = np.full(self.J, c_init, np.float32)
+        self.r = self.y.copy()
+        self.t = 0
+        self._prob = _Problem(self.N, self.J, _p(self.x), _p(self.row_idx), _p(self.col_ptr),
+                              self.lam, self.rho, self.eta, self.l_prime, self.p_max, self.seed)
+
+    def set_state(self, beta, dbeta, r, t):
+        self.beta[:] = beta
+        self.dbeta[:] = dbeta
+        self.r[:] = r
+        self.t = int(t)
+
+    def round(self, want_gram=False, forced_cand=None, forced_kept_pos=None) -> dict:
+        Lmax = max(self.l_prime if forced_cand is None else len(forced_cand), 1)
+        cand = np.empty(Lmax, np.int32)
+        kept_pos = np.empty(Lmax, np.int32)
+        kept = np.empty(Lmax, np.int32)
+        z = np.empty(Lmax, np.float64)
+        delta = np.empty(Lmax, np.float64)
+        G = np.empty((Lmax, Lmax), np.float32) if want_gram else None
+        fc = None if forced_cand is None else _arr(forced_cand, np.int32)
+        fk = None if forced_kept_pos is None else _arr(forced_kept_pos, np.int32)
+        ncand = C.c_int32(0)
+        k = lib().oracle_round(C.byref(self._prob), self.t, _p(self.beta), _p(self.dbeta), _p(self.r),
+                               _p(fc), 0 if fc is None else fc.shape[0],
+                               _p(fk), 0 if fk is None else fk.shape[0],
+                               _p(cand), C.byref(ncand), _p(kept_pos), _p(kept), _p(G), _p(z), _p(delta))
+        if k < 0:
+            raise MemoryError("oracle_round allocation failed")
+        L = ncand.value
+        self.t += 1
+        out = {"cand": cand[:L].copy(), "kept_pos": kept_pos[:k].copy(), "kept": kept[:k].copy(),
+               "z": z[:k].copy(), "delta": delta[:k].copy()}
+        if want_gram:
+            out["G"] = G[:L, :L] if L == Lmax else G.reshape(-1)[:L * L].reshape(L, L).copy()
+        return out
+
+    def objective(self) -> float:
+        return objective(self.r, self.beta, self.lam)
+
+    def kkt(self, want_g=False):
+        g = np.empty(self.J, np.float64) if want_g else None
+        if self.csc:
+            v = lib().oracle_kkt_csc(self.J, _p(self.x), _p(self.row_idx), _p(self.col_ptr), _p(self.r),
+                                     _p(self.beta), self.lam, _p(g))
+        else:
+            v = lib().oracle_kkt_dense(self.N, self.J, _p(self.x), _p(self.r), _p(self.beta), self.lam, _p(g))
+        return (float(v), g) if want_g else float(v)
