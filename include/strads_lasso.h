@@ -1,0 +1,172 @@
+/*
+ * strads_lasso.h -- C ABI of the MI355X (gfx950) library for one hot path:
+ * scheduling rounds of SAP/STRADS-scheduled parallel coordinate descent for the
+ * Lasso (Lee, Kim, Ho, Gibson, Xing, "Structure-Aware Dynamic Scheduler for
+ * Parallel Machine Learning", Section 2.1: Algorithm 1, eq. (1), eq. (2)).
+ *
+ * Problem (eq. (1) with squared loss):  min_beta  1/2 ||y - X beta||^2 + lambda ||beta||_1
+ * over a design X (N rows, J columns) whose columns are standardised to unit
+ * l2 norm (dense designs: also zero mean), no intercept.
+ *
+ * One round (Algorithm 1's loop body, Steps 1-4 of Section 2.1):
+ *   1. draw P' = l_prime distinct candidate coordinates, probability proportional
+ *      to (delta beta_j)^2 + eta           (Step 1 with Theorem 1's squared weight)
+ *   2. candidate dependencies |x_a^T x_b|; walk the candidates in draw order and
+ *      keep one iff its dependency with everything kept so far is < rho   (Step 2)
+ *   3. for every kept j, from the SAME residual r = y - X beta:
+ *        beta_j <- S(x_j^T r + beta_j, lambda)                         (eq. (2))
+ *   4. r <- r - sum_j x_j * (change of beta_j);  delta beta_j <- |change|  (Step 4)
+ *
+ * Conventions for every entry point
+ *   - Pointers marked DEVICE are HIP device addresses on the GPU that is current
+ *     when the call is made; pointers marked HOST are ordinary host memory.
+ *   - The library never allocates or frees device memory: the caller supplies one
+ *     workspace (size from strads_lasso_workspace_bytes) and owns X, y and the
+ *     stream.  All of them are borrowed and must outlive the handle.  X and y
+ *     are never written.
+ *   - Every function returns STRADS_OK (0) or a negative STRADS_E_* code; on
+ *     error no output argument is written.  Nothing aborts or throws.
+ *   - Work is enqueued on the caller's stream.  Calls on one handle must not
+ *     overlap (the handle's workspace is shared state).
+ */
+#ifndef STRADS_LASSO_H
+#define STRADS_LASSO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define STRADS_OK                     0
+#define STRADS_E_INVALID_ARG         -1
+#define STRADS_E_WORKSPACE_TOO_SMALL -2
+#define STRADS_E_HIP                 -3   /* a HIP runtime call or kernel launch failed */
+#define STRADS_E_DIVERGED            -4   /* objective is not finite (rho too large can do this) */
+#define STRADS_E_UNSUPPORTED         -5
+
+#define STRADS_LAYOUT_DENSE_COLMAJOR  0   /* x[j*n + i] = X_ij, fp32, leading dimension n */
+#define STRADS_LAYOUT_CSC             1   /* values / row_idx / col_ptr */
+
+#define STRADS_MAX_L_PRIME         8192   /* largest supported candidate count per round */
+
+typedef struct strads_lasso strads_lasso_t;   /* opaque, host side */
+
+typedef struct {
+    int64_t        n;             /* rows N (> 0) */
+    int64_t        j;             /* columns J (> 0, < 2^31) */
+    int32_t        layout;        /* STRADS_LAYOUT_* */
+    const float   *x;             /* DEVICE. dense: n*j values, column-major; CSC: nnz values */
+    const int32_t *row_idx;       /* DEVICE, CSC only: nnz row indices, increasing within a column */
+    const int64_t *col_ptr;       /* DEVICE, CSC only: j+1 offsets, col_ptr[0] = 0 */
+    const float   *y;             /* DEVICE, n values */
+    float          lambda;        /* regularisation weight of eq. (1), >= 0, finite */
+    float          rho;           /* dependency threshold of Step 2, > 0 */
+    float          eta;           /* priority floor of Algorithm 1, >= 1e-30 */
+    float          c_init;        /* Algorithm 1's "very large constant" C: initial delta beta (> 0) */
+    int32_t        l_prime;       /* P': candidates per round, 1..STRADS_MAX_L_PRIME; clamped to j */
+    int32_t        p_max;         /* P: cap on the kept set; 0 = keep every admissible candidate */
+    uint64_t       seed;          /* keys the counter-based random stream with (round, j) */
+    int32_t        keep_gram;     /* nonzero: also store the full fp32 candidate Gram of the last
+                                     round so strads_lasso_last_round can return it (costs
+                                     4*L^2 bytes of workspace and one extra write per round) */
+    void          *workspace;     /* DEVICE, 256-byte aligned, caller-allocated */
+    size_t         workspace_bytes;
+    void          *stream;        /* hipStream_t owned by the caller (NULL = the default stream) */
+} strads_lasso_config_t;
+
+typedef struct {
+    int64_t round;                /* index t of the round this describes (0-based) */
+    int32_t n_cand;               /* |U|  = min(l_prime, j) */
+    int32_t n_kept;               /* |B_1| */
+    int32_t n_moved;              /* kept coordinates whose beta changed */
+    int32_t near_rho_pairs;       /* candidate pairs with | |x_a^T x_b| - rho | <= 1e-6 */
+    float   max_abs_delta;        /* max |change of beta_j| over the kept set */
+} strads_round_info_t;
+
+typedef struct {
+    int64_t rounds_done;          /* rounds executed by this call */
+    int64_t updates_done;         /* sum of |B_1| over those rounds */
+    double  objective;            /* eq. (1) at exit */
+    float   kkt_violation;        /* max_j violation at the last check (absolute) */
+    int32_t converged;            /* 1 iff kkt_violation <= kkt_tol * lambda at exit */
+} strads_run_info_t;
+
+/* Bytes of workspace a configuration needs (depends on n, j, layout, l_prime,
+ * keep_gram only; pointers in cfg are ignored).  Makes no device call.
+ * Returns 0 if cfg is NULL or a size field is invalid. */
+size_t strads_lasso_workspace_bytes(const strads_lasso_config_t *cfg);
+
+/* Validate cfg, carve the workspace and enqueue Algorithm 1's initialisation:
+ * beta = 0, delta beta = c_init for every j, r = y, round counter = 0.
+ * *out receives a host-side handle (free it with strads_lasso_destroy). */
+int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out);
+
+/* Enqueue one round (Algorithm 1's loop body) on the stream.  info == NULL: returns
+ * without synchronising.  info != NULL (HOST): waits for the round and fills it. */
+int strads_lasso_round(strads_lasso_t *h, strads_round_info_t *info);
+
+/* Run rounds until max_rounds have been done or, every check_every rounds
+ * (check_every <= 0: never), the optimality violation of eq. (1)
+ *   v_j = max(|x_j^T r| - lambda, 0)            if beta_j == 0
+ *       = |x_j^T r - lambda * sign(beta_j)|     otherwise
+ * satisfies max_j v_j <= kkt_tol * lambda.  Synchronises at each check and at
+ * exit.  out (HOST, may be NULL) receives the summary.  Returns STRADS_E_DIVERGED
+ * if the objective at exit is not finite. */
+int strads_lasso_run(strads_lasso_t *h, int64_t max_rounds, float kkt_tol, int32_t check_every,
+                     strads_run_info_t *out);
+
+/* Objective of eq. (1) at the current state, 1/2 sum r_i^2 + lambda sum |beta_j|,
+ * accumulated in fp64 from the fp32 state.  Synchronises.  out is HOST. */
+int strads_lasso_objective(strads_lasso_t *h, double *out);
+
+/* max_j v_j (see strads_lasso_run) at the current state.  Streams all of X once.
+ * Synchronises.  max_violation is HOST.  g_or_null (DEVICE, j floats, may be
+ * NULL) receives x_j^T r for every column. */
+int strads_lasso_kkt(strads_lasso_t *h, float *max_violation, float *g_or_null);
+
+/* Copy the solver state out of / into the handle.  All pointers DEVICE
+ * (beta, dbeta: j floats; r: n floats); any may be NULL to skip it.  round is
+ * HOST.  The random stream is a pure function of (seed, round, j), so a state
+ * restored with its round index continues exactly. */
+int strads_lasso_get_state(strads_lasso_t *h, float *beta, float *dbeta, float *r, int64_t *round);
+int strads_lasso_set_state(strads_lasso_t *h, const float *beta, const float *dbeta, const float *r,
+                           int64_t round);
+
+/* Stage outputs of the most recent round, for parity checks.  Output arrays are
+ * DEVICE and sized for l_prime entries (gram_or_null: n_cand*n_cand floats,
+ * row-major, only when the handle was created with keep_gram); any may be NULL.
+ * cand: candidates in draw order; kept_pos: positions into cand of the kept set
+ * (increasing); z: x_j^T r per kept coordinate; delta: change of beta_j per kept
+ * coordinate.  n_cand / n_kept are HOST.  Synchronises. */
+int strads_lasso_last_round(strads_lasso_t *h, int32_t *cand, int32_t *kept_pos, float *z, float *delta,
+                            float *gram_or_null, int32_t *n_cand, int32_t *n_kept);
+
+/* Stage entry: the sampling keys log2(w_j) - log2(-log2 u_j) of Step 1 that round
+ * `round` would use with the current delta beta (j floats, DEVICE). */
+int strads_lasso_stage_keys(strads_lasso_t *h, int64_t round, float *keys_out);
+
+/* Stage entry: run only the dependency filter of Step 2 on a caller-supplied
+ * Gram.  gram: DEVICE, l*l floats row-major (symmetric), 1 <= l <= l_prime.
+ * kept_pos: DEVICE, l ints.  n_kept: HOST.  Uses the handle's rho and p_max and
+ * overwrites the handle's last-round filter outputs.  Synchronises. */
+int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, int32_t *kept_pos,
+                              int32_t *n_kept);
+
+/* Launch-shape knobs for measurement sweeps (never change results except the
+ * fp32 summation order of the Gram when split_k changes):
+ *   "gram_split_k"  0 = automatic, else the number of K-slices per Gram tile
+ *   "select_cap"    boundary-list length above which the sampler's final
+ *                   selection falls back to its multi-pass path (default 16384)
+ * Returns STRADS_E_INVALID_ARG for an unknown name or a value out of range. */
+int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value);
+
+void strads_lasso_destroy(strads_lasso_t *h);
+
+const char *strads_lasso_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STRADS_LASSO_H */

@@ -1,0 +1,6 @@
+"""MI355X-native hot path of SAP/STRADS-scheduled Lasso coordinate descent.
+
+The product is libstrads_lasso.so (hand-written HIP for gfx950, C ABI in
+include/strads_lasso.h); this package is its thin Python binding."""
+from .binding import (StradsLasso, StradsError, RoundInfo, RunInfo, load, LIB_PATH, EXPORTS,  # noqa: F401
+                      strads_lasso_workspace_bytes, LAYOUT_DENSE, LAYOUT_CSC, MAX_L_PRIME)

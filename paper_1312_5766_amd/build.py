@@ -1,0 +1,35 @@
+"""Build libstrads_lasso.so (hand-written HIP for gfx950) in-tree with hipcc."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+INCLUDE = os.path.join(os.path.dirname(HERE), "include")
+LIB = os.path.join(HERE, "libstrads_lasso.so")
+SOURCES = ["api.hip", "sampler.hip", "gram.hip", "filter.hip", "update.hip", "csc.hip"]
+
+
+def build(verbose: bool = False) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
+           "-I", INCLUDE, "-I", CSRC,
+           # packed fp32 instructions are not to be generated on this target
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # the sampling key is specified operation by operation: no contraction
+           "-ffp-contract=off",
+           "-Wall", "-Wno-unused-function",
+           "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode != 0:
+        print(" ".join(cmd))
+        print(res.stdout)
+        print("\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l))
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed building libstrads_lasso.so")
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,339 @@
+// C ABI of libstrads_lasso: argument checking, workspace carving and the order in which the
+// kernels of one round (Algorithm 1's loop body) are enqueued on the caller's stream.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "strads_internal.h"
+
+namespace strads {
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static int split_for_workspace(int64_t n, int32_t lpad)
+{
+    // the automatic choice, but never more than 64 MiB... of slices beyond what a round will use
+    return gram_split_auto(n, lpad);
+}
+
+Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram)
+{
+    Workspace w;
+    memset(&w, 0, sizeof(w));
+    const int64_t lpad = (l + kGramTile - 1) / kGramTile * kGramTile;
+    const int64_t npad = (n + 3) / 4 * 4;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    w.beta = take((size_t)j * 4);
+    w.dbeta = take((size_t)j * 4);
+    w.r = take((size_t)npad * 4);
+    w.keys = take((size_t)j * 4);
+    w.hist = take((size_t)2 * kHistBins * 4);
+    w.scalars = take(sizeof(RoundScalars));
+    w.sel = take((size_t)2 * STRADS_MAX_L_PRIME * 8);
+    w.bnd = take((size_t)j * 8);
+    w.cand = take((size_t)lpad * 4);
+    if (layout == STRADS_LAYOUT_DENSE_COLMAJOR)
+        w.partial = take((size_t)split_for_workspace(n, (int32_t)lpad) * lpad * lpad * 4);
+    else
+        w.partial = take(256);
+    w.gram = take(keep_gram || layout == STRADS_LAYOUT_CSC ? (size_t)lpad * lpad * 4 : 256);
+    w.mask = take((size_t)lpad * (lpad / 64) * 8);
+    w.kept_pos = take((size_t)lpad * 4);
+    w.kept = take((size_t)lpad * 4);
+    w.z = take((size_t)lpad * 4);
+    w.delta = take((size_t)lpad * 4);
+    w.mv_col = take((size_t)lpad * 4);
+    w.mv_delta = take((size_t)lpad * 4);
+    w.rpart = take((size_t)kMaxResidualGroups * npad * 4);
+    w.objpart = take((size_t)kObjBlocks * 8);
+    w.objout = take(8);
+    w.csc_scratch_bytes = layout == STRADS_LAYOUT_CSC ? csc_scratch_bytes(n, (int32_t)lpad) : 0;
+    w.csc_scratch = take(w.csc_scratch_bytes ? w.csc_scratch_bytes : 256);
+    w.total = off;
+    return w;
+}
+
+static bool sizes_ok(const strads_lasso_config_t *c)
+{
+    if (!c) return false;
+    if (c->n <= 0 || c->j <= 0 || c->j >= (int64_t)1 << 31) return false;
+    if (c->layout != STRADS_LAYOUT_DENSE_COLMAJOR && c->layout != STRADS_LAYOUT_CSC) return false;
+    if (c->l_prime < 1 || c->l_prime > STRADS_MAX_L_PRIME) return false;
+    if (c->layout == STRADS_LAYOUT_CSC && c->n >= (int64_t)1 << 31) return false;
+    return true;
+}
+
+static int32_t clamp_l(const strads_lasso_config_t *c)
+{
+    return (int64_t)c->l_prime < c->j ? c->l_prime : (int32_t)c->j;
+}
+
+} // namespace strads
+
+using namespace strads;
+
+#define HIP_TRY(expr) do { if ((expr) != hipSuccess) return STRADS_E_HIP; } while (0)
+
+extern "C" {
+
+size_t strads_lasso_workspace_bytes(const strads_lasso_config_t *cfg)
+{
+    if (!sizes_ok(cfg)) return 0;
+    return carve(cfg->n, cfg->j, cfg->layout, clamp_l(cfg), cfg->keep_gram).total;
+}
+
+int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
+{
+    if (!out || !sizes_ok(cfg)) return STRADS_E_INVALID_ARG;
+    if (!cfg->x || !cfg->y || !cfg->workspace) return STRADS_E_INVALID_ARG;
+    if (cfg->layout == STRADS_LAYOUT_CSC && (!cfg->row_idx || !cfg->col_ptr)) return STRADS_E_INVALID_ARG;
+    if (!(cfg->lambda >= 0.f) || !isfinite(cfg->lambda)) return STRADS_E_INVALID_ARG;
+    if (!(cfg->rho > 0.f) || isnan(cfg->rho)) return STRADS_E_INVALID_ARG;
+    if (!(cfg->eta >= 1e-30f) || !isfinite(cfg->eta)) return STRADS_E_INVALID_ARG;
+    if (!(cfg->c_init > 0.f) || !(cfg->c_init <= 1e18f)) return STRADS_E_INVALID_ARG;
+    if (cfg->p_max < 0) return STRADS_E_INVALID_ARG;
+    if (((uintptr_t)cfg->workspace & 255u) != 0) return STRADS_E_INVALID_ARG;
+    if (((uintptr_t)cfg->x & 3u) != 0 || ((uintptr_t)cfg->y & 3u) != 0) return STRADS_E_INVALID_ARG;
+
+    const int32_t L = clamp_l(cfg);
+    const Workspace ws = carve(cfg->n, cfg->j, cfg->layout, L, cfg->keep_gram);
+    if (cfg->workspace_bytes < ws.total) return STRADS_E_WORKSPACE_TOO_SMALL;
+
+    strads_lasso *h = (strads_lasso *)calloc(1, sizeof(strads_lasso));
+    if (!h) return STRADS_E_INVALID_ARG;
+    h->cfg = *cfg;
+    h->ws = ws;
+    h->base = (char *)cfg->workspace;
+    h->stream = (hipStream_t)cfg->stream;
+    h->L = L;
+    h->Lpad = (L + kGramTile - 1) / kGramTile * kGramTile;
+    h->Npad = (cfg->n + 3) / 4 * 4;
+    h->split_max = cfg->layout == STRADS_LAYOUT_DENSE_COLMAJOR ? gram_split_auto(cfg->n, h->Lpad) : 1;
+    h->split_user = 0;
+    h->select_cap = kSelectCapDefault;
+    h->round = 0;
+    h->vec4 = cfg->layout == STRADS_LAYOUT_DENSE_COLMAJOR && (cfg->n % 4 == 0) && (((uintptr_t)cfg->x & 15u) == 0);
+
+    if (sampler_prepare() != hipSuccess || gram_prepare() != hipSuccess) { free(h); return STRADS_E_HIP; }
+    if (launch_init_state(h) != hipSuccess) {
+        free(h);
+        return STRADS_E_HIP;
+    }
+    *out = h;
+    return STRADS_OK;
+}
+
+void strads_lasso_destroy(strads_lasso_t *h)
+{
+    if (h) free(h);
+}
+
+static int enqueue_round(strads_lasso *h)
+{
+    HIP_TRY(launch_sampler(h, h->round));
+    if (h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR) {
+        HIP_TRY(launch_gram_dense(h));
+        HIP_TRY(launch_filter(h, h->L, true));
+        HIP_TRY(launch_dots_dense(h));
+        HIP_TRY(launch_update(h));
+        HIP_TRY(launch_residual_dense(h));
+    } else {
+        HIP_TRY(launch_gram_csc(h));
+        HIP_TRY(launch_filter(h, h->L, true));
+        HIP_TRY(launch_dots_csc(h));
+        HIP_TRY(launch_update(h));
+        HIP_TRY(launch_residual_csc(h));
+    }
+    h->round += 1;
+    return STRADS_OK;
+}
+
+static int read_scalars(strads_lasso *h, RoundScalars *host)
+{
+    HIP_TRY(hipMemcpyAsync(host, h->base + h->ws.scalars, sizeof(RoundScalars), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(hipStreamSynchronize(h->stream));
+    return STRADS_OK;
+}
+
+int strads_lasso_round(strads_lasso_t *h, strads_round_info_t *info)
+{
+    if (!h) return STRADS_E_INVALID_ARG;
+    const int rc = enqueue_round(h);
+    if (rc != STRADS_OK) return rc;
+    if (info) {
+        RoundScalars sc;
+        const int rs = read_scalars(h, &sc);
+        if (rs != STRADS_OK) return rs;
+        info->round = h->round - 1;
+        info->n_cand = h->L;
+        info->n_kept = sc.n_kept;
+        info->n_moved = sc.n_moved;
+        info->near_rho_pairs = sc.near_rho_pairs;
+        info->max_abs_delta = sc.max_abs_delta;
+    }
+    return STRADS_OK;
+}
+
+int strads_lasso_objective(strads_lasso_t *h, double *out)
+{
+    if (!h || !out) return STRADS_E_INVALID_ARG;
+    HIP_TRY(launch_objective(h));
+    double v = 0.0;
+    HIP_TRY(hipMemcpyAsync(&v, h->base + h->ws.objout, sizeof(double), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(hipStreamSynchronize(h->stream));
+    *out = v;
+    return STRADS_OK;
+}
+
+int strads_lasso_kkt(strads_lasso_t *h, float *max_violation, float *g_or_null)
+{
+    if (!h || !max_violation) return STRADS_E_INVALID_ARG;
+    if (h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR) HIP_TRY(launch_kkt_dense(h, g_or_null));
+    else HIP_TRY(launch_kkt_csc(h, g_or_null));
+    RoundScalars sc;
+    const int rs = read_scalars(h, &sc);
+    if (rs != STRADS_OK) return rs;
+    float v;
+    memcpy(&v, &sc.kkt_max_bits, 4);
+    *max_violation = v;
+    return STRADS_OK;
+}
+
+int strads_lasso_run(strads_lasso_t *h, int64_t max_rounds, float kkt_tol, int32_t check_every,
+                     strads_run_info_t *out)
+{
+    if (!h || max_rounds < 0 || !(kkt_tol >= 0.f)) return STRADS_E_INVALID_ARG;
+    int64_t done = 0;
+    float viol = INFINITY;
+    int converged = 0;
+    // |B_1| is summed on the device; rounds between checks are only enqueued, never waited for
+    RoundScalars sc0;
+    { const int rs = read_scalars(h, &sc0); if (rs != STRADS_OK) return rs; }
+    while (done < max_rounds) {
+        int64_t burst = max_rounds - done;
+        if (check_every > 0 && burst > check_every) burst = check_every;
+        for (int64_t i = 0; i < burst; ++i) {
+            const int rc = enqueue_round(h);
+            if (rc != STRADS_OK) return rc;
+        }
+        done += burst;
+        if (check_every > 0) {
+            const int rc = strads_lasso_kkt(h, &viol, nullptr);
+            if (rc != STRADS_OK) return rc;
+            if (viol <= kkt_tol * h->cfg.lambda) { converged = 1; break; }
+        }
+    }
+    double obj = 0.0;
+    const int rc = strads_lasso_objective(h, &obj);
+    if (rc != STRADS_OK) return rc;
+    RoundScalars sc1;
+    { const int rs = read_scalars(h, &sc1); if (rs != STRADS_OK) return rs; }
+    if (out) {
+        out->rounds_done = done;
+        out->updates_done = (int64_t)(sc1.updates_total - sc0.updates_total);
+        out->objective = obj;
+        out->kkt_violation = viol;
+        out->converged = converged;
+    }
+    return isfinite(obj) ? STRADS_OK : STRADS_E_DIVERGED;
+}
+
+int strads_lasso_get_state(strads_lasso_t *h, float *beta, float *dbeta, float *r, int64_t *round)
+{
+    if (!h) return STRADS_E_INVALID_ARG;
+    if (beta) HIP_TRY(hipMemcpyAsync(beta, h->base + h->ws.beta, (size_t)h->cfg.j * 4, hipMemcpyDeviceToDevice, h->stream));
+    if (dbeta) HIP_TRY(hipMemcpyAsync(dbeta, h->base + h->ws.dbeta, (size_t)h->cfg.j * 4, hipMemcpyDeviceToDevice, h->stream));
+    if (r) HIP_TRY(hipMemcpyAsync(r, h->base + h->ws.r, (size_t)h->cfg.n * 4, hipMemcpyDeviceToDevice, h->stream));
+    HIP_TRY(hipStreamSynchronize(h->stream));
+    if (round) *round = h->round;
+    return STRADS_OK;
+}
+
+int strads_lasso_set_state(strads_lasso_t *h, const float *beta, const float *dbeta, const float *r, int64_t round)
+{
+    if (!h || round < 0) return STRADS_E_INVALID_ARG;
+    if (beta) HIP_TRY(hipMemcpyAsync(h->base + h->ws.beta, beta, (size_t)h->cfg.j * 4, hipMemcpyDeviceToDevice, h->stream));
+    if (dbeta) HIP_TRY(hipMemcpyAsync(h->base + h->ws.dbeta, dbeta, (size_t)h->cfg.j * 4, hipMemcpyDeviceToDevice, h->stream));
+    if (r) HIP_TRY(hipMemcpyAsync(h->base + h->ws.r, r, (size_t)h->cfg.n * 4, hipMemcpyDeviceToDevice, h->stream));
+    HIP_TRY(hipStreamSynchronize(h->stream));
+    h->round = round;
+    return STRADS_OK;
+}
+
+int strads_lasso_last_round(strads_lasso_t *h, int32_t *cand, int32_t *kept_pos, float *z, float *delta,
+                            float *gram_or_null, int32_t *n_cand, int32_t *n_kept)
+{
+    if (!h) return STRADS_E_INVALID_ARG;
+    if (gram_or_null && !h->cfg.keep_gram) return STRADS_E_INVALID_ARG;
+    const size_t lb = (size_t)h->L * 4;
+    if (cand) HIP_TRY(hipMemcpyAsync(cand, h->base + h->ws.cand, lb, hipMemcpyDeviceToDevice, h->stream));
+    if (kept_pos) HIP_TRY(hipMemcpyAsync(kept_pos, h->base + h->ws.kept_pos, lb, hipMemcpyDeviceToDevice, h->stream));
+    if (z) HIP_TRY(hipMemcpyAsync(z, h->base + h->ws.z, lb, hipMemcpyDeviceToDevice, h->stream));
+    if (delta) HIP_TRY(hipMemcpyAsync(delta, h->base + h->ws.delta, lb, hipMemcpyDeviceToDevice, h->stream));
+    if (gram_or_null)
+        HIP_TRY(hipMemcpy2DAsync(gram_or_null, lb, h->base + h->ws.gram, (size_t)h->Lpad * 4, lb, (size_t)h->L,
+                                 hipMemcpyDeviceToDevice, h->stream));
+    RoundScalars sc;
+    const int rs = read_scalars(h, &sc);
+    if (rs != STRADS_OK) return rs;
+    if (n_cand) *n_cand = h->L;
+    if (n_kept) *n_kept = sc.n_kept;
+    return STRADS_OK;
+}
+
+int strads_lasso_stage_keys(strads_lasso_t *h, int64_t round, float *keys_out)
+{
+    if (!h || !keys_out || round < 0) return STRADS_E_INVALID_ARG;
+    HIP_TRY(launch_keys_only(h, round, keys_out));
+    HIP_TRY(hipStreamSynchronize(h->stream));
+    return STRADS_OK;
+}
+
+int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, int32_t *kept_pos, int32_t *n_kept)
+{
+    if (!h || !gram || !kept_pos || !n_kept || l < 1 || l > h->L) return STRADS_E_INVALID_ARG;
+    HIP_TRY(launch_mask_from_gram(h, gram, l));
+    HIP_TRY(launch_filter(h, l, false));
+    RoundScalars sc;
+    const int rs = read_scalars(h, &sc);
+    if (rs != STRADS_OK) return rs;
+    if (sc.n_kept > 0) {
+        HIP_TRY(hipMemcpyAsync(kept_pos, h->base + h->ws.kept_pos, (size_t)sc.n_kept * 4, hipMemcpyDeviceToDevice,
+                               h->stream));
+        HIP_TRY(hipStreamSynchronize(h->stream));
+    }
+    *n_kept = sc.n_kept;
+    return STRADS_OK;
+}
+
+int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
+{
+    if (!h || !name) return STRADS_E_INVALID_ARG;
+    if (strcmp(name, "gram_split_k") == 0) {
+        if (value < 0 || value > h->split_max) return STRADS_E_INVALID_ARG;
+        h->split_user = (int32_t)value;
+        return STRADS_OK;
+    }
+    if (strcmp(name, "select_cap") == 0) {
+        if (value < 1 || value > 2 * STRADS_MAX_L_PRIME) return STRADS_E_INVALID_ARG;
+        h->select_cap = (int32_t)value;
+        return STRADS_OK;
+    }
+    return STRADS_E_INVALID_ARG;
+}
+
+const char *strads_lasso_strerror(int code)
+{
+    switch (code) {
+    case STRADS_OK: return "ok";
+    case STRADS_E_INVALID_ARG: return "invalid argument";
+    case STRADS_E_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case STRADS_E_HIP: return "HIP runtime error";
+    case STRADS_E_DIVERGED: return "objective is not finite";
+    case STRADS_E_UNSUPPORTED: return "not supported";
+    default: return "unknown error";
+    }
+}
+
+} // extern "C"

@@ -1,0 +1,354 @@
+// Step 1 of SAP for the Lasso (Section 2.1, Step 1; Algorithm 1's "draw a set U of P'
+// coefficients"; Theorem 1's weight): draw P' distinct coordinates with probability
+// proportional to w_j = (delta beta_j)^2 + eta.
+//
+// Successive sampling without replacement is done with the Gumbel-top-k identity: the P'
+// largest of  key_j = log2 w_j - log2(-log2 u_j),  u_j uniform in (0,1), ARE such a draw, in
+// draw order.  u_j comes from a counter-based generator (Philox-4x32-10, Salmon et al., SC'11)
+// keyed by (seed, round, j), so a draw never depends on the launch shape.  The fp32 key
+// arithmetic is specified operation by operation (correctly rounded IEEE add / fma only), which
+// makes the key bits, and with them the candidate list, reproducible on any IEEE machine.
+//
+// Selection of the P' largest (key desc, j asc) out of J: MSB-first radix select on the
+// order-preserving 32-bit image of the key, two 11-bit histogram passes, then everything
+// strictly above the 22-bit boundary prefix is appended to the output and the few keys on the
+// boundary prefix are resolved and everything is sorted by one workgroup in LDS.
+#include "strads_internal.h"
+
+namespace strads {
+
+// ---------------------------------------------------------------------------------------------
+// random numbers and the specified log2
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                        uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0;
+        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return c0;
+}
+
+// log2 of a positive normal float: exponent by bit extraction, mantissa folded into
+// [sqrt(1/2), sqrt(2)], then e + f*Q(f) with a fixed degree-8 Q in Horner form.
+__device__ __forceinline__ float log2_spec(float x)
+{
+    const uint32_t bits = __float_as_uint(x);
+    int e = (int)(bits >> 23) - 127;
+    const uint32_t man = bits & 0x007FFFFFu;
+    uint32_t mb;
+    if (man > 0x003504F3u) { mb = man | 0x3F000000u; e += 1; }
+    else                   { mb = man | 0x3F800000u; }
+    const float f = __fsub_rn(__uint_as_float(mb), 1.0f);
+    float q = 0x1.f841dcp-4f;
+    q = __fmaf_rn(q, f, -0x1.a59aeap-3f);
+    q = __fmaf_rn(q, f, 0x1.ba8738p-3f);
+    q = __fmaf_rn(q, f, -0x1.e9d1e6p-3f);
+    q = __fmaf_rn(q, f, 0x1.26d01cp-2f);
+    q = __fmaf_rn(q, f, -0x1.715994p-2f);
+    q = __fmaf_rn(q, f, 0x1.ec73dep-2f);
+    q = __fmaf_rn(q, f, -0x1.715474p-1f);
+    q = __fmaf_rn(q, f, 0x1.715476p+0f);
+    return __fmaf_rn(f, q, (float)e);
+}
+
+__device__ __forceinline__ float priority_key(float dbeta, float eta, uint64_t seed, uint64_t t, uint32_t j)
+{
+    const float w = __fmaf_rn(dbeta, dbeta, eta);
+    const uint32_t x = philox4x32_10_word0(j, 0u, (uint32_t)t, (uint32_t)(t >> 32), (uint32_t)seed,
+                                           (uint32_t)(seed >> 32));
+    const float u = __fmul_rn((float)(2u * (x >> 9) + 1u), 0x1.0p-24f);   // odd multiple of 2^-24, exact
+    const float e = -log2_spec(u);
+    const float key = __fsub_rn(log2_spec(w), log2_spec(e));
+    return __fadd_rn(key, 0.0f);                                          // -0 -> +0
+}
+
+// order-preserving map float -> uint32 (larger float <=> larger integer)
+__device__ __forceinline__ uint32_t orderable(float key)
+{
+    const uint32_t b = __float_as_uint(key);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// ---------------------------------------------------------------------------------------------
+// block helpers (256-thread workgroups unless stated)
+// ---------------------------------------------------------------------------------------------
+// In a histogram whose bins are ordered ascending, find the bin that holds the K-th largest
+// element: above(bin) < K <= above(bin) + hist[bin].  All 256 threads call it; results are
+// returned to all.  tmp: 256 + 2 uint32 of LDS.
+__device__ void find_bin_desc(const uint32_t *__restrict__ hist, uint32_t K, uint32_t *tmp, uint32_t &bin,
+                              uint32_t &above)
+{
+    const int t = threadIdx.x;
+    uint32_t loc[8];
+    uint32_t s = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { loc[i] = hist[8 * t + i]; s += loc[i]; }
+    tmp[t] = s;
+    if (t == 0) { tmp[256] = 0; tmp[257] = 0; }
+    __syncthreads();
+    // inclusive suffix sums over the 256 per-thread totals
+    for (int off = 1; off < 256; off <<= 1) {
+        uint32_t v = (t + off < 256) ? tmp[t + off] : 0u;
+        __syncthreads();
+        tmp[t] += v;
+        __syncthreads();
+    }
+    uint32_t ab = tmp[t] - s;      // elements in bins above this thread's 8 bins
+#pragma unroll
+    for (int i = 7; i >= 0; --i) {
+        if (ab < K && K <= ab + loc[i]) { tmp[256] = 8 * t + i; tmp[257] = ab; }
+        ab += loc[i];
+    }
+    __syncthreads();
+    bin = tmp[256];
+    above = tmp[257];
+    __syncthreads();
+}
+
+// Append one 64-bit item per flagged lane to a global list; one atomic per wavefront.
+__device__ __forceinline__ void wave_append(bool flag, uint64_t item, uint64_t *__restrict__ list,
+                                            uint32_t *__restrict__ counter)
+{
+    const uint64_t m = __ballot(flag);
+    if (m == 0) return;
+    const int lane = __lane_id();
+    uint32_t base = 0;
+    if (lane == __ffsll((long long)m) - 1) base = atomicAdd(counter, (uint32_t)__popcll(m));
+    base = __shfl(base, __ffsll((long long)m) - 1);
+    if (flag) list[base + __popcll(m & ((1ull << lane) - 1ull))] = item;
+}
+
+// ---------------------------------------------------------------------------------------------
+// pass 1: keys + histogram of the top 11 bits
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_keys_hist(const float *__restrict__ dbeta, uint32_t J, float eta,
+                                                   uint64_t seed, uint64_t t, uint32_t *__restrict__ keys,
+                                                   uint32_t *__restrict__ hist0)
+{
+    __shared__ uint32_t lh[kHistBins];
+    for (int i = threadIdx.x; i < kHistBins; i += 256) lh[i] = 0;
+    __syncthreads();
+    for (uint32_t j = blockIdx.x * 256u + threadIdx.x; j < J; j += gridDim.x * 256u) {
+        const uint32_t ok = orderable(priority_key(dbeta[j], eta, seed, t, j));
+        keys[j] = ok;
+        atomicAdd(&lh[ok >> 21], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kHistBins; i += 256)
+        if (lh[i]) atomicAdd(&hist0[i], lh[i]);
+}
+
+__global__ __launch_bounds__(256) void k_keys_only(const float *__restrict__ dbeta, uint32_t J, float eta,
+                                                   uint64_t seed, uint64_t t, float *__restrict__ keys)
+{
+    for (uint32_t j = blockIdx.x * 256u + threadIdx.x; j < J; j += gridDim.x * 256u)
+        keys[j] = priority_key(dbeta[j], eta, seed, t, j);
+}
+
+// pass 2: histogram of the next 11 bits among keys in the boundary bin of pass 1
+__global__ __launch_bounds__(256) void k_hist2(const uint32_t *__restrict__ keys, uint32_t J, uint32_t L,
+                                               const uint32_t *__restrict__ hist0, uint32_t *__restrict__ hist1,
+                                               RoundScalars *__restrict__ sc)
+{
+    __shared__ uint32_t lh[kHistBins];
+    __shared__ uint32_t tmp[258];
+    uint32_t b0, above;
+    find_bin_desc(hist0, L, tmp, b0, above);
+    if (blockIdx.x == 0 && threadIdx.x == 0) { sc->bin0 = b0; sc->rem1 = L - above; }
+    for (int i = threadIdx.x; i < kHistBins; i += 256) lh[i] = 0;
+    __syncthreads();
+    for (uint32_t j = blockIdx.x * 256u + threadIdx.x; j < J; j += gridDim.x * 256u) {
+        const uint32_t ok = keys[j];
+        if ((ok >> 21) == b0) atomicAdd(&lh[(ok >> 10) & 0x7FFu], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kHistBins; i += 256)
+        if (lh[i]) atomicAdd(&hist1[i], lh[i]);
+}
+
+// pass 3: everything strictly above the 22-bit boundary prefix is selected; keys on the prefix
+// go to the boundary list.  Items are (orderable key << 32) | (2^32-1 - j): all distinct, and
+// larger item <=> (larger key, then smaller j).
+__global__ __launch_bounds__(256) void k_collect(const uint32_t *__restrict__ keys, uint32_t J,
+                                                 const uint32_t *__restrict__ hist1, RoundScalars *__restrict__ sc,
+                                                 uint64_t *__restrict__ sel, uint64_t *__restrict__ bnd)
+{
+    __shared__ uint32_t tmp[258];
+    const uint32_t b0 = sc->bin0, rem1 = sc->rem1;
+    uint32_t b1, above;
+    find_bin_desc(hist1, rem1, tmp, b1, above);
+    const uint32_t p22 = (b0 << 11) | b1;
+    if (blockIdx.x == 0 && threadIdx.x == 0) { sc->prefix22 = p22; sc->rem2 = rem1 - above; }
+    const uint32_t jend = ((J + 255u) / 256u) * 256u;      // keep whole wavefronts in the loop
+    for (uint32_t j = blockIdx.x * 256u + threadIdx.x; j < jend; j += gridDim.x * 256u) {
+        const bool in = j < J;
+        const uint32_t ok = in ? keys[j] : 0u;
+        const uint32_t p = ok >> 10;
+        const uint64_t item = ((uint64_t)ok << 32) | (uint64_t)(0xFFFFFFFFu - j);
+        wave_append(in && p > p22, item, sel, &sc->n_sel);
+        wave_append(in && p == p22, item, bnd, &sc->n_bnd);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// final: one workgroup of 1024 threads
+// ---------------------------------------------------------------------------------------------
+__device__ void bitonic_sort_desc(uint64_t *a, uint32_t n /* power of two */)
+{
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t k = 2; k <= n; k <<= 1) {
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            for (uint32_t i = tid; i < n; i += 1024u) {
+                const uint32_t p = i ^ j;
+                if (p > i) {
+                    const uint64_t x = a[i], y = a[p];
+                    const bool desc = (i & k) == 0;
+                    if (desc ? (x < y) : (x > y)) { a[i] = y; a[p] = x; }
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// exclusive rank of a flagged thread among the flagged threads of a 1024-thread block
+__device__ __forceinline__ uint32_t block_rank(bool flag, uint32_t *wave_tot /* 17 */, uint32_t &total)
+{
+    const int lane = __lane_id(), wave = threadIdx.x >> 6;
+    const uint64_t m = __ballot(flag);
+    if (lane == 0) wave_tot[wave] = (uint32_t)__popcll(m);
+    __syncthreads();
+    uint32_t before = 0, tot = 0;
+    for (int w = 0; w < 16; ++w) { const uint32_t c = wave_tot[w]; if (w < wave) before += c; tot += c; }
+    __syncthreads();
+    total = tot;
+    return before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+}
+
+__global__ __launch_bounds__(1024) void k_finalize(RoundScalars *__restrict__ sc, uint64_t *__restrict__ sel,
+                                                   uint64_t *__restrict__ bnd, uint32_t L, uint32_t Lpad,
+                                                   uint32_t cap, int32_t *__restrict__ cand,
+                                                   uint32_t *__restrict__ hist)
+{
+    extern __shared__ uint64_t lds[];
+    __shared__ uint32_t h8[256];
+    __shared__ uint32_t wt[17];
+    __shared__ uint32_t pick[2];
+    const uint32_t tid = threadIdx.x;
+    uint32_t n_sel = sc->n_sel, nb = sc->n_bnd, need = sc->rem2;
+
+    // A. (rare) boundary list longer than the LDS sort can hold: peel 8-bit digits below the
+    //    22-bit prefix until it fits.  Items are distinct, so this always terminates.
+    int shift = 42;
+    while (nb > cap && shift > 0) {
+        const int width = shift < 8 ? shift : 8;
+        shift -= width;
+        const uint32_t dmask = (1u << width) - 1u;
+        if (tid < 256) h8[tid] = 0;
+        __syncthreads();
+        for (uint32_t i = tid; i < nb; i += 1024u) atomicAdd(&h8[(uint32_t)(bnd[i] >> shift) & dmask], 1u);
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t ab = 0; int d = (int)dmask;
+            for (; d > 0; --d) { if (need <= ab + h8[d]) break; ab += h8[d]; }
+            pick[0] = (uint32_t)d; pick[1] = ab;
+        }
+        __syncthreads();
+        const uint32_t d = pick[0], ab = pick[1];
+        uint32_t w_eq = 0, w_gt = n_sel;
+        for (uint32_t s = 0; s < nb; s += 1024u) {
+            const uint32_t i = s + tid;
+            const uint64_t v = i < nb ? bnd[i] : 0ull;
+            const uint32_t dg = (uint32_t)(v >> shift) & dmask;
+            const bool gt = i < nb && dg > d, eq = i < nb && dg == d;
+            uint32_t tg, te;
+            const uint32_t rg = block_rank(gt, wt, tg);
+            const uint32_t re = block_rank(eq, wt, te);   // block_rank's barriers also order the reads above
+            if (gt) sel[w_gt + rg] = v;
+            if (eq) bnd[w_eq + re] = v;                    // w_eq + re <= s + tid: already read
+            w_gt += tg; w_eq += te;
+            __syncthreads();
+        }
+        n_sel += ab; need -= ab; nb = w_eq;
+        __syncthreads();
+    }
+
+    // B. take the `need` largest boundary items
+    if (nb == need) {
+        for (uint32_t i = tid; i < nb; i += 1024u) sel[n_sel + i] = bnd[i];
+    } else {
+        uint32_t p2 = 1; while (p2 < nb) p2 <<= 1;
+        for (uint32_t i = tid; i < p2; i += 1024u) lds[i] = i < nb ? bnd[i] : 0ull;
+        __syncthreads();
+        bitonic_sort_desc(lds, p2);
+        for (uint32_t i = tid; i < need; i += 1024u) sel[n_sel + i] = lds[i];
+    }
+    __threadfence_block();
+    __syncthreads();
+
+    // C. sort the L selected items: descending item = draw order
+    {
+        uint32_t p2 = 1; while (p2 < L) p2 <<= 1;
+        for (uint32_t i = tid; i < p2; i += 1024u) lds[i] = i < L ? sel[i] : 0ull;
+        __syncthreads();
+        bitonic_sort_desc(lds, p2);
+        for (uint32_t i = tid; i < Lpad; i += 1024u)
+            cand[i] = i < L ? (int32_t)(0xFFFFFFFFu - (uint32_t)lds[i]) : 0;
+    }
+
+    // D. leave the histograms and per-round scalars clean for the next round
+    for (uint32_t i = tid; i < 2u * kHistBins; i += 1024u) hist[i] = 0;
+    if (tid == 0) { sc->n_sel = 0; sc->n_bnd = 0; sc->near_rho_pairs = 0; }
+}
+
+// ---------------------------------------------------------------------------------------------
+static inline int sampler_grid(int64_t J)
+{
+    int64_t b = (J + 256 * 4 - 1) / (256 * 4);
+    if (b < 1) b = 1;
+    if (b > 1024) b = 1024;
+    return (int)b;
+}
+
+hipError_t launch_sampler(strads_lasso *h, int64_t round)
+{
+    const uint32_t J = (uint32_t)h->cfg.j, L = (uint32_t)h->L;
+    const int g = sampler_grid(h->cfg.j);
+    uint32_t *keys = h->at<uint32_t>(h->ws.keys);
+    uint32_t *hist = h->at<uint32_t>(h->ws.hist);
+    RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    uint64_t *sel = h->at<uint64_t>(h->ws.sel), *bnd = h->at<uint64_t>(h->ws.bnd);
+    hipLaunchKernelGGL(k_keys_hist, dim3(g), dim3(256), 0, h->stream, h->at<float>(h->ws.dbeta), J, h->cfg.eta,
+                       h->cfg.seed, (uint64_t)round, keys, hist);
+    hipLaunchKernelGGL(k_hist2, dim3(g), dim3(256), 0, h->stream, keys, J, L, hist, hist + kHistBins, sc);
+    hipLaunchKernelGGL(k_collect, dim3(g), dim3(256), 0, h->stream, keys, J, hist + kHistBins, sc, sel, bnd);
+    const uint32_t cap = (uint32_t)h->select_cap;
+    const size_t lds = (size_t)(cap > 2u * STRADS_MAX_L_PRIME ? cap : 2u * STRADS_MAX_L_PRIME) * sizeof(uint64_t);
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(1024), lds, h->stream, sc, sel, bnd, L, (uint32_t)h->Lpad, cap,
+                       h->at<int32_t>(h->ws.cand), hist);
+    return hipGetLastError();
+}
+
+hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys)
+{
+    hipLaunchKernelGGL(k_keys_only, dim3(sampler_grid(h->cfg.j)), dim3(256), 0, h->stream,
+                       h->at<float>(h->ws.dbeta), (uint32_t)h->cfg.j, h->cfg.eta, h->cfg.seed, (uint64_t)round, keys);
+    return hipGetLastError();
+}
+
+hipError_t sampler_prepare()
+{
+    // the final kernel sorts up to 16384 64-bit items in LDS (128 KiB): raise its dynamic-LDS limit
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_finalize),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STRADS_MAX_L_PRIME * 8);
+}
+
+} // namespace strads

@@ -1,0 +1,105 @@
+// Internal declarations shared by the HIP translation units of libstrads_lasso.
+// Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "strads_lasso.h"
+
+namespace strads {
+
+constexpr int kHistBins = 2048;        // 11-bit digits of the orderable 32-bit key
+constexpr int kGramTile = 128;         // candidate-Gram output tile edge (per workgroup)
+constexpr int kGramKT = 32;            // K (row) extent of one LDS stage, floats
+constexpr int kMaxResidualGroups = 64; // column groups of the residual update
+constexpr int kObjBlocks = 256;        // workgroups of the objective reduction
+constexpr int kSelectCapDefault = 16384;
+
+// Device-side scalars of one round, kept in one small block of the workspace.
+struct RoundScalars {
+    unsigned long long updates_total;   // sum of |B_1| over all rounds since create
+    uint32_t n_sel;        // keys strictly above the 22-bit boundary prefix
+    uint32_t n_bnd;        // keys on the boundary prefix
+    uint32_t bin0, rem1;   // first digit of the L'-th key, rank still to find below it
+    uint32_t prefix22, rem2;
+    int32_t n_kept;
+    int32_t n_moved;
+    int32_t near_rho_pairs;
+    float max_abs_delta;
+    uint32_t kkt_max_bits; // float bits of the running max violation (>= 0, so uint order = float order)
+    uint32_t pad;
+};
+
+struct Workspace {
+    // offsets in bytes from the workspace base
+    size_t beta, dbeta, r;
+    size_t keys;            // uint32 [J]
+    size_t hist;            // uint32 [2][kHistBins]
+    size_t scalars;         // RoundScalars
+    size_t sel;             // uint64 [2 * STRADS_MAX_L_PRIME]
+    size_t bnd;             // uint64 [J]
+    size_t cand;            // int32 [Lpad]
+    size_t partial;         // float [split_max][Lpad][Lpad]   (dense Gram K-slices)
+    size_t gram;            // float [Lpad][Lpad] (keep_gram only)
+    size_t mask;            // uint64 [Lpad][Lpad/64]
+    size_t kept_pos, kept;  // int32 [Lpad]
+    size_t z, delta;        // float [Lpad]
+    size_t mv_col;          // int32 [Lpad]
+    size_t mv_delta;        // float [Lpad]
+    size_t rpart;           // float [kMaxResidualGroups][Npad]
+    size_t objpart;         // double [kObjBlocks]
+    size_t objout;          // double [1]
+    size_t csc_scratch;     // CSC only: see csc.hip
+    size_t csc_scratch_bytes;
+    size_t total;
+};
+
+} // namespace strads
+
+struct strads_lasso {
+    strads_lasso_config_t cfg;
+    strads::Workspace ws;
+    char *base;
+    hipStream_t stream;
+    int32_t L;          // min(l_prime, J)
+    int32_t Lpad;       // L rounded up to the Gram tile
+    int64_t Npad;       // N rounded up to 4
+    int32_t split_max;  // K-slices the workspace was sized for
+    int32_t split_user; // tuning override (0 = automatic)
+    int32_t select_cap;
+    int64_t round;
+    bool vec4;          // dense columns are 16-byte aligned (N % 4 == 0 and x aligned)
+
+    template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(base + off); }
+};
+
+namespace strads {
+
+int gram_split_auto(int64_t n, int32_t lpad);
+Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram);
+
+// Each launcher enqueues on h->stream and returns the hipError_t of the launch.
+hipError_t launch_sampler(strads_lasso *h, int64_t round);                 // Step 1 -> cand[L]
+hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys);  // stage entry
+hipError_t launch_gram_dense(strads_lasso *h);                             // Step 2a -> mask (and gram)
+hipError_t launch_mask_from_gram(strads_lasso *h, const float *gram, int32_t l);
+hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates);                    // Step 2b -> kept_pos, kept, n_kept
+hipError_t launch_dots_dense(strads_lasso *h);                             // x_j^T r for the kept set
+hipError_t launch_update(strads_lasso *h);                                 // eq. (2) + bookkeeping
+hipError_t launch_residual_dense(strads_lasso *h);                         // r -= X_B delta_B
+hipError_t launch_objective(strads_lasso *h);                              // -> objout
+hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null);            // -> scalars.kkt_max_bits
+hipError_t launch_init_state(strads_lasso *h);
+hipError_t launch_clear_kkt(strads_lasso *h);
+hipError_t sampler_prepare();
+hipError_t gram_prepare();
+// CSC design
+hipError_t launch_gram_csc(strads_lasso *h);
+hipError_t launch_dots_csc(strads_lasso *h);
+hipError_t launch_residual_csc(strads_lasso *h);
+hipError_t launch_kkt_csc(strads_lasso *h, float *g_or_null);
+size_t csc_scratch_bytes(int64_t n, int32_t l);
+
+} // namespace strads

@@ -1,0 +1,351 @@
+// The worker side of Algorithm 1 for a dense column-major design: eq. (2) evaluated for every
+// kept coordinate from the SAME residual r = y - X beta (with unit-norm columns
+//   x_j^T y - sum_{k != j} x_j^T x_k beta_k  =  x_j^T r + beta_j ),
+// the soft-threshold S(a, lambda) = sign(a) max(|a| - lambda, 0), Step 4's bookkeeping
+// (delta beta_j <- |change|), the residual update r <- r - sum_j x_j * change_j, the objective of
+// eq. (1) and the optimality (KKT) check used as stopping rule.
+//
+// All of these stream columns of X once; they are HBM-bandwidth work: 16-byte coalesced loads
+// along a column, fp32 FMA, fixed-order reductions (no floating-point atomics), so results are
+// reproducible run to run.
+#include "strads_internal.h"
+
+namespace strads {
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
+    return v;                                   // lane 0 holds the sum
+}
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
+    return v;
+}
+
+// dot product of one column with r by TPC threads (TPC = 64: one wavefront, 256: a workgroup)
+template <int TPC, bool VEC4>
+__device__ __forceinline__ float column_dot(const float *__restrict__ x, const float *__restrict__ r, int64_t N,
+                                            int t, float *red /* TPC/64 floats of LDS, TPC > 64 only */)
+{
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (VEC4) {
+        const float4 *x4 = reinterpret_cast<const float4 *>(x);
+        const float4 *r4 = reinterpret_cast<const float4 *>(r);
+        const int64_t n4 = N >> 2;
+        int64_t i = t;
+        for (; i + 3 * TPC < n4; i += 4 * TPC) {
+            const float4 a0 = x4[i], a1 = x4[i + TPC], a2 = x4[i + 2 * TPC], a3 = x4[i + 3 * TPC];
+            const float4 b0 = r4[i], b1 = r4[i + TPC], b2 = r4[i + 2 * TPC], b3 = r4[i + 3 * TPC];
+            s0 += a0.x * b0.x + a0.y * b0.y + a0.z * b0.z + a0.w * b0.w;
+            s1 += a1.x * b1.x + a1.y * b1.y + a1.z * b1.z + a1.w * b1.w;
+            s2 += a2.x * b2.x + a2.y * b2.y + a2.z * b2.z + a2.w * b2.w;
+            s3 += a3.x * b3.x + a3.y * b3.y + a3.z * b3.z + a3.w * b3.w;
+        }
+        for (; i < n4; i += TPC) {
+            const float4 a = x4[i], b = r4[i];
+            s0 += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+        }
+    } else {
+        for (int64_t i = t; i < N; i += TPC) s0 += x[i] * r[i];
+    }
+    float s = wave_sum((s0 + s1) + (s2 + s3));
+    if (TPC > 64) {
+        if ((t & 63) == 0) red[t >> 6] = s;
+        __syncthreads();
+        s = 0.f;
+        if (t == 0) for (int w = 0; w < TPC / 64; ++w) s += red[w];
+    }
+    return s;                                   // valid in thread 0 of the group
+}
+
+// z[c] = x_{kept[c]}^T r for c < n_kept.  Launched for the worst case (L columns); groups past
+// the device-side count exit.
+template <int TPC, bool VEC4>
+__global__ __launch_bounds__(256) void k_dots(const float *__restrict__ X, int64_t N, const int32_t *__restrict__ kept,
+                                              const RoundScalars *__restrict__ sc, const float *__restrict__ r,
+                                              float *__restrict__ z)
+{
+    __shared__ float red[4];
+    constexpr int CPB = 256 / TPC;              // columns per workgroup
+    const int c = blockIdx.x * CPB + threadIdx.x / TPC;
+    if (TPC == 256) { if (c >= sc->n_kept) return; }
+    const bool on = c < sc->n_kept;
+    if (TPC == 64 && !on) return;               // whole wavefront
+    const float s = column_dot<TPC, VEC4>(X + (int64_t)kept[c] * N, r, N, threadIdx.x % TPC, red);
+    if (threadIdx.x % TPC == 0) z[c] = s;
+}
+
+__device__ __forceinline__ float soft_threshold(float a, float lambda)
+{
+    const float m = fabsf(a) - lambda;
+    return m > 0.f ? copysignf(m, a) : 0.f;
+}
+
+// eq. (2) + Step 4 for the kept set, and the ordered list of coordinates that actually moved.
+__global__ __launch_bounds__(1024) void k_update(const int32_t *__restrict__ kept, const float *__restrict__ z,
+                                                 float lambda, float *__restrict__ beta, float *__restrict__ dbeta,
+                                                 float *__restrict__ delta, int32_t *__restrict__ mv_col,
+                                                 float *__restrict__ mv_delta, RoundScalars *__restrict__ sc)
+{
+    __shared__ uint32_t wt[16];
+    __shared__ float wm[16];
+    const int n = sc->n_kept;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t base = 0;
+    float mx = 0.f;
+    for (int s = 0; s < n; s += 1024) {
+        const int c = s + threadIdx.x;
+        float d = 0.f;
+        int32_t j = 0;
+        if (c < n) {
+            j = kept[c];
+            const float b = beta[j];
+            const float nb = soft_threshold(z[c] + b, lambda);
+            d = nb - b;
+            beta[j] = nb;
+            dbeta[j] = fabsf(d);
+            delta[c] = d;
+            mx = fmaxf(mx, fabsf(d));
+        }
+        const bool mv = c < n && d != 0.f;
+        const uint64_t m = __ballot(mv);
+        if (lane == 0) wt[wave] = (uint32_t)__popcll(m);
+        __syncthreads();
+        uint32_t before = 0, tot = 0;
+        for (int w = 0; w < 16; ++w) { const uint32_t v = wt[w]; if (w < wave) before += v; tot += v; }
+        if (mv) {
+            const uint32_t p = base + before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            mv_col[p] = j;
+            mv_delta[p] = d;
+        }
+        base += tot;
+        __syncthreads();
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_down(mx, off));
+    if (lane == 0) wm[wave] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float m = 0.f;
+        for (int w = 0; w < 16; ++w) m = fmaxf(m, wm[w]);
+        sc->n_moved = (int32_t)base;
+        sc->max_abs_delta = m;
+    }
+}
+
+// Residual update, stage 1: column group g sums its share of x_j * change_j for 4 rows per
+// thread, in list order.  part[g][i].
+template <bool VEC4>
+__global__ __launch_bounds__(256) void k_residual_partial(const float *__restrict__ X, int64_t N, int64_t Npad,
+                                                          const int32_t *__restrict__ mv_col,
+                                                          const float *__restrict__ mv_delta,
+                                                          const RoundScalars *__restrict__ sc, float *__restrict__ part)
+{
+    const int m = sc->n_moved;
+    const int G = gridDim.y, g = blockIdx.y;
+    const int c0 = (int)((int64_t)m * g / G), c1 = (int)((int64_t)m * (g + 1) / G);
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= N) return;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (VEC4) {
+        int c = c0;
+        for (; c + 3 < c1; c += 4) {
+            const float4 v0 = *reinterpret_cast<const float4 *>(X + (int64_t)mv_col[c] * N + i);
+            const float4 v1 = *reinterpret_cast<const float4 *>(X + (int64_t)mv_col[c + 1] * N + i);
+            const float4 v2 = *reinterpret_cast<const float4 *>(X + (int64_t)mv_col[c + 2] * N + i);
+            const float4 v3 = *reinterpret_cast<const float4 *>(X + (int64_t)mv_col[c + 3] * N + i);
+            const float d0 = mv_delta[c], d1 = mv_delta[c + 1], d2 = mv_delta[c + 2], d3 = mv_delta[c + 3];
+            acc.x += v0.x * d0; acc.y += v0.y * d0; acc.z += v0.z * d0; acc.w += v0.w * d0;
+            acc.x += v1.x * d1; acc.y += v1.y * d1; acc.z += v1.z * d1; acc.w += v1.w * d1;
+            acc.x += v2.x * d2; acc.y += v2.y * d2; acc.z += v2.z * d2; acc.w += v2.w * d2;
+            acc.x += v3.x * d3; acc.y += v3.y * d3; acc.z += v3.z * d3; acc.w += v3.w * d3;
+        }
+        for (; c < c1; ++c) {
+            const float4 v = *reinterpret_cast<const float4 *>(X + (int64_t)mv_col[c] * N + i);
+            const float d = mv_delta[c];
+            acc.x += v.x * d; acc.y += v.y * d; acc.z += v.z * d; acc.w += v.w * d;
+        }
+    } else {
+        for (int c = c0; c < c1; ++c) {
+            const float *x = X + (int64_t)mv_col[c] * N + i;
+            const float d = mv_delta[c];
+            acc.x += x[0] * d;
+            if (i + 1 < N) acc.y += x[1] * d;
+            if (i + 2 < N) acc.z += x[2] * d;
+            if (i + 3 < N) acc.w += x[3] * d;
+        }
+    }
+    *reinterpret_cast<float4 *>(part + (int64_t)g * Npad + i) = acc;
+}
+
+// stage 2: r[i] -= sum_g part[g][i], groups in order
+__global__ __launch_bounds__(256) void k_residual_apply(const float *__restrict__ part, int G, int64_t N, int64_t Npad,
+                                                        const RoundScalars *__restrict__ sc, float *__restrict__ r)
+{
+    if (sc->n_moved == 0) return;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= N) return;
+    float s = 0.f;
+    for (int g = 0; g < G; ++g) s += part[(int64_t)g * Npad + i];
+    r[i] -= s;
+}
+
+// eq. (1): 1/2 sum r_i^2 + lambda sum |beta_j|, fp64 accumulation, two fixed-order stages
+__global__ __launch_bounds__(256) void k_objective_partial(const float *__restrict__ r, int64_t N,
+                                                           const float *__restrict__ beta, int64_t J, double lambda,
+                                                           double *__restrict__ part)
+{
+    __shared__ double red[4];
+    double s = 0.0;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < N; i += stride) { const double v = r[i]; s += 0.5 * v * v; }
+    for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < J; j += stride) s += lambda * fabs((double)beta[j]);
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) part[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(256) void k_objective_final(const double *__restrict__ part, int n, double *__restrict__ out)
+{
+    __shared__ double red[4];
+    double s = threadIdx.x < n ? part[threadIdx.x] : 0.0;
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) *out = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// Optimality violation of eq. (1) per column and its maximum (integer atomicMax on the float
+// bits of a non-negative number: order-preserving and deterministic).
+template <int TPC, bool VEC4>
+__global__ __launch_bounds__(256) void k_kkt(const float *__restrict__ X, int64_t N, int64_t J,
+                                             const float *__restrict__ r, const float *__restrict__ beta, float lambda,
+                                             float *__restrict__ g_out, RoundScalars *__restrict__ sc)
+{
+    __shared__ float red[4];
+    constexpr int CPB = 256 / TPC;
+    const int64_t j = (int64_t)blockIdx.x * CPB + threadIdx.x / TPC;
+    if (j >= J) return;                         // TPC = 64: whole wavefront; TPC = 256: whole workgroup
+    const float g = column_dot<TPC, VEC4>(X + j * N, r, N, threadIdx.x % TPC, red);
+    if (threadIdx.x % TPC == 0) {
+        if (g_out) g_out[j] = g;
+        const float b = beta[j];
+        float v;
+        if (b == 0.f) v = fmaxf(fabsf(g) - lambda, 0.f);
+        else v = fabsf(g - copysignf(lambda, b));
+        if (!(v == v)) v = __uint_as_float(0x7F800000u);     // NaN counts as an infinite violation
+        atomicMax(&sc->kkt_max_bits, __float_as_uint(v));
+    }
+}
+
+__global__ __launch_bounds__(256) void k_init_state(const float *__restrict__ y, int64_t N, int64_t J, float c_init,
+                                                    float *__restrict__ beta, float *__restrict__ dbeta,
+                                                    float *__restrict__ r, uint32_t *__restrict__ hist,
+                                                    uint32_t *__restrict__ scalars_words, int n_scalar_words)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    // histograms and round scalars start at zero (the sampler's last kernel re-zeroes them every round)
+    if (blockIdx.x == 0) {
+        for (int i = threadIdx.x; i < 2 * kHistBins; i += 256) hist[i] = 0u;
+        for (int i = threadIdx.x; i < n_scalar_words; i += 256) scalars_words[i] = 0u;
+    }
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < N; i += stride) r[i] = y[i];
+    for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < J; j += stride) { beta[j] = 0.f; dbeta[j] = c_init; }
+}
+
+__global__ void k_clear_kkt(RoundScalars *sc) { sc->kkt_max_bits = 0u; }
+
+// ---------------------------------------------------------------------------------------------
+hipError_t launch_dots_dense(strads_lasso *h)
+{
+    const RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    const float *r = h->at<float>(h->ws.r);
+    float *z = h->at<float>(h->ws.z);
+    const int32_t *kept = h->at<int32_t>(h->ws.kept);
+    const bool wide = h->cfg.n > 2048;
+    const unsigned grid = wide ? (unsigned)h->L : (unsigned)((h->L + 3) / 4);
+#define STRADS_DOTS(TPC, V) hipLaunchKernelGGL((k_dots<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, kept, sc, r, z)
+    if (wide) { if (h->vec4) STRADS_DOTS(256, true); else STRADS_DOTS(256, false); }
+    else      { if (h->vec4) STRADS_DOTS(64, true);  else STRADS_DOTS(64, false); }
+#undef STRADS_DOTS
+    return hipGetLastError();
+}
+
+hipError_t launch_update(strads_lasso *h)
+{
+    hipLaunchKernelGGL(k_update, dim3(1), dim3(1024), 0, h->stream, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.z),
+                       h->cfg.lambda, h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.delta),
+                       h->at<int32_t>(h->ws.mv_col), h->at<float>(h->ws.mv_delta), h->at<RoundScalars>(h->ws.scalars));
+    return hipGetLastError();
+}
+
+static int residual_groups(const strads_lasso *h)
+{
+    const int64_t rowblocks = (h->cfg.n + 1023) / 1024;
+    int64_t G = 2048 / rowblocks;
+    if (G > kMaxResidualGroups) G = kMaxResidualGroups;
+    if (G > h->L) G = h->L;
+    if (G < 1) G = 1;
+    return (int)G;
+}
+
+hipError_t launch_residual_dense(strads_lasso *h)
+{
+    const RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    const int G = residual_groups(h);
+    const dim3 grid((unsigned)((h->cfg.n + 1023) / 1024), (unsigned)G);
+    float *part = h->at<float>(h->ws.rpart);
+    if (h->vec4)
+        hipLaunchKernelGGL(k_residual_partial<true>, grid, dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->Npad,
+                           h->at<int32_t>(h->ws.mv_col), h->at<float>(h->ws.mv_delta), sc, part);
+    else
+        hipLaunchKernelGGL(k_residual_partial<false>, grid, dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->Npad,
+                           h->at<int32_t>(h->ws.mv_col), h->at<float>(h->ws.mv_delta), sc, part);
+    hipLaunchKernelGGL(k_residual_apply, dim3((unsigned)((h->cfg.n + 255) / 256)), dim3(256), 0, h->stream, part, G,
+                       h->cfg.n, h->Npad, sc, h->at<float>(h->ws.r));
+    return hipGetLastError();
+}
+
+hipError_t launch_objective(strads_lasso *h)
+{
+    double *part = h->at<double>(h->ws.objpart);
+    hipLaunchKernelGGL(k_objective_partial, dim3(kObjBlocks), dim3(256), 0, h->stream, h->at<float>(h->ws.r), h->cfg.n,
+                       h->at<float>(h->ws.beta), h->cfg.j, (double)h->cfg.lambda, part);
+    hipLaunchKernelGGL(k_objective_final, dim3(1), dim3(256), 0, h->stream, part, kObjBlocks,
+                       h->at<double>(h->ws.objout));
+    return hipGetLastError();
+}
+
+hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null)
+{
+    RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    hipLaunchKernelGGL(k_clear_kkt, dim3(1), dim3(1), 0, h->stream, sc);
+    const bool wide = h->cfg.n > 2048;
+    const unsigned grid = wide ? (unsigned)h->cfg.j : (unsigned)((h->cfg.j + 3) / 4);
+#define STRADS_KKT(TPC, V) hipLaunchKernelGGL((k_kkt<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->cfg.j, h->at<float>(h->ws.r), h->at<float>(h->ws.beta), h->cfg.lambda, g_or_null, sc)
+    if (wide) { if (h->vec4) STRADS_KKT(256, true); else STRADS_KKT(256, false); }
+    else      { if (h->vec4) STRADS_KKT(64, true);  else STRADS_KKT(64, false); }
+#undef STRADS_KKT
+    return hipGetLastError();
+}
+
+hipError_t launch_clear_kkt(strads_lasso *h)
+{
+    hipLaunchKernelGGL(k_clear_kkt, dim3(1), dim3(1), 0, h->stream, h->at<RoundScalars>(h->ws.scalars));
+    return hipGetLastError();
+}
+
+hipError_t launch_init_state(strads_lasso *h)
+{
+    hipLaunchKernelGGL(k_init_state, dim3(1024), dim3(256), 0, h->stream, h->cfg.y, h->cfg.n, h->cfg.j, h->cfg.c_init,
+                       h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.r),
+                       h->at<uint32_t>(h->ws.hist), h->at<uint32_t>(h->ws.scalars), (int)(sizeof(RoundScalars) / 4));
+    return hipGetLastError();
+}
+
+} // namespace strads

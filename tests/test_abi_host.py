@@ -1,0 +1,87 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function the
+header declares, sizes workspaces, and rejects bad arguments before any device call."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_1312_5766_amd as pk
+from paper_1312_5766_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "strads_lasso.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(strads_lasso_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = pk.load()
+    names = _declared_functions()
+    assert len(names) >= 14
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(pk.EXPORTS) == names
+
+
+def test_workspace_bytes_scales_and_rejects():
+    small = pk.strads_lasso_workspace_bytes(1000, 5000, 200)
+    big = pk.strads_lasso_workspace_bytes(10000, 100000, 1000)
+    assert 0 < small < big < 1 << 30
+    assert pk.strads_lasso_workspace_bytes(1000, 5000, 200, keep_gram=True) > small
+    assert pk.strads_lasso_workspace_bytes(0, 5000, 200) == 0
+    assert pk.strads_lasso_workspace_bytes(1000, 0, 200) == 0
+    assert pk.strads_lasso_workspace_bytes(1000, 5000, 0) == 0
+    assert pk.strads_lasso_workspace_bytes(1000, 5000, pk.MAX_L_PRIME + 1) == 0
+    assert pk.strads_lasso_workspace_bytes(1000, 1 << 31, 200) == 0
+    assert pk.load().strads_lasso_workspace_bytes(None) == 0
+    # l_prime larger than j is clamped, not rejected
+    assert pk.strads_lasso_workspace_bytes(100, 50, 200) == pk.strads_lasso_workspace_bytes(100, 50, 50)
+
+
+def _cfg(**kw):
+    base = dict(n=100, j=50, layout=0, x=256, y=256, lam=0.1, rho=0.1, eta=1e-6, c_init=1e6, l_prime=10,
+                p_max=0, seed=0, keep_gram=0, workspace=256, workspace_bytes=1 << 40, stream=None)
+    base.update(kw)
+    return b.Config(**base)
+
+
+@pytest.mark.parametrize("bad", [
+    dict(n=0), dict(j=0), dict(layout=7), dict(x=None), dict(y=None), dict(workspace=None),
+    dict(lam=-1.0), dict(lam=float("nan")), dict(lam=float("inf")), dict(rho=0.0), dict(rho=-0.1),
+    dict(rho=float("nan")), dict(eta=0.0), dict(eta=float("nan")), dict(c_init=0.0), dict(c_init=float("inf")),
+    dict(l_prime=0), dict(l_prime=pk.MAX_L_PRIME + 1), dict(p_max=-1), dict(workspace=257), dict(x=258),
+    dict(layout=1, row_idx=None, col_ptr=None),
+])
+def test_create_rejects_invalid_arguments_without_touching_the_device(bad):
+    lib = pk.load()
+    h = C.c_void_p(0x1234)
+    rc = lib.strads_lasso_create(C.byref(_cfg(**bad)), C.byref(h))
+    assert rc == b.E_INVALID_ARG
+    assert h.value == 0x1234                    # outputs untouched on error
+
+
+def test_create_reports_small_workspace_and_null_handles():
+    lib = pk.load()
+    h = C.c_void_p()
+    assert lib.strads_lasso_create(C.byref(_cfg(workspace_bytes=1024)), C.byref(h)) == b.E_WORKSPACE_TOO_SMALL
+    assert lib.strads_lasso_create(None, C.byref(h)) == b.E_INVALID_ARG
+    assert lib.strads_lasso_create(C.byref(_cfg()), None) == b.E_INVALID_ARG
+    assert lib.strads_lasso_round(None, None) == b.E_INVALID_ARG
+    assert lib.strads_lasso_run(None, 1, 0.0, 0, None) == b.E_INVALID_ARG
+    assert lib.strads_lasso_objective(None, None) == b.E_INVALID_ARG
+    assert lib.strads_lasso_kkt(None, None, None) == b.E_INVALID_ARG
+    assert lib.strads_lasso_set_tuning(None, b"gram_split_k", 1) == b.E_INVALID_ARG
+    lib.strads_lasso_destroy(None)              # a no-op
+    assert lib.strads_lasso_strerror(0) == b"ok"
+    assert b"workspace" in lib.strads_lasso_strerror(b.E_WORKSPACE_TOO_SMALL)
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        b.load()

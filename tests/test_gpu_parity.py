@@ -1,0 +1,320 @@
+"""GPU parity: libstrads_lasso (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: index work (candidate lists; kept sets given identical Gram values) bit-exact; Gram and dot
+products within 1e-4 relative + a small absolute floor; beta within 1e-4 relative + 1e-6;
+objective trajectory within 1e-5 relative.  Candidate pairs whose |x_a^T x_b| lies within 1e-6 of
+rho may be decided differently by the two sides; such rounds are logged, never silently accepted:
+the GPU's decision must still be the greedy result on its own Gram values.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from oracle.oracle import OracleLasso
+from synth import lasso_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+DOT_RTOL, BETA_RTOL, OBJ_RTOL = 1e-4, 1e-4, 1e-5
+
+
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1312_5766_amd as pk
+    pk.load()
+    return pk
+
+
+def _pair(p, keep_gram=True, **kw):
+    """(GPU solver, oracle) on the same arrays."""
+    pk = _gpu()
+    dev = torch.device("cuda:0")
+    args = dict(lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
+    args.update(kw)
+    if p.layout == "dense":
+        xg = p.x.to(dev)
+        g = pk.StradsLasso(x=xg, y=p.y.to(dev), keep_gram=keep_gram, **args)
+        o = OracleLasso(x=p.x.cpu().numpy(), y=p.y.cpu().numpy(), **args)
+    else:
+        g = pk.StradsLasso(values=p.values.to(dev), row_idx=p.row_idx.to(dev), col_ptr=p.col_ptr.to(dev), n=p.n,
+                           y=p.y.to(dev), keep_gram=keep_gram, **args)
+        o = OracleLasso(values=p.values.cpu().numpy(), row_idx=p.row_idx.cpu().numpy(),
+                        col_ptr=p.col_ptr.cpu().numpy(), n=p.n, y=p.y.cpu().numpy(), **args)
+    return g, o
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def _assert_close(got, ref, rtol, atol, what):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    err = np.abs(got - ref) - (rtol * np.abs(ref) + atol)
+    assert err.size == 0 or err.max() <= 0, f"{what}: worst excess {err.max():.3e} at {err.argmax()}"
+
+
+def _check_round(g, o, log, teacher_forced):
+    """One round on both sides, every stage compared.  The oracle follows the GPU's index
+    decisions once they have been shown admissible."""
+    if teacher_forced:
+        g.set_state(o.beta, o.dbeta, o.r, o.t)
+    beta0, dbeta0, r0, t0 = o.beta.copy(), o.dbeta.copy(), o.r.copy(), o.t
+    gb0, gd0 = (beta0, dbeta0) if teacher_forced else [_np(a) for a in g.get_state()[:2]]
+    g.round()
+    lr = g.last_round(want_gram=True)
+    cand, kept_pos = _np(lr["cand"]), _np(lr["kept_pos"])
+    # Step 1: candidate list, set and order, bit-exact (from the oracle's own delta-beta in
+    # teacher-forced mode; from the GPU's delta-beta otherwise, which the oracle has followed)
+    keys = orc.priority_keys(dbeta0, o.eta, o.seed, t0)
+    ref_cand = orc.draw(keys, o.l_prime)
+    if not np.array_equal(cand, ref_cand):
+        # admissible only if delta-beta differs in the last bits between the two sides
+        assert not teacher_forced, "candidate list differs on identical delta-beta"
+        log.append(("cand_fork", t0))
+        return False
+    # Step 2a: Gram values
+    L = len(cand)
+    if o.csc:
+        Gref = orc.gram_csc(o.x, o.row_idx, o.col_ptr, cand)
+    else:
+        Gref = orc.gram_dense(o.x, cand)
+    Ggpu = _np(lr["G"])
+    _assert_close(Ggpu, Gref, DOT_RTOL, 1e-6, f"gram (round {t0})")
+    # Step 2b: the GPU's kept set is the greedy result on the GPU's own Gram values, bit-exact
+    kept_from_gpu_gram = orc.greedy_filter(Ggpu, o.rho, o.p_max)
+    assert np.array_equal(kept_pos, kept_from_gpu_gram), f"filter differs on identical Gram (round {t0})"
+    kept_ref = orc.greedy_filter(Gref, o.rho, o.p_max)
+    if not np.array_equal(kept_pos, kept_ref):
+        near = np.abs(np.abs(Gref.astype(np.float64)) - float(o.rho)) <= 1e-6
+        np.fill_diagonal(near, False)
+        assert near.any(), f"kept sets differ without a pair near rho (round {t0})"
+        log.append(("near_rho", t0, int(near.sum()) // 2))
+    # Steps 3-4 with the oracle following the GPU's (admissible) decisions
+    out = o.round(forced_cand=cand, forced_kept_pos=kept_pos)
+    rn = float(np.linalg.norm(r0.astype(np.float64)))
+    _assert_close(_np(lr["z"]), out["z"], DOT_RTOL, 1e-6 * max(rn, 1.0), f"dots (round {t0})")
+    _assert_close(_np(lr["delta"]), out["delta"], BETA_RTOL, 2e-6 * max(rn, 1.0), f"delta (round {t0})")
+    beta, dbeta, r, t = g.get_state()
+    assert t == o.t
+    _assert_close(_np(beta), o.beta, BETA_RTOL, 2e-6 * max(rn, 1.0), f"beta (round {t0})")
+    _assert_close(_np(r), o.r, DOT_RTOL, 2e-6 * max(rn, 1.0), f"residual (round {t0})")
+    # coordinates outside the kept set are untouched, bit for bit
+    untouched = np.ones(o.J, bool)
+    untouched[out["kept"]] = False
+    assert np.array_equal(_np(beta)[untouched], gb0[untouched])
+    assert np.array_equal(_np(dbeta)[untouched], gd0[untouched])
+    return True
+
+
+# ---------------------------------------------------------------------------------------------
+# Step 1: keys and candidate lists
+# ---------------------------------------------------------------------------------------------
+def test_sampling_keys_are_bit_identical():
+    p = si.make("c1_dense_iid", n=64, j=70001, nnz=5, l_prime=100)
+    g, o = _pair(p, keep_gram=False)
+    rng = np.random.default_rng(0)
+    db = np.abs(rng.normal(size=p.j)).astype(np.float32)
+    db[::7] = 1e6
+    db[1::7] = 0.0
+    db[2::7] = 1e-20
+    db[3::7] = np.float32(3.4e18)
+    for t in (0, 1, 12345678901):
+        g.set_state(None, db, None, t)
+        got = _np(g.stage_keys(t))
+        ref = orc.priority_keys(db, p.eta, p.seed, t)
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("j,l_prime", [(1, 1), (5, 5), (63, 7), (257, 256), (1000, 1000), (5000, 200),
+                                       (70001, 1000), (300000, 8192), (300000, 1)])
+def test_candidate_lists_are_bit_identical(j, l_prime):
+    p = si.make("c1_dense_iid", n=8, j=j, nnz=1, l_prime=l_prime)
+    g, o = _pair(p, keep_gram=False)
+    rng = np.random.default_rng(j)
+    for t, mode in enumerate(["init", "mixed", "equal", "few_large"]):
+        if mode == "init":
+            db = np.full(j, 1e6, np.float32)
+        elif mode == "mixed":
+            db = np.abs(rng.normal(size=j)).astype(np.float32)
+            db[rng.random(j) < 0.3] = 1e6
+            db[rng.random(j) < 0.3] = 0.0
+        elif mode == "equal":
+            db = np.zeros(j, np.float32)               # all weights = eta: many exactly equal keys
+        else:
+            db = np.zeros(j, np.float32)
+            db[rng.integers(0, j, max(1, l_prime // 3))] = 0.5
+        g.set_state(None, db, None, t)
+        g.round()
+        cand = _np(g.last_round()["cand"])
+        ref = orc.draw(orc.priority_keys(db, p.eta, p.seed, t), l_prime)
+        assert np.array_equal(cand, ref), (mode, j, l_prime)
+
+
+def test_selection_fallback_path_gives_the_same_list():
+    # force the multi-pass boundary selection by shrinking the list length it is meant for
+    p = si.make("c1_dense_iid", n=8, j=200000, nnz=1, l_prime=3000)
+    g, o = _pair(p, keep_gram=False)
+    db = np.zeros(p.j, np.float32)
+    for cap in (1, 7, 64):
+        g.set_tuning("select_cap", cap)
+        g.set_state(None, db, None, 3)
+        g.round()
+        cand = _np(g.last_round()["cand"])
+        ref = orc.draw(orc.priority_keys(db, p.eta, p.seed, 3), p.l_prime)
+        assert np.array_equal(cand, ref), cap
+
+
+# ---------------------------------------------------------------------------------------------
+# Step 2: Gram and filter
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,j,l_prime", [(1000, 600, 200), (1001, 300, 130), (37, 400, 257), (4096, 300, 128),
+                                         (10, 200, 64), (3, 50, 50)])
+def test_gram_matches_oracle_across_shapes(n, j, l_prime):
+    p = si.make("c2_dense_block_corr", n=n, j=j, nnz=5, l_prime=l_prime)
+    g, o = _pair(p)
+    g.round()
+    lr = g.last_round(want_gram=True)
+    cand = _np(lr["cand"])
+    Gref = orc.gram_dense(o.x, cand)
+    _assert_close(_np(lr["G"]), Gref, DOT_RTOL, 1e-6, "gram")
+    assert np.array_equal(_np(lr["G"]), _np(lr["G"]).T)
+
+
+def test_gram_split_k_variants_agree_with_oracle():
+    p = si.make("c2_dense_block_corr", n=5000, j=600, nnz=5, l_prime=300)
+    for split in (1, 2, 5, 0):
+        g, o = _pair(p)
+        g.set_tuning("gram_split_k", split)
+        g.round()
+        lr = g.last_round(want_gram=True)
+        Gref = orc.gram_dense(o.x, _np(lr["cand"]))
+        _assert_close(_np(lr["G"]), Gref, DOT_RTOL, 1e-6, f"gram split {split}")
+
+
+@pytest.mark.parametrize("L", [1, 2, 63, 64, 65, 200, 1000, 2500])
+def test_filter_is_bit_exact_on_given_gram(L):
+    p = si.make("c1_dense_iid", n=8, j=max(L, 2), nnz=1, l_prime=L)
+    rng = np.random.default_rng(L)
+    for p_max, scale in ((0, 0.035), (0, 0.08), (max(1, L // 3), 0.035)):
+        g, o = _pair(p, keep_gram=False, p_max=p_max)
+        A = (rng.standard_normal((L, L)) * scale).astype(np.float32)
+        G = np.triu(A, 1) + np.triu(A, 1).T + np.eye(L, dtype=np.float32)
+        if L > 3:
+            G[0, 2] = G[2, 0] = np.float32(p.rho)                               # exactly rho: conflict
+            G[0, 3] = G[3, 0] = np.nextafter(np.float32(p.rho), np.float32(0))   # just below: admissible
+        got = _np(g.stage_filter(torch.from_numpy(G)))
+        ref = orc.greedy_filter(G, p.rho, p_max)
+        assert np.array_equal(got, ref), (L, p_max, scale)
+        assert 1 <= len(ref) <= L
+
+
+# ---------------------------------------------------------------------------------------------
+# whole rounds
+# ---------------------------------------------------------------------------------------------
+def test_config1_teacher_forced_rounds():
+    p = si.make("c1_dense_iid")                      # the full first configuration: 1000 x 5000, L'=200
+    g, o = _pair(p)
+    log = []
+    for _ in range(p.rounds):
+        assert _check_round(g, o, log, teacher_forced=True)
+        assert g.objective() == pytest.approx(o.objective(), rel=OBJ_RTOL)
+    print("logged:", log)
+
+
+def test_config1_free_run_objective_trajectory():
+    p = si.make("c1_dense_iid")
+    g, o = _pair(p)
+    log = []
+    f_prev = g.objective()
+    assert f_prev == pytest.approx(o.objective(), rel=OBJ_RTOL)
+    for t in range(p.rounds):
+        ok = _check_round(g, o, log, teacher_forced=False)
+        if not ok:                                   # admissible fork of the draw: re-synchronise and go on
+            o.set_state(*[_np(a) if isinstance(a, torch.Tensor) else a for a in g.get_state()])
+        assert g.objective() == pytest.approx(o.objective(), rel=OBJ_RTOL)
+    v_gpu, v_ref = g.kkt(), o.kkt()
+    assert v_gpu == pytest.approx(v_ref, rel=1e-3, abs=1e-6)
+    print("logged:", log)
+
+
+@pytest.mark.parametrize("config,kw,rounds", [
+    ("c2_dense_block_corr", dict(n=2000, j=6000, nnz=40, l_prime=500), 8),
+    ("c3_genotype", dict(n=500, j=20000, nnz=20, l_prime=700), 6),
+    ("c5_dense_duplicates", dict(n=3000, j=5000, nnz=30, l_prime=400), 8),
+    ("c1_dense_iid", dict(n=1003, j=900, nnz=10, l_prime=150), 6),        # N not a multiple of 4
+])
+def test_reduced_configs_teacher_forced(config, kw, rounds):
+    p = si.make(config, **kw)
+    g, o = _pair(p)
+    log = []
+    for _ in range(rounds):
+        assert _check_round(g, o, log, teacher_forced=True)
+    assert g.objective() == pytest.approx(o.objective(), rel=OBJ_RTOL)
+    v, gg = g.kkt(want_g=True)
+    v_ref, g_ref = o.kkt(want_g=True)
+    rn = float(np.linalg.norm(o.r.astype(np.float64)))
+    _assert_close(_np(gg), g_ref, DOT_RTOL, 1e-6 * max(rn, 1.0), "x_j^T r for all columns")
+    assert v == pytest.approx(v_ref, rel=1e-3, abs=1e-6 * max(rn, 1.0))
+    print("logged:", log)
+
+
+def test_run_matches_repeated_rounds_and_is_deterministic():
+    p = si.make("c1_dense_iid", n=800, j=2000, nnz=20, l_prime=128)
+    a, _ = _pair(p, keep_gram=False)
+    b, _ = _pair(p, keep_gram=False)
+    info = a.run(15)
+    kept = 0
+    for _ in range(15):
+        kept += b.round(want_info=True).n_kept
+    assert info.rounds_done == 15 and info.updates_done == kept
+    sa, sb = a.get_state(), b.get_state()
+    for u, v in zip(sa[:3], sb[:3]):
+        assert torch.equal(u, v)                      # bit-identical: no order-dependent arithmetic
+    assert info.objective == b.objective()
+    # save / restore: 15 rounds == 10 + restore + 5
+    c, _ = _pair(p, keep_gram=False)
+    c.run(10)
+    st = c.get_state()
+    d, _ = _pair(p, keep_gram=False)
+    d.set_state(*st)
+    d.run(5)
+    for u, v in zip(d.get_state()[:3], sa[:3]):
+        assert torch.equal(u, v)
+
+
+def test_run_stops_on_kkt_and_solution_is_optimal():
+    p = si.make("c1_dense_iid", n=300, j=400, nnz=8, l_prime=64)
+    g, o = _pair(p, keep_gram=False)
+    info = g.run(20000, kkt_tol=1e-4, check_every=50)
+    assert info.converged == 1 and info.rounds_done < 20000
+    assert info.kkt_violation <= 1e-4 * p.lam
+    beta = _np(g.get_state()[0])
+    # the oracle, run to the same tolerance, reaches the same minimiser
+    for _ in range(info.rounds_done):
+        o.round()
+    assert o.kkt() <= 2e-4 * p.lam
+    _assert_close(beta, o.beta, 1e-3, 1e-4, "converged beta")
+
+
+def test_degenerate_cases():
+    # lambda above max |X^T y|: nothing ever moves
+    p = si.make("c1_dense_iid", n=200, j=300, nnz=5, l_prime=300)
+    g, o = _pair(p, keep_gram=False, lam=float(p.lam) * 11.0)
+    for _ in range(3):
+        info = g.round(want_info=True)
+        assert info.n_moved == 0 and info.max_abs_delta == 0.0 and info.n_cand == 300
+    beta, dbeta, r, t = g.get_state()
+    assert not beta.any() and torch.equal(r.cpu(), p.y) and t == 3
+    # l_prime above J is clamped; p_max = 1 is sequential coordinate descent
+    p = si.make("c1_dense_iid", n=100, j=40, nnz=4, l_prime=40)
+    g, o = _pair(p, keep_gram=True, l_prime=4000, p_max=1)
+    f = g.objective()
+    log = []
+    for _ in range(30):
+        assert _check_round(g, o, log, teacher_forced=True)
+        assert len(g.last_round()["kept"]) == 1
+        f2 = g.objective()
+        assert f2 <= f * (1 + 1e-6)
+        f = f2
