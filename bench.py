@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the SAP-scheduled Lasso round on one MI355X.
+
+A "step" is one scheduling round (Algorithm 1's loop body: draw candidates, candidate Gram,
+greedy rho filter, x_j^T r, soft-threshold update, residual update) on the second configuration
+of the workload list: dense Lasso, N=10000, J=100000, block-correlated columns, L'=1000.
+Inputs are synthetic, generated on the GPU and resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-job coordinate updates per second, plus
+  roofline     -- the candidate-Gram MFMA tile kernel against the fp32 matrix peak, its duration
+                  measured with HIP events on the solver's stream inside the timed region
+  cpu_baseline -- the CPU oracle timed on this machine's host cores on the first rounds of the same
+                  workload (a reported baseline, not a target)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_FP32_PEAK_TFLOPS = 157.3
+HBM_PEAK_GBPS = 8000.0
+
+WORKLOADS = {
+    # name -> (config key of synth.lasso_inputs, overrides)
+    "c2_dense_block_corr": ("c2_dense_block_corr", {}),
+    "c1_dense_iid": ("c1_dense_iid", {}),
+    "c3_genotype": ("c3_genotype", {}),
+    "c2_small": ("c2_dense_block_corr", dict(n=2000, j=8000, nnz=40, l_prime=500, rounds=16)),
+}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2_dense_block_corr", choices=sorted(WORKLOADS))
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing (0 = skip)")
+    ap.add_argument("--profile-level", type=int, default=1, choices=(0, 1, 2),
+                    help="HIP-event timing inside the timed region: 1 = Gram kernel only, 2 = every stage")
+    ap.add_argument("--split-k", type=int, default=0)
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the whole scheduling round on ONE GPU (scheduler and workers "
+              "collapse onto it); there is no multi-GPU path to time. Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_1312_5766_amd as pk
+    from synth import lasso_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    pk.load()                                   # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    key, over = WORKLOADS[args.workload]
+    t0 = time.time()
+    p = si.make(key, device=dev, **over)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t0
+
+    def fresh():
+        return pk.StradsLasso(x=p.x, y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
+
+    # warm-up on a throw-away handle, so that the timed region is the configuration's own
+    # trajectory from round 0
+    g = fresh()
+    if args.split_k:
+        g.set_tuning("gram_split_k", args.split_k)
+    for _ in range(args.warmup):
+        g.round()
+    torch.cuda.synchronize()
+    g.close()
+
+    g = fresh()
+    if args.split_k:
+        g.set_tuning("gram_split_k", args.split_k)
+    f0 = g.objective()
+    g.set_tuning("profile_rounds", max(args.steps, 1))
+    g.set_tuning("profile_level", args.profile_level)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    info = g.run(args.steps)                    # enqueues K rounds, waits once at the end
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    stage = g.stage_times() if args.profile_level else {"rounds": 0}
+    g.set_tuning("profile_level", 0)
+    updates = int(info.updates_done)
+    f1 = float(info.objective)
+
+    # the HBM-bound pass: x_j^T r for all J columns (the stopping test streams X once)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g.kkt()
+    e0.record()
+    viol = g.kkt()
+    e1.record()
+    torch.cuda.synchronize()
+    kkt_ms = e0.elapsed_time(e1)
+    kkt_gbps = 4.0 * p.n * p.j / (kkt_ms * 1e-3) / 1e9
+
+    L, N = g.L, p.n
+    gram_flops = float(N) * L * (L - 1)          # algorithmic: every unordered pair once, 2 flops per row
+    roofline = None
+    if args.profile_level and stage["rounds"] > 0 and stage["gram_tiles"] > 0:
+        ach = gram_flops / (stage["gram_tiles"] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "k_gram_tiles", "achieved": round(ach, 3),
+                    "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_FP32_PEAK_TFLOPS, 4),
+                    "traffic": None, "avg_ms": round(stage["gram_tiles"], 5), "launches": stage["rounds"],
+                    "flops_per_launch": gram_flops}
+
+    cpu = None
+    if args.cpu_seconds > 0:
+        from oracle.oracle import OracleLasso
+        xh = p.x.cpu().numpy()
+        o = OracleLasso(x=xh, y=p.y.cpu().numpy(), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
+        n_upd, n_rounds = 0, 0
+        tc = time.perf_counter()
+        while True:
+            n_upd += len(o.round()["kept"])
+            n_rounds += 1
+            el = time.perf_counter() - tc
+            if n_rounds >= args.steps or el + el / n_rounds > args.cpu_seconds:
+                break
+        el = time.perf_counter() - tc
+        cpu = {"value": round(n_upd / el, 2), "unit": "updates/s", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+               "kind": "oracle", "sample": f"first {n_rounds} rounds of the same workload ({el:.1f} s)",
+               "rounds_per_s": round(n_rounds / el, 4)}
+
+    out = {
+        "metric": "coordinate_updates_per_sec", "value": round(updates / wall, 1), "unit": "updates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall / max(args.steps, 1) * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "n": p.n, "j": p.j, "l_prime": p.l_prime, "rho": p.rho,
+                   "eta": p.eta, "lambda": p.lam, "rounds": args.steps, "parallelism": "1 GPU"},
+        "rounds_per_s": round(args.steps / wall, 2), "updates": updates,
+        "objective_start": f0, "objective_end": f1, "kkt_violation_end": viol,
+        "roofline": roofline,
+        "hbm_pass": {"kernel": "k_kkt", "bytes": 4.0 * p.n * p.j, "ms": round(kkt_ms, 4), "achieved": round(kkt_gbps, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(kkt_gbps / HBM_PEAK_GBPS, 4)},
+        "stage_ms": {k: round(v, 5) for k, v in stage.items() if k != "rounds"},
+        "cpu_baseline": cpu,
+        "input_generation_s": round(t_gen, 2),
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -51,6 +51,15 @@ extern "C" {
 
 #define STRADS_MAX_L_PRIME         8192   /* largest supported candidate count per round */
 
+/* Stages of one round, in stream order, as timed by strads_lasso_stage_times */
+#define STRADS_STAGE_SAMPLER     0   /* Step 1: keys, top-P' selection, draw order */
+#define STRADS_STAGE_GRAM_TILES  1   /* Step 2: candidate Gram, MFMA tile kernel (K-slices) */
+#define STRADS_STAGE_GRAM_MASK   2   /* Step 2: K-slice sum and |g| < rho conflict bits */
+#define STRADS_STAGE_FILTER      3   /* Step 2: greedy choice of B_1 */
+#define STRADS_STAGE_UPDATE      4   /* eq. (2): x_j^T r for B_1, soft-threshold, bookkeeping */
+#define STRADS_STAGE_RESIDUAL    5   /* r <- r - X_B * change */
+#define STRADS_N_STAGES          6
+
 typedef struct strads_lasso strads_lasso_t;   /* opaque, host side */
 
 typedef struct {
@@ -159,8 +168,18 @@ int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, i
  *   "gram_split_k"  0 = automatic, else the number of K-slices per Gram tile
  *   "select_cap"    boundary-list length above which the sampler's final
  *                   selection falls back to its multi-pass path (default 16384)
+ *   "profile_level", "profile_rounds"   see strads_lasso_stage_times
  * Returns STRADS_E_INVALID_ARG for an unknown name or a value out of range. */
 int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value);
+
+/* Average duration in milliseconds of each stage (HOST array of STRADS_N_STAGES floats) over the
+ * rounds enqueued since profiling was switched on or since the last call, measured with HIP events
+ * recorded on the handle's stream.  Switch on with strads_lasso_set_tuning(h, "profile_level", v):
+ * v = 1 records only around the Gram tile kernel (other entries read 0), v = 2 records every stage
+ * boundary, v = 0 switches off.  "profile_rounds" (default 256, set it while profiling is off) is the
+ * number of rounds the event pool holds; later rounds are not recorded.  Synchronises and resets
+ * the pool.  rounds_timed is HOST. */
+int strads_lasso_stage_times(strads_lasso_t *h, float *avg_ms, int32_t *rounds_timed);
 
 void strads_lasso_destroy(strads_lasso_t *h);
 

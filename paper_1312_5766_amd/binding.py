@@ -20,12 +20,14 @@ STRADS_OK = 0
 E_INVALID_ARG, E_WORKSPACE_TOO_SMALL, E_HIP, E_DIVERGED, E_UNSUPPORTED = -1, -2, -3, -4, -5
 LAYOUT_DENSE, LAYOUT_CSC = 0, 1
 MAX_L_PRIME = 8192
+N_STAGES = 6
+STAGE_NAMES = ["sampler", "gram_tiles", "gram_mask", "filter", "update", "residual"]
 
 EXPORTS = [
     "strads_lasso_workspace_bytes", "strads_lasso_create", "strads_lasso_round", "strads_lasso_run",
     "strads_lasso_objective", "strads_lasso_kkt", "strads_lasso_get_state", "strads_lasso_set_state",
     "strads_lasso_last_round", "strads_lasso_stage_keys", "strads_lasso_stage_filter",
-    "strads_lasso_set_tuning", "strads_lasso_destroy", "strads_lasso_strerror",
+    "strads_lasso_set_tuning", "strads_lasso_stage_times", "strads_lasso_destroy", "strads_lasso_strerror",
 ]
 
 
@@ -73,6 +75,7 @@ def load():
     L.strads_lasso_stage_keys.argtypes = [vp, C.c_int64, vp]
     L.strads_lasso_stage_filter.argtypes = [vp, vp, C.c_int32, vp, C.POINTER(C.c_int32)]
     L.strads_lasso_set_tuning.argtypes = [vp, C.c_char_p, C.c_int64]
+    L.strads_lasso_stage_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     L.strads_lasso_destroy.argtypes = [vp]
     L.strads_lasso_destroy.restype = None
     L.strads_lasso_strerror.argtypes = [C.c_int]
@@ -233,6 +236,12 @@ class StradsLasso:
         _check(load().strads_lasso_stage_filter(self._h, _ptr(G), l, _ptr(kept), C.byref(nk)),
                "strads_lasso_stage_filter")
         return kept[:nk.value]
+
+    def stage_times(self) -> dict:
+        ms = (C.c_float * N_STAGES)()
+        n = C.c_int32()
+        _check(load().strads_lasso_stage_times(self._h, ms, C.byref(n)), "strads_lasso_stage_times")
+        return {"rounds": n.value, **{name: float(ms[i]) for i, name in enumerate(STAGE_NAMES)}}
 
     def set_tuning(self, name: str, value: int):
         _check(load().strads_lasso_set_tuning(self._h, name.encode(), int(value)), "strads_lasso_set_tuning")

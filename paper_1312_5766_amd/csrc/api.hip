@@ -113,6 +113,10 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->split_user = 0;
     h->select_cap = kSelectCapDefault;
     h->round = 0;
+    h->profile_level = 0;
+    h->profile_rounds = 256;
+    h->profiled = 0;
+    h->events = nullptr;
     h->vec4 = cfg->layout == STRADS_LAYOUT_DENSE_COLMAJOR && (cfg->n % 4 == 0) && (((uintptr_t)cfg->x & 15u) == 0);
 
     if (sampler_prepare() != hipSuccess || gram_prepare() != hipSuccess) { free(h); return STRADS_E_HIP; }
@@ -124,29 +128,58 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     return STRADS_OK;
 }
 
+static void drop_events(strads_lasso *h);
+
 void strads_lasso_destroy(strads_lasso_t *h)
 {
-    if (h) free(h);
+    if (!h) return;
+    drop_events(h);
+    free(h);
+}
+
+// Stage boundaries of a round, in stream order: 0 | sampler | 1 | Gram tiles | 2 | Gram sum+mask
+// | 3 | filter | 4 | dots + update | 5 | residual | 6
+static inline int mark(strads_lasso *h, int boundary)
+{
+    if (h->profile_level == 0 || h->profiled >= h->profile_rounds) return STRADS_OK;
+    if (h->profile_level == 1 && boundary != 1 && boundary != 2) return STRADS_OK;
+    HIP_TRY(hipEventRecord(h->events[(size_t)h->profiled * kStageEvents + boundary], h->stream));
+    return STRADS_OK;
 }
 
 static int enqueue_round(strads_lasso *h)
 {
+    const bool dense = h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR;
+    int rc;
+    if ((rc = mark(h, 0)) != STRADS_OK) return rc;
     HIP_TRY(launch_sampler(h, h->round));
-    if (h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR) {
-        HIP_TRY(launch_gram_dense(h));
-        HIP_TRY(launch_filter(h, h->L, true));
-        HIP_TRY(launch_dots_dense(h));
-        HIP_TRY(launch_update(h));
-        HIP_TRY(launch_residual_dense(h));
-    } else {
-        HIP_TRY(launch_gram_csc(h));
-        HIP_TRY(launch_filter(h, h->L, true));
-        HIP_TRY(launch_dots_csc(h));
-        HIP_TRY(launch_update(h));
-        HIP_TRY(launch_residual_csc(h));
-    }
+    if ((rc = mark(h, 1)) != STRADS_OK) return rc;
+    if (dense) HIP_TRY(launch_gram_dense(h, 0)); else HIP_TRY(launch_gram_csc(h));
+    if ((rc = mark(h, 2)) != STRADS_OK) return rc;
+    if (dense) HIP_TRY(launch_gram_dense(h, 1));
+    if ((rc = mark(h, 3)) != STRADS_OK) return rc;
+    HIP_TRY(launch_filter(h, h->L, true));
+    if ((rc = mark(h, 4)) != STRADS_OK) return rc;
+    if (dense) HIP_TRY(launch_dots_dense(h)); else HIP_TRY(launch_dots_csc(h));
+    HIP_TRY(launch_update(h));
+    if ((rc = mark(h, 5)) != STRADS_OK) return rc;
+    if (dense) HIP_TRY(launch_residual_dense(h)); else HIP_TRY(launch_residual_csc(h));
+    if ((rc = mark(h, 6)) != STRADS_OK) return rc;
+    if (h->profile_level != 0 && h->profiled < h->profile_rounds) h->profiled += 1;
     h->round += 1;
     return STRADS_OK;
+}
+
+static void drop_events(strads_lasso *h)
+{
+    if (h->events) {
+        for (size_t i = 0; i < (size_t)h->profile_rounds * kStageEvents; ++i)
+            if (h->events[i]) (void)hipEventDestroy(h->events[i]);
+        free(h->events);
+        h->events = nullptr;
+    }
+    h->profile_level = 0;
+    h->profiled = 0;
 }
 
 static int read_scalars(strads_lasso *h, RoundScalars *host)
@@ -315,12 +348,53 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
         h->split_user = (int32_t)value;
         return STRADS_OK;
     }
+    if (strcmp(name, "profile_rounds") == 0) {
+        if (value < 1 || value > 1 << 20 || h->profile_level != 0) return STRADS_E_INVALID_ARG;
+        h->profile_rounds = (int32_t)value;
+        return STRADS_OK;
+    }
+    if (strcmp(name, "profile_level") == 0) {
+        if (value < 0 || value > 2) return STRADS_E_INVALID_ARG;
+        HIP_TRY(hipStreamSynchronize(h->stream));
+        const int32_t keep_rounds = h->profile_rounds;
+        drop_events(h);
+        h->profile_rounds = keep_rounds;
+        if (value == 0) return STRADS_OK;
+        const size_t n = (size_t)h->profile_rounds * kStageEvents;
+        h->events = (hipEvent_t *)calloc(n, sizeof(hipEvent_t));
+        if (!h->events) return STRADS_E_INVALID_ARG;
+        for (size_t i = 0; i < n; ++i)
+            if (hipEventCreate(&h->events[i]) != hipSuccess) { drop_events(h); return STRADS_E_HIP; }
+        h->profile_level = (int32_t)value;
+        return STRADS_OK;
+    }
     if (strcmp(name, "select_cap") == 0) {
         if (value < 1 || value > 2 * STRADS_MAX_L_PRIME) return STRADS_E_INVALID_ARG;
         h->select_cap = (int32_t)value;
         return STRADS_OK;
     }
     return STRADS_E_INVALID_ARG;
+}
+
+int strads_lasso_stage_times(strads_lasso_t *h, float *avg_ms, int32_t *rounds_timed)
+{
+    if (!h || !avg_ms || !rounds_timed) return STRADS_E_INVALID_ARG;
+    HIP_TRY(hipStreamSynchronize(h->stream));
+    double sum[STRADS_N_STAGES];
+    for (int s = 0; s < STRADS_N_STAGES; ++s) sum[s] = 0.0;
+    for (int32_t r = 0; r < h->profiled; ++r) {
+        hipEvent_t *e = h->events + (size_t)r * kStageEvents;
+        for (int s = 0; s < STRADS_N_STAGES; ++s) {
+            if (h->profile_level == 1 && s != 1) continue;
+            float ms = 0.f;
+            HIP_TRY(hipEventElapsedTime(&ms, e[s], e[s + 1]));
+            sum[s] += ms;
+        }
+    }
+    for (int s = 0; s < STRADS_N_STAGES; ++s) avg_ms[s] = h->profiled > 0 ? (float)(sum[s] / h->profiled) : 0.f;
+    *rounds_timed = h->profiled;
+    h->profiled = 0;
+    return STRADS_OK;
 }
 
 const char *strads_lasso_strerror(int code)

@@ -197,7 +197,7 @@ int gram_split_auto(int64_t n, int32_t lpad)
     return (int)split;
 }
 
-hipError_t launch_gram_dense(strads_lasso *h)
+hipError_t launch_gram_dense(strads_lasso *h, int part)
 {
     const int32_t T = h->Lpad / kGramTile;
     int32_t split = h->split_user > 0 ? h->split_user : gram_split_auto(h->cfg.n, h->Lpad);
@@ -208,16 +208,19 @@ hipError_t launch_gram_dense(strads_lasso *h)
     const size_t lds = 2 * 2 * kPanel * sizeof(float);
     float *P = h->at<float>(h->ws.partial);
     const dim3 grid((unsigned)(T * T * split));
+    if (part == 1) {
+        RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+        hipLaunchKernelGGL(k_gram_mask, dim3((h->Lpad + 255) / 256, h->Lpad), dim3(256), 0, h->stream, P, split,
+                           h->L, h->Lpad, h->cfg.rho, h->at<uint64_t>(h->ws.mask),
+                           h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr, &sc->near_rho_pairs);
+        return hipGetLastError();
+    }
     if (h->vec4)
         hipLaunchKernelGGL(k_gram_tiles<true>, grid, dim3(256), lds, h->stream, h->cfg.x, h->cfg.n,
                            h->at<int32_t>(h->ws.cand), h->L, h->Lpad, T, split, kchunk, P);
     else
         hipLaunchKernelGGL(k_gram_tiles<false>, grid, dim3(256), lds, h->stream, h->cfg.x, h->cfg.n,
                            h->at<int32_t>(h->ws.cand), h->L, h->Lpad, T, split, kchunk, P);
-    RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
-    hipLaunchKernelGGL(k_gram_mask, dim3((h->Lpad + 255) / 256, h->Lpad), dim3(256), 0, h->stream, P,
-                       split, h->L, h->Lpad, h->cfg.rho, h->at<uint64_t>(h->ws.mask),
-                       h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr, &sc->near_rho_pairs);
     return hipGetLastError();
 }
 

@@ -16,6 +16,7 @@ constexpr int kGramKT = 32;            // K (row) extent of one LDS stage, float
 constexpr int kMaxResidualGroups = 64; // column groups of the residual update
 constexpr int kObjBlocks = 256;        // workgroups of the objective reduction
 constexpr int kSelectCapDefault = 16384;
+constexpr int kStageEvents = STRADS_N_STAGES + 1;
 
 // Device-side scalars of one round, kept in one small block of the workspace.
 struct RoundScalars {
@@ -71,6 +72,11 @@ struct strads_lasso {
     int32_t select_cap;
     int64_t round;
     bool vec4;          // dense columns are 16-byte aligned (N % 4 == 0 and x aligned)
+    // optional stage timing with HIP events on the caller's stream
+    int32_t profile_level;   // 0 off, 1 Gram tile kernel only, 2 every stage boundary
+    int32_t profile_rounds;  // rounds the event pool can hold
+    int32_t profiled;        // rounds recorded so far
+    hipEvent_t *events;      // [profile_rounds][kStageEvents]
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(base + off); }
 };
@@ -83,7 +89,7 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
 // Each launcher enqueues on h->stream and returns the hipError_t of the launch.
 hipError_t launch_sampler(strads_lasso *h, int64_t round);                 // Step 1 -> cand[L]
 hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys);  // stage entry
-hipError_t launch_gram_dense(strads_lasso *h);                             // Step 2a -> mask (and gram)
+hipError_t launch_gram_dense(strads_lasso *h, int part);  // Step 2a; part 0: K-slice tiles, part 1: sum + conflict mask
 hipError_t launch_mask_from_gram(strads_lasso *h, const float *gram, int32_t l);
 hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates);                    // Step 2b -> kept_pos, kept, n_kept
 hipError_t launch_dots_dense(strads_lasso *h);                             // x_j^T r for the kept set
