@@ -119,7 +119,7 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->events = nullptr;
     h->vec4 = cfg->layout == STRADS_LAYOUT_DENSE_COLMAJOR && (cfg->n % 4 == 0) && (((uintptr_t)cfg->x & 15u) == 0);
 
-    if (sampler_prepare() != hipSuccess || gram_prepare() != hipSuccess) { free(h); return STRADS_E_HIP; }
+    if (sampler_prepare() != hipSuccess || gram_prepare() != hipSuccess || filter_prepare() != hipSuccess) { free(h); return STRADS_E_HIP; }
     if (launch_init_state(h) != hipSuccess) {
         free(h);
         return STRADS_E_HIP;

@@ -2,14 +2,18 @@
 // from U such that |x_j^T x_k| < rho for all pairs"): walk the candidates in draw order and keep
 // one iff it conflicts with nothing kept so far.
 //
-// The walk is inherently sequential in the kept set, so one wavefront does it, arranged so that
-// the serial chain is short: candidates are taken 64 at a time.  `dead` (one bit per candidate,
-// spread over the lanes' registers) marks candidates that conflict with something already kept.
-// For a chunk, the 64x64 diagonal block of conflict bits decides the chunk with scalar bit
-// operations (one lane-read per KEPT candidate); afterwards the conflict rows of the newly kept
-// candidates are OR-ed into `dead` for the later chunks, 64 words per load, all lanes busy.
+// The walk is sequential in the kept set, so the work is arranged to keep the serial chain short.
+// One workgroup of 1024 threads takes the candidates 64 at a time (a "chunk").  `dead` (one bit
+// per candidate, in LDS) marks candidates that conflict with something already kept.
+//   * The chunk's 64 conflict rows (words at or right of the chunk's own word) are staged in LDS;
+//     the rows of chunk c+1 are fetched from global memory into registers while chunk c is being
+//     decided, so no global-memory latency sits on the serial chain.
+//   * Wavefront 0 decides the chunk: candidates that are alive and have no conflict with another
+//     alive candidate of the chunk are kept at once; only the few with an in-chunk conflict are
+//     walked one by one (scalar bit operations on the 64x64 diagonal block).
+//   * All threads then OR the rows of the newly kept candidates into `dead` for later chunks.
 // Only bits (a, b) with b in a's 128-tile or right of it are read, matching what the Gram
-// kernel writes.
+// kernel writes.  Bit-exact: the result depends on the conflict bits only.
 #include "strads_internal.h"
 
 namespace strads {
@@ -21,66 +25,132 @@ __device__ __forceinline__ uint64_t readlane64(uint64_t v, int l)
     return ((uint64_t)hi << 32) | lo;
 }
 
-constexpr int kDeadSlots = STRADS_MAX_L_PRIME / 64 / 64;   // mask words per lane (2)
+constexpr int kMaxWords = STRADS_MAX_L_PRIME / 64;   // mask words per row (128)
+constexpr int kFilterThreads = 1024;
+constexpr int kRowWordsPerThread = 64 * kMaxWords / kFilterThreads;   // 8
 
-__global__ __launch_bounds__(64) void k_filter(const uint64_t *__restrict__ mask, int32_t L, int32_t W,
-                                               int32_t p_max, const int32_t *__restrict__ cand,
-                                               int32_t *__restrict__ kept_pos, int32_t *__restrict__ kept,
-                                               RoundScalars *__restrict__ sc, int count_updates)
+__global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__restrict__ mask, int32_t L, int32_t W,
+                                                           int32_t p_max, const int32_t *__restrict__ cand,
+                                                           int32_t *__restrict__ kept_pos, int32_t *__restrict__ kept,
+                                                           RoundScalars *__restrict__ sc, int count_updates)
 {
-    const int lane = threadIdx.x;
-    uint64_t dead[kDeadSlots];
-#pragma unroll
-    for (int s = 0; s < kDeadSlots; ++s) dead[s] = 0;
-    int32_t nk = 0;
+    extern __shared__ uint64_t rows[];            // [2][64][W]  (row-major, all W words kept for simplicity)
+    __shared__ uint64_t dead[kMaxWords];
+    __shared__ uint64_t keptw_s;
+    __shared__ int32_t nk_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int32_t cap = p_max > 0 ? p_max : L;
     const int32_t chunks = (L + 63) / 64;
-    for (int32_t c = 0; c < chunks && nk < cap; ++c) {
-        // word c of `dead` lives in slot c/64 of lane c%64
-        uint64_t cur = 0;
+    const int32_t items = 64 * W;                 // words of one chunk's rows
+
+    for (int i = tid; i < W; i += kFilterThreads) dead[i] = 0;
+    if (tid == 0) nk_s = 0;
+
+    // stage chunk 0
+    uint64_t pre[kRowWordsPerThread];
+    auto fetch = [&](int32_t c) {
 #pragma unroll
-        for (int s = 0; s < kDeadSlots; ++s)
-            if (s == (c >> 6)) cur = readlane64(dead[s], c & 63);
-        const int32_t a = c * 64 + lane;
-        const uint64_t diag = a < L ? mask[(int64_t)a * W + c] : 0ull;
-        const int32_t nvalid = L - c * 64;
-        uint64_t alive = ~cur & (nvalid >= 64 ? ~0ull : ((1ull << nvalid) - 1ull));
-        uint64_t keptw = 0;
-        const int32_t nk0 = nk;
-        while (alive != 0 && nk < cap) {            // uniform across the wavefront
-            const int l = __ffsll((long long)alive) - 1;
-            keptw |= 1ull << l;
-            ++nk;
-            alive &= ~(1ull << l);
-            alive &= ~readlane64(diag, l);
+        for (int q = 0; q < kRowWordsPerThread; ++q) {
+            const int32_t it = tid + q * kFilterThreads;
+            const int32_t rw = it / W, w = it - rw * W;
+            const int32_t a = c * 64 + rw;
+            pre[q] = (it < items && a < L && w >= c) ? mask[(int64_t)a * W + w] : 0ull;
         }
-        if ((keptw >> lane) & 1ull) {
-            const int32_t idx = nk0 + __popcll(keptw & ((1ull << lane) - 1ull));
-            kept_pos[idx] = a;
-            kept[idx] = cand[a];
-        }
-        // rows of the newly kept candidates kill later candidates
-        uint64_t m = keptw;
-        while (m != 0) {
-            const int l = __ffsll((long long)m) - 1;
-            m &= m - 1;
-            const uint64_t *row = mask + (int64_t)(c * 64 + l) * W;
+    };
+    auto stash = [&](int buf) {
 #pragma unroll
-            for (int s = 0; s < kDeadSlots; ++s) {
-                const int32_t w = lane + 64 * s;
-                if (w > c && w < W) dead[s] |= row[w];
+        for (int q = 0; q < kRowWordsPerThread; ++q) {
+            const int32_t it = tid + q * kFilterThreads;
+            if (it < items) rows[(size_t)buf * items + it] = pre[q];
+        }
+    };
+    fetch(0);
+    stash(0);
+    __syncthreads();
+
+    for (int32_t c = 0; c < chunks; ++c) {
+        const uint64_t *rb = rows + (size_t)(c & 1) * items;
+        if (c + 1 < chunks) fetch(c + 1);         // in flight while this chunk is decided
+        if (wave == 0) {
+            const int32_t nk0 = nk_s;
+            int32_t nk = nk0;
+            const uint64_t cur = dead[c];
+            const int32_t nvalid = L - c * 64;
+            uint64_t alive = ~cur & (nvalid >= 64 ? ~0ull : ((1ull << nvalid) - 1ull));
+            const uint64_t diag = rb[lane * W + c];
+            uint64_t keptw = 0;
+            if (nk < cap) {
+                // lanes whose row meets another alive candidate of this chunk need the serial walk
+                const uint64_t tangled = __ballot((diag & alive) != 0) & alive;
+                const uint64_t freeb = alive & ~tangled;
+                if (tangled == 0 && nk + __popcll(freeb) <= cap) {
+                    keptw = freeb;
+                    nk += __popcll(freeb);
+                } else {
+                    uint64_t todo = alive;
+                    while (todo != 0 && nk < cap) {       // uniform across the wavefront
+                        // free candidates before the next tangled one are kept in one step
+                        const uint64_t tn = todo & tangled;
+                        const int l = tn ? __ffsll((long long)tn) - 1 : 64;
+                        uint64_t run = todo & (l >= 64 ? ~0ull : ((1ull << l) - 1ull));
+                        int32_t nrun = __popcll(run);
+                        if (nk + nrun > cap) {            // the cap cuts the run: keep its first cap-nk bits
+                            while (nrun > cap - nk) { run &= ~(1ull << (63 - __builtin_clzll(run))); --nrun; }
+                            keptw |= run; nk += nrun; todo = 0; break;
+                        }
+                        keptw |= run; nk += nrun; todo &= ~run;
+                        if (l >= 64 || nk >= cap) break;
+                        keptw |= 1ull << l;
+                        ++nk;
+                        todo &= ~(1ull << l);
+                        todo &= ~readlane64(diag, l);
+                    }
+                }
+            }
+            if ((keptw >> lane) & 1ull) {
+                const int32_t idx = nk0 + __popcll(keptw & ((1ull << lane) - 1ull));
+                kept_pos[idx] = c * 64 + lane;
+                kept[idx] = cand[c * 64 + lane];
+            }
+            if (lane == 0) { keptw_s = keptw; nk_s = nk; }
+        }
+        __syncthreads();
+        const uint64_t keptw = keptw_s;
+        const bool full = nk_s >= cap;
+        // OR the kept rows into dead[w], w > c
+        if (!full && keptw != 0) {
+            for (int32_t it = tid; it < items; it += kFilterThreads) {
+                const int32_t rw = it / W, w = it - rw * W;
+                if (w > c && ((keptw >> rw) & 1ull)) {
+                    const uint64_t v = rb[it];
+                    if (v) atomicOr((unsigned long long *)&dead[w], (unsigned long long)v);
+                }
             }
         }
+        if (c + 1 < chunks) stash((c + 1) & 1);
+        __syncthreads();
+        if (full) break;
     }
-    if (lane == 0) { sc->n_kept = nk; if (count_updates) sc->updates_total += (unsigned long long)nk; }
+    if (tid == 0) {
+        sc->n_kept = nk_s;
+        if (count_updates) sc->updates_total += (unsigned long long)nk_s;
+    }
 }
 
 hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates)
 {
-    hipLaunchKernelGGL(k_filter, dim3(1), dim3(64), 0, h->stream, h->at<uint64_t>(h->ws.mask), l, h->Lpad / 64,
+    const int32_t W = h->Lpad / 64;
+    const size_t lds = (size_t)2 * 64 * W * sizeof(uint64_t);
+    hipLaunchKernelGGL(k_filter, dim3(1), dim3(kFilterThreads), lds, h->stream, h->at<uint64_t>(h->ws.mask), l, W,
                        h->cfg.p_max, h->at<int32_t>(h->ws.cand), h->at<int32_t>(h->ws.kept_pos),
                        h->at<int32_t>(h->ws.kept), h->at<RoundScalars>(h->ws.scalars), count_updates ? 1 : 0);
     return hipGetLastError();
+}
+
+hipError_t filter_prepare()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_filter), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               2 * 64 * kMaxWords * (int)sizeof(uint64_t));
 }
 
 } // namespace strads

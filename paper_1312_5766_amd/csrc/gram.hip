@@ -24,23 +24,30 @@ constexpr int kPad = 4;                         // LDS row padding, floats
 constexpr int kRow = kGramKT + kPad;            // LDS row stride, floats
 constexpr int kPanel = kGramTile * kRow;        // floats per operand panel per stage
 
+// 4 consecutive K values of one column, zero beyond kend.  No branch: the address is clamped into
+// the column and the value is selected, so the main loop stays one straight-line block.
 template <bool VEC4>
 __device__ __forceinline__ float4 load_k4(const float *__restrict__ col, int64_t k, int64_t kend)
 {
     if (VEC4) {
-        if (k < kend) return *reinterpret_cast<const float4 *>(col + k);
-        return make_float4(0.f, 0.f, 0.f, 0.f);
+        const bool in = k < kend;                             // kend and k are multiples of 4 here
+        const float4 v = *reinterpret_cast<const float4 *>(col + (in ? k : kend - 4));
+        return in ? v : make_float4(0.f, 0.f, 0.f, 0.f);
     } else {
         float4 v;
-        v.x = (k + 0 < kend) ? col[k + 0] : 0.f;
-        v.y = (k + 1 < kend) ? col[k + 1] : 0.f;
-        v.z = (k + 2 < kend) ? col[k + 2] : 0.f;
-        v.w = (k + 3 < kend) ? col[k + 3] : 0.f;
+        const int64_t last = kend - 1;
+        v.x = col[k + 0 <= last ? k + 0 : last]; v.x = (k + 0 <= last) ? v.x : 0.f;
+        v.y = col[k + 1 <= last ? k + 1 : last]; v.y = (k + 1 <= last) ? v.y : 0.f;
+        v.z = col[k + 2 <= last ? k + 2 : last]; v.z = (k + 2 <= last) ? v.z : 0.f;
+        v.w = col[k + 3 <= last ? k + 3 : last]; v.w = (k + 3 <= last) ? v.w : 0.f;
         return v;
     }
 }
 
-// grid.x = T*T*split (T = Lpad/128).  Tiles below the diagonal exit at once.
+// grid.x = T(T+1)/2 * split (T = Lpad/128): upper-triangular tiles only, K-slice fastest.
+// Software pipeline per LDS stage st (32 K values): registers hold stage st+1 (fetched one stage
+// ago), they are written to the other LDS buffer, the fetch of stage st+2 is issued, then stage st
+// is multiplied out of LDS; one barrier per stage.
 template <bool VEC4>
 __global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__ X, int64_t N,
                                                        const int32_t *__restrict__ cand, int32_t L, int32_t Lpad,
@@ -48,9 +55,10 @@ __global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__
                                                        float *__restrict__ P)
 {
     const int32_t s = blockIdx.x % split;
-    const int32_t tile = blockIdx.x / split;
-    const int32_t ta = tile / T, tb = tile % T;
-    if (ta > tb) return;
+    int32_t u = blockIdx.x / split;             // index into the row-major upper triangle
+    int32_t ta = 0;
+    while (u >= T - ta) { u -= T - ta; ++ta; }
+    const int32_t tb = ta + u;
 
     extern __shared__ float smem[];             // [2 stages][A panel | B panel]
     const int tid = threadIdx.x;
@@ -58,31 +66,32 @@ __global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__
     const int64_t kend = (kbeg + kchunk < N) ? kbeg + kchunk : N;
     const int nstage = (int)((kend - kbeg + kGramKT - 1) / kGramKT);
 
-    // this thread stages 4 A-columns and 4 B-columns: column (it*32 + tid/8), floats (tid%8)*4..+3
+    // this thread stages 4 A-columns and 4 B-columns: column (it*32 + tid/8), floats (tid%8)*4..+3.
+    // Columns past the candidate count are clamped to the last candidate: their products land in
+    // rows/columns >= L of the tile, which nobody reads.
     const int crow = tid >> 3, kq = (tid & 7) * 4;
-    const float *acol[4], *bcol[4];
+    const float *col[8];
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-        const int ia = ta * kGramTile + it * 32 + crow, ib = tb * kGramTile + it * 32 + crow;
-        acol[it] = ia < L ? X + (int64_t)cand[ia] * N : nullptr;
-        bcol[it] = ib < L ? X + (int64_t)cand[ib] * N : nullptr;
+        int ia = ta * kGramTile + it * 32 + crow, ib = tb * kGramTile + it * 32 + crow;
+        ia = ia < L ? ia : L - 1;
+        ib = ib < L ? ib : L - 1;
+        col[it] = X + (int64_t)cand[ia] * N;
+        col[4 + it] = X + (int64_t)cand[ib] * N;
     }
 
-    float4 ra[4], rb[4];
+    float4 R[8];
     auto fetch = [&](int st) {
         const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            ra[it] = acol[it] ? load_k4<VEC4>(acol[it], k, kend) : make_float4(0.f, 0.f, 0.f, 0.f);
-            rb[it] = bcol[it] ? load_k4<VEC4>(bcol[it], k, kend) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+        for (int i = 0; i < 8; ++i) R[i] = load_k4<VEC4>(col[i], k, kend);
     };
     auto stash = [&](int buf) {
         float *pa = smem + buf * 2 * kPanel, *pb = pa + kPanel;
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            *reinterpret_cast<float4 *>(pa + (it * 32 + crow) * kRow + kq) = ra[it];
-            *reinterpret_cast<float4 *>(pb + (it * 32 + crow) * kRow + kq) = rb[it];
+            *reinterpret_cast<float4 *>(pa + (it * 32 + crow) * kRow + kq) = R[it];
+            *reinterpret_cast<float4 *>(pb + (it * 32 + crow) * kRow + kq) = R[4 + it];
         }
     };
 
@@ -98,13 +107,11 @@ __global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    if (nstage > 0) { fetch(0); stash(0); }
-    __syncthreads();
-    for (int st = 0; st < nstage; ++st) {
-        const int buf = st & 1;
-        if (st + 1 < nstage) fetch(st + 1);
-        const float *pa = smem + buf * 2 * kPanel + (wr * 64 + li) * kRow + lh * 4;
-        const float *pb = smem + buf * 2 * kPanel + kPanel + (wc * 64 + li) * kRow + lh * 4;
+    const int offa = (wr * 64 + li) * kRow + lh * 4;
+    const int offb = kPanel + (wc * 64 + li) * kRow + lh * 4;
+    auto compute = [&](int buf) {
+        const float *pa = smem + buf * 2 * kPanel + offa;
+        const float *pb = smem + buf * 2 * kPanel + offb;
 #pragma unroll
         for (int ks = 0; ks < kGramKT / 8; ++ks) {
             const float4 a0 = *reinterpret_cast<const float4 *>(pa + ks * 8);
@@ -121,9 +128,26 @@ __global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__
                 acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av1[c], bv1[c], acc[1][1], 0, 0, 0);
             }
         }
-        if (st + 1 < nstage) stash(buf ^ 1);
+    };
+
+    fetch(0);
+    stash(0);
+    if (nstage > 1) fetch(1);
+    __syncthreads();
+    int st = 0;
+    for (; st + 2 < nstage; ++st) {             // steady state: no conditionals inside
+        stash((st + 1) & 1);
+        fetch(st + 2);
+        compute(st & 1);
         __syncthreads();
     }
+    if (st + 1 < nstage) {
+        stash((st + 1) & 1);
+        compute(st & 1);
+        __syncthreads();
+        ++st;
+    }
+    compute(st & 1);
 
     // accumulator layout of the 32x32 MFMA: register v of lane (li, lh) holds
     // row 8*(v/4) + 4*lh + (v%4), column li of the 32x32 block.
@@ -132,11 +156,11 @@ __global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__
     for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
-            const int col = tb * kGramTile + wc * 64 + b * 32 + li;
+            const int colo = tb * kGramTile + wc * 64 + b * 32 + li;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = ta * kGramTile + wr * 64 + a * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                out[(int64_t)row * Lpad + col] = acc[a][b][v];
+                out[(int64_t)row * Lpad + colo] = acc[a][b][v];
             }
         }
 }
@@ -186,15 +210,24 @@ __global__ __launch_bounds__(256) void k_mask_from_gram(const float *__restrict_
 
 int gram_split_auto(int64_t n, int32_t lpad)
 {
+    // Workgroups = upper-triangular tiles x K-slices.  Two workgroups are resident per compute
+    // unit (LDS), so the launch runs in rounds of 512; pick the slice count that wastes the least
+    // of the last round, preferring fewer slices (less partial-sum traffic) among equals, and keep
+    // at least 8 LDS stages per slice.
     const int64_t T = lpad / kGramTile;
     const int64_t tiles = T * (T + 1) / 2;
-    // aim at two resident workgroups on each of the 256 compute units
-    int64_t split = (512 + tiles - 1) / tiles;
-    const int64_t max_split = (n + 4 * kGramKT - 1) / (4 * kGramKT);   // at least 4 LDS stages per slice
-    if (split > max_split) split = max_split;
-    if (split > 64) split = 64;
-    if (split < 1) split = 1;
-    return (int)split;
+    int64_t max_split = n / (8 * kGramKT);
+    if (max_split > 64) max_split = 64;
+    if (max_split < 1) max_split = 1;
+    int64_t best = 1;
+    double best_eff = 0.0;
+    for (int64_t s = 1; s <= max_split; ++s) {
+        const int64_t wg = tiles * s;
+        const int64_t rounds = (wg + 511) / 512;
+        const double eff = (double)wg / (double)(rounds * 512);
+        if (eff > best_eff + 0.02) { best_eff = eff; best = s; }
+    }
+    return (int)best;
 }
 
 hipError_t launch_gram_dense(strads_lasso *h, int part)
@@ -207,7 +240,7 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
     split = (int32_t)((h->cfg.n + kchunk - 1) / kchunk);
     const size_t lds = 2 * 2 * kPanel * sizeof(float);
     float *P = h->at<float>(h->ws.partial);
-    const dim3 grid((unsigned)(T * T * split));
+    const dim3 grid((unsigned)(T * (T + 1) / 2 * split));
     if (part == 1) {
         RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
         hipLaunchKernelGGL(k_gram_mask, dim3((h->Lpad + 255) / 256, h->Lpad), dim3(256), 0, h->stream, P, split,

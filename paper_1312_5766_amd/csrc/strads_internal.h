@@ -101,6 +101,7 @@ hipError_t launch_init_state(strads_lasso *h);
 hipError_t launch_clear_kkt(strads_lasso *h);
 hipError_t sampler_prepare();
 hipError_t gram_prepare();
+hipError_t filter_prepare();
 // CSC design
 hipError_t launch_gram_csc(strads_lasso *h);
 hipError_t launch_dots_csc(strads_lasso *h);

@@ -190,7 +190,15 @@ __global__ __launch_bounds__(256) void k_residual_apply(const float *__restrict_
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= N) return;
     float s = 0.f;
-    for (int g = 0; g < G; ++g) s += part[(int64_t)g * Npad + i];
+    int g = 0;
+    for (; g + 7 < G; g += 8) {                 // eight independent loads in flight, summed in group order
+        float v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = part[(int64_t)(g + q) * Npad + i];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s += v[q];
+    }
+    for (; g < G; ++g) s += part[(int64_t)g * Npad + i];
     r[i] -= s;
 }
 
