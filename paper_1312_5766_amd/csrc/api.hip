@@ -161,7 +161,6 @@ static int enqueue_round(strads_lasso *h)
     HIP_TRY(launch_filter(h, h->L, true));
     if ((rc = mark(h, 4)) != STRADS_OK) return rc;
     if (dense) HIP_TRY(launch_dots_dense(h)); else HIP_TRY(launch_dots_csc(h));
-    HIP_TRY(launch_update(h));
     if ((rc = mark(h, 5)) != STRADS_OK) return rc;
     if (dense) HIP_TRY(launch_residual_dense(h)); else HIP_TRY(launch_residual_csc(h));
     if ((rc = mark(h, 6)) != STRADS_OK) return rc;

@@ -174,6 +174,8 @@ __global__ __launch_bounds__(256) void k_hist2(const uint32_t *__restrict__ keys
         if (lh[i]) atomicAdd(&hist1[i], lh[i]);
 }
 
+constexpr int kCollectPerThread = 4;
+
 // pass 3: everything strictly above the 22-bit boundary prefix is selected; keys on the prefix
 // go to the boundary list.  Items are (orderable key << 32) | (2^32-1 - j): all distinct, and
 // larger item <=> (larger key, then smaller j).
@@ -187,14 +189,43 @@ __global__ __launch_bounds__(256) void k_collect(const uint32_t *__restrict__ ke
     find_bin_desc(hist1, rem1, tmp, b1, above);
     const uint32_t p22 = (b0 << 11) | b1;
     if (blockIdx.x == 0 && threadIdx.x == 0) { sc->prefix22 = p22; sc->rem2 = rem1 - above; }
-    const uint32_t jend = ((J + 255u) / 256u) * 256u;      // keep whole wavefronts in the loop
-    for (uint32_t j = blockIdx.x * 256u + threadIdx.x; j < jend; j += gridDim.x * 256u) {
-        const bool in = j < J;
-        const uint32_t ok = in ? keys[j] : 0u;
-        const uint32_t p = ok >> 10;
-        const uint64_t item = ((uint64_t)ok << 32) | (uint64_t)(0xFFFFFFFFu - j);
-        wave_append(in && p > p22, item, sel, &sc->n_sel);
-        wave_append(in && p == p22, item, bnd, &sc->n_bnd);
+    // Each thread looks at kCollectPerThread keys first and appends afterwards, so a wavefront
+    // issues at most one atomic per list however many keys it scans.
+    const uint32_t base = (blockIdx.x * 256u + (threadIdx.x & ~63u)) * kCollectPerThread + (threadIdx.x & 63u);
+    uint32_t okv[kCollectPerThread];
+    uint32_t n_gt = 0, n_eq = 0;
+#pragma unroll
+    for (int q = 0; q < kCollectPerThread; ++q) {
+        const uint32_t j = base + q * 64u;
+        okv[q] = j < J ? keys[j] : 0u;
+        const uint32_t p = okv[q] >> 10;
+        n_gt += (j < J && p > p22) ? 1u : 0u;
+        n_eq += (j < J && p == p22) ? 1u : 0u;
+    }
+    // wavefront-level exclusive scan of the per-lane counts
+    const int lane = __lane_id();
+    uint32_t off_gt = n_gt, off_eq = n_eq;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t a = __shfl_up(off_gt, d), b = __shfl_up(off_eq, d);
+        if (lane >= d) { off_gt += a; off_eq += b; }
+    }
+    const uint32_t tot_gt = __shfl(off_gt, 63), tot_eq = __shfl(off_eq, 63);
+    off_gt -= n_gt; off_eq -= n_eq;
+    uint32_t base_gt = 0, base_eq = 0;
+    if (lane == 0) {
+        if (tot_gt) base_gt = atomicAdd(&sc->n_sel, tot_gt);
+        if (tot_eq) base_eq = atomicAdd(&sc->n_bnd, tot_eq);
+    }
+    base_gt = __shfl(base_gt, 0) + off_gt;
+    base_eq = __shfl(base_eq, 0) + off_eq;
+#pragma unroll
+    for (int q = 0; q < kCollectPerThread; ++q) {
+        const uint32_t j = base + q * 64u;
+        const uint32_t p = okv[q] >> 10;
+        const uint64_t item = ((uint64_t)okv[q] << 32) | (uint64_t)(0xFFFFFFFFu - j);
+        if (j < J && p > p22) sel[base_gt++] = item;
+        if (j < J && p == p22) bnd[base_eq++] = item;
     }
 }
 
@@ -218,6 +249,34 @@ __device__ void bitonic_sort_desc(uint64_t *a, uint32_t n /* power of two */)
         }
     }
 }
+
+// Bitonic sort, descending, of up to 1024 items held one per thread (1024 threads): exchanges
+// with a partner less than 64 lanes away go through the wavefront's lane crossbar, the few longer
+// strides through LDS.  Returns the item that belongs at position threadIdx.x.
+__device__ uint64_t bitonic_sort_desc_1024(uint64_t x, uint64_t *xch /* 1024 items of LDS */)
+{
+    const uint32_t i = threadIdx.x;
+    for (uint32_t k = 2; k <= 1024u; k <<= 1) {
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            uint64_t y;
+            if (j < 64u) {
+                const uint32_t lo = __shfl_xor((uint32_t)x, (int)j), hi = __shfl_xor((uint32_t)(x >> 32), (int)j);
+                y = ((uint64_t)hi << 32) | lo;
+            } else {
+                xch[i] = x;
+                __syncthreads();
+                y = xch[i ^ j];
+                __syncthreads();
+            }
+            const bool desc = (i & k) == 0, lower = (i & j) == 0;
+            const bool take_max = desc == lower;          // the lower index of a descending pair keeps the larger
+            x = take_max ? (x > y ? x : y) : (x < y ? x : y);
+        }
+    }
+    return x;
+}
+
+constexpr uint32_t kRegSortMax = 1024;
 
 // exclusive rank of a flagged thread among the flagged threads of a 1024-thread block
 __device__ __forceinline__ uint32_t block_rank(bool flag, uint32_t *wave_tot /* 17 */, uint32_t &total)
@@ -284,6 +343,9 @@ __global__ __launch_bounds__(1024) void k_finalize(RoundScalars *__restrict__ sc
     // B. take the `need` largest boundary items
     if (nb == need) {
         for (uint32_t i = tid; i < nb; i += 1024u) sel[n_sel + i] = bnd[i];
+    } else if (nb <= kRegSortMax) {
+        const uint64_t v = bitonic_sort_desc_1024(tid < nb ? bnd[tid] : 0ull, lds);
+        if (tid < need) sel[n_sel + tid] = v;
     } else {
         uint32_t p2 = 1; while (p2 < nb) p2 <<= 1;
         for (uint32_t i = tid; i < p2; i += 1024u) lds[i] = i < nb ? bnd[i] : 0ull;
@@ -295,7 +357,10 @@ __global__ __launch_bounds__(1024) void k_finalize(RoundScalars *__restrict__ sc
     __syncthreads();
 
     // C. sort the L selected items: descending item = draw order
-    {
+    if (L <= kRegSortMax) {
+        const uint64_t v = bitonic_sort_desc_1024(tid < L ? sel[tid] : 0ull, lds);
+        if (tid < Lpad) cand[tid] = tid < L ? (int32_t)(0xFFFFFFFFu - (uint32_t)v) : 0;
+    } else {
         uint32_t p2 = 1; while (p2 < L) p2 <<= 1;
         for (uint32_t i = tid; i < p2; i += 1024u) lds[i] = i < L ? sel[i] : 0ull;
         __syncthreads();
@@ -329,7 +394,8 @@ hipError_t launch_sampler(strads_lasso *h, int64_t round)
     hipLaunchKernelGGL(k_keys_hist, dim3(g), dim3(256), 0, h->stream, h->at<float>(h->ws.dbeta), J, h->cfg.eta,
                        h->cfg.seed, (uint64_t)round, keys, hist);
     hipLaunchKernelGGL(k_hist2, dim3(g), dim3(256), 0, h->stream, keys, J, L, hist, hist + kHistBins, sc);
-    hipLaunchKernelGGL(k_collect, dim3(g), dim3(256), 0, h->stream, keys, J, hist + kHistBins, sc, sel, bnd);
+    const unsigned gc = (unsigned)((h->cfg.j + 256 * kCollectPerThread - 1) / (256 * kCollectPerThread));
+    hipLaunchKernelGGL(k_collect, dim3(gc), dim3(256), 0, h->stream, keys, J, hist + kHistBins, sc, sel, bnd);
     const uint32_t cap = (uint32_t)h->select_cap;
     const size_t lds = (size_t)(cap > 2u * STRADS_MAX_L_PRIME ? cap : 2u * STRADS_MAX_L_PRIME) * sizeof(uint64_t);
     hipLaunchKernelGGL(k_finalize, dim3(1), dim3(1024), lds, h->stream, sc, sel, bnd, L, (uint32_t)h->Lpad, cap,

@@ -92,8 +92,7 @@ hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys);  // st
 hipError_t launch_gram_dense(strads_lasso *h, int part);  // Step 2a; part 0: K-slice tiles, part 1: sum + conflict mask
 hipError_t launch_mask_from_gram(strads_lasso *h, const float *gram, int32_t l);
 hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates);                    // Step 2b -> kept_pos, kept, n_kept
-hipError_t launch_dots_dense(strads_lasso *h);                             // x_j^T r for the kept set
-hipError_t launch_update(strads_lasso *h);                                 // eq. (2) + bookkeeping
+hipError_t launch_dots_dense(strads_lasso *h);                             // x_j^T r for the kept set + eq. (2) update
 hipError_t launch_residual_dense(strads_lasso *h);                         // r -= X_B delta_B
 hipError_t launch_objective(strads_lasso *h);                              // -> objout
 hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null);            // -> scalars.kkt_max_bits

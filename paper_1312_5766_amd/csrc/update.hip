@@ -62,131 +62,133 @@ __device__ __forceinline__ float column_dot(const float *__restrict__ x, const f
     return s;                                   // valid in thread 0 of the group
 }
 
-// z[c] = x_{kept[c]}^T r for c < n_kept.  Launched for the worst case (L columns); groups past
-// the device-side count exit.
-template <int TPC, bool VEC4>
-__global__ __launch_bounds__(256) void k_dots(const float *__restrict__ X, int64_t N, const int32_t *__restrict__ kept,
-                                              const RoundScalars *__restrict__ sc, const float *__restrict__ r,
-                                              float *__restrict__ z)
-{
-    __shared__ float red[4];
-    constexpr int CPB = 256 / TPC;              // columns per workgroup
-    const int c = blockIdx.x * CPB + threadIdx.x / TPC;
-    if (TPC == 256) { if (c >= sc->n_kept) return; }
-    const bool on = c < sc->n_kept;
-    if (TPC == 64 && !on) return;               // whole wavefront
-    const float s = column_dot<TPC, VEC4>(X + (int64_t)kept[c] * N, r, N, threadIdx.x % TPC, red);
-    if (threadIdx.x % TPC == 0) z[c] = s;
-}
-
 __device__ __forceinline__ float soft_threshold(float a, float lambda)
 {
     const float m = fabsf(a) - lambda;
     return m > 0.f ? copysignf(m, a) : 0.f;
 }
 
-// eq. (2) + Step 4 for the kept set, and the ordered list of coordinates that actually moved.
-__global__ __launch_bounds__(1024) void k_update(const int32_t *__restrict__ kept, const float *__restrict__ z,
-                                                 float lambda, float *__restrict__ beta, float *__restrict__ dbeta,
-                                                 float *__restrict__ delta, int32_t *__restrict__ mv_col,
-                                                 float *__restrict__ mv_delta, RoundScalars *__restrict__ sc)
+// For every kept coordinate c < n_kept: z[c] = x_j^T r (r as it was when the round began), then
+// eq. (2) and Step 4 at once: beta_j <- S(z + beta_j, lambda), delta[c] = change, dbeta_j = |change|.
+// Kept coordinates are distinct, so each beta_j has exactly one writer.  Launched for the worst
+// case (L columns); groups past the device-side count exit.
+template <int TPC, bool VEC4>
+__global__ __launch_bounds__(256) void k_dots_update(const float *__restrict__ X, int64_t N,
+                                                     const int32_t *__restrict__ kept,
+                                                     const RoundScalars *__restrict__ sc, const float *__restrict__ r,
+                                                     float lambda, float *__restrict__ beta, float *__restrict__ dbeta,
+                                                     float *__restrict__ z, float *__restrict__ delta)
 {
-    __shared__ uint32_t wt[16];
-    __shared__ float wm[16];
-    const int n = sc->n_kept;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t base = 0;
-    float mx = 0.f;
-    for (int s = 0; s < n; s += 1024) {
-        const int c = s + threadIdx.x;
-        float d = 0.f;
-        int32_t j = 0;
-        if (c < n) {
-            j = kept[c];
-            const float b = beta[j];
-            const float nb = soft_threshold(z[c] + b, lambda);
-            d = nb - b;
-            beta[j] = nb;
-            dbeta[j] = fabsf(d);
-            delta[c] = d;
-            mx = fmaxf(mx, fabsf(d));
-        }
-        const bool mv = c < n && d != 0.f;
-        const uint64_t m = __ballot(mv);
-        if (lane == 0) wt[wave] = (uint32_t)__popcll(m);
-        __syncthreads();
-        uint32_t before = 0, tot = 0;
-        for (int w = 0; w < 16; ++w) { const uint32_t v = wt[w]; if (w < wave) before += v; tot += v; }
-        if (mv) {
-            const uint32_t p = base + before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-            mv_col[p] = j;
-            mv_delta[p] = d;
-        }
-        base += tot;
-        __syncthreads();
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_down(mx, off));
-    if (lane == 0) wm[wave] = mx;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        float m = 0.f;
-        for (int w = 0; w < 16; ++w) m = fmaxf(m, wm[w]);
-        sc->n_moved = (int32_t)base;
-        sc->max_abs_delta = m;
+    __shared__ float red[4];
+    constexpr int CPB = 256 / TPC;              // columns per workgroup
+    const int c = blockIdx.x * CPB + threadIdx.x / TPC;
+    if (c >= sc->n_kept) return;                // TPC = 256: whole workgroup; TPC = 64: whole wavefront
+    const int32_t j = kept[c];
+    const float s = column_dot<TPC, VEC4>(X + (int64_t)j * N, r, N, threadIdx.x % TPC, red);
+    if (threadIdx.x % TPC == 0) {
+        const float b = beta[j];
+        const float nb = soft_threshold(s + b, lambda);
+        const float d = nb - b;
+        z[c] = s;
+        delta[c] = d;
+        beta[j] = nb;
+        dbeta[j] = fabsf(d);
     }
 }
 
-// Residual update, stage 1: column group g sums its share of x_j * change_j for 4 rows per
-// thread, in list order.  part[g][i].
+// Residual update r <- r - sum_c x_{kept[c]} * delta[c], stage 1.  grid = (row tiles of 1024 rows,
+// G column groups).  Group g owns kept positions [k*g/G, k*(g+1)/G) and sums its movers
+// (delta != 0) in list order for 4 rows per thread -> part[g][i].
 template <bool VEC4>
 __global__ __launch_bounds__(256) void k_residual_partial(const float *__restrict__ X, int64_t N, int64_t Npad,
-                                                          const int32_t *__restrict__ mv_col,
-                                                          const float *__restrict__ mv_delta,
-                                                          const RoundScalars *__restrict__ sc, float *__restrict__ part)
+                                                          const int32_t *__restrict__ kept,
+                                                          const float *__restrict__ delta,
+                                                          RoundScalars *__restrict__ sc, float *__restrict__ part)
 {
-    const int m = sc->n_moved;
+    __shared__ int32_t mcol[256];
+    __shared__ float mdel[256];
+    __shared__ uint32_t wcnt[4];
+    const int k = sc->n_kept;
     const int G = gridDim.y, g = blockIdx.y;
-    const int c0 = (int)((int64_t)m * g / G), c1 = (int)((int64_t)m * (g + 1) / G);
-    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
-    if (i >= N) return;
+    const int c0 = (int)((int64_t)k * g / G), c1 = (int)((int64_t)k * (g + 1) / G);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t i = ((int64_t)blockIdx.x * 256 + tid) * 4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (VEC4) {
-        int c = c0;
-        for (; c + 3 < c1; c += 4) {
-            const float4 v0 = *reinterpret_cast<const float4 *>(X + (int64_t)mv_col[c] * N + i);
-            const float4 v1 = *reinterpret_cast<const float4 *>(X + (int64_t)mv_col[c + 1] * N + i);
-            const float4 v2 = *reinterpret_cast<const float4 *>(X + (int64_t)mv_col[c + 2] * N + i);
-            const float4 v3 = *reinterpret_cast<const float4 *>(X + (int64_t)mv_col[c + 3] * N + i);
-            const float d0 = mv_delta[c], d1 = mv_delta[c + 1], d2 = mv_delta[c + 2], d3 = mv_delta[c + 3];
-            acc.x += v0.x * d0; acc.y += v0.y * d0; acc.z += v0.z * d0; acc.w += v0.w * d0;
-            acc.x += v1.x * d1; acc.y += v1.y * d1; acc.z += v1.z * d1; acc.w += v1.w * d1;
-            acc.x += v2.x * d2; acc.y += v2.y * d2; acc.z += v2.z * d2; acc.w += v2.w * d2;
-            acc.x += v3.x * d3; acc.y += v3.y * d3; acc.z += v3.z * d3; acc.w += v3.w * d3;
+
+    for (int cb = c0; cb < c1; cb += 256) {     // movers of this group, 256 kept positions at a time
+        const int c = cb + tid;
+        const float d = c < c1 ? delta[c] : 0.f;
+        const bool mv = d != 0.f;
+        const uint64_t m = __ballot(mv);
+        if (lane == 0) wcnt[wave] = (uint32_t)__popcll(m);
+        __syncthreads();
+        uint32_t before = 0, tot = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { const uint32_t v = wcnt[w]; if (w < wave) before += v; tot += v; }
+        if (mv) {
+            const uint32_t p = before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            mcol[p] = kept[c];
+            mdel[p] = d;
         }
-        for (; c < c1; ++c) {
-            const float4 v = *reinterpret_cast<const float4 *>(X + (int64_t)mv_col[c] * N + i);
-            const float d = mv_delta[c];
-            acc.x += v.x * d; acc.y += v.y * d; acc.z += v.z * d; acc.w += v.w * d;
+        __syncthreads();
+        if (i < N) {
+            if (VEC4) {
+                uint32_t q = 0;
+                for (; q + 3 < tot; q += 4) {
+                    const float4 v0 = *reinterpret_cast<const float4 *>(X + (int64_t)mcol[q] * N + i);
+                    const float4 v1 = *reinterpret_cast<const float4 *>(X + (int64_t)mcol[q + 1] * N + i);
+                    const float4 v2 = *reinterpret_cast<const float4 *>(X + (int64_t)mcol[q + 2] * N + i);
+                    const float4 v3 = *reinterpret_cast<const float4 *>(X + (int64_t)mcol[q + 3] * N + i);
+                    const float d0 = mdel[q], d1 = mdel[q + 1], d2 = mdel[q + 2], d3 = mdel[q + 3];
+                    acc.x += v0.x * d0; acc.y += v0.y * d0; acc.z += v0.z * d0; acc.w += v0.w * d0;
+                    acc.x += v1.x * d1; acc.y += v1.y * d1; acc.z += v1.z * d1; acc.w += v1.w * d1;
+                    acc.x += v2.x * d2; acc.y += v2.y * d2; acc.z += v2.z * d2; acc.w += v2.w * d2;
+                    acc.x += v3.x * d3; acc.y += v3.y * d3; acc.z += v3.z * d3; acc.w += v3.w * d3;
+                }
+                for (; q < tot; ++q) {
+                    const float4 v = *reinterpret_cast<const float4 *>(X + (int64_t)mcol[q] * N + i);
+                    const float dd = mdel[q];
+                    acc.x += v.x * dd; acc.y += v.y * dd; acc.z += v.z * dd; acc.w += v.w * dd;
+                }
+            } else {
+                for (uint32_t q = 0; q < tot; ++q) {
+                    const float *x = X + (int64_t)mcol[q] * N + i;
+                    const float dd = mdel[q];
+                    acc.x += x[0] * dd;
+                    if (i + 1 < N) acc.y += x[1] * dd;
+                    if (i + 2 < N) acc.z += x[2] * dd;
+                    if (i + 3 < N) acc.w += x[3] * dd;
+                }
+            }
         }
-    } else {
-        for (int c = c0; c < c1; ++c) {
-            const float *x = X + (int64_t)mv_col[c] * N + i;
-            const float d = mv_delta[c];
-            acc.x += x[0] * d;
-            if (i + 1 < N) acc.y += x[1] * d;
-            if (i + 2 < N) acc.z += x[2] * d;
-            if (i + 3 < N) acc.w += x[3] * d;
+        __syncthreads();
+    }
+    if (i < N) *reinterpret_cast<float4 *>(part + (int64_t)g * Npad + i) = acc;
+
+    // round summary for strads_lasso_round's info (one workgroup does it; cheap: k <= 8192)
+    if (blockIdx.x == 0 && g == 0) {
+        uint32_t nm = 0;
+        float mx = 0.f;
+        for (int c = tid; c < k; c += 256) { const float d = delta[c]; nm += d != 0.f; mx = fmaxf(mx, fabsf(d)); }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) { nm += __shfl_down(nm, off); mx = fmaxf(mx, __shfl_down(mx, off)); }
+        __shared__ uint32_t snm[4];
+        __shared__ float smx[4];
+        if (lane == 0) { snm[wave] = nm; smx[wave] = mx; }
+        __syncthreads();
+        if (tid == 0) {
+            sc->n_moved = (int32_t)(snm[0] + snm[1] + snm[2] + snm[3]);
+            sc->max_abs_delta = fmaxf(fmaxf(smx[0], smx[1]), fmaxf(smx[2], smx[3]));
         }
     }
-    *reinterpret_cast<float4 *>(part + (int64_t)g * Npad + i) = acc;
+
 }
 
-// stage 2: r[i] -= sum_g part[g][i], groups in order
+// stage 2: r[i] -= sum_g part[g][i], groups in order (a kernel boundary, not an in-kernel fence,
+// makes the partial sums visible: a device-wide fence would write back every L2 of the 8 dies)
 __global__ __launch_bounds__(256) void k_residual_apply(const float *__restrict__ part, int G, int64_t N, int64_t Npad,
-                                                        const RoundScalars *__restrict__ sc, float *__restrict__ r)
+                                                        float *__restrict__ r)
 {
-    if (sc->n_moved == 0) return;
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= N) return;
     float s = 0.f;
@@ -273,49 +275,40 @@ hipError_t launch_dots_dense(strads_lasso *h)
 {
     const RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     const float *r = h->at<float>(h->ws.r);
-    float *z = h->at<float>(h->ws.z);
     const int32_t *kept = h->at<int32_t>(h->ws.kept);
     const bool wide = h->cfg.n > 2048;
     const unsigned grid = wide ? (unsigned)h->L : (unsigned)((h->L + 3) / 4);
-#define STRADS_DOTS(TPC, V) hipLaunchKernelGGL((k_dots<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, kept, sc, r, z)
+#define STRADS_DOTS(TPC, V) hipLaunchKernelGGL((k_dots_update<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, kept, sc, r, h->cfg.lambda, h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.z), h->at<float>(h->ws.delta))
     if (wide) { if (h->vec4) STRADS_DOTS(256, true); else STRADS_DOTS(256, false); }
     else      { if (h->vec4) STRADS_DOTS(64, true);  else STRADS_DOTS(64, false); }
 #undef STRADS_DOTS
     return hipGetLastError();
 }
 
-hipError_t launch_update(strads_lasso *h)
+int residual_groups(int64_t n, int32_t l)
 {
-    hipLaunchKernelGGL(k_update, dim3(1), dim3(1024), 0, h->stream, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.z),
-                       h->cfg.lambda, h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.delta),
-                       h->at<int32_t>(h->ws.mv_col), h->at<float>(h->ws.mv_delta), h->at<RoundScalars>(h->ws.scalars));
-    return hipGetLastError();
-}
-
-static int residual_groups(const strads_lasso *h)
-{
-    const int64_t rowblocks = (h->cfg.n + 1023) / 1024;
+    const int64_t rowblocks = (n + 1023) / 1024;
     int64_t G = 2048 / rowblocks;
     if (G > kMaxResidualGroups) G = kMaxResidualGroups;
-    if (G > h->L) G = h->L;
+    if (G > l) G = l;
     if (G < 1) G = 1;
     return (int)G;
 }
 
 hipError_t launch_residual_dense(strads_lasso *h)
 {
-    const RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
-    const int G = residual_groups(h);
+    RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    const int G = residual_groups(h->cfg.n, h->L);
     const dim3 grid((unsigned)((h->cfg.n + 1023) / 1024), (unsigned)G);
     float *part = h->at<float>(h->ws.rpart);
     if (h->vec4)
         hipLaunchKernelGGL(k_residual_partial<true>, grid, dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->Npad,
-                           h->at<int32_t>(h->ws.mv_col), h->at<float>(h->ws.mv_delta), sc, part);
+                           h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc, part);
     else
         hipLaunchKernelGGL(k_residual_partial<false>, grid, dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->Npad,
-                           h->at<int32_t>(h->ws.mv_col), h->at<float>(h->ws.mv_delta), sc, part);
+                           h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc, part);
     hipLaunchKernelGGL(k_residual_apply, dim3((unsigned)((h->cfg.n + 255) / 256)), dim3(256), 0, h->stream, part, G,
-                       h->cfg.n, h->Npad, sc, h->at<float>(h->ws.r));
+                       h->cfg.n, h->Npad, h->at<float>(h->ws.r));
     return hipGetLastError();
 }
 
