@@ -80,6 +80,8 @@ typedef struct {
     int32_t        keep_gram;     /* nonzero: also store the full fp32 candidate Gram of the last
                                      round so strads_lasso_last_round can return it (costs
                                      4*L^2 bytes of workspace and one extra write per round) */
+    int32_t        max_col_nnz;   /* CSC only: an upper bound (>= 1) on the nonzeros of any column;
+                                     sizes the per-round inverted index; checked at create */
     void          *workspace;     /* DEVICE, 256-byte aligned, caller-allocated */
     size_t         workspace_bytes;
     void          *stream;        /* hipStream_t owned by the caller (NULL = the default stream) */
@@ -104,11 +106,13 @@ typedef struct {
 
 /* Bytes of workspace a configuration needs (depends on n, j, layout, l_prime,
  * keep_gram only; pointers in cfg are ignored).  Makes no device call.
- * Returns 0 if cfg is NULL or a size field is invalid. */
+ * (and max_col_nnz for CSC).  Returns 0 if cfg is NULL or a size field is invalid. */
 size_t strads_lasso_workspace_bytes(const strads_lasso_config_t *cfg);
 
 /* Validate cfg, carve the workspace and enqueue Algorithm 1's initialisation:
- * beta = 0, delta beta = c_init for every j, r = y, round counter = 0.
+ * beta = 0, delta beta = c_init for every j, r = y, round counter = 0.  For a CSC design it also
+ * checks col_ptr (starts at 0, non-decreasing, no column above max_col_nnz) on the device and
+ * waits for that check; row indices must lie in [0, n) and are not checked.
  * *out receives a host-side handle (free it with strads_lasso_destroy). */
 int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out);
 

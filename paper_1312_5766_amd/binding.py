@@ -36,7 +36,7 @@ class Config(C.Structure):
                 ("row_idx", C.c_void_p), ("col_ptr", C.c_void_p), ("y", C.c_void_p),
                 ("lam", C.c_float), ("rho", C.c_float), ("eta", C.c_float), ("c_init", C.c_float),
                 ("l_prime", C.c_int32), ("p_max", C.c_int32), ("seed", C.c_uint64), ("keep_gram", C.c_int32),
-                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
+                ("max_col_nnz", C.c_int32), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
 
 
 class RoundInfo(C.Structure):
@@ -102,8 +102,8 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else t.data_ptr()
 
 
-def strads_lasso_workspace_bytes(n, j, l_prime, layout=LAYOUT_DENSE, keep_gram=False) -> int:
-    cfg = Config(n=n, j=j, layout=layout, l_prime=l_prime, keep_gram=int(keep_gram))
+def strads_lasso_workspace_bytes(n, j, l_prime, layout=LAYOUT_DENSE, keep_gram=False, max_col_nnz=0) -> int:
+    cfg = Config(n=n, j=j, layout=layout, l_prime=l_prime, keep_gram=int(keep_gram), max_col_nnz=int(max_col_nnz))
     return int(load().strads_lasso_workspace_bytes(C.byref(cfg)))
 
 
@@ -114,7 +114,8 @@ class StradsLasso:
                  p_max: int = 0, c_init: float = 1e6, keep_gram: bool = False,
                  x: Optional[torch.Tensor] = None, values: Optional[torch.Tensor] = None,
                  row_idx: Optional[torch.Tensor] = None, col_ptr: Optional[torch.Tensor] = None,
-                 n: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None):
+                 n: Optional[int] = None, max_col_nnz: Optional[int] = None,
+                 stream: Optional[torch.cuda.Stream] = None):
         lib = load()
         self._h = None
         dev = y.device
@@ -131,13 +132,15 @@ class StradsLasso:
             self.J, self.N = col_ptr.numel() - 1, int(n)
             layout = LAYOUT_CSC
             self._keep = (values, row_idx, col_ptr, y)
+            if max_col_nnz is None:
+                max_col_nnz = int((col_ptr[1:] - col_ptr[:-1]).max().item())
         assert y.dtype == torch.float32 and y.is_contiguous() and y.numel() == self.N
         self.L = min(int(l_prime), self.J)
         self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
         cfg = Config(n=self.N, j=self.J, layout=layout, x=_ptr(x if x is not None else values),
                      row_idx=_ptr(row_idx), col_ptr=_ptr(col_ptr), y=_ptr(y), lam=lam, rho=rho, eta=eta,
                      c_init=c_init, l_prime=int(l_prime), p_max=int(p_max), seed=int(seed),
-                     keep_gram=int(keep_gram), stream=self.stream.cuda_stream)
+                     keep_gram=int(keep_gram), max_col_nnz=int(max_col_nnz or 0), stream=self.stream.cuda_stream)
         nbytes = int(lib.strads_lasso_workspace_bytes(C.byref(cfg)))
         if nbytes == 0:
             raise StradsError(E_INVALID_ARG, "strads_lasso_workspace_bytes")

@@ -16,7 +16,7 @@ static int split_for_workspace(int64_t n, int32_t lpad)
     return gram_split_auto(n, lpad);
 }
 
-Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram)
+Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram, int32_t max_col_nnz)
 {
     Workspace w;
     memset(&w, 0, sizeof(w));
@@ -37,7 +37,7 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
         w.partial = take((size_t)split_for_workspace(n, (int32_t)lpad) * lpad * lpad * 4);
     else
         w.partial = take(256);
-    w.gram = take(keep_gram || layout == STRADS_LAYOUT_CSC ? (size_t)lpad * lpad * 4 : 256);
+    w.gram = take(keep_gram ? (size_t)lpad * lpad * 4 : 256);
     w.mask = take((size_t)lpad * (lpad / 64) * 8);
     w.kept_pos = take((size_t)lpad * 4);
     w.kept = take((size_t)lpad * 4);
@@ -48,7 +48,7 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
     w.rpart = take((size_t)kMaxResidualGroups * npad * 4);
     w.objpart = take((size_t)kObjBlocks * 8);
     w.objout = take(8);
-    w.csc_scratch_bytes = layout == STRADS_LAYOUT_CSC ? csc_scratch_bytes(n, (int32_t)lpad) : 0;
+    w.csc_scratch_bytes = layout == STRADS_LAYOUT_CSC ? csc_scratch_bytes(n, l, max_col_nnz) : 0;
     w.csc_scratch = take(w.csc_scratch_bytes ? w.csc_scratch_bytes : 256);
     w.total = off;
     return w;
@@ -60,7 +60,7 @@ static bool sizes_ok(const strads_lasso_config_t *c)
     if (c->n <= 0 || c->j <= 0 || c->j >= (int64_t)1 << 31) return false;
     if (c->layout != STRADS_LAYOUT_DENSE_COLMAJOR && c->layout != STRADS_LAYOUT_CSC) return false;
     if (c->l_prime < 1 || c->l_prime > STRADS_MAX_L_PRIME) return false;
-    if (c->layout == STRADS_LAYOUT_CSC && c->n >= (int64_t)1 << 31) return false;
+    if (c->layout == STRADS_LAYOUT_CSC && (c->n >= (int64_t)1 << 31 || c->max_col_nnz < 1)) return false;
     return true;
 }
 
@@ -80,7 +80,7 @@ extern "C" {
 size_t strads_lasso_workspace_bytes(const strads_lasso_config_t *cfg)
 {
     if (!sizes_ok(cfg)) return 0;
-    return carve(cfg->n, cfg->j, cfg->layout, clamp_l(cfg), cfg->keep_gram).total;
+    return carve(cfg->n, cfg->j, cfg->layout, clamp_l(cfg), cfg->keep_gram, cfg->max_col_nnz).total;
 }
 
 int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
@@ -97,7 +97,7 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     if (((uintptr_t)cfg->x & 3u) != 0 || ((uintptr_t)cfg->y & 3u) != 0) return STRADS_E_INVALID_ARG;
 
     const int32_t L = clamp_l(cfg);
-    const Workspace ws = carve(cfg->n, cfg->j, cfg->layout, L, cfg->keep_gram);
+    const Workspace ws = carve(cfg->n, cfg->j, cfg->layout, L, cfg->keep_gram, cfg->max_col_nnz);
     if (cfg->workspace_bytes < ws.total) return STRADS_E_WORKSPACE_TOO_SMALL;
 
     strads_lasso *h = (strads_lasso *)calloc(1, sizeof(strads_lasso));
@@ -123,6 +123,18 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     if (launch_init_state(h) != hipSuccess) {
         free(h);
         return STRADS_E_HIP;
+    }
+    if (cfg->layout == STRADS_LAYOUT_CSC) {
+        // the sparse kernels size their buckets from max_col_nnz: check col_ptr against it once
+        RoundScalars sc;
+        if (csc_prepare() != hipSuccess ||
+            launch_csc_init(h, &h->at<RoundScalars>(ws.scalars)->bad_input) != hipSuccess ||
+            hipMemcpyAsync(&sc, h->base + ws.scalars, sizeof(sc), hipMemcpyDeviceToHost, h->stream) != hipSuccess ||
+            hipStreamSynchronize(h->stream) != hipSuccess) {
+            free(h);
+            return STRADS_E_HIP;
+        }
+        if (sc.bad_input != 0) { free(h); return STRADS_E_INVALID_ARG; }
     }
     *out = h;
     return STRADS_OK;

@@ -1,10 +1,347 @@
-// CSC (sparse) design: placeholders until the sparse kernels are in.
+// The round for a sparse design in CSC form (column j = rows row_idx[col_ptr[j] .. col_ptr[j+1]),
+// increasing, with values val[...]).  Same steps as the dense path (Algorithm 1, eq. (2), Step 2's
+// d(x_a, x_b) = |x_a^T x_b|), different kernels:
+//
+//   candidate Gram   A dense MFMA Gram of gathered sparse columns would multiply zeros.  Instead an
+//                    inverted index of the candidate set is built per round (row -> list of
+//                    (candidate, value)); candidate a then walks its own rows and, for every other
+//                    candidate met in a row, adds the product into an LDS row G[a][*].
+//   residual update  r -= sum_j x_j * change_j scatters into rows that several columns may share.
+//
+// Both accumulate through integer atomics on a 2^-40 fixed-point image of each product (the fp64
+// product of two floats is exact; it is rounded once to the grid).  Integer addition is associative,
+// so the sums do not depend on the order in which atomics land: results are bit-reproducible, and
+// the rounding error (<= 2^-41 per term) is far below fp32 accumulation error.
+//
+//   dots / KKT       one wavefront per column: 8 bytes per nonzero streamed, r gathered from L2.
 #include "strads_internal.h"
 
 namespace strads {
-size_t csc_scratch_bytes(int64_t, int32_t) { return 0; }
-hipError_t launch_gram_csc(strads_lasso *) { return hipErrorNotSupported; }
-hipError_t launch_dots_csc(strads_lasso *) { return hipErrorNotSupported; }
-hipError_t launch_residual_csc(strads_lasso *) { return hipErrorNotSupported; }
-hipError_t launch_kkt_csc(strads_lasso *, float *) { return hipErrorNotSupported; }
+
+constexpr double kFixScale = 1099511627776.0;          // 2^40
+constexpr double kFixInv = 1.0 / 1099511627776.0;
+
+__device__ __forceinline__ long long fix40(float a, float b)
+{
+    return __double2ll_rn((double)a * (double)b * kFixScale);
+}
+
+struct CscEntry { int32_t cand; float val; };
+
+struct CscScratch {
+    uint32_t *cnt;          // [N]   per-row entry count (returns to zero after the fill pass)
+    uint32_t *row_start;    // [N+1] exclusive scan of cnt
+    CscEntry *entries;      // [L * max_col_nnz]
+    long long *racc;        // [N]   fixed-point residual accumulator (returns to zero after apply)
+};
+
+static CscScratch csc_carve(const strads_lasso *h)
+{
+    char *p = h->base + h->ws.csc_scratch;
+    const size_t n = (size_t)h->cfg.n;
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    CscScratch s;
+    s.cnt = (uint32_t *)p;               p += up(n * 4);
+    s.row_start = (uint32_t *)p;         p += up((n + 1) * 4);
+    s.racc = (long long *)p;             p += up(n * 8);
+    s.entries = (CscEntry *)p;
+    return s;
+}
+
+size_t csc_scratch_bytes(int64_t n, int32_t l, int32_t max_col_nnz)
+{
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    return up((size_t)n * 4) + up(((size_t)n + 1) * 4) + up((size_t)n * 8) +
+           up((size_t)l * (size_t)(max_col_nnz > 0 ? max_col_nnz : 1) * sizeof(CscEntry));
+}
+
+// ---------------------------------------------------------------------------------------------
+// create-time check: col_ptr non-decreasing, starts at 0, no column longer than max_col_nnz
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_csc_check(const int64_t *__restrict__ col_ptr, int64_t J, int32_t max_col_nnz,
+                                                   uint32_t *__restrict__ bad)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < J; j += stride) {
+        const int64_t d = col_ptr[j + 1] - col_ptr[j];
+        if (d < 0 || d > max_col_nnz || (j == 0 && col_ptr[0] != 0)) atomicOr(bad, 1u);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_csc_zero(uint32_t *__restrict__ cnt, long long *__restrict__ racc, int64_t N,
+                                                  uint32_t *__restrict__ bad)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < N; i += stride) { cnt[i] = 0u; racc[i] = 0; }
+    if (blockIdx.x == 0 && threadIdx.x == 0) *bad = 0u;
+}
+
+// ---------------------------------------------------------------------------------------------
+// inverted index of the candidate set
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_csc_count(const int32_t *__restrict__ cand, const int64_t *__restrict__ col_ptr,
+                                                  const int32_t *__restrict__ row_idx, uint32_t *__restrict__ cnt)
+{
+    const int32_t j = cand[blockIdx.x];
+    const int64_t p0 = col_ptr[j], p1 = col_ptr[j + 1];
+    for (int64_t p = p0 + threadIdx.x; p < p1; p += 64) atomicAdd(&cnt[row_idx[p]], 1u);
+}
+
+// exclusive scan of cnt[0..N) by one workgroup: every thread owns a contiguous chunk
+__global__ __launch_bounds__(1024) void k_csc_scan(const uint32_t *__restrict__ cnt, int64_t N,
+                                                   uint32_t *__restrict__ row_start)
+{
+    __shared__ uint32_t tot[1024];
+    const int t = threadIdx.x;
+    const int64_t chunk = (N + 1023) / 1024;
+    const int64_t b = (int64_t)t * chunk, e = b + chunk < N ? b + chunk : N;
+    uint32_t s = 0;
+    for (int64_t i = b; i < e; ++i) s += cnt[i];
+    tot[t] = s;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {           // inclusive prefix over the 1024 chunk totals
+        const uint32_t v = t >= off ? tot[t - off] : 0u;
+        __syncthreads();
+        tot[t] += v;
+        __syncthreads();
+    }
+    uint32_t run = tot[t] - s;
+    for (int64_t i = b; i < e; ++i) { row_start[i] = run; run += cnt[i]; }
+    if (t == 1023) row_start[N] = tot[1023];
+}
+
+// place (candidate, value) into its row's bucket; the count doubles as a countdown cursor, so it is
+// back at zero when the pass ends
+__global__ __launch_bounds__(64) void k_csc_fill(const int32_t *__restrict__ cand, const int64_t *__restrict__ col_ptr,
+                                                 const int32_t *__restrict__ row_idx, const float *__restrict__ val,
+                                                 const uint32_t *__restrict__ row_start, uint32_t *__restrict__ cnt,
+                                                 CscEntry *__restrict__ entries)
+{
+    const int32_t a = blockIdx.x;
+    const int32_t j = cand[a];
+    const int64_t p0 = col_ptr[j], p1 = col_ptr[j + 1];
+    for (int64_t p = p0 + threadIdx.x; p < p1; p += 64) {
+        const int32_t row = row_idx[p];
+        const uint32_t slot = atomicSub(&cnt[row], 1u) - 1u;
+        CscEntry e;
+        e.cand = a;
+        e.val = val[p];
+        entries[row_start[row] + slot] = e;
+    }
+}
+
+// G[a][*] for candidate a = blockIdx.x, conflict bits for the words at or right of a's 128-tile
+__global__ __launch_bounds__(256) void k_csc_gram(const int32_t *__restrict__ cand, const int64_t *__restrict__ col_ptr,
+                                                  const int32_t *__restrict__ row_idx, const float *__restrict__ val,
+                                                  const uint32_t *__restrict__ row_start,
+                                                  const CscEntry *__restrict__ entries, int32_t L, int32_t Lpad,
+                                                  float rho, uint64_t *__restrict__ mask, float *__restrict__ gram,
+                                                  int32_t *__restrict__ near_pairs)
+{
+    extern __shared__ long long acc[];            // [Lpad]
+    const int32_t a = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int32_t first = (a / kGramTile) * kGramTile;
+    for (int32_t b = tid; b < Lpad; b += 256) acc[b] = 0;
+    __syncthreads();
+    if (a < L) {
+        const int32_t j = cand[a];
+        const int64_t p0 = col_ptr[j], p1 = col_ptr[j + 1];
+        for (int64_t p = p0 + tid; p < p1; p += 256) {
+            const int32_t row = row_idx[p];
+            const float v = val[p];
+            const uint32_t s = row_start[row], e = row_start[row + 1];
+            for (uint32_t q = s; q < e; ++q) {
+                const CscEntry en = entries[q];
+                if (en.cand >= first || gram)
+                    atomicAdd((unsigned long long *)&acc[en.cand], (unsigned long long)fix40(v, en.val));
+            }
+        }
+    }
+    __syncthreads();
+    int32_t near = 0;
+    for (int32_t b0 = (gram ? 0 : first); b0 < Lpad; b0 += 256) {
+        const int32_t b = b0 + tid;
+        if (b >= Lpad) break;                     // whole wavefronts: Lpad is a multiple of 64
+        const float g = (float)((double)acc[b] * kFixInv);
+        const bool live = a < L && b < L && a != b;
+        const float ag = fabsf(g);
+        const uint64_t w = __ballot(live && !(ag < rho));
+        if (b >= first && (tid & 63) == 0) mask[(int64_t)a * (Lpad / 64) + (b >> 6)] = w;
+        near += (live && b > a && fabsf(ag - rho) <= 1e-6f) ? 1 : 0;
+        if (gram) gram[(int64_t)a * Lpad + b] = g;
+    }
+    if (near) atomicAdd(near_pairs, near);
+}
+
+// ---------------------------------------------------------------------------------------------
+// eq. (2) for the kept set: one wavefront per column
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum_f(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
+    return v;
+}
+
+__device__ __forceinline__ float sparse_dot(const float *__restrict__ val, const int32_t *__restrict__ row_idx,
+                                            int64_t p0, int64_t p1, const float *__restrict__ r, int lane)
+{
+    float s = 0.f;
+    for (int64_t p = p0 + lane; p < p1; p += 64) s += val[p] * r[row_idx[p]];
+    return wave_sum_f(s);
+}
+
+__global__ __launch_bounds__(256) void k_csc_dots_update(const float *__restrict__ val,
+                                                         const int32_t *__restrict__ row_idx,
+                                                         const int64_t *__restrict__ col_ptr,
+                                                         const int32_t *__restrict__ kept,
+                                                         const RoundScalars *__restrict__ sc, const float *__restrict__ r,
+                                                         float lambda, float *__restrict__ beta, float *__restrict__ dbeta,
+                                                         float *__restrict__ z, float *__restrict__ delta)
+{
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (c >= sc->n_kept) return;
+    const int32_t j = kept[c];
+    const float s = sparse_dot(val, row_idx, col_ptr[j], col_ptr[j + 1], r, threadIdx.x & 63);
+    if ((threadIdx.x & 63) == 0) {
+        const float b = beta[j];
+        const float m = fabsf(s + b) - lambda;
+        const float nb = m > 0.f ? copysignf(m, s + b) : 0.f;
+        const float d = nb - b;
+        z[c] = s;
+        delta[c] = d;
+        beta[j] = nb;
+        dbeta[j] = fabsf(d);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_csc_residual_acc(const float *__restrict__ val,
+                                                          const int32_t *__restrict__ row_idx,
+                                                          const int64_t *__restrict__ col_ptr,
+                                                          const int32_t *__restrict__ kept,
+                                                          const float *__restrict__ delta, RoundScalars *__restrict__ sc,
+                                                          long long *__restrict__ racc)
+{
+    const int k = sc->n_kept;
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (blockIdx.x == 0) {                        // round summary, as in the dense path
+        __shared__ uint32_t snm[4];
+        __shared__ float smx[4];
+        uint32_t nm = 0;
+        float mx = 0.f;
+        for (int q = threadIdx.x; q < k; q += 256) { const float d = delta[q]; nm += d != 0.f; mx = fmaxf(mx, fabsf(d)); }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) { nm += __shfl_down(nm, off); mx = fmaxf(mx, __shfl_down(mx, off)); }
+        if ((threadIdx.x & 63) == 0) { snm[threadIdx.x >> 6] = nm; smx[threadIdx.x >> 6] = mx; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            sc->n_moved = (int32_t)(snm[0] + snm[1] + snm[2] + snm[3]);
+            sc->max_abs_delta = fmaxf(fmaxf(smx[0], smx[1]), fmaxf(smx[2], smx[3]));
+        }
+    }
+    if (c >= k) return;
+    const float d = delta[c];
+    if (d == 0.f) return;
+    const int32_t j = kept[c];
+    const int64_t p0 = col_ptr[j], p1 = col_ptr[j + 1];
+    for (int64_t p = p0 + (threadIdx.x & 63); p < p1; p += 64)
+        atomicAdd((unsigned long long *)&racc[row_idx[p]], (unsigned long long)fix40(val[p], d));
+}
+
+__global__ __launch_bounds__(256) void k_csc_residual_apply(long long *__restrict__ racc, int64_t N,
+                                                            float *__restrict__ r)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= N) return;
+    const long long v = racc[i];
+    if (v != 0) {
+        r[i] = (float)((double)r[i] - (double)v * kFixInv);
+        racc[i] = 0;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_csc_kkt(const float *__restrict__ val, const int32_t *__restrict__ row_idx,
+                                                 const int64_t *__restrict__ col_ptr, int64_t J,
+                                                 const float *__restrict__ r, const float *__restrict__ beta, float lambda,
+                                                 float *__restrict__ g_out, RoundScalars *__restrict__ sc)
+{
+    const int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= J) return;
+    const float g = sparse_dot(val, row_idx, col_ptr[j], col_ptr[j + 1], r, threadIdx.x & 63);
+    if ((threadIdx.x & 63) == 0) {
+        if (g_out) g_out[j] = g;
+        const float b = beta[j];
+        float v;
+        if (b == 0.f) v = fmaxf(fabsf(g) - lambda, 0.f);
+        else v = fabsf(g - copysignf(lambda, b));
+        if (!(v == v)) v = __uint_as_float(0x7F800000u);
+        atomicMax(&sc->kkt_max_bits, __float_as_uint(v));
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+hipError_t csc_prepare()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_csc_gram), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               STRADS_MAX_L_PRIME * 8);
+}
+
+// zero the scratch counters and check col_ptr; *bad_host is valid after the stream is synchronised
+hipError_t launch_csc_init(strads_lasso *h, uint32_t *bad_dev)
+{
+    const CscScratch s = csc_carve(h);
+    hipLaunchKernelGGL(k_csc_zero, dim3(1024), dim3(256), 0, h->stream, s.cnt, s.racc, h->cfg.n, bad_dev);
+    hipLaunchKernelGGL(k_csc_check, dim3(1024), dim3(256), 0, h->stream, h->cfg.col_ptr, h->cfg.j,
+                       h->cfg.max_col_nnz, bad_dev);
+    return hipGetLastError();
+}
+
+hipError_t launch_gram_csc(strads_lasso *h)
+{
+    const CscScratch s = csc_carve(h);
+    const int32_t *cand = h->at<int32_t>(h->ws.cand);
+    RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    hipLaunchKernelGGL(k_csc_count, dim3(h->L), dim3(64), 0, h->stream, cand, h->cfg.col_ptr, h->cfg.row_idx, s.cnt);
+    hipLaunchKernelGGL(k_csc_scan, dim3(1), dim3(1024), 0, h->stream, s.cnt, h->cfg.n, s.row_start);
+    hipLaunchKernelGGL(k_csc_fill, dim3(h->L), dim3(64), 0, h->stream, cand, h->cfg.col_ptr, h->cfg.row_idx, h->cfg.x,
+                       s.row_start, s.cnt, s.entries);
+    hipLaunchKernelGGL(k_csc_gram, dim3(h->L), dim3(256), (size_t)h->Lpad * 8, h->stream, cand, h->cfg.col_ptr,
+                       h->cfg.row_idx, h->cfg.x, s.row_start, s.entries, h->L, h->Lpad, h->cfg.rho,
+                       h->at<uint64_t>(h->ws.mask), h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr,
+                       &sc->near_rho_pairs);
+    return hipGetLastError();
+}
+
+hipError_t launch_dots_csc(strads_lasso *h)
+{
+    hipLaunchKernelGGL(k_csc_dots_update, dim3((h->L + 3) / 4), dim3(256), 0, h->stream, h->cfg.x, h->cfg.row_idx,
+                       h->cfg.col_ptr, h->at<int32_t>(h->ws.kept), h->at<RoundScalars>(h->ws.scalars),
+                       h->at<float>(h->ws.r), h->cfg.lambda, h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta),
+                       h->at<float>(h->ws.z), h->at<float>(h->ws.delta));
+    return hipGetLastError();
+}
+
+hipError_t launch_residual_csc(strads_lasso *h)
+{
+    const CscScratch s = csc_carve(h);
+    hipLaunchKernelGGL(k_csc_residual_acc, dim3((h->L + 3) / 4), dim3(256), 0, h->stream, h->cfg.x, h->cfg.row_idx,
+                       h->cfg.col_ptr, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta),
+                       h->at<RoundScalars>(h->ws.scalars), s.racc);
+    hipLaunchKernelGGL(k_csc_residual_apply, dim3((unsigned)((h->cfg.n + 255) / 256)), dim3(256), 0, h->stream, s.racc,
+                       h->cfg.n, h->at<float>(h->ws.r));
+    return hipGetLastError();
+}
+
+hipError_t launch_kkt_csc(strads_lasso *h, float *g_or_null)
+{
+    RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    hipError_t e = launch_clear_kkt(h);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_csc_kkt, dim3((unsigned)((h->cfg.j + 3) / 4)), dim3(256), 0, h->stream, h->cfg.x,
+                       h->cfg.row_idx, h->cfg.col_ptr, h->cfg.j, h->at<float>(h->ws.r), h->at<float>(h->ws.beta),
+                       h->cfg.lambda, g_or_null, sc);
+    return hipGetLastError();
+}
+
 } // namespace strads

@@ -30,7 +30,7 @@ struct RoundScalars {
     int32_t near_rho_pairs;
     float max_abs_delta;
     uint32_t kkt_max_bits; // float bits of the running max violation (>= 0, so uint order = float order)
-    uint32_t pad;
+    uint32_t bad_input;    // set by the create-time check of a CSC design
 };
 
 struct Workspace {
@@ -84,7 +84,7 @@ struct strads_lasso {
 namespace strads {
 
 int gram_split_auto(int64_t n, int32_t lpad);
-Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram);
+Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram, int32_t max_col_nnz);
 
 // Each launcher enqueues on h->stream and returns the hipError_t of the launch.
 hipError_t launch_sampler(strads_lasso *h, int64_t round);                 // Step 1 -> cand[L]
@@ -106,6 +106,8 @@ hipError_t launch_gram_csc(strads_lasso *h);
 hipError_t launch_dots_csc(strads_lasso *h);
 hipError_t launch_residual_csc(strads_lasso *h);
 hipError_t launch_kkt_csc(strads_lasso *h, float *g_or_null);
-size_t csc_scratch_bytes(int64_t n, int32_t l);
+size_t csc_scratch_bytes(int64_t n, int32_t l, int32_t max_col_nnz);
+hipError_t csc_prepare();
+hipError_t launch_csc_init(strads_lasso *h, uint32_t *bad_dev);
 
 } // namespace strads

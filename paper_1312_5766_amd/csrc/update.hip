@@ -230,6 +230,15 @@ __global__ __launch_bounds__(256) void k_objective_final(const double *__restric
     if (threadIdx.x == 0) *out = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+__device__ __forceinline__ float kkt_violation(float g, float b, float lambda)
+{
+    float v;
+    if (b == 0.f) v = fmaxf(fabsf(g) - lambda, 0.f);
+    else v = fabsf(g - copysignf(lambda, b));
+    if (!(v == v)) v = __uint_as_float(0x7F800000u);         // NaN counts as an infinite violation
+    return v;
+}
+
 // Optimality violation of eq. (1) per column and its maximum (integer atomicMax on the float
 // bits of a non-negative number: order-preserving and deterministic).
 template <int TPC, bool VEC4>
@@ -244,13 +253,60 @@ __global__ __launch_bounds__(256) void k_kkt(const float *__restrict__ X, int64_
     const float g = column_dot<TPC, VEC4>(X + j * N, r, N, threadIdx.x % TPC, red);
     if (threadIdx.x % TPC == 0) {
         if (g_out) g_out[j] = g;
-        const float b = beta[j];
-        float v;
-        if (b == 0.f) v = fmaxf(fabsf(g) - lambda, 0.f);
-        else v = fabsf(g - copysignf(lambda, b));
-        if (!(v == v)) v = __uint_as_float(0x7F800000u);     // NaN counts as an infinite violation
-        atomicMax(&sc->kkt_max_bits, __float_as_uint(v));
+        atomicMax(&sc->kkt_max_bits, __float_as_uint(kkt_violation(g, beta[j], lambda)));
     }
+}
+
+// The same pass for 2048 < N <= 1024*NR with 16-byte aligned columns: a persistent workgroup keeps
+// its slice of r in registers (NR float4 per thread) and streams columns two at a time, so X is
+// the only HBM/L2 traffic and one block-level reduction serves two columns.
+template <int NR>
+__global__ __launch_bounds__(256) void k_kkt_stream(const float *__restrict__ X, int64_t N, int64_t J,
+                                                    const float *__restrict__ r, const float *__restrict__ beta,
+                                                    float lambda, float *__restrict__ g_out,
+                                                    RoundScalars *__restrict__ sc)
+{
+    __shared__ float red[2][4];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int64_t n4 = N >> 2;
+    float4 rr[NR];
+#pragma unroll
+    for (int q = 0; q < NR; ++q) {
+        const int64_t i = (int64_t)q * 256 + t;
+        rr[q] = i < n4 ? reinterpret_cast<const float4 *>(r)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    float vmax = 0.f;
+    for (int64_t j0 = (int64_t)blockIdx.x * 2; j0 < J; j0 += (int64_t)gridDim.x * 2) {
+        const bool two = j0 + 1 < J;
+        const float4 *xa = reinterpret_cast<const float4 *>(X + j0 * N);
+        const float4 *xb = reinterpret_cast<const float4 *>(X + (two ? j0 + 1 : j0) * N);
+        float4 va[NR], vb[NR];
+#pragma unroll
+        for (int q = 0; q < NR; ++q) {
+            const int64_t i = (int64_t)q * 256 + t;
+            const int64_t ii = i < n4 ? i : n4 - 1;             // clamped: rr is zero there
+            va[q] = xa[ii];
+            vb[q] = xb[ii];
+        }
+        float sa = 0.f, sb = 0.f;
+#pragma unroll
+        for (int q = 0; q < NR; ++q) {
+            sa += va[q].x * rr[q].x + va[q].y * rr[q].y + va[q].z * rr[q].z + va[q].w * rr[q].w;
+            sb += vb[q].x * rr[q].x + vb[q].y * rr[q].y + vb[q].z * rr[q].z + vb[q].w * rr[q].w;
+        }
+        sa = wave_sum(sa);
+        sb = wave_sum(sb);
+        if (lane == 0) { red[0][wave] = sa; red[1][wave] = sb; }
+        __syncthreads();
+        if (t < 2 && (t == 0 || two)) {
+            const float g = (red[t][0] + red[t][1]) + (red[t][2] + red[t][3]);
+            const int64_t j = j0 + t;
+            if (g_out) g_out[j] = g;
+            vmax = fmaxf(vmax, kkt_violation(g, beta[j], lambda));
+        }
+        __syncthreads();
+    }
+    if (t < 2) atomicMax(&sc->kkt_max_bits, __float_as_uint(vmax));
 }
 
 __global__ __launch_bounds__(256) void k_init_state(const float *__restrict__ y, int64_t N, int64_t J, float c_init,
@@ -327,6 +383,19 @@ hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null)
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     hipLaunchKernelGGL(k_clear_kkt, dim3(1), dim3(1), 0, h->stream, sc);
     const bool wide = h->cfg.n > 2048;
+    if (wide && h->vec4 && h->cfg.n <= 16 * 1024) {
+        // persistent: 8 workgroups per compute unit
+        int64_t g = (h->cfg.j + 1) / 2;
+        if (g > 256 * 8) g = 256 * 8;
+        const int nr = (int)((h->cfg.n / 4 + 255) / 256);
+#define STRADS_KKT_STREAM(NR) hipLaunchKernelGGL((k_kkt_stream<NR>), dim3((unsigned)g), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->cfg.j, h->at<float>(h->ws.r), h->at<float>(h->ws.beta), h->cfg.lambda, g_or_null, sc)
+        if (nr <= 4) STRADS_KKT_STREAM(4);
+        else if (nr <= 8) STRADS_KKT_STREAM(8);
+        else if (nr <= 12) STRADS_KKT_STREAM(12);
+        else STRADS_KKT_STREAM(16);
+#undef STRADS_KKT_STREAM
+        return hipGetLastError();
+    }
     const unsigned grid = wide ? (unsigned)h->cfg.j : (unsigned)((h->cfg.j + 3) / 4);
 #define STRADS_KKT(TPC, V) hipLaunchKernelGGL((k_kkt<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->cfg.j, h->at<float>(h->ws.r), h->at<float>(h->ws.beta), h->cfg.lambda, g_or_null, sc)
     if (wide) { if (h->vec4) STRADS_KKT(256, true); else STRADS_KKT(256, false); }

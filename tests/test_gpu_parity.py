@@ -260,6 +260,70 @@ def test_reduced_configs_teacher_forced(config, kw, rounds):
     print("logged:", log)
 
 
+@pytest.mark.parametrize("kw,rounds", [
+    (dict(n=3000, j=20000, nnz_per_col=30, nnz=20, l_prime=600, rho=0.05), 8),
+    (dict(n=257, j=900, nnz_per_col=12, nnz=8, l_prime=130, rho=0.2), 10),
+    (dict(n=64, j=300, nnz_per_col=64, nnz=5, l_prime=300, rho=0.3), 5),      # every column is dense: heavy buckets
+])
+def test_csc_design_teacher_forced(kw, rounds):
+    p = si.make("c4_sparse_csc", **kw)
+    g, o = _pair(p)
+    log = []
+    for _ in range(rounds):
+        assert _check_round(g, o, log, teacher_forced=True)
+    assert g.objective() == pytest.approx(o.objective(), rel=OBJ_RTOL)
+    v, gg = g.kkt(want_g=True)
+    v_ref, g_ref = o.kkt(want_g=True)
+    rn = float(np.linalg.norm(o.r.astype(np.float64)))
+    _assert_close(_np(gg), g_ref, DOT_RTOL, 1e-6 * max(rn, 1.0), "x_j^T r for all columns (CSC)")
+    assert v == pytest.approx(v_ref, rel=1e-3, abs=1e-6 * max(rn, 1.0))
+    print("logged:", log)
+
+
+def test_csc_free_run_is_deterministic_and_tracks_oracle():
+    p = si.make("c4_sparse_csc", n=2000, j=6000, nnz_per_col=20, nnz=15, l_prime=256, rho=0.1)
+    a, o = _pair(p, keep_gram=False)
+    b, _ = _pair(p, keep_gram=False)
+    a.run(12)
+    b.run(12)
+    for u, v in zip(a.get_state()[:3], b.get_state()[:3]):
+        assert torch.equal(u, v)
+    c, o = _pair(p, keep_gram=True)
+    log = []
+    for _ in range(12):
+        if not _check_round(c, o, log, teacher_forced=False):
+            o.set_state(*[_np(x) if isinstance(x, torch.Tensor) else x for x in c.get_state()])
+        assert c.objective() == pytest.approx(o.objective(), rel=OBJ_RTOL)
+
+
+def test_csc_create_checks_column_bound():
+    pk = _gpu()
+    p = si.make("c4_sparse_csc", n=500, j=400, nnz_per_col=10, nnz=5, l_prime=50)
+    dev = torch.device("cuda:0")
+    kw = dict(values=p.values.to(dev), row_idx=p.row_idx.to(dev), col_ptr=p.col_ptr.to(dev), n=p.n, y=p.y.to(dev),
+              lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime)
+    pk.StradsLasso(max_col_nnz=10, **kw).close()
+    with pytest.raises(pk.StradsError) as e:
+        pk.StradsLasso(max_col_nnz=9, **kw)
+    assert e.value.code == -1
+
+
+@pytest.mark.parametrize("n", [2052, 5000, 10000, 16000, 16384, 16388, 2050])
+def test_kkt_pass_matches_oracle_across_row_counts(n):
+    # covers the register-resident streaming kernel (4/8/12/16 float4 of r per thread), its
+    # ragged last slice, and the fallbacks (N not a multiple of 4, N above the register budget)
+    p = si.make("c1_dense_iid", n=n, j=301, nnz=10, l_prime=64)
+    g, o = _pair(p, keep_gram=False)
+    for _ in range(3):
+        g.round()
+    o.set_state(*[_np(x) if isinstance(x, torch.Tensor) else x for x in g.get_state()])
+    v, gg = g.kkt(want_g=True)
+    v_ref, g_ref = o.kkt(want_g=True)
+    rn = float(np.linalg.norm(o.r.astype(np.float64)))
+    _assert_close(_np(gg), g_ref, DOT_RTOL, 1e-6 * max(rn, 1.0), "x_j^T r")
+    assert v == pytest.approx(v_ref, rel=1e-4, abs=1e-6 * max(rn, 1.0))
+
+
 def test_run_matches_repeated_rounds_and_is_deterministic():
     p = si.make("c1_dense_iid", n=800, j=2000, nnz=20, l_prime=128)
     a, _ = _pair(p, keep_gram=False)
