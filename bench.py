@@ -32,6 +32,9 @@ WORKLOADS = {
     "c2_dense_block_corr": ("c2_dense_block_corr", {}),
     "c1_dense_iid": ("c1_dense_iid", {}),
     "c3_genotype": ("c3_genotype", {}),
+    "c4_sparse_csc": ("c4_sparse_csc", {}),
+    # the fifth configuration's rows, duplicate structure and L'=8000 with J cut to fit quick runs
+    "c5_dense_duplicates_j60k": ("c5_dense_duplicates", dict(j=60000, nnz=200, rounds=20)),
     "c2_small": ("c2_dense_block_corr", dict(n=2000, j=8000, nnz=40, l_prime=500, rounds=16)),
 }
 
@@ -71,7 +74,10 @@ def main() -> int:
     t_gen = time.time() - t0
 
     def fresh():
-        return pk.StradsLasso(x=p.x, y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
+        kw = dict(y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
+        if p.layout == "dense":
+            return pk.StradsLasso(x=p.x, **kw)
+        return pk.StradsLasso(values=p.values, row_idx=p.row_idx, col_ptr=p.col_ptr, n=p.n, **kw)
 
     # warm-up on a throw-away handle, so that the timed region is the configuration's own
     # trajectory from round 0
@@ -108,12 +114,13 @@ def main() -> int:
     e1.record()
     torch.cuda.synchronize()
     kkt_ms = e0.elapsed_time(e1)
-    kkt_gbps = 4.0 * p.n * p.j / (kkt_ms * 1e-3) / 1e9
+    kkt_bytes = 4.0 * p.n * p.j if p.layout == "dense" else 8.0 * float(p.values.numel())
+    kkt_gbps = kkt_bytes / (kkt_ms * 1e-3) / 1e9
 
     L, N = g.L, p.n
     gram_flops = float(N) * L * (L - 1)          # algorithmic: every unordered pair once, 2 flops per row
     roofline = None
-    if args.profile_level and stage["rounds"] > 0 and stage["gram_tiles"] > 0:
+    if args.profile_level and stage["rounds"] > 0 and stage["gram_tiles"] > 0 and p.layout == "dense":
         ach = gram_flops / (stage["gram_tiles"] * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "k_gram_tiles", "achieved": round(ach, 3),
                     "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_FP32_PEAK_TFLOPS, 4),
@@ -123,8 +130,12 @@ def main() -> int:
     cpu = None
     if args.cpu_seconds > 0:
         from oracle.oracle import OracleLasso
-        xh = p.x.cpu().numpy()
-        o = OracleLasso(x=xh, y=p.y.cpu().numpy(), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
+        okw = dict(y=p.y.cpu().numpy(), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
+        if p.layout == "dense":
+            o = OracleLasso(x=p.x.cpu().numpy(), **okw)
+        else:
+            o = OracleLasso(values=p.values.cpu().numpy(), row_idx=p.row_idx.cpu().numpy(),
+                            col_ptr=p.col_ptr.cpu().numpy(), n=p.n, **okw)
         n_upd, n_rounds = 0, 0
         tc = time.perf_counter()
         while True:
@@ -147,7 +158,7 @@ def main() -> int:
         "rounds_per_s": round(args.steps / wall, 2), "updates": updates,
         "objective_start": f0, "objective_end": f1, "kkt_violation_end": viol,
         "roofline": roofline,
-        "hbm_pass": {"kernel": "k_kkt", "bytes": 4.0 * p.n * p.j, "ms": round(kkt_ms, 4), "achieved": round(kkt_gbps, 1),
+        "hbm_pass": {"kernel": "k_kkt", "bytes": kkt_bytes, "ms": round(kkt_ms, 4), "achieved": round(kkt_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(kkt_gbps / HBM_PEAK_GBPS, 4)},
         "stage_ms": {k: round(v, 5) for k, v in stage.items() if k != "rounds"},
         "cpu_baseline": cpu,

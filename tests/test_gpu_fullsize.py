@@ -1,0 +1,163 @@
+"""GPU parity at the configurations' full sizes, in the launch configuration bench.py times
+(no debug Gram, automatic K-slices).  The oracle cannot hold or sweep these designs whole, so it is
+run on what a round actually touches: the candidate columns are gathered to the host and the oracle's
+stage functions are applied to that sub-matrix; candidate lists come from the full delta-beta vector.
+Checked per round: candidate list bit-exact; kept set equal to the oracle's (or explained by a pair
+within 1e-6 of rho); dots, changes, beta at the kept coordinates and the whole residual within the
+stated tolerances; objective within 1e-5.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from synth import lasso_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def _close(got, ref, rtol, atol, what):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    err = np.abs(got - ref) - (rtol * np.abs(ref) + atol)
+    assert err.size == 0 or err.max() <= 0, f"{what}: worst excess {err.max():.3e} at {err.argmax()}"
+
+
+def _rounds_dense(p, rounds, gram_pairs=None, seed=0):
+    import paper_1312_5766_amd as pk
+    g = pk.StradsLasso(x=p.x, y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed,
+                       keep_gram=gram_pairs is not None)
+    rng = np.random.default_rng(seed)
+    logged = []
+    for t in range(rounds):
+        beta0, dbeta0, r0, t0 = g.get_state()
+        assert t0 == t
+        g.round()
+        lr = g.last_round(want_gram=gram_pairs is not None)
+        cand, kept_pos = _np(lr["cand"]), _np(lr["kept_pos"])
+        # Step 1 from the full delta-beta vector
+        ref_cand = orc.draw(orc.priority_keys(_np(dbeta0), p.eta, p.seed, t), p.l_prime)
+        assert np.array_equal(cand, ref_cand), f"candidate list differs in round {t}"
+        xs = _np(p.x[torch.from_numpy(cand.astype(np.int64)).to(p.x.device)])         # (L, N) gathered columns
+        L = len(cand)
+        local = np.arange(L, dtype=np.int32)
+        if gram_pairs is None:
+            Gref = orc.gram_dense(xs, local)
+            kept_ref = orc.greedy_filter(Gref, p.rho, 0)
+            if not np.array_equal(kept_pos, kept_ref):
+                near = np.abs(np.abs(Gref.astype(np.float64)) - p.rho) <= 1e-6
+                np.fill_diagonal(near, False)
+                assert near.any(), f"kept sets differ without a pair near rho (round {t})"
+                logged.append(("near_rho", t))
+        else:
+            # L is too large for a full oracle Gram: sampled entries, and the filter on the GPU's values
+            Ggpu = _np(lr["G"])
+            a = rng.integers(0, L, gram_pairs)
+            b = rng.integers(0, L, gram_pairs)
+            ref = np.einsum("ij,ij->i", xs[a].astype(np.float64), xs[b].astype(np.float64))
+            _close(Ggpu[a, b], ref, 1e-4, 1e-6, f"sampled Gram entries (round {t})")
+            assert np.array_equal(kept_pos, orc.greedy_filter(Ggpu, p.rho, 0)), f"filter differs on identical Gram ({t})"
+            # every conflict bit the filter acted on is a real correlation
+            assert np.array_equal(Ggpu, Ggpu.T)
+        kept = cand[kept_pos]
+        # eq. (2) on the gathered kept columns
+        xk = xs[kept_pos].astype(np.float64)
+        r0h = _np(r0).astype(np.float64)
+        rn = max(float(np.linalg.norm(r0h)), 1.0)
+        z_ref = xk @ r0h
+        _close(_np(lr["z"]), z_ref, 1e-4, 1e-6 * rn, f"dots (round {t})")
+        b_old = _np(beta0)[kept].astype(np.float64)
+        a_ = z_ref + b_old
+        b_new = (np.sign(a_) * np.maximum(np.abs(a_) - p.lam, 0)).astype(np.float32).astype(np.float64)
+        d_ref = b_new - b_old
+        _close(_np(lr["delta"]), d_ref, 1e-4, 2e-6 * rn, f"delta (round {t})")
+        beta1, dbeta1, r1, _ = g.get_state()
+        _close(_np(beta1)[kept], b_new, 1e-4, 2e-6 * rn, f"beta (round {t})")
+        _close(_np(dbeta1)[kept], np.abs(d_ref), 1e-4, 2e-6 * rn, f"dbeta (round {t})")
+        r_ref = r0h - d_ref @ xk
+        _close(_np(r1), r_ref, 1e-4, 2e-6 * rn, f"residual (round {t})")
+        # nothing outside the kept set moved
+        mask = torch.ones(p.j, dtype=torch.bool, device=beta1.device)
+        mask[torch.from_numpy(kept.astype(np.int64)).to(beta1.device)] = False
+        assert torch.equal(beta1[mask], beta0[mask]) and torch.equal(dbeta1[mask], dbeta0[mask])
+        f_ref = 0.5 * float((r_ref ** 2).sum()) + p.lam * float(np.abs(_np(beta1).astype(np.float64)).sum())
+        assert g.objective() == pytest.approx(f_ref, rel=1e-5)
+    g.close()
+    return logged
+
+
+def _skip_without_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+
+
+def test_config2_full_size():
+    _skip_without_gpu()
+    p = si.make("c2_dense_block_corr", device="cuda:0")          # 10^4 x 10^5, L' = 1000 (the bench workload)
+    assert (p.n, p.j, p.l_prime) == (10000, 100000, 1000)
+    print("logged:", _rounds_dense(p, 4))
+
+
+def test_config3_full_size():
+    _skip_without_gpu()
+    p = si.make("c3_genotype", device="cuda:0")                  # 500 x 5*10^5, L' = 2000
+    assert (p.n, p.j, p.l_prime) == (500, 500000, 2000)
+    print("logged:", _rounds_dense(p, 3))
+
+
+def test_config5_shape_at_maximum_candidate_count():
+    _skip_without_gpu()
+    # the fifth configuration's row count, duplicate structure and L' = 8000 (the largest supported
+    # neighbourhood: 8192-wide tiles, 128-word mask rows, LDS bitonic sort), with J cut from 10^6 to
+    # 6*10^4 so that the design (12 GB) is generated in seconds
+    p = si.make("c5_dense_duplicates", device="cuda:0", j=60000, nnz=200)
+    assert (p.n, p.l_prime) == (50000, 8000)
+    print("logged:", _rounds_dense(p, 2, gram_pairs=4000))
+
+
+def test_config4_full_size_csc():
+    _skip_without_gpu()
+    import paper_1312_5766_amd as pk
+    p = si.make("c4_sparse_csc", device="cuda:0")                # 10^5 x 10^6, 100 nonzeros per column, L' = 4000
+    assert (p.n, p.j, p.l_prime) == (100000, 1000000, 4000)
+    g = pk.StradsLasso(values=p.values, row_idx=p.row_idx, col_ptr=p.col_ptr, n=p.n, y=p.y, lam=p.lam, rho=p.rho,
+                       eta=p.eta, l_prime=p.l_prime, seed=p.seed, max_col_nnz=100)
+    k = 100
+    for t in range(3):
+        beta0, dbeta0, r0, _ = g.get_state()
+        g.round()
+        lr = g.last_round()
+        cand, kept_pos = _np(lr["cand"]), _np(lr["kept_pos"])
+        ref_cand = orc.draw(orc.priority_keys(_np(dbeta0), p.eta, p.seed, t), p.l_prime)
+        assert np.array_equal(cand, ref_cand)
+        # gather the candidate columns into a small CSC of their own
+        ci = torch.from_numpy(cand.astype(np.int64)).to(p.values.device)
+        idx = (ci[:, None] * k + torch.arange(k, device=ci.device)[None, :]).flatten()
+        vals, rows = _np(p.values[idx]), _np(p.row_idx[idx])
+        cp = np.arange(len(cand) + 1, dtype=np.int64) * k
+        local = np.arange(len(cand), dtype=np.int32)
+        Gref = orc.gram_csc(vals, rows, cp, local)
+        kept_ref = orc.greedy_filter(Gref, p.rho, 0)
+        if not np.array_equal(kept_pos, kept_ref):
+            near = np.abs(np.abs(Gref.astype(np.float64)) - p.rho) <= 1e-6
+            np.fill_diagonal(near, False)
+            assert near.any()
+        r0h = _np(r0).astype(np.float64)
+        rn = max(float(np.linalg.norm(r0h)), 1.0)
+        kv, kr = vals.reshape(-1, k)[kept_pos].astype(np.float64), rows.reshape(-1, k)[kept_pos]
+        z_ref = (kv * r0h[kr]).sum(axis=1)
+        _close(_np(lr["z"]), z_ref, 1e-4, 1e-6 * rn, "dots")
+        kept = cand[kept_pos]
+        b_old = _np(beta0)[kept].astype(np.float64)
+        a_ = z_ref + b_old
+        b_new = (np.sign(a_) * np.maximum(np.abs(a_) - p.lam, 0)).astype(np.float32).astype(np.float64)
+        d_ref = b_new - b_old
+        r_ref = r0h.copy()
+        np.subtract.at(r_ref, kr.flatten(), (kv * d_ref[:, None]).flatten())
+        beta1, _, r1, _ = g.get_state()
+        _close(_np(beta1)[kept], b_new, 1e-4, 2e-6 * rn, "beta")
+        _close(_np(r1), r_ref, 1e-4, 2e-6 * rn, "residual")
+    g.close()
