@@ -266,18 +266,24 @@ __global__ __launch_bounds__(256) void k_csc_kkt(const float *__restrict__ val, 
                                                  const float *__restrict__ r, const float *__restrict__ beta, float lambda,
                                                  float *__restrict__ g_out, RoundScalars *__restrict__ sc)
 {
-    const int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (j >= J) return;
-    const float g = sparse_dot(val, row_idx, col_ptr[j], col_ptr[j + 1], r, threadIdx.x & 63);
-    if ((threadIdx.x & 63) == 0) {
-        if (g_out) g_out[j] = g;
-        const float b = beta[j];
-        float v;
-        if (b == 0.f) v = fmaxf(fabsf(g) - lambda, 0.f);
-        else v = fabsf(g - copysignf(lambda, b));
-        if (!(v == v)) v = __uint_as_float(0x7F800000u);
-        atomicMax(&sc->kkt_max_bits, __float_as_uint(v));
+    __shared__ float vm[4];
+    float vmax = 0.f;
+    for (int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); j < J; j += (int64_t)gridDim.x * 4) {
+        const float g = sparse_dot(val, row_idx, col_ptr[j], col_ptr[j + 1], r, threadIdx.x & 63);
+        if ((threadIdx.x & 63) == 0) {
+            if (g_out) g_out[j] = g;
+            const float b = beta[j];
+            float v;
+            if (b == 0.f) v = fmaxf(fabsf(g) - lambda, 0.f);
+            else v = fabsf(g - copysignf(lambda, b));
+            if (!(v == v)) v = __uint_as_float(0x7F800000u);
+            vmax = fmaxf(vmax, v);
+        }
     }
+    if ((threadIdx.x & 63) == 0) vm[threadIdx.x >> 6] = vmax;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        atomicMax(&sc->kkt_max_bits, __float_as_uint(fmaxf(fmaxf(vm[0], vm[1]), fmaxf(vm[2], vm[3]))));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -338,7 +344,7 @@ hipError_t launch_kkt_csc(strads_lasso *h, float *g_or_null)
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     hipError_t e = launch_clear_kkt(h);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_csc_kkt, dim3((unsigned)((h->cfg.j + 3) / 4)), dim3(256), 0, h->stream, h->cfg.x,
+    hipLaunchKernelGGL(k_csc_kkt, dim3((unsigned)((h->cfg.j + 3) / 4 < 256 * 16 ? (h->cfg.j + 3) / 4 : 256 * 16)), dim3(256), 0, h->stream, h->cfg.x,
                        h->cfg.row_idx, h->cfg.col_ptr, h->cfg.j, h->at<float>(h->ws.r), h->at<float>(h->ws.beta),
                        h->cfg.lambda, g_or_null, sc);
     return hipGetLastError();

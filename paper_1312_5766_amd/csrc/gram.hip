@@ -211,17 +211,19 @@ __global__ __launch_bounds__(256) void k_mask_from_gram(const float *__restrict_
 int gram_split_auto(int64_t n, int32_t lpad)
 {
     // Workgroups = upper-triangular tiles x K-slices.  Two workgroups are resident per compute
-    // unit (LDS), so the launch runs in rounds of 512; pick the slice count that wastes the least
-    // of the last round, preferring fewer slices (less partial-sum traffic) among equals, and keep
-    // at least 8 LDS stages per slice.
+    // unit (LDS), so the launch runs in rounds of 512.  With few tiles, slice K as far as a slice
+    // still has 2 LDS stages, to get enough workgroups in flight to cover memory latency; with
+    // many tiles, pick the slice count that wastes the least of the last round, preferring fewer
+    // slices (less partial-sum traffic) among near-equals.
     const int64_t T = lpad / kGramTile;
     const int64_t tiles = T * (T + 1) / 2;
-    int64_t max_split = n / (8 * kGramKT);
+    int64_t max_split = n / (2 * kGramKT);
     if (max_split > 64) max_split = 64;
     if (max_split < 1) max_split = 1;
+    if (tiles * max_split <= 512) return (int)max_split;
     int64_t best = 1;
     double best_eff = 0.0;
-    for (int64_t s = 1; s <= max_split; ++s) {
+    for (int64_t s = 1; s <= max_split && (s == 1 || tiles * s <= 4 * 512); ++s) {
         const int64_t wg = tiles * s;
         const int64_t rounds = (wg + 511) / 512;
         const double eff = (double)wg / (double)(rounds * 512);

@@ -239,22 +239,33 @@ __device__ __forceinline__ float kkt_violation(float g, float b, float lambda)
     return v;
 }
 
-// Optimality violation of eq. (1) per column and its maximum (integer atomicMax on the float
-// bits of a non-negative number: order-preserving and deterministic).
+// Optimality violation of eq. (1) per column and its maximum.  Workgroups stride over the
+// columns and keep a running maximum; one integer atomicMax per workgroup at the end (float bits
+// of a non-negative number are order-preserving), so the result is deterministic and the single
+// result word is not hammered once per column.
 template <int TPC, bool VEC4>
 __global__ __launch_bounds__(256) void k_kkt(const float *__restrict__ X, int64_t N, int64_t J,
                                              const float *__restrict__ r, const float *__restrict__ beta, float lambda,
                                              float *__restrict__ g_out, RoundScalars *__restrict__ sc)
 {
     __shared__ float red[4];
+    __shared__ float vm[4];
     constexpr int CPB = 256 / TPC;
-    const int64_t j = (int64_t)blockIdx.x * CPB + threadIdx.x / TPC;
-    if (j >= J) return;                         // TPC = 64: whole wavefront; TPC = 256: whole workgroup
-    const float g = column_dot<TPC, VEC4>(X + j * N, r, N, threadIdx.x % TPC, red);
-    if (threadIdx.x % TPC == 0) {
-        if (g_out) g_out[j] = g;
-        atomicMax(&sc->kkt_max_bits, __float_as_uint(kkt_violation(g, beta[j], lambda)));
+    float vmax = 0.f;
+    for (int64_t j0 = (int64_t)blockIdx.x * CPB; j0 < J; j0 += (int64_t)gridDim.x * CPB) {
+        const int64_t j = j0 + threadIdx.x / TPC;
+        if (TPC == 64 && j >= J) break;         // whole wavefront; TPC = 256 has one column per workgroup
+        const float g = column_dot<TPC, VEC4>(X + j * N, r, N, threadIdx.x % TPC, red);
+        if (threadIdx.x % TPC == 0) {
+            if (g_out) g_out[j] = g;
+            vmax = fmaxf(vmax, kkt_violation(g, beta[j], lambda));
+        }
+        if (TPC > 64) __syncthreads();          // red[] is reused by the next column
     }
+    if ((threadIdx.x & 63) == 0) vm[threadIdx.x >> 6] = vmax;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        atomicMax(&sc->kkt_max_bits, __float_as_uint(fmaxf(fmaxf(vm[0], vm[1]), fmaxf(vm[2], vm[3]))));
 }
 
 // The same pass for 2048 < N <= 1024*NR with 16-byte aligned columns: a persistent workgroup keeps
@@ -306,7 +317,7 @@ __global__ __launch_bounds__(256) void k_kkt_stream(const float *__restrict__ X,
         }
         __syncthreads();
     }
-    if (t < 2) atomicMax(&sc->kkt_max_bits, __float_as_uint(vmax));
+    if (t < 2 && vmax > 0.f) atomicMax(&sc->kkt_max_bits, __float_as_uint(vmax));
 }
 
 __global__ __launch_bounds__(256) void k_init_state(const float *__restrict__ y, int64_t N, int64_t J, float c_init,
@@ -396,7 +407,9 @@ hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null)
 #undef STRADS_KKT_STREAM
         return hipGetLastError();
     }
-    const unsigned grid = wide ? (unsigned)h->cfg.j : (unsigned)((h->cfg.j + 3) / 4);
+    int64_t gk = wide ? h->cfg.j : (h->cfg.j + 3) / 4;
+    if (gk > 256 * 16) gk = 256 * 16;           // persistent: a few workgroups per compute unit
+    const unsigned grid = (unsigned)gk;
 #define STRADS_KKT(TPC, V) hipLaunchKernelGGL((k_kkt<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->cfg.j, h->at<float>(h->ws.r), h->at<float>(h->ws.beta), h->cfg.lambda, g_or_null, sc)
     if (wide) { if (h->vec4) STRADS_KKT(256, true); else STRADS_KKT(256, false); }
     else      { if (h->vec4) STRADS_KKT(64, true);  else STRADS_KKT(64, false); }
