@@ -31,6 +31,7 @@ struct CscEntry { int32_t cand; float val; };
 struct CscScratch {
     uint32_t *cnt;          // [N]   per-row entry count (returns to zero after the fill pass)
     uint32_t *row_start;    // [N+1] exclusive scan of cnt
+    uint32_t *chunk_total;  // [ceil(N/4096)] scan scratch
     CscEntry *entries;      // [L * max_col_nnz]
     long long *racc;        // [N]   fixed-point residual accumulator (returns to zero after apply)
 };
@@ -43,6 +44,7 @@ static CscScratch csc_carve(const strads_lasso *h)
     CscScratch s;
     s.cnt = (uint32_t *)p;               p += up(n * 4);
     s.row_start = (uint32_t *)p;         p += up((n + 1) * 4);
+    s.chunk_total = (uint32_t *)p;       p += up(((n + 4095) / 4096 + 1) * 4);
     s.racc = (long long *)p;             p += up(n * 8);
     s.entries = (CscEntry *)p;
     return s;
@@ -51,7 +53,7 @@ static CscScratch csc_carve(const strads_lasso *h)
 size_t csc_scratch_bytes(int64_t n, int32_t l, int32_t max_col_nnz)
 {
     auto up = [](size_t v) { return (v + 255) / 256 * 256; };
-    return up((size_t)n * 4) + up(((size_t)n + 1) * 4) + up((size_t)n * 8) +
+    return up((size_t)n * 4) + up(((size_t)n + 1) * 4) + up((((size_t)n + 4095) / 4096 + 1) * 4) + up((size_t)n * 8) +
            up((size_t)l * (size_t)(max_col_nnz > 0 ? max_col_nnz : 1) * sizeof(CscEntry));
 }
 
@@ -87,27 +89,54 @@ __global__ __launch_bounds__(64) void k_csc_count(const int32_t *__restrict__ ca
     for (int64_t p = p0 + threadIdx.x; p < p1; p += 64) atomicAdd(&cnt[row_idx[p]], 1u);
 }
 
-// exclusive scan of cnt[0..N) by one workgroup: every thread owns a contiguous chunk
-__global__ __launch_bounds__(1024) void k_csc_scan(const uint32_t *__restrict__ cnt, int64_t N,
-                                                   uint32_t *__restrict__ row_start)
+// exclusive scan of cnt[0..N) in two kernels.  (1) every workgroup scans its own 4096 rows and
+// leaves the chunk total; (2) every workgroup adds the totals of the chunks before it.
+constexpr int kScanChunk = 4096;
+
+__global__ __launch_bounds__(1024) void k_csc_scan_local(const uint32_t *__restrict__ cnt, int64_t N,
+                                                         uint32_t *__restrict__ row_start,
+                                                         uint32_t *__restrict__ chunk_total)
 {
-    __shared__ uint32_t tot[1024];
-    const int t = threadIdx.x;
-    const int64_t chunk = (N + 1023) / 1024;
-    const int64_t b = (int64_t)t * chunk, e = b + chunk < N ? b + chunk : N;
-    uint32_t s = 0;
-    for (int64_t i = b; i < e; ++i) s += cnt[i];
-    tot[t] = s;
+    __shared__ uint32_t wsum[16];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int64_t i0 = (int64_t)blockIdx.x * kScanChunk + (int64_t)t * 4;
+    uint32_t v[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) v[q] = i0 + q < N ? cnt[i0 + q] : 0u;
+    const uint32_t mine = v[0] + v[1] + v[2] + v[3];
+    uint32_t inc = mine;                                   // inclusive scan across the wavefront
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) { const uint32_t u = __shfl_up(inc, d); if (lane >= d) inc += u; }
+    if (lane == 63) wsum[wave] = inc;
     __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {           // inclusive prefix over the 1024 chunk totals
-        const uint32_t v = t >= off ? tot[t - off] : 0u;
-        __syncthreads();
-        tot[t] += v;
-        __syncthreads();
-    }
-    uint32_t run = tot[t] - s;
-    for (int64_t i = b; i < e; ++i) { row_start[i] = run; run += cnt[i]; }
-    if (t == 1023) row_start[N] = tot[1023];
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) { const uint32_t u = wsum[w]; if (w < wave) before += u; total += u; }
+    uint32_t run = before + inc - mine;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { if (i0 + q < N) row_start[i0 + q] = run; run += v[q]; }
+    if (t == 0) chunk_total[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(1024) void k_csc_scan_add(int64_t N, int32_t n_chunks, uint32_t *__restrict__ row_start,
+                                                       const uint32_t *__restrict__ chunk_total)
+{
+    __shared__ uint32_t part[16];
+    __shared__ uint32_t base_s;
+    const int t = threadIdx.x;
+    uint32_t s = 0;
+    for (int c = t; c < (int)blockIdx.x; c += 1024) s += chunk_total[c];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off);
+    if ((t & 63) == 0) part[t >> 6] = s;
+    __syncthreads();
+    if (t == 0) { uint32_t b = 0; for (int w = 0; w < 16; ++w) b += part[w]; base_s = b; }
+    __syncthreads();
+    const uint32_t base = base_s;
+    const int64_t i0 = (int64_t)blockIdx.x * kScanChunk + (int64_t)t * 4;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) if (i0 + q < N) row_start[i0 + q] += base;
+    if ((int)blockIdx.x == n_chunks - 1 && t == 0) row_start[N] = base + chunk_total[blockIdx.x];
 }
 
 // place (candidate, value) into its row's bucket; the count doubles as a countdown cursor, so it is
@@ -309,7 +338,11 @@ hipError_t launch_gram_csc(strads_lasso *h)
     const int32_t *cand = h->at<int32_t>(h->ws.cand);
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     hipLaunchKernelGGL(k_csc_count, dim3(h->L), dim3(64), 0, h->stream, cand, h->cfg.col_ptr, h->cfg.row_idx, s.cnt);
-    hipLaunchKernelGGL(k_csc_scan, dim3(1), dim3(1024), 0, h->stream, s.cnt, h->cfg.n, s.row_start);
+    const int32_t n_chunks = (int32_t)((h->cfg.n + kScanChunk - 1) / kScanChunk);
+    hipLaunchKernelGGL(k_csc_scan_local, dim3(n_chunks), dim3(1024), 0, h->stream, s.cnt, h->cfg.n, s.row_start,
+                       s.chunk_total);
+    hipLaunchKernelGGL(k_csc_scan_add, dim3(n_chunks), dim3(1024), 0, h->stream, h->cfg.n, n_chunks, s.row_start,
+                       s.chunk_total);
     hipLaunchKernelGGL(k_csc_fill, dim3(h->L), dim3(64), 0, h->stream, cand, h->cfg.col_ptr, h->cfg.row_idx, h->cfg.x,
                        s.row_start, s.cnt, s.entries);
     hipLaunchKernelGGL(k_csc_gram, dim3(h->L), dim3(256), (size_t)h->Lpad * 8, h->stream, cand, h->cfg.col_ptr,

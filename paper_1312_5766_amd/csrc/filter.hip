@@ -27,11 +27,12 @@ __device__ __forceinline__ uint64_t readlane64(uint64_t v, int l)
 
 constexpr int kMaxWords = STRADS_MAX_L_PRIME / 64;   // mask words per row (128)
 constexpr int kFilterThreads = 1024;
-constexpr int kRowWordsPerThread = 64 * kMaxWords / kFilterThreads;   // 8
 
+// IPT = words of a chunk's 64 rows handled per thread = ceil(64 * W / 1024): 1, 2, 4 or 8.
+template <int kRowWordsPerThread>
 __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__restrict__ mask, int32_t L, int32_t W,
                                                            int32_t p_max, const int32_t *__restrict__ cand,
-                                                           int32_t *__restrict__ kept_pos, int32_t *__restrict__ kept,
+                                                           int32_t *kept_pos, int32_t *__restrict__ kept,
                                                            RoundScalars *__restrict__ sc, int count_updates)
 {
     extern __shared__ uint64_t rows[];            // [2][64][W]  (row-major, all W words kept for simplicity)
@@ -46,15 +47,23 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
     for (int i = tid; i < W; i += kFilterThreads) dead[i] = 0;
     if (tid == 0) nk_s = 0;
 
+    // this thread's share of a chunk's 64 x W words: the (row, word) of item tid + q*1024 does not
+    // depend on the chunk, so the divisions are done once
+    int16_t irow[kRowWordsPerThread], iword[kRowWordsPerThread];
+#pragma unroll
+    for (int q = 0; q < kRowWordsPerThread; ++q) {
+        const int32_t it = tid + q * kFilterThreads;
+        const int32_t rw = it / W;
+        irow[q] = (int16_t)rw;
+        iword[q] = it < items ? (int16_t)(it - rw * W) : (int16_t)-1;     // -1: no such item
+    }
     // stage chunk 0
     uint64_t pre[kRowWordsPerThread];
     auto fetch = [&](int32_t c) {
 #pragma unroll
         for (int q = 0; q < kRowWordsPerThread; ++q) {
-            const int32_t it = tid + q * kFilterThreads;
-            const int32_t rw = it / W, w = it - rw * W;
-            const int32_t a = c * 64 + rw;
-            pre[q] = (it < items && a < L && w >= c) ? mask[(int64_t)a * W + w] : 0ull;
+            const int32_t a = c * 64 + irow[q], w = iword[q];
+            pre[q] = (w >= c && a < L) ? mask[(int64_t)a * W + w] : 0ull;
         }
     };
     auto stash = [&](int buf) {
@@ -110,7 +119,6 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
             if ((keptw >> lane) & 1ull) {
                 const int32_t idx = nk0 + __popcll(keptw & ((1ull << lane) - 1ull));
                 kept_pos[idx] = c * 64 + lane;
-                kept[idx] = cand[c * 64 + lane];
             }
             if (lane == 0) { keptw_s = keptw; nk_s = nk; }
         }
@@ -119,10 +127,11 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
         const bool full = nk_s >= cap;
         // OR the kept rows into dead[w], w > c
         if (!full && keptw != 0) {
-            for (int32_t it = tid; it < items; it += kFilterThreads) {
-                const int32_t rw = it / W, w = it - rw * W;
-                if (w > c && ((keptw >> rw) & 1ull)) {
-                    const uint64_t v = rb[it];
+#pragma unroll
+            for (int q = 0; q < kRowWordsPerThread; ++q) {
+                const int32_t w = iword[q];
+                if (w > c && ((keptw >> irow[q]) & 1ull)) {
+                    const uint64_t v = rb[tid + q * kFilterThreads];
                     if (v) atomicOr((unsigned long long *)&dead[w], (unsigned long long)v);
                 }
             }
@@ -131,9 +140,13 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
         __syncthreads();
         if (full) break;
     }
+    // kept column ids, gathered once at the end (a global load inside the loop above would put
+    // a memory round trip on the serial chain of every chunk)
+    const int32_t nk = nk_s;
+    for (int32_t i = tid; i < nk; i += kFilterThreads) kept[i] = cand[kept_pos[i]];
     if (tid == 0) {
-        sc->n_kept = nk_s;
-        if (count_updates) sc->updates_total += (unsigned long long)nk_s;
+        sc->n_kept = nk;
+        if (count_updates) sc->updates_total += (unsigned long long)nk;
     }
 }
 
@@ -141,16 +154,23 @@ hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates)
 {
     const int32_t W = h->Lpad / 64;
     const size_t lds = (size_t)2 * 64 * W * sizeof(uint64_t);
-    hipLaunchKernelGGL(k_filter, dim3(1), dim3(kFilterThreads), lds, h->stream, h->at<uint64_t>(h->ws.mask), l, W,
-                       h->cfg.p_max, h->at<int32_t>(h->ws.cand), h->at<int32_t>(h->ws.kept_pos),
-                       h->at<int32_t>(h->ws.kept), h->at<RoundScalars>(h->ws.scalars), count_updates ? 1 : 0);
+#define STRADS_FILTER(IPT) hipLaunchKernelGGL(k_filter<IPT>, dim3(1), dim3(kFilterThreads), lds, h->stream, h->at<uint64_t>(h->ws.mask), l, W, h->cfg.p_max, h->at<int32_t>(h->ws.cand), h->at<int32_t>(h->ws.kept_pos), h->at<int32_t>(h->ws.kept), h->at<RoundScalars>(h->ws.scalars), count_updates ? 1 : 0)
+    if (W <= 16) STRADS_FILTER(1);
+    else if (W <= 32) STRADS_FILTER(2);
+    else if (W <= 64) STRADS_FILTER(4);
+    else STRADS_FILTER(8);
+#undef STRADS_FILTER
     return hipGetLastError();
 }
 
 hipError_t filter_prepare()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_filter), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               2 * 64 * kMaxWords * (int)sizeof(uint64_t));
+    const int lds = 2 * 64 * kMaxWords * (int)sizeof(uint64_t);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_filter<1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_filter<2>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_filter<4>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_filter<8>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    return e;
 }
 
 } // namespace strads

@@ -360,18 +360,52 @@ __global__ __launch_bounds__(1024) void k_finalize(RoundScalars *__restrict__ sc
     if (L <= kRegSortMax) {
         const uint64_t v = bitonic_sort_desc_1024(tid < L ? sel[tid] : 0ull, lds);
         if (tid < Lpad) cand[tid] = tid < L ? (int32_t)(0xFFFFFFFFu - (uint32_t)v) : 0;
-    } else {
-        uint32_t p2 = 1; while (p2 < L) p2 <<= 1;
-        for (uint32_t i = tid; i < p2; i += 1024u) lds[i] = i < L ? sel[i] : 0ull;
-        __syncthreads();
-        bitonic_sort_desc(lds, p2);
-        for (uint32_t i = tid; i < Lpad; i += 1024u)
-            cand[i] = i < L ? (int32_t)(0xFFFFFFFFu - (uint32_t)lds[i]) : 0;
     }
+    // longer lists are put in order by k_sort_chunks + k_merge_rank, spread over many workgroups
 
     // D. leave the histograms and per-round scalars clean for the next round
     for (uint32_t i = tid; i < 2u * kHistBins; i += 1024u) hist[i] = 0;
     if (tid == 0) { sc->n_sel = 0; sc->n_bnd = 0; sc->near_rho_pairs = 0; }
+}
+
+// Draw order for lists longer than 1024 items, in two kernels.  (1) every workgroup sorts one
+// chunk of 1024 items (descending) in registers.  (2) the items are distinct, so the final
+// position of an item is the number of items greater than it: its position inside its own sorted
+// chunk plus, for every other chunk, the count found by binary search.  All chunks sit in LDS.
+__global__ __launch_bounds__(1024) void k_sort_chunks(const uint64_t *__restrict__ sel, uint32_t L,
+                                                      uint64_t *__restrict__ sorted)
+{
+    __shared__ uint64_t xch[1024];
+    const uint32_t i = blockIdx.x * 1024u + threadIdx.x;
+    sorted[i] = bitonic_sort_desc_1024(i < L ? sel[i] : 0ull, xch);     // zeros (padding) sort last
+}
+
+__global__ __launch_bounds__(256) void k_merge_rank(const uint64_t *__restrict__ sorted, uint32_t L, uint32_t Lpad,
+                                                    uint32_t n_chunks, int32_t *__restrict__ cand)
+{
+    extern __shared__ uint64_t all[];             // [n_chunks * 1024]
+    const uint32_t n = n_chunks * 1024u;
+    for (uint32_t i = threadIdx.x; i < n; i += 256u) all[i] = sorted[i];
+    __syncthreads();
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t x = all[i];
+    if (x != 0ull) {
+        uint32_t rank = i & 1023u;
+        const uint32_t own = i >> 10;
+        for (uint32_t c = 0; c < n_chunks; ++c) {
+            if (c == own) continue;
+            const uint64_t *a = all + c * 1024u;  // descending: count of elements > x = first index with a[idx] < x
+            uint32_t lo = 0, hi = 1024;
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (a[mid] > x) lo = mid + 1; else hi = mid;
+            }
+            rank += lo;
+        }
+        cand[rank] = (int32_t)(0xFFFFFFFFu - (uint32_t)x);
+    }
+    if (i >= L && i < Lpad) cand[i] = 0;          // padding slots of the candidate list
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -379,7 +413,7 @@ static inline int sampler_grid(int64_t J)
 {
     int64_t b = (J + 256 * 4 - 1) / (256 * 4);
     if (b < 1) b = 1;
-    if (b > 1024) b = 1024;
+    if (b > 256) b = 256;        // every workgroup flushes its LDS histogram with global atomics: keep them few
     return (int)b;
 }
 
@@ -400,6 +434,13 @@ hipError_t launch_sampler(strads_lasso *h, int64_t round)
     const size_t lds = (size_t)(cap > 2u * STRADS_MAX_L_PRIME ? cap : 2u * STRADS_MAX_L_PRIME) * sizeof(uint64_t);
     hipLaunchKernelGGL(k_finalize, dim3(1), dim3(1024), lds, h->stream, sc, sel, bnd, L, (uint32_t)h->Lpad, cap,
                        h->at<int32_t>(h->ws.cand), hist);
+    if (L > kRegSortMax) {
+        const uint32_t n_chunks = (L + 1023u) / 1024u;
+        uint64_t *sorted = sel + STRADS_MAX_L_PRIME;          // second half of the selection buffer
+        hipLaunchKernelGGL(k_sort_chunks, dim3(n_chunks), dim3(1024), 0, h->stream, sel, L, sorted);
+        hipLaunchKernelGGL(k_merge_rank, dim3(n_chunks * 4u), dim3(256), (size_t)n_chunks * 1024u * 8u, h->stream,
+                           sorted, L, (uint32_t)h->Lpad, n_chunks, h->at<int32_t>(h->ws.cand));
+    }
     return hipGetLastError();
 }
 
@@ -412,6 +453,9 @@ hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys)
 
 hipError_t sampler_prepare()
 {
+    hipError_t e0 = hipFuncSetAttribute(reinterpret_cast<const void *>(k_merge_rank),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, STRADS_MAX_L_PRIME * 8);
+    if (e0 != hipSuccess) return e0;
     // the final kernel sorts up to 16384 64-bit items in LDS (128 KiB): raise its dynamic-LDS limit
     return hipFuncSetAttribute(reinterpret_cast<const void *>(k_finalize),
                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STRADS_MAX_L_PRIME * 8);
