@@ -27,6 +27,12 @@ if ROOT not in sys.path:
 MFMA_FP32_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBPS = 8000.0
 
+# HBM bytes per launch of the Gram tile kernel (read + written), measured offline with two
+# rocprofv3 --pmc runs (FETCH_SIZE x2.00, WRITE_SIZE x1.00 after calibration against a copy kernel of
+# known size); the summary is profiles/hbm_traffic_c2_dense_block_corr.txt.  Workloads that were
+# not measured report null.
+MEASURED_GRAM_TRAFFIC_BYTES = {"c2_dense_block_corr": 168.9e6 + 33.0e6}
+
 WORKLOADS = {
     # name -> (config key of synth.lasso_inputs, overrides)
     "c2_dense_block_corr": ("c2_dense_block_corr", {}),
@@ -124,7 +130,7 @@ def main() -> int:
         ach = gram_flops / (stage["gram_tiles"] * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "k_gram_tiles", "achieved": round(ach, 3),
                     "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_FP32_PEAK_TFLOPS, 4),
-                    "traffic": None, "avg_ms": round(stage["gram_tiles"], 5), "launches": stage["rounds"],
+                    "traffic": MEASURED_GRAM_TRAFFIC_BYTES.get(args.workload), "avg_ms": round(stage["gram_tiles"], 5), "launches": stage["rounds"],
                     "flops_per_launch": gram_flops}
 
     cpu = None
