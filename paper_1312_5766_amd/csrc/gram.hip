@@ -4,13 +4,23 @@
 //
 // This is a dense contraction (L' x N times N x L'), so it runs on the matrix cores:
 // v_mfma_f32_32x32x2_f32, fp32 in, fp32 accumulate.  A workgroup of 4 wavefronts owns one
-// 128 x 128 output tile of the upper triangle and one slice of the row (K) range; each
-// wavefront holds a 64 x 64 sub-tile as 2 x 2 MFMA accumulators.  Columns of X are contiguous
-// along K, so both operand panels are staged K-contiguous in LDS with coalesced 16-byte loads,
-// double-buffered, and read back 16 bytes per lane: lane (i, h) of a wavefront reads
+// 128 x 128 output tile of the upper triangle and one slice of the row (K) range.  Columns of X
+// are contiguous along K, so operand panels are staged K-contiguous in LDS with coalesced 16-byte
+// loads, double-buffered, and read back 16 bytes per lane: lane (i, h) of a wavefront reads
 // k = 8*s + 4*h .. +3 of column i and feeds component c to the c-th of four MFMAs.  The MFMA
 // sums over its two k-slots, and the assignment of k values to slots is the same for both
 // operands, so any such assignment yields the same dot products.
+//
+//   * Off-diagonal tiles: each wavefront holds a 64 x 64 sub-tile as 2 x 2 MFMA accumulators.
+//   * Diagonal tiles (both operands are the same 128 columns): only one panel is staged and only
+//     the 10 of 16 32x32 blocks on or above the diagonal are computed -- wavefronts 0 and 3 take
+//     the two 64 x 64 diagonal sub-tiles (3 blocks each), wavefronts 1 and 2 one row of two
+//     blocks each of the off-diagonal sub-tile -- and blocks above the diagonal are also stored
+//     mirrored, so the tile is complete in memory.  A diagonal tile costs 3/4 of an off-diagonal
+//     one per K step, so it gets proportionally longer K slices (fewer of them).
+//
+// Accumulators live in the accumulation registers (AGPRs): loads returning into the ordinary
+// vector registers then do not compete with the matrix pipe for register-file ports.
 //
 // K-slices are written as fp32 partial tiles and summed in fixed order by the mask kernel, so
 // results do not depend on scheduling.
@@ -23,9 +33,24 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kPad = 4;                         // LDS row padding, floats
 constexpr int kRow = kGramKT + kPad;            // LDS row stride, floats
 constexpr int kPanel = kGramTile * kRow;        // floats per operand panel per stage
+constexpr int kGramSlots = 512;                 // resident workgroups: 2 per compute unit (LDS)
 
-// 4 consecutive K values of one column, zero beyond kend.  No branch: the address is clamped into
-// the column and the value is selected, so the main loop stays one straight-line block.
+// D += A * B on the matrix core with the accumulator pinned to the AGPR file.
+__device__ __forceinline__ void mfma32(floatx16 &acc, float a, float b)
+{
+    asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+// The compiler does not see inside the MFMA statements above, so it cannot count the cycles the
+// last of them needs before its result may be read: wait them out (a 32x32x2 MFMA takes 16
+// passes of 4 cycles).
+__device__ __forceinline__ void mfma_drain()
+{
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+}
+
+// 4 consecutive K values of one column, zero beyond kend.  The address is clamped into the
+// column and the value is selected.
 template <bool VEC4>
 __device__ __forceinline__ float4 load_k4(const float *__restrict__ col, int64_t k, int64_t kend)
 {
@@ -44,26 +69,47 @@ __device__ __forceinline__ float4 load_k4(const float *__restrict__ col, int64_t
     }
 }
 
-// grid.x = T(T+1)/2 * split (T = Lpad/128): upper-triangular tiles only, K-slice fastest.
-// Software pipeline per LDS stage st (32 K values): registers hold stage st+1 (fetched one stage
-// ago), they are written to the other LDS buffer, the fetch of stage st+2 is issued, then stage st
-// is multiplied out of LDS; one barrier per stage.
-template <bool VEC4>
-__global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__ X, int64_t N,
-                                                       const int32_t *__restrict__ cand, int32_t L, int32_t Lpad,
-                                                       int32_t T, int32_t split, int64_t kchunk,
-                                                       float *__restrict__ P)
-{
-    const int32_t s = blockIdx.x % split;
-    int32_t u = blockIdx.x / split;             // index into the row-major upper triangle
-    int32_t ta = 0;
-    while (u >= T - ta) { u -= T - ta; ++ta; }
-    const int32_t tb = ta + u;
+struct GramShape {
+    int32_t L, Lpad, T;
+    int32_t split_off, split_diag;      // K-slices of an off-diagonal / a diagonal tile
+    int64_t kchunk_off, kchunk_diag;    // rows per slice (multiples of kGramKT)
+};
 
-    extern __shared__ float smem[];             // [2 stages][A panel | B panel]
+// store one 32x32 accumulator block: register v of lane (li, lh) holds row 8*(v/4) + 4*lh + (v%4),
+// column li of the block
+__device__ __forceinline__ void store_block(float *__restrict__ out, int32_t Lpad, int row0, int col0,
+                                            const floatx16 &acc, int li, int lh)
+{
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int row = row0 + 8 * (v >> 2) + 4 * lh + (v & 3);
+        out[(int64_t)row * Lpad + col0 + li] = acc[v];
+    }
+}
+
+// the same block written transposed: 4 consecutive registers are 4 consecutive columns of the
+// transposed block, i.e. one 16-byte store
+__device__ __forceinline__ void store_block_t(float *__restrict__ out, int32_t Lpad, int row0, int col0,
+                                              const floatx16 &acc, int li, int lh)
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const float4 v4 = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+        *reinterpret_cast<float4 *>(out + (int64_t)(col0 + li) * Lpad + row0 + 8 * q + 4 * lh) = v4;
+    }
+}
+
+// Off-diagonal tile (ta < tb).  Software pipeline per LDS stage st (32 K values): registers hold
+// stage st+1 (fetched one stage ago), they are written to the other LDS buffer, the fetch of stage
+// st+2 is issued, then stage st is multiplied out of LDS; one barrier per stage.
+template <bool VEC4>
+__device__ __forceinline__ void gram_tile_off(const float *__restrict__ X, int64_t N,
+                                              const int32_t *__restrict__ cand, const GramShape &g, int32_t ta,
+                                              int32_t tb, int32_t s, float *__restrict__ P, float *smem)
+{
     const int tid = threadIdx.x;
-    const int64_t kbeg = (int64_t)s * kchunk;
-    const int64_t kend = (kbeg + kchunk < N) ? kbeg + kchunk : N;
+    const int64_t kbeg = (int64_t)s * g.kchunk_off;
+    const int64_t kend = (kbeg + g.kchunk_off < N) ? kbeg + g.kchunk_off : N;
     const int nstage = (int)((kend - kbeg + kGramKT - 1) / kGramKT);
 
     // this thread stages 4 A-columns and 4 B-columns: column (it*32 + tid/8), floats (tid%8)*4..+3.
@@ -74,8 +120,8 @@ __global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
         int ia = ta * kGramTile + it * 32 + crow, ib = tb * kGramTile + it * 32 + crow;
-        ia = ia < L ? ia : L - 1;
-        ib = ib < L ? ib : L - 1;
+        ia = ia < g.L ? ia : g.L - 1;
+        ib = ib < g.L ? ib : g.L - 1;
         col[it] = X + (int64_t)cand[ia] * N;
         col[4 + it] = X + (int64_t)cand[ib] * N;
     }
@@ -122,10 +168,10 @@ __global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__
             const float bv0[4] = {b0.x, b0.y, b0.z, b0.w}, bv1[4] = {b1.x, b1.y, b1.z, b1.w};
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0[c], bv0[c], acc[0][0], 0, 0, 0);
-                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0[c], bv1[c], acc[0][1], 0, 0, 0);
-                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av1[c], bv0[c], acc[1][0], 0, 0, 0);
-                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av1[c], bv1[c], acc[1][1], 0, 0, 0);
+                mfma32(acc[0][0], av0[c], bv0[c]);
+                mfma32(acc[0][1], av0[c], bv1[c]);
+                mfma32(acc[1][0], av1[c], bv0[c]);
+                mfma32(acc[1][1], av1[c], bv1[c]);
             }
         }
     };
@@ -135,7 +181,7 @@ __global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__
     if (nstage > 1) fetch(1);
     __syncthreads();
     int st = 0;
-    for (; st + 2 < nstage; ++st) {             // steady state: no conditionals inside
+    for (; st + 2 < nstage; ++st) {             // steady state
         stash((st + 1) & 1);
         fetch(st + 2);
         compute(st & 1);
@@ -148,34 +194,167 @@ __global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__
         ++st;
     }
     compute(st & 1);
+    mfma_drain();
 
-    // accumulator layout of the 32x32 MFMA: register v of lane (li, lh) holds
-    // row 8*(v/4) + 4*lh + (v%4), column li of the 32x32 block.
-    float *out = P + (int64_t)s * Lpad * Lpad;
+    float *out = P + (int64_t)s * g.Lpad * g.Lpad;
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int colo = tb * kGramTile + wc * 64 + b * 32 + li;
+        for (int b = 0; b < 2; ++b)
+            store_block(out, g.Lpad, ta * kGramTile + wr * 64 + a * 32, tb * kGramTile + wc * 64 + b * 32,
+                        acc[a][b], li, lh);
+}
+
+// Diagonal tile: one panel of 128 columns; 32-column groups p < q (< r) of this wavefront:
+//   wavefront 0: (0,0) (0,1) (1,1)      wavefront 3: (2,2) (2,3) (3,3)
+//   wavefront 1: (0,2) (0,3)            wavefront 2: (1,2) (1,3)
+template <bool VEC4>
+__device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int64_t N,
+                                               const int32_t *__restrict__ cand, const GramShape &g, int32_t ta,
+                                               int32_t s, float *__restrict__ P, float *smem)
+{
+    const int tid = threadIdx.x;
+    const int64_t kbeg = (int64_t)s * g.kchunk_diag;
+    const int64_t kend = (kbeg + g.kchunk_diag < N) ? kbeg + g.kchunk_diag : N;
+    const int nstage = (int)((kend - kbeg + kGramKT - 1) / kGramKT);
+
+    const int crow = tid >> 3, kq = (tid & 7) * 4;
+    const float *col[4];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = ta * kGramTile + wr * 64 + a * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                out[(int64_t)row * Lpad + colo] = acc[a][b][v];
+    for (int it = 0; it < 4; ++it) {
+        int ia = ta * kGramTile + it * 32 + crow;
+        ia = ia < g.L ? ia : g.L - 1;
+        col[it] = X + (int64_t)cand[ia] * N;
+    }
+    float4 R[4];
+    auto fetch = [&](int st) {
+        const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) R[i] = load_k4<VEC4>(col[i], k, kend);
+    };
+    auto stash = [&](int buf) {
+        float *pa = smem + buf * 2 * kPanel;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) *reinterpret_cast<float4 *>(pa + (it * 32 + crow) * kRow + kq) = R[it];
+    };
+
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int li = lane & 31, lh = lane >> 5;
+    const bool sym = wave == 0 || wave == 3;            // uniform per wavefront
+    const int gp = wave == 0 ? 0 : wave == 3 ? 2 : wave - 1;    // 0, 0, 1, 2
+    const int gq = wave == 0 ? 1 : wave == 3 ? 3 : 2;           // 1, 2, 2, 3
+    const int gr = 3;                                           // rect wavefronts only
+
+    floatx16 acc[3];
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[a][v] = 0.f;
+
+    const int offp = (gp * 32 + li) * kRow + lh * 4;
+    const int offq = (gq * 32 + li) * kRow + lh * 4;
+    const int offr = (gr * 32 + li) * kRow + lh * 4;
+    auto compute = [&](int buf) {
+        const float *base = smem + buf * 2 * kPanel;
+        if (sym) {
+#pragma unroll
+            for (int ks = 0; ks < kGramKT / 8; ++ks) {
+                const float4 p4 = *reinterpret_cast<const float4 *>(base + offp + ks * 8);
+                const float4 q4 = *reinterpret_cast<const float4 *>(base + offq + ks * 8);
+                const float pv[4] = {p4.x, p4.y, p4.z, p4.w}, qv[4] = {q4.x, q4.y, q4.z, q4.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    mfma32(acc[0], pv[c], pv[c]);
+                    mfma32(acc[1], pv[c], qv[c]);
+                    mfma32(acc[2], qv[c], qv[c]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < kGramKT / 8; ++ks) {
+                const float4 p4 = *reinterpret_cast<const float4 *>(base + offp + ks * 8);
+                const float4 q4 = *reinterpret_cast<const float4 *>(base + offq + ks * 8);
+                const float4 r4 = *reinterpret_cast<const float4 *>(base + offr + ks * 8);
+                const float pv[4] = {p4.x, p4.y, p4.z, p4.w}, qv[4] = {q4.x, q4.y, q4.z, q4.w};
+                const float rv[4] = {r4.x, r4.y, r4.z, r4.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    mfma32(acc[0], pv[c], qv[c]);
+                    mfma32(acc[1], pv[c], rv[c]);
+                }
             }
         }
+    };
+
+    fetch(0);
+    stash(0);
+    if (nstage > 1) fetch(1);
+    __syncthreads();
+    int st = 0;
+    for (; st + 2 < nstage; ++st) {
+        stash((st + 1) & 1);
+        fetch(st + 2);
+        compute(st & 1);
+        __syncthreads();
+    }
+    if (st + 1 < nstage) {
+        stash((st + 1) & 1);
+        compute(st & 1);
+        __syncthreads();
+        ++st;
+    }
+    compute(st & 1);
+    mfma_drain();
+
+    float *out = P + (int64_t)s * g.Lpad * g.Lpad;
+    const int t0 = ta * kGramTile;
+    if (sym) {
+        store_block(out, g.Lpad, t0 + gp * 32, t0 + gp * 32, acc[0], li, lh);
+        store_block(out, g.Lpad, t0 + gp * 32, t0 + gq * 32, acc[1], li, lh);
+        store_block_t(out, g.Lpad, t0 + gp * 32, t0 + gq * 32, acc[1], li, lh);
+        store_block(out, g.Lpad, t0 + gq * 32, t0 + gq * 32, acc[2], li, lh);
+    } else {
+        store_block(out, g.Lpad, t0 + gp * 32, t0 + gq * 32, acc[0], li, lh);
+        store_block_t(out, g.Lpad, t0 + gp * 32, t0 + gq * 32, acc[0], li, lh);
+        store_block(out, g.Lpad, t0 + gp * 32, t0 + gr * 32, acc[1], li, lh);
+        store_block_t(out, g.Lpad, t0 + gp * 32, t0 + gr * 32, acc[1], li, lh);
+    }
+}
+
+// grid.x = T(T-1)/2 * split_off + T * split_diag: off-diagonal tiles of the upper triangle first
+// (K-slice fastest), then the diagonal tiles.
+template <bool VEC4>
+__global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__ X, int64_t N,
+                                                       const int32_t *__restrict__ cand, GramShape g,
+                                                       float *__restrict__ P)
+{
+    extern __shared__ float smem[];             // [2 stages][A panel | B panel]
+    const int32_t n_off = g.T * (g.T - 1) / 2 * g.split_off;
+    if ((int32_t)blockIdx.x < n_off) {
+        const int32_t s = blockIdx.x % g.split_off;
+        int32_t u = blockIdx.x / g.split_off;   // index into the row-major strict upper triangle
+        int32_t ta = 0;
+        while (u >= g.T - 1 - ta) { u -= g.T - 1 - ta; ++ta; }
+        gram_tile_off<VEC4>(X, N, cand, g, ta, ta + 1 + u, s, P, smem);
+    } else {
+        const int32_t d = blockIdx.x - n_off;
+        gram_tile_diag<VEC4>(X, N, cand, g, d / g.split_diag, d % g.split_diag, P, smem);
+    }
 }
 
 // Sum the K-slices in slice order and emit the conflict bits (and, optionally, the fp32 Gram).
 // One thread per (row a, column b) with b in the tiles at or right of a's diagonal tile; 64
 // consecutive b per wavefront make one 64-bit mask word.
-__global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, int32_t split, int32_t L,
-                                                   int32_t Lpad, float rho, uint64_t *__restrict__ mask,
-                                                   float *__restrict__ gram, int32_t *__restrict__ near_pairs)
+__global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, int32_t split_off,
+                                                   int32_t split_diag, int32_t L, int32_t Lpad, float rho,
+                                                   uint64_t *__restrict__ mask, float *__restrict__ gram,
+                                                   int32_t *__restrict__ near_pairs)
 {
     const int32_t a = blockIdx.y;
     const int32_t b = blockIdx.x * 256 + threadIdx.x;
     const int32_t first = (a / kGramTile) * kGramTile;      // first column of a's diagonal tile
     if (b < first || b >= Lpad) return;                     // uniform per wavefront (both are multiples of 64)
+    const int32_t split = b < first + kGramTile ? split_diag : split_off;
     float g = 0.f;
     const int64_t plane = (int64_t)Lpad * Lpad;
     for (int32_t s = 0; s < split; ++s) g += P[s * plane + (int64_t)a * Lpad + b];
@@ -208,54 +387,86 @@ __global__ __launch_bounds__(256) void k_mask_from_gram(const float *__restrict_
     if ((threadIdx.x & 63) == 0) mask[(int64_t)a * (Lpad / 64) + (b >> 6)] = w;
 }
 
+// K-slices of a diagonal tile for a given off-diagonal slice count: the fewest slices whose
+// cost (3/4 of an off-diagonal tile per K stage) exceeds an off-diagonal workgroup's by at most
+// one stage.
+static int diag_split_for(int64_t stages, int split_off)
+{
+    const int64_t off_len = (stages + split_off - 1) / split_off;
+    int sd = 1;
+    while (sd < split_off && 3 * ((stages + sd - 1) / sd) > 4 * (off_len + 1)) ++sd;
+    return sd;
+}
+
 int gram_split_auto(int64_t n, int32_t lpad)
 {
-    // Workgroups = upper-triangular tiles x K-slices.  Two workgroups are resident per compute
-    // unit (LDS), so the launch runs in rounds of 512.  With few tiles, slice K as far as a slice
-    // still has 2 LDS stages, to get enough workgroups in flight to cover memory latency; with
-    // many tiles, pick the slice count that wastes the least of the last round, preferring fewer
-    // slices (less partial-sum traffic) among near-equals.
+    // Workgroups = off-diagonal tiles x K-slices + diagonal tiles x their (fewer) K-slices.  Two
+    // workgroups are resident per compute unit (LDS), so the launch runs in rounds of 512.  The
+    // cost of a choice, in K stages of an off-diagonal workgroup: rounds x (stages per slice + a
+    // fixed prologue/epilogue allowance) + the partial-sum traffic it causes.  With one tile or
+    // very short K there is nothing to choose.
     const int64_t T = lpad / kGramTile;
-    const int64_t tiles = T * (T + 1) / 2;
-    int64_t max_split = n / (2 * kGramKT);
+    const int64_t stages = (n + kGramKT - 1) / kGramKT;
+    const int64_t n_off = T * (T - 1) / 2;
+    int64_t max_split = stages / 2;
     if (max_split > 64) max_split = 64;
     if (max_split < 1) max_split = 1;
-    if (tiles * max_split <= 512) return (int)max_split;
-    int64_t best = 1;
-    double best_eff = 0.0;
-    for (int64_t s = 1; s <= max_split && (s == 1 || tiles * s <= 4 * 512); ++s) {
-        const int64_t wg = tiles * s;
-        const int64_t rounds = (wg + 511) / 512;
-        const double eff = (double)wg / (double)(rounds * 512);
-        if (eff > best_eff + 0.02) { best_eff = eff; best = s; }
+    int best = 1;
+    double best_cost = 1e300;
+    for (int s = 1; s <= max_split; ++s) {
+        const int sd = diag_split_for(stages, s);
+        const int64_t wg = n_off * s + T * sd;
+        const int64_t rounds = (wg + kGramSlots - 1) / kGramSlots;
+        const int64_t len = (stages + s - 1) / s;
+        // 3 stages' worth per workgroup for first fetch and tile store; the partial tiles of 512
+        // workgroups (32 MiB written, then read by the mask kernel) cost about 2 stage-times
+        const double cost = (double)rounds * (double)(len + 3) + 2.0 * (double)wg / (double)kGramSlots;
+        if (cost < best_cost * 0.995) { best_cost = cost; best = s; }
     }
-    return (int)best;
+    return best;
+}
+
+static GramShape gram_shape(const strads_lasso *h)
+{
+    GramShape g;
+    g.L = h->L;
+    g.Lpad = h->Lpad;
+    g.T = h->Lpad / kGramTile;
+    const int64_t stages = (h->cfg.n + kGramKT - 1) / kGramKT;
+    int32_t so = h->split_user > 0 ? h->split_user : gram_split_auto(h->cfg.n, h->Lpad);
+    if (so > h->split_max) so = h->split_max;
+    if (so > stages) so = (int32_t)stages;
+    int64_t len = (stages + so - 1) / so;
+    so = (int32_t)((stages + len - 1) / len);               // drop empty slices
+    int32_t sd = diag_split_for(stages, so);
+    int64_t dlen = (stages + sd - 1) / sd;
+    sd = (int32_t)((stages + dlen - 1) / dlen);
+    g.split_off = so;
+    g.split_diag = sd;
+    g.kchunk_off = len * kGramKT;
+    g.kchunk_diag = dlen * kGramKT;
+    return g;
 }
 
 hipError_t launch_gram_dense(strads_lasso *h, int part)
 {
-    const int32_t T = h->Lpad / kGramTile;
-    int32_t split = h->split_user > 0 ? h->split_user : gram_split_auto(h->cfg.n, h->Lpad);
-    if (split > h->split_max) split = h->split_max;
-    int64_t kchunk = (h->cfg.n + split - 1) / split;
-    kchunk = ((kchunk + kGramKT - 1) / kGramKT) * kGramKT;
-    split = (int32_t)((h->cfg.n + kchunk - 1) / kchunk);
+    const GramShape g = gram_shape(h);
     const size_t lds = 2 * 2 * kPanel * sizeof(float);
     float *P = h->at<float>(h->ws.partial);
-    const dim3 grid((unsigned)(T * (T + 1) / 2 * split));
     if (part == 1) {
         RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
-        hipLaunchKernelGGL(k_gram_mask, dim3((h->Lpad + 255) / 256, h->Lpad), dim3(256), 0, h->stream, P, split,
-                           h->L, h->Lpad, h->cfg.rho, h->at<uint64_t>(h->ws.mask),
+        hipLaunchKernelGGL(k_gram_mask, dim3((h->Lpad + 255) / 256, h->Lpad), dim3(256), 0, h->stream, P,
+                           g.split_off, g.split_diag, h->L, h->Lpad, h->cfg.rho, h->at<uint64_t>(h->ws.mask),
                            h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr, &sc->near_rho_pairs);
         return hipGetLastError();
     }
+    const dim3 grid((unsigned)(g.T * (g.T - 1) / 2 * g.split_off + g.T * g.split_diag));
     if (h->vec4)
         hipLaunchKernelGGL(k_gram_tiles<true>, grid, dim3(256), lds, h->stream, h->cfg.x, h->cfg.n,
-                           h->at<int32_t>(h->ws.cand), h->L, h->Lpad, T, split, kchunk, P);
+                           h->at<int32_t>(h->ws.cand), g, P);
     else
         hipLaunchKernelGGL(k_gram_tiles<false>, grid, dim3(256), lds, h->stream, h->cfg.x, h->cfg.n,
-                           h->at<int32_t>(h->ws.cand), h->L, h->Lpad, T, split, kchunk, P);
+                           h->at<int32_t>(h->ws.cand), g, P);
     return hipGetLastError();
 }
 
