@@ -5,9 +5,10 @@
 // The walk is sequential in the kept set, so the work is arranged to keep the serial chain short.
 // One workgroup of 1024 threads takes the candidates 64 at a time (a "chunk").  `dead` (one bit
 // per candidate, in LDS) marks candidates that conflict with something already kept.
-//   * The chunk's 64 conflict rows (words at or right of the chunk's own word) are staged in LDS;
-//     the rows of chunk c+1 are fetched from global memory into registers while chunk c is being
-//     decided, so no global-memory latency sits on the serial chain.
+//   * The chunk's 64 conflict rows (words at or right of the chunk's own word) are staged in LDS.
+//     The mask was written by workgroups all over the chip, so its first read by this workgroup
+//     comes from HBM, about a microsecond away, while a chunk is decided in a fraction of that:
+//     the rows are therefore fetched into registers kFilterAhead chunks ahead of their use.
 //   * Wavefront 0 decides the chunk: candidates that are alive and have no conflict with another
 //     alive candidate of the chunk are kept at once; only the few with an in-chunk conflict are
 //     walked one by one (scalar bit operations on the 64x64 diagonal block).
@@ -27,6 +28,7 @@ __device__ __forceinline__ uint64_t readlane64(uint64_t v, int l)
 
 constexpr int kMaxWords = STRADS_MAX_L_PRIME / 64;   // mask words per row (128)
 constexpr int kFilterThreads = 1024;
+constexpr int kFilterAhead = 4;                     // chunks whose rows are in flight from memory
 
 // IPT = words of a chunk's 64 rows handled per thread = ceil(64 * W / 1024): 1, 2, 4 or 8.
 template <int kRowWordsPerThread>
@@ -57,29 +59,32 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
         irow[q] = (int16_t)rw;
         iword[q] = it < items ? (int16_t)(it - rw * W) : (int16_t)-1;     // -1: no such item
     }
-    // stage chunk 0
-    uint64_t pre[kRowWordsPerThread];
-    auto fetch = [&](int32_t c) {
+    // register sets of the chunks in flight: chunk c waits in set c % kFilterAhead
+    uint64_t pre[kFilterAhead][kRowWordsPerThread];
+    auto fetch = [&](int32_t c, uint64_t (&dst)[kRowWordsPerThread]) {
 #pragma unroll
         for (int q = 0; q < kRowWordsPerThread; ++q) {
             const int32_t a = c * 64 + irow[q], w = iword[q];
-            pre[q] = (w >= c && a < L) ? mask[(int64_t)a * W + w] : 0ull;
+            dst[q] = (c < chunks && w >= c && a < L) ? mask[(int64_t)a * W + w] : 0ull;
         }
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int buf, const uint64_t (&src)[kRowWordsPerThread]) {
 #pragma unroll
         for (int q = 0; q < kRowWordsPerThread; ++q) {
             const int32_t it = tid + q * kFilterThreads;
-            if (it < items) rows[(size_t)buf * items + it] = pre[q];
+            if (it < items) rows[(size_t)buf * items + it] = src[q];
         }
     };
-    fetch(0);
-    stash(0);
+#pragma unroll
+    for (int d = 0; d < kFilterAhead; ++d) fetch(d, pre[d]);
+    stash(0, pre[0]);
     __syncthreads();
 
-    for (int32_t c = 0; c < chunks; ++c) {
+    // one chunk; `mine` is the (now free) register set chunk c waited in, `next` holds chunk c+1.
+    // Returns true when the cap on the kept set has been reached.
+    auto step = [&](int32_t c, uint64_t (&mine)[kRowWordsPerThread], const uint64_t (&next)[kRowWordsPerThread]) -> bool {
         const uint64_t *rb = rows + (size_t)(c & 1) * items;
-        if (c + 1 < chunks) fetch(c + 1);         // in flight while this chunk is decided
+        fetch(c + kFilterAhead, mine);            // in flight while the next chunks are decided
         if (wave == 0) {
             const int32_t nk0 = nk_s;
             int32_t nk = nk0;
@@ -136,9 +141,18 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
                 }
             }
         }
-        if (c + 1 < chunks) stash((c + 1) & 1);
+        if (c + 1 < chunks) stash((c + 1) & 1, next);
         __syncthreads();
-        if (full) break;
+        return full;
+    };
+
+    for (int32_t c0 = 0; c0 < chunks; c0 += kFilterAhead) {
+        bool stop = false;
+#pragma unroll
+        for (int d = 0; d < kFilterAhead; ++d) {
+            if (!stop && c0 + d < chunks) stop = step(c0 + d, pre[d], pre[(d + 1) % kFilterAhead]);
+        }
+        if (stop) break;
     }
     // kept column ids, gathered once at the end (a global load inside the loop above would put
     // a memory round trip on the serial chain of every chunk)

@@ -82,34 +82,38 @@ __device__ __forceinline__ uint32_t orderable(float key)
 // ---------------------------------------------------------------------------------------------
 // In a histogram whose bins are ordered ascending, find the bin that holds the K-th largest
 // element: above(bin) < K <= above(bin) + hist[bin].  All 256 threads call it; results are
-// returned to all.  tmp: 256 + 2 uint32 of LDS.
+// returned to all.  tmp: 6 uint32 of LDS.  Thread t owns bins 8t..8t+7; the suffix sums over the
+// per-thread totals are taken inside each wavefront with lane shifts, then across the four
+// wavefronts through LDS (two barriers in all).
 __device__ void find_bin_desc(const uint32_t *__restrict__ hist, uint32_t K, uint32_t *tmp, uint32_t &bin,
                               uint32_t &above)
 {
-    const int t = threadIdx.x;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     uint32_t loc[8];
     uint32_t s = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) { loc[i] = hist[8 * t + i]; s += loc[i]; }
-    tmp[t] = s;
-    if (t == 0) { tmp[256] = 0; tmp[257] = 0; }
-    __syncthreads();
-    // inclusive suffix sums over the 256 per-thread totals
-    for (int off = 1; off < 256; off <<= 1) {
-        uint32_t v = (t + off < 256) ? tmp[t + off] : 0u;
-        __syncthreads();
-        tmp[t] += v;
-        __syncthreads();
+    uint32_t suf = s;                           // inclusive suffix sum over the lanes of this wavefront
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t v = __shfl_down(suf, d);
+        if (lane + d < 64) suf += v;
     }
-    uint32_t ab = tmp[t] - s;      // elements in bins above this thread's 8 bins
+    if (lane == 0) tmp[wave] = suf;             // total of this wavefront
+    if (t == 0) { tmp[4] = 0; tmp[5] = 0; }
+    __syncthreads();
+    uint32_t higher = 0;                        // totals of the wavefronts holding higher bins
+#pragma unroll
+    for (int w = 1; w < 4; ++w) if (w > wave) higher += tmp[w];
+    uint32_t ab = higher + suf - s;             // elements in bins above this thread's 8 bins
 #pragma unroll
     for (int i = 7; i >= 0; --i) {
-        if (ab < K && K <= ab + loc[i]) { tmp[256] = 8 * t + i; tmp[257] = ab; }
+        if (ab < K && K <= ab + loc[i]) { tmp[4] = 8 * t + i; tmp[5] = ab; }
         ab += loc[i];
     }
     __syncthreads();
-    bin = tmp[256];
-    above = tmp[257];
+    bin = tmp[4];
+    above = tmp[5];
     __syncthreads();
 }
 
@@ -174,23 +178,27 @@ __global__ __launch_bounds__(256) void k_hist2(const uint32_t *__restrict__ keys
         if (lh[i]) atomicAdd(&hist1[i], lh[i]);
 }
 
-constexpr int kCollectPerThread = 4;
+constexpr int kCollectPerThread = 16;
 
 // pass 3: everything strictly above the 22-bit boundary prefix is selected; keys on the prefix
 // go to the boundary list.  Items are (orderable key << 32) | (2^32-1 - j): all distinct, and
 // larger item <=> (larger key, then smaller j).
+//
+// Every appended item needs a slot from one of two device-wide counters, and atomics on one
+// address are served one after the other (roughly 8 ns each), so a workgroup looks at
+// 256 * kCollectPerThread keys, counts first, and reserves its slots with ONE atomic per list.
 __global__ __launch_bounds__(256) void k_collect(const uint32_t *__restrict__ keys, uint32_t J,
                                                  const uint32_t *__restrict__ hist1, RoundScalars *__restrict__ sc,
                                                  uint64_t *__restrict__ sel, uint64_t *__restrict__ bnd)
 {
     __shared__ uint32_t tmp[258];
+    __shared__ uint32_t wtot[2][4], wbase[2][4];
     const uint32_t b0 = sc->bin0, rem1 = sc->rem1;
     uint32_t b1, above;
     find_bin_desc(hist1, rem1, tmp, b1, above);
     const uint32_t p22 = (b0 << 11) | b1;
     if (blockIdx.x == 0 && threadIdx.x == 0) { sc->prefix22 = p22; sc->rem2 = rem1 - above; }
-    // Each thread looks at kCollectPerThread keys first and appends afterwards, so a wavefront
-    // issues at most one atomic per list however many keys it scans.
+    const int lane = __lane_id(), wave = threadIdx.x >> 6;
     const uint32_t base = (blockIdx.x * 256u + (threadIdx.x & ~63u)) * kCollectPerThread + (threadIdx.x & 63u);
     uint32_t okv[kCollectPerThread];
     uint32_t n_gt = 0, n_eq = 0;
@@ -202,23 +210,26 @@ __global__ __launch_bounds__(256) void k_collect(const uint32_t *__restrict__ ke
         n_gt += (j < J && p > p22) ? 1u : 0u;
         n_eq += (j < J && p == p22) ? 1u : 0u;
     }
-    // wavefront-level exclusive scan of the per-lane counts
-    const int lane = __lane_id();
+    // wavefront-level inclusive scan of the per-lane counts, then one reservation per workgroup
     uint32_t off_gt = n_gt, off_eq = n_eq;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
         const uint32_t a = __shfl_up(off_gt, d), b = __shfl_up(off_eq, d);
         if (lane >= d) { off_gt += a; off_eq += b; }
     }
-    const uint32_t tot_gt = __shfl(off_gt, 63), tot_eq = __shfl(off_eq, 63);
-    off_gt -= n_gt; off_eq -= n_eq;
-    uint32_t base_gt = 0, base_eq = 0;
-    if (lane == 0) {
-        if (tot_gt) base_gt = atomicAdd(&sc->n_sel, tot_gt);
-        if (tot_eq) base_eq = atomicAdd(&sc->n_bnd, tot_eq);
+    if (lane == 63) { wtot[0][wave] = off_gt; wtot[1][wave] = off_eq; }
+    __syncthreads();
+    if (threadIdx.x < 2) {
+        const int l = threadIdx.x;
+        const uint32_t t0 = wtot[l][0], t1 = wtot[l][1], t2 = wtot[l][2], t3 = wtot[l][3];
+        const uint32_t tot = t0 + t1 + t2 + t3;
+        uint32_t b = 0;
+        if (tot) b = atomicAdd(l == 0 ? &sc->n_sel : &sc->n_bnd, tot);
+        wbase[l][0] = b; wbase[l][1] = b + t0; wbase[l][2] = b + t0 + t1; wbase[l][3] = b + t0 + t1 + t2;
     }
-    base_gt = __shfl(base_gt, 0) + off_gt;
-    base_eq = __shfl(base_eq, 0) + off_eq;
+    __syncthreads();
+    uint32_t base_gt = wbase[0][wave] + off_gt - n_gt;
+    uint32_t base_eq = wbase[1][wave] + off_eq - n_eq;
 #pragma unroll
     for (int q = 0; q < kCollectPerThread; ++q) {
         const uint32_t j = base + q * 64u;
