@@ -81,6 +81,9 @@ def lib():
         L.oracle_round.argtypes = [C.POINTER(_Problem), u64, vp, vp, vp, vp, i32, vp, i32,
                                    vp, C.POINTER(i32), vp, vp, vp, vp, vp]
         L.oracle_round.restype = i32
+        L.oracle_round_dynamic.argtypes = [C.POINTER(_Problem), u64, vp, vp, vp, vp, i32, vp, vp, i32,
+                                           vp, C.POINTER(i32), vp, vp, vp, vp, vp, vp, vp, vp]
+        L.oracle_round_dynamic.restype = i32
         _lib = L
     return _lib
 
@@ -166,7 +169,8 @@ class OracleLasso:
     (row j = covariate j).  CSC: pass values,row_idx,col_ptr and n."""
 
     def __init__(self, y, lam, rho, eta, l_prime, seed=0, p_max=0, c_init=1e6, x=None,
-                 values=None, row_idx=None, col_ptr=None, n=None):
+                 values=None, row_idx=None, col_ptr=None, n=None, dynamic=False):
+        self.dynamic = bool(dynamic)          # update-aware dependencies (oracle_round_dynamic)
         self.y = _arr(y, np.float32)
         if x is not None:
             self.x = _arr(x, np.float32)
@@ -196,7 +200,10 @@ class OracleLasso:
         self.r[:] = r
         self.t = int(t)
 
-    def round(self, want_gram=False, forced_cand=None, forced_kept_pos=None) -> dict:
+    def round(self, want_gram=False, forced_cand=None, forced_kept_pos=None, forced_mover=None) -> dict:
+        if self.dynamic:
+            return self._round_dynamic(want_gram, forced_cand, forced_mover, forced_kept_pos)
+        assert forced_mover is None
         Lmax = max(self.l_prime if forced_cand is None else len(forced_cand), 1)
         cand = np.empty(Lmax, np.int32)
         kept_pos = np.empty(Lmax, np.int32)
@@ -217,6 +224,37 @@ class OracleLasso:
         self.t += 1
         out = {"cand": cand[:L].copy(), "kept_pos": kept_pos[:k].copy(), "kept": kept[:k].copy(),
                "z": z[:k].copy(), "delta": delta[:k].copy()}
+        if want_gram:
+            out["G"] = G[:L, :L] if L == Lmax else G.reshape(-1)[:L * L].reshape(L, L).copy()
+        return out
+
+    def _round_dynamic(self, want_gram, forced_cand, forced_mover, forced_kept_pos) -> dict:
+        Lmax = max(self.l_prime if forced_cand is None else len(forced_cand), 1)
+        cand = np.empty(Lmax, np.int32)
+        kept_pos = np.empty(Lmax, np.int32)
+        kept = np.empty(Lmax, np.int32)
+        mover = np.zeros(Lmax, np.uint8)
+        z_cand = np.empty(Lmax, np.float64)
+        d_cand = np.empty(Lmax, np.float64)
+        z = np.empty(Lmax, np.float64)
+        delta = np.empty(Lmax, np.float64)
+        G = np.empty((Lmax, Lmax), np.float32) if want_gram else None
+        fc = None if forced_cand is None else _arr(forced_cand, np.int32)
+        fm = None if forced_mover is None else _arr(forced_mover, np.uint8)
+        fk = None if forced_kept_pos is None else _arr(forced_kept_pos, np.int32)
+        ncand = C.c_int32(0)
+        k = lib().oracle_round_dynamic(C.byref(self._prob), self.t, _p(self.beta), _p(self.dbeta), _p(self.r),
+                                       _p(fc), 0 if fc is None else fc.shape[0], _p(fm),
+                                       _p(fk), 0 if fk is None else fk.shape[0],
+                                       _p(cand), C.byref(ncand), _p(mover), _p(z_cand), _p(d_cand),
+                                       _p(kept_pos), _p(kept), _p(G), _p(z), _p(delta))
+        if k < 0:
+            raise MemoryError("oracle_round_dynamic allocation failed")
+        L = ncand.value
+        self.t += 1
+        out = {"cand": cand[:L].copy(), "kept_pos": kept_pos[:k].copy(), "kept": kept[:k].copy(),
+               "z": z[:k].copy(), "delta": delta[:k].copy(), "mover": mover[:L].astype(bool),
+               "z_cand": z_cand[:L].copy(), "delta_cand": d_cand[:L].copy()}
         if want_gram:
             out["G"] = G[:L, :L] if L == Lmax else G.reshape(-1)[:L * L].reshape(L, L).copy()
         return out

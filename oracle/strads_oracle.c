@@ -23,7 +23,11 @@
  * greedy filter against brute-force subset enumeration; soft-threshold closed
  * form; orthonormal-design exact solution; KKT at convergence and agreement
  * with an independent library Lasso solver; monotone descent for sequential
- * updates; residual invariant r = y - X beta.
+ * updates; residual invariant r = y - X beta.  The round with update-aware
+ * dependencies (oracle_round_dynamic, tests/test_oracle_dynamic.py): equality
+ * with the plain round where the two must coincide (no conflicts; every
+ * candidate moves), brute-force enumeration, hand-built three-column designs,
+ * and the same fixed point.
  */
 #include <math.h>
 #include <stdint.h>
@@ -399,5 +403,110 @@ int32_t oracle_round(const oracle_problem_t *p, uint64_t t, float *beta, float *
     else            oracle_residual_dense(p->N, p->X, kept_cols, k, d, r);
     if (!z_out) free(z);
     if (!delta_out) free(d);
+    return k;
+}
+
+/* --------------------------------------------------------------------------
+ * Round with update-aware ("dynamic") dependencies.
+ *
+ * Section 1 ("Dynamic Block Structures") observes that a coefficient which
+ * stays where it is during a round neither disturbs nor is disturbed by the
+ * parallel update of a correlated one, however large the correlation; Step 4
+ * of Section 2 has the scheduler remove such dependencies.  In eq. (2) the
+ * interference of k with j's update is x_j^T x_k * (change of beta_k), which
+ * vanishes exactly when beta_k does not change.  So the dependency used by
+ * Step 2 becomes
+ *      d_t(a, b) = |x_a^T x_b|   if both a and b would move this round,
+ *                = 0             otherwise,
+ * where "a would move" means its update from the residual of the start of the
+ * round, S(x_a^T r + beta_a, lambda) - beta_a, is not zero.  Everything else
+ * is Algorithm 1 unchanged: draw U, choose B_1 greedily in draw order under
+ * d_t < rho (and the cap p_max), update B_1 from the same r, bookkeeping.  A
+ * kept coordinate that does not move gets delta beta = 0, as in Algorithm 1.
+ *
+ * Outputs per candidate (L entries each; any may be NULL): z_cand = x^T r,
+ * delta_cand = tentative change, mover = 1/0.  G_out (L x L, may be NULL)
+ * receives d_t's signed values (x_a^T x_b for mover pairs, 0 elsewhere).
+ * forced_cand / forced_mover / forced_kept_pos replace the oracle's own index
+ * decisions (see oracle_round); a candidate forced to "does not move" is
+ * committed with change 0.
+ * Returns |B_1| or a negative number on allocation failure.
+ * ------------------------------------------------------------------------ */
+int32_t oracle_round_dynamic(const oracle_problem_t *p, uint64_t t, float *beta, float *dbeta, float *r,
+                             const int32_t *forced_cand, int32_t forced_n_cand,
+                             const uint8_t *forced_mover,
+                             const int32_t *forced_kept_pos, int32_t forced_n_kept,
+                             int32_t *cand, int32_t *n_cand_out, uint8_t *mover_out,
+                             double *z_cand_out, double *delta_cand_out,
+                             int32_t *kept_pos, int32_t *kept_cols, float *G_out,
+                             double *z_out, double *delta_out)
+{
+    int32_t L;
+    if (forced_cand) {
+        L = forced_n_cand;
+        memcpy(cand, forced_cand, (size_t)L * sizeof(int32_t));
+    } else {
+        float *keys = (float *)malloc((size_t)(p->J > 0 ? p->J : 1) * sizeof(float));
+        if (!keys) return -1;
+        oracle_priority_keys(p->J, dbeta, p->eta, p->seed, t, keys);
+        L = oracle_draw(p->J, keys, p->l_prime, cand);
+        free(keys);
+        if (L < 0) return -1;
+    }
+    *n_cand_out = L;
+    const size_t Ls = (size_t)(L > 0 ? L : 1);
+
+    /* every candidate's update from the residual as it stands */
+    double *zc = (double *)malloc(Ls * sizeof(double));
+    double *dc = (double *)malloc(Ls * sizeof(double));
+    float *nb = (float *)malloc(Ls * sizeof(float));
+    uint8_t *mv = (uint8_t *)malloc(Ls);
+    float *G = G_out ? G_out : (float *)malloc(Ls * Ls * sizeof(float));
+    if (!zc || !dc || !nb || !mv || !G) return -1;
+    if (p->row_idx) oracle_dots_csc(p->X, p->row_idx, p->col_ptr, cand, L, r, zc);
+    else            oracle_dots_dense(p->N, p->X, cand, L, r, zc);
+    for (int32_t a = 0; a < L; ++a) {
+        const double old = (double)beta[cand[a]];
+        nb[a] = (float)oracle_soft_threshold(zc[a] + old, (double)p->lambda);
+        dc[a] = (double)nb[a] - old;
+        mv[a] = forced_mover ? (uint8_t)(forced_mover[a] != 0) : (uint8_t)(dc[a] != 0.0);
+        if (!mv[a]) { dc[a] = 0.0; nb[a] = beta[cand[a]]; }
+    }
+
+    /* dependencies among the candidates, kept only between two movers */
+    if (p->row_idx) oracle_gram_csc(p->X, p->row_idx, p->col_ptr, cand, L, G);
+    else            oracle_gram_dense(p->N, p->X, cand, L, G);
+    for (int32_t a = 0; a < L; ++a)
+        for (int32_t b = 0; b < L; ++b)
+            if (!(mv[a] && mv[b])) G[(int64_t)a * L + b] = 0.0f;
+
+    int32_t k;
+    if (forced_kept_pos) {
+        k = forced_n_kept;
+        memcpy(kept_pos, forced_kept_pos, (size_t)k * sizeof(int32_t));
+    } else {
+        k = oracle_filter(L, G, p->rho, p->p_max, kept_pos);
+    }
+
+    /* commit B_1 (all from the same r), then the residual */
+    double *dk = delta_out ? delta_out : (double *)malloc((size_t)(k > 0 ? k : 1) * sizeof(double));
+    if (!dk) return -1;
+    for (int32_t c = 0; c < k; ++c) {
+        const int32_t a = kept_pos[c], j = cand[a];
+        kept_cols[c] = j;
+        if (z_out) z_out[c] = zc[a];
+        dk[c] = dc[a];
+        dbeta[j] = (float)fabs(dc[a]);
+        beta[j] = nb[a];
+    }
+    if (p->row_idx) oracle_residual_csc(p->N, p->X, p->row_idx, p->col_ptr, kept_cols, k, dk, r);
+    else            oracle_residual_dense(p->N, p->X, kept_cols, k, dk, r);
+
+    if (mover_out) memcpy(mover_out, mv, (size_t)L);
+    if (z_cand_out) memcpy(z_cand_out, zc, (size_t)L * sizeof(double));
+    if (delta_cand_out) memcpy(delta_cand_out, dc, (size_t)L * sizeof(double));
+    if (!delta_out) free(dk);
+    if (!G_out) free(G);
+    free(zc); free(dc); free(nb); free(mv);
     return k;
 }
