@@ -55,6 +55,9 @@ def main() -> int:
     ap.add_argument("--profile-level", type=int, default=1, choices=(0, 1, 2),
                     help="HIP-event timing inside the timed region: 1 = Gram kernel only, 2 = every stage")
     ap.add_argument("--split-k", type=int, default=0)
+    ap.add_argument("--deps", default="static", choices=("static", "dynamic"),
+                    help="dependency rule of Step 2: static = Algorithm 1 as printed (the headline workload); "
+                         "dynamic = only pairs of candidates that both move are checked (dense designs)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -80,7 +83,8 @@ def main() -> int:
     t_gen = time.time() - t0
 
     def fresh():
-        kw = dict(y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
+        kw = dict(y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed,
+                  dynamic=args.deps == "dynamic")
         if p.layout == "dense":
             return pk.StradsLasso(x=p.x, **kw)
         return pk.StradsLasso(values=p.values, row_idx=p.row_idx, col_ptr=p.col_ptr, n=p.n, **kw)
@@ -126,7 +130,8 @@ def main() -> int:
     L, N = g.L, p.n
     gram_flops = float(N) * L * (L - 1)          # algorithmic: every unordered pair once, 2 flops per row
     roofline = None
-    if args.profile_level and stage["rounds"] > 0 and stage["gram_tiles"] > 0 and p.layout == "dense":
+    if (args.profile_level and stage["rounds"] > 0 and stage["gram_tiles"] > 0 and p.layout == "dense"
+            and args.deps == "static"):
         ach = gram_flops / (stage["gram_tiles"] * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "k_gram_tiles", "achieved": round(ach, 3),
                     "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_FP32_PEAK_TFLOPS, 4),
@@ -136,7 +141,8 @@ def main() -> int:
     cpu = None
     if args.cpu_seconds > 0:
         from oracle.oracle import OracleLasso
-        okw = dict(y=p.y.cpu().numpy(), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
+        okw = dict(y=p.y.cpu().numpy(), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed,
+                   dynamic=args.deps == "dynamic")
         if p.layout == "dense":
             o = OracleLasso(x=p.x.cpu().numpy(), **okw)
         else:
@@ -160,7 +166,7 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall / max(args.steps, 1) * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "n": p.n, "j": p.j, "l_prime": p.l_prime, "rho": p.rho,
-                   "eta": p.eta, "lambda": p.lam, "rounds": args.steps, "parallelism": "1 GPU"},
+                   "eta": p.eta, "lambda": p.lam, "rounds": args.steps, "deps": args.deps, "parallelism": "1 GPU"},
         "rounds_per_s": round(args.steps / wall, 2), "updates": updates,
         "objective_start": f0, "objective_end": f1, "kkt_violation_end": viol,
         "roofline": roofline,

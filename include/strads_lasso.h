@@ -53,12 +53,22 @@ extern "C" {
 
 /* Stages of one round, in stream order, as timed by strads_lasso_stage_times */
 #define STRADS_STAGE_SAMPLER     0   /* Step 1: keys, top-P' selection, draw order */
-#define STRADS_STAGE_GRAM_TILES  1   /* Step 2: candidate Gram, MFMA tile kernel (K-slices) */
-#define STRADS_STAGE_GRAM_MASK   2   /* Step 2: K-slice sum and |g| < rho conflict bits */
-#define STRADS_STAGE_FILTER      3   /* Step 2: greedy choice of B_1 */
-#define STRADS_STAGE_UPDATE      4   /* eq. (2): x_j^T r for B_1, soft-threshold, bookkeeping */
-#define STRADS_STAGE_RESIDUAL    5   /* r <- r - X_B * change */
-#define STRADS_N_STAGES          6
+#define STRADS_STAGE_CAND_DOTS   1   /* dynamic dependencies only: x_j^T r and the tentative change of
+                                        every candidate, and the list of those that would move */
+#define STRADS_STAGE_GRAM_TILES  2   /* Step 2: candidate Gram, MFMA tile kernel (K-slices) */
+#define STRADS_STAGE_GRAM_MASK   3   /* Step 2: K-slice sum and |g| < rho conflict bits */
+#define STRADS_STAGE_FILTER      4   /* Step 2: greedy choice of B_1 */
+#define STRADS_STAGE_UPDATE      5   /* eq. (2): x_j^T r for B_1, soft-threshold, bookkeeping */
+#define STRADS_STAGE_RESIDUAL    6   /* r <- r - X_B * change */
+#define STRADS_N_STAGES          7
+
+/* Dependency rule of Step 2 */
+#define STRADS_DEPS_STATIC        0  /* Algorithm 1: d(a,b) = |x_a^T x_b| for every candidate pair */
+#define STRADS_DEPS_DYNAMIC       1  /* Section 1 "Dynamic Block Structures" / Step 4: a candidate whose
+                                        coefficient would not change this round (its update from the
+                                        current residual is zero) has no dependency with anyone;
+                                        d(a,b) = |x_a^T x_b| only between two candidates that both move.
+                                        The Gram and the greedy walk then run over the movers only. */
 
 typedef struct strads_lasso strads_lasso_t;   /* opaque, host side */
 
@@ -82,6 +92,7 @@ typedef struct {
                                      4*L^2 bytes of workspace and one extra write per round) */
     int32_t        max_col_nnz;   /* CSC only: an upper bound (>= 1) on the nonzeros of any column;
                                      sizes the per-round inverted index; checked at create */
+    int32_t        deps;          /* STRADS_DEPS_*: dependency rule of Step 2 (dynamic: dense designs only) */
     void          *workspace;     /* DEVICE, 256-byte aligned, caller-allocated */
     size_t         workspace_bytes;
     void          *stream;        /* hipStream_t owned by the caller (NULL = the default stream) */
@@ -104,9 +115,9 @@ typedef struct {
     int32_t converged;            /* 1 iff kkt_violation <= kkt_tol * lambda at exit */
 } strads_run_info_t;
 
-/* Bytes of workspace a configuration needs (depends on n, j, layout, l_prime,
- * keep_gram only; pointers in cfg are ignored).  Makes no device call.
- * (and max_col_nnz for CSC).  Returns 0 if cfg is NULL or a size field is invalid. */
+/* Bytes of workspace a configuration needs (depends on n, j, layout, l_prime, keep_gram, deps and,
+ * for CSC, max_col_nnz only; pointers in cfg are ignored).  Makes no device call.
+ * Returns 0 if cfg is NULL or a size field is invalid. */
 size_t strads_lasso_workspace_bytes(const strads_lasso_config_t *cfg);
 
 /* Validate cfg, carve the workspace and enqueue Algorithm 1's initialisation:
@@ -152,9 +163,16 @@ int strads_lasso_set_state(strads_lasso_t *h, const float *beta, const float *db
  * row-major, only when the handle was created with keep_gram); any may be NULL.
  * cand: candidates in draw order; kept_pos: positions into cand of the kept set
  * (increasing); z: x_j^T r per kept coordinate; delta: change of beta_j per kept
- * coordinate.  n_cand / n_kept are HOST.  Synchronises. */
+ * coordinate.  n_cand / n_kept are HOST.  Synchronises.
+ * With dynamic dependencies the Gram holds x_a^T x_b for pairs of movers and 0 elsewhere. */
 int strads_lasso_last_round(strads_lasso_t *h, int32_t *cand, int32_t *kept_pos, float *z, float *delta,
                             float *gram_or_null, int32_t *n_cand, int32_t *n_kept);
+
+/* Dynamic dependencies only: per candidate of the most recent round (DEVICE arrays of l_prime
+ * floats, any may be NULL) z_cand = x_j^T r and delta_cand = the change its update would make
+ * (S(z + beta_j, lambda) - beta_j; nonzero = "moves"); n_movers is HOST.  Synchronises.
+ * Returns STRADS_E_UNSUPPORTED on a handle with static dependencies. */
+int strads_lasso_last_candidates(strads_lasso_t *h, float *z_cand, float *delta_cand, int32_t *n_movers);
 
 /* Stage entry: the sampling keys log2(w_j) - log2(-log2 u_j) of Step 1 that round
  * `round` would use with the current delta beta (j floats, DEVICE). */

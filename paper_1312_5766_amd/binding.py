@@ -20,13 +20,14 @@ STRADS_OK = 0
 E_INVALID_ARG, E_WORKSPACE_TOO_SMALL, E_HIP, E_DIVERGED, E_UNSUPPORTED = -1, -2, -3, -4, -5
 LAYOUT_DENSE, LAYOUT_CSC = 0, 1
 MAX_L_PRIME = 8192
-N_STAGES = 6
-STAGE_NAMES = ["sampler", "gram_tiles", "gram_mask", "filter", "update", "residual"]
+N_STAGES = 7
+STAGE_NAMES = ["sampler", "cand_dots", "gram_tiles", "gram_mask", "filter", "update", "residual"]
+DEPS_STATIC, DEPS_DYNAMIC = 0, 1
 
 EXPORTS = [
     "strads_lasso_workspace_bytes", "strads_lasso_create", "strads_lasso_round", "strads_lasso_run",
     "strads_lasso_objective", "strads_lasso_kkt", "strads_lasso_get_state", "strads_lasso_set_state",
-    "strads_lasso_last_round", "strads_lasso_stage_keys", "strads_lasso_stage_filter",
+    "strads_lasso_last_round", "strads_lasso_last_candidates", "strads_lasso_stage_keys", "strads_lasso_stage_filter",
     "strads_lasso_set_tuning", "strads_lasso_stage_times", "strads_lasso_destroy", "strads_lasso_strerror",
 ]
 
@@ -36,7 +37,7 @@ class Config(C.Structure):
                 ("row_idx", C.c_void_p), ("col_ptr", C.c_void_p), ("y", C.c_void_p),
                 ("lam", C.c_float), ("rho", C.c_float), ("eta", C.c_float), ("c_init", C.c_float),
                 ("l_prime", C.c_int32), ("p_max", C.c_int32), ("seed", C.c_uint64), ("keep_gram", C.c_int32),
-                ("max_col_nnz", C.c_int32), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
+                ("max_col_nnz", C.c_int32), ("deps", C.c_int32), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
 
 
 class RoundInfo(C.Structure):
@@ -72,6 +73,7 @@ def load():
     L.strads_lasso_get_state.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_int64)]
     L.strads_lasso_set_state.argtypes = [vp, vp, vp, vp, C.c_int64]
     L.strads_lasso_last_round.argtypes = [vp, vp, vp, vp, vp, vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    L.strads_lasso_last_candidates.argtypes = [vp, vp, vp, C.POINTER(C.c_int32)]
     L.strads_lasso_stage_keys.argtypes = [vp, C.c_int64, vp]
     L.strads_lasso_stage_filter.argtypes = [vp, vp, C.c_int32, vp, C.POINTER(C.c_int32)]
     L.strads_lasso_set_tuning.argtypes = [vp, C.c_char_p, C.c_int64]
@@ -102,8 +104,10 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else t.data_ptr()
 
 
-def strads_lasso_workspace_bytes(n, j, l_prime, layout=LAYOUT_DENSE, keep_gram=False, max_col_nnz=0) -> int:
-    cfg = Config(n=n, j=j, layout=layout, l_prime=l_prime, keep_gram=int(keep_gram), max_col_nnz=int(max_col_nnz))
+def strads_lasso_workspace_bytes(n, j, l_prime, layout=LAYOUT_DENSE, keep_gram=False, max_col_nnz=0,
+                                 dynamic=False) -> int:
+    cfg = Config(n=n, j=j, layout=layout, l_prime=l_prime, keep_gram=int(keep_gram), max_col_nnz=int(max_col_nnz),
+                 deps=DEPS_DYNAMIC if dynamic else DEPS_STATIC)
     return int(load().strads_lasso_workspace_bytes(C.byref(cfg)))
 
 
@@ -115,7 +119,7 @@ class StradsLasso:
                  x: Optional[torch.Tensor] = None, values: Optional[torch.Tensor] = None,
                  row_idx: Optional[torch.Tensor] = None, col_ptr: Optional[torch.Tensor] = None,
                  n: Optional[int] = None, max_col_nnz: Optional[int] = None,
-                 stream: Optional[torch.cuda.Stream] = None):
+                 stream: Optional[torch.cuda.Stream] = None, dynamic: bool = False):
         lib = load()
         self._h = None
         dev = y.device
@@ -140,7 +144,8 @@ class StradsLasso:
         cfg = Config(n=self.N, j=self.J, layout=layout, x=_ptr(x if x is not None else values),
                      row_idx=_ptr(row_idx), col_ptr=_ptr(col_ptr), y=_ptr(y), lam=lam, rho=rho, eta=eta,
                      c_init=c_init, l_prime=int(l_prime), p_max=int(p_max), seed=int(seed),
-                     keep_gram=int(keep_gram), max_col_nnz=int(max_col_nnz or 0), stream=self.stream.cuda_stream)
+                     keep_gram=int(keep_gram), max_col_nnz=int(max_col_nnz or 0),
+                     deps=DEPS_DYNAMIC if dynamic else DEPS_STATIC, stream=self.stream.cuda_stream)
         nbytes = int(lib.strads_lasso_workspace_bytes(C.byref(cfg)))
         if nbytes == 0:
             raise StradsError(E_INVALID_ARG, "strads_lasso_workspace_bytes")
@@ -225,6 +230,14 @@ class StradsLasso:
         if want_gram:
             out["G"] = G
         return out
+
+    def last_candidates(self) -> dict:
+        z = torch.empty(self.L, dtype=torch.float32, device=self.device)
+        d = torch.empty(self.L, dtype=torch.float32, device=self.device)
+        nm = C.c_int32()
+        _check(load().strads_lasso_last_candidates(self._h, _ptr(z), _ptr(d), C.byref(nm)),
+               "strads_lasso_last_candidates")
+        return {"z_cand": z, "delta_cand": d, "n_movers": nm.value}
 
     def stage_keys(self, t: int) -> torch.Tensor:
         keys = torch.empty(self.J, dtype=torch.float32, device=self.device)

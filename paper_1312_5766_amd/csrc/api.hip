@@ -10,13 +10,7 @@ namespace strads {
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-static int split_for_workspace(int64_t n, int32_t lpad)
-{
-    // the automatic choice, but never more than 64 MiB... of slices beyond what a round will use
-    return gram_split_auto(n, lpad);
-}
-
-Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram, int32_t max_col_nnz)
+Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram, int32_t max_col_nnz, int32_t deps)
 {
     Workspace w;
     memset(&w, 0, sizeof(w));
@@ -34,7 +28,7 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
     w.bnd = take((size_t)j * 8);
     w.cand = take((size_t)lpad * 4);
     if (layout == STRADS_LAYOUT_DENSE_COLMAJOR)
-        w.partial = take((size_t)split_for_workspace(n, (int32_t)lpad) * lpad * lpad * 4);
+        w.partial = take(gram_partial_floats(n, (int32_t)lpad, deps == STRADS_DEPS_DYNAMIC) * 4);
     else
         w.partial = take(256);
     w.gram = take(keep_gram ? (size_t)lpad * lpad * 4 : 256);
@@ -48,6 +42,15 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
     w.rpart = take((size_t)kMaxResidualGroups * npad * 4);
     w.objpart = take((size_t)kObjBlocks * 8);
     w.objout = take(8);
+    const size_t dyn = deps == STRADS_DEPS_DYNAMIC ? (size_t)lpad * 4 : 256;
+    w.zc = take(dyn);
+    w.dc = take(dyn);
+    w.nbc = take(dyn);
+    w.mpos = take(dyn);
+    w.mcand = take(dyn);
+    w.mkept_pos = take(dyn);
+    w.dshape = take(sizeof(GramShape));
+    w.dtable = take(sizeof(GramShape) * (STRADS_MAX_L_PRIME / kGramTile + 1));
     w.csc_scratch_bytes = layout == STRADS_LAYOUT_CSC ? csc_scratch_bytes(n, l, max_col_nnz) : 0;
     w.csc_scratch = take(w.csc_scratch_bytes ? w.csc_scratch_bytes : 256);
     w.total = off;
@@ -61,6 +64,7 @@ static bool sizes_ok(const strads_lasso_config_t *c)
     if (c->layout != STRADS_LAYOUT_DENSE_COLMAJOR && c->layout != STRADS_LAYOUT_CSC) return false;
     if (c->l_prime < 1 || c->l_prime > STRADS_MAX_L_PRIME) return false;
     if (c->layout == STRADS_LAYOUT_CSC && (c->n >= (int64_t)1 << 31 || c->max_col_nnz < 1)) return false;
+    if (c->deps != STRADS_DEPS_STATIC && c->deps != STRADS_DEPS_DYNAMIC) return false;
     return true;
 }
 
@@ -80,12 +84,13 @@ extern "C" {
 size_t strads_lasso_workspace_bytes(const strads_lasso_config_t *cfg)
 {
     if (!sizes_ok(cfg)) return 0;
-    return carve(cfg->n, cfg->j, cfg->layout, clamp_l(cfg), cfg->keep_gram, cfg->max_col_nnz).total;
+    return carve(cfg->n, cfg->j, cfg->layout, clamp_l(cfg), cfg->keep_gram, cfg->max_col_nnz, cfg->deps).total;
 }
 
 int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
 {
     if (!out || !sizes_ok(cfg)) return STRADS_E_INVALID_ARG;
+    if (cfg->deps == STRADS_DEPS_DYNAMIC && cfg->layout != STRADS_LAYOUT_DENSE_COLMAJOR) return STRADS_E_UNSUPPORTED;
     if (!cfg->x || !cfg->y || !cfg->workspace) return STRADS_E_INVALID_ARG;
     if (cfg->layout == STRADS_LAYOUT_CSC && (!cfg->row_idx || !cfg->col_ptr)) return STRADS_E_INVALID_ARG;
     if (!(cfg->lambda >= 0.f) || !isfinite(cfg->lambda)) return STRADS_E_INVALID_ARG;
@@ -97,7 +102,7 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     if (((uintptr_t)cfg->x & 3u) != 0 || ((uintptr_t)cfg->y & 3u) != 0) return STRADS_E_INVALID_ARG;
 
     const int32_t L = clamp_l(cfg);
-    const Workspace ws = carve(cfg->n, cfg->j, cfg->layout, L, cfg->keep_gram, cfg->max_col_nnz);
+    const Workspace ws = carve(cfg->n, cfg->j, cfg->layout, L, cfg->keep_gram, cfg->max_col_nnz, cfg->deps);
     if (cfg->workspace_bytes < ws.total) return STRADS_E_WORKSPACE_TOO_SMALL;
 
     strads_lasso *h = (strads_lasso *)calloc(1, sizeof(strads_lasso));
@@ -124,6 +129,16 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
         free(h);
         return STRADS_E_HIP;
     }
+    if (cfg->deps == STRADS_DEPS_DYNAMIC) {
+        // Gram decomposition per mover-tile count, looked up by the mover kernel every round
+        gram_shape_table(cfg->n, h->Lpad, h->shape_table);
+        if (hipMemcpyAsync(h->base + ws.dtable, h->shape_table, sizeof(GramShape) * (size_t)(h->Lpad / kGramTile + 1),
+                           hipMemcpyHostToDevice, h->stream) != hipSuccess ||
+            hipStreamSynchronize(h->stream) != hipSuccess) {
+            free(h);
+            return STRADS_E_HIP;
+        }
+    }
     if (cfg->layout == STRADS_LAYOUT_CSC) {
         // the sparse kernels size their buckets from max_col_nnz: check col_ptr against it once
         RoundScalars sc;
@@ -149,33 +164,44 @@ void strads_lasso_destroy(strads_lasso_t *h)
     free(h);
 }
 
-// Stage boundaries of a round, in stream order: 0 | sampler | 1 | Gram tiles | 2 | Gram sum+mask
-// | 3 | filter | 4 | dots + update | 5 | residual | 6
+// Stage boundaries of a round, in stream order: boundary b precedes stage b (STRADS_STAGE_*)
+// and boundary STRADS_N_STAGES closes the round.
 static inline int mark(strads_lasso *h, int boundary)
 {
     if (h->profile_level == 0 || h->profiled >= h->profile_rounds) return STRADS_OK;
-    if (h->profile_level == 1 && boundary != 1 && boundary != 2) return STRADS_OK;
+    if (h->profile_level == 1 && boundary != STRADS_STAGE_GRAM_TILES && boundary != STRADS_STAGE_GRAM_TILES + 1)
+        return STRADS_OK;
     HIP_TRY(hipEventRecord(h->events[(size_t)h->profiled * kStageEvents + boundary], h->stream));
     return STRADS_OK;
 }
 
+#define MARK(b) do { const int rc_ = mark(h, (b)); if (rc_ != STRADS_OK) return rc_; } while (0)
+
 static int enqueue_round(strads_lasso *h)
 {
     const bool dense = h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR;
-    int rc;
-    if ((rc = mark(h, 0)) != STRADS_OK) return rc;
+    const bool dynamic = h->cfg.deps == STRADS_DEPS_DYNAMIC;
+    MARK(STRADS_STAGE_SAMPLER);
     HIP_TRY(launch_sampler(h, h->round));
-    if ((rc = mark(h, 1)) != STRADS_OK) return rc;
+    MARK(STRADS_STAGE_CAND_DOTS);
+    if (dynamic) {
+        // every candidate's update from the current residual; the movers; how to tile their Gram
+        HIP_TRY(launch_dots_cand(h));
+        HIP_TRY(launch_movers(h));
+    }
+    MARK(STRADS_STAGE_GRAM_TILES);
     if (dense) HIP_TRY(launch_gram_dense(h, 0)); else HIP_TRY(launch_gram_csc(h));
-    if ((rc = mark(h, 2)) != STRADS_OK) return rc;
+    MARK(STRADS_STAGE_GRAM_MASK);
     if (dense) HIP_TRY(launch_gram_dense(h, 1));
-    if ((rc = mark(h, 3)) != STRADS_OK) return rc;
-    HIP_TRY(launch_filter(h, h->L, true));
-    if ((rc = mark(h, 4)) != STRADS_OK) return rc;
-    if (dense) HIP_TRY(launch_dots_dense(h)); else HIP_TRY(launch_dots_csc(h));
-    if ((rc = mark(h, 5)) != STRADS_OK) return rc;
+    MARK(STRADS_STAGE_FILTER);
+    if (dynamic) HIP_TRY(launch_filter_movers(h)); else HIP_TRY(launch_filter(h, h->L, true));
+    MARK(STRADS_STAGE_UPDATE);
+    if (dynamic) HIP_TRY(launch_commit_dynamic(h));
+    else if (dense) HIP_TRY(launch_dots_dense(h));
+    else HIP_TRY(launch_dots_csc(h));
+    MARK(STRADS_STAGE_RESIDUAL);
     if (dense) HIP_TRY(launch_residual_dense(h)); else HIP_TRY(launch_residual_csc(h));
-    if ((rc = mark(h, 6)) != STRADS_OK) return rc;
+    MARK(STRADS_N_STAGES);
     if (h->profile_level != 0 && h->profiled < h->profile_rounds) h->profiled += 1;
     h->round += 1;
     return STRADS_OK;
@@ -315,7 +341,9 @@ int strads_lasso_last_round(strads_lasso_t *h, int32_t *cand, int32_t *kept_pos,
     if (kept_pos) HIP_TRY(hipMemcpyAsync(kept_pos, h->base + h->ws.kept_pos, lb, hipMemcpyDeviceToDevice, h->stream));
     if (z) HIP_TRY(hipMemcpyAsync(z, h->base + h->ws.z, lb, hipMemcpyDeviceToDevice, h->stream));
     if (delta) HIP_TRY(hipMemcpyAsync(delta, h->base + h->ws.delta, lb, hipMemcpyDeviceToDevice, h->stream));
-    if (gram_or_null)
+    if (gram_or_null && h->cfg.deps == STRADS_DEPS_DYNAMIC)
+        HIP_TRY(launch_scatter_mover_gram(h, gram_or_null));
+    else if (gram_or_null)
         HIP_TRY(hipMemcpy2DAsync(gram_or_null, lb, h->base + h->ws.gram, (size_t)h->Lpad * 4, lb, (size_t)h->L,
                                  hipMemcpyDeviceToDevice, h->stream));
     RoundScalars sc;
@@ -323,6 +351,20 @@ int strads_lasso_last_round(strads_lasso_t *h, int32_t *cand, int32_t *kept_pos,
     if (rs != STRADS_OK) return rs;
     if (n_cand) *n_cand = h->L;
     if (n_kept) *n_kept = sc.n_kept;
+    return STRADS_OK;
+}
+
+int strads_lasso_last_candidates(strads_lasso_t *h, float *z_cand, float *delta_cand, int32_t *n_movers)
+{
+    if (!h) return STRADS_E_INVALID_ARG;
+    if (h->cfg.deps != STRADS_DEPS_DYNAMIC) return STRADS_E_UNSUPPORTED;
+    const size_t lb = (size_t)h->L * 4;
+    if (z_cand) HIP_TRY(hipMemcpyAsync(z_cand, h->base + h->ws.zc, lb, hipMemcpyDeviceToDevice, h->stream));
+    if (delta_cand) HIP_TRY(hipMemcpyAsync(delta_cand, h->base + h->ws.dc, lb, hipMemcpyDeviceToDevice, h->stream));
+    RoundScalars sc;
+    const int rs = read_scalars(h, &sc);
+    if (rs != STRADS_OK) return rs;
+    if (n_movers) *n_movers = sc.n_movers;
     return STRADS_OK;
 }
 
@@ -356,6 +398,7 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
     if (!h || !name) return STRADS_E_INVALID_ARG;
     if (strcmp(name, "gram_split_k") == 0) {
         if (value < 0 || value > h->split_max) return STRADS_E_INVALID_ARG;
+        if (value != 0 && h->cfg.deps == STRADS_DEPS_DYNAMIC) return STRADS_E_UNSUPPORTED;   // chosen on the device
         h->split_user = (int32_t)value;
         return STRADS_OK;
     }
@@ -396,7 +439,7 @@ int strads_lasso_stage_times(strads_lasso_t *h, float *avg_ms, int32_t *rounds_t
     for (int32_t r = 0; r < h->profiled; ++r) {
         hipEvent_t *e = h->events + (size_t)r * kStageEvents;
         for (int s = 0; s < STRADS_N_STAGES; ++s) {
-            if (h->profile_level == 1 && s != 1) continue;
+            if (h->profile_level == 1 && s != STRADS_STAGE_GRAM_TILES) continue;
             float ms = 0.f;
             HIP_TRY(hipEventElapsedTime(&ms, e[s], e[s + 1]));
             sum[s] += ms;

@@ -33,10 +33,17 @@ constexpr int kFilterAhead = 4;                     // chunks whose rows are in 
 // IPT = words of a chunk's 64 rows handled per thread = ceil(64 * W / 1024): 1, 2, 4 or 8.
 template <int kRowWordsPerThread>
 __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__restrict__ mask, int32_t L, int32_t W,
+                                                           const GramShape *__restrict__ gdev,
                                                            int32_t p_max, const int32_t *__restrict__ cand,
                                                            int32_t *kept_pos, int32_t *__restrict__ kept,
-                                                           RoundScalars *__restrict__ sc, int count_updates)
+                                                           RoundScalars *__restrict__ sc, int32_t *__restrict__ n_out,
+                                                           int count_updates)
 {
+    if (gdev) { L = gdev->L; W = gdev->Lpad / 64; }   // dynamic dependencies: the movers, counted on the device
+    if (L <= 0) {                                      // nothing moves this round
+        if (threadIdx.x == 0) *n_out = 0;
+        return;
+    }
     extern __shared__ uint64_t rows[];            // [2][64][W]  (row-major, all W words kept for simplicity)
     __shared__ uint64_t dead[kMaxWords];
     __shared__ uint64_t keptw_s;
@@ -159,22 +166,42 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
     const int32_t nk = nk_s;
     for (int32_t i = tid; i < nk; i += kFilterThreads) kept[i] = cand[kept_pos[i]];
     if (tid == 0) {
-        sc->n_kept = nk;
+        *n_out = nk;
         if (count_updates) sc->updates_total += (unsigned long long)nk;
     }
 }
 
-hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates)
+// Launch for row width W (words); with gdev the kernel takes the actual length and width from
+// device memory (they can only be smaller).
+static hipError_t launch_filter_kernel(strads_lasso *h, int32_t l, int32_t W, const GramShape *gdev, int32_t p_max,
+                                       const int32_t *cand, int32_t *kept_pos, int32_t *kept, int32_t *n_out,
+                                       bool count_updates)
 {
-    const int32_t W = h->Lpad / 64;
     const size_t lds = (size_t)2 * 64 * W * sizeof(uint64_t);
-#define STRADS_FILTER(IPT) hipLaunchKernelGGL(k_filter<IPT>, dim3(1), dim3(kFilterThreads), lds, h->stream, h->at<uint64_t>(h->ws.mask), l, W, h->cfg.p_max, h->at<int32_t>(h->ws.cand), h->at<int32_t>(h->ws.kept_pos), h->at<int32_t>(h->ws.kept), h->at<RoundScalars>(h->ws.scalars), count_updates ? 1 : 0)
+#define STRADS_FILTER(IPT) hipLaunchKernelGGL(k_filter<IPT>, dim3(1), dim3(kFilterThreads), lds, h->stream, h->at<uint64_t>(h->ws.mask), l, W, gdev, p_max, cand, kept_pos, kept, h->at<RoundScalars>(h->ws.scalars), n_out, count_updates ? 1 : 0)
     if (W <= 16) STRADS_FILTER(1);
     else if (W <= 32) STRADS_FILTER(2);
     else if (W <= 64) STRADS_FILTER(4);
     else STRADS_FILTER(8);
 #undef STRADS_FILTER
     return hipGetLastError();
+}
+
+hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates)
+{
+    RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    return launch_filter_kernel(h, l, h->Lpad / 64, nullptr, h->cfg.p_max, h->at<int32_t>(h->ws.cand),
+                                h->at<int32_t>(h->ws.kept_pos), h->at<int32_t>(h->ws.kept), &sc->n_kept, count_updates);
+}
+
+// Dynamic dependencies: the walk runs over the movers only (their conflict mask has the row
+// width of the padded mover count); the cap on |B_1| is applied when the kept set is assembled.
+hipError_t launch_filter_movers(strads_lasso *h)
+{
+    RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    return launch_filter_kernel(h, h->L, h->Lpad / 64, h->at<GramShape>(h->ws.dshape), 0,
+                                h->at<int32_t>(h->ws.mcand), h->at<int32_t>(h->ws.mkept_pos),
+                                h->at<int32_t>(h->ws.kept), &sc->n_mkept, false);
 }
 
 hipError_t filter_prepare()

@@ -69,12 +69,6 @@ __device__ __forceinline__ float4 load_k4(const float *__restrict__ col, int64_t
     }
 }
 
-struct GramShape {
-    int32_t L, Lpad, T;
-    int32_t split_off, split_diag;      // K-slices of an off-diagonal / a diagonal tile
-    int64_t kchunk_off, kchunk_diag;    // rows per slice (multiples of kGramKT)
-};
-
 // store one 32x32 accumulator block: register v of lane (li, lh) holds row 8*(v/4) + 4*lh + (v%4),
 // column li of the block
 __device__ __forceinline__ void store_block(float *__restrict__ out, int32_t Lpad, int row0, int col0,
@@ -321,56 +315,87 @@ __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int6
     }
 }
 
-// grid.x = T(T-1)/2 * split_off + T * split_diag: off-diagonal tiles of the upper triangle first
-// (K-slice fastest), then the diagonal tiles.
+// One job = one (tile, K-slice) pair.  Jobs are numbered with the off-diagonal tiles of the upper
+// triangle first (K-slice fastest), then the diagonal tiles.
+template <bool VEC4>
+__device__ __forceinline__ void gram_job(const float *__restrict__ X, int64_t N, const int32_t *__restrict__ cand,
+                                         const GramShape &g, int32_t job, float *__restrict__ P, float *smem)
+{
+    const int32_t n_off = g.T * (g.T - 1) / 2 * g.split_off;
+    if (job < n_off) {
+        const int32_t s = job % g.split_off;
+        int32_t u = job / g.split_off;          // index into the row-major strict upper triangle
+        int32_t ta = 0;
+        while (u >= g.T - 1 - ta) { u -= g.T - 1 - ta; ++ta; }
+        gram_tile_off<VEC4>(X, N, cand, g, ta, ta + 1 + u, s, P, smem);
+    } else {
+        const int32_t d = job - n_off;
+        gram_tile_diag<VEC4>(X, N, cand, g, d / g.split_diag, d % g.split_diag, P, smem);
+    }
+}
+
+// Static dependencies: the decomposition is known on the host; grid.x = number of jobs.
 template <bool VEC4>
 __global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__ X, int64_t N,
                                                        const int32_t *__restrict__ cand, GramShape g,
                                                        float *__restrict__ P)
 {
     extern __shared__ float smem[];             // [2 stages][A panel | B panel]
-    const int32_t n_off = g.T * (g.T - 1) / 2 * g.split_off;
-    if ((int32_t)blockIdx.x < n_off) {
-        const int32_t s = blockIdx.x % g.split_off;
-        int32_t u = blockIdx.x / g.split_off;   // index into the row-major strict upper triangle
-        int32_t ta = 0;
-        while (u >= g.T - 1 - ta) { u -= g.T - 1 - ta; ++ta; }
-        gram_tile_off<VEC4>(X, N, cand, g, ta, ta + 1 + u, s, P, smem);
-    } else {
-        const int32_t d = blockIdx.x - n_off;
-        gram_tile_diag<VEC4>(X, N, cand, g, d / g.split_diag, d % g.split_diag, P, smem);
+    gram_job<VEC4>(X, N, cand, g, (int32_t)blockIdx.x, P, smem);
+}
+
+// Dynamic dependencies: the Gram of the movers only.  Their number is known on the device alone,
+// so the launch has a fixed number of resident workgroups, which read the decomposition the mover
+// kernel chose and share its jobs round-robin.
+template <bool VEC4>
+__global__ __launch_bounds__(256, 2) void k_gram_tiles_dyn(const float *__restrict__ X, int64_t N,
+                                                           const int32_t *__restrict__ mcand,
+                                                           const GramShape *__restrict__ gdev,
+                                                           float *__restrict__ P)
+{
+    extern __shared__ float smem[];
+    const GramShape g = *gdev;
+    const int32_t total = g.T * (g.T - 1) / 2 * g.split_off + g.T * g.split_diag;
+    for (int32_t job = blockIdx.x; job < total; job += gridDim.x) {
+        gram_job<VEC4>(X, N, mcand, g, job, P, smem);
+        __syncthreads();                        // the next job reuses the LDS panels
     }
 }
 
 // Sum the K-slices in slice order and emit the conflict bits (and, optionally, the fp32 Gram).
 // One thread per (row a, column b) with b in the tiles at or right of a's diagonal tile; 64
-// consecutive b per wavefront make one 64-bit mask word.
-__global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, int32_t split_off,
-                                                   int32_t split_diag, int32_t L, int32_t Lpad, float rho,
+// consecutive b per wavefront make one 64-bit mask word.  gdev != NULL: the shape is read from
+// device memory (dynamic dependencies) and the grid strides over it.
+__global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, GramShape gh,
+                                                   const GramShape *__restrict__ gdev, float rho,
                                                    uint64_t *__restrict__ mask, float *__restrict__ gram,
                                                    int32_t *__restrict__ near_pairs)
 {
-    const int32_t a = blockIdx.y;
-    const int32_t b = blockIdx.x * 256 + threadIdx.x;
-    const int32_t first = (a / kGramTile) * kGramTile;      // first column of a's diagonal tile
-    if (b < first || b >= Lpad) return;                     // uniform per wavefront (both are multiples of 64)
-    const int32_t split = b < first + kGramTile ? split_diag : split_off;
-    float g = 0.f;
+    const GramShape g = gdev ? *gdev : gh;
+    const int32_t L = g.L, Lpad = g.Lpad;
     const int64_t plane = (int64_t)Lpad * Lpad;
-    for (int32_t s = 0; s < split; ++s) g += P[s * plane + (int64_t)a * Lpad + b];
-    const bool live = a < L && b < L && a != b;
-    const float ag = fabsf(g);
-    const bool conflict = live && !(ag < rho);
-    const uint64_t w = __ballot(conflict);
-    if ((threadIdx.x & 63) == 0) mask[(int64_t)a * (Lpad / 64) + (b >> 6)] = w;
-    if (near_pairs) {
-        const bool nr = live && b > a && fabsf(ag - rho) <= 1e-6f;
-        const uint64_t m = __ballot(nr);
-        if (m && (threadIdx.x & 63) == 0) atomicAdd(near_pairs, (int32_t)__popcll(m));
-    }
-    if (gram) {
-        gram[(int64_t)a * Lpad + b] = g;
-        if (b >= first + kGramTile) gram[(int64_t)b * Lpad + a] = g;   // mirror the tiles right of the diagonal
+    for (int32_t a = blockIdx.y; a < Lpad; a += gridDim.y) {
+        const int32_t first = (a / kGramTile) * kGramTile;  // first column of a's diagonal tile
+        for (int32_t b = blockIdx.x * 256 + threadIdx.x; b < Lpad; b += gridDim.x * 256) {
+            if (b < first) continue;                        // uniform per wavefront (both are multiples of 64)
+            const int32_t split = b < first + kGramTile ? g.split_diag : g.split_off;
+            float v = 0.f;
+            for (int32_t s = 0; s < split; ++s) v += P[s * plane + (int64_t)a * Lpad + b];
+            const bool live = a < L && b < L && a != b;
+            const float ag = fabsf(v);
+            const bool conflict = live && !(ag < rho);
+            const uint64_t w = __ballot(conflict);
+            if ((threadIdx.x & 63) == 0) mask[(int64_t)a * (Lpad / 64) + (b >> 6)] = w;
+            if (near_pairs) {
+                const bool nr = live && b > a && fabsf(ag - rho) <= 1e-6f;
+                const uint64_t m = __ballot(nr);
+                if (m && (threadIdx.x & 63) == 0) atomicAdd(near_pairs, (int32_t)__popcll(m));
+            }
+            if (gram) {
+                gram[(int64_t)a * Lpad + b] = v;
+                if (b >= first + kGramTile) gram[(int64_t)b * Lpad + a] = v;   // mirror the tiles right of the diagonal
+            }
+        }
     }
 }
 
@@ -390,7 +415,7 @@ __global__ __launch_bounds__(256) void k_mask_from_gram(const float *__restrict_
 // K-slices of a diagonal tile for a given off-diagonal slice count: the fewest slices whose
 // cost (3/4 of an off-diagonal tile per K stage) exceeds an off-diagonal workgroup's by at most
 // one stage.
-static int diag_split_for(int64_t stages, int split_off)
+__host__ __device__ static inline int diag_split_for(int64_t stages, int split_off)
 {
     const int64_t off_len = (stages + split_off - 1) / split_off;
     int sd = 1;
@@ -398,13 +423,13 @@ static int diag_split_for(int64_t stages, int split_off)
     return sd;
 }
 
-int gram_split_auto(int64_t n, int32_t lpad)
+// Number of K-slices per off-diagonal tile.
+// Workgroups = off-diagonal tiles x K-slices + diagonal tiles x their (fewer) K-slices.  Two
+// workgroups are resident per compute unit (LDS), so the launch runs in rounds of 512.  The cost
+// of a choice, in K stages of an off-diagonal workgroup: rounds x (stages per slice + a fixed
+// prologue/epilogue allowance) + the partial-sum traffic it causes.
+__host__ __device__ static inline int gram_split_choose(int64_t n, int32_t lpad)
 {
-    // Workgroups = off-diagonal tiles x K-slices + diagonal tiles x their (fewer) K-slices.  Two
-    // workgroups are resident per compute unit (LDS), so the launch runs in rounds of 512.  The
-    // cost of a choice, in K stages of an off-diagonal workgroup: rounds x (stages per slice + a
-    // fixed prologue/epilogue allowance) + the partial-sum traffic it causes.  With one tile or
-    // very short K there is nothing to choose.
     const int64_t T = lpad / kGramTile;
     const int64_t stages = (n + kGramKT - 1) / kGramKT;
     const int64_t n_off = T * (T - 1) / 2;
@@ -426,20 +451,26 @@ int gram_split_auto(int64_t n, int32_t lpad)
     return best;
 }
 
-static GramShape gram_shape(const strads_lasso *h)
+int gram_split_auto(int64_t n, int32_t lpad) { return gram_split_choose(n, lpad); }
+
+// L columns over N rows -> tiles, slices and slice lengths.  split_off_wanted = 0: automatic.
+__host__ __device__ static inline GramShape gram_shape_for(int64_t n, int32_t L, int32_t split_off_wanted,
+                                                           int32_t split_cap)
 {
     GramShape g;
-    g.L = h->L;
-    g.Lpad = h->Lpad;
-    g.T = h->Lpad / kGramTile;
-    const int64_t stages = (h->cfg.n + kGramKT - 1) / kGramKT;
-    int32_t so = h->split_user > 0 ? h->split_user : gram_split_auto(h->cfg.n, h->Lpad);
-    if (so > h->split_max) so = h->split_max;
+    g.L = L;
+    g.Lpad = (L + kGramTile - 1) / kGramTile * kGramTile;
+    g.T = g.Lpad / kGramTile;
+    g.pad_ = 0;
+    const int64_t stages = (n + kGramKT - 1) / kGramKT;
+    int32_t so = split_off_wanted > 0 ? split_off_wanted : (g.T > 0 ? gram_split_choose(n, g.Lpad) : 1);
+    if (so > split_cap) so = split_cap;
     if (so > stages) so = (int32_t)stages;
-    int64_t len = (stages + so - 1) / so;
+    if (so < 1) so = 1;
+    const int64_t len = (stages + so - 1) / so;
     so = (int32_t)((stages + len - 1) / len);               // drop empty slices
     int32_t sd = diag_split_for(stages, so);
-    int64_t dlen = (stages + sd - 1) / sd;
+    const int64_t dlen = (stages + sd - 1) / sd;
     sd = (int32_t)((stages + dlen - 1) / dlen);
     g.split_off = so;
     g.split_diag = sd;
@@ -448,16 +479,131 @@ static GramShape gram_shape(const strads_lasso *h)
     return g;
 }
 
+size_t gram_partial_floats(int64_t n, int32_t lpad, bool dynamic)
+{
+    if (!dynamic) return (size_t)gram_split_choose(n, lpad) * lpad * lpad;
+    size_t most = 0;                                        // any mover count up to lpad
+    for (int32_t l = kGramTile; l <= lpad; l += kGramTile) {
+        const size_t need = (size_t)gram_split_choose(n, l) * l * l;
+        if (need > most) most = need;
+    }
+    return most;
+}
+
+static GramShape gram_shape(const strads_lasso *h)
+{
+    return gram_shape_for(h->cfg.n, h->L, h->split_user, h->split_max);
+}
+
+// Dynamic dependencies: list the movers (candidates whose tentative change is not zero) in draw
+// order and look up the decomposition of their Gram.  One workgroup of 1024 threads, 8 consecutive
+// candidate positions per thread (L <= 8192).
+__global__ __launch_bounds__(1024) void k_movers(const float *__restrict__ dc, const int32_t *__restrict__ cand,
+                                                 int32_t L, const GramShape *__restrict__ table,
+                                                 int32_t *__restrict__ mpos, int32_t *__restrict__ mcand,
+                                                 RoundScalars *__restrict__ sc, GramShape *__restrict__ gout)
+{
+    __shared__ uint32_t wtot[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t flags = 0, cnt = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int32_t a = tid * 8 + q;
+        const bool mv = a < L && dc[a] != 0.f;
+        flags |= (mv ? 1u : 0u) << q;
+        cnt += mv ? 1u : 0u;
+    }
+    uint32_t incl = cnt;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t v = __shfl_up(incl, d);
+        if (lane >= d) incl += v;
+    }
+    if (lane == 63) wtot[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) { const uint32_t v = wtot[w]; if (w < wave) before += v; total += v; }
+    uint32_t idx = before + incl - cnt;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        if ((flags >> q) & 1u) {
+            const int32_t a = tid * 8 + q;
+            mpos[idx] = a;
+            mcand[idx] = cand[a];
+            ++idx;
+        }
+    }
+    if (tid == 0) {
+        // the decomposition depends on the mover count only through the number of tiles: the host
+        // tabulated it per tile count when the handle was created
+        GramShape g = table[(total + kGramTile - 1) / kGramTile];
+        g.L = (int32_t)total;
+        sc->n_movers = (int32_t)total;
+        *gout = g;
+    }
+}
+
+void gram_shape_table(int64_t n, int32_t lpad, GramShape *out)
+{
+    for (int32_t t = 0; t <= lpad / kGramTile; ++t) out[t] = gram_shape_for(n, t * kGramTile, 0, 64);
+}
+
+hipError_t launch_movers(strads_lasso *h)
+{
+    hipLaunchKernelGGL(k_movers, dim3(1), dim3(1024), 0, h->stream, h->at<float>(h->ws.dc),
+                       h->at<int32_t>(h->ws.cand), h->L, h->at<GramShape>(h->ws.dtable), h->at<int32_t>(h->ws.mpos),
+                       h->at<int32_t>(h->ws.mcand), h->at<RoundScalars>(h->ws.scalars),
+                       h->at<GramShape>(h->ws.dshape));
+    return hipGetLastError();
+}
+
+// L x L image (row-major) of the mover Gram for parity checks: x_a^T x_b where both candidate
+// positions a and b are movers, 0 elsewhere.
+__global__ __launch_bounds__(256) void k_scatter_mover_gram(const float *__restrict__ gram,
+                                                            const GramShape *__restrict__ gdev,
+                                                            const int32_t *__restrict__ mpos, int32_t L,
+                                                            float *__restrict__ out)
+{
+    const int32_t m = gdev->L, Lpad = gdev->Lpad;
+    for (int32_t i = blockIdx.y; i < m; i += gridDim.y)
+        for (int32_t k = blockIdx.x * 256 + threadIdx.x; k < m; k += gridDim.x * 256)
+            out[(int64_t)mpos[i] * L + mpos[k]] = gram[(int64_t)i * Lpad + k];
+}
+
+hipError_t launch_scatter_mover_gram(strads_lasso *h, float *out)
+{
+    hipError_t e = hipMemsetAsync(out, 0, (size_t)h->L * h->L * 4, h->stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_scatter_mover_gram, dim3(4, 1024), dim3(256), 0, h->stream, h->at<float>(h->ws.gram),
+                       h->at<GramShape>(h->ws.dshape), h->at<int32_t>(h->ws.mpos), h->L, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_gram_dense(strads_lasso *h, int part)
 {
+    const bool dynamic = h->cfg.deps == STRADS_DEPS_DYNAMIC;
     const GramShape g = gram_shape(h);
+    const GramShape *gdev = dynamic ? h->at<GramShape>(h->ws.dshape) : nullptr;
     const size_t lds = 2 * 2 * kPanel * sizeof(float);
     float *P = h->at<float>(h->ws.partial);
     if (part == 1) {
         RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
-        hipLaunchKernelGGL(k_gram_mask, dim3((h->Lpad + 255) / 256, h->Lpad), dim3(256), 0, h->stream, P,
-                           g.split_off, g.split_diag, h->L, h->Lpad, h->cfg.rho, h->at<uint64_t>(h->ws.mask),
-                           h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr, &sc->near_rho_pairs);
+        dim3 grid((h->Lpad + 255) / 256, h->Lpad);
+        if (dynamic) { if (grid.x > 4) grid.x = 4; if (grid.y > 1024) grid.y = 1024; }
+        hipLaunchKernelGGL(k_gram_mask, grid, dim3(256), 0, h->stream, P, g, gdev, h->cfg.rho,
+                           h->at<uint64_t>(h->ws.mask), h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr,
+                           &sc->near_rho_pairs);
+        return hipGetLastError();
+    }
+    if (dynamic) {
+        const int32_t *mcand = h->at<int32_t>(h->ws.mcand);
+        if (h->vec4)
+            hipLaunchKernelGGL(k_gram_tiles_dyn<true>, dim3(kGramSlots), dim3(256), lds, h->stream, h->cfg.x,
+                               h->cfg.n, mcand, gdev, P);
+        else
+            hipLaunchKernelGGL(k_gram_tiles_dyn<false>, dim3(kGramSlots), dim3(256), lds, h->stream, h->cfg.x,
+                               h->cfg.n, mcand, gdev, P);
         return hipGetLastError();
     }
     const dim3 grid((unsigned)(g.T * (g.T - 1) / 2 * g.split_off + g.T * g.split_diag));
@@ -482,9 +628,13 @@ hipError_t gram_prepare()
     const int lds = 2 * 2 * kPanel * (int)sizeof(float);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gram_tiles<true>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_gram_tiles<false>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gram_tiles<false>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gram_tiles_dyn<true>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gram_tiles_dyn<false>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    return e;
 }
 
 } // namespace strads

@@ -31,6 +31,17 @@ struct RoundScalars {
     float max_abs_delta;
     uint32_t kkt_max_bits; // float bits of the running max violation (>= 0, so uint order = float order)
     uint32_t bad_input;    // set by the create-time check of a CSC design
+    int32_t n_movers;      // dynamic dependencies: candidates whose update is not zero
+    int32_t n_mkept;       // dynamic dependencies: movers that passed the filter
+};
+
+// Decomposition of a candidate Gram into workgroup jobs (see gram.hip).  With dynamic
+// dependencies it is chosen on the device from the number of movers.
+struct GramShape {
+    int32_t L, Lpad, T;                 // columns, padded to the tile, tiles per side
+    int32_t split_off, split_diag;      // K-slices of an off-diagonal / a diagonal tile
+    int32_t pad_;
+    int64_t kchunk_off, kchunk_diag;    // rows per slice (multiples of kGramKT)
 };
 
 struct Workspace {
@@ -52,6 +63,12 @@ struct Workspace {
     size_t rpart;           // float [kMaxResidualGroups][Npad]
     size_t objpart;         // double [kObjBlocks]
     size_t objout;          // double [1]
+    // dynamic dependencies (per candidate position, then per mover)
+    size_t zc, dc, nbc;     // float [Lpad]: x_j^T r, tentative change, tentative new beta
+    size_t mpos, mcand;     // int32 [Lpad]: candidate position / column id of each mover, draw order
+    size_t mkept_pos;       // int32 [Lpad]: positions into the mover list that passed the filter
+    size_t dshape;          // GramShape of the current round's movers
+    size_t dtable;          // GramShape [STRADS_MAX_L_PRIME / kGramTile + 1], by number of tiles per side
     size_t csc_scratch;     // CSC only: see csc.hip
     size_t csc_scratch_bytes;
     size_t total;
@@ -77,6 +94,7 @@ struct strads_lasso {
     int32_t profile_rounds;  // rounds the event pool can hold
     int32_t profiled;        // rounds recorded so far
     hipEvent_t *events;      // [profile_rounds][kStageEvents]
+    strads::GramShape shape_table[STRADS_MAX_L_PRIME / strads::kGramTile + 1];   // host copy of ws.dtable
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(base + off); }
 };
@@ -84,7 +102,9 @@ struct strads_lasso {
 namespace strads {
 
 int gram_split_auto(int64_t n, int32_t lpad);
-Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram, int32_t max_col_nnz);
+size_t gram_partial_floats(int64_t n, int32_t lpad, bool dynamic);   // floats of K-slice partial tiles to reserve
+void gram_shape_table(int64_t n, int32_t lpad, GramShape *out);      // out[t], t = 0 .. lpad/kGramTile
+Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram, int32_t max_col_nnz, int32_t deps);
 
 // Each launcher enqueues on h->stream and returns the hipError_t of the launch.
 hipError_t launch_sampler(strads_lasso *h, int64_t round);                 // Step 1 -> cand[L]
@@ -92,6 +112,12 @@ hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys);  // st
 hipError_t launch_gram_dense(strads_lasso *h, int part);  // Step 2a; part 0: K-slice tiles, part 1: sum + conflict mask
 hipError_t launch_mask_from_gram(strads_lasso *h, const float *gram, int32_t l);
 hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates);                    // Step 2b -> kept_pos, kept, n_kept
+// dynamic dependencies
+hipError_t launch_dots_cand(strads_lasso *h);             // x_j^T r and tentative change of every candidate
+hipError_t launch_movers(strads_lasso *h);                // mover list + Gram decomposition for it
+hipError_t launch_filter_movers(strads_lasso *h);         // greedy walk over the movers -> mkept_pos, n_mkept
+hipError_t launch_commit_dynamic(strads_lasso *h);        // B_1 = non-movers + kept movers; beta, delta beta
+hipError_t launch_scatter_mover_gram(strads_lasso *h, float *out);   // L x L image of the mover Gram
 hipError_t launch_dots_dense(strads_lasso *h);                             // x_j^T r for the kept set + eq. (2) update
 hipError_t launch_residual_dense(strads_lasso *h);                         // r -= X_B delta_B
 hipError_t launch_objective(strads_lasso *h);                              // -> objout

@@ -96,6 +96,93 @@ __global__ __launch_bounds__(256) void k_dots_update(const float *__restrict__ X
     }
 }
 
+// Dynamic dependencies: the update every candidate would make from the current residual.  For
+// candidate position c < L: zc[c] = x_j^T r, nbc[c] = S(zc + beta_j, lambda), dc[c] = nbc - beta_j.
+// Nothing of the solver state is written: which candidates are committed is decided later.
+template <int TPC, bool VEC4>
+__global__ __launch_bounds__(256) void k_dots_cand(const float *__restrict__ X, int64_t N,
+                                                   const int32_t *__restrict__ cand, int32_t L,
+                                                   const float *__restrict__ r, float lambda,
+                                                   const float *__restrict__ beta, float *__restrict__ zc,
+                                                   float *__restrict__ dc, float *__restrict__ nbc)
+{
+    __shared__ float red[4];
+    constexpr int CPB = 256 / TPC;
+    const int c = blockIdx.x * CPB + threadIdx.x / TPC;
+    if (c >= L) return;
+    const int32_t j = cand[c];
+    const float s = column_dot<TPC, VEC4>(X + (int64_t)j * N, r, N, threadIdx.x % TPC, red);
+    if (threadIdx.x % TPC == 0) {
+        const float b = beta[j];
+        const float nb = soft_threshold(s + b, lambda);
+        zc[c] = s;
+        nbc[c] = nb;
+        dc[c] = nb - b;
+    }
+}
+
+// Dynamic dependencies: assemble B_1 = (candidates that do not move) + (movers that passed the
+// filter), in draw order, cut at the cap, and commit it: beta_j <- its tentative value,
+// delta beta_j <- |change| (0 for a kept candidate that does not move).  One workgroup of 1024
+// threads, 8 consecutive candidate positions per thread.
+__global__ __launch_bounds__(1024) void k_commit_dynamic(const int32_t *__restrict__ cand, int32_t L, int32_t p_max,
+                                                         const float *__restrict__ zc, const float *__restrict__ dc,
+                                                         const float *__restrict__ nbc,
+                                                         const int32_t *__restrict__ mpos,
+                                                         const int32_t *__restrict__ mkept_pos,
+                                                         RoundScalars *__restrict__ sc, float *__restrict__ beta,
+                                                         float *__restrict__ dbeta, int32_t *__restrict__ kept_pos,
+                                                         int32_t *__restrict__ kept, float *__restrict__ z,
+                                                         float *__restrict__ delta)
+{
+    __shared__ uint8_t keep[STRADS_MAX_L_PRIME];
+    __shared__ uint32_t wtot[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int32_t cap = p_max > 0 ? p_max : L;
+    for (int32_t a = tid; a < L; a += 1024) keep[a] = dc[a] == 0.f ? 1 : 0;
+    __syncthreads();
+    const int32_t nmk = sc->n_mkept;
+    for (int32_t i = tid; i < nmk; i += 1024) keep[mpos[mkept_pos[i]]] = 1;
+    __syncthreads();
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { const int32_t a = tid * 8 + q; cnt += (a < L && keep[a]) ? 1u : 0u; }
+    uint32_t incl = cnt;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t v = __shfl_up(incl, d);
+        if (lane >= d) incl += v;
+    }
+    if (lane == 63) wtot[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) { const uint32_t v = wtot[w]; if (w < wave) before += v; total += v; }
+    int32_t idx = (int32_t)(before + incl - cnt);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int32_t a = tid * 8 + q;
+        if (a < L && keep[a]) {
+            if (idx < cap) {
+                const int32_t j = cand[a];
+                const float d = dc[a];
+                kept_pos[idx] = a;
+                kept[idx] = j;
+                z[idx] = zc[a];
+                delta[idx] = d;
+                beta[j] = nbc[a];
+                dbeta[j] = fabsf(d);
+            }
+            ++idx;
+        }
+    }
+    if (tid == 0) {
+        const int32_t nk = (int32_t)total < cap ? (int32_t)total : cap;
+        sc->n_kept = nk;
+        sc->updates_total += (unsigned long long)nk;
+    }
+}
+
 // Residual update r <- r - sum_c x_{kept[c]} * delta[c], stage 1.  grid = (row tiles of 1024 rows,
 // G column groups).  Group g owns kept positions [k*g/G, k*(g+1)/G) and sums its movers
 // (delta != 0) in list order for 4 rows per thread -> part[g][i].
@@ -349,6 +436,28 @@ hipError_t launch_dots_dense(strads_lasso *h)
     if (wide) { if (h->vec4) STRADS_DOTS(256, true); else STRADS_DOTS(256, false); }
     else      { if (h->vec4) STRADS_DOTS(64, true);  else STRADS_DOTS(64, false); }
 #undef STRADS_DOTS
+    return hipGetLastError();
+}
+
+hipError_t launch_dots_cand(strads_lasso *h)
+{
+    const bool wide = h->cfg.n > 2048;
+    const unsigned grid = wide ? (unsigned)h->L : (unsigned)((h->L + 3) / 4);
+#define STRADS_DOTS_CAND(TPC, V) hipLaunchKernelGGL((k_dots_cand<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), h->L, h->at<float>(h->ws.r), h->cfg.lambda, h->at<float>(h->ws.beta), h->at<float>(h->ws.zc), h->at<float>(h->ws.dc), h->at<float>(h->ws.nbc))
+    if (wide) { if (h->vec4) STRADS_DOTS_CAND(256, true); else STRADS_DOTS_CAND(256, false); }
+    else      { if (h->vec4) STRADS_DOTS_CAND(64, true);  else STRADS_DOTS_CAND(64, false); }
+#undef STRADS_DOTS_CAND
+    return hipGetLastError();
+}
+
+hipError_t launch_commit_dynamic(strads_lasso *h)
+{
+    hipLaunchKernelGGL(k_commit_dynamic, dim3(1), dim3(1024), 0, h->stream, h->at<int32_t>(h->ws.cand), h->L,
+                       h->cfg.p_max, h->at<float>(h->ws.zc), h->at<float>(h->ws.dc), h->at<float>(h->ws.nbc),
+                       h->at<int32_t>(h->ws.mpos), h->at<int32_t>(h->ws.mkept_pos),
+                       h->at<RoundScalars>(h->ws.scalars), h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta),
+                       h->at<int32_t>(h->ws.kept_pos), h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.z),
+                       h->at<float>(h->ws.delta));
     return hipGetLastError();
 }
 
