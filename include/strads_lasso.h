@@ -69,6 +69,15 @@ extern "C" {
                                         current residual is zero) has no dependency with anyone;
                                         d(a,b) = |x_a^T x_b| only between two candidates that both move.
                                         The Gram and the greedy walk then run over the movers only. */
+#define STRADS_DEPS_NONE          2  /* no dependency check: the first p_max candidates of the draw (all of
+                                        them if p_max = 0) are updated together.  With the uniform priority
+                                        this is the Shotgun scheduler Section 5.1 compares against. */
+
+/* Priority of Step 1: the draw takes coordinate j with probability proportional to */
+#define STRADS_PRIORITY_SQUARED   0  /* (delta beta_j)^2 + eta   (Theorem 1) */
+#define STRADS_PRIORITY_LINEAR    1  /* |delta beta_j| + eta     (Algorithm 1 and Step 1 as printed) */
+#define STRADS_PRIORITY_UNIFORM   2  /* 1: no priority.  With STRADS_DEPS_STATIC this is the "static
+                                        correlation" scheduler of Section 5.1. */
 
 typedef struct strads_lasso strads_lasso_t;   /* opaque, host side */
 
@@ -93,6 +102,7 @@ typedef struct {
     int32_t        max_col_nnz;   /* CSC only: an upper bound (>= 1) on the nonzeros of any column;
                                      sizes the per-round inverted index; checked at create */
     int32_t        deps;          /* STRADS_DEPS_*: dependency rule of Step 2 (dynamic: dense designs only) */
+    int32_t        priority;      /* STRADS_PRIORITY_*: weight of Step 1's draw */
     void          *workspace;     /* DEVICE, 256-byte aligned, caller-allocated */
     size_t         workspace_bytes;
     void          *stream;        /* hipStream_t owned by the caller (NULL = the default stream) */

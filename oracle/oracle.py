@@ -33,7 +33,11 @@ def build(force: bool = False) -> str:
 class _Problem(C.Structure):
     _fields_ = [("N", C.c_int64), ("J", C.c_int64), ("X", C.c_void_p), ("row_idx", C.c_void_p),
                 ("col_ptr", C.c_void_p), ("lam", C.c_float), ("rho", C.c_float), ("eta", C.c_float),
-                ("l_prime", C.c_int32), ("p_max", C.c_int32), ("seed", C.c_uint64)]
+                ("l_prime", C.c_int32), ("p_max", C.c_int32), ("seed", C.c_uint64),
+                ("priority", C.c_int32), ("deps", C.c_int32)]
+
+
+PRIORITY = {"squared": 0, "linear": 1, "uniform": 2}
 
 
 def lib():
@@ -52,6 +56,10 @@ def lib():
         L.oracle_priority_key.restype = f32
         L.oracle_priority_keys.argtypes = [i64, vp, f32, u64, u64, vp]
         L.oracle_priority_keys.restype = None
+        L.oracle_priority_keys_mode.argtypes = [i64, vp, f32, u64, u64, i32, vp]
+        L.oracle_priority_keys_mode.restype = None
+        L.oracle_priority_weight.argtypes = [f32, f32, i32]
+        L.oracle_priority_weight.restype = f32
         L.oracle_draw.argtypes = [i64, vp, i32, vp]
         L.oracle_draw.restype = i32
         L.oracle_gram_dense.argtypes = [i64, vp, vp, i32, vp]
@@ -114,10 +122,10 @@ def log2_spec(x: float) -> float:
     return float(lib().oracle_log2_spec(np.float32(x)))
 
 
-def priority_keys(dbeta, eta, seed, t) -> np.ndarray:
+def priority_keys(dbeta, eta, seed, t, priority="squared") -> np.ndarray:
     d = _arr(dbeta, np.float32)
     keys = np.empty(d.shape[0], np.float32)
-    lib().oracle_priority_keys(d.shape[0], _p(d), np.float32(eta), seed, t, _p(keys))
+    lib().oracle_priority_keys_mode(d.shape[0], _p(d), np.float32(eta), seed, t, PRIORITY[priority], _p(keys))
     return keys
 
 
@@ -169,8 +177,12 @@ class OracleLasso:
     (row j = covariate j).  CSC: pass values,row_idx,col_ptr and n."""
 
     def __init__(self, y, lam, rho, eta, l_prime, seed=0, p_max=0, c_init=1e6, x=None,
-                 values=None, row_idx=None, col_ptr=None, n=None, dynamic=False):
+                 values=None, row_idx=None, col_ptr=None, n=None, dynamic=False, priority="squared",
+                 no_deps=False):
         self.dynamic = bool(dynamic)          # update-aware dependencies (oracle_round_dynamic)
+        self.priority = priority              # "squared" | "linear" | "uniform"
+        self.no_deps = bool(no_deps)          # skip Step 2 (Shotgun)
+        assert not (self.dynamic and self.no_deps)
         self.y = _arr(y, np.float32)
         if x is not None:
             self.x = _arr(x, np.float32)
@@ -192,7 +204,8 @@ class OracleLasso:
         self.r = self.y.copy()
         self.t = 0
         self._prob = _Problem(self.N, self.J, _p(self.x), _p(self.row_idx), _p(self.col_ptr),
-                              self.lam, self.rho, self.eta, self.l_prime, self.p_max, self.seed)
+                              self.lam, self.rho, self.eta, self.l_prime, self.p_max, self.seed,
+                              PRIORITY[priority], 2 if self.no_deps else (1 if self.dynamic else 0))
 
     def set_state(self, beta, dbeta, r, t):
         self.beta[:] = beta

@@ -118,11 +118,37 @@ float oracle_priority_key(float dbeta, float eta, uint64_t seed, uint64_t t, uin
     return oracle_log2_spec(w) - oracle_log2_spec(e);
 }
 
-void oracle_priority_keys(int64_t J, const float *dbeta, float eta, uint64_t seed, uint64_t t, float *keys)
+/* The weight of coordinate j under the three priorities the paper names:
+ *   0  (delta beta_j)^2 + eta    Theorem 1 (the one this build's rounds use by default)
+ *   1  |delta beta_j| + eta      Algorithm 1 and Step 1 as printed
+ *   2  1                         no priority: the uniform draw of the comparison
+ *                                schedulers of Section 5.1 (static correlation, Shotgun) */
+float oracle_priority_weight(float dbeta, float eta, int32_t priority)
+{
+    if (priority == 1) return fabsf(dbeta) + eta;
+    if (priority == 2) return 1.0f;
+    return fmaf(dbeta, dbeta, eta);
+}
+
+float oracle_priority_key_mode(float dbeta, float eta, uint64_t seed, uint64_t t, uint64_t j, int32_t priority)
+{
+    float w = oracle_priority_weight(dbeta, eta, priority);
+    float u = oracle_uniform(seed, t, j);
+    float e = -oracle_log2_spec(u);
+    return oracle_log2_spec(w) - oracle_log2_spec(e);
+}
+
+void oracle_priority_keys_mode(int64_t J, const float *dbeta, float eta, uint64_t seed, uint64_t t,
+                               int32_t priority, float *keys)
 {
 #pragma omp parallel for schedule(static)
     for (int64_t j = 0; j < J; ++j)
-        keys[j] = oracle_priority_key(dbeta[j], eta, seed, t, (uint64_t)j);
+        keys[j] = oracle_priority_key_mode(dbeta[j], eta, seed, t, (uint64_t)j, priority);
+}
+
+void oracle_priority_keys(int64_t J, const float *dbeta, float eta, uint64_t seed, uint64_t t, float *keys)
+{
+    oracle_priority_keys_mode(J, dbeta, eta, seed, t, 0, keys);
 }
 
 typedef struct { float key; int32_t j; } keyed_t;
@@ -352,6 +378,10 @@ typedef struct {
     float lambda, rho, eta;
     int32_t l_prime, p_max;
     uint64_t seed;
+    int32_t priority;          /* see oracle_priority_weight */
+    int32_t deps;              /* 0: Algorithm 1's dependency check; 2: none (every candidate is
+                                  dispatched, up to p_max: the Shotgun scheduler of Section 5.1).
+                                  1 is oracle_round_dynamic's rule and is not read here. */
 } oracle_problem_t;
 
 int32_t oracle_round(const oracle_problem_t *p, uint64_t t, float *beta, float *dbeta, float *r,
@@ -367,7 +397,7 @@ int32_t oracle_round(const oracle_problem_t *p, uint64_t t, float *beta, float *
     } else {
         float *keys = (float *)malloc((size_t)(p->J > 0 ? p->J : 1) * sizeof(float));
         if (!keys) return -1;
-        oracle_priority_keys(p->J, dbeta, p->eta, p->seed, t, keys);
+        oracle_priority_keys_mode(p->J, dbeta, p->eta, p->seed, t, p->priority, keys);
         L = oracle_draw(p->J, keys, p->l_prime, cand);
         free(keys);
         if (L < 0) return -1;
@@ -375,7 +405,12 @@ int32_t oracle_round(const oracle_problem_t *p, uint64_t t, float *beta, float *
     *n_cand_out = L;
 
     int32_t k;
-    if (forced_kept_pos && !G_out) {
+    if (p->deps == 2 && !forced_kept_pos) {
+        /* no dependency check: the first p_max candidates (all of them without a cap) */
+        k = (p->p_max > 0 && p->p_max < L) ? p->p_max : L;
+        for (int32_t a = 0; a < k; ++a) kept_pos[a] = a;
+        if (G_out) memset(G_out, 0, (size_t)L * (size_t)L * sizeof(float));
+    } else if (forced_kept_pos && !G_out) {
         k = forced_n_kept;
         memcpy(kept_pos, forced_kept_pos, (size_t)k * sizeof(int32_t));
     } else {
@@ -448,7 +483,7 @@ int32_t oracle_round_dynamic(const oracle_problem_t *p, uint64_t t, float *beta,
     } else {
         float *keys = (float *)malloc((size_t)(p->J > 0 ? p->J : 1) * sizeof(float));
         if (!keys) return -1;
-        oracle_priority_keys(p->J, dbeta, p->eta, p->seed, t, keys);
+        oracle_priority_keys_mode(p->J, dbeta, p->eta, p->seed, t, p->priority, keys);
         L = oracle_draw(p->J, keys, p->l_prime, cand);
         free(keys);
         if (L < 0) return -1;

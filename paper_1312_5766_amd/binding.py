@@ -22,7 +22,8 @@ LAYOUT_DENSE, LAYOUT_CSC = 0, 1
 MAX_L_PRIME = 8192
 N_STAGES = 7
 STAGE_NAMES = ["sampler", "cand_dots", "gram_tiles", "gram_mask", "filter", "update", "residual"]
-DEPS_STATIC, DEPS_DYNAMIC = 0, 1
+DEPS_STATIC, DEPS_DYNAMIC, DEPS_NONE = 0, 1, 2
+PRIORITY = {"squared": 0, "linear": 1, "uniform": 2}
 
 EXPORTS = [
     "strads_lasso_workspace_bytes", "strads_lasso_create", "strads_lasso_round", "strads_lasso_run",
@@ -37,7 +38,7 @@ class Config(C.Structure):
                 ("row_idx", C.c_void_p), ("col_ptr", C.c_void_p), ("y", C.c_void_p),
                 ("lam", C.c_float), ("rho", C.c_float), ("eta", C.c_float), ("c_init", C.c_float),
                 ("l_prime", C.c_int32), ("p_max", C.c_int32), ("seed", C.c_uint64), ("keep_gram", C.c_int32),
-                ("max_col_nnz", C.c_int32), ("deps", C.c_int32), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
+                ("max_col_nnz", C.c_int32), ("deps", C.c_int32), ("priority", C.c_int32), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
 
 
 class RoundInfo(C.Structure):
@@ -119,7 +120,8 @@ class StradsLasso:
                  x: Optional[torch.Tensor] = None, values: Optional[torch.Tensor] = None,
                  row_idx: Optional[torch.Tensor] = None, col_ptr: Optional[torch.Tensor] = None,
                  n: Optional[int] = None, max_col_nnz: Optional[int] = None,
-                 stream: Optional[torch.cuda.Stream] = None, dynamic: bool = False):
+                 stream: Optional[torch.cuda.Stream] = None, dynamic: bool = False, priority: str = "squared",
+                 no_deps: bool = False):
         lib = load()
         self._h = None
         dev = y.device
@@ -145,7 +147,8 @@ class StradsLasso:
                      row_idx=_ptr(row_idx), col_ptr=_ptr(col_ptr), y=_ptr(y), lam=lam, rho=rho, eta=eta,
                      c_init=c_init, l_prime=int(l_prime), p_max=int(p_max), seed=int(seed),
                      keep_gram=int(keep_gram), max_col_nnz=int(max_col_nnz or 0),
-                     deps=DEPS_DYNAMIC if dynamic else DEPS_STATIC, stream=self.stream.cuda_stream)
+                     deps=DEPS_NONE if no_deps else (DEPS_DYNAMIC if dynamic else DEPS_STATIC),
+                     priority=PRIORITY[priority], stream=self.stream.cuda_stream)
         nbytes = int(lib.strads_lasso_workspace_bytes(C.byref(cfg)))
         if nbytes == 0:
             raise StradsError(E_INVALID_ARG, "strads_lasso_workspace_bytes")

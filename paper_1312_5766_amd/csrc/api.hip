@@ -64,7 +64,9 @@ static bool sizes_ok(const strads_lasso_config_t *c)
     if (c->layout != STRADS_LAYOUT_DENSE_COLMAJOR && c->layout != STRADS_LAYOUT_CSC) return false;
     if (c->l_prime < 1 || c->l_prime > STRADS_MAX_L_PRIME) return false;
     if (c->layout == STRADS_LAYOUT_CSC && (c->n >= (int64_t)1 << 31 || c->max_col_nnz < 1)) return false;
-    if (c->deps != STRADS_DEPS_STATIC && c->deps != STRADS_DEPS_DYNAMIC) return false;
+    if (c->deps != STRADS_DEPS_STATIC && c->deps != STRADS_DEPS_DYNAMIC && c->deps != STRADS_DEPS_NONE) return false;
+    if (c->priority != STRADS_PRIORITY_SQUARED && c->priority != STRADS_PRIORITY_LINEAR &&
+        c->priority != STRADS_PRIORITY_UNIFORM) return false;
     return true;
 }
 
@@ -181,6 +183,7 @@ static int enqueue_round(strads_lasso *h)
 {
     const bool dense = h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR;
     const bool dynamic = h->cfg.deps == STRADS_DEPS_DYNAMIC;
+    const bool unchecked = h->cfg.deps == STRADS_DEPS_NONE;
     MARK(STRADS_STAGE_SAMPLER);
     HIP_TRY(launch_sampler(h, h->round));
     MARK(STRADS_STAGE_CAND_DOTS);
@@ -190,11 +193,13 @@ static int enqueue_round(strads_lasso *h)
         HIP_TRY(launch_movers(h));
     }
     MARK(STRADS_STAGE_GRAM_TILES);
-    if (dense) HIP_TRY(launch_gram_dense(h, 0)); else HIP_TRY(launch_gram_csc(h));
+    if (!unchecked) { if (dense) HIP_TRY(launch_gram_dense(h, 0)); else HIP_TRY(launch_gram_csc(h)); }
     MARK(STRADS_STAGE_GRAM_MASK);
-    if (dense) HIP_TRY(launch_gram_dense(h, 1));
+    if (!unchecked && dense) HIP_TRY(launch_gram_dense(h, 1));
     MARK(STRADS_STAGE_FILTER);
-    if (dynamic) HIP_TRY(launch_filter_movers(h)); else HIP_TRY(launch_filter(h, h->L, true));
+    if (unchecked) HIP_TRY(launch_keep_all(h));
+    else if (dynamic) HIP_TRY(launch_filter_movers(h));
+    else HIP_TRY(launch_filter(h, h->L, true));
     MARK(STRADS_STAGE_UPDATE);
     if (dynamic) HIP_TRY(launch_commit_dynamic(h));
     else if (dense) HIP_TRY(launch_dots_dense(h));
@@ -335,7 +340,7 @@ int strads_lasso_last_round(strads_lasso_t *h, int32_t *cand, int32_t *kept_pos,
                             float *gram_or_null, int32_t *n_cand, int32_t *n_kept)
 {
     if (!h) return STRADS_E_INVALID_ARG;
-    if (gram_or_null && !h->cfg.keep_gram) return STRADS_E_INVALID_ARG;
+    if (gram_or_null && (!h->cfg.keep_gram || h->cfg.deps == STRADS_DEPS_NONE)) return STRADS_E_INVALID_ARG;
     const size_t lb = (size_t)h->L * 4;
     if (cand) HIP_TRY(hipMemcpyAsync(cand, h->base + h->ws.cand, lb, hipMemcpyDeviceToDevice, h->stream));
     if (kept_pos) HIP_TRY(hipMemcpyAsync(kept_pos, h->base + h->ws.kept_pos, lb, hipMemcpyDeviceToDevice, h->stream));

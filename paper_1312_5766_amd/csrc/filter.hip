@@ -204,6 +204,30 @@ hipError_t launch_filter_movers(strads_lasso *h)
                                 h->at<int32_t>(h->ws.kept), &sc->n_mkept, false);
 }
 
+// No dependency check (the Shotgun scheduler of Section 5.1): B_1 is the head of the draw.
+__global__ __launch_bounds__(256) void k_keep_all(const int32_t *__restrict__ cand, int32_t L, int32_t p_max,
+                                                  int32_t *__restrict__ kept_pos, int32_t *__restrict__ kept,
+                                                  RoundScalars *__restrict__ sc)
+{
+    const int32_t k = (p_max > 0 && p_max < L) ? p_max : L;
+    for (int32_t i = blockIdx.x * 256 + threadIdx.x; i < k; i += gridDim.x * 256) {
+        kept_pos[i] = i;
+        kept[i] = cand[i];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        sc->n_kept = k;
+        sc->updates_total += (unsigned long long)k;
+    }
+}
+
+hipError_t launch_keep_all(strads_lasso *h)
+{
+    hipLaunchKernelGGL(k_keep_all, dim3((h->L + 255) / 256), dim3(256), 0, h->stream, h->at<int32_t>(h->ws.cand),
+                       h->L, h->cfg.p_max, h->at<int32_t>(h->ws.kept_pos), h->at<int32_t>(h->ws.kept),
+                       h->at<RoundScalars>(h->ws.scalars));
+    return hipGetLastError();
+}
+
 hipError_t filter_prepare()
 {
     const int lds = 2 * 64 * kMaxWords * (int)sizeof(uint64_t);

@@ -59,9 +59,19 @@ __device__ __forceinline__ float log2_spec(float x)
     return __fmaf_rn(f, q, (float)e);
 }
 
-__device__ __forceinline__ float priority_key(float dbeta, float eta, uint64_t seed, uint64_t t, uint32_t j)
+// weight of coordinate j in the draw: (delta beta)^2 + eta (Theorem 1), |delta beta| + eta
+// (Algorithm 1 as printed) or 1 (the uniform draw of the comparison schedulers of Section 5.1)
+__device__ __forceinline__ float priority_weight(float dbeta, float eta, int priority)
 {
-    const float w = __fmaf_rn(dbeta, dbeta, eta);
+    if (priority == STRADS_PRIORITY_LINEAR) return __fadd_rn(fabsf(dbeta), eta);
+    if (priority == STRADS_PRIORITY_UNIFORM) return 1.0f;
+    return __fmaf_rn(dbeta, dbeta, eta);
+}
+
+__device__ __forceinline__ float priority_key(float dbeta, float eta, uint64_t seed, uint64_t t, uint32_t j,
+                                              int priority)
+{
+    const float w = priority_weight(dbeta, eta, priority);
     const uint32_t x = philox4x32_10_word0(j, 0u, (uint32_t)t, (uint32_t)(t >> 32), (uint32_t)seed,
                                            (uint32_t)(seed >> 32));
     const float u = __fmul_rn((float)(2u * (x >> 9) + 1u), 0x1.0p-24f);   // odd multiple of 2^-24, exact
@@ -134,14 +144,14 @@ __device__ __forceinline__ void wave_append(bool flag, uint64_t item, uint64_t *
 // pass 1: keys + histogram of the top 11 bits
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_keys_hist(const float *__restrict__ dbeta, uint32_t J, float eta,
-                                                   uint64_t seed, uint64_t t, uint32_t *__restrict__ keys,
-                                                   uint32_t *__restrict__ hist0)
+                                                   uint64_t seed, uint64_t t, int priority,
+                                                   uint32_t *__restrict__ keys, uint32_t *__restrict__ hist0)
 {
     __shared__ uint32_t lh[kHistBins];
     for (int i = threadIdx.x; i < kHistBins; i += 256) lh[i] = 0;
     __syncthreads();
     for (uint32_t j = blockIdx.x * 256u + threadIdx.x; j < J; j += gridDim.x * 256u) {
-        const uint32_t ok = orderable(priority_key(dbeta[j], eta, seed, t, j));
+        const uint32_t ok = orderable(priority_key(dbeta[j], eta, seed, t, j, priority));
         keys[j] = ok;
         atomicAdd(&lh[ok >> 21], 1u);
     }
@@ -151,10 +161,11 @@ __global__ __launch_bounds__(256) void k_keys_hist(const float *__restrict__ dbe
 }
 
 __global__ __launch_bounds__(256) void k_keys_only(const float *__restrict__ dbeta, uint32_t J, float eta,
-                                                   uint64_t seed, uint64_t t, float *__restrict__ keys)
+                                                   uint64_t seed, uint64_t t, int priority,
+                                                   float *__restrict__ keys)
 {
     for (uint32_t j = blockIdx.x * 256u + threadIdx.x; j < J; j += gridDim.x * 256u)
-        keys[j] = priority_key(dbeta[j], eta, seed, t, j);
+        keys[j] = priority_key(dbeta[j], eta, seed, t, j, priority);
 }
 
 // pass 2: histogram of the next 11 bits among keys in the boundary bin of pass 1
@@ -437,7 +448,7 @@ hipError_t launch_sampler(strads_lasso *h, int64_t round)
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     uint64_t *sel = h->at<uint64_t>(h->ws.sel), *bnd = h->at<uint64_t>(h->ws.bnd);
     hipLaunchKernelGGL(k_keys_hist, dim3(g), dim3(256), 0, h->stream, h->at<float>(h->ws.dbeta), J, h->cfg.eta,
-                       h->cfg.seed, (uint64_t)round, keys, hist);
+                       h->cfg.seed, (uint64_t)round, h->cfg.priority, keys, hist);
     hipLaunchKernelGGL(k_hist2, dim3(g), dim3(256), 0, h->stream, keys, J, L, hist, hist + kHistBins, sc);
     const unsigned gc = (unsigned)((h->cfg.j + 256 * kCollectPerThread - 1) / (256 * kCollectPerThread));
     hipLaunchKernelGGL(k_collect, dim3(gc), dim3(256), 0, h->stream, keys, J, hist + kHistBins, sc, sel, bnd);
@@ -458,7 +469,8 @@ hipError_t launch_sampler(strads_lasso *h, int64_t round)
 hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys)
 {
     hipLaunchKernelGGL(k_keys_only, dim3(sampler_grid(h->cfg.j)), dim3(256), 0, h->stream,
-                       h->at<float>(h->ws.dbeta), (uint32_t)h->cfg.j, h->cfg.eta, h->cfg.seed, (uint64_t)round, keys);
+                       h->at<float>(h->ws.dbeta), (uint32_t)h->cfg.j, h->cfg.eta, h->cfg.seed, (uint64_t)round,
+                       h->cfg.priority, keys);
     return hipGetLastError();
 }
 

@@ -112,6 +112,7 @@ hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys);  // st
 hipError_t launch_gram_dense(strads_lasso *h, int part);  // Step 2a; part 0: K-slice tiles, part 1: sum + conflict mask
 hipError_t launch_mask_from_gram(strads_lasso *h, const float *gram, int32_t l);
 hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates);                    // Step 2b -> kept_pos, kept, n_kept
+hipError_t launch_keep_all(strads_lasso *h);              // no dependency check: B_1 = first p_max candidates
 // dynamic dependencies
 hipError_t launch_dots_cand(strads_lasso *h);             // x_j^T r and tentative change of every candidate
 hipError_t launch_movers(strads_lasso *h);                // mover list + Gram decomposition for it

@@ -57,7 +57,7 @@ def _check_round(g, o, log, teacher_forced=True):
     lr = g.last_round(want_gram=True)
     lc = g.last_candidates()
     cand, kept_pos = _np(lr["cand"]), _np(lr["kept_pos"])
-    ref_cand = orc.draw(orc.priority_keys(dbeta0, o.eta, o.seed, t0), o.l_prime)
+    ref_cand = orc.draw(orc.priority_keys(dbeta0, o.eta, o.seed, t0, o.priority), o.l_prime)
     assert np.array_equal(cand, ref_cand), f"candidate list differs (round {t0})"
     L = len(cand)
     rn = max(float(np.linalg.norm(r0.astype(np.float64))), 1.0)

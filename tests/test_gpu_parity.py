@@ -63,19 +63,24 @@ def _check_round(g, o, log, teacher_forced):
     beta0, dbeta0, r0, t0 = o.beta.copy(), o.dbeta.copy(), o.r.copy(), o.t
     gb0, gd0 = (beta0, dbeta0) if teacher_forced else [_np(a) for a in g.get_state()[:2]]
     g.round()
-    lr = g.last_round(want_gram=True)
+    lr = g.last_round(want_gram=not o.no_deps)
     cand, kept_pos = _np(lr["cand"]), _np(lr["kept_pos"])
     # Step 1: candidate list, set and order, bit-exact (from the oracle's own delta-beta in
     # teacher-forced mode; from the GPU's delta-beta otherwise, which the oracle has followed)
-    keys = orc.priority_keys(dbeta0, o.eta, o.seed, t0)
+    keys = orc.priority_keys(dbeta0, o.eta, o.seed, t0, o.priority)
     ref_cand = orc.draw(keys, o.l_prime)
     if not np.array_equal(cand, ref_cand):
         # admissible only if delta-beta differs in the last bits between the two sides
         assert not teacher_forced, "candidate list differs on identical delta-beta"
         log.append(("cand_fork", t0))
         return False
-    # Step 2a: Gram values
     L = len(cand)
+    if o.no_deps:
+        # no dependency check: B_1 is the head of the draw
+        k = min(L, o.p_max) if o.p_max > 0 else L
+        assert np.array_equal(kept_pos, np.arange(k, dtype=np.int32))
+        return _finish_round(g, o, lr, cand, kept_pos, r0, t0, gb0, gd0)
+    # Step 2a: Gram values
     if o.csc:
         Gref = orc.gram_csc(o.x, o.row_idx, o.col_ptr, cand)
     else:
@@ -91,6 +96,10 @@ def _check_round(g, o, log, teacher_forced):
         np.fill_diagonal(near, False)
         assert near.any(), f"kept sets differ without a pair near rho (round {t0})"
         log.append(("near_rho", t0, int(near.sum()) // 2))
+    return _finish_round(g, o, lr, cand, kept_pos, r0, t0, gb0, gd0)
+
+
+def _finish_round(g, o, lr, cand, kept_pos, r0, t0, gb0, gd0):
     # Steps 3-4 with the oracle following the GPU's (admissible) decisions
     out = o.round(forced_cand=cand, forced_kept_pos=kept_pos)
     rn = float(np.linalg.norm(r0.astype(np.float64)))
