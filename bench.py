@@ -31,7 +31,7 @@ HBM_PEAK_GBPS = 8000.0
 # rocprofv3 --pmc runs (FETCH_SIZE x2.00, WRITE_SIZE x1.00 after calibration against a copy kernel of
 # known size); the summary is profiles/hbm_traffic_c2_dense_block_corr.txt.  Workloads that were
 # not measured report null.
-MEASURED_GRAM_TRAFFIC_BYTES = {"c2_dense_block_corr": 168.9e6 + 33.0e6}
+MEASURED_GRAM_TRAFFIC_BYTES = {"c2_dense_block_corr": 302.4e6 + 33.3e6}
 
 WORKLOADS = {
     # name -> (config key of synth.lasso_inputs, overrides)
@@ -41,6 +41,8 @@ WORKLOADS = {
     "c4_sparse_csc": ("c4_sparse_csc", {}),
     # the fifth configuration's rows, duplicate structure and L'=8000 with J cut to fit quick runs
     "c5_dense_duplicates_j60k": ("c5_dense_duplicates", dict(j=60000, nnz=200, rounds=20)),
+    # the fifth configuration at full size: 50000 x 1000000 fp32 = 200 GB of X resident in HBM
+    "c5_dense_duplicates": ("c5_dense_duplicates", {}),
     "c2_small": ("c2_dense_block_corr", dict(n=2000, j=8000, nnz=40, l_prime=500, rounds=16)),
 }
 
@@ -55,9 +57,21 @@ def main() -> int:
     ap.add_argument("--profile-level", type=int, default=1, choices=(0, 1, 2),
                     help="HIP-event timing inside the timed region: 1 = Gram kernel only, 2 = every stage")
     ap.add_argument("--split-k", type=int, default=0)
-    ap.add_argument("--deps", default="static", choices=("static", "dynamic"),
+    ap.add_argument("--deps", default="static", choices=("static", "dynamic", "none"),
                     help="dependency rule of Step 2: static = Algorithm 1 as printed (the headline workload); "
-                         "dynamic = only pairs of candidates that both move are checked (dense designs)")
+                         "dynamic = only pairs of candidates that both move are checked (dense designs); "
+                         "none = no check (Shotgun when combined with --priority uniform)")
+    ap.add_argument("--priority", default="squared", choices=("squared", "linear", "uniform"),
+                    help="weight of Step 1's draw: (delta beta)^2+eta (headline), |delta beta|+eta, or 1")
+    ap.add_argument("--p-max", type=int, default=0, help="cap on the kept set (Algorithm 1's P); 0 = none")
+    ap.add_argument("--kkt-tol", type=float, default=0.0,
+                    help="> 0: --steps is an upper bound and the run stops once the optimality violation is "
+                         "<= kkt_tol * lambda, tested every --check-every rounds (each test streams X once)")
+    ap.add_argument("--check-every", type=int, default=25)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="after the timed region run one elementwise kernel of known traffic (reads 1 GiB, "
+                         "writes 1 GiB) so that a rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command "
+                         "carries its own scale factor")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -81,10 +95,11 @@ def main() -> int:
     p = si.make(key, device=dev, **over)
     torch.cuda.synchronize()
     t_gen = time.time() - t0
+    print(f"bench.py: inputs for {args.workload} generated in {t_gen:.1f} s", file=sys.stderr, flush=True)
 
     def fresh():
-        kw = dict(y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed,
-                  dynamic=args.deps == "dynamic")
+        kw = dict(y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed, p_max=args.p_max,
+                  dynamic=args.deps == "dynamic", no_deps=args.deps == "none", priority=args.priority)
         if p.layout == "dense":
             return pk.StradsLasso(x=p.x, **kw)
         return pk.StradsLasso(values=p.values, row_idx=p.row_idx, col_ptr=p.col_ptr, n=p.n, **kw)
@@ -98,6 +113,7 @@ def main() -> int:
         g.round()
     torch.cuda.synchronize()
     g.close()
+    print("bench.py: warm-up done", file=sys.stderr, flush=True)
 
     g = fresh()
     if args.split_k:
@@ -107,11 +123,15 @@ def main() -> int:
     g.set_tuning("profile_level", args.profile_level)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    info = g.run(args.steps)                    # enqueues K rounds, waits once at the end
+    if args.kkt_tol > 0:
+        info = g.run(args.steps, args.kkt_tol, args.check_every)
+    else:
+        info = g.run(args.steps)                # enqueues K rounds, waits once at the end
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     stage = g.stage_times() if args.profile_level else {"rounds": 0}
     g.set_tuning("profile_level", 0)
+    rounds_done = int(info.rounds_done)
     updates = int(info.updates_done)
     f1 = float(info.objective)
 
@@ -126,6 +146,14 @@ def main() -> int:
     kkt_ms = e0.elapsed_time(e1)
     kkt_bytes = 4.0 * p.n * p.j if p.layout == "dense" else 8.0 * float(p.values.numel())
     kkt_gbps = kkt_bytes / (kkt_ms * 1e-3) / 1e9
+
+    if args.pmc_calibration:
+        a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        torch.add(a, 1.0, out=b)                 # 2^28 floats in, 2^28 floats out
+        torch.cuda.synchronize()
+        del a, b
 
     L, N = g.L, p.n
     gram_flops = float(N) * L * (L - 1)          # algorithmic: every unordered pair once, 2 flops per row
@@ -142,7 +170,8 @@ def main() -> int:
     if args.cpu_seconds > 0:
         from oracle.oracle import OracleLasso
         okw = dict(y=p.y.cpu().numpy(), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed,
-                   dynamic=args.deps == "dynamic")
+                   p_max=args.p_max, dynamic=args.deps == "dynamic", no_deps=args.deps == "none",
+                   priority=args.priority)
         if p.layout == "dense":
             o = OracleLasso(x=p.x.cpu().numpy(), **okw)
         else:
@@ -163,11 +192,13 @@ def main() -> int:
 
     out = {
         "metric": "coordinate_updates_per_sec", "value": round(updates / wall, 1), "unit": "updates/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall / max(args.steps, 1) * 1e3, 4),
+        "n_gpus": 1, "steps": rounds_done, "warmup": args.warmup, "ms_per_step": round(wall / max(rounds_done, 1) * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "n": p.n, "j": p.j, "l_prime": p.l_prime, "rho": p.rho,
-                   "eta": p.eta, "lambda": p.lam, "rounds": args.steps, "deps": args.deps, "parallelism": "1 GPU"},
-        "rounds_per_s": round(args.steps / wall, 2), "updates": updates,
+                   "eta": p.eta, "lambda": p.lam, "rounds": rounds_done, "deps": args.deps, "priority": args.priority, "p_max": args.p_max,
+                   "parallelism": "1 GPU"},
+        "rounds_per_s": round(rounds_done / wall, 2), "updates": updates, "seconds": round(wall, 4),
+        "kkt_tol": args.kkt_tol, "converged": int(info.converged),
         "objective_start": f0, "objective_end": f1, "kkt_violation_end": viol,
         "roofline": roofline,
         "hbm_pass": {"kernel": "k_kkt", "bytes": kkt_bytes, "ms": round(kkt_ms, 4), "achieved": round(kkt_gbps, 1),
