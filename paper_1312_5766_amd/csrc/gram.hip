@@ -33,7 +33,10 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kPad = 4;                         // LDS row padding, floats
 constexpr int kRow = kGramKT + kPad;            // LDS row stride, floats
 constexpr int kPanel = kGramTile * kRow;        // floats per operand panel per stage
-constexpr int kGramSlots = 512;                 // resident workgroups: 2 per compute unit (LDS)
+constexpr int kGramSlots = 256 * kGramOcc;      // resident workgroups on 256 compute units
+constexpr int kKQ = kGramKT / 4;                // 16-byte pieces of one column per stage
+constexpr int kColsPerPass = 256 / kKQ;         // columns the 256 threads stage in one pass
+constexpr int kPasses = kGramTile / kColsPerPass;   // passes per 128-column panel
 
 // D += A * B on the matrix core with the accumulator pinned to the AGPR file.
 __device__ __forceinline__ void mfma32(floatx16 &acc, float a, float b)
@@ -106,32 +109,32 @@ __device__ __forceinline__ void gram_tile_off(const float *__restrict__ X, int64
     const int64_t kend = (kbeg + g.kchunk_off < N) ? kbeg + g.kchunk_off : N;
     const int nstage = (int)((kend - kbeg + kGramKT - 1) / kGramKT);
 
-    // this thread stages 4 A-columns and 4 B-columns: column (it*32 + tid/8), floats (tid%8)*4..+3.
-    // Columns past the candidate count are clamped to the last candidate: their products land in
-    // rows/columns >= L of the tile, which nobody reads.
-    const int crow = tid >> 3, kq = (tid & 7) * 4;
-    const float *col[8];
+    // this thread stages kPasses A-columns and kPasses B-columns: column (it*kColsPerPass + tid/kKQ),
+    // floats (tid%kKQ)*4..+3.  Columns past the candidate count are clamped to the last candidate:
+    // their products land in rows/columns >= L of the tile, which nobody reads.
+    const int crow = tid / kKQ, kq = (tid % kKQ) * 4;
+    const float *col[2 * kPasses];
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        int ia = ta * kGramTile + it * 32 + crow, ib = tb * kGramTile + it * 32 + crow;
+    for (int it = 0; it < kPasses; ++it) {
+        int ia = ta * kGramTile + it * kColsPerPass + crow, ib = tb * kGramTile + it * kColsPerPass + crow;
         ia = ia < g.L ? ia : g.L - 1;
         ib = ib < g.L ? ib : g.L - 1;
         col[it] = X + (int64_t)cand[ia] * N;
-        col[4 + it] = X + (int64_t)cand[ib] * N;
+        col[kPasses + it] = X + (int64_t)cand[ib] * N;
     }
 
-    float4 R[8];
+    float4 R[2 * kPasses];
     auto fetch = [&](int st) {
         const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) R[i] = load_k4<VEC4>(col[i], k, kend);
+        for (int i = 0; i < 2 * kPasses; ++i) R[i] = load_k4<VEC4>(col[i], k, kend);
     };
     auto stash = [&](int buf) {
         float *pa = smem + buf * 2 * kPanel, *pb = pa + kPanel;
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            *reinterpret_cast<float4 *>(pa + (it * 32 + crow) * kRow + kq) = R[it];
-            *reinterpret_cast<float4 *>(pb + (it * 32 + crow) * kRow + kq) = R[4 + it];
+        for (int it = 0; it < kPasses; ++it) {
+            *reinterpret_cast<float4 *>(pa + (it * kColsPerPass + crow) * kRow + kq) = R[it];
+            *reinterpret_cast<float4 *>(pb + (it * kColsPerPass + crow) * kRow + kq) = R[kPasses + it];
         }
     };
 
@@ -212,24 +215,25 @@ __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int6
     const int64_t kend = (kbeg + g.kchunk_diag < N) ? kbeg + g.kchunk_diag : N;
     const int nstage = (int)((kend - kbeg + kGramKT - 1) / kGramKT);
 
-    const int crow = tid >> 3, kq = (tid & 7) * 4;
-    const float *col[4];
+    const int crow = tid / kKQ, kq = (tid % kKQ) * 4;
+    const float *col[kPasses];
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        int ia = ta * kGramTile + it * 32 + crow;
+    for (int it = 0; it < kPasses; ++it) {
+        int ia = ta * kGramTile + it * kColsPerPass + crow;
         ia = ia < g.L ? ia : g.L - 1;
         col[it] = X + (int64_t)cand[ia] * N;
     }
-    float4 R[4];
+    float4 R[kPasses];
     auto fetch = [&](int st) {
         const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) R[i] = load_k4<VEC4>(col[i], k, kend);
+        for (int i = 0; i < kPasses; ++i) R[i] = load_k4<VEC4>(col[i], k, kend);
     };
     auto stash = [&](int buf) {
         float *pa = smem + buf * 2 * kPanel;
 #pragma unroll
-        for (int it = 0; it < 4; ++it) *reinterpret_cast<float4 *>(pa + (it * 32 + crow) * kRow + kq) = R[it];
+        for (int it = 0; it < kPasses; ++it)
+            *reinterpret_cast<float4 *>(pa + (it * kColsPerPass + crow) * kRow + kq) = R[it];
     };
 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -336,7 +340,7 @@ __device__ __forceinline__ void gram_job(const float *__restrict__ X, int64_t N,
 
 // Static dependencies: the decomposition is known on the host; grid.x = number of jobs.
 template <bool VEC4>
-__global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__ X, int64_t N,
+__global__ __launch_bounds__(256, kGramOcc) void k_gram_tiles(const float *__restrict__ X, int64_t N,
                                                        const int32_t *__restrict__ cand, GramShape g,
                                                        float *__restrict__ P)
 {
@@ -348,7 +352,7 @@ __global__ __launch_bounds__(256, 2) void k_gram_tiles(const float *__restrict__
 // so the launch has a fixed number of resident workgroups, which read the decomposition the mover
 // kernel chose and share its jobs round-robin.
 template <bool VEC4>
-__global__ __launch_bounds__(256, 2) void k_gram_tiles_dyn(const float *__restrict__ X, int64_t N,
+__global__ __launch_bounds__(256, kGramOcc) void k_gram_tiles_dyn(const float *__restrict__ X, int64_t N,
                                                            const int32_t *__restrict__ mcand,
                                                            const GramShape *__restrict__ gdev,
                                                            float *__restrict__ P)
@@ -425,7 +429,7 @@ __host__ __device__ static inline int diag_split_for(int64_t stages, int split_o
 
 // Number of K-slices per off-diagonal tile.
 // Workgroups = off-diagonal tiles x K-slices + diagonal tiles x their (fewer) K-slices.  Two
-// workgroups are resident per compute unit (LDS), so the launch runs in rounds of 512.  The cost
+// workgroups are resident per compute unit (LDS), so the launch runs in rounds of kGramSlots.  The cost
 // of a choice, in K stages of an off-diagonal workgroup: rounds x (stages per slice + a fixed
 // prologue/epilogue allowance) + the partial-sum traffic it causes.
 __host__ __device__ static inline int gram_split_choose(int64_t n, int32_t lpad)
@@ -443,9 +447,9 @@ __host__ __device__ static inline int gram_split_choose(int64_t n, int32_t lpad)
         const int64_t wg = n_off * s + T * sd;
         const int64_t rounds = (wg + kGramSlots - 1) / kGramSlots;
         const int64_t len = (stages + s - 1) / s;
-        // 3 stages' worth per workgroup for first fetch and tile store; the partial tiles of 512
-        // workgroups (32 MiB written, then read by the mask kernel) cost about 2 stage-times
-        const double cost = (double)rounds * (double)(len + 3) + 2.0 * (double)wg / (double)kGramSlots;
+        // about 96 rows' worth of K per workgroup for first fetch and tile store; the partial tiles of
+        // 512 workgroups (32 MiB written, then read by the mask kernel) cost about 64 rows' worth
+        const double cost = (double)rounds * (double)(len + 96 / kGramKT) + (64.0 / kGramKT) * (double)wg / 512.0;
         if (cost < best_cost * 0.995) { best_cost = cost; best = s; }
     }
     return best;
@@ -496,8 +500,8 @@ static GramShape gram_shape(const strads_lasso *h)
 }
 
 // Dynamic dependencies: list the movers (candidates whose tentative change is not zero) in draw
-// order and look up the decomposition of their Gram.  One workgroup of 1024 threads, 8 consecutive
-// candidate positions per thread (L <= 8192).
+// order and look up the decomposition of their Gram.  One workgroup of 1024 threads walks the
+// candidate positions 1024 at a time (coalesced reads, wavefront ballots for the ordered offsets).
 __global__ __launch_bounds__(1024) void k_movers(const float *__restrict__ dc, const int32_t *__restrict__ cand,
                                                  int32_t L, const GramShape *__restrict__ table,
                                                  int32_t *__restrict__ mpos, int32_t *__restrict__ mcand,
@@ -505,41 +509,31 @@ __global__ __launch_bounds__(1024) void k_movers(const float *__restrict__ dc, c
 {
     __shared__ uint32_t wtot[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    uint32_t flags = 0, cnt = 0;
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        const int32_t a = tid * 8 + q;
+    uint32_t base = 0;
+    for (int32_t a0 = 0; a0 < L; a0 += 1024) {          // 1024 positions at a time, in order
+        const int32_t a = a0 + tid;
         const bool mv = a < L && dc[a] != 0.f;
-        flags |= (mv ? 1u : 0u) << q;
-        cnt += mv ? 1u : 0u;
-    }
-    uint32_t incl = cnt;
+        const int32_t j = mv ? cand[a] : 0;
+        const uint64_t m = __ballot(mv);
+        if (lane == 0) wtot[wave] = (uint32_t)__popcll(m);
+        __syncthreads();
+        uint32_t before = 0, total = 0;
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t v = __shfl_up(incl, d);
-        if (lane >= d) incl += v;
-    }
-    if (lane == 63) wtot[wave] = incl;
-    __syncthreads();
-    uint32_t before = 0, total = 0;
-#pragma unroll
-    for (int w = 0; w < 16; ++w) { const uint32_t v = wtot[w]; if (w < wave) before += v; total += v; }
-    uint32_t idx = before + incl - cnt;
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        if ((flags >> q) & 1u) {
-            const int32_t a = tid * 8 + q;
+        for (int w = 0; w < 16; ++w) { const uint32_t v = wtot[w]; if (w < wave) before += v; total += v; }
+        if (mv) {
+            const uint32_t idx = base + before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
             mpos[idx] = a;
-            mcand[idx] = cand[a];
-            ++idx;
+            mcand[idx] = j;
         }
+        base += total;
+        __syncthreads();                                // wtot is reused by the next pass
     }
     if (tid == 0) {
         // the decomposition depends on the mover count only through the number of tiles: the host
         // tabulated it per tile count when the handle was created
-        GramShape g = table[(total + kGramTile - 1) / kGramTile];
-        g.L = (int32_t)total;
-        sc->n_movers = (int32_t)total;
+        GramShape g = table[(base + kGramTile - 1) / kGramTile];
+        g.L = (int32_t)base;
+        sc->n_movers = (int32_t)base;
         *gout = g;
     }
 }

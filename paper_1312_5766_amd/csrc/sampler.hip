@@ -299,6 +299,7 @@ __device__ uint64_t bitonic_sort_desc_1024(uint64_t x, uint64_t *xch /* 1024 ite
 }
 
 constexpr uint32_t kRegSortMax = 1024;
+constexpr uint32_t kRankMax = 192;      // boundary lists up to this length are ranked by counting
 
 // exclusive rank of a flagged thread among the flagged threads of a 1024-thread block
 __device__ __forceinline__ uint32_t block_rank(bool flag, uint32_t *wave_tot /* 17 */, uint32_t &total)
@@ -365,6 +366,18 @@ __global__ __launch_bounds__(1024) void k_finalize(RoundScalars *__restrict__ sc
     // B. take the `need` largest boundary items
     if (nb == need) {
         for (uint32_t i = tid; i < nb; i += 1024u) sel[n_sel + i] = bnd[i];
+    } else if (nb <= kRankMax) {
+        // few items (the usual case with a 22-bit prefix): an item's rank is the number of larger
+        // items, counted against all of them through LDS broadcasts; items are distinct, so the
+        // ranks 0..need-1 are exactly the wanted ones.  Step C puts everything in order anyway.
+        if (tid < nb) lds[tid] = bnd[tid];
+        __syncthreads();
+        if (tid < nb) {
+            const uint64_t x = lds[tid];
+            uint32_t rank = 0;
+            for (uint32_t i = 0; i < nb; ++i) rank += lds[i] > x ? 1u : 0u;
+            if (rank < need) sel[n_sel + rank] = x;
+        }
     } else if (nb <= kRegSortMax) {
         const uint64_t v = bitonic_sort_desc_1024(tid < nb ? bnd[tid] : 0ull, lds);
         if (tid < need) sel[n_sel + tid] = v;

@@ -12,7 +12,14 @@ namespace strads {
 
 constexpr int kHistBins = 2048;        // 11-bit digits of the orderable 32-bit key
 constexpr int kGramTile = 128;         // candidate-Gram output tile edge (per workgroup)
-constexpr int kGramKT = 32;            // K (row) extent of one LDS stage, floats
+#ifndef STRADS_GRAM_KT
+#define STRADS_GRAM_KT 32
+#endif
+#ifndef STRADS_GRAM_OCC
+#define STRADS_GRAM_OCC 2
+#endif
+constexpr int kGramKT = STRADS_GRAM_KT;   // K (row) extent of one LDS stage, floats (16 or 32)
+constexpr int kGramOcc = STRADS_GRAM_OCC; // Gram workgroups resident per compute unit (LDS and registers allow it)
 constexpr int kMaxResidualGroups = 64; // column groups of the residual update
 constexpr int kObjBlocks = 256;        // workgroups of the objective reduction
 constexpr int kSelectCapDefault = 16384;

@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void k_dots_cand(const float *__restrict__ X, 
 // Dynamic dependencies: assemble B_1 = (candidates that do not move) + (movers that passed the
 // filter), in draw order, cut at the cap, and commit it: beta_j <- its tentative value,
 // delta beta_j <- |change| (0 for a kept candidate that does not move).  One workgroup of 1024
-// threads, 8 consecutive candidate positions per thread.
+// threads walks the candidate positions 1024 at a time.
 __global__ __launch_bounds__(1024) void k_commit_dynamic(const int32_t *__restrict__ cand, int32_t L, int32_t p_max,
                                                          const float *__restrict__ zc, const float *__restrict__ dc,
                                                          const float *__restrict__ nbc,
@@ -135,49 +135,41 @@ __global__ __launch_bounds__(1024) void k_commit_dynamic(const int32_t *__restri
                                                          int32_t *__restrict__ kept, float *__restrict__ z,
                                                          float *__restrict__ delta)
 {
-    __shared__ uint8_t keep[STRADS_MAX_L_PRIME];
+    __shared__ uint8_t mkept[STRADS_MAX_L_PRIME];       // 1: a mover at this position passed the filter
     __shared__ uint32_t wtot[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int32_t cap = p_max > 0 ? p_max : L;
-    for (int32_t a = tid; a < L; a += 1024) keep[a] = dc[a] == 0.f ? 1 : 0;
+    for (int32_t a = tid; a < L; a += 1024) mkept[a] = 0;
     __syncthreads();
     const int32_t nmk = sc->n_mkept;
-    for (int32_t i = tid; i < nmk; i += 1024) keep[mpos[mkept_pos[i]]] = 1;
+    for (int32_t i = tid; i < nmk; i += 1024) mkept[mpos[mkept_pos[i]]] = 1;
     __syncthreads();
-    uint32_t cnt = 0;
+    uint32_t base = 0;
+    for (int32_t a0 = 0; a0 < L; a0 += 1024) {
+        const int32_t a = a0 + tid;
+        const float d = a < L ? dc[a] : 0.f;
+        const bool keep = a < L && (d == 0.f || mkept[a]);
+        const uint64_t m = __ballot(keep);
+        if (lane == 0) wtot[wave] = (uint32_t)__popcll(m);
+        __syncthreads();
+        uint32_t before = 0, total = 0;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) { const int32_t a = tid * 8 + q; cnt += (a < L && keep[a]) ? 1u : 0u; }
-    uint32_t incl = cnt;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t v = __shfl_up(incl, d);
-        if (lane >= d) incl += v;
-    }
-    if (lane == 63) wtot[wave] = incl;
-    __syncthreads();
-    uint32_t before = 0, total = 0;
-#pragma unroll
-    for (int w = 0; w < 16; ++w) { const uint32_t v = wtot[w]; if (w < wave) before += v; total += v; }
-    int32_t idx = (int32_t)(before + incl - cnt);
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        const int32_t a = tid * 8 + q;
-        if (a < L && keep[a]) {
-            if (idx < cap) {
-                const int32_t j = cand[a];
-                const float d = dc[a];
-                kept_pos[idx] = a;
-                kept[idx] = j;
-                z[idx] = zc[a];
-                delta[idx] = d;
-                beta[j] = nbc[a];
-                dbeta[j] = fabsf(d);
-            }
-            ++idx;
+        for (int w = 0; w < 16; ++w) { const uint32_t v = wtot[w]; if (w < wave) before += v; total += v; }
+        const int32_t idx = (int32_t)(base + before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull)));
+        if (keep && idx < cap) {
+            const int32_t j = cand[a];
+            kept_pos[idx] = a;
+            kept[idx] = j;
+            z[idx] = zc[a];
+            delta[idx] = d;
+            beta[j] = nbc[a];
+            dbeta[j] = fabsf(d);
         }
+        base += total;
+        __syncthreads();
     }
     if (tid == 0) {
-        const int32_t nk = (int32_t)total < cap ? (int32_t)total : cap;
+        const int32_t nk = (int32_t)base < cap ? (int32_t)base : cap;
         sc->n_kept = nk;
         sc->updates_total += (unsigned long long)nk;
     }
