@@ -34,7 +34,7 @@ class _Problem(C.Structure):
     _fields_ = [("N", C.c_int64), ("J", C.c_int64), ("X", C.c_void_p), ("row_idx", C.c_void_p),
                 ("col_ptr", C.c_void_p), ("lam", C.c_float), ("rho", C.c_float), ("eta", C.c_float),
                 ("l_prime", C.c_int32), ("p_max", C.c_int32), ("seed", C.c_uint64),
-                ("priority", C.c_int32), ("deps", C.c_int32)]
+                ("priority", C.c_int32), ("deps", C.c_int32), ("n_shards", C.c_int32)]
 
 
 PRIORITY = {"squared": 0, "linear": 1, "uniform": 2}
@@ -178,10 +178,11 @@ class OracleLasso:
 
     def __init__(self, y, lam, rho, eta, l_prime, seed=0, p_max=0, c_init=1e6, x=None,
                  values=None, row_idx=None, col_ptr=None, n=None, dynamic=False, priority="squared",
-                 no_deps=False):
+                 no_deps=False, n_shards=1):
         self.dynamic = bool(dynamic)          # update-aware dependencies (oracle_round_dynamic)
         self.priority = priority              # "squared" | "linear" | "uniform"
         self.no_deps = bool(no_deps)          # skip Step 2 (Shotgun)
+        self.n_shards = max(1, int(n_shards)) # scheduler shards taking turns; coordinate j is in shard j % S
         assert not (self.dynamic and self.no_deps)
         self.y = _arr(y, np.float32)
         if x is not None:
@@ -197,7 +198,7 @@ class OracleLasso:
             self.csc = True
         assert self.y.shape[0] == self.N
         self.lam, self.rho, self.eta = np.float32(lam), np.float32(rho), np.float32(eta)
-        self.l_prime, self.p_max, self.seed = min(int(l_prime), self.J), int(p_max), int(seed)
+        self.l_prime, self.p_max, self.seed = min(int(l_prime), self.J // max(1, int(n_shards))), int(p_max), int(seed)
         # Algorithm 1 initialisation: beta^(t-1) = 0, beta^(t-2) = C  =>  delta beta_j = C for all j
         self.beta = np.zeros(self.J, np.float32)
         self.dbeta = np.full(self.J, c_init, np.float32)
@@ -205,7 +206,8 @@ class OracleLasso:
         self.t = 0
         self._prob = _Problem(self.N, self.J, _p(self.x), _p(self.row_idx), _p(self.col_ptr),
                               self.lam, self.rho, self.eta, self.l_prime, self.p_max, self.seed,
-                              PRIORITY[priority], 2 if self.no_deps else (1 if self.dynamic else 0))
+                              PRIORITY[priority], 2 if self.no_deps else (1 if self.dynamic else 0),
+                              self.n_shards)
 
     def set_state(self, beta, dbeta, r, t):
         self.beta[:] = beta

@@ -382,7 +382,32 @@ typedef struct {
     int32_t deps;              /* 0: Algorithm 1's dependency check; 2: none (every candidate is
                                   dispatched, up to p_max: the Shotgun scheduler of Section 5.1).
                                   1 is oracle_round_dynamic's rule and is not read here. */
+    int32_t n_shards;          /* S scheduler shards taking turns (Section 3); <= 1: one scheduler */
 } oracle_problem_t;
+
+/* Step 1 for round t.  With S > 1 scheduler shards (Section 3, "Implementation Overview"): every
+ * coordinate belongs to exactly one shard for good, shard s = t mod S has the turn in round t, and it
+ * draws its P' candidates from its own coordinates only, with p_s(j) the same priority restricted
+ * to them.  The paper assigns coordinates to shards at random; here coordinate j belongs to shard
+ * j mod S.  The random number of coordinate j is keyed by j itself, whatever the sharding.
+ * Returns the number of candidates (min(P', size of the shard)) or -1. */
+static int32_t draw_for_round(const oracle_problem_t *p, uint64_t t, const float *dbeta, int32_t *cand)
+{
+    const int64_t S = p->n_shards > 1 ? p->n_shards : 1;
+    const int64_t s = (int64_t)(t % (uint64_t)S);
+    const int64_t Js = p->J > s ? (p->J - s + S - 1) / S : 0;
+    float *keys = (float *)malloc((size_t)(Js > 0 ? Js : 1) * sizeof(float));
+    if (!keys) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < Js; ++i) {
+        const int64_t j = i * S + s;
+        keys[i] = oracle_priority_key_mode(dbeta[j], p->eta, p->seed, t, (uint64_t)j, p->priority);
+    }
+    int32_t L = oracle_draw(Js, keys, p->l_prime, cand);     /* positions within the shard */
+    free(keys);
+    for (int32_t a = 0; a < L; ++a) cand[a] = (int32_t)((int64_t)cand[a] * S + s);
+    return L;
+}
 
 int32_t oracle_round(const oracle_problem_t *p, uint64_t t, float *beta, float *dbeta, float *r,
                      const int32_t *forced_cand, int32_t forced_n_cand,
@@ -395,11 +420,7 @@ int32_t oracle_round(const oracle_problem_t *p, uint64_t t, float *beta, float *
         L = forced_n_cand;
         memcpy(cand, forced_cand, (size_t)L * sizeof(int32_t));
     } else {
-        float *keys = (float *)malloc((size_t)(p->J > 0 ? p->J : 1) * sizeof(float));
-        if (!keys) return -1;
-        oracle_priority_keys_mode(p->J, dbeta, p->eta, p->seed, t, p->priority, keys);
-        L = oracle_draw(p->J, keys, p->l_prime, cand);
-        free(keys);
+        L = draw_for_round(p, t, dbeta, cand);
         if (L < 0) return -1;
     }
     *n_cand_out = L;
@@ -481,11 +502,7 @@ int32_t oracle_round_dynamic(const oracle_problem_t *p, uint64_t t, float *beta,
         L = forced_n_cand;
         memcpy(cand, forced_cand, (size_t)L * sizeof(int32_t));
     } else {
-        float *keys = (float *)malloc((size_t)(p->J > 0 ? p->J : 1) * sizeof(float));
-        if (!keys) return -1;
-        oracle_priority_keys_mode(p->J, dbeta, p->eta, p->seed, t, p->priority, keys);
-        L = oracle_draw(p->J, keys, p->l_prime, cand);
-        free(keys);
+        L = draw_for_round(p, t, dbeta, cand);
         if (L < 0) return -1;
     }
     *n_cand_out = L;
