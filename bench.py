@@ -64,6 +64,9 @@ def main() -> int:
     ap.add_argument("--priority", default="squared", choices=("squared", "linear", "uniform"),
                     help="weight of Step 1's draw: (delta beta)^2+eta (headline), |delta beta|+eta, or 1")
     ap.add_argument("--p-max", type=int, default=0, help="cap on the kept set (Algorithm 1's P); 0 = none")
+    ap.add_argument("--shards", type=int, default=1,
+                    help="scheduler shards taking turns (Section 3); > 1 overlaps the shards' scheduling work on "
+                         "separate streams (the headline workload uses 1: Algorithm 1 with one scheduler)")
     ap.add_argument("--kkt-tol", type=float, default=0.0,
                     help="> 0: --steps is an upper bound and the run stops once the optimality violation is "
                          "<= kkt_tol * lambda, tested every --check-every rounds (each test streams X once)")
@@ -99,7 +102,8 @@ def main() -> int:
 
     def fresh():
         kw = dict(y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed, p_max=args.p_max,
-                  dynamic=args.deps == "dynamic", no_deps=args.deps == "none", priority=args.priority)
+                  dynamic=args.deps == "dynamic", no_deps=args.deps == "none", priority=args.priority,
+                  n_shards=args.shards)
         if p.layout == "dense":
             return pk.StradsLasso(x=p.x, **kw)
         return pk.StradsLasso(values=p.values, row_idx=p.row_idx, col_ptr=p.col_ptr, n=p.n, **kw)
@@ -119,6 +123,8 @@ def main() -> int:
     if args.split_k:
         g.set_tuning("gram_split_k", args.split_k)
     f0 = g.objective()
+    if args.shards > 1:
+        args.profile_level = 0                  # stages of different shards overlap: no per-stage timing
     g.set_tuning("profile_rounds", max(args.steps, 1))
     g.set_tuning("profile_level", args.profile_level)
     torch.cuda.synchronize()
@@ -171,7 +177,7 @@ def main() -> int:
         from oracle.oracle import OracleLasso
         okw = dict(y=p.y.cpu().numpy(), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed,
                    p_max=args.p_max, dynamic=args.deps == "dynamic", no_deps=args.deps == "none",
-                   priority=args.priority)
+                   priority=args.priority, n_shards=args.shards)
         if p.layout == "dense":
             o = OracleLasso(x=p.x.cpu().numpy(), **okw)
         else:
@@ -195,7 +201,7 @@ def main() -> int:
         "n_gpus": 1, "steps": rounds_done, "warmup": args.warmup, "ms_per_step": round(wall / max(rounds_done, 1) * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "n": p.n, "j": p.j, "l_prime": p.l_prime, "rho": p.rho,
-                   "eta": p.eta, "lambda": p.lam, "rounds": rounds_done, "deps": args.deps, "priority": args.priority, "p_max": args.p_max,
+                   "eta": p.eta, "lambda": p.lam, "rounds": rounds_done, "deps": args.deps, "priority": args.priority, "p_max": args.p_max, "shards": args.shards,
                    "parallelism": "1 GPU"},
         "rounds_per_s": round(rounds_done / wall, 2), "updates": updates, "seconds": round(wall, 4),
         "kkt_tol": args.kkt_tol, "converged": int(info.converged),

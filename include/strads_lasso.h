@@ -27,7 +27,11 @@
  *   - Every function returns STRADS_OK (0) or a negative STRADS_E_* code; on
  *     error no output argument is written.  Nothing aborts or throws.
  *   - Work is enqueued on the caller's stream.  Calls on one handle must not
- *     overlap (the handle's workspace is shared state).
+ *     overlap (the handle's workspace is shared state).  A handle with n_shards > 1 also owns
+ *     n_shards - 1 streams of its own (default priority, created at create, destroyed at destroy):
+ *     every call that enqueues rounds makes them wait for the caller's stream first and makes the
+ *     caller's stream wait for them before it returns, so from outside the work is still ordered
+ *     as if it ran on the caller's stream; the shards overlap within one strads_lasso_run call.
  */
 #ifndef STRADS_LASSO_H
 #define STRADS_LASSO_H
@@ -50,6 +54,7 @@ extern "C" {
 #define STRADS_LAYOUT_CSC             1   /* values / row_idx / col_ptr */
 
 #define STRADS_MAX_L_PRIME         8192   /* largest supported candidate count per round */
+#define STRADS_MAX_SHARDS             8   /* largest supported number of scheduler shards */
 
 /* Stages of one round, in stream order, as timed by strads_lasso_stage_times */
 #define STRADS_STAGE_SAMPLER     0   /* Step 1: keys, top-P' selection, draw order */
@@ -103,6 +108,12 @@ typedef struct {
                                      sizes the per-round inverted index; checked at create */
     int32_t        deps;          /* STRADS_DEPS_*: dependency rule of Step 2 (dynamic: dense designs only) */
     int32_t        priority;      /* STRADS_PRIORITY_*: weight of Step 1's draw */
+    int32_t        n_shards;      /* S scheduler shards taking turns (Section 3): coordinate j belongs to
+                                     shard j mod S for good, round t is shard (t mod S)'s turn and draws its
+                                     candidates (l_prime clamped to floor(j / S)) from that shard only.
+                                     0 or 1: one scheduler.  With S > 1 the shards' scheduling work
+                                     (draw, Gram, greedy walk) runs on library-owned streams concurrently;
+                                     the updates are applied in round order.  At most STRADS_MAX_SHARDS. */
     void          *workspace;     /* DEVICE, 256-byte aligned, caller-allocated */
     size_t         workspace_bytes;
     void          *stream;        /* hipStream_t owned by the caller (NULL = the default stream) */
@@ -199,7 +210,7 @@ int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, i
  * fp32 summation order of the Gram when split_k changes):
  *   "gram_split_k"  0 = automatic, else the number of K-slices per Gram tile
  *   "select_cap"    boundary-list length above which the sampler's final
- *                   selection falls back to its multi-pass path (default 16384)
+ *                   selection falls back to its multi-pass path (default 4096)
  *   "profile_level", "profile_rounds"   see strads_lasso_stage_times
  * Returns STRADS_E_INVALID_ARG for an unknown name or a value out of range. */
 int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value);

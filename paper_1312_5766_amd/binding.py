@@ -38,7 +38,7 @@ class Config(C.Structure):
                 ("row_idx", C.c_void_p), ("col_ptr", C.c_void_p), ("y", C.c_void_p),
                 ("lam", C.c_float), ("rho", C.c_float), ("eta", C.c_float), ("c_init", C.c_float),
                 ("l_prime", C.c_int32), ("p_max", C.c_int32), ("seed", C.c_uint64), ("keep_gram", C.c_int32),
-                ("max_col_nnz", C.c_int32), ("deps", C.c_int32), ("priority", C.c_int32), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
+                ("max_col_nnz", C.c_int32), ("deps", C.c_int32), ("priority", C.c_int32), ("n_shards", C.c_int32), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
 
 
 class RoundInfo(C.Structure):
@@ -121,7 +121,7 @@ class StradsLasso:
                  row_idx: Optional[torch.Tensor] = None, col_ptr: Optional[torch.Tensor] = None,
                  n: Optional[int] = None, max_col_nnz: Optional[int] = None,
                  stream: Optional[torch.cuda.Stream] = None, dynamic: bool = False, priority: str = "squared",
-                 no_deps: bool = False):
+                 no_deps: bool = False, n_shards: int = 1):
         lib = load()
         self._h = None
         dev = y.device
@@ -141,14 +141,14 @@ class StradsLasso:
             if max_col_nnz is None:
                 max_col_nnz = int((col_ptr[1:] - col_ptr[:-1]).max().item())
         assert y.dtype == torch.float32 and y.is_contiguous() and y.numel() == self.N
-        self.L = min(int(l_prime), self.J)
+        self.L = min(int(l_prime), self.J // max(1, int(n_shards)))
         self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
         cfg = Config(n=self.N, j=self.J, layout=layout, x=_ptr(x if x is not None else values),
                      row_idx=_ptr(row_idx), col_ptr=_ptr(col_ptr), y=_ptr(y), lam=lam, rho=rho, eta=eta,
                      c_init=c_init, l_prime=int(l_prime), p_max=int(p_max), seed=int(seed),
                      keep_gram=int(keep_gram), max_col_nnz=int(max_col_nnz or 0),
                      deps=DEPS_NONE if no_deps else (DEPS_DYNAMIC if dynamic else DEPS_STATIC),
-                     priority=PRIORITY[priority], stream=self.stream.cuda_stream)
+                     priority=PRIORITY[priority], n_shards=int(n_shards), stream=self.stream.cuda_stream)
         nbytes = int(lib.strads_lasso_workspace_bytes(C.byref(cfg)))
         if nbytes == 0:
             raise StradsError(E_INVALID_ARG, "strads_lasso_workspace_bytes")

@@ -10,22 +10,30 @@ namespace strads {
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram, int32_t max_col_nnz, int32_t deps)
+Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram, int32_t max_col_nnz, int32_t deps,
+                int32_t n_shards)
 {
     Workspace w;
     memset(&w, 0, sizeof(w));
+    const int64_t S = n_shards > 1 ? n_shards : 1;
+    const int64_t js = (j + S - 1) / S;                  // coordinates of the largest shard
     const int64_t lpad = (l + kGramTile - 1) / kGramTile * kGramTile;
     const int64_t npad = (n + 3) / 4 * 4;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    // shared by all shards: the solver state and the objective scratch
     w.beta = take((size_t)j * 4);
     w.dbeta = take((size_t)j * 4);
     w.r = take((size_t)npad * 4);
-    w.keys = take((size_t)j * 4);
+    w.objpart = take((size_t)kObjBlocks * 8);
+    w.objout = take(8);
+    // once per shard
+    w.lane_begin = off;
+    w.keys = take((size_t)js * 4);
     w.hist = take((size_t)2 * kHistBins * 4);
     w.scalars = take(sizeof(RoundScalars));
     w.sel = take((size_t)2 * STRADS_MAX_L_PRIME * 8);
-    w.bnd = take((size_t)j * 8);
+    w.bnd = take((size_t)js * 8);
     w.cand = take((size_t)lpad * 4);
     if (layout == STRADS_LAYOUT_DENSE_COLMAJOR)
         w.partial = take(gram_partial_floats(n, (int32_t)lpad, deps == STRADS_DEPS_DYNAMIC) * 4);
@@ -40,8 +48,6 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
     w.mv_col = take((size_t)lpad * 4);
     w.mv_delta = take((size_t)lpad * 4);
     w.rpart = take((size_t)kMaxResidualGroups * npad * 4);
-    w.objpart = take((size_t)kObjBlocks * 8);
-    w.objout = take(8);
     const size_t dyn = deps == STRADS_DEPS_DYNAMIC ? (size_t)lpad * 4 : 256;
     w.zc = take(dyn);
     w.dc = take(dyn);
@@ -53,7 +59,19 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
     w.dtable = take(sizeof(GramShape) * (STRADS_MAX_L_PRIME / kGramTile + 1));
     w.csc_scratch_bytes = layout == STRADS_LAYOUT_CSC ? csc_scratch_bytes(n, l, max_col_nnz) : 0;
     w.csc_scratch = take(w.csc_scratch_bytes ? w.csc_scratch_bytes : 256);
-    w.total = off;
+    w.lane_stride = off - w.lane_begin;
+    w.total = w.lane_begin + (size_t)S * w.lane_stride;
+    return w;
+}
+
+Workspace workspace_of_lane(const Workspace &w0, int32_t lane)
+{
+    Workspace w = w0;
+    const size_t d = (size_t)lane * w0.lane_stride;
+    size_t *per_lane[] = {&w.keys, &w.hist, &w.scalars, &w.sel, &w.bnd, &w.cand, &w.partial, &w.gram, &w.mask,
+                          &w.kept_pos, &w.kept, &w.z, &w.delta, &w.mv_col, &w.mv_delta, &w.rpart, &w.zc, &w.dc,
+                          &w.nbc, &w.mpos, &w.mcand, &w.mkept_pos, &w.dshape, &w.dtable, &w.csc_scratch};
+    for (size_t *f : per_lane) *f += d;
     return w;
 }
 
@@ -67,12 +85,17 @@ static bool sizes_ok(const strads_lasso_config_t *c)
     if (c->deps != STRADS_DEPS_STATIC && c->deps != STRADS_DEPS_DYNAMIC && c->deps != STRADS_DEPS_NONE) return false;
     if (c->priority != STRADS_PRIORITY_SQUARED && c->priority != STRADS_PRIORITY_LINEAR &&
         c->priority != STRADS_PRIORITY_UNIFORM) return false;
+    if (c->n_shards < 0 || c->n_shards > STRADS_MAX_SHARDS || (int64_t)c->n_shards > c->j) return false;
     return true;
 }
 
+static int32_t shard_count(const strads_lasso_config_t *c) { return c->n_shards > 1 ? c->n_shards : 1; }
+
+// candidates per round: P' clamped to the size of the smallest shard
 static int32_t clamp_l(const strads_lasso_config_t *c)
 {
-    return (int64_t)c->l_prime < c->j ? c->l_prime : (int32_t)c->j;
+    const int64_t smallest = c->j / shard_count(c);
+    return (int64_t)c->l_prime < smallest ? c->l_prime : (int32_t)smallest;
 }
 
 } // namespace strads
@@ -86,7 +109,8 @@ extern "C" {
 size_t strads_lasso_workspace_bytes(const strads_lasso_config_t *cfg)
 {
     if (!sizes_ok(cfg)) return 0;
-    return carve(cfg->n, cfg->j, cfg->layout, clamp_l(cfg), cfg->keep_gram, cfg->max_col_nnz, cfg->deps).total;
+    return carve(cfg->n, cfg->j, cfg->layout, clamp_l(cfg), cfg->keep_gram, cfg->max_col_nnz, cfg->deps,
+                 shard_count(cfg)).total;
 }
 
 int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
@@ -104,7 +128,8 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     if (((uintptr_t)cfg->x & 3u) != 0 || ((uintptr_t)cfg->y & 3u) != 0) return STRADS_E_INVALID_ARG;
 
     const int32_t L = clamp_l(cfg);
-    const Workspace ws = carve(cfg->n, cfg->j, cfg->layout, L, cfg->keep_gram, cfg->max_col_nnz, cfg->deps);
+    const int32_t S = shard_count(cfg);
+    const Workspace ws = carve(cfg->n, cfg->j, cfg->layout, L, cfg->keep_gram, cfg->max_col_nnz, cfg->deps, S);
     if (cfg->workspace_bytes < ws.total) return STRADS_E_WORKSPACE_TOO_SMALL;
 
     strads_lasso *h = (strads_lasso *)calloc(1, sizeof(strads_lasso));
@@ -126,32 +151,69 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->events = nullptr;
     h->vec4 = cfg->layout == STRADS_LAYOUT_DENSE_COLMAJOR && (cfg->n % 4 == 0) && (((uintptr_t)cfg->x & 15u) == 0);
 
-    if (sampler_prepare() != hipSuccess || gram_prepare() != hipSuccess || filter_prepare() != hipSuccess) { free(h); return STRADS_E_HIP; }
-    if (launch_init_state(h) != hipSuccess) {
-        free(h);
-        return STRADS_E_HIP;
+    h->n_lanes = S;
+    h->lane_id = 0;
+    h->lanes[0] = h;
+    int rc = STRADS_OK;
+    if (sampler_prepare() != hipSuccess || gram_prepare() != hipSuccess || filter_prepare() != hipSuccess ||
+        (cfg->layout == STRADS_LAYOUT_CSC && csc_prepare() != hipSuccess))
+        rc = STRADS_E_HIP;
+    // the other scheduler shards: same problem, own per-shard block of the workspace, own stream
+    for (int32_t s = 1; s < S && rc == STRADS_OK; ++s) {
+        strads_lasso *ln = (strads_lasso *)malloc(sizeof(strads_lasso));
+        if (!ln) { rc = STRADS_E_INVALID_ARG; break; }
+        *ln = *h;
+        ln->ws = workspace_of_lane(ws, s);
+        ln->lane_id = s;
+        ln->stream = nullptr;
+        ln->ev_resid = ln->ev_join = ln->ev_fork = nullptr;
+        h->lanes[s] = ln;
+        if (hipStreamCreateWithFlags(&ln->stream, hipStreamNonBlocking) != hipSuccess) rc = STRADS_E_HIP;
     }
-    if (cfg->deps == STRADS_DEPS_DYNAMIC) {
-        // Gram decomposition per mover-tile count, looked up by the mover kernel every round
-        gram_shape_table(cfg->n, h->Lpad, h->shape_table);
-        if (hipMemcpyAsync(h->base + ws.dtable, h->shape_table, sizeof(GramShape) * (size_t)(h->Lpad / kGramTile + 1),
-                           hipMemcpyHostToDevice, h->stream) != hipSuccess ||
-            hipStreamSynchronize(h->stream) != hipSuccess) {
-            free(h);
-            return STRADS_E_HIP;
+    for (int32_t s = 0; s < S && rc == STRADS_OK; ++s) {
+        strads_lasso *ln = h->lanes[s];
+        ln->Js = (cfg->j - s + S - 1) / S;
+        if (S > 1 && (hipEventCreateWithFlags(&ln->ev_resid, hipEventDisableTiming) != hipSuccess ||
+                      hipEventCreateWithFlags(&ln->ev_join, hipEventDisableTiming) != hipSuccess))
+            rc = STRADS_E_HIP;
+    }
+    if (rc == STRADS_OK && S > 1 && hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming) != hipSuccess)
+        rc = STRADS_E_HIP;
+
+    // everything below is enqueued on the caller's stream and waited for before create returns
+    if (rc == STRADS_OK && launch_init_state(h) != hipSuccess) rc = STRADS_E_HIP;
+    for (int32_t s = 0; s < S && rc == STRADS_OK; ++s) {
+        strads_lasso *ln = h->lanes[s];
+        if (s > 0 && (hipMemsetAsync(h->base + ln->ws.hist, 0, (size_t)2 * kHistBins * 4, h->stream) != hipSuccess ||
+                      hipMemsetAsync(h->base + ln->ws.scalars, 0, sizeof(RoundScalars), h->stream) != hipSuccess))
+            rc = STRADS_E_HIP;
+        if (rc == STRADS_OK && cfg->deps == STRADS_DEPS_DYNAMIC) {
+            // Gram decomposition per mover-tile count, looked up by the mover kernel every round
+            gram_shape_table(cfg->n, h->Lpad, h->shape_table);
+            if (hipMemcpyAsync(h->base + ln->ws.dtable, h->shape_table,
+                               sizeof(GramShape) * (size_t)(h->Lpad / kGramTile + 1), hipMemcpyHostToDevice,
+                               h->stream) != hipSuccess)
+                rc = STRADS_E_HIP;
+        }
+        if (rc == STRADS_OK && cfg->layout == STRADS_LAYOUT_CSC) {
+            // the sparse kernels size their buckets from max_col_nnz: col_ptr is checked against it
+            // (bad_input of shard 0 is read back below); every shard's counters start at zero
+            strads_lasso tmp = *ln;
+            tmp.stream = h->stream;
+            if (launch_csc_init(&tmp, &h->at<RoundScalars>(ln->ws.scalars)->bad_input) != hipSuccess) rc = STRADS_E_HIP;
         }
     }
-    if (cfg->layout == STRADS_LAYOUT_CSC) {
-        // the sparse kernels size their buckets from max_col_nnz: check col_ptr against it once
+    if (rc == STRADS_OK) {
         RoundScalars sc;
-        if (csc_prepare() != hipSuccess ||
-            launch_csc_init(h, &h->at<RoundScalars>(ws.scalars)->bad_input) != hipSuccess ||
-            hipMemcpyAsync(&sc, h->base + ws.scalars, sizeof(sc), hipMemcpyDeviceToHost, h->stream) != hipSuccess ||
-            hipStreamSynchronize(h->stream) != hipSuccess) {
-            free(h);
-            return STRADS_E_HIP;
-        }
-        if (sc.bad_input != 0) { free(h); return STRADS_E_INVALID_ARG; }
+        if (hipMemcpyAsync(&sc, h->base + ws.scalars, sizeof(sc), hipMemcpyDeviceToHost, h->stream) != hipSuccess ||
+            hipStreamSynchronize(h->stream) != hipSuccess)
+            rc = STRADS_E_HIP;
+        else if (sc.bad_input != 0)
+            rc = STRADS_E_INVALID_ARG;
+    }
+    if (rc != STRADS_OK) {
+        strads_lasso_destroy(h);
+        return rc;
     }
     *out = h;
     return STRADS_OK;
@@ -163,6 +225,15 @@ void strads_lasso_destroy(strads_lasso_t *h)
 {
     if (!h) return;
     drop_events(h);
+    for (int32_t s = 0; s < h->n_lanes; ++s) {
+        strads_lasso *ln = h->lanes[s];
+        if (!ln) continue;
+        if (s > 0 && ln->stream) { (void)hipStreamSynchronize(ln->stream); (void)hipStreamDestroy(ln->stream); }
+        if (ln->ev_resid) (void)hipEventDestroy(ln->ev_resid);
+        if (ln->ev_join) (void)hipEventDestroy(ln->ev_join);
+        if (s > 0) free(ln);
+    }
+    if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
     free(h);
 }
 
@@ -177,18 +248,27 @@ static inline int mark(strads_lasso *h, int boundary)
     return STRADS_OK;
 }
 
-#define MARK(b) do { const int rc_ = mark(h, (b)); if (rc_ != STRADS_OK) return rc_; } while (0)
-
-static int enqueue_round(strads_lasso *h)
+// Enqueue round h->round.  With S scheduler shards it is shard (round mod S)'s turn: its draw, Gram
+// and greedy walk go to its own stream and depend on nothing another shard does, so they overlap
+// with the other shards' work; whatever reads or writes the residual waits for the previous
+// round's residual update, so the updates are applied in round order (Section 3: the schedulers
+// prepare concurrently and take turns to dispatch).
+static int enqueue_round(strads_lasso *top)
 {
+    const int32_t S = top->n_lanes;
+    strads_lasso *h = top->lanes[top->round % S];
+    strads_lasso *prev = top->lanes[(top->round + S - 1) % S];
     const bool dense = h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR;
     const bool dynamic = h->cfg.deps == STRADS_DEPS_DYNAMIC;
     const bool unchecked = h->cfg.deps == STRADS_DEPS_NONE;
+#define MARK(b) do { const int rc_ = mark(top, (b)); if (rc_ != STRADS_OK) return rc_; } while (0)
+#define AFTER_PREVIOUS_ROUND() do { if (S > 1) HIP_TRY(hipStreamWaitEvent(h->stream, prev->ev_resid, 0)); } while (0)
     MARK(STRADS_STAGE_SAMPLER);
-    HIP_TRY(launch_sampler(h, h->round));
+    HIP_TRY(launch_sampler(h, top->round));
     MARK(STRADS_STAGE_CAND_DOTS);
     if (dynamic) {
         // every candidate's update from the current residual; the movers; how to tile their Gram
+        AFTER_PREVIOUS_ROUND();
         HIP_TRY(launch_dots_cand(h));
         HIP_TRY(launch_movers(h));
     }
@@ -201,14 +281,37 @@ static int enqueue_round(strads_lasso *h)
     else if (dynamic) HIP_TRY(launch_filter_movers(h));
     else HIP_TRY(launch_filter(h, h->L, true));
     MARK(STRADS_STAGE_UPDATE);
+    if (!dynamic) AFTER_PREVIOUS_ROUND();
     if (dynamic) HIP_TRY(launch_commit_dynamic(h));
     else if (dense) HIP_TRY(launch_dots_dense(h));
     else HIP_TRY(launch_dots_csc(h));
     MARK(STRADS_STAGE_RESIDUAL);
     if (dense) HIP_TRY(launch_residual_dense(h)); else HIP_TRY(launch_residual_csc(h));
     MARK(STRADS_N_STAGES);
-    if (h->profile_level != 0 && h->profiled < h->profile_rounds) h->profiled += 1;
-    h->round += 1;
+    if (S > 1) HIP_TRY(hipEventRecord(h->ev_resid, h->stream));
+#undef MARK
+#undef AFTER_PREVIOUS_ROUND
+    if (top->profile_level != 0 && top->profiled < top->profile_rounds) top->profiled += 1;
+    top->round += 1;
+    return STRADS_OK;
+}
+
+// The shards' streams start after everything already on the caller's stream ...
+static int fork_lanes(strads_lasso *h)
+{
+    if (h->n_lanes == 1) return STRADS_OK;
+    HIP_TRY(hipEventRecord(h->ev_fork, h->stream));
+    for (int32_t s = 1; s < h->n_lanes; ++s) HIP_TRY(hipStreamWaitEvent(h->lanes[s]->stream, h->ev_fork, 0));
+    return STRADS_OK;
+}
+
+// ... and the caller's stream continues after everything the shards were given.
+static int join_lanes(strads_lasso *h)
+{
+    for (int32_t s = 1; s < h->n_lanes; ++s) {
+        HIP_TRY(hipEventRecord(h->lanes[s]->ev_join, h->lanes[s]->stream));
+        HIP_TRY(hipStreamWaitEvent(h->stream, h->lanes[s]->ev_join, 0));
+    }
     return STRADS_OK;
 }
 
@@ -224,21 +327,44 @@ static void drop_events(strads_lasso *h)
     h->profiled = 0;
 }
 
-static int read_scalars(strads_lasso *h, RoundScalars *host)
+// Round scalars of shard `lane`, read on the caller's stream (which every enqueueing call leaves
+// ordered after the shards' streams).
+static int read_lane_scalars(strads_lasso *h, int32_t lane, RoundScalars *host)
 {
-    HIP_TRY(hipMemcpyAsync(host, h->base + h->ws.scalars, sizeof(RoundScalars), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(hipMemcpyAsync(host, h->base + h->lanes[lane]->ws.scalars, sizeof(RoundScalars), hipMemcpyDeviceToHost,
+                           h->stream));
     HIP_TRY(hipStreamSynchronize(h->stream));
+    return STRADS_OK;
+}
+
+static int read_scalars(strads_lasso *h, RoundScalars *host) { return read_lane_scalars(h, 0, host); }
+
+// the shard that ran the most recent round
+static int32_t last_lane(const strads_lasso *h) { return h->round > 0 ? (int32_t)((h->round - 1) % h->n_lanes) : 0; }
+
+static int total_updates(strads_lasso *h, unsigned long long *out)
+{
+    unsigned long long sum = 0;
+    for (int32_t s = 0; s < h->n_lanes; ++s) {
+        RoundScalars sc;
+        const int rs = read_lane_scalars(h, s, &sc);
+        if (rs != STRADS_OK) return rs;
+        sum += sc.updates_total;
+    }
+    *out = sum;
     return STRADS_OK;
 }
 
 int strads_lasso_round(strads_lasso_t *h, strads_round_info_t *info)
 {
     if (!h) return STRADS_E_INVALID_ARG;
-    const int rc = enqueue_round(h);
+    int rc = fork_lanes(h);
+    if (rc == STRADS_OK) rc = enqueue_round(h);
+    if (rc == STRADS_OK) rc = join_lanes(h);
     if (rc != STRADS_OK) return rc;
     if (info) {
         RoundScalars sc;
-        const int rs = read_scalars(h, &sc);
+        const int rs = read_lane_scalars(h, last_lane(h), &sc);
         if (rs != STRADS_OK) return rs;
         info->round = h->round - 1;
         info->n_cand = h->L;
@@ -283,18 +409,18 @@ int strads_lasso_run(strads_lasso_t *h, int64_t max_rounds, float kkt_tol, int32
     float viol = INFINITY;
     int converged = 0;
     // |B_1| is summed on the device; rounds between checks are only enqueued, never waited for
-    RoundScalars sc0;
-    { const int rs = read_scalars(h, &sc0); if (rs != STRADS_OK) return rs; }
+    unsigned long long upd0 = 0, upd1 = 0;
+    { const int rs = total_updates(h, &upd0); if (rs != STRADS_OK) return rs; }
     while (done < max_rounds) {
         int64_t burst = max_rounds - done;
         if (check_every > 0 && burst > check_every) burst = check_every;
-        for (int64_t i = 0; i < burst; ++i) {
-            const int rc = enqueue_round(h);
-            if (rc != STRADS_OK) return rc;
-        }
+        int rc = fork_lanes(h);
+        for (int64_t i = 0; i < burst && rc == STRADS_OK; ++i) rc = enqueue_round(h);
+        if (rc == STRADS_OK) rc = join_lanes(h);
+        if (rc != STRADS_OK) return rc;
         done += burst;
         if (check_every > 0) {
-            const int rc = strads_lasso_kkt(h, &viol, nullptr);
+            rc = strads_lasso_kkt(h, &viol, nullptr);
             if (rc != STRADS_OK) return rc;
             if (viol <= kkt_tol * h->cfg.lambda) { converged = 1; break; }
         }
@@ -302,11 +428,10 @@ int strads_lasso_run(strads_lasso_t *h, int64_t max_rounds, float kkt_tol, int32
     double obj = 0.0;
     const int rc = strads_lasso_objective(h, &obj);
     if (rc != STRADS_OK) return rc;
-    RoundScalars sc1;
-    { const int rs = read_scalars(h, &sc1); if (rs != STRADS_OK) return rs; }
+    { const int rs = total_updates(h, &upd1); if (rs != STRADS_OK) return rs; }
     if (out) {
         out->rounds_done = done;
-        out->updates_done = (int64_t)(sc1.updates_total - sc0.updates_total);
+        out->updates_done = (int64_t)(upd1 - upd0);
         out->objective = obj;
         out->kkt_violation = viol;
         out->converged = converged;
@@ -341,18 +466,23 @@ int strads_lasso_last_round(strads_lasso_t *h, int32_t *cand, int32_t *kept_pos,
 {
     if (!h) return STRADS_E_INVALID_ARG;
     if (gram_or_null && (!h->cfg.keep_gram || h->cfg.deps == STRADS_DEPS_NONE)) return STRADS_E_INVALID_ARG;
+    const int32_t lane = last_lane(h);
+    const Workspace &ws = h->lanes[lane]->ws;           // outputs of the shard that ran the round
     const size_t lb = (size_t)h->L * 4;
-    if (cand) HIP_TRY(hipMemcpyAsync(cand, h->base + h->ws.cand, lb, hipMemcpyDeviceToDevice, h->stream));
-    if (kept_pos) HIP_TRY(hipMemcpyAsync(kept_pos, h->base + h->ws.kept_pos, lb, hipMemcpyDeviceToDevice, h->stream));
-    if (z) HIP_TRY(hipMemcpyAsync(z, h->base + h->ws.z, lb, hipMemcpyDeviceToDevice, h->stream));
-    if (delta) HIP_TRY(hipMemcpyAsync(delta, h->base + h->ws.delta, lb, hipMemcpyDeviceToDevice, h->stream));
-    if (gram_or_null && h->cfg.deps == STRADS_DEPS_DYNAMIC)
-        HIP_TRY(launch_scatter_mover_gram(h, gram_or_null));
-    else if (gram_or_null)
-        HIP_TRY(hipMemcpy2DAsync(gram_or_null, lb, h->base + h->ws.gram, (size_t)h->Lpad * 4, lb, (size_t)h->L,
+    if (cand) HIP_TRY(hipMemcpyAsync(cand, h->base + ws.cand, lb, hipMemcpyDeviceToDevice, h->stream));
+    if (kept_pos) HIP_TRY(hipMemcpyAsync(kept_pos, h->base + ws.kept_pos, lb, hipMemcpyDeviceToDevice, h->stream));
+    if (z) HIP_TRY(hipMemcpyAsync(z, h->base + ws.z, lb, hipMemcpyDeviceToDevice, h->stream));
+    if (delta) HIP_TRY(hipMemcpyAsync(delta, h->base + ws.delta, lb, hipMemcpyDeviceToDevice, h->stream));
+    if (gram_or_null && h->cfg.deps == STRADS_DEPS_DYNAMIC) {
+        strads_lasso view = *h->lanes[lane];            // the shard's buffers, on the caller's stream
+        view.stream = h->stream;
+        HIP_TRY(launch_scatter_mover_gram(&view, gram_or_null));
+    } else if (gram_or_null) {
+        HIP_TRY(hipMemcpy2DAsync(gram_or_null, lb, h->base + ws.gram, (size_t)h->Lpad * 4, lb, (size_t)h->L,
                                  hipMemcpyDeviceToDevice, h->stream));
+    }
     RoundScalars sc;
-    const int rs = read_scalars(h, &sc);
+    const int rs = read_lane_scalars(h, lane, &sc);
     if (rs != STRADS_OK) return rs;
     if (n_cand) *n_cand = h->L;
     if (n_kept) *n_kept = sc.n_kept;
@@ -364,10 +494,12 @@ int strads_lasso_last_candidates(strads_lasso_t *h, float *z_cand, float *delta_
     if (!h) return STRADS_E_INVALID_ARG;
     if (h->cfg.deps != STRADS_DEPS_DYNAMIC) return STRADS_E_UNSUPPORTED;
     const size_t lb = (size_t)h->L * 4;
-    if (z_cand) HIP_TRY(hipMemcpyAsync(z_cand, h->base + h->ws.zc, lb, hipMemcpyDeviceToDevice, h->stream));
-    if (delta_cand) HIP_TRY(hipMemcpyAsync(delta_cand, h->base + h->ws.dc, lb, hipMemcpyDeviceToDevice, h->stream));
+    const int32_t lane = last_lane(h);
+    const Workspace &ws = h->lanes[lane]->ws;
+    if (z_cand) HIP_TRY(hipMemcpyAsync(z_cand, h->base + ws.zc, lb, hipMemcpyDeviceToDevice, h->stream));
+    if (delta_cand) HIP_TRY(hipMemcpyAsync(delta_cand, h->base + ws.dc, lb, hipMemcpyDeviceToDevice, h->stream));
     RoundScalars sc;
-    const int rs = read_scalars(h, &sc);
+    const int rs = read_lane_scalars(h, lane, &sc);
     if (rs != STRADS_OK) return rs;
     if (n_movers) *n_movers = sc.n_movers;
     return STRADS_OK;
@@ -404,7 +536,7 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
     if (strcmp(name, "gram_split_k") == 0) {
         if (value < 0 || value > h->split_max) return STRADS_E_INVALID_ARG;
         if (value != 0 && h->cfg.deps == STRADS_DEPS_DYNAMIC) return STRADS_E_UNSUPPORTED;   // chosen on the device
-        h->split_user = (int32_t)value;
+        for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->split_user = (int32_t)value;
         return STRADS_OK;
     }
     if (strcmp(name, "profile_rounds") == 0) {
@@ -414,6 +546,7 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
     }
     if (strcmp(name, "profile_level") == 0) {
         if (value < 0 || value > 2) return STRADS_E_INVALID_ARG;
+        if (value != 0 && h->n_lanes > 1) return STRADS_E_UNSUPPORTED;   // stages of different shards overlap
         HIP_TRY(hipStreamSynchronize(h->stream));
         const int32_t keep_rounds = h->profile_rounds;
         drop_events(h);
@@ -429,7 +562,7 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
     }
     if (strcmp(name, "select_cap") == 0) {
         if (value < 1 || value > 2 * STRADS_MAX_L_PRIME) return STRADS_E_INVALID_ARG;
-        h->select_cap = (int32_t)value;
+        for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->select_cap = (int32_t)value;
         return STRADS_OK;
     }
     return STRADS_E_INVALID_ARG;

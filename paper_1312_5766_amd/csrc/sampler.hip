@@ -143,16 +143,21 @@ __device__ __forceinline__ void wave_append(bool flag, uint64_t item, uint64_t *
 // ---------------------------------------------------------------------------------------------
 // pass 1: keys + histogram of the top 11 bits
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_keys_hist(const float *__restrict__ dbeta, uint32_t J, float eta,
-                                                   uint64_t seed, uint64_t t, int priority,
-                                                   uint32_t *__restrict__ keys, uint32_t *__restrict__ hist0)
+// Js coordinates of scheduler shard `shard` out of `shards`: position i of the shard is coordinate
+// j = i * shards + shard (one shard: j = i).  Keys are stored by position; the random number and
+// delta beta are those of coordinate j.
+__global__ __launch_bounds__(256) void k_keys_hist(const float *__restrict__ dbeta, uint32_t Js, uint32_t shards,
+                                                   uint32_t shard, float eta, uint64_t seed, uint64_t t,
+                                                   int priority, uint32_t *__restrict__ keys,
+                                                   uint32_t *__restrict__ hist0)
 {
     __shared__ uint32_t lh[kHistBins];
     for (int i = threadIdx.x; i < kHistBins; i += 256) lh[i] = 0;
     __syncthreads();
-    for (uint32_t j = blockIdx.x * 256u + threadIdx.x; j < J; j += gridDim.x * 256u) {
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < Js; i += gridDim.x * 256u) {
+        const uint32_t j = i * shards + shard;
         const uint32_t ok = orderable(priority_key(dbeta[j], eta, seed, t, j, priority));
-        keys[j] = ok;
+        keys[i] = ok;
         atomicAdd(&lh[ok >> 21], 1u);
     }
     __syncthreads();
@@ -193,14 +198,16 @@ constexpr int kCollectPerThread = 16;
 
 // pass 3: everything strictly above the 22-bit boundary prefix is selected; keys on the prefix
 // go to the boundary list.  Items are (orderable key << 32) | (2^32-1 - j): all distinct, and
-// larger item <=> (larger key, then smaller j).
+// larger item <=> (larger key, then smaller j).  Keys are indexed by position in the scheduler
+// shard; the item carries the coordinate itself (position * shards + shard).
 //
 // Every appended item needs a slot from one of two device-wide counters, and atomics on one
 // address are served one after the other (roughly 8 ns each), so a workgroup looks at
 // 256 * kCollectPerThread keys, counts first, and reserves its slots with ONE atomic per list.
-__global__ __launch_bounds__(256) void k_collect(const uint32_t *__restrict__ keys, uint32_t J,
-                                                 const uint32_t *__restrict__ hist1, RoundScalars *__restrict__ sc,
-                                                 uint64_t *__restrict__ sel, uint64_t *__restrict__ bnd)
+__global__ __launch_bounds__(256) void k_collect(const uint32_t *__restrict__ keys, uint32_t J, uint32_t shards,
+                                                 uint32_t shard, const uint32_t *__restrict__ hist1,
+                                                 RoundScalars *__restrict__ sc, uint64_t *__restrict__ sel,
+                                                 uint64_t *__restrict__ bnd)
 {
     __shared__ uint32_t tmp[258];
     __shared__ uint32_t wtot[2][4], wbase[2][4];
@@ -245,7 +252,7 @@ __global__ __launch_bounds__(256) void k_collect(const uint32_t *__restrict__ ke
     for (int q = 0; q < kCollectPerThread; ++q) {
         const uint32_t j = base + q * 64u;
         const uint32_t p = okv[q] >> 10;
-        const uint64_t item = ((uint64_t)okv[q] << 32) | (uint64_t)(0xFFFFFFFFu - j);
+        const uint64_t item = ((uint64_t)okv[q] << 32) | (uint64_t)(0xFFFFFFFFu - (j * shards + shard));
         if (j < J && p > p22) sel[base_gt++] = item;
         if (j < J && p == p22) bnd[base_eq++] = item;
     }
@@ -454,19 +461,25 @@ static inline int sampler_grid(int64_t J)
 
 hipError_t launch_sampler(strads_lasso *h, int64_t round)
 {
-    const uint32_t J = (uint32_t)h->cfg.j, L = (uint32_t)h->L;
-    const int g = sampler_grid(h->cfg.j);
+    const uint32_t J = (uint32_t)h->Js, L = (uint32_t)h->L;      // this shard's coordinates
+    const uint32_t S = (uint32_t)h->n_lanes, sh = (uint32_t)h->lane_id;
+    const int g = sampler_grid(h->Js);
     uint32_t *keys = h->at<uint32_t>(h->ws.keys);
     uint32_t *hist = h->at<uint32_t>(h->ws.hist);
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     uint64_t *sel = h->at<uint64_t>(h->ws.sel), *bnd = h->at<uint64_t>(h->ws.bnd);
-    hipLaunchKernelGGL(k_keys_hist, dim3(g), dim3(256), 0, h->stream, h->at<float>(h->ws.dbeta), J, h->cfg.eta,
+    hipLaunchKernelGGL(k_keys_hist, dim3(g), dim3(256), 0, h->stream, h->at<float>(h->ws.dbeta), J, S, sh, h->cfg.eta,
                        h->cfg.seed, (uint64_t)round, h->cfg.priority, keys, hist);
     hipLaunchKernelGGL(k_hist2, dim3(g), dim3(256), 0, h->stream, keys, J, L, hist, hist + kHistBins, sc);
-    const unsigned gc = (unsigned)((h->cfg.j + 256 * kCollectPerThread - 1) / (256 * kCollectPerThread));
-    hipLaunchKernelGGL(k_collect, dim3(gc), dim3(256), 0, h->stream, keys, J, hist + kHistBins, sc, sel, bnd);
+    const unsigned gc = (unsigned)((h->Js + 256 * kCollectPerThread - 1) / (256 * kCollectPerThread));
+    hipLaunchKernelGGL(k_collect, dim3(gc), dim3(256), 0, h->stream, keys, J, S, sh, hist + kHistBins, sc, sel, bnd);
+    // LDS of the final kernel: the 1024-item exchange buffer of the register sort, or the boundary
+    // list (at most `cap` items, padded to a power of two) when that is longer.  Kept small so the
+    // kernel can share a compute unit with another shard's Gram workgroups.
     const uint32_t cap = (uint32_t)h->select_cap;
-    const size_t lds = (size_t)(cap > 2u * STRADS_MAX_L_PRIME ? cap : 2u * STRADS_MAX_L_PRIME) * sizeof(uint64_t);
+    uint32_t items = 1024u;
+    while (items < cap) items <<= 1;
+    const size_t lds = (size_t)items * sizeof(uint64_t);
     hipLaunchKernelGGL(k_finalize, dim3(1), dim3(1024), lds, h->stream, sc, sel, bnd, L, (uint32_t)h->Lpad, cap,
                        h->at<int32_t>(h->ws.cand), hist);
     if (L > kRegSortMax) {

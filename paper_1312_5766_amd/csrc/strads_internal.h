@@ -22,7 +22,7 @@ constexpr int kGramKT = STRADS_GRAM_KT;   // K (row) extent of one LDS stage, fl
 constexpr int kGramOcc = STRADS_GRAM_OCC; // Gram workgroups resident per compute unit (LDS and registers allow it)
 constexpr int kMaxResidualGroups = 64; // column groups of the residual update
 constexpr int kObjBlocks = 256;        // workgroups of the objective reduction
-constexpr int kSelectCapDefault = 16384;
+constexpr int kSelectCapDefault = 4096;
 constexpr int kStageEvents = STRADS_N_STAGES + 1;
 
 // Device-side scalars of one round, kept in one small block of the workspace.
@@ -52,7 +52,8 @@ struct GramShape {
 };
 
 struct Workspace {
-    // offsets in bytes from the workspace base
+    // offsets in bytes from the workspace base.  beta, dbeta, r, objpart, objout are shared by all
+    // scheduler shards; everything else exists once per shard, lane_stride bytes apart.
     size_t beta, dbeta, r;
     size_t keys;            // uint32 [J]
     size_t hist;            // uint32 [2][kHistBins]
@@ -78,6 +79,7 @@ struct Workspace {
     size_t dtable;          // GramShape [STRADS_MAX_L_PRIME / kGramTile + 1], by number of tiles per side
     size_t csc_scratch;     // CSC only: see csc.hip
     size_t csc_scratch_bytes;
+    size_t lane_begin, lane_stride;   // the per-shard block of shard s starts at lane_begin + s * lane_stride
     size_t total;
 };
 
@@ -101,6 +103,14 @@ struct strads_lasso {
     int32_t profile_rounds;  // rounds the event pool can hold
     int32_t profiled;        // rounds recorded so far
     hipEvent_t *events;      // [profile_rounds][kStageEvents]
+    // scheduler shards (Section 3).  The handle the caller holds is shard 0 and owns the others.
+    int32_t n_lanes;         // S
+    int32_t lane_id;         // this handle's shard
+    int64_t Js;              // coordinates of this shard: #{j < J : j mod S == lane_id}
+    strads_lasso *lanes[STRADS_MAX_SHARDS];   // shard 0 only: [0] is the handle itself
+    hipEvent_t ev_resid;     // recorded after this shard's residual update
+    hipEvent_t ev_fork;      // shard 0 only: the caller's stream at the start of an enqueueing call
+    hipEvent_t ev_join;      // this shard's stream at the end of an enqueueing call
     strads::GramShape shape_table[STRADS_MAX_L_PRIME / strads::kGramTile + 1];   // host copy of ws.dtable
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(base + off); }
@@ -111,7 +121,9 @@ namespace strads {
 int gram_split_auto(int64_t n, int32_t lpad);
 size_t gram_partial_floats(int64_t n, int32_t lpad, bool dynamic);   // floats of K-slice partial tiles to reserve
 void gram_shape_table(int64_t n, int32_t lpad, GramShape *out);      // out[t], t = 0 .. lpad/kGramTile
-Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram, int32_t max_col_nnz, int32_t deps);
+Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram, int32_t max_col_nnz, int32_t deps,
+                int32_t n_shards);
+Workspace workspace_of_lane(const Workspace &w0, int32_t lane);
 
 // Each launcher enqueues on h->stream and returns the hipError_t of the launch.
 hipError_t launch_sampler(strads_lasso *h, int64_t round);                 // Step 1 -> cand[L]
@@ -131,6 +143,7 @@ hipError_t launch_residual_dense(strads_lasso *h);                         // r 
 hipError_t launch_objective(strads_lasso *h);                              // -> objout
 hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null);            // -> scalars.kkt_max_bits
 hipError_t launch_init_state(strads_lasso *h);
+hipError_t launch_init_lane(strads_lasso *h);             // zero a shard's histograms and round scalars
 hipError_t launch_clear_kkt(strads_lasso *h);
 hipError_t sampler_prepare();
 hipError_t gram_prepare();

@@ -43,6 +43,16 @@ def _np(t):
     return t.detach().cpu().numpy()
 
 
+def _ref_candidates(o, dbeta, t):
+    """Step 1 from the oracle's stage functions.  With S scheduler shards the candidates of round t are
+    the full draw order restricted to shard t mod S (pinned in tests/test_oracle_shards.py)."""
+    keys = orc.priority_keys(dbeta, o.eta, o.seed, t, o.priority)
+    if o.n_shards == 1:
+        return orc.draw(keys, o.l_prime)
+    full = orc.draw(keys, o.J)
+    return full[full % o.n_shards == t % o.n_shards][:o.l_prime]
+
+
 def _assert_close(got, ref, rtol, atol, what):
     got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
     err = np.abs(got - ref) - (rtol * np.abs(ref) + atol)
@@ -57,7 +67,7 @@ def _check_round(g, o, log, teacher_forced=True):
     lr = g.last_round(want_gram=True)
     lc = g.last_candidates()
     cand, kept_pos = _np(lr["cand"]), _np(lr["kept_pos"])
-    ref_cand = orc.draw(orc.priority_keys(dbeta0, o.eta, o.seed, t0, o.priority), o.l_prime)
+    ref_cand = _ref_candidates(o, dbeta0, t0)
     assert np.array_equal(cand, ref_cand), f"candidate list differs (round {t0})"
     L = len(cand)
     rn = max(float(np.linalg.norm(r0.astype(np.float64))), 1.0)

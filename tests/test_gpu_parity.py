@@ -49,6 +49,16 @@ def _np(t):
     return t.detach().cpu().numpy()
 
 
+def _ref_candidates(o, dbeta, t):
+    """Step 1 from the oracle's stage functions.  With S scheduler shards the candidates of round t are
+    the full draw order restricted to shard t mod S (pinned in tests/test_oracle_shards.py)."""
+    keys = orc.priority_keys(dbeta, o.eta, o.seed, t, o.priority)
+    if o.n_shards == 1:
+        return orc.draw(keys, o.l_prime)
+    full = orc.draw(keys, o.J)
+    return full[full % o.n_shards == t % o.n_shards][:o.l_prime]
+
+
 def _assert_close(got, ref, rtol, atol, what):
     got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
     err = np.abs(got - ref) - (rtol * np.abs(ref) + atol)
@@ -67,8 +77,7 @@ def _check_round(g, o, log, teacher_forced):
     cand, kept_pos = _np(lr["cand"]), _np(lr["kept_pos"])
     # Step 1: candidate list, set and order, bit-exact (from the oracle's own delta-beta in
     # teacher-forced mode; from the GPU's delta-beta otherwise, which the oracle has followed)
-    keys = orc.priority_keys(dbeta0, o.eta, o.seed, t0, o.priority)
-    ref_cand = orc.draw(keys, o.l_prime)
+    ref_cand = _ref_candidates(o, dbeta0, t0)
     if not np.array_equal(cand, ref_cand):
         # admissible only if delta-beta differs in the last bits between the two sides
         assert not teacher_forced, "candidate list differs on identical delta-beta"
