@@ -71,6 +71,9 @@ def main() -> int:
                     help="> 0: --steps is an upper bound and the run stops once the optimality violation is "
                          "<= kkt_tol * lambda, tested every --check-every rounds (each test streams X once)")
     ap.add_argument("--check-every", type=int, default=25)
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the extra legs that time the same workload with 4 scheduler shards and with "
+                         "dynamic dependencies (reported under 'variants'; the headline value is unaffected)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="after the timed region run one elementwise kernel of known traffic (reads 1 GiB, "
                          "writes 1 GiB) so that a rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command "
@@ -153,6 +156,37 @@ def main() -> int:
     kkt_bytes = 4.0 * p.n * p.j if p.layout == "dense" else 8.0 * float(p.values.numel())
     kkt_gbps = kkt_bytes / (kkt_ms * 1e-3) / 1e9
 
+    # the same workload and round count under the two widenings of the schedule (not the headline)
+    variants = None
+    headline = (args.deps == "static" and args.shards == 1 and args.priority == "squared" and args.kkt_tol == 0
+                and args.p_max == 0)
+    if headline and not args.no_variants:
+        variants = {}
+        legs = {"shards4": dict(n_shards=4), "dynamic": dict(dynamic=True)}
+        if p.layout != "dense":
+            del legs["dynamic"]
+        for name, extra in legs.items():
+            kw = dict(y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed, **extra)
+            if p.layout == "dense":
+                v = pk.StradsLasso(x=p.x, **kw)
+            else:
+                v = pk.StradsLasso(values=p.values, row_idx=p.row_idx, col_ptr=p.col_ptr, n=p.n, **kw)
+            v.run(min(args.warmup, 10))
+            v.close()
+            if p.layout == "dense":
+                v = pk.StradsLasso(x=p.x, **kw)
+            else:
+                v = pk.StradsLasso(values=p.values, row_idx=p.row_idx, col_ptr=p.col_ptr, n=p.n, **kw)
+            torch.cuda.synchronize()
+            tv = time.perf_counter()
+            iv = v.run(args.steps)
+            torch.cuda.synchronize()
+            wv = time.perf_counter() - tv
+            variants[name] = {"value": round(int(iv.updates_done) / wv, 1), "unit": "updates/s",
+                              "ms_per_step": round(wv / max(args.steps, 1) * 1e3, 4), "updates": int(iv.updates_done),
+                              "objective_end": float(iv.objective)}
+            v.close()
+
     if args.pmc_calibration:
         a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         b = torch.empty_like(a)
@@ -211,6 +245,7 @@ def main() -> int:
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(kkt_gbps / HBM_PEAK_GBPS, 4)},
         "stage_ms": {k: round(v, 5) for k, v in stage.items() if k != "rounds"},
         "cpu_baseline": cpu,
+        "variants": variants,
         "input_generation_s": round(t_gen, 2),
     }
     print(json.dumps(out))
