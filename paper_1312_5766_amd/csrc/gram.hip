@@ -366,10 +366,21 @@ __global__ __launch_bounds__(256, kGramOcc) void k_gram_tiles_dyn(const float *_
     }
 }
 
+// bit k of a 16-bit value -> bit 4k of the result
+__device__ __forceinline__ uint64_t spread_every_4th(uint64_t x)
+{
+    x = (x | (x << 24)) & 0x000000FF000000FFull;
+    x = (x | (x << 12)) & 0x000F000F000F000Full;
+    x = (x | (x << 6)) & 0x0303030303030303ull;
+    x = (x | (x << 3)) & 0x1111111111111111ull;
+    return x;
+}
+
 // Sum the K-slices in slice order and emit the conflict bits (and, optionally, the fp32 Gram).
-// One thread per (row a, column b) with b in the tiles at or right of a's diagonal tile; 64
-// consecutive b per wavefront make one 64-bit mask word.  gdev != NULL: the shape is read from
-// device memory (dynamic dependencies) and the grid strides over it.
+// A thread owns 4 consecutive columns b of one row a (16-byte loads of every slice), a wavefront
+// 256 columns = four 64-bit mask words, assembled from one ballot per column-in-thread; only
+// columns in the tiles at or right of a's diagonal tile exist.  gdev != NULL: the shape is read
+// from device memory (dynamic dependencies) and the grid strides over it.
 __global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, GramShape gh,
                                                    const GramShape *__restrict__ gdev, float rho,
                                                    uint64_t *__restrict__ mask, float *__restrict__ gram,
@@ -378,26 +389,49 @@ __global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, 
     const GramShape g = gdev ? *gdev : gh;
     const int32_t L = g.L, Lpad = g.Lpad;
     const int64_t plane = (int64_t)Lpad * Lpad;
+    const int lane = threadIdx.x & 63;
     for (int32_t a = blockIdx.y; a < Lpad; a += gridDim.y) {
         const int32_t first = (a / kGramTile) * kGramTile;  // first column of a's diagonal tile
-        for (int32_t b = blockIdx.x * 256 + threadIdx.x; b < Lpad; b += gridDim.x * 256) {
-            if (b < first) continue;                        // uniform per wavefront (both are multiples of 64)
-            const int32_t split = b < first + kGramTile ? g.split_diag : g.split_off;
-            float v = 0.f;
-            for (int32_t s = 0; s < split; ++s) v += P[s * plane + (int64_t)a * Lpad + b];
-            const bool live = a < L && b < L && a != b;
-            const float ag = fabsf(v);
-            const bool conflict = live && !(ag < rho);
-            const uint64_t w = __ballot(conflict);
-            if ((threadIdx.x & 63) == 0) mask[(int64_t)a * (Lpad / 64) + (b >> 6)] = w;
-            if (near_pairs) {
-                const bool nr = live && b > a && fabsf(ag - rho) <= 1e-6f;
-                const uint64_t m = __ballot(nr);
-                if (m && (threadIdx.x & 63) == 0) atomicAdd(near_pairs, (int32_t)__popcll(m));
+        for (int32_t b0 = (blockIdx.x * 256 + (threadIdx.x & ~63)) * 4; b0 < Lpad; b0 += gridDim.x * 1024) {
+            // b0: first column of this wavefront's 256; Lpad is a multiple of 128, so a wavefront is
+            // either fully inside or half inside (its first 128 columns)
+            if (b0 + 256 <= first) continue;                // uniform per wavefront
+            const int32_t b = b0 + 4 * lane;
+            const bool have = b >= first && b < Lpad;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (have) {
+                const int32_t split = b < first + kGramTile ? g.split_diag : g.split_off;
+                const float *p = P + (int64_t)a * Lpad + b;
+                for (int32_t s = 0; s < split; ++s) {
+                    const float4 q = *reinterpret_cast<const float4 *>(p + s * plane);
+                    v[0] += q.x; v[1] += q.y; v[2] += q.z; v[3] += q.w;
+                }
             }
-            if (gram) {
-                gram[(int64_t)a * Lpad + b] = v;
-                if (b >= first + kGramTile) gram[(int64_t)b * Lpad + a] = v;   // mirror the tiles right of the diagonal
+            uint64_t B[4];
+            uint32_t n_near = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bool live = have && a < L && b + c < L && a != b + c;
+                const float ag = fabsf(v[c]);
+                B[c] = __ballot(live && !(ag < rho));
+                if (near_pairs) n_near += (uint32_t)__popcll(__ballot(live && b + c > a && fabsf(ag - rho) <= 1e-6f));
+            }
+            if (lane < 4) {
+                const int32_t wb = b0 + 64 * lane;          // first column of mask word `lane` of this wavefront
+                if (wb >= first && wb < Lpad) {
+                    uint64_t w = 0;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) w |= spread_every_4th((B[c] >> (16 * lane)) & 0xFFFFull) << c;
+                    mask[(int64_t)a * (Lpad / 64) + (wb >> 6)] = w;
+                }
+            }
+            if (near_pairs && n_near && lane == 0) atomicAdd(near_pairs, (int32_t)n_near);
+            if (gram && have) {
+                *reinterpret_cast<float4 *>(gram + (int64_t)a * Lpad + b) = make_float4(v[0], v[1], v[2], v[3]);
+                if (b >= first + kGramTile) {               // mirror the tiles right of the diagonal
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) gram[(int64_t)(b + c) * Lpad + a] = v[c];
+                }
             }
         }
     }
@@ -583,8 +617,8 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
     float *P = h->at<float>(h->ws.partial);
     if (part == 1) {
         RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
-        dim3 grid((h->Lpad + 255) / 256, h->Lpad);
-        if (dynamic) { if (grid.x > 4) grid.x = 4; if (grid.y > 1024) grid.y = 1024; }
+        dim3 grid((h->Lpad + 1023) / 1024, h->Lpad);       // 1024 columns of one row per workgroup
+        if (dynamic) { if (grid.x > 2) grid.x = 2; if (grid.y > 2048) grid.y = 2048; }
         hipLaunchKernelGGL(k_gram_mask, grid, dim3(256), 0, h->stream, P, g, gdev, h->cfg.rho,
                            h->at<uint64_t>(h->ws.mask), h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr,
                            &sc->near_rho_pairs);
