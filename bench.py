@@ -59,7 +59,7 @@ def main() -> int:
     ap.add_argument("--split-k", type=int, default=0)
     ap.add_argument("--deps", default="static", choices=("static", "dynamic", "none"),
                     help="dependency rule of Step 2: static = Algorithm 1 as printed (the headline workload); "
-                         "dynamic = only pairs of candidates that both move are checked (dense designs); "
+                         "dynamic = only pairs of candidates that both move are checked; "
                          "none = no check (Shotgun when combined with --priority uniform)")
     ap.add_argument("--priority", default="squared", choices=("squared", "linear", "uniform"),
                     help="weight of Step 1's draw: (delta beta)^2+eta (headline), |delta beta|+eta, or 1")
@@ -163,8 +163,6 @@ def main() -> int:
     if headline and not args.no_variants:
         variants = {}
         legs = {"shards4": dict(n_shards=4), "dynamic": dict(dynamic=True)}
-        if p.layout != "dense":
-            del legs["dynamic"]
         for name, extra in legs.items():
             kw = dict(y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed, **extra)
             if p.layout == "dense":

@@ -106,7 +106,7 @@ typedef struct {
                                      4*L^2 bytes of workspace and one extra write per round) */
     int32_t        max_col_nnz;   /* CSC only: an upper bound (>= 1) on the nonzeros of any column;
                                      sizes the per-round inverted index; checked at create */
-    int32_t        deps;          /* STRADS_DEPS_*: dependency rule of Step 2 (dynamic: dense designs only) */
+    int32_t        deps;          /* STRADS_DEPS_*: dependency rule of Step 2 */
     int32_t        priority;      /* STRADS_PRIORITY_*: weight of Step 1's draw */
     int32_t        n_shards;      /* S scheduler shards taking turns (Section 3): coordinate j belongs to
                                      shard j mod S for good, round t is shard (t mod S)'s turn and draws its

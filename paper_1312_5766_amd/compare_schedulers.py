@@ -50,8 +50,6 @@ def main() -> int:
         "static-corr": dict(priority="uniform"),
         "shotgun": dict(priority="uniform", no_deps=True, p_max=args.shotgun_p),
     }
-    if p.layout != "dense":
-        del modes["strads-dynamic"]
     for name, kw in modes.items():
         g = pk.StradsLasso(**base, **kw)
         g.round()                               # first-launch costs stay out of the clock

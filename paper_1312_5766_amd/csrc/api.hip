@@ -116,7 +116,6 @@ size_t strads_lasso_workspace_bytes(const strads_lasso_config_t *cfg)
 int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
 {
     if (!out || !sizes_ok(cfg)) return STRADS_E_INVALID_ARG;
-    if (cfg->deps == STRADS_DEPS_DYNAMIC && cfg->layout != STRADS_LAYOUT_DENSE_COLMAJOR) return STRADS_E_UNSUPPORTED;
     if (!cfg->x || !cfg->y || !cfg->workspace) return STRADS_E_INVALID_ARG;
     if (cfg->layout == STRADS_LAYOUT_CSC && (!cfg->row_idx || !cfg->col_ptr)) return STRADS_E_INVALID_ARG;
     if (!(cfg->lambda >= 0.f) || !isfinite(cfg->lambda)) return STRADS_E_INVALID_ARG;
@@ -269,7 +268,7 @@ static int enqueue_round(strads_lasso *top)
     if (dynamic) {
         // every candidate's update from the current residual; the movers; how to tile their Gram
         AFTER_PREVIOUS_ROUND();
-        HIP_TRY(launch_dots_cand(h));
+        if (dense) HIP_TRY(launch_dots_cand(h)); else HIP_TRY(launch_dots_cand_csc(h));
         HIP_TRY(launch_movers(h));
     }
     MARK(STRADS_STAGE_GRAM_TILES);

@@ -81,9 +81,13 @@ __global__ __launch_bounds__(256) void k_csc_zero(uint32_t *__restrict__ cnt, lo
 // ---------------------------------------------------------------------------------------------
 // inverted index of the candidate set
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void k_csc_count(const int32_t *__restrict__ cand, const int64_t *__restrict__ col_ptr,
+// n_dev != NULL (dynamic dependencies): the list is the movers, counted on the device; workgroups
+// past the count have nothing to do.
+__global__ __launch_bounds__(64) void k_csc_count(const int32_t *__restrict__ cand, const GramShape *__restrict__ n_dev,
+                                                  const int64_t *__restrict__ col_ptr,
                                                   const int32_t *__restrict__ row_idx, uint32_t *__restrict__ cnt)
 {
+    if (n_dev && (int32_t)blockIdx.x >= n_dev->L) return;
     const int32_t j = cand[blockIdx.x];
     const int64_t p0 = col_ptr[j], p1 = col_ptr[j + 1];
     for (int64_t p = p0 + threadIdx.x; p < p1; p += 64) atomicAdd(&cnt[row_idx[p]], 1u);
@@ -141,11 +145,13 @@ __global__ __launch_bounds__(1024) void k_csc_scan_add(int64_t N, int32_t n_chun
 
 // place (candidate, value) into its row's bucket; the count doubles as a countdown cursor, so it is
 // back at zero when the pass ends
-__global__ __launch_bounds__(64) void k_csc_fill(const int32_t *__restrict__ cand, const int64_t *__restrict__ col_ptr,
+__global__ __launch_bounds__(64) void k_csc_fill(const int32_t *__restrict__ cand, const GramShape *__restrict__ n_dev,
+                                                 const int64_t *__restrict__ col_ptr,
                                                  const int32_t *__restrict__ row_idx, const float *__restrict__ val,
                                                  const uint32_t *__restrict__ row_start, uint32_t *__restrict__ cnt,
                                                  CscEntry *__restrict__ entries)
 {
+    if (n_dev && (int32_t)blockIdx.x >= n_dev->L) return;
     const int32_t a = blockIdx.x;
     const int32_t j = cand[a];
     const int64_t p0 = col_ptr[j], p1 = col_ptr[j + 1];
@@ -160,7 +166,8 @@ __global__ __launch_bounds__(64) void k_csc_fill(const int32_t *__restrict__ can
 }
 
 // G[a][*] for candidate a = blockIdx.x, conflict bits for the words at or right of a's 128-tile
-__global__ __launch_bounds__(256) void k_csc_gram(const int32_t *__restrict__ cand, const int64_t *__restrict__ col_ptr,
+__global__ __launch_bounds__(256) void k_csc_gram(const int32_t *__restrict__ cand, const GramShape *__restrict__ n_dev,
+                                                  const int64_t *__restrict__ col_ptr,
                                                   const int32_t *__restrict__ row_idx, const float *__restrict__ val,
                                                   const uint32_t *__restrict__ row_start,
                                                   const CscEntry *__restrict__ entries, int32_t L, int32_t Lpad,
@@ -168,7 +175,9 @@ __global__ __launch_bounds__(256) void k_csc_gram(const int32_t *__restrict__ ca
                                                   int32_t *__restrict__ near_pairs)
 {
     extern __shared__ long long acc[];            // [Lpad]
+    if (n_dev) L = n_dev->L;                      // the movers only; rows past the count are never read
     const int32_t a = blockIdx.x;
+    if (a >= L && n_dev) return;
     const int tid = threadIdx.x;
     const int32_t first = (a / kGramTile) * kGramTile;
     for (int32_t b = tid; b < Lpad; b += 256) acc[b] = 0;
@@ -242,6 +251,29 @@ __global__ __launch_bounds__(256) void k_csc_dots_update(const float *__restrict
         delta[c] = d;
         beta[j] = nb;
         dbeta[j] = fabsf(d);
+    }
+}
+
+// Dynamic dependencies: x_j^T r and the tentative update of every candidate (nothing is committed).
+__global__ __launch_bounds__(256) void k_csc_dots_cand(const float *__restrict__ val,
+                                                       const int32_t *__restrict__ row_idx,
+                                                       const int64_t *__restrict__ col_ptr,
+                                                       const int32_t *__restrict__ cand, int32_t L,
+                                                       const float *__restrict__ r, float lambda,
+                                                       const float *__restrict__ beta, float *__restrict__ zc,
+                                                       float *__restrict__ dc, float *__restrict__ nbc)
+{
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (c >= L) return;
+    const int32_t j = cand[c];
+    const float s = sparse_dot(val, row_idx, col_ptr[j], col_ptr[j + 1], r, threadIdx.x & 63);
+    if ((threadIdx.x & 63) == 0) {
+        const float b = beta[j];
+        const float m = fabsf(s + b) - lambda;
+        const float nb = m > 0.f ? copysignf(m, s + b) : 0.f;
+        zc[c] = s;
+        nbc[c] = nb;
+        dc[c] = nb - b;
     }
 }
 
@@ -335,20 +367,33 @@ hipError_t launch_csc_init(strads_lasso *h, uint32_t *bad_dev)
 hipError_t launch_gram_csc(strads_lasso *h)
 {
     const CscScratch s = csc_carve(h);
-    const int32_t *cand = h->at<int32_t>(h->ws.cand);
+    // dynamic dependencies: the list is the movers and its length lives on the device
+    const bool dynamic = h->cfg.deps == STRADS_DEPS_DYNAMIC;
+    const int32_t *cand = dynamic ? h->at<int32_t>(h->ws.mcand) : h->at<int32_t>(h->ws.cand);
+    const GramShape *n_dev = dynamic ? h->at<GramShape>(h->ws.dshape) : nullptr;
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
-    hipLaunchKernelGGL(k_csc_count, dim3(h->L), dim3(64), 0, h->stream, cand, h->cfg.col_ptr, h->cfg.row_idx, s.cnt);
+    hipLaunchKernelGGL(k_csc_count, dim3(h->L), dim3(64), 0, h->stream, cand, n_dev, h->cfg.col_ptr, h->cfg.row_idx,
+                       s.cnt);
     const int32_t n_chunks = (int32_t)((h->cfg.n + kScanChunk - 1) / kScanChunk);
     hipLaunchKernelGGL(k_csc_scan_local, dim3(n_chunks), dim3(1024), 0, h->stream, s.cnt, h->cfg.n, s.row_start,
                        s.chunk_total);
     hipLaunchKernelGGL(k_csc_scan_add, dim3(n_chunks), dim3(1024), 0, h->stream, h->cfg.n, n_chunks, s.row_start,
                        s.chunk_total);
-    hipLaunchKernelGGL(k_csc_fill, dim3(h->L), dim3(64), 0, h->stream, cand, h->cfg.col_ptr, h->cfg.row_idx, h->cfg.x,
-                       s.row_start, s.cnt, s.entries);
-    hipLaunchKernelGGL(k_csc_gram, dim3(h->L), dim3(256), (size_t)h->Lpad * 8, h->stream, cand, h->cfg.col_ptr,
+    hipLaunchKernelGGL(k_csc_fill, dim3(h->L), dim3(64), 0, h->stream, cand, n_dev, h->cfg.col_ptr, h->cfg.row_idx,
+                       h->cfg.x, s.row_start, s.cnt, s.entries);
+    hipLaunchKernelGGL(k_csc_gram, dim3(h->L), dim3(256), (size_t)h->Lpad * 8, h->stream, cand, n_dev, h->cfg.col_ptr,
                        h->cfg.row_idx, h->cfg.x, s.row_start, s.entries, h->L, h->Lpad, h->cfg.rho,
                        h->at<uint64_t>(h->ws.mask), h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr,
                        &sc->near_rho_pairs);
+    return hipGetLastError();
+}
+
+hipError_t launch_dots_cand_csc(strads_lasso *h)
+{
+    hipLaunchKernelGGL(k_csc_dots_cand, dim3((h->L + 3) / 4), dim3(256), 0, h->stream, h->cfg.x, h->cfg.row_idx,
+                       h->cfg.col_ptr, h->at<int32_t>(h->ws.cand), h->L, h->at<float>(h->ws.r), h->cfg.lambda,
+                       h->at<float>(h->ws.beta), h->at<float>(h->ws.zc), h->at<float>(h->ws.dc),
+                       h->at<float>(h->ws.nbc));
     return hipGetLastError();
 }
 

@@ -537,7 +537,7 @@ static GramShape gram_shape(const strads_lasso *h)
 // order and look up the decomposition of their Gram.  One workgroup of 1024 threads walks the
 // candidate positions 1024 at a time (coalesced reads, wavefront ballots for the ordered offsets).
 __global__ __launch_bounds__(1024) void k_movers(const float *__restrict__ dc, const int32_t *__restrict__ cand,
-                                                 int32_t L, const GramShape *__restrict__ table,
+                                                 int32_t L, const GramShape *__restrict__ table, int32_t lpad_fixed,
                                                  int32_t *__restrict__ mpos, int32_t *__restrict__ mcand,
                                                  RoundScalars *__restrict__ sc, GramShape *__restrict__ gout)
 {
@@ -563,9 +563,16 @@ __global__ __launch_bounds__(1024) void k_movers(const float *__restrict__ dc, c
         __syncthreads();                                // wtot is reused by the next pass
     }
     if (tid == 0) {
-        // the decomposition depends on the mover count only through the number of tiles: the host
-        // tabulated it per tile count when the handle was created
-        GramShape g = table[(base + kGramTile - 1) / kGramTile];
+        // dense designs: the decomposition depends on the mover count only through the number of
+        // tiles, and the host tabulated it per tile count when the handle was created.  CSC designs
+        // have no tiles: only the count is needed, the conflict rows keep the full row width.
+        GramShape g;
+        if (table) {
+            g = table[(base + kGramTile - 1) / kGramTile];
+        } else {
+            g.Lpad = lpad_fixed; g.T = lpad_fixed / kGramTile; g.split_off = g.split_diag = 1; g.pad_ = 0;
+            g.kchunk_off = g.kchunk_diag = 0;
+        }
         g.L = (int32_t)base;
         sc->n_movers = (int32_t)base;
         *gout = g;
@@ -579,8 +586,10 @@ void gram_shape_table(int64_t n, int32_t lpad, GramShape *out)
 
 hipError_t launch_movers(strads_lasso *h)
 {
+    const bool dense = h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR;
     hipLaunchKernelGGL(k_movers, dim3(1), dim3(1024), 0, h->stream, h->at<float>(h->ws.dc),
-                       h->at<int32_t>(h->ws.cand), h->L, h->at<GramShape>(h->ws.dtable), h->at<int32_t>(h->ws.mpos),
+                       h->at<int32_t>(h->ws.cand), h->L, dense ? h->at<GramShape>(h->ws.dtable) : nullptr,
+                       dense ? 0 : h->Lpad, h->at<int32_t>(h->ws.mpos),
                        h->at<int32_t>(h->ws.mcand), h->at<RoundScalars>(h->ws.scalars),
                        h->at<GramShape>(h->ws.dshape));
     return hipGetLastError();

@@ -151,6 +151,7 @@ hipError_t filter_prepare();
 // CSC design
 hipError_t launch_gram_csc(strads_lasso *h);
 hipError_t launch_dots_csc(strads_lasso *h);
+hipError_t launch_dots_cand_csc(strads_lasso *h);         // dynamic dependencies: all candidates, nothing committed
 hipError_t launch_residual_csc(strads_lasso *h);
 hipError_t launch_kkt_csc(strads_lasso *h, float *g_or_null);
 size_t csc_scratch_bytes(int64_t n, int32_t l, int32_t max_col_nnz);

@@ -34,8 +34,14 @@ def _pair(p, keep_gram=True, dynamic=True, **kw):
     dev = torch.device("cuda:0")
     args = dict(lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
     args.update(kw)
-    g = pk.StradsLasso(x=p.x.to(dev), y=p.y.to(dev), keep_gram=keep_gram, dynamic=dynamic, **args)
-    o = OracleLasso(x=p.x.cpu().numpy(), y=p.y.cpu().numpy(), dynamic=dynamic, **args)
+    if p.layout == "dense":
+        g = pk.StradsLasso(x=p.x.to(dev), y=p.y.to(dev), keep_gram=keep_gram, dynamic=dynamic, **args)
+        o = OracleLasso(x=p.x.cpu().numpy(), y=p.y.cpu().numpy(), dynamic=dynamic, **args)
+    else:
+        g = pk.StradsLasso(values=p.values.to(dev), row_idx=p.row_idx.to(dev), col_ptr=p.col_ptr.to(dev), n=p.n,
+                           y=p.y.to(dev), keep_gram=keep_gram, dynamic=dynamic, **args)
+        o = OracleLasso(values=p.values.cpu().numpy(), row_idx=p.row_idx.cpu().numpy(),
+                        col_ptr=p.col_ptr.cpu().numpy(), n=p.n, y=p.y.cpu().numpy(), dynamic=dynamic, **args)
     return g, o
 
 
@@ -73,8 +79,11 @@ def _check_round(g, o, log, teacher_forced=True):
     rn = max(float(np.linalg.norm(r0.astype(np.float64))), 1.0)
 
     # every candidate's dot product and tentative change
-    X64 = o.x[cand].astype(np.float64)
-    z_ref = X64 @ r0.astype(np.float64)
+    if o.csc:
+        z_ref = np.array([float(np.dot(o.x[o.col_ptr[j]:o.col_ptr[j + 1]].astype(np.float64),
+                                       r0[o.row_idx[o.col_ptr[j]:o.col_ptr[j + 1]]].astype(np.float64))) for j in cand])
+    else:
+        z_ref = o.x[cand].astype(np.float64) @ r0.astype(np.float64)
     z_gpu, d_gpu = _np(lc["z_cand"]), _np(lc["delta_cand"])
     _assert_close(z_gpu, z_ref, DOT_RTOL, 1e-6 * rn, f"candidate dots (round {t0})")
     mover_gpu = d_gpu != 0
@@ -94,7 +103,7 @@ def _check_round(g, o, log, teacher_forced=True):
     Ggpu = _np(lr["G"])
     assert np.all(Ggpu[~mover_gpu, :] == 0) and np.all(Ggpu[:, ~mover_gpu] == 0)
     mm = np.ix_(mover_gpu, mover_gpu)
-    Gref_full = orc.gram_dense(o.x, cand)
+    Gref_full = orc.gram_csc(o.x, o.row_idx, o.col_ptr, cand) if o.csc else orc.gram_dense(o.x, cand)
     _assert_close(Ggpu[mm], Gref_full[mm], DOT_RTOL, 1e-6, f"mover gram (round {t0})")
     assert np.array_equal(Ggpu, Ggpu.T)
     # the kept set is the greedy result under d_t on the GPU's own values, bit-exact
@@ -197,12 +206,19 @@ def test_degenerate_cases():
         g, o = _pair(p)
         for _ in range(3):
             _check_round(g, o, [])
-    # dynamic dependencies are not offered for CSC designs
-    q = si.make("c4_sparse_csc", n=200, j=300, nnz_per_col=10, nnz=8, l_prime=30)
-    with pytest.raises(pk.StradsError) as e:
-        pk.StradsLasso(values=q.values.to(dev), row_idx=q.row_idx.to(dev), col_ptr=q.col_ptr.to(dev), n=q.n,
-                       y=q.y.to(dev), lam=q.lam, rho=q.rho, eta=q.eta, l_prime=q.l_prime, dynamic=True)
-    assert e.value.code == pk.E_UNSUPPORTED
+
+
+def test_csc_design_teacher_forced():
+    for kw, rounds in ((dict(n=3000, j=6000, nnz_per_col=30, nnz=30, l_prime=300), 16),
+                       (dict(n=500, j=2000, nnz_per_col=60, nnz=20, l_prime=700, rho=0.2), 10)):
+        p = si.make("c4_sparse_csc", **kw)
+        g, o = _pair(p)
+        log, most = [], 0
+        for _ in range(rounds):
+            m, k = _check_round(g, o, log)
+            most = max(most, m)
+        assert most > 0
+        print("csc", kw, "most movers", most, log)
 
 
 def test_run_reaches_the_lasso_solution():
