@@ -186,6 +186,7 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
         if (s > 0 && (hipMemsetAsync(h->base + ln->ws.hist, 0, (size_t)2 * kHistBins * 4, h->stream) != hipSuccess ||
                       hipMemsetAsync(h->base + ln->ws.scalars, 0, sizeof(RoundScalars), h->stream) != hipSuccess))
             rc = STRADS_E_HIP;
+        if (rc == STRADS_OK && launch_set_next_round(ln, h->stream, s) != hipSuccess) rc = STRADS_E_HIP;
         if (rc == STRADS_OK && cfg->deps == STRADS_DEPS_DYNAMIC) {
             // Gram decomposition per mover-tile count, looked up by the mover kernel every round
             gram_shape_table(cfg->n, h->Lpad, h->shape_table);
@@ -263,7 +264,7 @@ static int enqueue_round(strads_lasso *top)
 #define MARK(b) do { const int rc_ = mark(top, (b)); if (rc_ != STRADS_OK) return rc_; } while (0)
 #define AFTER_PREVIOUS_ROUND() do { if (S > 1) HIP_TRY(hipStreamWaitEvent(h->stream, prev->ev_resid, 0)); } while (0)
     MARK(STRADS_STAGE_SAMPLER);
-    HIP_TRY(launch_sampler(h, top->round));
+    HIP_TRY(launch_sampler(h));                 // the round index is the shard's device-side counter
     MARK(STRADS_STAGE_CAND_DOTS);
     if (dynamic) {
         // every candidate's update from the current residual; the movers; how to tile their Gram
@@ -455,6 +456,11 @@ int strads_lasso_set_state(strads_lasso_t *h, const float *beta, const float *db
     if (beta) HIP_TRY(hipMemcpyAsync(h->base + h->ws.beta, beta, (size_t)h->cfg.j * 4, hipMemcpyDeviceToDevice, h->stream));
     if (dbeta) HIP_TRY(hipMemcpyAsync(h->base + h->ws.dbeta, dbeta, (size_t)h->cfg.j * 4, hipMemcpyDeviceToDevice, h->stream));
     if (r) HIP_TRY(hipMemcpyAsync(h->base + h->ws.r, r, (size_t)h->cfg.n * 4, hipMemcpyDeviceToDevice, h->stream));
+    // shard s runs next the first round >= `round` whose turn is s's
+    for (int32_t s = 0; s < h->n_lanes; ++s) {
+        const int64_t S = h->n_lanes;
+        HIP_TRY(launch_set_next_round(h->lanes[s], h->stream, round + ((s - round % S) + S) % S));
+    }
     HIP_TRY(hipStreamSynchronize(h->stream));
     h->round = round;
     return STRADS_OK;

@@ -147,11 +147,12 @@ __device__ __forceinline__ void wave_append(bool flag, uint64_t item, uint64_t *
 // j = i * shards + shard (one shard: j = i).  Keys are stored by position; the random number and
 // delta beta are those of coordinate j.
 __global__ __launch_bounds__(256) void k_keys_hist(const float *__restrict__ dbeta, uint32_t Js, uint32_t shards,
-                                                   uint32_t shard, float eta, uint64_t seed, uint64_t t,
-                                                   int priority, uint32_t *__restrict__ keys,
-                                                   uint32_t *__restrict__ hist0)
+                                                   uint32_t shard, float eta, uint64_t seed,
+                                                   const RoundScalars *__restrict__ sc, int priority,
+                                                   uint32_t *__restrict__ keys, uint32_t *__restrict__ hist0)
 {
     __shared__ uint32_t lh[kHistBins];
+    const uint64_t t = sc->next_round;          // advanced by the shard's last sampler kernel
     for (int i = threadIdx.x; i < kHistBins; i += 256) lh[i] = 0;
     __syncthreads();
     for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < Js; i += gridDim.x * 256u) {
@@ -324,7 +325,7 @@ __device__ __forceinline__ uint32_t block_rank(bool flag, uint32_t *wave_tot /* 
 
 __global__ __launch_bounds__(1024) void k_finalize(RoundScalars *__restrict__ sc, uint64_t *__restrict__ sel,
                                                    uint64_t *__restrict__ bnd, uint32_t L, uint32_t Lpad,
-                                                   uint32_t cap, int32_t *__restrict__ cand,
+                                                   uint32_t cap, uint32_t shards, int32_t *__restrict__ cand,
                                                    uint32_t *__restrict__ hist)
 {
     extern __shared__ uint64_t lds[];
@@ -407,7 +408,7 @@ __global__ __launch_bounds__(1024) void k_finalize(RoundScalars *__restrict__ sc
 
     // D. leave the histograms and per-round scalars clean for the next round
     for (uint32_t i = tid; i < 2u * kHistBins; i += 1024u) hist[i] = 0;
-    if (tid == 0) { sc->n_sel = 0; sc->n_bnd = 0; sc->near_rho_pairs = 0; }
+    if (tid == 0) { sc->n_sel = 0; sc->n_bnd = 0; sc->near_rho_pairs = 0; sc->next_round += shards; }
 }
 
 // Draw order for lists longer than 1024 items, in two kernels.  (1) every workgroup sorts one
@@ -459,7 +460,16 @@ static inline int sampler_grid(int64_t J)
     return (int)b;
 }
 
-hipError_t launch_sampler(strads_lasso *h, int64_t round)
+__global__ void k_set_next_round(RoundScalars *sc, unsigned long long t) { sc->next_round = t; }
+
+hipError_t launch_set_next_round(strads_lasso *h, hipStream_t stream, int64_t next_round)
+{
+    hipLaunchKernelGGL(k_set_next_round, dim3(1), dim3(1), 0, stream, h->at<RoundScalars>(h->ws.scalars),
+                       (unsigned long long)next_round);
+    return hipGetLastError();
+}
+
+hipError_t launch_sampler(strads_lasso *h)
 {
     const uint32_t J = (uint32_t)h->Js, L = (uint32_t)h->L;      // this shard's coordinates
     const uint32_t S = (uint32_t)h->n_lanes, sh = (uint32_t)h->lane_id;
@@ -469,7 +479,7 @@ hipError_t launch_sampler(strads_lasso *h, int64_t round)
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     uint64_t *sel = h->at<uint64_t>(h->ws.sel), *bnd = h->at<uint64_t>(h->ws.bnd);
     hipLaunchKernelGGL(k_keys_hist, dim3(g), dim3(256), 0, h->stream, h->at<float>(h->ws.dbeta), J, S, sh, h->cfg.eta,
-                       h->cfg.seed, (uint64_t)round, h->cfg.priority, keys, hist);
+                       h->cfg.seed, sc, h->cfg.priority, keys, hist);
     hipLaunchKernelGGL(k_hist2, dim3(g), dim3(256), 0, h->stream, keys, J, L, hist, hist + kHistBins, sc);
     const unsigned gc = (unsigned)((h->Js + 256 * kCollectPerThread - 1) / (256 * kCollectPerThread));
     hipLaunchKernelGGL(k_collect, dim3(gc), dim3(256), 0, h->stream, keys, J, S, sh, hist + kHistBins, sc, sel, bnd);
@@ -480,7 +490,7 @@ hipError_t launch_sampler(strads_lasso *h, int64_t round)
     uint32_t items = 1024u;
     while (items < cap) items <<= 1;
     const size_t lds = (size_t)items * sizeof(uint64_t);
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(1024), lds, h->stream, sc, sel, bnd, L, (uint32_t)h->Lpad, cap,
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(1024), lds, h->stream, sc, sel, bnd, L, (uint32_t)h->Lpad, cap, S,
                        h->at<int32_t>(h->ws.cand), hist);
     if (L > kRegSortMax) {
         const uint32_t n_chunks = (L + 1023u) / 1024u;

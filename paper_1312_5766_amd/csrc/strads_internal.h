@@ -28,6 +28,9 @@ constexpr int kStageEvents = STRADS_N_STAGES + 1;
 // Device-side scalars of one round, kept in one small block of the workspace.
 struct RoundScalars {
     unsigned long long updates_total;   // sum of |B_1| over all rounds since create
+    unsigned long long next_round;      // index t of the round this shard runs next (keys the random
+                                        // stream); advanced on the device so that a recorded HIP graph
+                                        // of rounds can be replayed without new kernel arguments
     uint32_t n_sel;        // keys strictly above the 22-bit boundary prefix
     uint32_t n_bnd;        // keys on the boundary prefix
     uint32_t bin0, rem1;   // first digit of the L'-th key, rank still to find below it
@@ -126,7 +129,8 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
 Workspace workspace_of_lane(const Workspace &w0, int32_t lane);
 
 // Each launcher enqueues on h->stream and returns the hipError_t of the launch.
-hipError_t launch_sampler(strads_lasso *h, int64_t round);                 // Step 1 -> cand[L]
+hipError_t launch_sampler(strads_lasso *h);                                // Step 1 -> cand[L]; round index from the device
+hipError_t launch_set_next_round(strads_lasso *h, hipStream_t stream, int64_t next_round);
 hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys);  // stage entry
 hipError_t launch_gram_dense(strads_lasso *h, int part);  // Step 2a; part 0: K-slice tiles, part 1: sum + conflict mask
 hipError_t launch_mask_from_gram(strads_lasso *h, const float *gram, int32_t l);
