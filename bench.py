@@ -71,6 +71,10 @@ def main() -> int:
                     help="> 0: --steps is an upper bound and the run stops once the optimality violation is "
                          "<= kkt_tol * lambda, tested every --check-every rounds (each test streams X once)")
     ap.add_argument("--check-every", type=int, default=25)
+    ap.add_argument("--graph-rounds", type=int, default=0,
+                    help="> 0: strads_lasso_run records this many rounds once as a HIP graph and replays it "
+                         "(default 0: every round is enqueued; on this runtime a replay does not run the "
+                         "shards' branches concurrently)")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip the extra legs that time the same workload with 4 scheduler shards and with "
                          "dynamic dependencies (reported under 'variants'; the headline value is unaffected)")
@@ -95,6 +99,11 @@ def main() -> int:
     pk.load()                                   # fails loudly if the HIP library is not built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.graph_rounds > 0:
+        # HIP-graph replay of groups of rounds needs a stream that can be captured (the legacy default
+        # stream cannot); otherwise the default stream is used: a stream of our own would take one of
+        # the four hardware queues away from the scheduler shards
+        torch.cuda.set_stream(torch.cuda.Stream(dev))
 
     key, over = WORKLOADS[args.workload]
     t0 = time.time()
@@ -125,6 +134,8 @@ def main() -> int:
     g = fresh()
     if args.split_k:
         g.set_tuning("gram_split_k", args.split_k)
+    if args.graph_rounds > 0:
+        g.set_tuning("graph_rounds", args.graph_rounds)
     f0 = g.objective()
     if args.shards > 1:
         args.profile_level = 0                  # stages of different shards overlap: no per-stage timing
@@ -236,7 +247,7 @@ def main() -> int:
                    "eta": p.eta, "lambda": p.lam, "rounds": rounds_done, "deps": args.deps, "priority": args.priority, "p_max": args.p_max, "shards": args.shards,
                    "parallelism": "1 GPU"},
         "rounds_per_s": round(rounds_done / wall, 2), "updates": updates, "seconds": round(wall, 4),
-        "kkt_tol": args.kkt_tol, "converged": int(info.converged),
+        "kkt_tol": args.kkt_tol, "converged": int(info.converged), "graph_replays": int(info.graph_replays),
         "objective_start": f0, "objective_end": f1, "kkt_violation_end": viol,
         "roofline": roofline,
         "hbm_pass": {"kernel": "k_kkt", "bytes": kkt_bytes, "ms": round(kkt_ms, 4), "achieved": round(kkt_gbps, 1),

@@ -134,6 +134,7 @@ typedef struct {
     double  objective;            /* eq. (1) at exit */
     float   kkt_violation;        /* max_j violation at the last check (absolute) */
     int32_t converged;            /* 1 iff kkt_violation <= kkt_tol * lambda at exit */
+    int32_t graph_replays;        /* HIP-graph launches this call made (each = "graph_rounds" rounds) */
 } strads_run_info_t;
 
 /* Bytes of workspace a configuration needs (depends on n, j, layout, l_prime, keep_gram, deps and,
@@ -211,6 +212,12 @@ int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, i
  *   "gram_split_k"  0 = automatic, else the number of K-slices per Gram tile
  *   "select_cap"    boundary-list length above which the sampler's final
  *                   selection falls back to its multi-pass path (default 4096)
+ *   "graph_rounds"  > 0: strads_lasso_run records this many consecutive rounds once as a HIP graph and
+ *                   replays it (rounds left over are enqueued one by one); 0 (default) = never.
+ *                   Replays and directly enqueued rounds give identical results.  Needs a caller
+ *                   stream that can be captured (not the legacy default stream); otherwise the
+ *                   library falls back to enqueueing.  On ROCm 7.2 a replay runs the shards'
+ *                   branches one after the other, so it only pays for n_shards = 1.
  *   "profile_level", "profile_rounds"   see strads_lasso_stage_times
  * Returns STRADS_E_INVALID_ARG for an unknown name or a value out of range. */
 int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value);

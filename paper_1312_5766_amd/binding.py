@@ -48,7 +48,7 @@ class RoundInfo(C.Structure):
 
 class RunInfo(C.Structure):
     _fields_ = [("rounds_done", C.c_int64), ("updates_done", C.c_int64), ("objective", C.c_double),
-                ("kkt_violation", C.c_float), ("converged", C.c_int32)]
+                ("kkt_violation", C.c_float), ("converged", C.c_int32), ("graph_replays", C.c_int32)]
 
 
 _lib = None

@@ -151,6 +151,7 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->vec4 = cfg->layout == STRADS_LAYOUT_DENSE_COLMAJOR && (cfg->n % 4 == 0) && (((uintptr_t)cfg->x & 15u) == 0);
 
     h->n_lanes = S;
+    h->graph_rounds = 0;                        // off unless asked for (set_tuning "graph_rounds")
     h->lane_id = 0;
     h->lanes[0] = h;
     int rc = STRADS_OK;
@@ -220,11 +221,13 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
 }
 
 static void drop_events(strads_lasso *h);
+static void drop_graphs(strads_lasso *h);
 
 void strads_lasso_destroy(strads_lasso_t *h)
 {
     if (!h) return;
     drop_events(h);
+    drop_graphs(h);
     for (int32_t s = 0; s < h->n_lanes; ++s) {
         strads_lasso *ln = h->lanes[s];
         if (!ln) continue;
@@ -262,7 +265,8 @@ static int enqueue_round(strads_lasso *top)
     const bool dynamic = h->cfg.deps == STRADS_DEPS_DYNAMIC;
     const bool unchecked = h->cfg.deps == STRADS_DEPS_NONE;
 #define MARK(b) do { const int rc_ = mark(top, (b)); if (rc_ != STRADS_OK) return rc_; } while (0)
-#define AFTER_PREVIOUS_ROUND() do { if (S > 1) HIP_TRY(hipStreamWaitEvent(h->stream, prev->ev_resid, 0)); } while (0)
+    // (the first round after a fork needs no event: the fork itself orders it after everything before)
+#define AFTER_PREVIOUS_ROUND() do { if (S > 1 && top->rounds_since_fork > 0) HIP_TRY(hipStreamWaitEvent(h->stream, prev->ev_resid, 0)); } while (0)
     MARK(STRADS_STAGE_SAMPLER);
     HIP_TRY(launch_sampler(h));                 // the round index is the shard's device-side counter
     MARK(STRADS_STAGE_CAND_DOTS);
@@ -293,12 +297,14 @@ static int enqueue_round(strads_lasso *top)
 #undef AFTER_PREVIOUS_ROUND
     if (top->profile_level != 0 && top->profiled < top->profile_rounds) top->profiled += 1;
     top->round += 1;
+    top->rounds_since_fork += 1;
     return STRADS_OK;
 }
 
 // The shards' streams start after everything already on the caller's stream ...
 static int fork_lanes(strads_lasso *h)
 {
+    h->rounds_since_fork = 0;
     if (h->n_lanes == 1) return STRADS_OK;
     HIP_TRY(hipEventRecord(h->ev_fork, h->stream));
     for (int32_t s = 1; s < h->n_lanes; ++s) HIP_TRY(hipStreamWaitEvent(h->lanes[s]->stream, h->ev_fork, 0));
@@ -355,6 +361,75 @@ static int total_updates(strads_lasso *h, unsigned long long *out)
     return STRADS_OK;
 }
 
+static void drop_graphs(strads_lasso *h)
+{
+    for (int32_t s = 0; s < STRADS_MAX_SHARDS; ++s) {
+        if (h->graph_exec[s]) (void)hipGraphExecDestroy(h->graph_exec[s]);
+        if (h->graph[s]) (void)hipGraphDestroy(h->graph[s]);
+        h->graph_exec[s] = nullptr;
+        h->graph[s] = nullptr;
+    }
+}
+
+// Record h->graph_rounds rounds, starting with the shard whose turn it is, into a HIP graph:
+// the caller's stream is put in capture mode, the fork makes the shards' streams part of the
+// capture, the join brings them back.  Nothing runs; the host-side round counter is restored.
+// Kernel arguments are fixed per handle (the round index lives on the device), so the graph
+// stays valid until a tuning knob that changes a launch is touched.
+static int record_graph(strads_lasso *h, int32_t first_lane)
+{
+    const int64_t round0 = h->round;
+    if (hipStreamBeginCapture(h->stream, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+        // e.g. the caller handed over the legacy default stream, which cannot be captured:
+        // from now on rounds are enqueued one by one
+        (void)hipGetLastError();
+        h->graph_rounds = 0;
+        return STRADS_E_UNSUPPORTED;
+    }
+    int rc = fork_lanes(h);
+    for (int32_t i = 0; i < h->graph_rounds && rc == STRADS_OK; ++i) rc = enqueue_round(h);
+    if (rc == STRADS_OK) rc = join_lanes(h);
+    hipGraph_t g = nullptr;
+    const hipError_t e = hipStreamEndCapture(h->stream, &g);
+    h->round = round0;
+    if (rc != STRADS_OK || e != hipSuccess || !g) {
+        if (g) (void)hipGraphDestroy(g);
+        return rc != STRADS_OK ? rc : STRADS_E_HIP;
+    }
+    hipGraphExec_t ex = nullptr;
+    if (hipGraphInstantiate(&ex, g, nullptr, nullptr, 0) != hipSuccess) {
+        (void)hipGraphDestroy(g);
+        return STRADS_E_HIP;
+    }
+    h->graph[first_lane] = g;
+    h->graph_exec[first_lane] = ex;
+    return STRADS_OK;
+}
+
+// Enqueue `count` rounds: whole groups of graph_rounds as graph replays, the rest one by one.
+static int enqueue_rounds(strads_lasso *h, int64_t count, int32_t *replays)
+{
+    while (h->graph_rounds > 0 && h->profile_level == 0 && count >= h->graph_rounds) {
+        const int32_t lane = (int32_t)(h->round % h->n_lanes);
+        if (!h->graph_exec[lane]) {
+            const int rc = record_graph(h, lane);
+            if (rc == STRADS_E_UNSUPPORTED) break;      // this stream cannot be captured
+            if (rc != STRADS_OK) return rc;
+        }
+        HIP_TRY(hipGraphLaunch(h->graph_exec[lane], h->stream));
+        *replays += 1;
+        h->round += h->graph_rounds;
+        count -= h->graph_rounds;
+    }
+    if (count > 0) {
+        int rc = fork_lanes(h);
+        for (int64_t i = 0; i < count && rc == STRADS_OK; ++i) rc = enqueue_round(h);
+        if (rc == STRADS_OK) rc = join_lanes(h);
+        if (rc != STRADS_OK) return rc;
+    }
+    return STRADS_OK;
+}
+
 int strads_lasso_round(strads_lasso_t *h, strads_round_info_t *info)
 {
     if (!h) return STRADS_E_INVALID_ARG;
@@ -408,15 +483,14 @@ int strads_lasso_run(strads_lasso_t *h, int64_t max_rounds, float kkt_tol, int32
     int64_t done = 0;
     float viol = INFINITY;
     int converged = 0;
+    int32_t replays = 0;
     // |B_1| is summed on the device; rounds between checks are only enqueued, never waited for
     unsigned long long upd0 = 0, upd1 = 0;
     { const int rs = total_updates(h, &upd0); if (rs != STRADS_OK) return rs; }
     while (done < max_rounds) {
         int64_t burst = max_rounds - done;
         if (check_every > 0 && burst > check_every) burst = check_every;
-        int rc = fork_lanes(h);
-        for (int64_t i = 0; i < burst && rc == STRADS_OK; ++i) rc = enqueue_round(h);
-        if (rc == STRADS_OK) rc = join_lanes(h);
+        int rc = enqueue_rounds(h, burst, &replays);
         if (rc != STRADS_OK) return rc;
         done += burst;
         if (check_every > 0) {
@@ -435,6 +509,7 @@ int strads_lasso_run(strads_lasso_t *h, int64_t max_rounds, float kkt_tol, int32
         out->objective = obj;
         out->kkt_violation = viol;
         out->converged = converged;
+        out->graph_replays = replays;
     }
     return isfinite(obj) ? STRADS_OK : STRADS_E_DIVERGED;
 }
@@ -538,9 +613,18 @@ int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, i
 int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
 {
     if (!h || !name) return STRADS_E_INVALID_ARG;
+    if (strcmp(name, "graph_rounds") == 0) {
+        if (value < 0 || value > 4096) return STRADS_E_INVALID_ARG;
+        HIP_TRY(hipStreamSynchronize(h->stream));
+        drop_graphs(h);
+        h->graph_rounds = (int32_t)value;
+        return STRADS_OK;
+    }
     if (strcmp(name, "gram_split_k") == 0) {
         if (value < 0 || value > h->split_max) return STRADS_E_INVALID_ARG;
         if (value != 0 && h->cfg.deps == STRADS_DEPS_DYNAMIC) return STRADS_E_UNSUPPORTED;   // chosen on the device
+        HIP_TRY(hipStreamSynchronize(h->stream));
+        drop_graphs(h);                                 // recorded launches carry the old decomposition
         for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->split_user = (int32_t)value;
         return STRADS_OK;
     }
@@ -567,6 +651,8 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
     }
     if (strcmp(name, "select_cap") == 0) {
         if (value < 1 || value > 2 * STRADS_MAX_L_PRIME) return STRADS_E_INVALID_ARG;
+        HIP_TRY(hipStreamSynchronize(h->stream));
+        drop_graphs(h);
         for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->select_cap = (int32_t)value;
         return STRADS_OK;
     }

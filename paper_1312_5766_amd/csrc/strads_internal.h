@@ -114,6 +114,12 @@ struct strads_lasso {
     hipEvent_t ev_resid;     // recorded after this shard's residual update
     hipEvent_t ev_fork;      // shard 0 only: the caller's stream at the start of an enqueueing call
     hipEvent_t ev_join;      // this shard's stream at the end of an enqueueing call
+    int64_t rounds_since_fork;   // shard 0 only: rounds enqueued since the shards' streams were last forked
+    // HIP graph of graph_rounds consecutive rounds, recorded once per starting shard and replayed by
+    // strads_lasso_run (shard 0 only)
+    int32_t graph_rounds;                       // 0: never use graphs
+    hipGraph_t graph[STRADS_MAX_SHARDS];
+    hipGraphExec_t graph_exec[STRADS_MAX_SHARDS];
     strads::GramShape shape_table[STRADS_MAX_L_PRIME / strads::kGramTile + 1];   // host copy of ws.dtable
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(base + off); }
