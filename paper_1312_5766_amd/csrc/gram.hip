@@ -129,6 +129,12 @@ __device__ __forceinline__ void gram_tile_off(const float *__restrict__ X, int64
 #pragma unroll
         for (int i = 0; i < 2 * kPasses; ++i) R[i] = load_k4<VEC4>(col[i], k, kend);
     };
+    auto fetch_full = [&](int st) {             // a stage that lies entirely inside the slice: no clamping
+        const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
+#pragma unroll
+        for (int i = 0; i < 2 * kPasses; ++i) R[i] = *reinterpret_cast<const float4 *>(col[i] + k);
+    };
+    const int nfull = VEC4 ? (int)((kend - kbeg) / kGramKT) : 0;   // stages 0 .. nfull-1 are full
     auto stash = [&](int buf) {
         float *pa = smem + buf * 2 * kPanel, *pb = pa + kPanel;
 #pragma unroll
@@ -152,24 +158,44 @@ __device__ __forceinline__ void gram_tile_off(const float *__restrict__ X, int64
 
     const int offa = (wr * 64 + li) * kRow + lh * 4;
     const int offb = kPanel + (wc * 64 + li) * kRow + lh * 4;
-    auto compute = [&](int buf) {
-        const float *pa = smem + buf * 2 * kPanel + offa;
-        const float *pb = smem + buf * 2 * kPanel + offb;
+    // Operands of one 8-row K step: lane (li, lh) reads k = 8*ks + 4*lh .. +3 of its two A columns
+    // and two B columns.  The operands of step ks+1 are requested before the MFMAs of step ks are
+    // issued, and those of a stage's first step before the stage's LDS writes and global loads, so
+    // that LDS latency is never waited for with an empty matrix pipe.
+    struct Ops { float4 a0, a1, b0, b1; };
+    auto read_ops = [&](int buf, int ks) {
+        const float *pa = smem + buf * 2 * kPanel + offa + ks * 8;
+        const float *pb = smem + buf * 2 * kPanel + offb + ks * 8;
+        Ops o;
+        o.a0 = *reinterpret_cast<const float4 *>(pa);
+        o.a1 = *reinterpret_cast<const float4 *>(pa + 32 * kRow);
+        o.b0 = *reinterpret_cast<const float4 *>(pb);
+        o.b1 = *reinterpret_cast<const float4 *>(pb + 32 * kRow);
+        return o;
+    };
+    auto mma = [&](const Ops &o) {
+        const float av0[4] = {o.a0.x, o.a0.y, o.a0.z, o.a0.w}, av1[4] = {o.a1.x, o.a1.y, o.a1.z, o.a1.w};
+        const float bv0[4] = {o.b0.x, o.b0.y, o.b0.z, o.b0.w}, bv1[4] = {o.b1.x, o.b1.y, o.b1.z, o.b1.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            mfma32(acc[0][0], av0[c], bv0[c]);
+            mfma32(acc[0][1], av0[c], bv1[c]);
+            mfma32(acc[1][0], av1[c], bv0[c]);
+            mfma32(acc[1][1], av1[c], bv1[c]);
+        }
+    };
+    // multiply stage `buf` out of LDS, its first operands already in `first`; `between` runs after
+    // the MFMAs of the first K step have been issued (the next stage's LDS writes and global loads:
+    // whatever they wait for is then waited for behind a full matrix pipe)
+    auto compute = [&](int buf, Ops first, auto between) {
+        Ops cur = first;
 #pragma unroll
         for (int ks = 0; ks < kGramKT / 8; ++ks) {
-            const float4 a0 = *reinterpret_cast<const float4 *>(pa + ks * 8);
-            const float4 a1 = *reinterpret_cast<const float4 *>(pa + 32 * kRow + ks * 8);
-            const float4 b0 = *reinterpret_cast<const float4 *>(pb + ks * 8);
-            const float4 b1 = *reinterpret_cast<const float4 *>(pb + 32 * kRow + ks * 8);
-            const float av0[4] = {a0.x, a0.y, a0.z, a0.w}, av1[4] = {a1.x, a1.y, a1.z, a1.w};
-            const float bv0[4] = {b0.x, b0.y, b0.z, b0.w}, bv1[4] = {b1.x, b1.y, b1.z, b1.w};
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                mfma32(acc[0][0], av0[c], bv0[c]);
-                mfma32(acc[0][1], av0[c], bv1[c]);
-                mfma32(acc[1][0], av1[c], bv0[c]);
-                mfma32(acc[1][1], av1[c], bv1[c]);
-            }
+            Ops next = cur;
+            if (ks + 1 < kGramKT / 8) next = read_ops(buf, ks + 1);
+            mma(cur);
+            if (ks == 0) between();
+            cur = next;
         }
     };
 
@@ -178,19 +204,20 @@ __device__ __forceinline__ void gram_tile_off(const float *__restrict__ X, int64
     if (nstage > 1) fetch(1);
     __syncthreads();
     int st = 0;
-    for (; st + 2 < nstage; ++st) {             // steady state
-        stash((st + 1) & 1);
-        fetch(st + 2);
-        compute(st & 1);
+    for (; st + 2 < nfull; ++st) {              // steady state
+        compute(st & 1, read_ops(st & 1, 0), [&] { stash((st + 1) & 1); fetch_full(st + 2); });
+        __syncthreads();
+    }
+    for (; st + 2 < nstage; ++st) {             // a ragged last stage is fetched with clamping
+        compute(st & 1, read_ops(st & 1, 0), [&] { stash((st + 1) & 1); fetch(st + 2); });
         __syncthreads();
     }
     if (st + 1 < nstage) {
-        stash((st + 1) & 1);
-        compute(st & 1);
+        compute(st & 1, read_ops(st & 1, 0), [&] { stash((st + 1) & 1); });
         __syncthreads();
         ++st;
     }
-    compute(st & 1);
+    compute(st & 1, read_ops(st & 1, 0), [] {});
     mfma_drain();
 
     float *out = P + (int64_t)s * g.Lpad * g.Lpad;
@@ -229,6 +256,12 @@ __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int6
 #pragma unroll
         for (int i = 0; i < kPasses; ++i) R[i] = load_k4<VEC4>(col[i], k, kend);
     };
+    auto fetch_full = [&](int st) {
+        const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
+#pragma unroll
+        for (int i = 0; i < kPasses; ++i) R[i] = *reinterpret_cast<const float4 *>(col[i] + k);
+    };
+    const int nfull = VEC4 ? (int)((kend - kbeg) / kGramKT) : 0;
     auto stash = [&](int buf) {
         float *pa = smem + buf * 2 * kPanel;
 #pragma unroll
@@ -289,6 +322,12 @@ __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int6
     if (nstage > 1) fetch(1);
     __syncthreads();
     int st = 0;
+    for (; st + 2 < nfull; ++st) {
+        stash((st + 1) & 1);
+        fetch_full(st + 2);
+        compute(st & 1);
+        __syncthreads();
+    }
     for (; st + 2 < nstage; ++st) {
         stash((st + 1) & 1);
         fetch(st + 2);
