@@ -38,6 +38,8 @@ WORKLOADS = {
     "c2_dense_block_corr": ("c2_dense_block_corr", {}),
     "c1_dense_iid": ("c1_dense_iid", {}),
     "c3_genotype": ("c3_genotype", {}),
+    # the third configuration stored as 2-bit genotype counts (16 rows per 32-bit word)
+    "c3_genotype_packed": ("c3_genotype_packed", {}),
     "c4_sparse_csc": ("c4_sparse_csc", {}),
     # the fifth configuration's rows, duplicate structure and L'=8000 with J cut to fit quick runs
     "c5_dense_duplicates_j60k": ("c5_dense_duplicates", dict(j=60000, nnz=200, rounds=20)),
@@ -45,6 +47,22 @@ WORKLOADS = {
     "c5_dense_duplicates": ("c5_dense_duplicates", {}),
     "c2_small": ("c2_dense_block_corr", dict(n=2000, j=8000, nnz=40, l_prime=500, rounds=16)),
 }
+
+
+def design_args(p, host=False):
+    """The design matrix of a synthetic problem as constructor arguments: of the library (device
+    tensors, packed codes where the workload has them) or, with host, of the oracle (numpy; a packed
+    design as the fp32 matrix its codes stand for)."""
+    if host:
+        if p.layout in ("dense", "geno2"):
+            return dict(x=p.x.cpu().numpy())
+        return dict(values=p.values.cpu().numpy(), row_idx=p.row_idx.cpu().numpy(), col_ptr=p.col_ptr.cpu().numpy(),
+                    n=p.n)
+    if p.layout == "dense":
+        return dict(x=p.x)
+    if p.layout == "geno2":
+        return dict(codes=p.codes, col_mean=p.col_mean, col_scale=p.col_scale, n=p.n)
+    return dict(values=p.values, row_idx=p.row_idx, col_ptr=p.col_ptr, n=p.n)
 
 
 def main() -> int:
@@ -116,9 +134,7 @@ def main() -> int:
         kw = dict(y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed, p_max=args.p_max,
                   dynamic=args.deps == "dynamic", no_deps=args.deps == "none", priority=args.priority,
                   n_shards=args.shards)
-        if p.layout == "dense":
-            return pk.StradsLasso(x=p.x, **kw)
-        return pk.StradsLasso(values=p.values, row_idx=p.row_idx, col_ptr=p.col_ptr, n=p.n, **kw)
+        return pk.StradsLasso(**design_args(p), **kw)
 
     # warm-up on a throw-away handle, so that the timed region is the configuration's own
     # trajectory from round 0
@@ -164,7 +180,12 @@ def main() -> int:
     e1.record()
     torch.cuda.synchronize()
     kkt_ms = e0.elapsed_time(e1)
-    kkt_bytes = 4.0 * p.n * p.j if p.layout == "dense" else 8.0 * float(p.values.numel())
+    if p.layout == "dense":
+        kkt_bytes = 4.0 * p.n * p.j
+    elif p.layout == "geno2":
+        kkt_bytes = 4.0 * float(p.codes.numel())
+    else:
+        kkt_bytes = 8.0 * float(p.values.numel())
     kkt_gbps = kkt_bytes / (kkt_ms * 1e-3) / 1e9
 
     # the same workload and round count under the two widenings of the schedule (not the headline)
@@ -176,16 +197,10 @@ def main() -> int:
         legs = {"shards4": dict(n_shards=4), "dynamic": dict(dynamic=True)}
         for name, extra in legs.items():
             kw = dict(y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed, **extra)
-            if p.layout == "dense":
-                v = pk.StradsLasso(x=p.x, **kw)
-            else:
-                v = pk.StradsLasso(values=p.values, row_idx=p.row_idx, col_ptr=p.col_ptr, n=p.n, **kw)
+            v = pk.StradsLasso(**design_args(p), **kw)
             v.run(min(args.warmup, 10))
             v.close()
-            if p.layout == "dense":
-                v = pk.StradsLasso(x=p.x, **kw)
-            else:
-                v = pk.StradsLasso(values=p.values, row_idx=p.row_idx, col_ptr=p.col_ptr, n=p.n, **kw)
+            v = pk.StradsLasso(**design_args(p), **kw)
             torch.cuda.synchronize()
             tv = time.perf_counter()
             iv = v.run(args.steps)
@@ -207,7 +222,7 @@ def main() -> int:
     L, N = g.L, p.n
     gram_flops = float(N) * L * (L - 1)          # algorithmic: every unordered pair once, 2 flops per row
     roofline = None
-    if (args.profile_level and stage["rounds"] > 0 and stage["gram_tiles"] > 0 and p.layout == "dense"
+    if (args.profile_level and stage["rounds"] > 0 and stage["gram_tiles"] > 0 and p.layout in ("dense", "geno2")
             and args.deps == "static"):
         ach = gram_flops / (stage["gram_tiles"] * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "k_gram_tiles", "achieved": round(ach, 3),
@@ -221,11 +236,7 @@ def main() -> int:
         okw = dict(y=p.y.cpu().numpy(), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed,
                    p_max=args.p_max, dynamic=args.deps == "dynamic", no_deps=args.deps == "none",
                    priority=args.priority, n_shards=args.shards)
-        if p.layout == "dense":
-            o = OracleLasso(x=p.x.cpu().numpy(), **okw)
-        else:
-            o = OracleLasso(values=p.values.cpu().numpy(), row_idx=p.row_idx.cpu().numpy(),
-                            col_ptr=p.col_ptr.cpu().numpy(), n=p.n, **okw)
+        o = OracleLasso(**design_args(p, host=True), **okw)
         n_upd, n_rounds = 0, 0
         tc = time.perf_counter()
         while True:

@@ -52,6 +52,13 @@ extern "C" {
 
 #define STRADS_LAYOUT_DENSE_COLMAJOR  0   /* x[j*n + i] = X_ij, fp32, leading dimension n */
 #define STRADS_LAYOUT_CSC             1   /* values / row_idx / col_ptr */
+#define STRADS_LAYOUT_GENO2           2   /* genotype counts in {0,1,2}, 2 bits each, with a mean and a scale per
+                                             column: X_ij = fl(fl(g_ij - col_mean[j]) * col_scale[j]), both
+                                             operations rounded to fp32.  x points at 32-bit words: column j
+                                             starts at word j * geno_words(n); word w of a column holds rows
+                                             16w .. 16w+15, row 16w+e in bits 2e, 2e+1; rows past n hold 0.
+                                             geno_words(n) = 4 * ceil(n / 64) (columns are 16-byte aligned).
+                                             16 times fewer bytes than fp32 for every pass over X. */
 
 #define STRADS_MAX_L_PRIME         8192   /* largest supported candidate count per round */
 #define STRADS_MAX_SHARDS             8   /* largest supported number of scheduler shards */
@@ -90,9 +97,12 @@ typedef struct {
     int64_t        n;             /* rows N (> 0) */
     int64_t        j;             /* columns J (> 0, < 2^31) */
     int32_t        layout;        /* STRADS_LAYOUT_* */
-    const float   *x;             /* DEVICE. dense: n*j values, column-major; CSC: nnz values */
+    const float   *x;             /* DEVICE. dense: n*j values, column-major; CSC: nnz values;
+                                     GENO2: the packed words (cast), 16-byte aligned */
     const int32_t *row_idx;       /* DEVICE, CSC only: nnz row indices, increasing within a column */
     const int64_t *col_ptr;       /* DEVICE, CSC only: j+1 offsets, col_ptr[0] = 0 */
+    const float   *col_mean;      /* DEVICE, GENO2 only: j column means */
+    const float   *col_scale;     /* DEVICE, GENO2 only: j column scales (1 / l2 norm of the centred column) */
     const float   *y;             /* DEVICE, n values */
     float          lambda;        /* regularisation weight of eq. (1), >= 0, finite */
     float          rho;           /* dependency threshold of Step 2, > 0 */

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libstrads_lasso.so")
 
 STRADS_OK = 0
 E_INVALID_ARG, E_WORKSPACE_TOO_SMALL, E_HIP, E_DIVERGED, E_UNSUPPORTED = -1, -2, -3, -4, -5
-LAYOUT_DENSE, LAYOUT_CSC = 0, 1
+LAYOUT_DENSE, LAYOUT_CSC, LAYOUT_GENO2 = 0, 1, 2
 MAX_L_PRIME = 8192
 N_STAGES = 7
 STAGE_NAMES = ["sampler", "cand_dots", "gram_tiles", "gram_mask", "filter", "update", "residual"]
@@ -35,7 +35,8 @@ EXPORTS = [
 
 class Config(C.Structure):
     _fields_ = [("n", C.c_int64), ("j", C.c_int64), ("layout", C.c_int32), ("x", C.c_void_p),
-                ("row_idx", C.c_void_p), ("col_ptr", C.c_void_p), ("y", C.c_void_p),
+                ("row_idx", C.c_void_p), ("col_ptr", C.c_void_p), ("col_mean", C.c_void_p), ("col_scale", C.c_void_p),
+                ("y", C.c_void_p),
                 ("lam", C.c_float), ("rho", C.c_float), ("eta", C.c_float), ("c_init", C.c_float),
                 ("l_prime", C.c_int32), ("p_max", C.c_int32), ("seed", C.c_uint64), ("keep_gram", C.c_int32),
                 ("max_col_nnz", C.c_int32), ("deps", C.c_int32), ("priority", C.c_int32), ("n_shards", C.c_int32), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
@@ -119,6 +120,8 @@ class StradsLasso:
                  p_max: int = 0, c_init: float = 1e6, keep_gram: bool = False,
                  x: Optional[torch.Tensor] = None, values: Optional[torch.Tensor] = None,
                  row_idx: Optional[torch.Tensor] = None, col_ptr: Optional[torch.Tensor] = None,
+                 codes: Optional[torch.Tensor] = None, col_mean: Optional[torch.Tensor] = None,
+                 col_scale: Optional[torch.Tensor] = None,
                  n: Optional[int] = None, max_col_nnz: Optional[int] = None,
                  stream: Optional[torch.cuda.Stream] = None, dynamic: bool = False, priority: str = "squared",
                  no_deps: bool = False, n_shards: int = 1):
@@ -133,6 +136,14 @@ class StradsLasso:
             self.J, self.N = x.shape                      # row j of the tensor = column x_j (ld = N)
             layout = LAYOUT_DENSE
             self._keep = (x, y)
+        elif codes is not None:
+            # packed genotype counts: (J, 4*ceil(N/64)) int32 words plus a mean and a scale per column
+            assert codes.dtype == torch.int32 and codes.is_contiguous() and codes.dim() == 2
+            assert col_mean.dtype == torch.float32 and col_scale.dtype == torch.float32
+            self.J, self.N = codes.shape[0], int(n)
+            assert codes.shape[1] == (self.N + 63) // 64 * 4 and col_mean.numel() == self.J == col_scale.numel()
+            layout = LAYOUT_GENO2
+            self._keep = (codes, col_mean, col_scale, y)
         else:
             assert values.dtype == torch.float32 and row_idx.dtype == torch.int32 and col_ptr.dtype == torch.int64
             self.J, self.N = col_ptr.numel() - 1, int(n)
@@ -143,8 +154,10 @@ class StradsLasso:
         assert y.dtype == torch.float32 and y.is_contiguous() and y.numel() == self.N
         self.L = min(int(l_prime), self.J // max(1, int(n_shards)))
         self.stream = stream if stream is not None else torch.cuda.current_stream(dev)
-        cfg = Config(n=self.N, j=self.J, layout=layout, x=_ptr(x if x is not None else values),
-                     row_idx=_ptr(row_idx), col_ptr=_ptr(col_ptr), y=_ptr(y), lam=lam, rho=rho, eta=eta,
+        data = x if x is not None else (codes if codes is not None else values)
+        cfg = Config(n=self.N, j=self.J, layout=layout, x=_ptr(data),
+                     row_idx=_ptr(row_idx), col_ptr=_ptr(col_ptr), col_mean=_ptr(col_mean),
+                     col_scale=_ptr(col_scale), y=_ptr(y), lam=lam, rho=rho, eta=eta,
                      c_init=c_init, l_prime=int(l_prime), p_max=int(p_max), seed=int(seed),
                      keep_gram=int(keep_gram), max_col_nnz=int(max_col_nnz or 0),
                      deps=DEPS_NONE if no_deps else (DEPS_DYNAMIC if dynamic else DEPS_STATIC),

@@ -18,7 +18,7 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
     const int64_t S = n_shards > 1 ? n_shards : 1;
     const int64_t js = (j + S - 1) / S;                  // coordinates of the largest shard
     const int64_t lpad = (l + kGramTile - 1) / kGramTile * kGramTile;
-    const int64_t npad = (n + 3) / 4 * 4;
+    const int64_t npad = (n + 63) / 64 * 64;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     // shared by all shards: the solver state and the objective scratch
@@ -35,7 +35,7 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
     w.sel = take((size_t)2 * STRADS_MAX_L_PRIME * 8);
     w.bnd = take((size_t)js * 8);
     w.cand = take((size_t)lpad * 4);
-    if (layout == STRADS_LAYOUT_DENSE_COLMAJOR)
+    if (layout != STRADS_LAYOUT_CSC)
         w.partial = take(gram_partial_floats(n, (int32_t)lpad, deps == STRADS_DEPS_DYNAMIC) * 4);
     else
         w.partial = take(256);
@@ -79,7 +79,8 @@ static bool sizes_ok(const strads_lasso_config_t *c)
 {
     if (!c) return false;
     if (c->n <= 0 || c->j <= 0 || c->j >= (int64_t)1 << 31) return false;
-    if (c->layout != STRADS_LAYOUT_DENSE_COLMAJOR && c->layout != STRADS_LAYOUT_CSC) return false;
+    if (c->layout != STRADS_LAYOUT_DENSE_COLMAJOR && c->layout != STRADS_LAYOUT_CSC &&
+        c->layout != STRADS_LAYOUT_GENO2) return false;
     if (c->l_prime < 1 || c->l_prime > STRADS_MAX_L_PRIME) return false;
     if (c->layout == STRADS_LAYOUT_CSC && (c->n >= (int64_t)1 << 31 || c->max_col_nnz < 1)) return false;
     if (c->deps != STRADS_DEPS_STATIC && c->deps != STRADS_DEPS_DYNAMIC && c->deps != STRADS_DEPS_NONE) return false;
@@ -118,6 +119,8 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     if (!out || !sizes_ok(cfg)) return STRADS_E_INVALID_ARG;
     if (!cfg->x || !cfg->y || !cfg->workspace) return STRADS_E_INVALID_ARG;
     if (cfg->layout == STRADS_LAYOUT_CSC && (!cfg->row_idx || !cfg->col_ptr)) return STRADS_E_INVALID_ARG;
+    if (cfg->layout == STRADS_LAYOUT_GENO2 && (!cfg->col_mean || !cfg->col_scale || ((uintptr_t)cfg->x & 15u) != 0))
+        return STRADS_E_INVALID_ARG;
     if (!(cfg->lambda >= 0.f) || !isfinite(cfg->lambda)) return STRADS_E_INVALID_ARG;
     if (!(cfg->rho > 0.f) || isnan(cfg->rho)) return STRADS_E_INVALID_ARG;
     if (!(cfg->eta >= 1e-30f) || !isfinite(cfg->eta)) return STRADS_E_INVALID_ARG;
@@ -139,8 +142,8 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->stream = (hipStream_t)cfg->stream;
     h->L = L;
     h->Lpad = (L + kGramTile - 1) / kGramTile * kGramTile;
-    h->Npad = (cfg->n + 3) / 4 * 4;
-    h->split_max = cfg->layout == STRADS_LAYOUT_DENSE_COLMAJOR ? gram_split_auto(cfg->n, h->Lpad) : 1;
+    h->Npad = (cfg->n + 63) / 64 * 64;
+    h->split_max = cfg->layout != STRADS_LAYOUT_CSC ? gram_split_auto(cfg->n, h->Lpad) : 1;
     h->split_user = 0;
     h->select_cap = kSelectCapDefault;
     h->round = 0;
@@ -261,7 +264,7 @@ static int enqueue_round(strads_lasso *top)
     const int32_t S = top->n_lanes;
     strads_lasso *h = top->lanes[top->round % S];
     strads_lasso *prev = top->lanes[(top->round + S - 1) % S];
-    const bool dense = h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR;
+    const bool csc = h->cfg.layout == STRADS_LAYOUT_CSC, geno = h->cfg.layout == STRADS_LAYOUT_GENO2;
     const bool dynamic = h->cfg.deps == STRADS_DEPS_DYNAMIC;
     const bool unchecked = h->cfg.deps == STRADS_DEPS_NONE;
 #define MARK(b) do { const int rc_ = mark(top, (b)); if (rc_ != STRADS_OK) return rc_; } while (0)
@@ -273,13 +276,15 @@ static int enqueue_round(strads_lasso *top)
     if (dynamic) {
         // every candidate's update from the current residual; the movers; how to tile their Gram
         AFTER_PREVIOUS_ROUND();
-        if (dense) HIP_TRY(launch_dots_cand(h)); else HIP_TRY(launch_dots_cand_csc(h));
+        if (csc) HIP_TRY(launch_dots_cand_csc(h));
+        else if (geno) HIP_TRY(launch_dots_cand_geno(h));
+        else HIP_TRY(launch_dots_cand(h));
         HIP_TRY(launch_movers(h));
     }
     MARK(STRADS_STAGE_GRAM_TILES);
-    if (!unchecked) { if (dense) HIP_TRY(launch_gram_dense(h, 0)); else HIP_TRY(launch_gram_csc(h)); }
+    if (!unchecked) { if (csc) HIP_TRY(launch_gram_csc(h)); else HIP_TRY(launch_gram_dense(h, 0)); }
     MARK(STRADS_STAGE_GRAM_MASK);
-    if (!unchecked && dense) HIP_TRY(launch_gram_dense(h, 1));
+    if (!unchecked && !csc) HIP_TRY(launch_gram_dense(h, 1));
     MARK(STRADS_STAGE_FILTER);
     if (unchecked) HIP_TRY(launch_keep_all(h));
     else if (dynamic) HIP_TRY(launch_filter_movers(h));
@@ -287,10 +292,13 @@ static int enqueue_round(strads_lasso *top)
     MARK(STRADS_STAGE_UPDATE);
     if (!dynamic) AFTER_PREVIOUS_ROUND();
     if (dynamic) HIP_TRY(launch_commit_dynamic(h));
-    else if (dense) HIP_TRY(launch_dots_dense(h));
-    else HIP_TRY(launch_dots_csc(h));
+    else if (csc) HIP_TRY(launch_dots_csc(h));
+    else if (geno) HIP_TRY(launch_dots_geno(h));
+    else HIP_TRY(launch_dots_dense(h));
     MARK(STRADS_STAGE_RESIDUAL);
-    if (dense) HIP_TRY(launch_residual_dense(h)); else HIP_TRY(launch_residual_csc(h));
+    if (csc) HIP_TRY(launch_residual_csc(h));
+    else if (geno) HIP_TRY(launch_residual_geno(h));
+    else HIP_TRY(launch_residual_dense(h));
     MARK(STRADS_N_STAGES);
     if (S > 1) HIP_TRY(hipEventRecord(h->ev_resid, h->stream));
 #undef MARK
@@ -466,6 +474,7 @@ int strads_lasso_kkt(strads_lasso_t *h, float *max_violation, float *g_or_null)
 {
     if (!h || !max_violation) return STRADS_E_INVALID_ARG;
     if (h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR) HIP_TRY(launch_kkt_dense(h, g_or_null));
+    else if (h->cfg.layout == STRADS_LAYOUT_GENO2) HIP_TRY(launch_kkt_geno(h, g_or_null));
     else HIP_TRY(launch_kkt_csc(h, g_or_null));
     RoundScalars sc;
     const int rs = read_scalars(h, &sc);

@@ -72,6 +72,143 @@ __device__ __forceinline__ float4 load_k4(const float *__restrict__ col, int64_t
     }
 }
 
+// How the columns of X reach the kernel.
+enum { kLoadScalar = 0, kLoadVec4 = 1, kLoadGeno2 = 2 };
+
+// Packed genotype design: per-column mean and scale, words per column (see STRADS_LAYOUT_GENO2).
+struct GenoCols {
+    const float *mean, *scale;
+    int64_t words;
+};
+
+// Staging of NPAN panels of 128 columns, one stage of kGramKT rows at a time: fetch() brings a
+// stage from global memory into registers, stash() writes it K-contiguous into an LDS stage
+// ([panel][128 rows of kRow floats]).
+//   fp32 designs: a thread holds kPasses float4 per panel: column (it*kColsPerPass + tid/kKQ),
+//     floats (tid%kKQ)*4..+3.
+//   packed genotypes: a thread holds one 32-bit word (16 rows) per panel: column tid/2, rows
+//     16*(tid%2)..+15 of the stage; stash() decodes it to fp32 through the column's three values
+//     fl(fl(g - mean) * scale), g = 0, 1, 2.
+// Columns past the candidate count are clamped to the last candidate: their products land in
+// rows/columns >= L of the tile, which nobody reads.
+template <int LOAD, int NPAN>
+struct PanelLoader {
+    int64_t kbeg, kend;
+    // fp32
+    const float *col[NPAN * kPasses];
+    float4 R[NPAN * kPasses];
+    int crow, kq;
+    // packed genotypes
+    const uint32_t *wp[NPAN];
+    uint32_t W[NPAN];
+    int valid[NPAN];
+    float lut[NPAN][3];
+
+    __device__ __forceinline__ void init(const float *__restrict__ X, int64_t N, const int32_t *__restrict__ cand,
+                                         int32_t L, const int32_t (&tile)[NPAN], const GenoCols &gc, int64_t kb,
+                                         int64_t ke)
+    {
+        kbeg = kb;
+        kend = ke;
+        const int tid = threadIdx.x;
+        if (LOAD == kLoadGeno2) {
+            static_assert(LOAD != kLoadGeno2 || kGramKT == 32, "the genotype loader stages 32 rows at a time");
+            const uint32_t *Xw = reinterpret_cast<const uint32_t *>(X);
+#pragma unroll
+            for (int p = 0; p < NPAN; ++p) {
+                int i = tile[p] * kGramTile + (tid >> 1);
+                i = i < L ? i : L - 1;
+                const int64_t j = cand[i];
+                wp[p] = Xw + j * gc.words + kb / 16 + (tid & 1);
+                const float m = gc.mean[j], sc = gc.scale[j];
+                lut[p][0] = __fmul_rn(__fsub_rn(0.f, m), sc);
+                lut[p][1] = __fmul_rn(__fsub_rn(1.f, m), sc);
+                lut[p][2] = __fmul_rn(__fsub_rn(2.f, m), sc);
+                W[p] = 0u;
+                valid[p] = 0;
+            }
+        } else {
+            crow = tid / kKQ;
+            kq = (tid % kKQ) * 4;
+#pragma unroll
+            for (int p = 0; p < NPAN; ++p)
+#pragma unroll
+                for (int it = 0; it < kPasses; ++it) {
+                    int i = tile[p] * kGramTile + it * kColsPerPass + crow;
+                    i = i < L ? i : L - 1;
+                    col[p * kPasses + it] = X + (int64_t)cand[i] * N;
+                }
+        }
+    }
+
+    // stages 0 .. nfull()-1 lie entirely inside the slice and can be fetched without clamping
+    __device__ __forceinline__ int nfull() const
+    {
+        return LOAD == kLoadScalar ? 0 : (int)((kend - kbeg) / kGramKT);
+    }
+
+    __device__ __forceinline__ void fetch(int st)
+    {
+        if (LOAD == kLoadGeno2) {
+            const int64_t row0 = kbeg + (int64_t)st * kGramKT + 16 * (threadIdx.x & 1);
+            const int64_t left = kend - row0;                 // rows of this word inside the slice
+            const int v = left >= 16 ? 16 : (left > 0 ? (int)left : 0);
+#pragma unroll
+            for (int p = 0; p < NPAN; ++p) {
+                W[p] = v > 0 ? wp[p][2 * st] : 0u;            // a word that starts inside the column exists in full
+                valid[p] = v;
+            }
+        } else {
+            const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
+#pragma unroll
+            for (int i = 0; i < NPAN * kPasses; ++i) R[i] = load_k4<LOAD == kLoadVec4>(col[i], k, kend);
+        }
+    }
+
+    __device__ __forceinline__ void fetch_full(int st)
+    {
+        if (LOAD == kLoadGeno2) {
+#pragma unroll
+            for (int p = 0; p < NPAN; ++p) { W[p] = wp[p][2 * st]; valid[p] = 16; }
+        } else {
+            const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
+#pragma unroll
+            for (int i = 0; i < NPAN * kPasses; ++i) R[i] = *reinterpret_cast<const float4 *>(col[i] + k);
+        }
+    }
+
+    __device__ __forceinline__ void stash(float *stage) const
+    {
+        if (LOAD == kLoadGeno2) {
+            const int tid = threadIdx.x;
+#pragma unroll
+            for (int p = 0; p < NPAN; ++p) {
+                float *dst = stage + p * kPanel + (tid >> 1) * kRow + 16 * (tid & 1);
+                const uint32_t w = W[p];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float x[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int e = 4 * q + c;
+                        const uint32_t gq = (w >> (2 * e)) & 3u;
+                        const float val = gq == 0u ? lut[p][0] : (gq == 1u ? lut[p][1] : lut[p][2]);
+                        x[c] = e < valid[p] ? val : 0.f;
+                    }
+                    *reinterpret_cast<float4 *>(dst + 4 * q) = make_float4(x[0], x[1], x[2], x[3]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < NPAN; ++p)
+#pragma unroll
+                for (int it = 0; it < kPasses; ++it)
+                    *reinterpret_cast<float4 *>(stage + p * kPanel + (it * kColsPerPass + crow) * kRow + kq) =
+                        R[p * kPasses + it];
+        }
+    }
+};
+
 // store one 32x32 accumulator block: register v of lane (li, lh) holds row 8*(v/4) + 4*lh + (v%4),
 // column li of the block
 __device__ __forceinline__ void store_block(float *__restrict__ out, int32_t Lpad, int row0, int col0,
@@ -99,50 +236,24 @@ __device__ __forceinline__ void store_block_t(float *__restrict__ out, int32_t L
 // Off-diagonal tile (ta < tb).  Software pipeline per LDS stage st (32 K values): registers hold
 // stage st+1 (fetched one stage ago), they are written to the other LDS buffer, the fetch of stage
 // st+2 is issued, then stage st is multiplied out of LDS; one barrier per stage.
-template <bool VEC4>
+template <int LOAD>
 __device__ __forceinline__ void gram_tile_off(const float *__restrict__ X, int64_t N,
-                                              const int32_t *__restrict__ cand, const GramShape &g, int32_t ta,
-                                              int32_t tb, int32_t s, float *__restrict__ P, float *smem)
+                                              const int32_t *__restrict__ cand, const GramShape &g,
+                                              const GenoCols &gc, int32_t ta, int32_t tb, int32_t s,
+                                              float *__restrict__ P, float *smem)
 {
     const int tid = threadIdx.x;
     const int64_t kbeg = (int64_t)s * g.kchunk_off;
     const int64_t kend = (kbeg + g.kchunk_off < N) ? kbeg + g.kchunk_off : N;
     const int nstage = (int)((kend - kbeg + kGramKT - 1) / kGramKT);
 
-    // this thread stages kPasses A-columns and kPasses B-columns: column (it*kColsPerPass + tid/kKQ),
-    // floats (tid%kKQ)*4..+3.  Columns past the candidate count are clamped to the last candidate:
-    // their products land in rows/columns >= L of the tile, which nobody reads.
-    const int crow = tid / kKQ, kq = (tid % kKQ) * 4;
-    const float *col[2 * kPasses];
-#pragma unroll
-    for (int it = 0; it < kPasses; ++it) {
-        int ia = ta * kGramTile + it * kColsPerPass + crow, ib = tb * kGramTile + it * kColsPerPass + crow;
-        ia = ia < g.L ? ia : g.L - 1;
-        ib = ib < g.L ? ib : g.L - 1;
-        col[it] = X + (int64_t)cand[ia] * N;
-        col[kPasses + it] = X + (int64_t)cand[ib] * N;
-    }
-
-    float4 R[2 * kPasses];
-    auto fetch = [&](int st) {
-        const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
-#pragma unroll
-        for (int i = 0; i < 2 * kPasses; ++i) R[i] = load_k4<VEC4>(col[i], k, kend);
-    };
-    auto fetch_full = [&](int st) {             // a stage that lies entirely inside the slice: no clamping
-        const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
-#pragma unroll
-        for (int i = 0; i < 2 * kPasses; ++i) R[i] = *reinterpret_cast<const float4 *>(col[i] + k);
-    };
-    const int nfull = VEC4 ? (int)((kend - kbeg) / kGramKT) : 0;   // stages 0 .. nfull-1 are full
-    auto stash = [&](int buf) {
-        float *pa = smem + buf * 2 * kPanel, *pb = pa + kPanel;
-#pragma unroll
-        for (int it = 0; it < kPasses; ++it) {
-            *reinterpret_cast<float4 *>(pa + (it * kColsPerPass + crow) * kRow + kq) = R[it];
-            *reinterpret_cast<float4 *>(pb + (it * kColsPerPass + crow) * kRow + kq) = R[kPasses + it];
-        }
-    };
+    PanelLoader<LOAD, 2> ld;
+    const int32_t tiles[2] = {ta, tb};
+    ld.init(X, N, cand, g.L, tiles, gc, kbeg, kend);
+    auto fetch = [&](int st) { ld.fetch(st); };
+    auto fetch_full = [&](int st) { ld.fetch_full(st); };
+    auto stash = [&](int buf) { ld.stash(smem + buf * 2 * kPanel); };
+    const int nfull = ld.nfull();
 
     const int wave = tid >> 6, lane = tid & 63;
     const int wr = wave >> 1, wc = wave & 1;    // 64x64 sub-tile of this wavefront
@@ -232,42 +343,24 @@ __device__ __forceinline__ void gram_tile_off(const float *__restrict__ X, int64
 // Diagonal tile: one panel of 128 columns; 32-column groups p < q (< r) of this wavefront:
 //   wavefront 0: (0,0) (0,1) (1,1)      wavefront 3: (2,2) (2,3) (3,3)
 //   wavefront 1: (0,2) (0,3)            wavefront 2: (1,2) (1,3)
-template <bool VEC4>
+template <int LOAD>
 __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int64_t N,
-                                               const int32_t *__restrict__ cand, const GramShape &g, int32_t ta,
-                                               int32_t s, float *__restrict__ P, float *smem)
+                                               const int32_t *__restrict__ cand, const GramShape &g,
+                                               const GenoCols &gc, int32_t ta, int32_t s, float *__restrict__ P,
+                                               float *smem)
 {
     const int tid = threadIdx.x;
     const int64_t kbeg = (int64_t)s * g.kchunk_diag;
     const int64_t kend = (kbeg + g.kchunk_diag < N) ? kbeg + g.kchunk_diag : N;
     const int nstage = (int)((kend - kbeg + kGramKT - 1) / kGramKT);
 
-    const int crow = tid / kKQ, kq = (tid % kKQ) * 4;
-    const float *col[kPasses];
-#pragma unroll
-    for (int it = 0; it < kPasses; ++it) {
-        int ia = ta * kGramTile + it * kColsPerPass + crow;
-        ia = ia < g.L ? ia : g.L - 1;
-        col[it] = X + (int64_t)cand[ia] * N;
-    }
-    float4 R[kPasses];
-    auto fetch = [&](int st) {
-        const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
-#pragma unroll
-        for (int i = 0; i < kPasses; ++i) R[i] = load_k4<VEC4>(col[i], k, kend);
-    };
-    auto fetch_full = [&](int st) {
-        const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
-#pragma unroll
-        for (int i = 0; i < kPasses; ++i) R[i] = *reinterpret_cast<const float4 *>(col[i] + k);
-    };
-    const int nfull = VEC4 ? (int)((kend - kbeg) / kGramKT) : 0;
-    auto stash = [&](int buf) {
-        float *pa = smem + buf * 2 * kPanel;
-#pragma unroll
-        for (int it = 0; it < kPasses; ++it)
-            *reinterpret_cast<float4 *>(pa + (it * kColsPerPass + crow) * kRow + kq) = R[it];
-    };
+    PanelLoader<LOAD, 1> ld;
+    const int32_t tiles[1] = {ta};
+    ld.init(X, N, cand, g.L, tiles, gc, kbeg, kend);
+    auto fetch = [&](int st) { ld.fetch(st); };
+    auto fetch_full = [&](int st) { ld.fetch_full(st); };
+    auto stash = [&](int buf) { ld.stash(smem + buf * 2 * kPanel); };
+    const int nfull = ld.nfull();
 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int li = lane & 31, lh = lane >> 5;
@@ -360,9 +453,10 @@ __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int6
 
 // One job = one (tile, K-slice) pair.  Jobs are numbered with the off-diagonal tiles of the upper
 // triangle first (K-slice fastest), then the diagonal tiles.
-template <bool VEC4>
+template <int LOAD>
 __device__ __forceinline__ void gram_job(const float *__restrict__ X, int64_t N, const int32_t *__restrict__ cand,
-                                         const GramShape &g, int32_t job, float *__restrict__ P, float *smem)
+                                         const GramShape &g, const GenoCols &gc, int32_t job, float *__restrict__ P,
+                                         float *smem)
 {
     const int32_t n_off = g.T * (g.T - 1) / 2 * g.split_off;
     if (job < n_off) {
@@ -370,37 +464,37 @@ __device__ __forceinline__ void gram_job(const float *__restrict__ X, int64_t N,
         int32_t u = job / g.split_off;          // index into the row-major strict upper triangle
         int32_t ta = 0;
         while (u >= g.T - 1 - ta) { u -= g.T - 1 - ta; ++ta; }
-        gram_tile_off<VEC4>(X, N, cand, g, ta, ta + 1 + u, s, P, smem);
+        gram_tile_off<LOAD>(X, N, cand, g, gc, ta, ta + 1 + u, s, P, smem);
     } else {
         const int32_t d = job - n_off;
-        gram_tile_diag<VEC4>(X, N, cand, g, d / g.split_diag, d % g.split_diag, P, smem);
+        gram_tile_diag<LOAD>(X, N, cand, g, gc, d / g.split_diag, d % g.split_diag, P, smem);
     }
 }
 
 // Static dependencies: the decomposition is known on the host; grid.x = number of jobs.
-template <bool VEC4>
+template <int LOAD>
 __global__ __launch_bounds__(256, kGramOcc) void k_gram_tiles(const float *__restrict__ X, int64_t N,
                                                        const int32_t *__restrict__ cand, GramShape g,
-                                                       float *__restrict__ P)
+                                                       GenoCols gc, float *__restrict__ P)
 {
     extern __shared__ float smem[];             // [2 stages][A panel | B panel]
-    gram_job<VEC4>(X, N, cand, g, (int32_t)blockIdx.x, P, smem);
+    gram_job<LOAD>(X, N, cand, g, gc, (int32_t)blockIdx.x, P, smem);
 }
 
 // Dynamic dependencies: the Gram of the movers only.  Their number is known on the device alone,
 // so the launch has a fixed number of resident workgroups, which read the decomposition the mover
 // kernel chose and share its jobs round-robin.
-template <bool VEC4>
+template <int LOAD>
 __global__ __launch_bounds__(256, kGramOcc) void k_gram_tiles_dyn(const float *__restrict__ X, int64_t N,
                                                            const int32_t *__restrict__ mcand,
-                                                           const GramShape *__restrict__ gdev,
+                                                           const GramShape *__restrict__ gdev, GenoCols gc,
                                                            float *__restrict__ P)
 {
     extern __shared__ float smem[];
     const GramShape g = *gdev;
     const int32_t total = g.T * (g.T - 1) / 2 * g.split_off + g.T * g.split_diag;
     for (int32_t job = blockIdx.x; job < total; job += gridDim.x) {
-        gram_job<VEC4>(X, N, mcand, g, job, P, smem);
+        gram_job<LOAD>(X, N, mcand, g, gc, job, P, smem);
         __syncthreads();                        // the next job reuses the LDS panels
     }
 }
@@ -625,10 +719,10 @@ void gram_shape_table(int64_t n, int32_t lpad, GramShape *out)
 
 hipError_t launch_movers(strads_lasso *h)
 {
-    const bool dense = h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR;
+    const bool tiled = h->cfg.layout != STRADS_LAYOUT_CSC;      // dense and packed designs share the tile kernel
     hipLaunchKernelGGL(k_movers, dim3(1), dim3(1024), 0, h->stream, h->at<float>(h->ws.dc),
-                       h->at<int32_t>(h->ws.cand), h->L, dense ? h->at<GramShape>(h->ws.dtable) : nullptr,
-                       dense ? 0 : h->Lpad, h->at<int32_t>(h->ws.mpos),
+                       h->at<int32_t>(h->ws.cand), h->L, tiled ? h->at<GramShape>(h->ws.dtable) : nullptr,
+                       tiled ? 0 : h->Lpad, h->at<int32_t>(h->ws.mpos),
                        h->at<int32_t>(h->ws.mcand), h->at<RoundScalars>(h->ws.scalars),
                        h->at<GramShape>(h->ws.dshape));
     return hipGetLastError();
@@ -672,23 +766,26 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
                            &sc->near_rho_pairs);
         return hipGetLastError();
     }
+    const int load = h->cfg.layout == STRADS_LAYOUT_GENO2 ? kLoadGeno2 : (h->vec4 ? kLoadVec4 : kLoadScalar);
+    GenoCols gc;
+    gc.mean = h->cfg.col_mean;
+    gc.scale = h->cfg.col_scale;
+    gc.words = geno_words(h->cfg.n);
     if (dynamic) {
         const int32_t *mcand = h->at<int32_t>(h->ws.mcand);
-        if (h->vec4)
-            hipLaunchKernelGGL(k_gram_tiles_dyn<true>, dim3(kGramSlots), dim3(256), lds, h->stream, h->cfg.x,
-                               h->cfg.n, mcand, gdev, P);
-        else
-            hipLaunchKernelGGL(k_gram_tiles_dyn<false>, dim3(kGramSlots), dim3(256), lds, h->stream, h->cfg.x,
-                               h->cfg.n, mcand, gdev, P);
+#define STRADS_GRAM_DYN(LD) hipLaunchKernelGGL(k_gram_tiles_dyn<LD>, dim3(kGramSlots), dim3(256), lds, h->stream, h->cfg.x, h->cfg.n, mcand, gdev, gc, P)
+        if (load == kLoadGeno2) STRADS_GRAM_DYN(kLoadGeno2);
+        else if (load == kLoadVec4) STRADS_GRAM_DYN(kLoadVec4);
+        else STRADS_GRAM_DYN(kLoadScalar);
+#undef STRADS_GRAM_DYN
         return hipGetLastError();
     }
     const dim3 grid((unsigned)(g.T * (g.T - 1) / 2 * g.split_off + g.T * g.split_diag));
-    if (h->vec4)
-        hipLaunchKernelGGL(k_gram_tiles<true>, grid, dim3(256), lds, h->stream, h->cfg.x, h->cfg.n,
-                           h->at<int32_t>(h->ws.cand), g, P);
-    else
-        hipLaunchKernelGGL(k_gram_tiles<false>, grid, dim3(256), lds, h->stream, h->cfg.x, h->cfg.n,
-                           h->at<int32_t>(h->ws.cand), g, P);
+#define STRADS_GRAM(LD) hipLaunchKernelGGL(k_gram_tiles<LD>, grid, dim3(256), lds, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), g, gc, P)
+    if (load == kLoadGeno2) STRADS_GRAM(kLoadGeno2);
+    else if (load == kLoadVec4) STRADS_GRAM(kLoadVec4);
+    else STRADS_GRAM(kLoadScalar);
+#undef STRADS_GRAM
     return hipGetLastError();
 }
 
@@ -702,15 +799,17 @@ hipError_t launch_mask_from_gram(strads_lasso *h, const float *gram, int32_t l)
 hipError_t gram_prepare()
 {
     const int lds = 2 * 2 * kPanel * (int)sizeof(float);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gram_tiles<true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gram_tiles<false>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gram_tiles_dyn<true>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_gram_tiles_dyn<false>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    return e;
+    const void *kernels[] = {reinterpret_cast<const void *>(k_gram_tiles<kLoadScalar>),
+                             reinterpret_cast<const void *>(k_gram_tiles<kLoadVec4>),
+                             reinterpret_cast<const void *>(k_gram_tiles<kLoadGeno2>),
+                             reinterpret_cast<const void *>(k_gram_tiles_dyn<kLoadScalar>),
+                             reinterpret_cast<const void *>(k_gram_tiles_dyn<kLoadVec4>),
+                             reinterpret_cast<const void *>(k_gram_tiles_dyn<kLoadGeno2>)};
+    for (const void *k : kernels) {
+        const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 } // namespace strads

@@ -95,7 +95,7 @@ struct strads_lasso {
     hipStream_t stream;
     int32_t L;          // min(l_prime, J)
     int32_t Lpad;       // L rounded up to the Gram tile
-    int64_t Npad;       // N rounded up to 4
+    int64_t Npad;       // N rounded up to 64; r[N .. Npad) is kept at zero
     int32_t split_max;  // K-slices the workspace was sized for
     int32_t split_user; // tuning override (0 = automatic)
     int32_t select_cap;
@@ -150,6 +150,8 @@ hipError_t launch_commit_dynamic(strads_lasso *h);        // B_1 = non-movers + 
 hipError_t launch_scatter_mover_gram(strads_lasso *h, float *out);   // L x L image of the mover Gram
 hipError_t launch_dots_dense(strads_lasso *h);                             // x_j^T r for the kept set + eq. (2) update
 hipError_t launch_residual_dense(strads_lasso *h);                         // r -= X_B delta_B
+hipError_t launch_residual_apply(strads_lasso *h, int groups);             // r -= sum of the groups' partial sums
+int residual_groups(int64_t n, int32_t l);
 hipError_t launch_objective(strads_lasso *h);                              // -> objout
 hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null);            // -> scalars.kkt_max_bits
 hipError_t launch_init_state(strads_lasso *h);
@@ -158,6 +160,12 @@ hipError_t launch_clear_kkt(strads_lasso *h);
 hipError_t sampler_prepare();
 hipError_t gram_prepare();
 hipError_t filter_prepare();
+// packed genotype design (STRADS_LAYOUT_GENO2); the Gram uses launch_gram_dense with a decoding loader
+inline int64_t geno_words(int64_t n) { return (n + 63) / 64 * 4; }   // 32-bit words per column
+hipError_t launch_dots_geno(strads_lasso *h);
+hipError_t launch_dots_cand_geno(strads_lasso *h);
+hipError_t launch_residual_geno(strads_lasso *h);
+hipError_t launch_kkt_geno(strads_lasso *h, float *g_or_null);
 // CSC design
 hipError_t launch_gram_csc(strads_lasso *h);
 hipError_t launch_dots_csc(strads_lasso *h);

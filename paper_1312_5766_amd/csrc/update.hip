@@ -399,7 +399,8 @@ __global__ __launch_bounds__(256) void k_kkt_stream(const float *__restrict__ X,
     if (t < 2 && vmax > 0.f) atomicMax(&sc->kkt_max_bits, __float_as_uint(vmax));
 }
 
-__global__ __launch_bounds__(256) void k_init_state(const float *__restrict__ y, int64_t N, int64_t J, float c_init,
+__global__ __launch_bounds__(256) void k_init_state(const float *__restrict__ y, int64_t N, int64_t Npad, int64_t J,
+                                                    float c_init,
                                                     float *__restrict__ beta, float *__restrict__ dbeta,
                                                     float *__restrict__ r, uint32_t *__restrict__ hist,
                                                     uint32_t *__restrict__ scalars_words, int n_scalar_words)
@@ -410,7 +411,8 @@ __global__ __launch_bounds__(256) void k_init_state(const float *__restrict__ y,
         for (int i = threadIdx.x; i < 2 * kHistBins; i += 256) hist[i] = 0u;
         for (int i = threadIdx.x; i < n_scalar_words; i += 256) scalars_words[i] = 0u;
     }
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < N; i += stride) r[i] = y[i];
+    // the padding of r stays zero for good: kernels that work on whole 64-row groups rely on it
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < Npad; i += stride) r[i] = i < N ? y[i] : 0.f;
     for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < J; j += stride) { beta[j] = 0.f; dbeta[j] = c_init; }
 }
 
@@ -475,8 +477,14 @@ hipError_t launch_residual_dense(strads_lasso *h)
     else
         hipLaunchKernelGGL(k_residual_partial<false>, grid, dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->Npad,
                            h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc, part);
-    hipLaunchKernelGGL(k_residual_apply, dim3((unsigned)((h->cfg.n + 255) / 256)), dim3(256), 0, h->stream, part, G,
-                       h->cfg.n, h->Npad, h->at<float>(h->ws.r));
+    const hipError_t e = hipGetLastError();
+    return e != hipSuccess ? e : launch_residual_apply(h, G);
+}
+
+hipError_t launch_residual_apply(strads_lasso *h, int groups)
+{
+    hipLaunchKernelGGL(k_residual_apply, dim3((unsigned)((h->cfg.n + 255) / 256)), dim3(256), 0, h->stream,
+                       h->at<float>(h->ws.rpart), groups, h->cfg.n, h->Npad, h->at<float>(h->ws.r));
     return hipGetLastError();
 }
 
@@ -526,7 +534,8 @@ hipError_t launch_clear_kkt(strads_lasso *h)
 
 hipError_t launch_init_state(strads_lasso *h)
 {
-    hipLaunchKernelGGL(k_init_state, dim3(1024), dim3(256), 0, h->stream, h->cfg.y, h->cfg.n, h->cfg.j, h->cfg.c_init,
+    hipLaunchKernelGGL(k_init_state, dim3(1024), dim3(256), 0, h->stream, h->cfg.y, h->cfg.n, h->Npad, h->cfg.j,
+                       h->cfg.c_init,
                        h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.r),
                        h->at<uint32_t>(h->ws.hist), h->at<uint32_t>(h->ws.scalars), (int)(sizeof(RoundScalars) / 4));
     return hipGetLastError();

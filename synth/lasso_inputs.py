@@ -30,7 +30,7 @@ class LassoProblem:
     name: str
     n: int                      # rows (samples)
     j: int                      # columns (covariates)
-    layout: str                 # "dense" | "csc"
+    layout: str                 # "dense" | "csc" | "geno2"
     y: torch.Tensor             # (n,) fp32
     lam: float                  # lambda of eq. (1)
     rho: float                  # dependency threshold
@@ -43,6 +43,9 @@ class LassoProblem:
     values: Optional[torch.Tensor] = None   # csc: (nnz,) fp32
     row_idx: Optional[torch.Tensor] = None  # csc: (nnz,) int32, sorted per column
     col_ptr: Optional[torch.Tensor] = None  # csc: (j+1,) int64
+    codes: Optional[torch.Tensor] = None    # geno2: (j, 4*ceil(n/64)) int32, 16 two-bit genotype counts per word
+    col_mean: Optional[torch.Tensor] = None   # geno2: (j,) fp32
+    col_scale: Optional[torch.Tensor] = None  # geno2: (j,) fp32; x_ij = fl(fl(g_ij - mean_j) * scale_j)
 
     def to(self, device) -> "LassoProblem":
         kw = {}
@@ -171,6 +174,89 @@ def genotype(n=500, j=500000, nnz=100, sigma=0.5, lam_frac=0.05, l_prime=2000, r
     return _finish_dense(name, x, nnz, 0.2, 1.0, sigma, lam_frac, rho, eta, l_prime, rounds, seed, g)
 
 
+def geno_words(n: int) -> int:
+    """32-bit words per packed genotype column: 16 rows per word, columns padded to 16 bytes."""
+    return (n + 63) // 64 * 4
+
+
+def pack_genotypes(g: torch.Tensor) -> torch.Tensor:
+    """(j, n) integer counts in {0,1,2} -> (j, geno_words(n)) int32: row 16w+e of a column sits in
+    bits 2e, 2e+1 of its word w; rows past n are 0."""
+    j, n = g.shape
+    words = geno_words(n)
+    pad = torch.zeros((j, words * 16), dtype=torch.int64, device=g.device)
+    pad[:, :n] = g.to(torch.int64)
+    shifts = (2 * torch.arange(16, device=g.device, dtype=torch.int64)).view(1, 1, 16)
+    packed = (pad.view(j, words, 16) << shifts).sum(dim=2)              # < 2^32
+    return torch.where(packed >= 2 ** 31, packed - 2 ** 32, packed).to(torch.int32)
+
+
+def unpack_genotypes(codes: torch.Tensor, n: int) -> torch.Tensor:
+    """Inverse of pack_genotypes: (j, n) uint8."""
+    j, words = codes.shape
+    w = codes.to(torch.int64) & 0xFFFFFFFF
+    shifts = (2 * torch.arange(16, device=codes.device, dtype=torch.int64)).view(1, 1, 16)
+    return ((w.view(j, words, 1) >> shifts) & 3).view(j, words * 16)[:, :n].to(torch.uint8)
+
+
+def decode_genotypes(codes: torch.Tensor, mean: torch.Tensor, scale: torch.Tensor, n: int) -> torch.Tensor:
+    """The fp32 design a packed genotype matrix stands for: x_ij = fl(fl(g_ij - mean_j) * scale_j),
+    both operations in fp32 (exactly what the library's kernels decode)."""
+    g = unpack_genotypes(codes, n).to(torch.float32)
+    return (g - mean.view(-1, 1).to(torch.float32)) * scale.view(-1, 1).to(torch.float32)
+
+
+def genotype_packed(n=500, j=500000, nnz=100, sigma=0.5, lam_frac=0.05, l_prime=2000, rho=0.1, eta=1e-6,
+                    rounds=200, seed=0, device="cpu", chunk=20000, keep_dense=True,
+                    name="genotype_packed") -> LassoProblem:
+    """Config 3 stored as 2-bit genotype counts plus a mean and a scale per column.  The counts are
+    drawn as in `genotype`; mean and scale are the fp64 column mean and 1 / l2-norm of the centred
+    column, rounded to fp32.  With keep_dense the decoded fp32 design (what the oracle is given) is
+    kept in `x`; y and lambda are always computed from it, chunk by chunk."""
+    g = _gen(seed, device)
+    words = geno_words(n)
+    codes = torch.empty((j, words), dtype=torch.int32, device=device)
+    mean = torch.empty(j, dtype=torch.float32, device=device)
+    scale = torch.empty(j, dtype=torch.float32, device=device)
+    x = torch.empty((j, n), dtype=torch.float32, device=device) if keep_dense else None
+    for s in range(0, j, chunk):
+        e = min(j, s + chunk)
+        p = 0.05 + 0.45 * torch.rand((e - s, 1), generator=g, device=device)
+        blk = ((torch.rand((e - s, n), generator=g, device=device) < p).to(torch.int64)
+               + (torch.rand((e - s, n), generator=g, device=device) < p).to(torch.int64))
+        const = (blk.max(dim=1).values == blk.min(dim=1).values)
+        if bool(const.any()):
+            rows = torch.nonzero(const).flatten()
+            pos = torch.randint(0, n, (rows.numel(),), generator=g, device=device)
+            blk[rows] = 0
+            blk[rows, pos] = 1
+        b64 = blk.to(torch.float64)
+        mu = b64.mean(dim=1)
+        nrm = (b64 - mu.view(-1, 1)).norm(dim=1)
+        mean[s:e] = mu.to(torch.float32)
+        scale[s:e] = (1.0 / nrm).to(torch.float32)
+        codes[s:e] = pack_genotypes(blk)
+        if keep_dense:
+            x[s:e] = decode_genotypes(codes[s:e], mean[s:e], scale[s:e], n)
+
+    def cols(ids):                                       # decoded columns, on demand
+        return x[ids] if keep_dense else decode_genotypes(codes[ids], mean[ids], scale[ids], n)
+
+    beta64 = _planted_beta(j, nnz, 0.2, 1.0, g, device)
+    nz = torch.nonzero(beta64).flatten()
+    y64 = beta64[nz] @ cols(nz).to(torch.float64)
+    y64 += sigma * torch.randn(n, generator=g, device=device, dtype=torch.float64)
+    y32 = y64.to(torch.float32)
+    m = 0.0
+    for s in range(0, j, chunk):
+        ids = torch.arange(s, min(j, s + chunk), device=device)
+        m = max(m, float((cols(ids).to(torch.float64) @ y32.to(torch.float64)).abs().max()))
+    lam = float(torch.tensor(lam_frac * m, dtype=torch.float32))
+    return LassoProblem(name=name, n=n, j=j, layout="geno2", x=x, y=y32, lam=lam, rho=rho, eta=eta,
+                        l_prime=min(l_prime, j), rounds=rounds, seed=seed, beta_true=beta64.to(torch.float32),
+                        codes=codes, col_mean=mean, col_scale=scale)
+
+
 def dense_duplicates(n=50000, j=1000000, dup_frac=0.3, dup_corr=0.9, nnz=2000, sigma=0.1,
                      lam_frac=0.02, l_prime=8000, rho=0.1, eta=1e-6, rounds=0, seed=0, device="cpu",
                      chunk=2048, name="dense_duplicates") -> LassoProblem:
@@ -273,6 +359,7 @@ CONFIGS = {
     "c3_genotype": genotype,
     "c4_sparse_csc": sparse_csc,
     "c5_dense_duplicates": dense_duplicates,
+    "c3_genotype_packed": genotype_packed,
 }
 
 

@@ -37,6 +37,10 @@ def _pair(p, keep_gram=True, dynamic=True, **kw):
     if p.layout == "dense":
         g = pk.StradsLasso(x=p.x.to(dev), y=p.y.to(dev), keep_gram=keep_gram, dynamic=dynamic, **args)
         o = OracleLasso(x=p.x.cpu().numpy(), y=p.y.cpu().numpy(), dynamic=dynamic, **args)
+    elif p.layout == "geno2":
+        g = pk.StradsLasso(codes=p.codes.to(dev), col_mean=p.col_mean.to(dev), col_scale=p.col_scale.to(dev),
+                           n=p.n, y=p.y.to(dev), keep_gram=keep_gram, dynamic=dynamic, **args)
+        o = OracleLasso(x=p.x.cpu().numpy(), y=p.y.cpu().numpy(), dynamic=dynamic, **args)
     else:
         g = pk.StradsLasso(values=p.values.to(dev), row_idx=p.row_idx.to(dev), col_ptr=p.col_ptr.to(dev), n=p.n,
                            y=p.y.to(dev), keep_gram=keep_gram, dynamic=dynamic, **args)

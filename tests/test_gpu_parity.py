@@ -37,6 +37,11 @@ def _pair(p, keep_gram=True, **kw):
         xg = p.x.to(dev)
         g = pk.StradsLasso(x=xg, y=p.y.to(dev), keep_gram=keep_gram, **args)
         o = OracleLasso(x=p.x.cpu().numpy(), y=p.y.cpu().numpy(), **args)
+    elif p.layout == "geno2":
+        # packed 2-bit design on the GPU; the oracle gets the fp32 matrix the codes stand for
+        g = pk.StradsLasso(codes=p.codes.to(dev), col_mean=p.col_mean.to(dev), col_scale=p.col_scale.to(dev),
+                           n=p.n, y=p.y.to(dev), keep_gram=keep_gram, **args)
+        o = OracleLasso(x=p.x.cpu().numpy(), y=p.y.cpu().numpy(), **args)
     else:
         g = pk.StradsLasso(values=p.values.to(dev), row_idx=p.row_idx.to(dev), col_ptr=p.col_ptr.to(dev), n=p.n,
                            y=p.y.to(dev), keep_gram=keep_gram, **args)

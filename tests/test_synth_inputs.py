@@ -57,3 +57,31 @@ def test_c5_duplicates():
     g = (p.x.double() @ p.x.double().T).abs() - torch.eye(600, dtype=torch.float64)
     n_corr = int((g.max(dim=1).values > 0.8).sum())
     assert 0.3 * 600 <= n_corr <= 0.62 * 600          # each duplicate and (at most) its source
+
+
+def test_packed_genotypes_bit_layout_and_decoding():
+    # bit layout written out by hand: rows 0, 1, 2, 17 of one column hold 1, 2, 0, 2
+    g = torch.zeros((1, 20), dtype=torch.int64)
+    g[0, 0], g[0, 1], g[0, 17] = 1, 2, 2
+    w = si.pack_genotypes(g)
+    assert w.shape == (1, 4) and w.tolist() == [[1 | (2 << 2), 2 << 2, 0, 0]]
+    # the top pair of bits of a word (row 15) survives the signed 32-bit storage
+    g = torch.zeros((1, 16), dtype=torch.int64)
+    g[0, 15] = 2
+    w = si.pack_genotypes(g)
+    assert int(w[0, 0]) == -(1 << 31) and si.unpack_genotypes(w, 16)[0].tolist() == [0] * 15 + [2]
+    # column stride: multiples of 16 bytes
+    assert [si.geno_words(n) for n in (1, 16, 64, 65, 128, 500)] == [4, 4, 4, 8, 8, 32]
+    # round trip, and the decoded matrix is a standardised design whose columns take three values
+    p = si.make("c3_genotype_packed", n=203, j=700, nnz=10, l_prime=50)
+    gg = si.unpack_genotypes(p.codes, p.n)
+    assert int(gg.max()) <= 2 and torch.equal(si.pack_genotypes(gg), p.codes)
+    assert p.codes.dtype == torch.int32 and p.codes.shape == (700, si.geno_words(203))
+    _check_standardized(p.x)
+    x64 = (gg.double() - p.col_mean.double().view(-1, 1)) * p.col_scale.double().view(-1, 1)
+    assert (p.x.double() - x64).abs().max() < 1e-6
+    assert max(len(torch.unique(p.x[j])) for j in range(0, 700, 31)) <= 3
+    # the two roundings of the decode, one at a time
+    j, i = 5, 11
+    d = (gg[j, i].float() - p.col_mean[j])            # fp32 subtraction
+    assert float(p.x[j, i]) == float(d * p.col_scale[j])
