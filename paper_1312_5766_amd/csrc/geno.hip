@@ -10,12 +10,11 @@
 
 namespace strads {
 
-constexpr int kGenoCols = 4;   // columns a wavefront processes together
-
-static __device__ __forceinline__ float gwave_sum(float v)
+// sum over the wavefront, returned in every lane (butterfly: the same tree in every lane)
+static __device__ __forceinline__ float gwave_sum_all(float v)
 {
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
     return v;
 }
 
@@ -42,104 +41,161 @@ static __device__ __forceinline__ float soft_threshold_g(float a, float lambda)
     return m > 0.f ? copysignf(m, a) : 0.f;
 }
 
-// x_j^T r for up to kGenoCols columns by one wavefront; out[c] valid in lane 0.  cols[c] < 0: skip.
-static __device__ __forceinline__ void geno_dots(const uint32_t *__restrict__ Xw, int64_t words,
-                                                 const float *__restrict__ mean, const float *__restrict__ scale,
-                                                 const int64_t (&cols)[kGenoCols], const float *__restrict__ r,
-                                                 int lane, float (&out)[kGenoCols])
+// ---------------------------------------------------------------------------------------------
+// x_j^T r on packed words.  With g the genotype count,
+//     x_j^T r = scale_j * (sum_i g_ij r_i  -  mean_j * sum_i r_i),
+// so a column needs one multiply-add per entry on the raw count and no per-entry decode; rows past
+// N hold count 0 and add nothing.  (This differs from summing the decoded fl(fl(g - mean) * scale)
+// entries by rounding only.)
+//
+// A lane owns a column.  Work proceeds in slabs of SW words (16 SW rows): a wavefront brings its 64
+// columns' slab in with 16-byte loads (SW/4 lanes cover one column's piece), turns it through its
+// own piece of LDS, and then every lane walks its column's words while the slab of r is read at
+// wave-uniform addresses.  Within a word the four byte lanes of (word >> 2q) & 0x03030303
+// are entries q, q+4, q+8, q+12; masking in place instead of shifting leaves the count scaled by
+// 4^q, which one exact multiply per column removes at the end.
+//   COLS = 256: a wavefront walks all slabs (512 rows each) of its 64 columns: the pass over all J
+//               columns.
+//   COLS =  64: the four wavefronts of a workgroup share 64 columns and take every fourth slab of
+//               128 rows, combined in wavefront order: short lists of candidates, where a round
+//               waits on this kernel and the row range has to be spread to shorten it.
+template <int COLS> struct GenoSlab {
+    static constexpr int kWords = COLS == 256 ? 32 : 8;
+    static constexpr int kStride = kWords + 1;  // odd stride: lanes reading one word each hit distinct banks
+};
+
+struct GenoSums { float gr, rs; };             // sum g r, sum r over the slabs a wavefront walked
+
+template <int COLS>
+static __device__ __forceinline__ GenoSums geno_column_sums(const uint32_t *__restrict__ Xw, int64_t words,
+                                                            int64_t col, const float *__restrict__ r,
+                                                            uint32_t *__restrict__ lds_wave)
 {
-    GenoLut lut[kGenoCols];
-    const uint32_t *cp[kGenoCols];
+    constexpr int PH = 256 / COLS;             // wavefronts sharing a column
+    constexpr int SW = GenoSlab<COLS>::kWords, STRIDE = GenoSlab<COLS>::kStride;
+    constexpr int CH = SW / 4;                 // 16-byte pieces of a column's slab = lanes per column = passes
+    const int lane = threadIdx.x & 63;
+    const int phase = COLS == 256 ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int nslab = (int)((words + SW - 1) / SW);
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f, rs = 0.f;
+    for (int sl = phase; sl < nslab; sl += PH) {
+        const int64_t w0 = (int64_t)sl * SW;
+        // stage: pass i brings 16 bytes of each of 64/CH columns
+        uint4 v[CH];
 #pragma unroll
-    for (int c = 0; c < kGenoCols; ++c) {
-        const int64_t j = cols[c] >= 0 ? cols[c] : cols[0];
-        lut[c] = geno_lut(mean[j], scale[j]);
-        cp[c] = Xw + j * words;
-    }
-    float acc[kGenoCols] = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t w = lane; w < words; w += 64) {
-        const float4 *r4 = reinterpret_cast<const float4 *>(r + 16 * w);
-        const float4 ra = r4[0], rb = r4[1], rc = r4[2], rd = r4[3];
-        const float rv[16] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y, rb.z, rb.w, rc.x, rc.y, rc.z, rc.w, rd.x, rd.y, rd.z, rd.w};
-#pragma unroll
-        for (int c = 0; c < kGenoCols; ++c) {
-            const uint32_t word = cp[c][w];
-            float s = 0.f;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) s += geno_value(word, e, lut[c]) * rv[e];
-            acc[c] += s;
+        for (int i = 0; i < CH; ++i) {
+            const int slot = (64 / CH) * i + lane / CH;
+            const int64_t cj = __shfl(col, slot);
+            const int64_t w = w0 + 4 * (lane % CH);
+            v[i] = w < words ? *reinterpret_cast<const uint4 *>(Xw + cj * words + w) : make_uint4(0u, 0u, 0u, 0u);
         }
-    }
+        // sum of r over the slab, in a fixed order
+        float rpart = 0.f;
 #pragma unroll
-    for (int c = 0; c < kGenoCols; ++c) out[c] = gwave_sum(acc[c]);
+        for (int k = 0; k < SW / 4; ++k) {
+            const int64_t i = 16 * w0 + lane + 64 * k;
+            rpart += i < 16 * words ? r[i] : 0.f;
+        }
+        rs += gwave_sum_all(rpart);
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            uint32_t *dst = lds_wave + ((64 / CH) * i + lane / CH) * STRIDE + 4 * (lane % CH);
+            dst[0] = v[i].x; dst[1] = v[i].y; dst[2] = v[i].z; dst[3] = v[i].w;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int nw = words - w0 < SW ? (int)(words - w0) : SW;
+        const uint32_t *src = lds_wave + lane * STRIDE;
+#pragma unroll 4
+        for (int w = 0; w < nw; ++w) {
+            const uint32_t code = src[w];
+            const float *rw = r + 16 * (w0 + w);           // wave-uniform address
+            uint32_t t0 = code & 0x03030303u, t1 = code & 0x0C0C0C0Cu;
+            uint32_t t2 = code & 0x30303030u, t3 = code & 0xC0C0C0C0u;
+            // keep the four masked words as they are, so that each entry is one byte-to-float conversion
+            asm volatile("" : "+v"(t0), "+v"(t1), "+v"(t2), "+v"(t3));
+#define STRADS_GENO_ACC(A, T, Q)                                                                    \
+            A = __builtin_fmaf((float)((T) & 0xFFu), rw[Q], A);                                     \
+            A = __builtin_fmaf((float)(((T) >> 8) & 0xFFu), rw[(Q) + 4], A);                        \
+            A = __builtin_fmaf((float)(((T) >> 16) & 0xFFu), rw[(Q) + 8], A);                       \
+            A = __builtin_fmaf((float)((T) >> 24), rw[(Q) + 12], A)
+            STRADS_GENO_ACC(a0, t0, 0);
+            STRADS_GENO_ACC(a1, t1, 1);
+            STRADS_GENO_ACC(a2, t2, 2);
+            STRADS_GENO_ACC(a3, t3, 3);
+#undef STRADS_GENO_ACC
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();                    // the slab is consumed before the next one lands
+    }
+    GenoSums out;
+    out.gr = (a0 + 0.25f * a1) + (0.0625f * a2 + 0.015625f * a3);
+    out.rs = rs;
+    return out;
 }
 
-// eq. (2) and Step 4 for the kept set (COMMIT) or the tentative update of every candidate (!COMMIT)
-template <bool COMMIT>
+enum { kGenoCommit = 0, kGenoTentative = 1, kGenoAll = 2 };
+
+// MODE kGenoCommit:    eq. (2) and Step 4 for the kept set (count on the device)
+// MODE kGenoTentative: dot product and tentative update of every candidate
+// MODE kGenoAll:       x_j^T r and the optimality violation of all J columns (see k_kkt)
+template <int MODE, int COLS>
 __global__ __launch_bounds__(256) void k_geno_dots(const uint32_t *__restrict__ Xw, int64_t words,
                                                    const float *__restrict__ mean, const float *__restrict__ scale,
-                                                   const int32_t *__restrict__ list, int32_t n_host,
-                                                   const RoundScalars *__restrict__ sc, const float *__restrict__ r,
+                                                   const int32_t *__restrict__ list, int64_t n_host,
+                                                   RoundScalars *__restrict__ sc, const float *__restrict__ r,
                                                    float lambda, float *__restrict__ beta, float *__restrict__ dbeta,
                                                    float *__restrict__ z, float *__restrict__ delta,
                                                    float *__restrict__ newbeta)
 {
-    const int n = COMMIT ? sc->n_kept : n_host;
-    const int c0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kGenoCols;
-    if (c0 >= n) return;                        // whole wavefront
-    int64_t cols[kGenoCols];
-#pragma unroll
-    for (int c = 0; c < kGenoCols; ++c) cols[c] = c0 + c < n ? (int64_t)list[c0 + c] : -1;
-    float s[kGenoCols];
-    geno_dots(Xw, words, mean, scale, cols, r, threadIdx.x & 63, s);
-    if ((threadIdx.x & 63) == 0) {
-#pragma unroll
-        for (int c = 0; c < kGenoCols; ++c) {
-            if (cols[c] < 0) continue;
-            const int64_t j = cols[c];
-            const float b = beta[j];
-            const float nb = soft_threshold_g(s[c] + b, lambda);
-            const float d = nb - b;
-            z[c0 + c] = s[c];
-            delta[c0 + c] = d;
-            if (COMMIT) { beta[j] = nb; dbeta[j] = fabsf(d); }
-            else newbeta[c0 + c] = nb;
-        }
-    }
-}
-
-// optimality violation over all columns (see k_kkt): persistent wavefronts, four columns each step
-__global__ __launch_bounds__(256) void k_geno_kkt(const uint32_t *__restrict__ Xw, int64_t words,
-                                                  const float *__restrict__ mean, const float *__restrict__ scale,
-                                                  int64_t J, const float *__restrict__ r,
-                                                  const float *__restrict__ beta, float lambda,
-                                                  float *__restrict__ g_out, RoundScalars *__restrict__ sc)
-{
+    __shared__ uint32_t slab[4][64 * GenoSlab<COLS>::kStride];
+    __shared__ GenoSums comb[4][64];
     __shared__ float vm[4];
-    float vmax = 0.f;
+    const int64_t n = MODE == kGenoCommit ? (int64_t)sc->n_kept : n_host;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (int64_t j0 = ((int64_t)blockIdx.x * 4 + wave) * kGenoCols; j0 < J; j0 += (int64_t)gridDim.x * 4 * kGenoCols) {
-        int64_t cols[kGenoCols];
-#pragma unroll
-        for (int c = 0; c < kGenoCols; ++c) cols[c] = j0 + c < J ? j0 + c : -1;
-        float s[kGenoCols];
-        geno_dots(Xw, words, mean, scale, cols, r, lane, s);
-        if (lane == 0) {
-#pragma unroll
-            for (int c = 0; c < kGenoCols; ++c) {
-                if (cols[c] < 0) continue;
-                const float g = s[c], b = beta[cols[c]];
-                if (g_out) g_out[cols[c]] = g;
-                float v = b == 0.f ? fmaxf(fabsf(g) - lambda, 0.f) : fabsf(g - copysignf(lambda, b));
-                if (!(v == v)) v = __uint_as_float(0x7F800000u);
-                vmax = fmaxf(vmax, v);
-            }
-        }
+    const int64_t c = COLS == 256 ? (int64_t)blockIdx.x * 256 + threadIdx.x : (int64_t)blockIdx.x * 64 + lane;
+    if ((int64_t)blockIdx.x * COLS >= n) return;            // whole workgroup
+    const bool live = c < n;
+    // lanes past the end walk the workgroup's first column and drop the result
+    const int64_t cc = live ? c : (int64_t)blockIdx.x * COLS;
+    const int64_t j = MODE == kGenoAll ? cc : (int64_t)list[cc];
+    GenoSums s = geno_column_sums<COLS>(Xw, words, j, r, slab[wave]);
+    if (COLS == 64) {
+        comb[wave][lane] = s;
+        __syncthreads();
+        if (wave != 0) return;
+        s.gr = (comb[0][lane].gr + comb[1][lane].gr) + (comb[2][lane].gr + comb[3][lane].gr);
+        s.rs = (comb[0][lane].rs + comb[1][lane].rs) + (comb[2][lane].rs + comb[3][lane].rs);
     }
-    if (lane == 0) vm[wave] = vmax;
-    __syncthreads();
-    if (threadIdx.x == 0)
-        atomicMax(&sc->kkt_max_bits, __float_as_uint(fmaxf(fmaxf(vm[0], vm[1]), fmaxf(vm[2], vm[3]))));
+    const float dot = scale[j] * (s.gr - mean[j] * s.rs);
+    if (MODE == kGenoAll) {
+        float v = 0.f;
+        if (live) {
+            const float b = beta[j];
+            if (z) z[j] = dot;
+            v = b == 0.f ? fmaxf(fabsf(dot) - lambda, 0.f) : fabsf(dot - copysignf(lambda, b));
+            if (!(v == v)) v = __uint_as_float(0x7F800000u);
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_down(v, off));
+        if (COLS == 64) {
+            if (lane == 0) atomicMax(&sc->kkt_max_bits, __float_as_uint(v));
+        } else {
+            if (lane == 0) vm[wave] = v;
+            __syncthreads();
+            if (threadIdx.x == 0)
+                atomicMax(&sc->kkt_max_bits, __float_as_uint(fmaxf(fmaxf(vm[0], vm[1]), fmaxf(vm[2], vm[3]))));
+        }
+    } else if (live) {
+        const float b = beta[j];
+        const float nb = soft_threshold_g(dot + b, lambda);
+        const float d = nb - b;
+        z[c] = dot;
+        delta[c] = d;
+        if (MODE == kGenoCommit) { beta[j] = nb; dbeta[j] = fabsf(d); }
+        else newbeta[c] = nb;
+    }
 }
 
 // Residual update, stage 1 (stage 2 is k_residual_apply of the dense path): grid = (blocks of 256
@@ -219,25 +275,39 @@ __global__ __launch_bounds__(256) void k_geno_residual_partial(const uint32_t *_
 // ---------------------------------------------------------------------------------------------
 static inline const uint32_t *geno_words_ptr(const strads_lasso *h) { return reinterpret_cast<const uint32_t *>(h->cfg.x); }
 
+// the walk over all slabs per wavefront needs enough columns to fill the chip; short lists use the
+// variant that spreads a column's slabs over a workgroup's four wavefronts
+static inline bool geno_wide(int64_t ncols) { return ncols >= 256 * 256; }
+
+#define STRADS_GENO_DOTS(MODE, LIST, NHOST, Z, DELTA, NB)                                                          \
+    do {                                                                                                           \
+        const int64_t ncols_ = (NHOST);                                                                            \
+        if (geno_wide(ncols_))                                                                                     \
+            hipLaunchKernelGGL((k_geno_dots<MODE, 256>), dim3((unsigned)((ncols_ + 255) / 256)), dim3(256), 0,     \
+                               h->stream, geno_words_ptr(h), geno_words(h->cfg.n), h->cfg.col_mean,                \
+                               h->cfg.col_scale, LIST, ncols_, h->at<RoundScalars>(h->ws.scalars),                 \
+                               h->at<float>(h->ws.r), h->cfg.lambda, h->at<float>(h->ws.beta),                     \
+                               h->at<float>(h->ws.dbeta), Z, DELTA, NB);                                           \
+        else                                                                                                       \
+            hipLaunchKernelGGL((k_geno_dots<MODE, 64>), dim3((unsigned)((ncols_ + 63) / 64)), dim3(256), 0,        \
+                               h->stream, geno_words_ptr(h), geno_words(h->cfg.n), h->cfg.col_mean,                \
+                               h->cfg.col_scale, LIST, ncols_, h->at<RoundScalars>(h->ws.scalars),                 \
+                               h->at<float>(h->ws.r), h->cfg.lambda, h->at<float>(h->ws.beta),                     \
+                               h->at<float>(h->ws.dbeta), Z, DELTA, NB);                                           \
+    } while (0)
+
 hipError_t launch_dots_geno(strads_lasso *h)
 {
-    const unsigned grid = (unsigned)((h->L + 4 * kGenoCols - 1) / (4 * kGenoCols));
-    hipLaunchKernelGGL(k_geno_dots<true>, dim3(grid), dim3(256), 0, h->stream, geno_words_ptr(h), geno_words(h->cfg.n),
-                       h->cfg.col_mean, h->cfg.col_scale, h->at<int32_t>(h->ws.kept), 0,
-                       h->at<RoundScalars>(h->ws.scalars), h->at<float>(h->ws.r), h->cfg.lambda,
-                       h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.z),
-                       h->at<float>(h->ws.delta), (float *)nullptr);
+    // the grid covers all L candidates; workgroups past the kept count (known on the device) leave at once
+    STRADS_GENO_DOTS(kGenoCommit, h->at<int32_t>(h->ws.kept), (int64_t)h->L, h->at<float>(h->ws.z),
+                     h->at<float>(h->ws.delta), (float *)nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_dots_cand_geno(strads_lasso *h)
 {
-    const unsigned grid = (unsigned)((h->L + 4 * kGenoCols - 1) / (4 * kGenoCols));
-    hipLaunchKernelGGL(k_geno_dots<false>, dim3(grid), dim3(256), 0, h->stream, geno_words_ptr(h), geno_words(h->cfg.n),
-                       h->cfg.col_mean, h->cfg.col_scale, h->at<int32_t>(h->ws.cand), h->L,
-                       h->at<RoundScalars>(h->ws.scalars), h->at<float>(h->ws.r), h->cfg.lambda,
-                       h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.zc),
-                       h->at<float>(h->ws.dc), h->at<float>(h->ws.nbc));
+    STRADS_GENO_DOTS(kGenoTentative, h->at<int32_t>(h->ws.cand), (int64_t)h->L, h->at<float>(h->ws.zc),
+                     h->at<float>(h->ws.dc), h->at<float>(h->ws.nbc));
     return hipGetLastError();
 }
 
@@ -245,13 +315,10 @@ hipError_t launch_kkt_geno(strads_lasso *h, float *g_or_null)
 {
     hipError_t e = launch_clear_kkt(h);
     if (e != hipSuccess) return e;
-    int64_t g = (h->cfg.j + 4 * kGenoCols - 1) / (4 * kGenoCols);
-    if (g > 256 * 8) g = 256 * 8;               // persistent: a few workgroups per compute unit
-    hipLaunchKernelGGL(k_geno_kkt, dim3((unsigned)g), dim3(256), 0, h->stream, geno_words_ptr(h), geno_words(h->cfg.n),
-                       h->cfg.col_mean, h->cfg.col_scale, h->cfg.j, h->at<float>(h->ws.r), h->at<float>(h->ws.beta),
-                       h->cfg.lambda, g_or_null, h->at<RoundScalars>(h->ws.scalars));
+    STRADS_GENO_DOTS(kGenoAll, (const int32_t *)nullptr, h->cfg.j, g_or_null, (float *)nullptr, (float *)nullptr);
     return hipGetLastError();
 }
+#undef STRADS_GENO_DOTS
 
 hipError_t launch_residual_geno(strads_lasso *h)
 {
