@@ -87,8 +87,8 @@ struct GenoCols {
 //   fp32 designs: a thread holds kPasses float4 per panel: column (it*kColsPerPass + tid/kKQ),
 //     floats (tid%kKQ)*4..+3.
 //   packed genotypes: a thread holds one 32-bit word (16 rows) per panel: column tid/2, rows
-//     16*(tid%2)..+15 of the stage; stash() decodes it to fp32 through the column's three values
-//     fl(fl(g - mean) * scale), g = 0, 1, 2.
+//     16*(tid%2)..+15 of the stage; stash() decodes it to fp32 as fl(fl(g - mean) * scale), both
+//     operations rounded separately as the layout defines them.
 // Columns past the candidate count are clamped to the last candidate: their products land in
 // rows/columns >= L of the tile, which nobody reads.
 template <int LOAD, int NPAN>
@@ -102,7 +102,7 @@ struct PanelLoader {
     const uint32_t *wp[NPAN];
     uint32_t W[NPAN];
     int valid[NPAN];
-    float lut[NPAN][3];
+    float mean[NPAN], scale[NPAN];
 
     __device__ __forceinline__ void init(const float *__restrict__ X, int64_t N, const int32_t *__restrict__ cand,
                                          int32_t L, const int32_t (&tile)[NPAN], const GenoCols &gc, int64_t kb,
@@ -120,10 +120,8 @@ struct PanelLoader {
                 i = i < L ? i : L - 1;
                 const int64_t j = cand[i];
                 wp[p] = Xw + j * gc.words + kb / 16 + (tid & 1);
-                const float m = gc.mean[j], sc = gc.scale[j];
-                lut[p][0] = __fmul_rn(__fsub_rn(0.f, m), sc);
-                lut[p][1] = __fmul_rn(__fsub_rn(1.f, m), sc);
-                lut[p][2] = __fmul_rn(__fsub_rn(2.f, m), sc);
+                mean[p] = gc.mean[j];
+                scale[p] = gc.scale[j];
                 W[p] = 0u;
                 valid[p] = 0;
             }
@@ -177,27 +175,36 @@ struct PanelLoader {
         }
     }
 
+    // packed genotypes: entries q, q+4, q+8, q+12 of a word are the four bytes of (word >> 2q) & 0x03030303
+    template <bool FULL>
+    __device__ __forceinline__ void stash_geno(float *stage) const
+    {
+        const int tid = threadIdx.x;
+#pragma unroll
+        for (int p = 0; p < NPAN; ++p) {
+            float *dst = stage + p * kPanel + (tid >> 1) * kRow + 16 * (tid & 1);
+            const float m = mean[p], sc = scale[p];
+            float x[16];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t t = (W[p] >> (2 * q)) & 0x03030303u;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float g = (float)((t >> (8 * c)) & 0xFFu);
+                    const float val = __fmul_rn(__fsub_rn(g, m), sc);
+                    x[4 * c + q] = FULL || 4 * c + q < valid[p] ? val : 0.f;
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float4 *>(dst + 4 * q) = make_float4(x[4 * q], x[4 * q + 1], x[4 * q + 2], x[4 * q + 3]);
+        }
+    }
+
     __device__ __forceinline__ void stash(float *stage) const
     {
         if (LOAD == kLoadGeno2) {
-            const int tid = threadIdx.x;
-#pragma unroll
-            for (int p = 0; p < NPAN; ++p) {
-                float *dst = stage + p * kPanel + (tid >> 1) * kRow + 16 * (tid & 1);
-                const uint32_t w = W[p];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float x[4];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const int e = 4 * q + c;
-                        const uint32_t gq = (w >> (2 * e)) & 3u;
-                        const float val = gq == 0u ? lut[p][0] : (gq == 1u ? lut[p][1] : lut[p][2]);
-                        x[c] = e < valid[p] ? val : 0.f;
-                    }
-                    *reinterpret_cast<float4 *>(dst + 4 * q) = make_float4(x[0], x[1], x[2], x[3]);
-                }
-            }
+            stash_geno<false>(stage);
         } else {
 #pragma unroll
             for (int p = 0; p < NPAN; ++p)
@@ -206,6 +213,13 @@ struct PanelLoader {
                     *reinterpret_cast<float4 *>(stage + p * kPanel + (it * kColsPerPass + crow) * kRow + kq) =
                         R[p * kPasses + it];
         }
+    }
+
+    // a stage brought in by fetch_full(): no row of it lies past the slice
+    __device__ __forceinline__ void stash_full(float *stage) const
+    {
+        if (LOAD == kLoadGeno2) stash_geno<true>(stage);
+        else stash(stage);
     }
 };
 
@@ -253,6 +267,7 @@ __device__ __forceinline__ void gram_tile_off(const float *__restrict__ X, int64
     auto fetch = [&](int st) { ld.fetch(st); };
     auto fetch_full = [&](int st) { ld.fetch_full(st); };
     auto stash = [&](int buf) { ld.stash(smem + buf * 2 * kPanel); };
+    auto stash_full = [&](int buf) { ld.stash_full(smem + buf * 2 * kPanel); };
     const int nfull = ld.nfull();
 
     const int wave = tid >> 6, lane = tid & 63;
@@ -316,7 +331,7 @@ __device__ __forceinline__ void gram_tile_off(const float *__restrict__ X, int64
     __syncthreads();
     int st = 0;
     for (; st + 2 < nfull; ++st) {              // steady state
-        compute(st & 1, read_ops(st & 1, 0), [&] { stash((st + 1) & 1); fetch_full(st + 2); });
+        compute(st & 1, read_ops(st & 1, 0), [&] { stash_full((st + 1) & 1); fetch_full(st + 2); });
         __syncthreads();
     }
     for (; st + 2 < nstage; ++st) {             // a ragged last stage is fetched with clamping
@@ -360,6 +375,7 @@ __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int6
     auto fetch = [&](int st) { ld.fetch(st); };
     auto fetch_full = [&](int st) { ld.fetch_full(st); };
     auto stash = [&](int buf) { ld.stash(smem + buf * 2 * kPanel); };
+    auto stash_full = [&](int buf) { ld.stash_full(smem + buf * 2 * kPanel); };
     const int nfull = ld.nfull();
 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -416,7 +432,7 @@ __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int6
     __syncthreads();
     int st = 0;
     for (; st + 2 < nfull; ++st) {
-        stash((st + 1) & 1);
+        stash_full((st + 1) & 1);
         fetch_full(st + 2);
         compute(st & 1);
         __syncthreads();
