@@ -27,6 +27,36 @@ def test_library_exports_every_declared_symbol():
     assert sorted(pk.EXPORTS) == names
 
 
+def test_ctypes_structs_match_the_header_layout(tmp_path):
+    # the header, compiled by the host C compiler, reports size and field offsets of its three
+    # structs; the binding's ctypes mirrors must agree field by field
+    pairs = [("strads_lasso_config_t", b.Config), ("strads_round_info_t", b.RoundInfo), ("strads_run_info_t", b.RunInfo)]
+    lines = ['#include <stdio.h>', '#include "strads_lasso.h"', 'int main(void) {']
+    for cname, ct in pairs:
+        lines.append(f'  printf("{cname} %zu\\n", sizeof({cname}));')
+        for fname, _ in ct._fields_:
+            cfield = {"lam": "lambda"}.get(fname, fname)
+            lines.append(f'  printf("{cname}.{fname} %zu\\n", offsetof({cname}, {cfield}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    import subprocess
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)], check=True)
+    out = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for cname, ct in pairs:
+        assert int(out[cname]) == C.sizeof(ct), cname
+        for fname, _ in ct._fields_:
+            assert int(out[f"{cname}.{fname}"]) == getattr(ct, fname).offset, f"{cname}.{fname}"
+        # and no field of the header is missing from the mirror
+        text = open(os.path.join(ROOT, "include", "strads_lasso.h")).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        end = text.index("} " + cname + ";")
+        body = text[text.rindex("typedef struct {", 0, end) + len("typedef struct {"):end]
+        n_decl = sum(len(d.split(",")) for d in body.split(";") if d.strip())
+        assert n_decl == len(ct._fields_), cname
+
+
 def test_workspace_bytes_scales_and_rejects():
     small = pk.strads_lasso_workspace_bytes(1000, 5000, 200)
     big = pk.strads_lasso_workspace_bytes(10000, 100000, 1000)
@@ -55,6 +85,9 @@ def _cfg(**kw):
     dict(rho=float("nan")), dict(eta=0.0), dict(eta=float("nan")), dict(c_init=0.0), dict(c_init=float("inf")),
     dict(l_prime=0), dict(l_prime=pk.MAX_L_PRIME + 1), dict(p_max=-1), dict(workspace=257), dict(x=258),
     dict(layout=1, row_idx=None, col_ptr=None),
+    dict(layout=2, col_mean=None, col_scale=256), dict(layout=2, col_mean=256, col_scale=None),
+    dict(layout=2, col_mean=256, col_scale=256, x=264),          # packed columns start on 16-byte boundaries
+    dict(deps=3), dict(priority=3), dict(n_shards=-1), dict(n_shards=9), dict(n_shards=8, j=5),
 ])
 def test_create_rejects_invalid_arguments_without_touching_the_device(bad):
     lib = pk.load()
