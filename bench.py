@@ -188,6 +188,36 @@ def main() -> int:
         kkt_bytes = 8.0 * float(p.values.numel())
     kkt_gbps = kkt_bytes / (kkt_ms * 1e-3) / 1e9
 
+    # the two HBM streams of a round (x_j^T r for the kept set; the residual update), timed per stage on
+    # a second pass over the same trajectory with every stage bracketed by events (not the headline run:
+    # the extra events and the per-round readback of |B| and the mover count cost a few microseconds)
+    streams = None
+    if args.profile_level and args.shards == 1 and args.deps == "static" and p.layout == "dense":
+        v = fresh()
+        v.set_tuning("profile_rounds", max(args.steps, 1))
+        v.set_tuning("profile_level", 2)
+        kept = moved = 0
+        for _ in range(args.steps):
+            ri = v.round(want_info=True)
+            kept += ri.n_kept
+            moved += ri.n_moved
+        st2 = v.stage_times()
+        v.set_tuning("profile_level", 0)
+        v.close()
+        if st2["rounds"] > 0 and st2["update"] > 0 and st2["residual"] > 0:
+            k, k1 = kept / st2["rounds"], moved / st2["rounds"]
+            dots_b, res_b = 4.0 * p.n * (k + 1), 4.0 * p.n * k1 + 8.0 * p.n
+            dots_g, res_g = dots_b / (st2["update"] * 1e-3) / 1e9, res_b / (st2["residual"] * 1e-3) / 1e9
+            streams = {
+                "dots": {"kernel": "k_dots_update", "bytes": round(dots_b), "ms": round(st2["update"], 5),
+                         "achieved": round(dots_g, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": round(dots_g / HBM_PEAK_GBPS, 4), "avg_kept": round(k, 1)},
+                "residual": {"kernel": "k_residual_partial+k_residual_apply", "bytes": round(res_b),
+                             "ms": round(st2["residual"], 5), "achieved": round(res_g, 1), "peak": HBM_PEAK_GBPS,
+                             "unit": "GB/s", "frac": round(res_g / HBM_PEAK_GBPS, 4), "avg_moved": round(k1, 1)},
+                "stage_ms": {kk: round(vv, 5) for kk, vv in st2.items() if kk != "rounds"},
+            }
+
     # the same workload and round count under the two widenings of the schedule (not the headline)
     variants = None
     headline = (args.deps == "static" and args.shards == 1 and args.priority == "squared" and args.kkt_tol == 0
@@ -248,7 +278,11 @@ def main() -> int:
         el = time.perf_counter() - tc
         cpu = {"value": round(n_upd / el, 2), "unit": "updates/s", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
                "kind": "oracle", "sample": f"first {n_rounds} rounds of the same workload ({el:.1f} s)",
-               "rounds_per_s": round(n_rounds / el, 4)}
+               "rounds_per_s": round(n_rounds / el, 4),
+               # time to objective: both sides follow the same trajectory from round 0, so the objective the
+               # oracle holds after its sample is the one the GPU path holds after the same number of rounds
+               "objective_after_sample": float(o.objective()), "seconds_to_that_objective": round(el, 3),
+               "gpu_seconds_to_that_objective": round(n_rounds * wall / max(rounds_done, 1), 6)}
 
     out = {
         "metric": "coordinate_updates_per_sec", "value": round(updates / wall, 1), "unit": "updates/s",
@@ -264,6 +298,7 @@ def main() -> int:
         "hbm_pass": {"kernel": "k_kkt", "bytes": kkt_bytes, "ms": round(kkt_ms, 4), "achieved": round(kkt_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(kkt_gbps / HBM_PEAK_GBPS, 4)},
         "stage_ms": {k: round(v, 5) for k, v in stage.items() if k != "rounds"},
+        "hbm_streams": streams,
         "cpu_baseline": cpu,
         "variants": variants,
         "input_generation_s": round(t_gen, 2),

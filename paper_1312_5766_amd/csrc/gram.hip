@@ -551,7 +551,15 @@ __global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, 
             if (have) {
                 const int32_t split = b < first + kGramTile ? g.split_diag : g.split_off;
                 const float *p = P + (int64_t)a * Lpad + b;
-                for (int32_t s = 0; s < split; ++s) {
+                int32_t s = 0;
+                for (; s + 7 < split; s += 8) {             // eight slices in flight, added in slice order
+                    float4 q[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) q[u] = *reinterpret_cast<const float4 *>(p + (s + u) * plane);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) { v[0] += q[u].x; v[1] += q[u].y; v[2] += q[u].z; v[3] += q[u].w; }
+                }
+                for (; s < split; ++s) {
                     const float4 q = *reinterpret_cast<const float4 *>(p + s * plane);
                     v[0] += q.x; v[1] += q.y; v[2] += q.z; v[3] += q.w;
                 }
@@ -620,6 +628,10 @@ __host__ __device__ static inline int gram_split_choose(int64_t n, int32_t lpad)
     const int64_t T = lpad / kGramTile;
     const int64_t stages = (n + kGramKT - 1) / kGramKT;
     const int64_t n_off = T * (T - 1) / 2;
+    if (T < 1) return 1;
+    // at most 64 slices.  (More slices for one or two tiles were tried: at one tile and N = 50000 the tile
+    // kernel goes from 60 us to 21-32 us with 160-200 workgroups, but the sum over the slices in the mask
+    // kernel grows as fast, and at 261 workgroups both kernels take 105 us.)
     int64_t max_split = stages / 2;
     if (max_split > 64) max_split = 64;
     if (max_split < 1) max_split = 1;
