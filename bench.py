@@ -75,6 +75,8 @@ def main() -> int:
     ap.add_argument("--profile-level", type=int, default=1, choices=(0, 1, 2),
                     help="HIP-event timing inside the timed region: 1 = Gram kernel only, 2 = every stage")
     ap.add_argument("--split-k", type=int, default=0)
+    ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
+                    help="strads_lasso_set_tuning knob applied to every solver of the run (repeatable)")
     ap.add_argument("--deps", default="static", choices=("static", "dynamic", "none"),
                     help="dependency rule of Step 2: static = Algorithm 1 as printed (the headline workload); "
                          "dynamic = only pairs of candidates that both move are checked; "
@@ -134,7 +136,11 @@ def main() -> int:
         kw = dict(y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed, p_max=args.p_max,
                   dynamic=args.deps == "dynamic", no_deps=args.deps == "none", priority=args.priority,
                   n_shards=args.shards)
-        return pk.StradsLasso(**design_args(p), **kw)
+        h = pk.StradsLasso(**design_args(p), **kw)
+        for t in args.tune:
+            name, value = t.split("=")
+            h.set_tuning(name, int(value))
+        return h
 
     # warm-up on a throw-away handle, so that the timed region is the configuration's own
     # trajectory from round 0

@@ -216,11 +216,11 @@ def test_gram_split_k_variants_agree_with_oracle():
         _assert_close(_np(lr["G"]), Gref, DOT_RTOL, 1e-6, f"gram split {split}")
 
 
-@pytest.mark.parametrize("L", [1, 2, 63, 64, 65, 200, 1000, 2500])
+@pytest.mark.parametrize("L", [1, 2, 63, 64, 65, 200, 1000, 2500, 4100, 8192])
 def test_filter_is_bit_exact_on_given_gram(L):
     p = si.make("c1_dense_iid", n=8, j=max(L, 2), nnz=1, l_prime=L)
     rng = np.random.default_rng(L)
-    for p_max, scale in ((0, 0.035), (0, 0.08), (max(1, L // 3), 0.035)):
+    for p_max, scale in ((0, 0.035), (0, 0.08), (max(1, L // 3), 0.035), (0, 0.02)):
         g, o = _pair(p, keep_gram=False, p_max=p_max)
         A = (rng.standard_normal((L, L)) * scale).astype(np.float32)
         G = np.triu(A, 1) + np.triu(A, 1).T + np.eye(L, dtype=np.float32)
