@@ -165,16 +165,26 @@ def main() -> int:
     g.set_tuning("profile_level", args.profile_level)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    rounds_done = updates = 0
     if args.kkt_tol > 0:
-        info = g.run(args.steps, args.kkt_tol, args.check_every)
+        # a run to tolerance can take minutes: it is made in segments of whole check intervals, with a
+        # progress line after each (the only cost is one extra synchronisation per segment)
+        seg = max(args.check_every, 1) * max(1, 20000 // max(args.check_every, 1))
+        while True:
+            info = g.run(min(seg, args.steps - rounds_done), args.kkt_tol, args.check_every)
+            rounds_done += int(info.rounds_done)
+            updates += int(info.updates_done)
+            print(f"bench.py: {rounds_done} rounds, {time.perf_counter() - t0:.1f} s, objective {info.objective:.6f}, "
+                  f"violation {info.kkt_violation:.3e}", file=sys.stderr, flush=True)
+            if info.converged or rounds_done >= args.steps or info.rounds_done == 0:
+                break
     else:
         info = g.run(args.steps)                # enqueues K rounds, waits once at the end
+        rounds_done, updates = int(info.rounds_done), int(info.updates_done)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     stage = g.stage_times() if args.profile_level else {"rounds": 0}
     g.set_tuning("profile_level", 0)
-    rounds_done = int(info.rounds_done)
-    updates = int(info.updates_done)
     f1 = float(info.objective)
 
     # the HBM-bound pass: x_j^T r for all J columns (the stopping test streams X once)
