@@ -91,35 +91,38 @@ __device__ __forceinline__ uint32_t orderable(float key)
 // block helpers (256-thread workgroups unless stated)
 // ---------------------------------------------------------------------------------------------
 // In a histogram whose bins are ordered ascending, find the bin that holds the K-th largest
-// element: above(bin) < K <= above(bin) + hist[bin].  All 256 threads call it; results are
-// returned to all.  tmp: 6 uint32 of LDS.  Thread t owns bins 8t..8t+7; the suffix sums over the
+// element: above(bin) < K <= above(bin) + hist[bin].  All threads of the workgroup (256 or more)
+// call it; results are returned to all.  tmp: 6 uint32 of LDS.  Thread t owns bins 8t..8t+7; the suffix sums over the
 // per-thread totals are taken inside each wavefront with lane shifts, then across the four
 // wavefronts through LDS (two barriers in all).
 __device__ void find_bin_desc(const uint32_t *__restrict__ hist, uint32_t K, uint32_t *tmp, uint32_t &bin,
                               uint32_t &above)
 {
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const bool owner = t < 256;                 // wider workgroups: the other threads only meet the barriers
     uint32_t loc[8];
     uint32_t s = 0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { loc[i] = hist[8 * t + i]; s += loc[i]; }
+    for (int i = 0; i < 8; ++i) { loc[i] = owner ? hist[8 * t + i] : 0u; s += loc[i]; }
     uint32_t suf = s;                           // inclusive suffix sum over the lanes of this wavefront
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
         const uint32_t v = __shfl_down(suf, d);
         if (lane + d < 64) suf += v;
     }
-    if (lane == 0) tmp[wave] = suf;             // total of this wavefront
+    if (owner && lane == 0) tmp[wave] = suf;    // total of this wavefront
     if (t == 0) { tmp[4] = 0; tmp[5] = 0; }
     __syncthreads();
-    uint32_t higher = 0;                        // totals of the wavefronts holding higher bins
+    if (owner) {
+        uint32_t higher = 0;                    // totals of the wavefronts holding higher bins
 #pragma unroll
-    for (int w = 1; w < 4; ++w) if (w > wave) higher += tmp[w];
-    uint32_t ab = higher + suf - s;             // elements in bins above this thread's 8 bins
+        for (int w = 1; w < 4; ++w) if (w > wave) higher += tmp[w];
+        uint32_t ab = higher + suf - s;         // elements in bins above this thread's 8 bins
 #pragma unroll
-    for (int i = 7; i >= 0; --i) {
-        if (ab < K && K <= ab + loc[i]) { tmp[4] = 8 * t + i; tmp[5] = ab; }
-        ab += loc[i];
+        for (int i = 7; i >= 0; --i) {
+            if (ab < K && K <= ab + loc[i]) { tmp[4] = 8 * t + i; tmp[5] = ab; }
+            ab += loc[i];
+        }
     }
     __syncthreads();
     bin = tmp[4];
@@ -146,23 +149,23 @@ __device__ __forceinline__ void wave_append(bool flag, uint64_t item, uint64_t *
 // Js coordinates of scheduler shard `shard` out of `shards`: position i of the shard is coordinate
 // j = i * shards + shard (one shard: j = i).  Keys are stored by position; the random number and
 // delta beta are those of coordinate j.
-__global__ __launch_bounds__(256) void k_keys_hist(const float *__restrict__ dbeta, uint32_t Js, uint32_t shards,
+__global__ __launch_bounds__(1024) void k_keys_hist(const float *__restrict__ dbeta, uint32_t Js, uint32_t shards,
                                                    uint32_t shard, float eta, uint64_t seed,
                                                    const RoundScalars *__restrict__ sc, int priority,
                                                    uint32_t *__restrict__ keys, uint32_t *__restrict__ hist0)
 {
     __shared__ uint32_t lh[kHistBins];
     const uint64_t t = sc->next_round;          // advanced by the shard's last sampler kernel
-    for (int i = threadIdx.x; i < kHistBins; i += 256) lh[i] = 0;
+    for (int i = threadIdx.x; i < kHistBins; i += blockDim.x) lh[i] = 0;
     __syncthreads();
-    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < Js; i += gridDim.x * 256u) {
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < Js; i += gridDim.x * blockDim.x) {
         const uint32_t j = i * shards + shard;
         const uint32_t ok = orderable(priority_key(dbeta[j], eta, seed, t, j, priority));
         keys[i] = ok;
         atomicAdd(&lh[ok >> 21], 1u);
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < kHistBins; i += 256)
+    for (int i = threadIdx.x; i < kHistBins; i += blockDim.x)
         if (lh[i]) atomicAdd(&hist0[i], lh[i]);
 }
 
@@ -175,7 +178,7 @@ __global__ __launch_bounds__(256) void k_keys_only(const float *__restrict__ dbe
 }
 
 // pass 2: histogram of the next 11 bits among keys in the boundary bin of pass 1
-__global__ __launch_bounds__(256) void k_hist2(const uint32_t *__restrict__ keys, uint32_t J, uint32_t L,
+__global__ __launch_bounds__(1024) void k_hist2(const uint32_t *__restrict__ keys, uint32_t J, uint32_t L,
                                                const uint32_t *__restrict__ hist0, uint32_t *__restrict__ hist1,
                                                RoundScalars *__restrict__ sc)
 {
@@ -184,14 +187,14 @@ __global__ __launch_bounds__(256) void k_hist2(const uint32_t *__restrict__ keys
     uint32_t b0, above;
     find_bin_desc(hist0, L, tmp, b0, above);
     if (blockIdx.x == 0 && threadIdx.x == 0) { sc->bin0 = b0; sc->rem1 = L - above; }
-    for (int i = threadIdx.x; i < kHistBins; i += 256) lh[i] = 0;
+    for (int i = threadIdx.x; i < kHistBins; i += blockDim.x) lh[i] = 0;
     __syncthreads();
-    for (uint32_t j = blockIdx.x * 256u + threadIdx.x; j < J; j += gridDim.x * 256u) {
+    for (uint32_t j = blockIdx.x * blockDim.x + threadIdx.x; j < J; j += gridDim.x * blockDim.x) {
         const uint32_t ok = keys[j];
         if ((ok >> 21) == b0) atomicAdd(&lh[(ok >> 10) & 0x7FFu], 1u);
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < kHistBins; i += 256)
+    for (int i = threadIdx.x; i < kHistBins; i += blockDim.x)
         if (lh[i]) atomicAdd(&hist1[i], lh[i]);
 }
 
@@ -452,11 +455,23 @@ __global__ __launch_bounds__(256) void k_merge_rank(const uint64_t *__restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
+// Workgroup width and count of the two histogram passes.  Every workgroup flushes its LDS histogram
+// with global atomics, so there are at most 256 of them; when that cap binds, the workgroups get
+// wider instead (up to 1024 threads), so that a thread's share stays at a few keys and each
+// compute unit has enough wavefronts to cover the memory latency.
+static inline int sampler_threads(int64_t J)
+{
+    int t = 256;
+    while (t < 1024 && (J + (int64_t)t * 4 - 1) / ((int64_t)t * 4) > 256) t *= 2;
+    return t;
+}
+
 static inline int sampler_grid(int64_t J)
 {
-    int64_t b = (J + 256 * 4 - 1) / (256 * 4);
+    const int64_t per = (int64_t)sampler_threads(J) * 4;
+    int64_t b = (J + per - 1) / per;
     if (b < 1) b = 1;
-    if (b > 256) b = 256;        // every workgroup flushes its LDS histogram with global atomics: keep them few
+    if (b > 256) b = 256;
     return (int)b;
 }
 
@@ -478,9 +493,10 @@ hipError_t launch_sampler(strads_lasso *h)
     uint32_t *hist = h->at<uint32_t>(h->ws.hist);
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     uint64_t *sel = h->at<uint64_t>(h->ws.sel), *bnd = h->at<uint64_t>(h->ws.bnd);
-    hipLaunchKernelGGL(k_keys_hist, dim3(g), dim3(256), 0, h->stream, h->at<float>(h->ws.dbeta), J, S, sh, h->cfg.eta,
+    const int bt = sampler_threads(h->Js);
+    hipLaunchKernelGGL(k_keys_hist, dim3(g), dim3(bt), 0, h->stream, h->at<float>(h->ws.dbeta), J, S, sh, h->cfg.eta,
                        h->cfg.seed, sc, h->cfg.priority, keys, hist);
-    hipLaunchKernelGGL(k_hist2, dim3(g), dim3(256), 0, h->stream, keys, J, L, hist, hist + kHistBins, sc);
+    hipLaunchKernelGGL(k_hist2, dim3(g), dim3(bt), 0, h->stream, keys, J, L, hist, hist + kHistBins, sc);
     const unsigned gc = (unsigned)((h->Js + 256 * kCollectPerThread - 1) / (256 * kCollectPerThread));
     hipLaunchKernelGGL(k_collect, dim3(gc), dim3(256), 0, h->stream, keys, J, S, sh, hist + kHistBins, sc, sel, bnd);
     // LDS of the final kernel: the 1024-item exchange buffer of the register sort, or the boundary
