@@ -188,15 +188,17 @@ def main() -> int:
     g.set_tuning("profile_level", 0)
     f1 = float(info.objective)
 
-    # the HBM-bound pass: x_j^T r for all J columns (the stopping test streams X once)
+    # the HBM-bound pass: x_j^T r for all J columns (the stopping test streams X once), timed by the
+    # library's events around its kernels (the read-back of the result is not part of the pass)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g.set_tuning("profile_level", 1)
     g.kkt()
-    e0.record()
-    viol = g.kkt()
-    e1.record()
-    torch.cuda.synchronize()
-    kkt_ms = e0.elapsed_time(e1)
+    kkt_times = []
+    for _ in range(3):
+        viol = g.kkt()
+        kkt_times.append(g.last_kkt_ms())
+    g.set_tuning("profile_level", 0)
+    kkt_ms = sum(kkt_times) / len(kkt_times)
     if p.layout == "dense":
         kkt_bytes = 4.0 * p.n * p.j
     elif p.layout == "geno2":

@@ -241,6 +241,12 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value);
  * the pool.  rounds_timed is HOST. */
 int strads_lasso_stage_times(strads_lasso_t *h, float *avg_ms, int32_t *rounds_timed);
 
+/* Duration in milliseconds (HOST float) of the most recent pass over all columns (strads_lasso_kkt,
+ * or a check inside strads_lasso_run), from HIP events recorded around its kernels on the handle's
+ * stream: the kernels alone, without the read-back of the result.  0 if profiling ("profile_level")
+ * was off during that pass or no pass has been made. */
+int strads_lasso_last_kkt_ms(strads_lasso_t *h, float *ms);
+
 void strads_lasso_destroy(strads_lasso_t *h);
 
 const char *strads_lasso_strerror(int code);

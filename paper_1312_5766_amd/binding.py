@@ -29,7 +29,8 @@ EXPORTS = [
     "strads_lasso_workspace_bytes", "strads_lasso_create", "strads_lasso_round", "strads_lasso_run",
     "strads_lasso_objective", "strads_lasso_kkt", "strads_lasso_get_state", "strads_lasso_set_state",
     "strads_lasso_last_round", "strads_lasso_last_candidates", "strads_lasso_stage_keys", "strads_lasso_stage_filter",
-    "strads_lasso_set_tuning", "strads_lasso_stage_times", "strads_lasso_destroy", "strads_lasso_strerror",
+    "strads_lasso_set_tuning", "strads_lasso_stage_times", "strads_lasso_last_kkt_ms", "strads_lasso_destroy",
+    "strads_lasso_strerror",
 ]
 
 
@@ -274,6 +275,11 @@ class StradsLasso:
         n = C.c_int32()
         _check(load().strads_lasso_stage_times(self._h, ms, C.byref(n)), "strads_lasso_stage_times")
         return {"rounds": n.value, **{name: float(ms[i]) for i, name in enumerate(STAGE_NAMES)}}
+
+    def last_kkt_ms(self) -> float:
+        ms = C.c_float()
+        _check(load().strads_lasso_last_kkt_ms(self._h, C.byref(ms)), "strads_lasso_last_kkt_ms")
+        return float(ms.value)
 
     def set_tuning(self, name: str, value: int):
         _check(load().strads_lasso_set_tuning(self._h, name.encode(), int(value)), "strads_lasso_set_tuning")

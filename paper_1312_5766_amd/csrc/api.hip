@@ -170,6 +170,8 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
         ln->lane_id = s;
         ln->stream = nullptr;
         ln->ev_resid = ln->ev_join = ln->ev_fork = nullptr;
+        ln->ev_kkt[0] = ln->ev_kkt[1] = nullptr;
+        ln->last_kkt_ms = 0.f;
         h->lanes[s] = ln;
         if (hipStreamCreateWithFlags(&ln->stream, hipStreamNonBlocking) != hipSuccess) rc = STRADS_E_HIP;
     }
@@ -240,6 +242,7 @@ void strads_lasso_destroy(strads_lasso_t *h)
         if (s > 0) free(ln);
     }
     if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+    for (int i = 0; i < 2; ++i) if (h->ev_kkt[i]) (void)hipEventDestroy(h->ev_kkt[i]);
     free(h);
 }
 
@@ -473,12 +476,21 @@ int strads_lasso_objective(strads_lasso_t *h, double *out)
 int strads_lasso_kkt(strads_lasso_t *h, float *max_violation, float *g_or_null)
 {
     if (!h || !max_violation) return STRADS_E_INVALID_ARG;
+    const bool timed = h->profile_level != 0;
+    if (timed) {
+        for (int i = 0; i < 2; ++i)
+            if (!h->ev_kkt[i]) HIP_TRY(hipEventCreate(&h->ev_kkt[i]));
+        HIP_TRY(hipEventRecord(h->ev_kkt[0], h->stream));
+    }
     if (h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR) HIP_TRY(launch_kkt_dense(h, g_or_null));
     else if (h->cfg.layout == STRADS_LAYOUT_GENO2) HIP_TRY(launch_kkt_geno(h, g_or_null));
     else HIP_TRY(launch_kkt_csc(h, g_or_null));
+    if (timed) HIP_TRY(hipEventRecord(h->ev_kkt[1], h->stream));
     RoundScalars sc;
     const int rs = read_scalars(h, &sc);
     if (rs != STRADS_OK) return rs;
+    h->last_kkt_ms = 0.f;
+    if (timed) HIP_TRY(hipEventElapsedTime(&h->last_kkt_ms, h->ev_kkt[0], h->ev_kkt[1]));
     float v;
     memcpy(&v, &sc.kkt_max_bits, 4);
     *max_violation = v;
@@ -686,6 +698,13 @@ int strads_lasso_stage_times(strads_lasso_t *h, float *avg_ms, int32_t *rounds_t
     for (int s = 0; s < STRADS_N_STAGES; ++s) avg_ms[s] = h->profiled > 0 ? (float)(sum[s] / h->profiled) : 0.f;
     *rounds_timed = h->profiled;
     h->profiled = 0;
+    return STRADS_OK;
+}
+
+int strads_lasso_last_kkt_ms(strads_lasso_t *h, float *ms)
+{
+    if (!h || !ms) return STRADS_E_INVALID_ARG;
+    *ms = h->last_kkt_ms;
     return STRADS_OK;
 }
 

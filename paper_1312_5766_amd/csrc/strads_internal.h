@@ -113,6 +113,8 @@ struct strads_lasso {
     strads_lasso *lanes[STRADS_MAX_SHARDS];   // shard 0 only: [0] is the handle itself
     hipEvent_t ev_resid;     // recorded after this shard's residual update
     hipEvent_t ev_fork;      // shard 0 only: the caller's stream at the start of an enqueueing call
+    hipEvent_t ev_kkt[2];    // shard 0 only: around the kernels of the pass over all columns (profiling)
+    float last_kkt_ms;
     hipEvent_t ev_join;      // this shard's stream at the end of an enqueueing call
     int64_t rounds_since_fork;   // shard 0 only: rounds enqueued since the shards' streams were last forked
     // HIP graph of graph_rounds consecutive rounds, recorded once per starting shard and replayed by

@@ -405,3 +405,17 @@ def test_degenerate_cases():
         f2 = g.objective()
         assert f2 <= f * (1 + 1e-6)
         f = f2
+
+
+def test_pass_over_all_columns_is_timed_only_while_profiling():
+    p = si.make("c1_dense_iid", n=500, j=2000, nnz=5, l_prime=64)
+    g, _ = _pair(p, keep_gram=False)
+    v0 = g.kkt()
+    assert g.last_kkt_ms() == 0.0
+    g.set_tuning("profile_level", 1)
+    v1 = g.kkt()
+    ms = g.last_kkt_ms()
+    assert v1 == v0 and 0.0 < ms < 50.0
+    g.set_tuning("profile_level", 0)
+    g.kkt()
+    assert g.last_kkt_ms() == 0.0
