@@ -54,28 +54,51 @@ static __device__ __forceinline__ float soft_threshold_g(float a, float lambda)
 // wave-uniform addresses.  Within a word the four byte lanes of (word >> 2q) & 0x03030303
 // are entries q, q+4, q+8, q+12; masking in place instead of shifting leaves the count scaled by
 // 4^q, which one exact multiply per column removes at the end.
-//   COLS = 256: a wavefront walks all slabs (512 rows each) of its 64 columns: the pass over all J
-//               columns.
-//   COLS =  64: the four wavefronts of a workgroup share 64 columns and take every fourth slab of
-//               128 rows, combined in wavefront order: short lists of candidates, where a round
-//               waits on this kernel and the row range has to be spread to shorten it.
-template <int COLS> struct GenoSlab {
-    static constexpr int kWords = COLS == 256 ? 32 : 8;
-    static constexpr int kStride = kWords + 1;  // odd stride: lanes reading one word each hit distinct banks
-};
+//   short lists (the kept set, the candidates; all columns of a small design): k_geno_dots.  The four
+//     wavefronts of a workgroup share 64 columns and take every fourth slab of 128 rows, combined in
+//     wavefront order: a round waits on this kernel, and the row range has to be spread to shorten it.
+//   all columns of a large design: k_geno_all, persistent wavefronts, slabs of 512 rows, next slab in flight.
+constexpr int kSlabShort = 8, kSlabLong = 32;  // words per slab; LDS rows are padded by one word (odd
+                                               // stride: lanes reading one word each hit distinct banks)
+
+// A lane's walk over nw words of its column (in LDS) against the rows at rbase (wave-uniform address):
+// a_q accumulates entries q, q+4, q+8, q+12 of every word, scaled by 4^q.
+static __device__ __forceinline__ void geno_consume(const uint32_t *__restrict__ src, int nw,
+                                                    const float *__restrict__ rbase, float &a0, float &a1,
+                                                    float &a2, float &a3)
+{
+#pragma unroll 4
+    for (int w = 0; w < nw; ++w) {
+        const uint32_t code = src[w];
+        const float *rw = rbase + 16 * w;
+        uint32_t t0 = code & 0x03030303u, t1 = code & 0x0C0C0C0Cu;
+        uint32_t t2 = code & 0x30303030u, t3 = code & 0xC0C0C0C0u;
+        // keep the four masked words as they are, so that each entry is one byte-to-float conversion
+        asm volatile("" : "+v"(t0), "+v"(t1), "+v"(t2), "+v"(t3));
+#define STRADS_GENO_ACC(A, T, Q)                                                                    \
+        A = __builtin_fmaf((float)((T) & 0xFFu), rw[Q], A);                                         \
+        A = __builtin_fmaf((float)(((T) >> 8) & 0xFFu), rw[(Q) + 4], A);                            \
+        A = __builtin_fmaf((float)(((T) >> 16) & 0xFFu), rw[(Q) + 8], A);                           \
+        A = __builtin_fmaf((float)((T) >> 24), rw[(Q) + 12], A)
+        STRADS_GENO_ACC(a0, t0, 0);
+        STRADS_GENO_ACC(a1, t1, 1);
+        STRADS_GENO_ACC(a2, t2, 2);
+        STRADS_GENO_ACC(a3, t3, 3);
+#undef STRADS_GENO_ACC
+    }
+}
 
 struct GenoSums { float gr, rs; };             // sum g r, sum r over the slabs a wavefront walked
 
-template <int COLS>
 static __device__ __forceinline__ GenoSums geno_column_sums(const uint32_t *__restrict__ Xw, int64_t words,
                                                             int64_t col, const float *__restrict__ r,
                                                             uint32_t *__restrict__ lds_wave)
 {
-    constexpr int PH = 256 / COLS;             // wavefronts sharing a column
-    constexpr int SW = GenoSlab<COLS>::kWords, STRIDE = GenoSlab<COLS>::kStride;
+    constexpr int PH = 4;                      // wavefronts sharing a column
+    constexpr int SW = kSlabShort, STRIDE = SW + 1;
     constexpr int CH = SW / 4;                 // 16-byte pieces of a column's slab = lanes per column = passes
     const int lane = threadIdx.x & 63;
-    const int phase = COLS == 256 ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int phase = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int nslab = (int)((words + SW - 1) / SW);
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f, rs = 0.f;
     for (int sl = phase; sl < nslab; sl += PH) {
@@ -106,26 +129,7 @@ static __device__ __forceinline__ GenoSums geno_column_sums(const uint32_t *__re
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         const int nw = words - w0 < SW ? (int)(words - w0) : SW;
-        const uint32_t *src = lds_wave + lane * STRIDE;
-#pragma unroll 4
-        for (int w = 0; w < nw; ++w) {
-            const uint32_t code = src[w];
-            const float *rw = r + 16 * (w0 + w);           // wave-uniform address
-            uint32_t t0 = code & 0x03030303u, t1 = code & 0x0C0C0C0Cu;
-            uint32_t t2 = code & 0x30303030u, t3 = code & 0xC0C0C0C0u;
-            // keep the four masked words as they are, so that each entry is one byte-to-float conversion
-            asm volatile("" : "+v"(t0), "+v"(t1), "+v"(t2), "+v"(t3));
-#define STRADS_GENO_ACC(A, T, Q)                                                                    \
-            A = __builtin_fmaf((float)((T) & 0xFFu), rw[Q], A);                                     \
-            A = __builtin_fmaf((float)(((T) >> 8) & 0xFFu), rw[(Q) + 4], A);                        \
-            A = __builtin_fmaf((float)(((T) >> 16) & 0xFFu), rw[(Q) + 8], A);                       \
-            A = __builtin_fmaf((float)((T) >> 24), rw[(Q) + 12], A)
-            STRADS_GENO_ACC(a0, t0, 0);
-            STRADS_GENO_ACC(a1, t1, 1);
-            STRADS_GENO_ACC(a2, t2, 2);
-            STRADS_GENO_ACC(a3, t3, 3);
-#undef STRADS_GENO_ACC
-        }
+        geno_consume(lds_wave + lane * STRIDE, nw, r + 16 * w0, a0, a1, a2, a3);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();                    // the slab is consumed before the next one lands
     }
@@ -139,8 +143,8 @@ enum { kGenoCommit = 0, kGenoTentative = 1, kGenoAll = 2 };
 
 // MODE kGenoCommit:    eq. (2) and Step 4 for the kept set (count on the device)
 // MODE kGenoTentative: dot product and tentative update of every candidate
-// MODE kGenoAll:       x_j^T r and the optimality violation of all J columns (see k_kkt)
-template <int MODE, int COLS>
+// MODE kGenoAll:       x_j^T r and the optimality violation of all J columns (see k_kkt), small J
+template <int MODE>
 __global__ __launch_bounds__(256) void k_geno_dots(const uint32_t *__restrict__ Xw, int64_t words,
                                                    const float *__restrict__ mean, const float *__restrict__ scale,
                                                    const int32_t *__restrict__ list, int64_t n_host,
@@ -149,25 +153,22 @@ __global__ __launch_bounds__(256) void k_geno_dots(const uint32_t *__restrict__ 
                                                    float *__restrict__ z, float *__restrict__ delta,
                                                    float *__restrict__ newbeta)
 {
-    __shared__ uint32_t slab[4][64 * GenoSlab<COLS>::kStride];
+    __shared__ uint32_t slab[4][64 * (kSlabShort + 1)];
     __shared__ GenoSums comb[4][64];
-    __shared__ float vm[4];
     const int64_t n = MODE == kGenoCommit ? (int64_t)sc->n_kept : n_host;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t c = COLS == 256 ? (int64_t)blockIdx.x * 256 + threadIdx.x : (int64_t)blockIdx.x * 64 + lane;
-    if ((int64_t)blockIdx.x * COLS >= n) return;            // whole workgroup
+    const int64_t c = (int64_t)blockIdx.x * 64 + lane;
+    if ((int64_t)blockIdx.x * 64 >= n) return;              // whole workgroup
     const bool live = c < n;
     // lanes past the end walk the workgroup's first column and drop the result
-    const int64_t cc = live ? c : (int64_t)blockIdx.x * COLS;
+    const int64_t cc = live ? c : (int64_t)blockIdx.x * 64;
     const int64_t j = MODE == kGenoAll ? cc : (int64_t)list[cc];
-    GenoSums s = geno_column_sums<COLS>(Xw, words, j, r, slab[wave]);
-    if (COLS == 64) {
-        comb[wave][lane] = s;
-        __syncthreads();
-        if (wave != 0) return;
-        s.gr = (comb[0][lane].gr + comb[1][lane].gr) + (comb[2][lane].gr + comb[3][lane].gr);
-        s.rs = (comb[0][lane].rs + comb[1][lane].rs) + (comb[2][lane].rs + comb[3][lane].rs);
-    }
+    GenoSums s = geno_column_sums(Xw, words, j, r, slab[wave]);
+    comb[wave][lane] = s;
+    __syncthreads();
+    if (wave != 0) return;
+    s.gr = (comb[0][lane].gr + comb[1][lane].gr) + (comb[2][lane].gr + comb[3][lane].gr);
+    s.rs = (comb[0][lane].rs + comb[1][lane].rs) + (comb[2][lane].rs + comb[3][lane].rs);
     const float dot = scale[j] * (s.gr - mean[j] * s.rs);
     if (MODE == kGenoAll) {
         float v = 0.f;
@@ -179,14 +180,7 @@ __global__ __launch_bounds__(256) void k_geno_dots(const uint32_t *__restrict__ 
         }
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_down(v, off));
-        if (COLS == 64) {
-            if (lane == 0) atomicMax(&sc->kkt_max_bits, __float_as_uint(v));
-        } else {
-            if (lane == 0) vm[wave] = v;
-            __syncthreads();
-            if (threadIdx.x == 0)
-                atomicMax(&sc->kkt_max_bits, __float_as_uint(fmaxf(fmaxf(vm[0], vm[1]), fmaxf(vm[2], vm[3]))));
-        }
+        if (lane == 0) atomicMax(&sc->kkt_max_bits, __float_as_uint(v));
     } else if (live) {
         const float b = beta[j];
         const float nb = soft_threshold_g(dot + b, lambda);
@@ -196,6 +190,91 @@ __global__ __launch_bounds__(256) void k_geno_dots(const uint32_t *__restrict__ 
         if (MODE == kGenoCommit) { beta[j] = nb; dbeta[j] = fabsf(d); }
         else newbeta[c] = nb;
     }
+}
+
+// The pass over all J columns (x_j^T r and the optimality violation, see k_kkt) for large J:
+// persistent wavefronts take 64 consecutive columns at a time and walk their slabs of 512 rows as in
+// geno_column_sums, but keep the next slab's 16-byte loads in flight while the current one is
+// turned through LDS and consumed, so that the memory latency is hidden behind the arithmetic.  The
+// sum of r is taken once per wavefront.
+__global__ __launch_bounds__(256) void k_geno_all(const uint32_t *__restrict__ Xw, int64_t words,
+                                                  const float *__restrict__ mean, const float *__restrict__ scale,
+                                                  int64_t J, RoundScalars *__restrict__ sc,
+                                                  const float *__restrict__ r, float lambda,
+                                                  const float *__restrict__ beta, float *__restrict__ g_out)
+{
+    constexpr int SW = kSlabLong, STRIDE = SW + 1, CH = SW / 4;
+    __shared__ uint32_t slab[4][64 * STRIDE];
+    __shared__ float vm[4];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    uint32_t *lds_wave = slab[wave];
+    const int nslab = (int)((words + SW - 1) / SW);
+    const int64_t ngroups = (J + 63) / 64;
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+
+    float rpart = 0.f;                          // sum of r, fixed order
+    for (int64_t i = lane; i < 16 * words; i += 64) rpart += r[i];
+    const float rs = gwave_sum_all(rpart);
+
+    // the 16-byte pieces of a slab this lane brings in: pass i covers columns 8 i .. 8 i + 7 of the group
+    auto fetch = [&](int64_t g, int sl, uint4 (&v)[CH]) {
+        const int64_t w = (int64_t)sl * SW + 4 * (lane % CH);
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            int64_t j = g * 64 + (64 / CH) * i + lane / CH;
+            j = j < J ? j : J - 1;              // the last group may be short: its extra lanes repeat a column
+            v[i] = w < words ? *reinterpret_cast<const uint4 *>(Xw + j * words + w) : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+
+    float vmax = 0.f;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    uint4 cur[CH], nxt[CH];
+    int64_t g = (int64_t)blockIdx.x * 4 + wave;
+    int sl = 0;
+    if (g < ngroups) fetch(g, 0, cur);
+    while (g < ngroups) {
+        int64_t g2 = g;
+        int sl2 = sl + 1;
+        if (sl2 == nslab) { sl2 = 0; g2 = g + nwaves; }
+        if (g2 < ngroups) fetch(g2, sl2, nxt);
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            uint32_t *dst = lds_wave + ((64 / CH) * i + lane / CH) * STRIDE + 4 * (lane % CH);
+            dst[0] = cur[i].x; dst[1] = cur[i].y; dst[2] = cur[i].z; dst[3] = cur[i].w;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int64_t w0 = (int64_t)sl * SW;
+        const int nw = words - w0 < SW ? (int)(words - w0) : SW;
+        geno_consume(lds_wave + lane * STRIDE, nw, r + 16 * w0, a0, a1, a2, a3);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();        // the slab is consumed before the next one lands
+        if (sl == nslab - 1) {                  // column finished
+            const int64_t j = g * 64 + lane;
+            if (j < J) {
+                const float gr = (a0 + 0.25f * a1) + (0.0625f * a2 + 0.015625f * a3);
+                const float dot = scale[j] * (gr - mean[j] * rs);
+                const float b = beta[j];
+                if (g_out) g_out[j] = dot;
+                float v = b == 0.f ? fmaxf(fabsf(dot) - lambda, 0.f) : fabsf(dot - copysignf(lambda, b));
+                if (!(v == v)) v = __uint_as_float(0x7F800000u);
+                vmax = fmaxf(vmax, v);
+            }
+            a0 = a1 = a2 = a3 = 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) cur[i] = nxt[i];
+        g = g2;
+        sl = sl2;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) vmax = fmaxf(vmax, __shfl_down(vmax, off));
+    if (lane == 0) vm[wave] = vmax;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        atomicMax(&sc->kkt_max_bits, __float_as_uint(fmaxf(fmaxf(vm[0], vm[1]), fmaxf(vm[2], vm[3]))));
 }
 
 // Residual update, stage 1 (stage 2 is k_residual_apply of the dense path): grid = (blocks of 256
@@ -275,25 +354,16 @@ __global__ __launch_bounds__(256) void k_geno_residual_partial(const uint32_t *_
 // ---------------------------------------------------------------------------------------------
 static inline const uint32_t *geno_words_ptr(const strads_lasso *h) { return reinterpret_cast<const uint32_t *>(h->cfg.x); }
 
-// the walk over all slabs per wavefront needs enough columns to fill the chip; short lists use the
-// variant that spreads a column's slabs over a workgroup's four wavefronts
+// the persistent pass needs enough columns to fill the chip (64 per wavefront)
 static inline bool geno_wide(int64_t ncols) { return ncols >= 256 * 256; }
 
 #define STRADS_GENO_DOTS(MODE, LIST, NHOST, Z, DELTA, NB)                                                          \
     do {                                                                                                           \
         const int64_t ncols_ = (NHOST);                                                                            \
-        if (geno_wide(ncols_))                                                                                     \
-            hipLaunchKernelGGL((k_geno_dots<MODE, 256>), dim3((unsigned)((ncols_ + 255) / 256)), dim3(256), 0,     \
-                               h->stream, geno_words_ptr(h), geno_words(h->cfg.n), h->cfg.col_mean,                \
-                               h->cfg.col_scale, LIST, ncols_, h->at<RoundScalars>(h->ws.scalars),                 \
-                               h->at<float>(h->ws.r), h->cfg.lambda, h->at<float>(h->ws.beta),                     \
-                               h->at<float>(h->ws.dbeta), Z, DELTA, NB);                                           \
-        else                                                                                                       \
-            hipLaunchKernelGGL((k_geno_dots<MODE, 64>), dim3((unsigned)((ncols_ + 63) / 64)), dim3(256), 0,        \
-                               h->stream, geno_words_ptr(h), geno_words(h->cfg.n), h->cfg.col_mean,                \
-                               h->cfg.col_scale, LIST, ncols_, h->at<RoundScalars>(h->ws.scalars),                 \
-                               h->at<float>(h->ws.r), h->cfg.lambda, h->at<float>(h->ws.beta),                     \
-                               h->at<float>(h->ws.dbeta), Z, DELTA, NB);                                           \
+        hipLaunchKernelGGL((k_geno_dots<MODE>), dim3((unsigned)((ncols_ + 63) / 64)), dim3(256), 0, h->stream,     \
+                           geno_words_ptr(h), geno_words(h->cfg.n), h->cfg.col_mean, h->cfg.col_scale, LIST,       \
+                           ncols_, h->at<RoundScalars>(h->ws.scalars), h->at<float>(h->ws.r), h->cfg.lambda,       \
+                           h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), Z, DELTA, NB);                     \
     } while (0)
 
 hipError_t launch_dots_geno(strads_lasso *h)
@@ -315,6 +385,16 @@ hipError_t launch_kkt_geno(strads_lasso *h, float *g_or_null)
 {
     hipError_t e = launch_clear_kkt(h);
     if (e != hipSuccess) return e;
+    if (geno_wide(h->cfg.j)) {
+        // persistent: four workgroups per compute unit (LDS allows no more), fewer if the columns run out
+        int64_t g = (h->cfg.j + 255) / 256;
+        if (g > 256 * 4) g = 256 * 4;
+        hipLaunchKernelGGL(k_geno_all, dim3((unsigned)g), dim3(256), 0, h->stream, geno_words_ptr(h),
+                           geno_words(h->cfg.n), h->cfg.col_mean, h->cfg.col_scale, h->cfg.j,
+                           h->at<RoundScalars>(h->ws.scalars), h->at<float>(h->ws.r), h->cfg.lambda,
+                           h->at<float>(h->ws.beta), g_or_null);
+        return hipGetLastError();
+    }
     STRADS_GENO_DOTS(kGenoAll, (const int32_t *)nullptr, h->cfg.j, g_or_null, (float *)nullptr, (float *)nullptr);
     return hipGetLastError();
 }
