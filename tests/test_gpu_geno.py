@@ -21,6 +21,8 @@ pytestmark = pytest.mark.gpu
     (dict(n=463, j=3000, nnz=10, l_prime=300), 6),           # last word of a column partly filled
     (dict(n=64, j=500, nnz=5, l_prime=130), 5),              # exactly one 16-byte group per column
     (dict(n=17, j=300, nnz=4, l_prime=64), 5),
+    (dict(n=5, j=7, nnz=2, l_prime=7), 4),                   # one word per column, every column a candidate
+    (dict(n=129, j=70000, nnz=10, l_prime=200), 3),          # enough columns for the persistent pass over all of them
     (dict(n=5000, j=1500, nnz=10, l_prime=257), 5),          # several row blocks in the residual update
 ])
 def test_teacher_forced_rounds(kw, rounds):
