@@ -118,6 +118,20 @@ def test_config5_shape_at_maximum_candidate_count():
     print("logged:", _rounds_dense(p, 2, gram_pairs=4000))
 
 
+def test_config5_full_size():
+    _skip_without_gpu()
+    # the whole fifth configuration: 5*10^4 x 10^6 fp32 = 200 GB of X resident in HBM, L' = 8000
+    torch.cuda.empty_cache()
+    free, _total = torch.cuda.mem_get_info()
+    if free < 215 * 10 ** 9:
+        pytest.skip(f"needs 215 GB of free HBM, {free / 1e9:.0f} GB available")
+    p = si.make("c5_dense_duplicates", device="cuda:0")
+    assert (p.n, p.j, p.l_prime) == (50000, 1000000, 8000)
+    print("logged:", _rounds_dense(p, 2, gram_pairs=4000))
+    del p
+    torch.cuda.empty_cache()
+
+
 def test_config4_full_size_csc():
     _skip_without_gpu()
     import paper_1312_5766_amd as pk
