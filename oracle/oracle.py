@@ -34,10 +34,12 @@ class _Problem(C.Structure):
     _fields_ = [("N", C.c_int64), ("J", C.c_int64), ("X", C.c_void_p), ("row_idx", C.c_void_p),
                 ("col_ptr", C.c_void_p), ("lam", C.c_float), ("rho", C.c_float), ("eta", C.c_float),
                 ("l_prime", C.c_int32), ("p_max", C.c_int32), ("seed", C.c_uint64),
-                ("priority", C.c_int32), ("deps", C.c_int32), ("n_shards", C.c_int32)]
+                ("priority", C.c_int32), ("deps", C.c_int32), ("n_shards", C.c_int32), ("loss", C.c_int32),
+                ("y", C.c_void_p)]
 
 
 PRIORITY = {"squared": 0, "linear": 1, "uniform": 2}
+LOSS = {"squared": 0, "logistic": 1}
 
 
 def lib():
@@ -74,7 +76,7 @@ def lib():
         L.oracle_dots_csc.restype = None
         L.oracle_soft_threshold.argtypes = [f64, f64]
         L.oracle_soft_threshold.restype = f64
-        L.oracle_update.argtypes = [i32, vp, vp, f32, vp, vp, vp]
+        L.oracle_update.argtypes = [i32, vp, vp, f32, f64, vp, vp, vp]
         L.oracle_update.restype = None
         L.oracle_residual_dense.argtypes = [i64, vp, vp, i32, vp, vp]
         L.oracle_residual_dense.restype = None
@@ -82,6 +84,10 @@ def lib():
         L.oracle_residual_csc.restype = None
         L.oracle_objective.argtypes = [i64, vp, i64, vp, f32]
         L.oracle_objective.restype = f64
+        L.oracle_logistic_weights.argtypes = [i64, vp, vp, vp]
+        L.oracle_logistic_weights.restype = None
+        L.oracle_objective_logistic.argtypes = [i64, vp, vp, i64, vp, f32]
+        L.oracle_objective_logistic.restype = f64
         L.oracle_kkt_dense.argtypes = [i64, i64, vp, vp, vp, f32, vp]
         L.oracle_kkt_dense.restype = f64
         L.oracle_kkt_csc.argtypes = [i64, vp, vp, vp, vp, vp, f32, vp]
@@ -178,12 +184,13 @@ class OracleLasso:
 
     def __init__(self, y, lam, rho, eta, l_prime, seed=0, p_max=0, c_init=1e6, x=None,
                  values=None, row_idx=None, col_ptr=None, n=None, dynamic=False, priority="squared",
-                 no_deps=False, n_shards=1):
+                 no_deps=False, n_shards=1, loss="squared"):
         self.dynamic = bool(dynamic)          # update-aware dependencies (oracle_round_dynamic)
         self.priority = priority              # "squared" | "linear" | "uniform"
         self.no_deps = bool(no_deps)          # skip Step 2 (Shotgun)
         self.n_shards = max(1, int(n_shards)) # scheduler shards taking turns; coordinate j is in shard j % S
         assert not (self.dynamic and self.no_deps)
+        self.loss = loss                      # "squared" | "logistic" (labels y in {-1, +1}; state vector -X beta)
         self.y = _arr(y, np.float32)
         if x is not None:
             self.x = _arr(x, np.float32)
@@ -202,12 +209,12 @@ class OracleLasso:
         # Algorithm 1 initialisation: beta^(t-1) = 0, beta^(t-2) = C  =>  delta beta_j = C for all j
         self.beta = np.zeros(self.J, np.float32)
         self.dbeta = np.full(self.J, c_init, np.float32)
-        self.r = self.y.copy()
+        self.r = self.y.copy() if loss == "squared" else np.zeros(self.N, np.float32)
         self.t = 0
         self._prob = _Problem(self.N, self.J, _p(self.x), _p(self.row_idx), _p(self.col_ptr),
                               self.lam, self.rho, self.eta, self.l_prime, self.p_max, self.seed,
                               PRIORITY[priority], 2 if self.no_deps else (1 if self.dynamic else 0),
-                              self.n_shards)
+                              self.n_shards, LOSS[loss], _p(self.y))
 
     def set_state(self, beta, dbeta, r, t):
         self.beta[:] = beta
@@ -275,13 +282,25 @@ class OracleLasso:
         return out
 
     def objective(self) -> float:
+        if self.loss == "logistic":
+            return float(lib().oracle_objective_logistic(self.N, _p(self.y), _p(self.r), self.J, _p(self.beta),
+                                                         self.lam))
         return objective(self.r, self.beta, self.lam)
+
+    def dots_vector(self) -> np.ndarray:
+        """What eq. (2) and the optimality test take dot products with: r, or the logistic weights."""
+        if self.loss != "logistic":
+            return self.r
+        w = np.empty(self.N, np.float32)
+        lib().oracle_logistic_weights(self.N, _p(self.y), _p(self.r), _p(w))
+        return w
 
     def kkt(self, want_g=False):
         g = np.empty(self.J, np.float64) if want_g else None
+        dv = self.dots_vector()
         if self.csc:
-            v = lib().oracle_kkt_csc(self.J, _p(self.x), _p(self.row_idx), _p(self.col_ptr), _p(self.r),
+            v = lib().oracle_kkt_csc(self.J, _p(self.x), _p(self.row_idx), _p(self.col_ptr), _p(dv),
                                      _p(self.beta), self.lam, _p(g))
         else:
-            v = lib().oracle_kkt_dense(self.N, self.J, _p(self.x), _p(self.r), _p(self.beta), self.lam, _p(g))
+            v = lib().oracle_kkt_dense(self.N, self.J, _p(self.x), _p(dv), _p(self.beta), self.lam, _p(g))
         return (float(v), g) if want_g else float(v)

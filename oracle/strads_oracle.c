@@ -272,14 +272,15 @@ double oracle_soft_threshold(double a, double lambda)
 }
 
 /* Apply eq. (2) to every kept coordinate (all from the same stale r), record
- * the change (Step 4: delta beta_j feeds the next draw). */
-void oracle_update(int32_t k, const int32_t *cols, const double *z, float lambda,
+ * the change (Step 4: delta beta_j feeds the next draw).  inv_kappa = 1 is eq. (2) as printed
+ * (squared loss, unit-norm columns); for the logistic loss see oracle_logistic_weights. */
+void oracle_update(int32_t k, const int32_t *cols, const double *z, float lambda, double inv_kappa,
                    float *beta, float *dbeta, double *delta)
 {
     for (int32_t c = 0; c < k; ++c) {
         int32_t j = cols[c];
         double old = (double)beta[j];
-        float nb = (float)oracle_soft_threshold(z[c] + old, (double)lambda);
+        float nb = (float)oracle_soft_threshold(z[c] * inv_kappa + old, (double)lambda * inv_kappa);
         double d = (double)nb - old;
         delta[c] = d;
         dbeta[j] = (float)fabs(d);
@@ -318,6 +319,39 @@ double oracle_objective(int64_t N, const float *r, int64_t J, const float *beta,
     for (int64_t i = 0; i < N; ++i) s += (double)r[i] * (double)r[i];
     for (int64_t j = 0; j < J; ++j) l1 += fabs((double)beta[j]);
     return 0.5 * s + (double)lambda * l1;
+}
+
+/* --------------------------------------------------------------------------
+ * Logistic loss.  Section 2.1 lets L in eq. (1) be "squared-loss or logistic-loss" and says the
+ * latter is handled "using the same approach" as in the parallel coordinate descent work it cites;
+ * no formula is given.  Taken here: labels y_i in {-1, +1},
+ *      L(beta) = sum_i log(1 + exp(-y_i m_i)),   m = X beta,
+ * whose derivative along coordinate j is -x_j^T w with w_i = y_i / (1 + exp(y_i m_i)), and whose
+ * second derivative along a unit-norm column is at most 1/4.  A coordinate update minimises the
+ * quadratic upper bound with that curvature, kappa = 1/4:
+ *      beta_j <- S(beta_j + (x_j^T w) / kappa, lambda / kappa),
+ * which never increases the objective when applied one coordinate at a time.  Everything else of
+ * Algorithm 1 is unchanged; w takes the place of the residual in eq. (2) and in the optimality test,
+ * and the state vector kept between rounds is v = -X beta (so that the same residual update
+ * v <- v - sum x_j delta_j maintains it): w_i = y_i / (1 + exp(-y_i v_i)).
+ * ------------------------------------------------------------------------ */
+void oracle_logistic_weights(int64_t N, const float *y, const float *v, float *w)
+{
+    for (int64_t i = 0; i < N; ++i)
+        w[i] = (float)((double)y[i] / (1.0 + exp(-(double)y[i] * (double)v[i])));
+}
+
+/* eq. (1) with the logistic loss: sum_i log(1 + exp(y_i v_i)) + lambda sum |beta_j|, v = -X beta. */
+double oracle_objective_logistic(int64_t N, const float *y, const float *v, int64_t J, const float *beta,
+                                 float lambda)
+{
+    double s = 0.0, l1 = 0.0;
+    for (int64_t i = 0; i < N; ++i) {
+        const double t = (double)y[i] * (double)v[i];
+        s += t > 0.0 ? t + log1p(exp(-t)) : log1p(exp(t));
+    }
+    for (int64_t j = 0; j < J; ++j) l1 += fabs((double)beta[j]);
+    return s + (double)lambda * l1;
 }
 
 /* Optimality (KKT) violation of eq. (1) at beta, g = X^T r:
@@ -383,7 +417,22 @@ typedef struct {
                                   dispatched, up to p_max: the Shotgun scheduler of Section 5.1).
                                   1 is oracle_round_dynamic's rule and is not read here. */
     int32_t n_shards;          /* S scheduler shards taking turns (Section 3); <= 1: one scheduler */
+    int32_t loss;              /* 0: squared loss (the state vector is r = y - X beta);
+                                  1: logistic loss (state vector v = -X beta, see oracle_logistic_weights) */
+    const float *y;            /* logistic loss only: the N labels */
 } oracle_problem_t;
+
+/* The vector that eq. (2)'s dot products are taken with: the residual itself, or the logistic
+ * weights computed from the state vector (the caller frees *owned if it is not NULL). */
+static const float *dots_vector(const oracle_problem_t *p, const float *r, float **owned)
+{
+    *owned = NULL;
+    if (p->loss != 1) return r;
+    *owned = (float *)malloc((size_t)(p->N > 0 ? p->N : 1) * sizeof(float));
+    if (!*owned) return NULL;
+    oracle_logistic_weights(p->N, p->y, r, *owned);
+    return *owned;
+}
 
 /* Step 1 for round t.  With S > 1 scheduler shards (Section 3, "Implementation Overview"): every
  * coordinate belongs to exactly one shard for good, shard s = t mod S has the turn in round t, and it
@@ -452,9 +501,13 @@ int32_t oracle_round(const oracle_problem_t *p, uint64_t t, float *beta, float *
     double *z = z_out ? z_out : (double *)malloc((size_t)(k > 0 ? k : 1) * sizeof(double));
     double *d = delta_out ? delta_out : (double *)malloc((size_t)(k > 0 ? k : 1) * sizeof(double));
     if (!z || !d) return -1;
-    if (p->row_idx) oracle_dots_csc(p->X, p->row_idx, p->col_ptr, kept_cols, k, r, z);
-    else            oracle_dots_dense(p->N, p->X, kept_cols, k, r, z);
-    oracle_update(k, kept_cols, z, p->lambda, beta, dbeta, d);
+    float *w_owned;
+    const float *dv = dots_vector(p, r, &w_owned);
+    if (!dv) return -1;
+    if (p->row_idx) oracle_dots_csc(p->X, p->row_idx, p->col_ptr, kept_cols, k, dv, z);
+    else            oracle_dots_dense(p->N, p->X, kept_cols, k, dv, z);
+    free(w_owned);
+    oracle_update(k, kept_cols, z, p->lambda, p->loss == 1 ? 4.0 : 1.0, beta, dbeta, d);
     if (p->row_idx) oracle_residual_csc(p->N, p->X, p->row_idx, p->col_ptr, kept_cols, k, d, r);
     else            oracle_residual_dense(p->N, p->X, kept_cols, k, d, r);
     if (!z_out) free(z);
@@ -515,11 +568,16 @@ int32_t oracle_round_dynamic(const oracle_problem_t *p, uint64_t t, float *beta,
     uint8_t *mv = (uint8_t *)malloc(Ls);
     float *G = G_out ? G_out : (float *)malloc(Ls * Ls * sizeof(float));
     if (!zc || !dc || !nb || !mv || !G) return -1;
-    if (p->row_idx) oracle_dots_csc(p->X, p->row_idx, p->col_ptr, cand, L, r, zc);
-    else            oracle_dots_dense(p->N, p->X, cand, L, r, zc);
+    float *w_owned;
+    const float *dv = dots_vector(p, r, &w_owned);
+    if (!dv) return -1;
+    if (p->row_idx) oracle_dots_csc(p->X, p->row_idx, p->col_ptr, cand, L, dv, zc);
+    else            oracle_dots_dense(p->N, p->X, cand, L, dv, zc);
+    free(w_owned);
+    const double ik = p->loss == 1 ? 4.0 : 1.0;
     for (int32_t a = 0; a < L; ++a) {
         const double old = (double)beta[cand[a]];
-        nb[a] = (float)oracle_soft_threshold(zc[a] + old, (double)p->lambda);
+        nb[a] = (float)oracle_soft_threshold(zc[a] * ik + old, (double)p->lambda * ik);
         dc[a] = (double)nb[a] - old;
         mv[a] = forced_mover ? (uint8_t)(forced_mover[a] != 0) : (uint8_t)(dc[a] != 0.0);
         if (!mv[a]) { dc[a] = 0.0; nb[a] = beta[cand[a]]; }

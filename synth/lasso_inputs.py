@@ -46,6 +46,7 @@ class LassoProblem:
     codes: Optional[torch.Tensor] = None    # geno2: (j, 4*ceil(n/64)) int32, 16 two-bit genotype counts per word
     col_mean: Optional[torch.Tensor] = None   # geno2: (j,) fp32
     col_scale: Optional[torch.Tensor] = None  # geno2: (j,) fp32; x_ij = fl(fl(g_ij - mean_j) * scale_j)
+    loss: str = "squared"                   # "squared" | "logistic" (then y holds labels in {-1, +1})
 
     def to(self, device) -> "LassoProblem":
         kw = {}
@@ -351,6 +352,24 @@ def csc_to_dense(p: LassoProblem) -> torch.Tensor:
     cols = torch.repeat_interleave(torch.arange(p.j, device=x.device), counts)
     x[cols, p.row_idx.to(torch.int64)] = p.values
     return x
+
+
+def with_labels(p: LassoProblem, margin_scale: float = 4.0, lam_frac: float = 0.1, seed: int = 1) -> LassoProblem:
+    """The same design as a classification problem (the logistic loss of Section 2.1): the planted
+    coefficients give margins m = X beta*, scaled so that their standard deviation is margin_scale;
+    label y_i = +1 with probability 1 / (1 + exp(-m_i)), else -1.  lambda = lam_frac * max |X^T y| / 2
+    (all coefficients stay at zero from lambda = max |X^T y| / 2 upwards).  Dense designs only."""
+    assert p.layout == "dense"
+    g = _gen(seed, p.x.device)
+    b64 = p.beta_true.to(torch.float64)
+    nz = torch.nonzero(b64).flatten()
+    m = b64[nz] @ p.x[nz].to(torch.float64)
+    m = m * (margin_scale / float(m.std()))
+    u = torch.rand(p.n, generator=g, device=p.x.device, dtype=torch.float64)
+    y = torch.where(u < torch.sigmoid(m), 1.0, -1.0).to(torch.float32)
+    lam = 0.5 * lam_frac * _dense_max_abs_xty(p.x, y.to(torch.float64))
+    lam = float(torch.tensor(lam, dtype=torch.float32))
+    return dataclasses.replace(p, name=p.name + "_logistic", y=y, lam=lam, loss="logistic")
 
 
 CONFIGS = {
