@@ -84,6 +84,9 @@ def main() -> int:
                          "none = no check (Shotgun when combined with --priority uniform)")
     ap.add_argument("--priority", default="squared", choices=("squared", "linear", "uniform"),
                     help="weight of Step 1's draw: (delta beta)^2+eta (headline), |delta beta|+eta, or 1")
+    ap.add_argument("--loss", default="squared", choices=("squared", "logistic"),
+                    help="loss of eq. (1); logistic: the workload's design with labels drawn from its planted "
+                         "coefficients (dense workloads; not the headline)")
     ap.add_argument("--p-max", type=int, default=0, help="cap on the kept set (Algorithm 1's P); 0 = none")
     ap.add_argument("--shards", type=int, default=1,
                     help="scheduler shards taking turns (Section 3); > 1 overlaps the shards' scheduling work on "
@@ -129,6 +132,8 @@ def main() -> int:
     key, over = WORKLOADS[args.workload]
     t0 = time.time()
     p = si.make(key, device=dev, **over)
+    if args.loss == "logistic":
+        p = si.with_labels(p)
     torch.cuda.synchronize()
     t_gen = time.time() - t0
     print(f"bench.py: inputs for {args.workload} generated in {t_gen:.1f} s", file=sys.stderr, flush=True)
@@ -136,7 +141,7 @@ def main() -> int:
     def fresh():
         kw = dict(y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed, p_max=args.p_max,
                   dynamic=args.deps == "dynamic", no_deps=args.deps == "none", priority=args.priority,
-                  n_shards=args.shards)
+                  n_shards=args.shards, loss=args.loss)
         h = pk.StradsLasso(**design_args(p), **kw)
         for t in args.tune:
             name, value = t.split("=")
@@ -251,7 +256,7 @@ def main() -> int:
     # the same workload and round count under the two widenings of the schedule (not the headline)
     variants = None
     headline = (args.deps == "static" and args.shards == 1 and args.priority == "squared" and args.kkt_tol == 0
-                and args.p_max == 0)
+                and args.p_max == 0 and args.loss == "squared")
     if headline and not args.no_variants:
         variants = {}
         legs = {"shards4": dict(n_shards=4), "dynamic": dict(dynamic=True)}
@@ -295,7 +300,7 @@ def main() -> int:
         from oracle.oracle import OracleLasso
         okw = dict(y=p.y.cpu().numpy(), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed,
                    p_max=args.p_max, dynamic=args.deps == "dynamic", no_deps=args.deps == "none",
-                   priority=args.priority, n_shards=args.shards)
+                   priority=args.priority, n_shards=args.shards, loss=args.loss)
         o = OracleLasso(**design_args(p, host=True), **okw)
         n_upd, n_rounds = 0, 0
         tc = time.perf_counter()
@@ -319,7 +324,7 @@ def main() -> int:
         "n_gpus": 1, "steps": rounds_done, "warmup": args.warmup, "ms_per_step": round(wall / max(rounds_done, 1) * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "n": p.n, "j": p.j, "l_prime": p.l_prime, "rho": p.rho,
-                   "eta": p.eta, "lambda": p.lam, "rounds": rounds_done, "deps": args.deps, "priority": args.priority, "p_max": args.p_max, "shards": args.shards,
+                   "eta": p.eta, "lambda": p.lam, "rounds": rounds_done, "deps": args.deps, "priority": args.priority, "p_max": args.p_max, "shards": args.shards, "loss": args.loss,
                    "parallelism": "1 GPU"},
         "rounds_per_s": round(rounds_done / wall, 2), "updates": updates, "seconds": round(wall, 4),
         "kkt_tol": args.kkt_tol, "converged": int(info.converged), "graph_replays": int(info.graph_replays),

@@ -61,6 +61,18 @@ extern "C" {
                                              16 times fewer bytes than fp32 for every pass over X. */
 
 #define STRADS_MAX_L_PRIME         8192   /* largest supported candidate count per round */
+/* Loss function of eq. (1) (Section 2.1: "squared-loss or logistic-loss").
+ *   SQUARED   L = 1/2 ||y - X beta||^2; the state vector r kept between rounds is the residual
+ *             y - X beta, and eq. (2) is beta_j <- S(x_j^T r + beta_j, lambda).
+ *   LOGISTIC  L = sum_i log(1 + exp(-y_i x_i^T beta)) with labels y_i in {-1, +1} (not checked).  The
+ *             paper gives no formula; a coordinate step minimises the quadratic upper bound of
+ *             curvature 1/4 (unit-norm columns): beta_j <- S(beta_j + 4 x_j^T w, 4 lambda) with
+ *             w_i = y_i / (1 + exp(y_i x_i^T beta)).  The state vector r is -X beta (zero at start),
+ *             maintained by the same residual update; "z" in strads_lasso_last_round is x_j^T w, and
+ *             the optimality test uses g = X^T w. */
+#define STRADS_LOSS_SQUARED  0
+#define STRADS_LOSS_LOGISTIC 1
+
 #define STRADS_MAX_SHARDS             8   /* largest supported number of scheduler shards */
 
 /* Stages of one round, in stream order, as timed by strads_lasso_stage_times */
@@ -124,6 +136,7 @@ typedef struct {
                                      0 or 1: one scheduler.  With S > 1 the shards' scheduling work
                                      (draw, Gram, greedy walk) runs on library-owned streams concurrently;
                                      the updates are applied in round order.  At most STRADS_MAX_SHARDS. */
+    int32_t        loss;          /* STRADS_LOSS_*: the loss L of eq. (1) */
     void          *workspace;     /* DEVICE, 256-byte aligned, caller-allocated */
     size_t         workspace_bytes;
     void          *stream;        /* hipStream_t owned by the caller (NULL = the default stream) */

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libstrads_lasso.so")
 STRADS_OK = 0
 E_INVALID_ARG, E_WORKSPACE_TOO_SMALL, E_HIP, E_DIVERGED, E_UNSUPPORTED = -1, -2, -3, -4, -5
 LAYOUT_DENSE, LAYOUT_CSC, LAYOUT_GENO2 = 0, 1, 2
+LOSS = {"squared": 0, "logistic": 1}
 MAX_L_PRIME = 8192
 N_STAGES = 7
 STAGE_NAMES = ["sampler", "cand_dots", "gram_tiles", "gram_mask", "filter", "update", "residual"]
@@ -40,7 +41,9 @@ class Config(C.Structure):
                 ("y", C.c_void_p),
                 ("lam", C.c_float), ("rho", C.c_float), ("eta", C.c_float), ("c_init", C.c_float),
                 ("l_prime", C.c_int32), ("p_max", C.c_int32), ("seed", C.c_uint64), ("keep_gram", C.c_int32),
-                ("max_col_nnz", C.c_int32), ("deps", C.c_int32), ("priority", C.c_int32), ("n_shards", C.c_int32), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
+                ("max_col_nnz", C.c_int32), ("deps", C.c_int32), ("priority", C.c_int32), ("n_shards", C.c_int32),
+                ("loss", C.c_int32), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("stream", C.c_void_p)]
 
 
 class RoundInfo(C.Structure):
@@ -125,7 +128,7 @@ class StradsLasso:
                  col_scale: Optional[torch.Tensor] = None,
                  n: Optional[int] = None, max_col_nnz: Optional[int] = None,
                  stream: Optional[torch.cuda.Stream] = None, dynamic: bool = False, priority: str = "squared",
-                 no_deps: bool = False, n_shards: int = 1):
+                 no_deps: bool = False, n_shards: int = 1, loss: str = "squared"):
         lib = load()
         self._h = None
         dev = y.device
@@ -162,7 +165,8 @@ class StradsLasso:
                      c_init=c_init, l_prime=int(l_prime), p_max=int(p_max), seed=int(seed),
                      keep_gram=int(keep_gram), max_col_nnz=int(max_col_nnz or 0),
                      deps=DEPS_NONE if no_deps else (DEPS_DYNAMIC if dynamic else DEPS_STATIC),
-                     priority=PRIORITY[priority], n_shards=int(n_shards), stream=self.stream.cuda_stream)
+                     priority=PRIORITY[priority], n_shards=int(n_shards), loss=LOSS[loss],
+                     stream=self.stream.cuda_stream)
         nbytes = int(lib.strads_lasso_workspace_bytes(C.byref(cfg)))
         if nbytes == 0:
             raise StradsError(E_INVALID_ARG, "strads_lasso_workspace_bytes")

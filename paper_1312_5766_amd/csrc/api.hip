@@ -25,6 +25,7 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
     w.beta = take((size_t)j * 4);
     w.dbeta = take((size_t)j * 4);
     w.r = take((size_t)npad * 4);
+    w.w = take((size_t)npad * 4);
     w.objpart = take((size_t)kObjBlocks * 8);
     w.objout = take(8);
     // once per shard
@@ -87,6 +88,7 @@ static bool sizes_ok(const strads_lasso_config_t *c)
     if (c->priority != STRADS_PRIORITY_SQUARED && c->priority != STRADS_PRIORITY_LINEAR &&
         c->priority != STRADS_PRIORITY_UNIFORM) return false;
     if (c->n_shards < 0 || c->n_shards > STRADS_MAX_SHARDS || (int64_t)c->n_shards > c->j) return false;
+    if (c->loss != STRADS_LOSS_SQUARED && c->loss != STRADS_LOSS_LOGISTIC) return false;
     return true;
 }
 
@@ -145,6 +147,7 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->Npad = (cfg->n + 63) / 64 * 64;
     h->split_max = cfg->layout != STRADS_LAYOUT_CSC ? gram_split_auto(cfg->n, h->Lpad) : 1;
     h->split_user = 0;
+    h->step_scale = cfg->loss == STRADS_LOSS_LOGISTIC ? 4.f : 1.f;
     h->select_cap = kSelectCapDefault;
     h->round = 0;
     h->profile_level = 0;
@@ -279,6 +282,7 @@ static int enqueue_round(strads_lasso *top)
     if (dynamic) {
         // every candidate's update from the current residual; the movers; how to tile their Gram
         AFTER_PREVIOUS_ROUND();
+        if (h->cfg.loss == STRADS_LOSS_LOGISTIC) HIP_TRY(launch_logistic_weights(h));
         if (csc) HIP_TRY(launch_dots_cand_csc(h));
         else if (geno) HIP_TRY(launch_dots_cand_geno(h));
         else HIP_TRY(launch_dots_cand(h));
@@ -294,6 +298,7 @@ static int enqueue_round(strads_lasso *top)
     else HIP_TRY(launch_filter(h, h->L, true));
     MARK(STRADS_STAGE_UPDATE);
     if (!dynamic) AFTER_PREVIOUS_ROUND();
+    if (!dynamic && h->cfg.loss == STRADS_LOSS_LOGISTIC) HIP_TRY(launch_logistic_weights(h));
     if (dynamic) HIP_TRY(launch_commit_dynamic(h));
     else if (csc) HIP_TRY(launch_dots_csc(h));
     else if (geno) HIP_TRY(launch_dots_geno(h));
@@ -482,6 +487,7 @@ int strads_lasso_kkt(strads_lasso_t *h, float *max_violation, float *g_or_null)
             if (!h->ev_kkt[i]) HIP_TRY(hipEventCreate(&h->ev_kkt[i]));
         HIP_TRY(hipEventRecord(h->ev_kkt[0], h->stream));
     }
+    if (h->cfg.loss == STRADS_LOSS_LOGISTIC) HIP_TRY(launch_logistic_weights(h));
     if (h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR) HIP_TRY(launch_kkt_dense(h, g_or_null));
     else if (h->cfg.layout == STRADS_LAYOUT_GENO2) HIP_TRY(launch_kkt_geno(h, g_or_null));
     else HIP_TRY(launch_kkt_csc(h, g_or_null));

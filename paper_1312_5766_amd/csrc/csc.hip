@@ -235,8 +235,9 @@ __global__ __launch_bounds__(256) void k_csc_dots_update(const float *__restrict
                                                          const int64_t *__restrict__ col_ptr,
                                                          const int32_t *__restrict__ kept,
                                                          const RoundScalars *__restrict__ sc, const float *__restrict__ r,
-                                                         float lambda, float *__restrict__ beta, float *__restrict__ dbeta,
-                                                         float *__restrict__ z, float *__restrict__ delta)
+                                                         float lambda, float step, float *__restrict__ beta,
+                                                         float *__restrict__ dbeta, float *__restrict__ z,
+                                                         float *__restrict__ delta)
 {
     const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (c >= sc->n_kept) return;
@@ -244,8 +245,9 @@ __global__ __launch_bounds__(256) void k_csc_dots_update(const float *__restrict
     const float s = sparse_dot(val, row_idx, col_ptr[j], col_ptr[j + 1], r, threadIdx.x & 63);
     if ((threadIdx.x & 63) == 0) {
         const float b = beta[j];
-        const float m = fabsf(s + b) - lambda;
-        const float nb = m > 0.f ? copysignf(m, s + b) : 0.f;
+        const float a = s * step + b;               // step = 1: eq. (2) as printed
+        const float m = fabsf(a) - lambda * step;
+        const float nb = m > 0.f ? copysignf(m, a) : 0.f;
         const float d = nb - b;
         z[c] = s;
         delta[c] = d;
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(256) void k_csc_dots_cand(const float *__restrict__
                                                        const int32_t *__restrict__ row_idx,
                                                        const int64_t *__restrict__ col_ptr,
                                                        const int32_t *__restrict__ cand, int32_t L,
-                                                       const float *__restrict__ r, float lambda,
+                                                       const float *__restrict__ r, float lambda, float step,
                                                        const float *__restrict__ beta, float *__restrict__ zc,
                                                        float *__restrict__ dc, float *__restrict__ nbc)
 {
@@ -269,8 +271,9 @@ __global__ __launch_bounds__(256) void k_csc_dots_cand(const float *__restrict__
     const float s = sparse_dot(val, row_idx, col_ptr[j], col_ptr[j + 1], r, threadIdx.x & 63);
     if ((threadIdx.x & 63) == 0) {
         const float b = beta[j];
-        const float m = fabsf(s + b) - lambda;
-        const float nb = m > 0.f ? copysignf(m, s + b) : 0.f;
+        const float a = s * step + b;
+        const float m = fabsf(a) - lambda * step;
+        const float nb = m > 0.f ? copysignf(m, a) : 0.f;
         zc[c] = s;
         nbc[c] = nb;
         dc[c] = nb - b;
@@ -391,7 +394,7 @@ hipError_t launch_gram_csc(strads_lasso *h)
 hipError_t launch_dots_cand_csc(strads_lasso *h)
 {
     hipLaunchKernelGGL(k_csc_dots_cand, dim3((h->L + 3) / 4), dim3(256), 0, h->stream, h->cfg.x, h->cfg.row_idx,
-                       h->cfg.col_ptr, h->at<int32_t>(h->ws.cand), h->L, h->at<float>(h->ws.r), h->cfg.lambda,
+                       h->cfg.col_ptr, h->at<int32_t>(h->ws.cand), h->L, dots_vector(h), h->cfg.lambda, h->step_scale,
                        h->at<float>(h->ws.beta), h->at<float>(h->ws.zc), h->at<float>(h->ws.dc),
                        h->at<float>(h->ws.nbc));
     return hipGetLastError();
@@ -401,8 +404,8 @@ hipError_t launch_dots_csc(strads_lasso *h)
 {
     hipLaunchKernelGGL(k_csc_dots_update, dim3((h->L + 3) / 4), dim3(256), 0, h->stream, h->cfg.x, h->cfg.row_idx,
                        h->cfg.col_ptr, h->at<int32_t>(h->ws.kept), h->at<RoundScalars>(h->ws.scalars),
-                       h->at<float>(h->ws.r), h->cfg.lambda, h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta),
-                       h->at<float>(h->ws.z), h->at<float>(h->ws.delta));
+                       dots_vector(h), h->cfg.lambda, h->step_scale, h->at<float>(h->ws.beta),
+                       h->at<float>(h->ws.dbeta), h->at<float>(h->ws.z), h->at<float>(h->ws.delta));
     return hipGetLastError();
 }
 
@@ -423,7 +426,7 @@ hipError_t launch_kkt_csc(strads_lasso *h, float *g_or_null)
     hipError_t e = launch_clear_kkt(h);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_csc_kkt, dim3((unsigned)((h->cfg.j + 3) / 4 < 256 * 16 ? (h->cfg.j + 3) / 4 : 256 * 16)), dim3(256), 0, h->stream, h->cfg.x,
-                       h->cfg.row_idx, h->cfg.col_ptr, h->cfg.j, h->at<float>(h->ws.r), h->at<float>(h->ws.beta),
+                       h->cfg.row_idx, h->cfg.col_ptr, h->cfg.j, dots_vector(h), h->at<float>(h->ws.beta),
                        h->cfg.lambda, g_or_null, sc);
     return hipGetLastError();
 }

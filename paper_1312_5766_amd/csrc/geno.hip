@@ -149,9 +149,9 @@ __global__ __launch_bounds__(256) void k_geno_dots(const uint32_t *__restrict__ 
                                                    const float *__restrict__ mean, const float *__restrict__ scale,
                                                    const int32_t *__restrict__ list, int64_t n_host,
                                                    RoundScalars *__restrict__ sc, const float *__restrict__ r,
-                                                   float lambda, float *__restrict__ beta, float *__restrict__ dbeta,
-                                                   float *__restrict__ z, float *__restrict__ delta,
-                                                   float *__restrict__ newbeta)
+                                                   float lambda, float step, float *__restrict__ beta,
+                                                   float *__restrict__ dbeta, float *__restrict__ z,
+                                                   float *__restrict__ delta, float *__restrict__ newbeta)
 {
     __shared__ uint32_t slab[4][64 * (kSlabShort + 1)];
     __shared__ GenoSums comb[4][64];
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(256) void k_geno_dots(const uint32_t *__restrict__ 
         if (lane == 0) atomicMax(&sc->kkt_max_bits, __float_as_uint(v));
     } else if (live) {
         const float b = beta[j];
-        const float nb = soft_threshold_g(dot + b, lambda);
+        const float nb = soft_threshold_g(dot * step + b, lambda * step);     // step = 1: eq. (2) as printed
         const float d = nb - b;
         z[c] = dot;
         delta[c] = d;
@@ -362,8 +362,8 @@ static inline bool geno_wide(int64_t ncols) { return ncols >= 256 * 256; }
         const int64_t ncols_ = (NHOST);                                                                            \
         hipLaunchKernelGGL((k_geno_dots<MODE>), dim3((unsigned)((ncols_ + 63) / 64)), dim3(256), 0, h->stream,     \
                            geno_words_ptr(h), geno_words(h->cfg.n), h->cfg.col_mean, h->cfg.col_scale, LIST,       \
-                           ncols_, h->at<RoundScalars>(h->ws.scalars), h->at<float>(h->ws.r), h->cfg.lambda,       \
-                           h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), Z, DELTA, NB);                     \
+                           ncols_, h->at<RoundScalars>(h->ws.scalars), dots_vector(h), h->cfg.lambda,              \
+                           h->step_scale, h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), Z, DELTA, NB);      \
     } while (0)
 
 hipError_t launch_dots_geno(strads_lasso *h)
@@ -391,7 +391,7 @@ hipError_t launch_kkt_geno(strads_lasso *h, float *g_or_null)
         if (g > 256 * 4) g = 256 * 4;
         hipLaunchKernelGGL(k_geno_all, dim3((unsigned)g), dim3(256), 0, h->stream, geno_words_ptr(h),
                            geno_words(h->cfg.n), h->cfg.col_mean, h->cfg.col_scale, h->cfg.j,
-                           h->at<RoundScalars>(h->ws.scalars), h->at<float>(h->ws.r), h->cfg.lambda,
+                           h->at<RoundScalars>(h->ws.scalars), dots_vector(h), h->cfg.lambda,
                            h->at<float>(h->ws.beta), g_or_null);
         return hipGetLastError();
     }

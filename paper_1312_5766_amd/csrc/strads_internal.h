@@ -58,6 +58,7 @@ struct Workspace {
     // offsets in bytes from the workspace base.  beta, dbeta, r, objpart, objout are shared by all
     // scheduler shards; everything else exists once per shard, lane_stride bytes apart.
     size_t beta, dbeta, r;
+    size_t w;               // float [Npad]: logistic loss, the weights eq. (2)'s dot products are taken with
     size_t keys;            // uint32 [J]
     size_t hist;            // uint32 [2][kHistBins]
     size_t scalars;         // RoundScalars
@@ -96,6 +97,7 @@ struct strads_lasso {
     int32_t L;          // min(l_prime, J)
     int32_t Lpad;       // L rounded up to the Gram tile
     int64_t Npad;       // N rounded up to 64; r[N .. Npad) is kept at zero
+    float step_scale;   // 1 / curvature of the coordinate step: 1 (squared loss), 4 (logistic loss)
     int32_t split_max;  // K-slices the workspace was sized for
     int32_t split_user; // tuning override (0 = automatic)
     int32_t select_cap;
@@ -155,6 +157,12 @@ hipError_t launch_residual_dense(strads_lasso *h);                         // r 
 hipError_t launch_residual_apply(strads_lasso *h, int groups);             // r -= sum of the groups' partial sums
 int residual_groups(int64_t n, int32_t l);
 hipError_t launch_objective(strads_lasso *h);                              // -> objout
+hipError_t launch_logistic_weights(strads_lasso *h);                       // r (= -X beta) -> w
+// the vector eq. (2) and the optimality test take dot products with
+inline const float *dots_vector(const strads_lasso *h)
+{
+    return reinterpret_cast<const float *>(h->base + (h->cfg.loss == STRADS_LOSS_LOGISTIC ? h->ws.w : h->ws.r));
+}
 hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null);            // -> scalars.kkt_max_bits
 hipError_t launch_init_state(strads_lasso *h);
 hipError_t launch_init_lane(strads_lasso *h);             // zero a shard's histograms and round scalars

@@ -76,8 +76,9 @@ template <int TPC, bool VEC4>
 __global__ __launch_bounds__(256) void k_dots_update(const float *__restrict__ X, int64_t N,
                                                      const int32_t *__restrict__ kept,
                                                      const RoundScalars *__restrict__ sc, const float *__restrict__ r,
-                                                     float lambda, float *__restrict__ beta, float *__restrict__ dbeta,
-                                                     float *__restrict__ z, float *__restrict__ delta)
+                                                     float lambda, float step, float *__restrict__ beta,
+                                                     float *__restrict__ dbeta, float *__restrict__ z,
+                                                     float *__restrict__ delta)
 {
     __shared__ float red[4];
     constexpr int CPB = 256 / TPC;              // columns per workgroup
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(256) void k_dots_update(const float *__restrict__ X
     const float s = column_dot<TPC, VEC4>(X + (int64_t)j * N, r, N, threadIdx.x % TPC, red);
     if (threadIdx.x % TPC == 0) {
         const float b = beta[j];
-        const float nb = soft_threshold(s + b, lambda);
+        const float nb = soft_threshold(s * step + b, lambda * step);     // step = 1: eq. (2) as printed
         const float d = nb - b;
         z[c] = s;
         delta[c] = d;
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(256) void k_dots_update(const float *__restrict__ X
 template <int TPC, bool VEC4>
 __global__ __launch_bounds__(256) void k_dots_cand(const float *__restrict__ X, int64_t N,
                                                    const int32_t *__restrict__ cand, int32_t L,
-                                                   const float *__restrict__ r, float lambda,
+                                                   const float *__restrict__ r, float lambda, float step,
                                                    const float *__restrict__ beta, float *__restrict__ zc,
                                                    float *__restrict__ dc, float *__restrict__ nbc)
 {
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(256) void k_dots_cand(const float *__restrict__ X, 
     const float s = column_dot<TPC, VEC4>(X + (int64_t)j * N, r, N, threadIdx.x % TPC, red);
     if (threadIdx.x % TPC == 0) {
         const float b = beta[j];
-        const float nb = soft_threshold(s + b, lambda);
+        const float nb = soft_threshold(s * step + b, lambda * step);
         zc[c] = s;
         nbc[c] = nb;
         dc[c] = nb - b;
@@ -299,6 +300,41 @@ __global__ __launch_bounds__(256) void k_objective_partial(const float *__restri
     if (threadIdx.x == 0) part[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+// eq. (1) with the logistic loss: sum_i log(1 + exp(y_i v_i)) + lambda sum |beta_j|, v = -X beta
+__global__ __launch_bounds__(256) void k_objective_logistic_partial(const float *__restrict__ y,
+                                                                    const float *__restrict__ v, int64_t N,
+                                                                    const float *__restrict__ beta, int64_t J,
+                                                                    double lambda, double *__restrict__ part)
+{
+    __shared__ double red[4];
+    double s = 0.0;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < N; i += stride) {
+        const double t = (double)y[i] * (double)v[i];
+        s += t > 0.0 ? t + log1p(exp(-t)) : log1p(exp(t));
+    }
+    for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < J; j += stride) s += lambda * fabs((double)beta[j]);
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) part[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// Logistic loss: the weights w_i = y_i / (1 + exp(-y_i v_i)), v = -X beta, that take the residual's place
+// in eq. (2) and in the optimality test; the padding up to Npad stays zero.
+__global__ __launch_bounds__(256) void k_logistic_weights(const float *__restrict__ y, const float *__restrict__ v,
+                                                          int64_t N, int64_t Npad, float *__restrict__ w)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= Npad) return;
+    float out = 0.f;
+    if (i < N) {
+        const float yi = y[i];
+        out = yi / (1.f + expf(-yi * v[i]));
+    }
+    w[i] = out;
+}
+
 __global__ __launch_bounds__(256) void k_objective_final(const double *__restrict__ part, int n, double *__restrict__ out)
 {
     __shared__ double red[4];
@@ -400,7 +436,7 @@ __global__ __launch_bounds__(256) void k_kkt_stream(const float *__restrict__ X,
 }
 
 __global__ __launch_bounds__(256) void k_init_state(const float *__restrict__ y, int64_t N, int64_t Npad, int64_t J,
-                                                    float c_init,
+                                                    float c_init, int zero_state,
                                                     float *__restrict__ beta, float *__restrict__ dbeta,
                                                     float *__restrict__ r, uint32_t *__restrict__ hist,
                                                     uint32_t *__restrict__ scalars_words, int n_scalar_words)
@@ -412,7 +448,9 @@ __global__ __launch_bounds__(256) void k_init_state(const float *__restrict__ y,
         for (int i = threadIdx.x; i < n_scalar_words; i += 256) scalars_words[i] = 0u;
     }
     // the padding of r stays zero for good: kernels that work on whole 64-row groups rely on it
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < Npad; i += stride) r[i] = i < N ? y[i] : 0.f;
+    // squared loss: r = y - X 0; logistic loss: the state vector is -X 0
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < Npad; i += stride)
+        r[i] = (i < N && !zero_state) ? y[i] : 0.f;
     for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < J; j += stride) { beta[j] = 0.f; dbeta[j] = c_init; }
 }
 
@@ -422,11 +460,11 @@ __global__ void k_clear_kkt(RoundScalars *sc) { sc->kkt_max_bits = 0u; }
 hipError_t launch_dots_dense(strads_lasso *h)
 {
     const RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
-    const float *r = h->at<float>(h->ws.r);
+    const float *r = dots_vector(h);
     const int32_t *kept = h->at<int32_t>(h->ws.kept);
     const bool wide = h->cfg.n > 2048;
     const unsigned grid = wide ? (unsigned)h->L : (unsigned)((h->L + 3) / 4);
-#define STRADS_DOTS(TPC, V) hipLaunchKernelGGL((k_dots_update<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, kept, sc, r, h->cfg.lambda, h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.z), h->at<float>(h->ws.delta))
+#define STRADS_DOTS(TPC, V) hipLaunchKernelGGL((k_dots_update<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, kept, sc, r, h->cfg.lambda, h->step_scale, h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.z), h->at<float>(h->ws.delta))
     if (wide) { if (h->vec4) STRADS_DOTS(256, true); else STRADS_DOTS(256, false); }
     else      { if (h->vec4) STRADS_DOTS(64, true);  else STRADS_DOTS(64, false); }
 #undef STRADS_DOTS
@@ -437,7 +475,7 @@ hipError_t launch_dots_cand(strads_lasso *h)
 {
     const bool wide = h->cfg.n > 2048;
     const unsigned grid = wide ? (unsigned)h->L : (unsigned)((h->L + 3) / 4);
-#define STRADS_DOTS_CAND(TPC, V) hipLaunchKernelGGL((k_dots_cand<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), h->L, h->at<float>(h->ws.r), h->cfg.lambda, h->at<float>(h->ws.beta), h->at<float>(h->ws.zc), h->at<float>(h->ws.dc), h->at<float>(h->ws.nbc))
+#define STRADS_DOTS_CAND(TPC, V) hipLaunchKernelGGL((k_dots_cand<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), h->L, dots_vector(h), h->cfg.lambda, h->step_scale, h->at<float>(h->ws.beta), h->at<float>(h->ws.zc), h->at<float>(h->ws.dc), h->at<float>(h->ws.nbc))
     if (wide) { if (h->vec4) STRADS_DOTS_CAND(256, true); else STRADS_DOTS_CAND(256, false); }
     else      { if (h->vec4) STRADS_DOTS_CAND(64, true);  else STRADS_DOTS_CAND(64, false); }
 #undef STRADS_DOTS_CAND
@@ -491,8 +529,13 @@ hipError_t launch_residual_apply(strads_lasso *h, int groups)
 hipError_t launch_objective(strads_lasso *h)
 {
     double *part = h->at<double>(h->ws.objpart);
-    hipLaunchKernelGGL(k_objective_partial, dim3(kObjBlocks), dim3(256), 0, h->stream, h->at<float>(h->ws.r), h->cfg.n,
-                       h->at<float>(h->ws.beta), h->cfg.j, (double)h->cfg.lambda, part);
+    if (h->cfg.loss == STRADS_LOSS_LOGISTIC)
+        hipLaunchKernelGGL(k_objective_logistic_partial, dim3(kObjBlocks), dim3(256), 0, h->stream, h->cfg.y,
+                           h->at<float>(h->ws.r), h->cfg.n, h->at<float>(h->ws.beta), h->cfg.j,
+                           (double)h->cfg.lambda, part);
+    else
+        hipLaunchKernelGGL(k_objective_partial, dim3(kObjBlocks), dim3(256), 0, h->stream, h->at<float>(h->ws.r),
+                           h->cfg.n, h->at<float>(h->ws.beta), h->cfg.j, (double)h->cfg.lambda, part);
     hipLaunchKernelGGL(k_objective_final, dim3(1), dim3(256), 0, h->stream, part, kObjBlocks,
                        h->at<double>(h->ws.objout));
     return hipGetLastError();
@@ -508,7 +551,7 @@ hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null)
         int64_t g = (h->cfg.j + 1) / 2;
         if (g > 256 * 8) g = 256 * 8;
         const int nr = (int)((h->cfg.n / 4 + 255) / 256);
-#define STRADS_KKT_STREAM(NR) hipLaunchKernelGGL((k_kkt_stream<NR>), dim3((unsigned)g), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->cfg.j, h->at<float>(h->ws.r), h->at<float>(h->ws.beta), h->cfg.lambda, g_or_null, sc)
+#define STRADS_KKT_STREAM(NR) hipLaunchKernelGGL((k_kkt_stream<NR>), dim3((unsigned)g), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->cfg.j, dots_vector(h), h->at<float>(h->ws.beta), h->cfg.lambda, g_or_null, sc)
         if (nr <= 4) STRADS_KKT_STREAM(4);
         else if (nr <= 8) STRADS_KKT_STREAM(8);
         else if (nr <= 12) STRADS_KKT_STREAM(12);
@@ -519,10 +562,17 @@ hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null)
     int64_t gk = wide ? h->cfg.j : (h->cfg.j + 3) / 4;
     if (gk > 256 * 16) gk = 256 * 16;           // persistent: a few workgroups per compute unit
     const unsigned grid = (unsigned)gk;
-#define STRADS_KKT(TPC, V) hipLaunchKernelGGL((k_kkt<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->cfg.j, h->at<float>(h->ws.r), h->at<float>(h->ws.beta), h->cfg.lambda, g_or_null, sc)
+#define STRADS_KKT(TPC, V) hipLaunchKernelGGL((k_kkt<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->cfg.j, dots_vector(h), h->at<float>(h->ws.beta), h->cfg.lambda, g_or_null, sc)
     if (wide) { if (h->vec4) STRADS_KKT(256, true); else STRADS_KKT(256, false); }
     else      { if (h->vec4) STRADS_KKT(64, true);  else STRADS_KKT(64, false); }
 #undef STRADS_KKT
+    return hipGetLastError();
+}
+
+hipError_t launch_logistic_weights(strads_lasso *h)
+{
+    hipLaunchKernelGGL(k_logistic_weights, dim3((unsigned)((h->Npad + 255) / 256)), dim3(256), 0, h->stream, h->cfg.y,
+                       h->at<float>(h->ws.r), h->cfg.n, h->Npad, h->at<float>(h->ws.w));
     return hipGetLastError();
 }
 
@@ -535,7 +585,7 @@ hipError_t launch_clear_kkt(strads_lasso *h)
 hipError_t launch_init_state(strads_lasso *h)
 {
     hipLaunchKernelGGL(k_init_state, dim3(1024), dim3(256), 0, h->stream, h->cfg.y, h->cfg.n, h->Npad, h->cfg.j,
-                       h->cfg.c_init,
+                       h->cfg.c_init, h->cfg.loss == STRADS_LOSS_LOGISTIC ? 1 : 0,
                        h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.r),
                        h->at<uint32_t>(h->ws.hist), h->at<uint32_t>(h->ws.scalars), (int)(sizeof(RoundScalars) / 4));
     return hipGetLastError();

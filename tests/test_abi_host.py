@@ -87,7 +87,7 @@ def _cfg(**kw):
     dict(layout=1, row_idx=None, col_ptr=None),
     dict(layout=2, col_mean=None, col_scale=256), dict(layout=2, col_mean=256, col_scale=None),
     dict(layout=2, col_mean=256, col_scale=256, x=264),          # packed columns start on 16-byte boundaries
-    dict(deps=3), dict(priority=3), dict(n_shards=-1), dict(n_shards=9), dict(n_shards=8, j=5),
+    dict(deps=3), dict(priority=3), dict(loss=2), dict(loss=-1), dict(n_shards=-1), dict(n_shards=9), dict(n_shards=8, j=5),
 ])
 def test_create_rejects_invalid_arguments_without_touching_the_device(bad):
     lib = pk.load()

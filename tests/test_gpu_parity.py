@@ -32,6 +32,8 @@ def _pair(p, keep_gram=True, **kw):
     pk = _gpu()
     dev = torch.device("cuda:0")
     args = dict(lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
+    if getattr(p, "loss", "squared") != "squared":
+        args["loss"] = p.loss
     args.update(kw)
     if p.layout == "dense":
         xg = p.x.to(dev)
@@ -75,7 +77,8 @@ def _check_round(g, o, log, teacher_forced):
     decisions once they have been shown admissible."""
     if teacher_forced:
         g.set_state(o.beta, o.dbeta, o.r, o.t)
-    beta0, dbeta0, r0, t0 = o.beta.copy(), o.dbeta.copy(), o.r.copy(), o.t
+    # r0: the vector the round's dot products are taken with (the residual; the weights under the logistic loss)
+    beta0, dbeta0, r0, t0 = o.beta.copy(), o.dbeta.copy(), o.dots_vector().copy(), o.t
     gb0, gd0 = (beta0, dbeta0) if teacher_forced else [_np(a) for a in g.get_state()[:2]]
     g.round()
     lr = g.last_round(want_gram=not o.no_deps)
