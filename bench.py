@@ -32,7 +32,7 @@ HBM_PEAK_GBPS = 8000.0
 # rocprofv3 --pmc runs (FETCH_SIZE x2.00, WRITE_SIZE x1.00 after calibration against a copy kernel of
 # known size); the summary is profiles/hbm_traffic_and_mfma_counters_c2_dense_block_corr.txt.  Workloads
 # that were not measured report null.
-MEASURED_GRAM_TRAFFIC_BYTES = {"c2_dense_block_corr": 310.3e6 + 33.3e6}
+MEASURED_GRAM_TRAFFIC_BYTES = {"c2_dense_block_corr": 70.0e6 + 33.3e6}
 
 WORKLOADS = {
     # name -> (config key of synth.lasso_inputs, overrides)

@@ -241,6 +241,9 @@ int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, i
  *                   stream that can be captured (not the legacy default stream); otherwise the
  *                   library falls back to enqueueing.  On ROCm 7.2 a replay runs the shards'
  *                   branches one after the other, so it only pays for n_shards = 1.
+ *   "gram_xcd_map"  1 (default): the Gram tile kernel's workgroups are numbered so that those sharing an
+ *                   L2 (one of the eight XCDs) work on the same K-slices; 0: tile by tile.  Results are
+ *                   identical.  Dense and packed designs with static or no dependencies only.
  *   "profile_level", "profile_rounds"   see strads_lasso_stage_times
  * Returns STRADS_E_INVALID_ARG for an unknown name or a value out of range. */
 int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value);

@@ -26,6 +26,8 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
     w.dbeta = take((size_t)j * 4);
     w.r = take((size_t)npad * 4);
     w.w = take((size_t)npad * 4);
+    w.jobtab = take(layout != STRADS_LAYOUT_CSC && deps != STRADS_DEPS_DYNAMIC
+                        ? gram_job_table_entries(n, (int32_t)lpad) * 4 : 256);
     w.objpart = take((size_t)kObjBlocks * 8);
     w.objout = take(8);
     // once per shard
@@ -107,6 +109,21 @@ using namespace strads;
 
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) return STRADS_E_HIP; } while (0)
 
+// (Re)build the Gram job table of the current decomposition on the host and copy it to the workspace
+// (shared by all shards: they have the same candidate count).  The staging buffer belongs to the handle,
+// so the copy may still be in flight when this returns; callers synchronise before it is rebuilt.
+static int upload_job_table(strads_lasso *h)
+{
+    const size_t cap = gram_job_table_entries(h->cfg.n, h->Lpad);
+    if (!h->jobtab_host) h->jobtab_host = (int32_t *)malloc(cap * sizeof(int32_t));
+    if (!h->jobtab_host) return STRADS_E_INVALID_ARG;
+    const int32_t total = gram_job_table(h, h->jobtab_host);
+    if ((size_t)total > cap) return STRADS_E_INVALID_ARG;
+    HIP_TRY(hipMemcpyAsync(h->base + h->ws.jobtab, h->jobtab_host, (size_t)total * sizeof(int32_t),
+                           hipMemcpyHostToDevice, h->stream));
+    return STRADS_OK;
+}
+
 extern "C" {
 
 size_t strads_lasso_workspace_bytes(const strads_lasso_config_t *cfg)
@@ -148,6 +165,7 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->split_max = cfg->layout != STRADS_LAYOUT_CSC ? gram_split_auto(cfg->n, h->Lpad) : 1;
     h->split_user = 0;
     h->step_scale = cfg->loss == STRADS_LOSS_LOGISTIC ? 4.f : 1.f;
+    h->jobtab_on = cfg->layout != STRADS_LAYOUT_CSC && cfg->deps != STRADS_DEPS_DYNAMIC ? 1 : 0;
     h->select_cap = kSelectCapDefault;
     h->round = 0;
     h->profile_level = 0;
@@ -190,6 +208,7 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
 
     // everything below is enqueued on the caller's stream and waited for before create returns
     if (rc == STRADS_OK && launch_init_state(h) != hipSuccess) rc = STRADS_E_HIP;
+    if (rc == STRADS_OK && h->jobtab_on) rc = upload_job_table(h);
     for (int32_t s = 0; s < S && rc == STRADS_OK; ++s) {
         strads_lasso *ln = h->lanes[s];
         if (s > 0 && (hipMemsetAsync(h->base + ln->ws.hist, 0, (size_t)2 * kHistBins * 4, h->stream) != hipSuccess ||
@@ -245,6 +264,7 @@ void strads_lasso_destroy(strads_lasso_t *h)
         if (s > 0) free(ln);
     }
     if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+    free(h->jobtab_host);
     for (int i = 0; i < 2; ++i) if (h->ev_kkt[i]) (void)hipEventDestroy(h->ev_kkt[i]);
     free(h);
 }
@@ -653,6 +673,19 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
         HIP_TRY(hipStreamSynchronize(h->stream));
         drop_graphs(h);                                 // recorded launches carry the old decomposition
         for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->split_user = (int32_t)value;
+        if (h->jobtab_on) {                             // the job numbering follows the decomposition
+            const int rc = upload_job_table(h);
+            if (rc != STRADS_OK) return rc;
+            HIP_TRY(hipStreamSynchronize(h->stream));
+        }
+        return STRADS_OK;
+    }
+    if (strcmp(name, "gram_xcd_map") == 0) {
+        if (value < 0 || value > 1) return STRADS_E_INVALID_ARG;
+        if (h->cfg.layout == STRADS_LAYOUT_CSC || h->cfg.deps == STRADS_DEPS_DYNAMIC) return STRADS_E_UNSUPPORTED;
+        HIP_TRY(hipStreamSynchronize(h->stream));
+        drop_graphs(h);
+        for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->jobtab_on = (int32_t)value;
         return STRADS_OK;
     }
     if (strcmp(name, "profile_rounds") == 0) {

@@ -25,6 +25,9 @@
 // K-slices are written as fp32 partial tiles and summed in fixed order by the mask kernel, so
 // results do not depend on scheduling.
 #include "strads_internal.h"
+#include <algorithm>
+#include <utility>
+#include <vector>
 
 namespace strads {
 
@@ -487,14 +490,17 @@ __device__ __forceinline__ void gram_job(const float *__restrict__ X, int64_t N,
     }
 }
 
-// Static dependencies: the decomposition is known on the host; grid.x = number of jobs.
+// Static dependencies: the decomposition is known on the host; grid.x = number of jobs.  jobtab (may be
+// NULL) says which job a workgroup takes, see gram_job_table.
 template <int LOAD>
 __global__ __launch_bounds__(256, kGramOcc) void k_gram_tiles(const float *__restrict__ X, int64_t N,
                                                        const int32_t *__restrict__ cand, GramShape g,
-                                                       GenoCols gc, float *__restrict__ P)
+                                                       GenoCols gc, const int32_t *__restrict__ jobtab,
+                                                       float *__restrict__ P)
 {
     extern __shared__ float smem[];             // [2 stages][A panel | B panel]
-    gram_job<LOAD>(X, N, cand, g, gc, (int32_t)blockIdx.x, P, smem);
+    const int32_t job = jobtab ? jobtab[blockIdx.x] : (int32_t)blockIdx.x;
+    gram_job<LOAD>(X, N, cand, g, gc, job, P, smem);
 }
 
 // Dynamic dependencies: the Gram of the movers only.  Their number is known on the device alone,
@@ -694,6 +700,39 @@ static GramShape gram_shape(const strads_lasso *h)
     return gram_shape_for(h->cfg.n, h->L, h->split_user, h->split_max);
 }
 
+// Which job the workgroup with a given blockIdx.x takes.  Workgroups are dealt to the chip's eight XCDs
+// in turn (workgroup b runs on XCD b mod 8), each XCD has its own L2, and all jobs of one K-slice read
+// the same rows of the same few panels.  Numbering the jobs tile by tile would spread every slice over
+// all eight L2s, and every panel row would cross the fabric eight times.  Instead the jobs are put in
+// order of their first row (then by tile) and every XCD gets a consecutive eighth of that order: the
+// workgroups that share an L2 then work on the same one or two K-slices.
+size_t gram_job_table_entries(int64_t n, int32_t lpad)
+{
+    const size_t T = (size_t)(lpad / kGramTile);
+    return (T * (T - 1) / 2 + T) * (size_t)gram_split_choose(n, lpad);      // any smaller slice count fits
+}
+
+int32_t gram_job_table(const strads_lasso *h, int32_t *out)
+{
+    const GramShape g = gram_shape(h);
+    const int32_t n_off = g.T * (g.T - 1) / 2 * g.split_off;
+    const int32_t total = n_off + g.T * g.split_diag;
+    std::vector<std::pair<int64_t, int32_t>> order((size_t)total);
+    for (int32_t job = 0; job < total; ++job) {
+        const int64_t kbeg = job < n_off ? (int64_t)(job % g.split_off) * g.kchunk_off
+                                         : (int64_t)((job - n_off) % g.split_diag) * g.kchunk_diag;
+        order[(size_t)job] = std::make_pair(kbeg, job);
+    }
+    std::sort(order.begin(), order.end());
+    const int32_t kXcds = 8, base = total / kXcds, rem = total % kXcds;
+    for (int32_t b = 0; b < total; ++b) {
+        const int32_t x = b % kXcds, q = b / kXcds;
+        const int32_t first = x * base + (x < rem ? x : rem);               // jobs of the XCDs before x
+        out[b] = order[(size_t)(first + q)].second;
+    }
+    return total;
+}
+
 // Dynamic dependencies: list the movers (candidates whose tentative change is not zero) in draw
 // order and look up the decomposition of their Gram.  One workgroup of 1024 threads walks the
 // candidate positions 1024 at a time (coalesced reads, wavefront ballots for the ordered offsets).
@@ -809,7 +848,8 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
         return hipGetLastError();
     }
     const dim3 grid((unsigned)(g.T * (g.T - 1) / 2 * g.split_off + g.T * g.split_diag));
-#define STRADS_GRAM(LD) hipLaunchKernelGGL(k_gram_tiles<LD>, grid, dim3(256), lds, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), g, gc, P)
+    const int32_t *jobtab = h->jobtab_on ? reinterpret_cast<const int32_t *>(h->base + h->ws.jobtab) : nullptr;
+#define STRADS_GRAM(LD) hipLaunchKernelGGL(k_gram_tiles<LD>, grid, dim3(256), lds, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), g, gc, jobtab, P)
     if (load == kLoadGeno2) STRADS_GRAM(kLoadGeno2);
     else if (load == kLoadVec4) STRADS_GRAM(kLoadVec4);
     else STRADS_GRAM(kLoadScalar);

@@ -59,6 +59,7 @@ struct Workspace {
     // scheduler shards; everything else exists once per shard, lane_stride bytes apart.
     size_t beta, dbeta, r;
     size_t w;               // float [Npad]: logistic loss, the weights eq. (2)'s dot products are taken with
+    size_t jobtab;          // int32 [jobs]: static dependencies, dense/packed: job of each Gram workgroup
     size_t keys;            // uint32 [J]
     size_t hist;            // uint32 [2][kHistBins]
     size_t scalars;         // RoundScalars
@@ -100,6 +101,8 @@ struct strads_lasso {
     float step_scale;   // 1 / curvature of the coordinate step: 1 (squared loss), 4 (logistic loss)
     int32_t split_max;  // K-slices the workspace was sized for
     int32_t split_user; // tuning override (0 = automatic)
+    int32_t jobtab_on;  // the Gram workgroups take their jobs from ws.jobtab (tuning "gram_xcd_map", default 1)
+    int32_t *jobtab_host;   // shard 0 only: host staging copy of the table
     int32_t select_cap;
     int64_t round;
     bool vec4;          // dense columns are 16-byte aligned (N % 4 == 0 and x aligned)
@@ -134,6 +137,8 @@ namespace strads {
 int gram_split_auto(int64_t n, int32_t lpad);
 size_t gram_partial_floats(int64_t n, int32_t lpad, bool dynamic);   // floats of K-slice partial tiles to reserve
 void gram_shape_table(int64_t n, int32_t lpad, GramShape *out);      // out[t], t = 0 .. lpad/kGramTile
+size_t gram_job_table_entries(int64_t n, int32_t lpad);              // capacity needed for gram_job_table
+int32_t gram_job_table(const strads_lasso *h, int32_t *out);         // out[blockIdx.x] = job; returns the job count
 Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram, int32_t max_col_nnz, int32_t deps,
                 int32_t n_shards);
 Workspace workspace_of_lane(const Workspace &w0, int32_t lane);

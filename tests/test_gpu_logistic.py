@@ -68,8 +68,8 @@ def test_run_to_tolerance_reaches_the_scikit_learn_solution():
     g, _ = _pair(p, keep_gram=False)
     info = g.run(40000, kkt_tol=1e-4, check_every=200)
     assert info.converged == 1
-    ref = LogisticRegression(penalty="l1", solver="liblinear", C=1.0 / p.lam, fit_intercept=False, tol=1e-10,
-                             max_iter=100000)
+    ref = LogisticRegression(penalty="l1", solver="liblinear", C=1.0 / p.lam, fit_intercept=False, tol=1e-8,
+                             max_iter=1000000)
     ref.fit(p.x.numpy().T.astype(np.float64), p.y.numpy().astype(np.float64))
     _assert_close(_np(g.get_state()[0]), ref.coef_[0], 1e-3, 3e-3, "converged beta")
 

@@ -422,3 +422,22 @@ def test_pass_over_all_columns_is_timed_only_while_profiling():
     g.set_tuning("profile_level", 0)
     g.kkt()
     assert g.last_kkt_ms() == 0.0
+
+
+def test_gram_job_numbering_does_not_change_results():
+    # "gram_xcd_map": which workgroup takes which (tile, K-slice) job; also after a change of the slice count
+    p = si.make("c2_dense_block_corr", n=3000, j=4000, nnz=30, l_prime=700)
+    a, _ = _pair(p, keep_gram=True)
+    b, _ = _pair(p, keep_gram=True)
+    b.set_tuning("gram_xcd_map", 0)
+    for k in (0, 3):
+        if k:
+            a.set_tuning("gram_split_k", k)
+            b.set_tuning("gram_split_k", k)
+        for _ in range(3):
+            a.round()
+            b.round()
+            la, lb = a.last_round(want_gram=True), b.last_round(want_gram=True)
+            assert torch.equal(la["G"], lb["G"]) and torch.equal(la["kept"], lb["kept"])
+    for u, v in zip(a.get_state()[:3], b.get_state()[:3]):
+        assert torch.equal(u, v)
