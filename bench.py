@@ -295,6 +295,32 @@ def main() -> int:
                     "traffic": MEASURED_GRAM_TRAFFIC_BYTES.get(args.workload), "avg_ms": round(stage["gram_tiles"], 5), "launches": stage["rounds"],
                     "flops_per_launch": gram_flops}
 
+    # for scale: the library route for the same Step 2 (gather the candidate columns, then the vendor
+    # GEMM on the panel and its transpose, fp32), timed live on this machine
+    if roofline is not None and p.layout == "dense" and not args.no_variants:
+        torch.backends.cuda.matmul.allow_tf32 = False
+        idx = torch.randperm(p.j, device=dev)[:L]
+        reps = 10 if float(N) * L * L < 1e12 else 2
+
+        def _time(f):
+            f()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        t_gather = _time(lambda: p.x[idx])
+        panel = p.x[idx]
+        t_mm = _time(lambda: panel @ panel.T)
+        del panel
+        roofline["library_route"] = {"what": "torch gather of the candidate columns + torch.mm(panel, panel.T), fp32",
+                                     "gather_ms": round(t_gather, 5), "gemm_ms": round(t_mm, 5),
+                                     "gemm_tflops_executed": round(2.0 * N * L * L / (t_mm * 1e-3) / 1e12, 2)}
+
     cpu = None
     if args.cpu_seconds > 0:
         from oracle.oracle import OracleLasso
