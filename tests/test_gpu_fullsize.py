@@ -26,10 +26,14 @@ def _close(got, ref, rtol, atol, what):
     assert err.size == 0 or err.max() <= 0, f"{what}: worst excess {err.max():.3e} at {err.argmax()}"
 
 
-def _rounds_dense(p, rounds, gram_pairs=None, seed=0):
+def _rounds_dense(p, rounds, gram_pairs=None, seed=0, n_shards=1):
     import paper_1312_5766_amd as pk
+    logistic = getattr(p, "loss", "squared") == "logistic"
+    step = 4.0 if logistic else 1.0             # 1 / curvature of the coordinate step
+    l_prime = min(p.l_prime, p.j // n_shards)
     g = pk.StradsLasso(x=p.x, y=p.y, lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed,
-                       keep_gram=gram_pairs is not None)
+                       keep_gram=gram_pairs is not None, n_shards=n_shards, loss="logistic" if logistic else "squared")
+    y64 = _np(p.y).astype(np.float64)
     rng = np.random.default_rng(seed)
     logged = []
     for t in range(rounds):
@@ -39,7 +43,12 @@ def _rounds_dense(p, rounds, gram_pairs=None, seed=0):
         lr = g.last_round(want_gram=gram_pairs is not None)
         cand, kept_pos = _np(lr["cand"]), _np(lr["kept_pos"])
         # Step 1 from the full delta-beta vector
-        ref_cand = orc.draw(orc.priority_keys(_np(dbeta0), p.eta, p.seed, t), p.l_prime)
+        keys = orc.priority_keys(_np(dbeta0), p.eta, p.seed, t)
+        if n_shards == 1:
+            ref_cand = orc.draw(keys, l_prime)
+        else:                                   # the full draw order restricted to shard t mod S
+            full = orc.draw(keys, p.j)
+            ref_cand = full[full % n_shards == t % n_shards][:l_prime]
         assert np.array_equal(cand, ref_cand), f"candidate list differs in round {t}"
         xs = _np(p.x[torch.from_numpy(cand.astype(np.int64)).to(p.x.device)])         # (L, N) gathered columns
         L = len(cand)
@@ -66,24 +75,27 @@ def _rounds_dense(p, rounds, gram_pairs=None, seed=0):
         # eq. (2) on the gathered kept columns
         xk = xs[kept_pos].astype(np.float64)
         r0h = _np(r0).astype(np.float64)
-        rn = max(float(np.linalg.norm(r0h)), 1.0)
-        z_ref = xk @ r0h
+        # the vector the dot products are taken with: the residual, or the logistic weights
+        v0 = y64 / (1.0 + np.exp(-y64 * r0h)) if logistic else r0h
+        rn = max(float(np.linalg.norm(v0)), 1.0)
+        z_ref = xk @ v0
         _close(_np(lr["z"]), z_ref, 1e-4, 1e-6 * rn, f"dots (round {t})")
         b_old = _np(beta0)[kept].astype(np.float64)
-        a_ = z_ref + b_old
-        b_new = (np.sign(a_) * np.maximum(np.abs(a_) - p.lam, 0)).astype(np.float32).astype(np.float64)
+        a_ = step * z_ref + b_old
+        b_new = (np.sign(a_) * np.maximum(np.abs(a_) - step * p.lam, 0)).astype(np.float32).astype(np.float64)
         d_ref = b_new - b_old
-        _close(_np(lr["delta"]), d_ref, 1e-4, 2e-6 * rn, f"delta (round {t})")
+        _close(_np(lr["delta"]), d_ref, 1e-4, 2e-6 * step * rn, f"delta (round {t})")
         beta1, dbeta1, r1, _ = g.get_state()
-        _close(_np(beta1)[kept], b_new, 1e-4, 2e-6 * rn, f"beta (round {t})")
-        _close(_np(dbeta1)[kept], np.abs(d_ref), 1e-4, 2e-6 * rn, f"dbeta (round {t})")
+        _close(_np(beta1)[kept], b_new, 1e-4, 2e-6 * step * rn, f"beta (round {t})")
+        _close(_np(dbeta1)[kept], np.abs(d_ref), 1e-4, 2e-6 * step * rn, f"dbeta (round {t})")
         r_ref = r0h - d_ref @ xk
-        _close(_np(r1), r_ref, 1e-4, 2e-6 * rn, f"residual (round {t})")
+        _close(_np(r1), r_ref, 1e-4, 2e-6 * step * rn, f"residual (round {t})")
         # nothing outside the kept set moved
         mask = torch.ones(p.j, dtype=torch.bool, device=beta1.device)
         mask[torch.from_numpy(kept.astype(np.int64)).to(beta1.device)] = False
         assert torch.equal(beta1[mask], beta0[mask]) and torch.equal(dbeta1[mask], dbeta0[mask])
-        f_ref = 0.5 * float((r_ref ** 2).sum()) + p.lam * float(np.abs(_np(beta1).astype(np.float64)).sum())
+        l1 = p.lam * float(np.abs(_np(beta1).astype(np.float64)).sum())
+        f_ref = (float(np.logaddexp(0.0, y64 * r_ref).sum()) if logistic else 0.5 * float((r_ref ** 2).sum())) + l1
         assert g.objective() == pytest.approx(f_ref, rel=1e-5)
     g.close()
     return logged
@@ -99,6 +111,13 @@ def test_config2_full_size():
     p = si.make("c2_dense_block_corr", device="cuda:0")          # 10^4 x 10^5, L' = 1000 (the bench workload)
     assert (p.n, p.j, p.l_prime) == (10000, 100000, 1000)
     print("logged:", _rounds_dense(p, 4))
+
+
+def test_config2_full_size_with_scheduler_shards_and_with_the_logistic_loss():
+    _skip_without_gpu()
+    p = si.make("c2_dense_block_corr", device="cuda:0")
+    print("logged (4 shards):", _rounds_dense(p, 5, n_shards=4))
+    print("logged (logistic):", _rounds_dense(si.with_labels(p), 3))
 
 
 def test_config3_full_size():
