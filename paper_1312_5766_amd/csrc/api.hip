@@ -264,6 +264,7 @@ void strads_lasso_destroy(strads_lasso_t *h)
         if (s > 0) free(ln);
     }
     if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+    if (h->jobtab_host) (void)hipStreamSynchronize(h->stream);    // its copy to the workspace may be in flight
     free(h->jobtab_host);
     for (int i = 0; i < 2; ++i) if (h->ev_kkt[i]) (void)hipEventDestroy(h->ev_kkt[i]);
     free(h);
