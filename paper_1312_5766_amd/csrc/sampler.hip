@@ -283,29 +283,80 @@ __device__ void bitonic_sort_desc(uint64_t *a, uint32_t n /* power of two */)
     }
 }
 
+// The value that lane (l ^ J) of the wavefront holds, for J a power of two below 64, without a
+// trip through LDS: quad permutes and row mirrors of the data-parallel move for J < 16 (an
+// exclusive-or of the lane number with 7 or 15 is a mirror; two of them compose to J = 4 and 8),
+// the row and half-wave swap instructions of gfx950 for J = 16 and 32.
+template <int J> __device__ __forceinline__ uint32_t lane_xor(uint32_t v)
+{
+    constexpr int kQuadXor1 = 0xB1, kQuadXor2 = 0x4E, kQuadXor3 = 0x1B, kRowMirror = 0x140, kHalfMirror = 0x141;
+    if constexpr (J == 1) {
+        return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, kQuadXor1, 0xF, 0xF, false);
+    } else if constexpr (J == 2) {
+        return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, kQuadXor2, 0xF, 0xF, false);
+    } else if constexpr (J == 4) {
+        const int t = __builtin_amdgcn_mov_dpp((int)v, kHalfMirror, 0xF, 0xF, false);
+        return (uint32_t)__builtin_amdgcn_mov_dpp(t, kQuadXor3, 0xF, 0xF, false);
+    } else if constexpr (J == 8) {
+        const int t = __builtin_amdgcn_mov_dpp((int)v, kRowMirror, 0xF, 0xF, false);
+        return (uint32_t)__builtin_amdgcn_mov_dpp(t, kHalfMirror, 0xF, 0xF, false);
+    } else if constexpr (J == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+        return (__lane_id() & 16) ? r[0] : r[1];
+    } else {
+        static_assert(J == 32, "lane_xor: J is a power of two below 64");
+        const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+        return (__lane_id() & 32) ? r[0] : r[1];
+    }
+}
+
+// One compare-exchange step of the bitonic network (merge width k, partner distance J < 64).
+// Items are distinct or equal padding, so "take the partner's item" is one comparison.
+template <int J> __device__ __forceinline__ uint64_t bitonic_step_in_wave(uint64_t x, uint32_t i, uint32_t k)
+{
+    const uint64_t y = ((uint64_t)lane_xor<J>((uint32_t)(x >> 32)) << 32) | lane_xor<J>((uint32_t)x);
+    const bool take_max = ((i & k) == 0) == ((i & (uint32_t)J) == 0);   // lower index of a descending pair keeps the larger
+    return ((x < y) == take_max) ? y : x;
+}
+
+template <int JMAX> __device__ __forceinline__ uint64_t bitonic_merge_in_wave(uint64_t x, uint32_t i, uint32_t k)
+{
+    if constexpr (JMAX >= 32) x = bitonic_step_in_wave<32>(x, i, k);
+    if constexpr (JMAX >= 16) x = bitonic_step_in_wave<16>(x, i, k);
+    if constexpr (JMAX >= 8) x = bitonic_step_in_wave<8>(x, i, k);
+    if constexpr (JMAX >= 4) x = bitonic_step_in_wave<4>(x, i, k);
+    if constexpr (JMAX >= 2) x = bitonic_step_in_wave<2>(x, i, k);
+    return bitonic_step_in_wave<1>(x, i, k);
+}
+
 // Bitonic sort, descending, of up to 1024 items held one per thread (1024 threads): exchanges
-// with a partner less than 64 lanes away go through the wavefront's lane crossbar, the few longer
-// strides through LDS.  Returns the item that belongs at position threadIdx.x.
-__device__ uint64_t bitonic_sort_desc_1024(uint64_t x, uint64_t *xch /* 1024 items of LDS */)
+// with a partner less than 64 lanes away stay in the vector registers (lane_xor), the ten longer
+// strides go through LDS, alternating between two buffers so that one barrier per step is enough.
+// Returns the item that belongs at position threadIdx.x.
+constexpr uint32_t kRegSortLdsItems = 2048;
+__device__ uint64_t bitonic_sort_desc_1024(uint64_t x, uint64_t *xch /* kRegSortLdsItems items of LDS */)
 {
     const uint32_t i = threadIdx.x;
-    for (uint32_t k = 2; k <= 1024u; k <<= 1) {
-        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-            uint64_t y;
-            if (j < 64u) {
-                const uint32_t lo = __shfl_xor((uint32_t)x, (int)j), hi = __shfl_xor((uint32_t)(x >> 32), (int)j);
-                y = ((uint64_t)hi << 32) | lo;
-            } else {
-                xch[i] = x;
-                __syncthreads();
-                y = xch[i ^ j];
-                __syncthreads();
-            }
-            const bool desc = (i & k) == 0, lower = (i & j) == 0;
-            const bool take_max = desc == lower;          // the lower index of a descending pair keeps the larger
-            x = take_max ? (x > y ? x : y) : (x < y ? x : y);
+    x = bitonic_merge_in_wave<1>(x, i, 2);
+    x = bitonic_merge_in_wave<2>(x, i, 4);
+    x = bitonic_merge_in_wave<4>(x, i, 8);
+    x = bitonic_merge_in_wave<8>(x, i, 16);
+    x = bitonic_merge_in_wave<16>(x, i, 32);
+    x = bitonic_merge_in_wave<32>(x, i, 64);
+    uint32_t half = 0;
+    for (uint32_t k = 128; k <= 1024u; k <<= 1) {
+        for (uint32_t j = k >> 1; j >= 64u; j >>= 1) {
+            uint64_t *buf = xch + half;
+            half ^= 1024u;                                // the step after the next reuses this buffer: its
+            buf[i] = x;                                   // readers have passed the barrier in between
+            __syncthreads();
+            const uint64_t y = buf[i ^ j];
+            const bool take_max = ((i & k) == 0) == ((i & j) == 0);
+            x = ((x < y) == take_max) ? y : x;
         }
+        x = bitonic_merge_in_wave<32>(x, i, k);
     }
+    __syncthreads();                                      // callers may reuse xch at once
     return x;
 }
 
@@ -421,7 +472,7 @@ __global__ __launch_bounds__(1024) void k_finalize(RoundScalars *__restrict__ sc
 __global__ __launch_bounds__(1024) void k_sort_chunks(const uint64_t *__restrict__ sel, uint32_t L,
                                                       uint64_t *__restrict__ sorted)
 {
-    __shared__ uint64_t xch[1024];
+    __shared__ uint64_t xch[kRegSortLdsItems];
     const uint32_t i = blockIdx.x * 1024u + threadIdx.x;
     sorted[i] = bitonic_sort_desc_1024(i < L ? sel[i] : 0ull, xch);     // zeros (padding) sort last
 }
@@ -499,11 +550,11 @@ hipError_t launch_sampler(strads_lasso *h)
     hipLaunchKernelGGL(k_hist2, dim3(g), dim3(bt), 0, h->stream, keys, J, L, hist, hist + kHistBins, sc);
     const unsigned gc = (unsigned)((h->Js + 256 * kCollectPerThread - 1) / (256 * kCollectPerThread));
     hipLaunchKernelGGL(k_collect, dim3(gc), dim3(256), 0, h->stream, keys, J, S, sh, hist + kHistBins, sc, sel, bnd);
-    // LDS of the final kernel: the 1024-item exchange buffer of the register sort, or the boundary
+    // LDS of the final kernel: the two exchange buffers of the register sort, or the boundary
     // list (at most `cap` items, padded to a power of two) when that is longer.  Kept small so the
     // kernel can share a compute unit with another shard's Gram workgroups.
     const uint32_t cap = (uint32_t)h->select_cap;
-    uint32_t items = 1024u;
+    uint32_t items = kRegSortLdsItems;
     while (items < cap) items <<= 1;
     const size_t lds = (size_t)items * sizeof(uint64_t);
     hipLaunchKernelGGL(k_finalize, dim3(1), dim3(1024), lds, h->stream, sc, sel, bnd, L, (uint32_t)h->Lpad, cap, S,
