@@ -231,7 +231,7 @@ int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, i
                               int32_t *n_kept);
 
 /* Launch-shape knobs for measurement sweeps (never change results except the
- * fp32 summation order of the Gram when split_k changes):
+ * fp32 summation order of the Gram when split_k changes, and of the residual update):
  *   "gram_split_k"  0 = automatic, else the number of K-slices per Gram tile
  *   "select_cap"    boundary-list length above which the sampler's final
  *                   selection falls back to its multi-pass path (default 4096)
@@ -244,6 +244,9 @@ int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, i
  *   "gram_xcd_map"  1 (default): the Gram tile kernel's workgroups are numbered so that those sharing an
  *                   L2 (one of the eight XCDs) work on the same K-slices; 0: tile by tile.  Results are
  *                   identical.  Dense and packed designs with static or no dependencies only.
+ *   "residual_fused" 1 (default): dense designs with l_prime <= 1024 apply r -= X_B delta_B in one
+ *                   kernel; 0: always the two-stage update (partial sums per column group, then their
+ *                   sum).  The two differ in fp32 summation order only.
  *   "profile_level", "profile_rounds"   see strads_lasso_stage_times
  * Returns STRADS_E_INVALID_ARG for an unknown name or a value out of range. */
 int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value);

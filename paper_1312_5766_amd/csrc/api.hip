@@ -165,6 +165,7 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->split_max = cfg->layout != STRADS_LAYOUT_CSC ? gram_split_auto(cfg->n, h->Lpad) : 1;
     h->split_user = 0;
     h->step_scale = cfg->loss == STRADS_LOSS_LOGISTIC ? 4.f : 1.f;
+    h->residual_fused = 1;
     h->jobtab_on = cfg->layout != STRADS_LAYOUT_CSC && cfg->deps != STRADS_DEPS_DYNAMIC ? 1 : 0;
     h->select_cap = kSelectCapDefault;
     h->round = 0;
@@ -687,6 +688,13 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
         HIP_TRY(hipStreamSynchronize(h->stream));
         drop_graphs(h);
         for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->jobtab_on = (int32_t)value;
+        return STRADS_OK;
+    }
+    if (strcmp(name, "residual_fused") == 0) {
+        if (value < 0 || value > 1) return STRADS_E_INVALID_ARG;
+        HIP_TRY(hipStreamSynchronize(h->stream));
+        drop_graphs(h);
+        for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->residual_fused = (int32_t)value;
         return STRADS_OK;
     }
     if (strcmp(name, "profile_rounds") == 0) {

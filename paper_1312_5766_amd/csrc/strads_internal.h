@@ -101,6 +101,7 @@ struct strads_lasso {
     float step_scale;   // 1 / curvature of the coordinate step: 1 (squared loss), 4 (logistic loss)
     int32_t split_max;  // K-slices the workspace was sized for
     int32_t split_user; // tuning override (0 = automatic)
+    int32_t residual_fused;  // lists of at most 1024 candidates update the residual in one kernel (tuning "residual_fused", default 1)
     int32_t jobtab_on;  // the Gram workgroups take their jobs from ws.jobtab (tuning "gram_xcd_map", default 1)
     int32_t *jobtab_host;   // shard 0 only: host staging copy of the table
     int32_t select_cap;

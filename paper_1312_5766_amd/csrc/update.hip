@@ -284,6 +284,76 @@ __global__ __launch_bounds__(256) void k_residual_apply(const float *__restrict_
     r[i] -= s;
 }
 
+// The same update in one kernel, for candidate lists of at most 1024: a workgroup of 16 wavefronts
+// owns 64 rows (one per lane).  Wavefront w sums the movers w, w+16, ... of the kept list in list
+// order, the 16 sums meet in LDS in wavefront order, and the first wavefront subtracts the total
+// from r.  No partial sums leave the chip and one kernel boundary is saved, which is what a round
+// of a small design spends its time on; long lists keep the two-stage path, whose grid grows with
+// the list.
+constexpr int kFusedResidualMaxL = 1024;
+__global__ __launch_bounds__(1024) void k_residual_fused(const float *__restrict__ X, int64_t N,
+                                                         const int32_t *__restrict__ kept,
+                                                         const float *__restrict__ delta,
+                                                         RoundScalars *__restrict__ sc, float *__restrict__ r)
+{
+    __shared__ int32_t mcol[kFusedResidualMaxL];
+    __shared__ float mdel[kFusedResidualMaxL];
+    __shared__ uint32_t wcnt[16];
+    __shared__ float red[16][64];
+    __shared__ float wmax[16];
+    const int k = sc->n_kept;                   // <= candidates per round <= kFusedResidualMaxL
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float d = tid < k ? delta[tid] : 0.f;
+    const bool mv = d != 0.f;
+    const uint64_t m = __ballot(mv);
+    if (lane == 0) wcnt[wave] = (uint32_t)__popcll(m);
+    __syncthreads();
+    uint32_t before = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) { const uint32_t v = wcnt[w]; if (w < wave) before += v; tot += v; }
+    if (mv) {
+        const uint32_t p = before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+        mcol[p] = kept[tid];
+        mdel[p] = d;
+    }
+    __syncthreads();
+
+    const int64_t i = (int64_t)blockIdx.x * 64 + lane;
+    float acc = 0.f;
+    if (i < N) {
+        uint32_t q = (uint32_t)wave;
+        for (; q + 48u < tot; q += 64u) {       // four columns in flight
+            const float v0 = X[(int64_t)mcol[q] * N + i], v1 = X[(int64_t)mcol[q + 16u] * N + i];
+            const float v2 = X[(int64_t)mcol[q + 32u] * N + i], v3 = X[(int64_t)mcol[q + 48u] * N + i];
+            acc += v0 * mdel[q];
+            acc += v1 * mdel[q + 16u];
+            acc += v2 * mdel[q + 32u];
+            acc += v3 * mdel[q + 48u];
+        }
+        for (; q < tot; q += 16u) acc += X[(int64_t)mcol[q] * N + i] * mdel[q];
+    }
+    red[wave][lane] = acc;
+    if (blockIdx.x == 0) {                      // round summary for strads_lasso_round's info
+        float mx = fabsf(d);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_down(mx, off));
+        if (lane == 0) wmax[wave] = mx;
+    }
+    __syncthreads();
+    if (wave == 0 && i < N) {
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) t += red[w][lane];
+        r[i] -= t;
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        float mx = 0.f;
+        for (int w = 0; w < 16; ++w) mx = fmaxf(mx, wmax[w]);
+        sc->n_moved = (int32_t)tot;
+        sc->max_abs_delta = mx;
+    }
+}
+
 // eq. (1): 1/2 sum r_i^2 + lambda sum |beta_j|, fp64 accumulation, two fixed-order stages
 __global__ __launch_bounds__(256) void k_objective_partial(const float *__restrict__ r, int64_t N,
                                                            const float *__restrict__ beta, int64_t J, double lambda,
@@ -506,6 +576,12 @@ int residual_groups(int64_t n, int32_t l)
 hipError_t launch_residual_dense(strads_lasso *h)
 {
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    if (h->residual_fused && h->L <= kFusedResidualMaxL) {
+        hipLaunchKernelGGL(k_residual_fused, dim3((unsigned)((h->cfg.n + 63) / 64)), dim3(1024), 0, h->stream,
+                           h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc,
+                           h->at<float>(h->ws.r));
+        return hipGetLastError();
+    }
     const int G = residual_groups(h->cfg.n, h->L);
     const dim3 grid((unsigned)((h->cfg.n + 1023) / 1024), (unsigned)G);
     float *part = h->at<float>(h->ws.rpart);

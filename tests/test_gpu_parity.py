@@ -286,6 +286,31 @@ def test_reduced_configs_teacher_forced(config, kw, rounds):
     print("logged:", log)
 
 
+@pytest.mark.parametrize("fused", [1, 0])
+@pytest.mark.parametrize("kw", [
+    dict(n=2000, j=6000, nnz=40, l_prime=500),
+    dict(n=1003, j=3000, nnz=40, l_prime=1024, lam_frac=0.001, rho=0.9),     # nearly every candidate is kept and moves
+    dict(n=61, j=500, nnz=5, l_prime=90, lam_frac=0.001),                    # fewer rows than one workgroup owns
+])
+def test_residual_update_in_one_kernel_and_in_two_stages(kw, fused):
+    # lists of at most 1024 candidates take the one-kernel update unless "residual_fused" is 0
+    p = si.make("c2_dense_block_corr", **kw)
+    g, o = _pair(p)
+    g.set_tuning("residual_fused", fused)
+    log = []
+    for _ in range(5):
+        assert _check_round(g, o, log, teacher_forced=True)
+    assert g.objective() == pytest.approx(o.objective(), rel=OBJ_RTOL)
+    # the round summary comes from the same kernel(s)
+    g.set_state(o.beta, o.dbeta, o.r, o.t)
+    info = g.round(want_info=True)
+    delta = _np(g.last_round(want_gram=False)["delta"])
+    assert info.n_moved == int(np.count_nonzero(delta))
+    assert info.max_abs_delta == np.float32(np.abs(delta).max(initial=0.0))
+    if kw["l_prime"] == 1024:
+        assert info.n_moved > 200          # every wavefront of the one-kernel update has several columns
+
+
 @pytest.mark.parametrize("kw,rounds", [
     (dict(n=3000, j=20000, nnz_per_col=30, nnz=20, l_prime=600, rho=0.05), 8),
     (dict(n=257, j=900, nnz_per_col=12, nnz=8, l_prime=130, rho=0.2), 10),
