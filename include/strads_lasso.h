@@ -81,8 +81,9 @@ extern "C" {
                                         every candidate, and the list of those that would move */
 #define STRADS_STAGE_GRAM_TILES  2   /* Step 2: candidate Gram, MFMA tile kernel (K-slices) */
 #define STRADS_STAGE_GRAM_MASK   3   /* Step 2: K-slice sum and |g| < rho conflict bits */
-#define STRADS_STAGE_FILTER      4   /* Step 2: greedy choice of B_1 */
-#define STRADS_STAGE_UPDATE      5   /* eq. (2): x_j^T r for B_1, soft-threshold, bookkeeping */
+#define STRADS_STAGE_FILTER      4   /* Step 2: greedy choice of B_1 (dynamic dependencies: and its commit) */
+#define STRADS_STAGE_UPDATE      5   /* eq. (2): x_j^T r for B_1, soft-threshold, bookkeeping (dynamic
+                                        dependencies: nothing, done in the two stages named above) */
 #define STRADS_STAGE_RESIDUAL    6   /* r <- r - X_B * change */
 #define STRADS_N_STAGES          7
 

@@ -321,7 +321,7 @@ static int enqueue_round(strads_lasso *top)
     MARK(STRADS_STAGE_UPDATE);
     if (!dynamic) AFTER_PREVIOUS_ROUND();
     if (!dynamic && h->cfg.loss == STRADS_LOSS_LOGISTIC) HIP_TRY(launch_logistic_weights(h));
-    if (dynamic) HIP_TRY(launch_commit_dynamic(h));
+    if (dynamic) { /* B_1 was committed by the filter's workgroup */ }
     else if (csc) HIP_TRY(launch_dots_csc(h));
     else if (geno) HIP_TRY(launch_dots_geno(h));
     else HIP_TRY(launch_dots_dense(h));

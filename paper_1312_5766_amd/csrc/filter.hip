@@ -30,6 +30,66 @@ constexpr int kMaxWords = STRADS_MAX_L_PRIME / 64;   // mask words per row (128)
 constexpr int kFilterThreads = 1024;
 constexpr int kFilterAhead = 4;                     // chunks whose rows are in flight from memory
 
+// Dynamic dependencies: what the walk over the movers is followed by, in the same workgroup (a
+// kernel of its own would cost a launch boundary, a good part of a short round).
+struct CommitArgs {
+    int32_t on;                 // 0: plain filter (the fields below are unused)
+    int32_t L;                  // all candidates of the round
+    const float *zc, *dc, *nbc; // every candidate's x_j^T r, tentative change and tentative value
+    const int32_t *cand;        // all candidates in draw order
+    const int32_t *mpos;        // mover -> candidate position
+    float *beta, *dbeta;
+    int32_t *kept_pos, *kept;
+    float *z, *delta;
+};
+
+// Assemble B_1 = (candidates that do not move) + (movers that passed the filter), in draw order,
+// cut at the cap, and commit it: beta_j <- its tentative value, delta beta_j <- |change| (0 for a
+// kept candidate that does not move).  The 1024 threads walk the candidate positions 1024 at a
+// time.  mkept: cm.L bytes of LDS scratch.  mkept_pos[0..nmk): the walk's result, written by this
+// workgroup before a barrier.
+__device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_max, const int32_t *mkept_pos,
+                                               int32_t nmk, uint8_t *mkept, RoundScalars *__restrict__ sc)
+{
+    __shared__ uint32_t wtot[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int32_t L = cm.L;
+    const int32_t cap = p_max > 0 ? p_max : L;
+    for (int32_t a = tid; a < L; a += kFilterThreads) mkept[a] = 0;
+    __syncthreads();
+    for (int32_t i = tid; i < nmk; i += kFilterThreads) mkept[cm.mpos[mkept_pos[i]]] = 1;
+    __syncthreads();
+    uint32_t base = 0;
+    for (int32_t a0 = 0; a0 < L; a0 += kFilterThreads) {
+        const int32_t a = a0 + tid;
+        const float d = a < L ? cm.dc[a] : 0.f;
+        const bool keep = a < L && (d == 0.f || mkept[a]);
+        const uint64_t m = __ballot(keep);
+        if (lane == 0) wtot[wave] = (uint32_t)__popcll(m);
+        __syncthreads();
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) { const uint32_t v = wtot[w]; if (w < wave) before += v; total += v; }
+        const int32_t idx = (int32_t)(base + before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull)));
+        if (keep && idx < cap) {
+            const int32_t j = cm.cand[a];
+            cm.kept_pos[idx] = a;
+            cm.kept[idx] = j;
+            cm.z[idx] = cm.zc[a];
+            cm.delta[idx] = d;
+            cm.beta[j] = cm.nbc[a];
+            cm.dbeta[j] = fabsf(d);
+        }
+        base += total;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const int32_t nk = (int32_t)base < cap ? (int32_t)base : cap;
+        sc->n_kept = nk;
+        sc->updates_total += (unsigned long long)nk;
+    }
+}
+
 // IPT = words of a chunk's 64 rows handled per thread = ceil(64 * W / 1024): 1, 2, 4 or 8.
 template <int kRowWordsPerThread>
 __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__restrict__ mask, int32_t L, int32_t W,
@@ -37,19 +97,20 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
                                                            int32_t p_max, const int32_t *__restrict__ cand,
                                                            int32_t *kept_pos, int32_t *__restrict__ kept,
                                                            RoundScalars *__restrict__ sc, int32_t *__restrict__ n_out,
-                                                           int count_updates)
+                                                           int count_updates, CommitArgs cm)
 {
+    extern __shared__ uint64_t rows[];            // [2][64][W]  (row-major, all W words kept for simplicity)
     if (gdev) { L = gdev->L; W = gdev->Lpad / 64; }   // dynamic dependencies: the movers, counted on the device
     if (L <= 0) {                                      // nothing moves this round
         if (threadIdx.x == 0) *n_out = 0;
+        if (cm.on) commit_dynamic(cm, p_max, kept_pos, 0, reinterpret_cast<uint8_t *>(rows), sc);
         return;
     }
-    extern __shared__ uint64_t rows[];            // [2][64][W]  (row-major, all W words kept for simplicity)
     __shared__ uint64_t dead[kMaxWords];
     __shared__ uint64_t keptw_s;
     __shared__ int32_t nk_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int32_t cap = p_max > 0 ? p_max : L;
+    const int32_t cap = (p_max > 0 && !cm.on) ? p_max : L;   // with a commit to follow, the cap is applied there
     const int32_t chunks = (L + 63) / 64;
     const int32_t items = 64 * W;                 // words of one chunk's rows
 
@@ -164,6 +225,13 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
     // kept column ids, gathered once at the end (a global load inside the loop above would put
     // a memory round trip on the serial chain of every chunk)
     const int32_t nk = nk_s;
+    if (cm.on) {
+        // the rows are done with (every thread is past the loop's last barrier): their LDS, sized by the
+        // host for the padded candidate count (16 bytes per candidate), serves as the commit's scratch
+        if (tid == 0) *n_out = nk;
+        commit_dynamic(cm, p_max, kept_pos, nk, reinterpret_cast<uint8_t *>(rows), sc);
+        return;
+    }
     for (int32_t i = tid; i < nk; i += kFilterThreads) kept[i] = cand[kept_pos[i]];
     if (tid == 0) {
         *n_out = nk;
@@ -175,10 +243,10 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
 // device memory (they can only be smaller).
 static hipError_t launch_filter_kernel(strads_lasso *h, int32_t l, int32_t W, const GramShape *gdev, int32_t p_max,
                                        const int32_t *cand, int32_t *kept_pos, int32_t *kept, int32_t *n_out,
-                                       bool count_updates)
+                                       bool count_updates, const CommitArgs &cm)
 {
     const size_t lds = (size_t)2 * 64 * W * sizeof(uint64_t);
-#define STRADS_FILTER(IPT) hipLaunchKernelGGL(k_filter<IPT>, dim3(1), dim3(kFilterThreads), lds, h->stream, h->at<uint64_t>(h->ws.mask), l, W, gdev, p_max, cand, kept_pos, kept, h->at<RoundScalars>(h->ws.scalars), n_out, count_updates ? 1 : 0)
+#define STRADS_FILTER(IPT) hipLaunchKernelGGL(k_filter<IPT>, dim3(1), dim3(kFilterThreads), lds, h->stream, h->at<uint64_t>(h->ws.mask), l, W, gdev, p_max, cand, kept_pos, kept, h->at<RoundScalars>(h->ws.scalars), n_out, count_updates ? 1 : 0, cm)
     if (W <= 16) STRADS_FILTER(1);
     else if (W <= 32) STRADS_FILTER(2);
     else if (W <= 64) STRADS_FILTER(4);
@@ -190,18 +258,36 @@ static hipError_t launch_filter_kernel(strads_lasso *h, int32_t l, int32_t W, co
 hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates)
 {
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    CommitArgs none = {};
     return launch_filter_kernel(h, l, h->Lpad / 64, nullptr, h->cfg.p_max, h->at<int32_t>(h->ws.cand),
-                                h->at<int32_t>(h->ws.kept_pos), h->at<int32_t>(h->ws.kept), &sc->n_kept, count_updates);
+                                h->at<int32_t>(h->ws.kept_pos), h->at<int32_t>(h->ws.kept), &sc->n_kept, count_updates,
+                                none);
 }
 
 // Dynamic dependencies: the walk runs over the movers only (their conflict mask has the row
-// width of the padded mover count); the cap on |B_1| is applied when the kept set is assembled.
+// width of the padded mover count) and leaves mkept_pos, n_mkept; the same workgroup then
+// assembles and commits B_1 (kept_pos, kept, z, delta, n_kept; beta and delta beta), where the cap
+// on |B_1| is applied.
 hipError_t launch_filter_movers(strads_lasso *h)
 {
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
-    return launch_filter_kernel(h, h->L, h->Lpad / 64, h->at<GramShape>(h->ws.dshape), 0,
+    CommitArgs cm;
+    cm.on = 1;
+    cm.L = h->L;
+    cm.zc = h->at<float>(h->ws.zc);
+    cm.dc = h->at<float>(h->ws.dc);
+    cm.nbc = h->at<float>(h->ws.nbc);
+    cm.cand = h->at<int32_t>(h->ws.cand);
+    cm.mpos = h->at<int32_t>(h->ws.mpos);
+    cm.beta = h->at<float>(h->ws.beta);
+    cm.dbeta = h->at<float>(h->ws.dbeta);
+    cm.kept_pos = h->at<int32_t>(h->ws.kept_pos);
+    cm.kept = h->at<int32_t>(h->ws.kept);
+    cm.z = h->at<float>(h->ws.z);
+    cm.delta = h->at<float>(h->ws.delta);
+    return launch_filter_kernel(h, h->L, h->Lpad / 64, h->at<GramShape>(h->ws.dshape), h->cfg.p_max,
                                 h->at<int32_t>(h->ws.mcand), h->at<int32_t>(h->ws.mkept_pos),
-                                h->at<int32_t>(h->ws.kept), &sc->n_mkept, false);
+                                h->at<int32_t>(h->ws.kept), &sc->n_mkept, false, cm);
 }
 
 // No dependency check (the Shotgun scheduler of Section 5.1): B_1 is the head of the draw.

@@ -155,8 +155,8 @@ hipError_t launch_keep_all(strads_lasso *h);              // no dependency check
 // dynamic dependencies
 hipError_t launch_dots_cand(strads_lasso *h);             // x_j^T r and tentative change of every candidate
 hipError_t launch_movers(strads_lasso *h);                // mover list + Gram decomposition for it
-hipError_t launch_filter_movers(strads_lasso *h);         // greedy walk over the movers -> mkept_pos, n_mkept
-hipError_t launch_commit_dynamic(strads_lasso *h);        // B_1 = non-movers + kept movers; beta, delta beta
+hipError_t launch_filter_movers(strads_lasso *h);         // greedy walk over the movers -> mkept_pos, n_mkept; then
+                                                          // B_1 = non-movers + kept movers; beta, delta beta
 hipError_t launch_scatter_mover_gram(strads_lasso *h, float *out);   // L x L image of the mover Gram
 hipError_t launch_dots_dense(strads_lasso *h);                             // x_j^T r for the kept set + eq. (2) update
 hipError_t launch_residual_dense(strads_lasso *h);                         // r -= X_B delta_B

@@ -122,60 +122,6 @@ __global__ __launch_bounds__(256) void k_dots_cand(const float *__restrict__ X, 
     }
 }
 
-// Dynamic dependencies: assemble B_1 = (candidates that do not move) + (movers that passed the
-// filter), in draw order, cut at the cap, and commit it: beta_j <- its tentative value,
-// delta beta_j <- |change| (0 for a kept candidate that does not move).  One workgroup of 1024
-// threads walks the candidate positions 1024 at a time.
-__global__ __launch_bounds__(1024) void k_commit_dynamic(const int32_t *__restrict__ cand, int32_t L, int32_t p_max,
-                                                         const float *__restrict__ zc, const float *__restrict__ dc,
-                                                         const float *__restrict__ nbc,
-                                                         const int32_t *__restrict__ mpos,
-                                                         const int32_t *__restrict__ mkept_pos,
-                                                         RoundScalars *__restrict__ sc, float *__restrict__ beta,
-                                                         float *__restrict__ dbeta, int32_t *__restrict__ kept_pos,
-                                                         int32_t *__restrict__ kept, float *__restrict__ z,
-                                                         float *__restrict__ delta)
-{
-    __shared__ uint8_t mkept[STRADS_MAX_L_PRIME];       // 1: a mover at this position passed the filter
-    __shared__ uint32_t wtot[16];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int32_t cap = p_max > 0 ? p_max : L;
-    for (int32_t a = tid; a < L; a += 1024) mkept[a] = 0;
-    __syncthreads();
-    const int32_t nmk = sc->n_mkept;
-    for (int32_t i = tid; i < nmk; i += 1024) mkept[mpos[mkept_pos[i]]] = 1;
-    __syncthreads();
-    uint32_t base = 0;
-    for (int32_t a0 = 0; a0 < L; a0 += 1024) {
-        const int32_t a = a0 + tid;
-        const float d = a < L ? dc[a] : 0.f;
-        const bool keep = a < L && (d == 0.f || mkept[a]);
-        const uint64_t m = __ballot(keep);
-        if (lane == 0) wtot[wave] = (uint32_t)__popcll(m);
-        __syncthreads();
-        uint32_t before = 0, total = 0;
-#pragma unroll
-        for (int w = 0; w < 16; ++w) { const uint32_t v = wtot[w]; if (w < wave) before += v; total += v; }
-        const int32_t idx = (int32_t)(base + before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull)));
-        if (keep && idx < cap) {
-            const int32_t j = cand[a];
-            kept_pos[idx] = a;
-            kept[idx] = j;
-            z[idx] = zc[a];
-            delta[idx] = d;
-            beta[j] = nbc[a];
-            dbeta[j] = fabsf(d);
-        }
-        base += total;
-        __syncthreads();
-    }
-    if (tid == 0) {
-        const int32_t nk = (int32_t)base < cap ? (int32_t)base : cap;
-        sc->n_kept = nk;
-        sc->updates_total += (unsigned long long)nk;
-    }
-}
-
 // Residual update r <- r - sum_c x_{kept[c]} * delta[c], stage 1.  grid = (row tiles of 1024 rows,
 // G column groups).  Group g owns kept positions [k*g/G, k*(g+1)/G) and sums its movers
 // (delta != 0) in list order for 4 rows per thread -> part[g][i].
@@ -549,17 +495,6 @@ hipError_t launch_dots_cand(strads_lasso *h)
     if (wide) { if (h->vec4) STRADS_DOTS_CAND(256, true); else STRADS_DOTS_CAND(256, false); }
     else      { if (h->vec4) STRADS_DOTS_CAND(64, true);  else STRADS_DOTS_CAND(64, false); }
 #undef STRADS_DOTS_CAND
-    return hipGetLastError();
-}
-
-hipError_t launch_commit_dynamic(strads_lasso *h)
-{
-    hipLaunchKernelGGL(k_commit_dynamic, dim3(1), dim3(1024), 0, h->stream, h->at<int32_t>(h->ws.cand), h->L,
-                       h->cfg.p_max, h->at<float>(h->ws.zc), h->at<float>(h->ws.dc), h->at<float>(h->ws.nbc),
-                       h->at<int32_t>(h->ws.mpos), h->at<int32_t>(h->ws.mkept_pos),
-                       h->at<RoundScalars>(h->ws.scalars), h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta),
-                       h->at<int32_t>(h->ws.kept_pos), h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.z),
-                       h->at<float>(h->ws.delta));
     return hipGetLastError();
 }
 
