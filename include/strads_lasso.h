@@ -82,8 +82,8 @@ extern "C" {
 #define STRADS_STAGE_GRAM_TILES  2   /* Step 2: candidate Gram, MFMA tile kernel (K-slices) */
 #define STRADS_STAGE_GRAM_MASK   3   /* Step 2: K-slice sum and |g| < rho conflict bits */
 #define STRADS_STAGE_FILTER      4   /* Step 2: greedy choice of B_1 (dynamic dependencies: and its commit) */
-#define STRADS_STAGE_UPDATE      5   /* eq. (2): x_j^T r for B_1, soft-threshold, bookkeeping (dynamic
-                                        dependencies: nothing, done in the two stages named above) */
+#define STRADS_STAGE_UPDATE      5   /* eq. (2): x_j^T r for B_1, soft-threshold, bookkeeping (nothing with
+                                        dynamic dependencies or "dots_with_gram": done in earlier stages) */
 #define STRADS_STAGE_RESIDUAL    6   /* r <- r - X_B * change */
 #define STRADS_N_STAGES          7
 
@@ -245,6 +245,10 @@ int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, i
  *   "gram_xcd_map"  1 (default): the Gram tile kernel's workgroups are numbered so that those sharing an
  *                   L2 (one of the eight XCDs) work on the same K-slices; 0: tile by tile.  Results are
  *                   identical.  Dense and packed designs with static or no dependencies only.
+ *   "dots_with_gram" 1 (default): fp32 dense designs with l_prime <= 1024, Algorithm 1's dependency rule and
+ *                   one scheduler take x_j^T r for every candidate in extra workgroups of the Gram
+ *                   launch, and the filter's workgroup applies eq. (2) to the kept ones; 0: a kernel
+ *                   after the filter takes the products for the kept set only.  Identical results.
  *   "residual_fused" 1 (default): dense designs with l_prime <= 1024 apply r -= X_B delta_B in one
  *                   kernel; 0: always the two-stage update (partial sums per column group, then their
  *                   sum).  The two differ in fp32 summation order only.

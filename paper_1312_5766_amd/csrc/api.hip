@@ -52,9 +52,9 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
     w.mv_delta = take((size_t)lpad * 4);
     w.rpart = take((size_t)kMaxResidualGroups * npad * 4);
     const size_t dyn = deps == STRADS_DEPS_DYNAMIC ? (size_t)lpad * 4 : 256;
-    w.zc = take(dyn);
-    w.dc = take(dyn);
-    w.nbc = take(dyn);
+    w.zc = take((size_t)lpad * 4);            // every candidate's tentative update
+    w.dc = take((size_t)lpad * 4);
+    w.nbc = take((size_t)lpad * 4);
     w.mpos = take(dyn);
     w.mcand = take(dyn);
     w.mkept_pos = take(dyn);
@@ -165,6 +165,7 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->split_max = cfg->layout != STRADS_LAYOUT_CSC ? gram_split_auto(cfg->n, h->Lpad) : 1;
     h->split_user = 0;
     h->step_scale = cfg->loss == STRADS_LOSS_LOGISTIC ? 4.f : 1.f;
+    h->dots_with_gram = 1;
     h->residual_fused = 1;
     h->jobtab_on = cfg->layout != STRADS_LAYOUT_CSC && cfg->deps != STRADS_DEPS_DYNAMIC ? 1 : 0;
     h->select_cap = kSelectCapDefault;
@@ -310,18 +311,20 @@ static int enqueue_round(strads_lasso *top)
         else HIP_TRY(launch_dots_cand(h));
         HIP_TRY(launch_movers(h));
     }
+    const bool ride = dots_ride_with_gram(h);   // the candidates' x_j^T r is taken by the Gram launch
     MARK(STRADS_STAGE_GRAM_TILES);
+    if (ride && h->cfg.loss == STRADS_LOSS_LOGISTIC) HIP_TRY(launch_logistic_weights(h));
     if (!unchecked) { if (csc) HIP_TRY(launch_gram_csc(h)); else HIP_TRY(launch_gram_dense(h, 0)); }
     MARK(STRADS_STAGE_GRAM_MASK);
     if (!unchecked && !csc) HIP_TRY(launch_gram_dense(h, 1));
     MARK(STRADS_STAGE_FILTER);
     if (unchecked) HIP_TRY(launch_keep_all(h));
     else if (dynamic) HIP_TRY(launch_filter_movers(h));
-    else HIP_TRY(launch_filter(h, h->L, true));
+    else HIP_TRY(launch_filter(h, h->L, true, ride));
     MARK(STRADS_STAGE_UPDATE);
     if (!dynamic) AFTER_PREVIOUS_ROUND();
-    if (!dynamic && h->cfg.loss == STRADS_LOSS_LOGISTIC) HIP_TRY(launch_logistic_weights(h));
-    if (dynamic) { /* B_1 was committed by the filter's workgroup */ }
+    if (!dynamic && !ride && h->cfg.loss == STRADS_LOSS_LOGISTIC) HIP_TRY(launch_logistic_weights(h));
+    if (dynamic || ride) { /* B_1 was committed by the filter's workgroup */ }
     else if (csc) HIP_TRY(launch_dots_csc(h));
     else if (geno) HIP_TRY(launch_dots_geno(h));
     else HIP_TRY(launch_dots_dense(h));
@@ -646,7 +649,7 @@ int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, i
 {
     if (!h || !gram || !kept_pos || !n_kept || l < 1 || l > h->L) return STRADS_E_INVALID_ARG;
     HIP_TRY(launch_mask_from_gram(h, gram, l));
-    HIP_TRY(launch_filter(h, l, false));
+    HIP_TRY(launch_filter(h, l, false, false));
     RoundScalars sc;
     const int rs = read_scalars(h, &sc);
     if (rs != STRADS_OK) return rs;
@@ -688,6 +691,13 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
         HIP_TRY(hipStreamSynchronize(h->stream));
         drop_graphs(h);
         for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->jobtab_on = (int32_t)value;
+        return STRADS_OK;
+    }
+    if (strcmp(name, "dots_with_gram") == 0) {
+        if (value < 0 || value > 1) return STRADS_E_INVALID_ARG;
+        HIP_TRY(hipStreamSynchronize(h->stream));
+        drop_graphs(h);
+        for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->dots_with_gram = (int32_t)value;
         return STRADS_OK;
     }
     if (strcmp(name, "residual_fused") == 0) {

@@ -1,0 +1,91 @@
+// Device helpers shared by the kernels that take x_j^T r over a dense column and apply eq. (2).
+// Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace strads {
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
+    return v;                                   // lane 0 holds the sum
+}
+
+// dot product of one column with r by TPC threads (TPC = 64: one wavefront, 256: a workgroup)
+template <int TPC, bool VEC4>
+__device__ __forceinline__ float column_dot(const float *__restrict__ x, const float *__restrict__ r, int64_t N,
+                                            int t, float *red /* TPC/64 floats of LDS, TPC > 64 only */)
+{
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (VEC4) {
+        const float4 *x4 = reinterpret_cast<const float4 *>(x);
+        const float4 *r4 = reinterpret_cast<const float4 *>(r);
+        const int64_t n4 = N >> 2;
+        int64_t i = t;
+        for (; i + 3 * TPC < n4; i += 4 * TPC) {
+            const float4 a0 = x4[i], a1 = x4[i + TPC], a2 = x4[i + 2 * TPC], a3 = x4[i + 3 * TPC];
+            const float4 b0 = r4[i], b1 = r4[i + TPC], b2 = r4[i + 2 * TPC], b3 = r4[i + 3 * TPC];
+            s0 += a0.x * b0.x + a0.y * b0.y + a0.z * b0.z + a0.w * b0.w;
+            s1 += a1.x * b1.x + a1.y * b1.y + a1.z * b1.z + a1.w * b1.w;
+            s2 += a2.x * b2.x + a2.y * b2.y + a2.z * b2.z + a2.w * b2.w;
+            s3 += a3.x * b3.x + a3.y * b3.y + a3.z * b3.z + a3.w * b3.w;
+        }
+        for (; i < n4; i += TPC) {
+            const float4 a = x4[i], b = r4[i];
+            s0 += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
+        }
+    } else {
+        for (int64_t i = t; i < N; i += TPC) s0 += x[i] * r[i];
+    }
+    float s = wave_sum((s0 + s1) + (s2 + s3));
+    if (TPC > 64) {
+        if ((t & 63) == 0) red[t >> 6] = s;
+        __syncthreads();
+        s = 0.f;
+        if (t == 0) for (int w = 0; w < TPC / 64; ++w) s += red[w];
+    }
+    return s;                                   // valid in thread 0 of the group
+}
+
+__device__ __forceinline__ float soft_threshold(float a, float lambda)
+{
+    const float m = fabsf(a) - lambda;
+    return m > 0.f ? copysignf(m, a) : 0.f;
+}
+
+// The update candidate position c would make from the vector r: zc[c] = x_j^T r,
+// nbc[c] = S(zc * step + beta_j, lambda * step) (step = 1: eq. (2) as printed), dc[c] = nbc - beta_j.
+// Nothing of the solver state is written.  One group of TPC threads per candidate, 256 / TPC
+// candidates per workgroup `block`.
+struct CandDots {
+    int32_t L;                  // candidates; 0: none wanted
+    int32_t wide;               // 1: a workgroup per candidate, 0: a wavefront per candidate
+    const float *r;
+    float lambda, step;
+    const float *beta;
+    float *zc, *dc, *nbc;
+};
+
+template <int TPC, bool VEC4>
+__device__ __forceinline__ void cand_dots_block(const float *__restrict__ X, int64_t N,
+                                                const int32_t *__restrict__ cand, const CandDots &cd, int block,
+                                                float *red)
+{
+    constexpr int CPB = 256 / TPC;
+    const int c = block * CPB + (int)threadIdx.x / TPC;
+    if (c >= cd.L) return;                      // TPC = 256: whole workgroup; TPC = 64: whole wavefront
+    const int32_t j = cand[c];
+    const float s = column_dot<TPC, VEC4>(X + (int64_t)j * N, cd.r, N, (int)threadIdx.x % TPC, red);
+    if (threadIdx.x % TPC == 0) {
+        const float b = cd.beta[j];
+        const float nb = soft_threshold(s * cd.step + b, cd.lambda * cd.step);
+        cd.zc[c] = s;
+        cd.nbc[c] = nb;
+        cd.dc[c] = nb - b;
+    }
+}
+
+} // namespace strads

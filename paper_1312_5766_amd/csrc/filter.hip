@@ -33,7 +33,7 @@ constexpr int kFilterAhead = 4;                     // chunks whose rows are in 
 // Dynamic dependencies: what the walk over the movers is followed by, in the same workgroup (a
 // kernel of its own would cost a launch boundary, a good part of a short round).
 struct CommitArgs {
-    int32_t on;                 // 0: plain filter (the fields below are unused)
+    int32_t on;                 // 0: plain filter (the fields below are unused); kCommitDynamic; kCommitKept
     int32_t L;                  // all candidates of the round
     const float *zc, *dc, *nbc; // every candidate's x_j^T r, tentative change and tentative value
     const int32_t *cand;        // all candidates in draw order
@@ -42,6 +42,9 @@ struct CommitArgs {
     int32_t *kept_pos, *kept;
     float *z, *delta;
 };
+
+constexpr int32_t kCommitDynamic = 1;  // dynamic dependencies: the walk ran over the movers, see commit_dynamic
+constexpr int32_t kCommitKept = 2;     // Algorithm 1's rule: eq. (2) for the kept candidates from their tentative updates
 
 // Assemble B_1 = (candidates that do not move) + (movers that passed the filter), in draw order,
 // cut at the cap, and commit it: beta_j <- its tentative value, delta beta_j <- |change| (0 for a
@@ -103,14 +106,14 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
     if (gdev) { L = gdev->L; W = gdev->Lpad / 64; }   // dynamic dependencies: the movers, counted on the device
     if (L <= 0) {                                      // nothing moves this round
         if (threadIdx.x == 0) *n_out = 0;
-        if (cm.on) commit_dynamic(cm, p_max, kept_pos, 0, reinterpret_cast<uint8_t *>(rows), sc);
+        if (cm.on == kCommitDynamic) commit_dynamic(cm, p_max, kept_pos, 0, reinterpret_cast<uint8_t *>(rows), sc);
         return;
     }
     __shared__ uint64_t dead[kMaxWords];
     __shared__ uint64_t keptw_s;
     __shared__ int32_t nk_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int32_t cap = (p_max > 0 && !cm.on) ? p_max : L;   // with a commit to follow, the cap is applied there
+    const int32_t cap = (p_max > 0 && cm.on != kCommitDynamic) ? p_max : L;   // the movers' walk has no cap: commit_dynamic applies it
     const int32_t chunks = (L + 63) / 64;
     const int32_t items = 64 * W;                 // words of one chunk's rows
 
@@ -225,14 +228,27 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
     // kept column ids, gathered once at the end (a global load inside the loop above would put
     // a memory round trip on the serial chain of every chunk)
     const int32_t nk = nk_s;
-    if (cm.on) {
+    if (cm.on == kCommitDynamic) {
         // the rows are done with (every thread is past the loop's last barrier): their LDS, sized by the
         // host for the padded candidate count (16 bytes per candidate), serves as the commit's scratch
         if (tid == 0) *n_out = nk;
         commit_dynamic(cm, p_max, kept_pos, nk, reinterpret_cast<uint8_t *>(rows), sc);
         return;
     }
-    for (int32_t i = tid; i < nk; i += kFilterThreads) kept[i] = cand[kept_pos[i]];
+    if (cm.on == kCommitKept) {
+        // eq. (2) and Step 4 for B_1, from the update every candidate was found to make when the Gram was formed
+        for (int32_t i = tid; i < nk; i += kFilterThreads) {
+            const int32_t a = kept_pos[i], j = cand[a];
+            const float d = cm.dc[a];
+            kept[i] = j;
+            cm.z[i] = cm.zc[a];
+            cm.delta[i] = d;
+            cm.beta[j] = cm.nbc[a];
+            cm.dbeta[j] = fabsf(d);
+        }
+    } else {
+        for (int32_t i = tid; i < nk; i += kFilterThreads) kept[i] = cand[kept_pos[i]];
+    }
     if (tid == 0) {
         *n_out = nk;
         if (count_updates) sc->updates_total += (unsigned long long)nk;
@@ -255,24 +271,10 @@ static hipError_t launch_filter_kernel(strads_lasso *h, int32_t l, int32_t W, co
     return hipGetLastError();
 }
 
-hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates)
+static CommitArgs commit_args(strads_lasso *h, int32_t mode)
 {
-    RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
-    CommitArgs none = {};
-    return launch_filter_kernel(h, l, h->Lpad / 64, nullptr, h->cfg.p_max, h->at<int32_t>(h->ws.cand),
-                                h->at<int32_t>(h->ws.kept_pos), h->at<int32_t>(h->ws.kept), &sc->n_kept, count_updates,
-                                none);
-}
-
-// Dynamic dependencies: the walk runs over the movers only (their conflict mask has the row
-// width of the padded mover count) and leaves mkept_pos, n_mkept; the same workgroup then
-// assembles and commits B_1 (kept_pos, kept, z, delta, n_kept; beta and delta beta), where the cap
-// on |B_1| is applied.
-hipError_t launch_filter_movers(strads_lasso *h)
-{
-    RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     CommitArgs cm;
-    cm.on = 1;
+    cm.on = mode;
     cm.L = h->L;
     cm.zc = h->at<float>(h->ws.zc);
     cm.dc = h->at<float>(h->ws.dc);
@@ -285,9 +287,27 @@ hipError_t launch_filter_movers(strads_lasso *h)
     cm.kept = h->at<int32_t>(h->ws.kept);
     cm.z = h->at<float>(h->ws.z);
     cm.delta = h->at<float>(h->ws.delta);
+    return cm;
+}
+
+hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates, bool commit)
+{
+    RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    return launch_filter_kernel(h, l, h->Lpad / 64, nullptr, h->cfg.p_max, h->at<int32_t>(h->ws.cand),
+                                h->at<int32_t>(h->ws.kept_pos), h->at<int32_t>(h->ws.kept), &sc->n_kept, count_updates,
+                                commit_args(h, commit ? kCommitKept : 0));
+}
+
+// Dynamic dependencies: the walk runs over the movers only (their conflict mask has the row
+// width of the padded mover count) and leaves mkept_pos, n_mkept; the same workgroup then
+// assembles and commits B_1 (kept_pos, kept, z, delta, n_kept; beta and delta beta), where the cap
+// on |B_1| is applied.
+hipError_t launch_filter_movers(strads_lasso *h)
+{
+    RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     return launch_filter_kernel(h, h->L, h->Lpad / 64, h->at<GramShape>(h->ws.dshape), h->cfg.p_max,
                                 h->at<int32_t>(h->ws.mcand), h->at<int32_t>(h->ws.mkept_pos),
-                                h->at<int32_t>(h->ws.kept), &sc->n_mkept, false, cm);
+                                h->at<int32_t>(h->ws.kept), &sc->n_mkept, false, commit_args(h, kCommitDynamic));
 }
 
 // No dependency check (the Shotgun scheduler of Section 5.1): B_1 is the head of the draw.

@@ -25,6 +25,7 @@
 // K-slices are written as fp32 partial tiles and summed in fixed order by the mask kernel, so
 // results do not depend on scheduling.
 #include "strads_internal.h"
+#include "dots.h"
 #include <algorithm>
 #include <utility>
 #include <vector>
@@ -490,15 +491,29 @@ __device__ __forceinline__ void gram_job(const float *__restrict__ X, int64_t N,
     }
 }
 
-// Static dependencies: the decomposition is known on the host; grid.x = number of jobs.  jobtab (may be
-// NULL) says which job a workgroup takes, see gram_job_table.
+// Static dependencies: the decomposition is known on the host; the first n_jobs workgroups take one job
+// each.  jobtab (may be NULL) says which, see gram_job_table.
+//
+// Workgroups past n_jobs (there are some when cd.L > 0; fp32 designs only) compute every candidate's
+// x_j^T r and tentative update.  They are dispatched last, into the slots the tile jobs leave free
+// while the last of them finish, they are bound by memory where the tiles are bound by the matrix
+// cores, and they read columns the tiles have just pulled on chip: for a short candidate list this
+// hides the whole pass, and the kernel that would otherwise make it after the filter is not needed.
 template <int LOAD>
 __global__ __launch_bounds__(256, kGramOcc) void k_gram_tiles(const float *__restrict__ X, int64_t N,
                                                        const int32_t *__restrict__ cand, GramShape g,
                                                        GenoCols gc, const int32_t *__restrict__ jobtab,
-                                                       float *__restrict__ P)
+                                                       float *__restrict__ P, int32_t n_jobs, CandDots cd)
 {
     extern __shared__ float smem[];             // [2 stages][A panel | B panel]
+    if ((int32_t)blockIdx.x >= n_jobs) {
+        if constexpr (LOAD != kLoadGeno2) {
+            const int block = (int)blockIdx.x - n_jobs;
+            if (cd.wide) cand_dots_block<256, LOAD == kLoadVec4>(X, N, cand, cd, block, smem);
+            else cand_dots_block<64, LOAD == kLoadVec4>(X, N, cand, cd, block, smem);
+        }
+        return;
+    }
     const int32_t job = jobtab ? jobtab[blockIdx.x] : (int32_t)blockIdx.x;
     gram_job<LOAD>(X, N, cand, g, gc, job, P, smem);
 }
@@ -847,9 +862,16 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
 #undef STRADS_GRAM_DYN
         return hipGetLastError();
     }
-    const dim3 grid((unsigned)(g.T * (g.T - 1) / 2 * g.split_off + g.T * g.split_diag));
+    const int32_t n_jobs = g.T * (g.T - 1) / 2 * g.split_off + g.T * g.split_diag;
+    CandDots cd = {};
+    unsigned extra = 0;
+    if (dots_ride_with_gram(h)) {
+        cd = cand_dots_args(h);
+        extra = cd.wide ? (unsigned)cd.L : (unsigned)((cd.L + 3) / 4);
+    }
+    const dim3 grid((unsigned)n_jobs + extra);
     const int32_t *jobtab = h->jobtab_on ? reinterpret_cast<const int32_t *>(h->base + h->ws.jobtab) : nullptr;
-#define STRADS_GRAM(LD) hipLaunchKernelGGL(k_gram_tiles<LD>, grid, dim3(256), lds, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), g, gc, jobtab, P)
+#define STRADS_GRAM(LD) hipLaunchKernelGGL(k_gram_tiles<LD>, grid, dim3(256), lds, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), g, gc, jobtab, P, n_jobs, cd)
     if (load == kLoadGeno2) STRADS_GRAM(kLoadGeno2);
     else if (load == kLoadVec4) STRADS_GRAM(kLoadVec4);
     else STRADS_GRAM(kLoadScalar);

@@ -101,6 +101,8 @@ struct strads_lasso {
     float step_scale;   // 1 / curvature of the coordinate step: 1 (squared loss), 4 (logistic loss)
     int32_t split_max;  // K-slices the workspace was sized for
     int32_t split_user; // tuning override (0 = automatic)
+    int32_t dots_with_gram;  // short lists: every candidate's x_j^T r rides along with the Gram launch and the filter's
+                             // workgroup commits B_1 (tuning "dots_with_gram", default 1; see dots_ride_with_gram)
     int32_t residual_fused;  // lists of at most 1024 candidates update the residual in one kernel (tuning "residual_fused", default 1)
     int32_t jobtab_on;  // the Gram workgroups take their jobs from ws.jobtab (tuning "gram_xcd_map", default 1)
     int32_t *jobtab_host;   // shard 0 only: host staging copy of the table
@@ -150,7 +152,8 @@ hipError_t launch_set_next_round(strads_lasso *h, hipStream_t stream, int64_t ne
 hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys);  // stage entry
 hipError_t launch_gram_dense(strads_lasso *h, int part);  // Step 2a; part 0: K-slice tiles, part 1: sum + conflict mask
 hipError_t launch_mask_from_gram(strads_lasso *h, const float *gram, int32_t l);
-hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates);                    // Step 2b -> kept_pos, kept, n_kept
+hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates, bool commit);       // Step 2b -> kept_pos, kept, n_kept;
+                                                          // commit: and eq. (2) for B_1 from the candidates' tentative updates
 hipError_t launch_keep_all(strads_lasso *h);              // no dependency check: B_1 = first p_max candidates
 // dynamic dependencies
 hipError_t launch_dots_cand(strads_lasso *h);             // x_j^T r and tentative change of every candidate
@@ -169,6 +172,19 @@ inline const float *dots_vector(const strads_lasso *h)
 {
     return reinterpret_cast<const float *>(h->base + (h->cfg.loss == STRADS_LOSS_LOGISTIC ? h->ws.w : h->ws.r));
 }
+// Short candidate lists of an fp32 design under Algorithm 1's dependency rule, one scheduler: a round
+// is a chain of short kernels and what it costs is their number.  Then the pass that takes x_j^T r is
+// made for all candidates by extra workgroups of the Gram launch (CandDots), and the filter's
+// workgroup applies eq. (2) to the ones it kept.  (With several schedulers the Gram of a round is
+// formed before the previous round's residual exists, so its products cannot be taken there.)
+constexpr int kShortList = 1024;
+inline bool dots_ride_with_gram(const strads_lasso *h)
+{
+    return h->dots_with_gram && h->cfg.deps == STRADS_DEPS_STATIC && h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR &&
+           h->n_lanes == 1 && h->L <= kShortList;
+}
+struct CandDots;
+CandDots cand_dots_args(strads_lasso *h);                 // arguments of the candidates' tentative updates
 hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null);            // -> scalars.kkt_max_bits
 hipError_t launch_init_state(strads_lasso *h);
 hipError_t launch_init_lane(strads_lasso *h);             // zero a shard's histograms and round scalars

@@ -9,63 +9,15 @@
 // along a column, fp32 FMA, fixed-order reductions (no floating-point atomics), so results are
 // reproducible run to run.
 #include "strads_internal.h"
+#include "dots.h"
 
 namespace strads {
-
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
-    return v;                                   // lane 0 holds the sum
-}
 
 __device__ __forceinline__ double wave_sum(double v)
 {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
     return v;
-}
-
-// dot product of one column with r by TPC threads (TPC = 64: one wavefront, 256: a workgroup)
-template <int TPC, bool VEC4>
-__device__ __forceinline__ float column_dot(const float *__restrict__ x, const float *__restrict__ r, int64_t N,
-                                            int t, float *red /* TPC/64 floats of LDS, TPC > 64 only */)
-{
-    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-    if (VEC4) {
-        const float4 *x4 = reinterpret_cast<const float4 *>(x);
-        const float4 *r4 = reinterpret_cast<const float4 *>(r);
-        const int64_t n4 = N >> 2;
-        int64_t i = t;
-        for (; i + 3 * TPC < n4; i += 4 * TPC) {
-            const float4 a0 = x4[i], a1 = x4[i + TPC], a2 = x4[i + 2 * TPC], a3 = x4[i + 3 * TPC];
-            const float4 b0 = r4[i], b1 = r4[i + TPC], b2 = r4[i + 2 * TPC], b3 = r4[i + 3 * TPC];
-            s0 += a0.x * b0.x + a0.y * b0.y + a0.z * b0.z + a0.w * b0.w;
-            s1 += a1.x * b1.x + a1.y * b1.y + a1.z * b1.z + a1.w * b1.w;
-            s2 += a2.x * b2.x + a2.y * b2.y + a2.z * b2.z + a2.w * b2.w;
-            s3 += a3.x * b3.x + a3.y * b3.y + a3.z * b3.z + a3.w * b3.w;
-        }
-        for (; i < n4; i += TPC) {
-            const float4 a = x4[i], b = r4[i];
-            s0 += a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
-        }
-    } else {
-        for (int64_t i = t; i < N; i += TPC) s0 += x[i] * r[i];
-    }
-    float s = wave_sum((s0 + s1) + (s2 + s3));
-    if (TPC > 64) {
-        if ((t & 63) == 0) red[t >> 6] = s;
-        __syncthreads();
-        s = 0.f;
-        if (t == 0) for (int w = 0; w < TPC / 64; ++w) s += red[w];
-    }
-    return s;                                   // valid in thread 0 of the group
-}
-
-__device__ __forceinline__ float soft_threshold(float a, float lambda)
-{
-    const float m = fabsf(a) - lambda;
-    return m > 0.f ? copysignf(m, a) : 0.f;
 }
 
 // For every kept coordinate c < n_kept: z[c] = x_j^T r (r as it was when the round began), then
@@ -102,24 +54,10 @@ __global__ __launch_bounds__(256) void k_dots_update(const float *__restrict__ X
 // Nothing of the solver state is written: which candidates are committed is decided later.
 template <int TPC, bool VEC4>
 __global__ __launch_bounds__(256) void k_dots_cand(const float *__restrict__ X, int64_t N,
-                                                   const int32_t *__restrict__ cand, int32_t L,
-                                                   const float *__restrict__ r, float lambda, float step,
-                                                   const float *__restrict__ beta, float *__restrict__ zc,
-                                                   float *__restrict__ dc, float *__restrict__ nbc)
+                                                   const int32_t *__restrict__ cand, CandDots cd)
 {
     __shared__ float red[4];
-    constexpr int CPB = 256 / TPC;
-    const int c = blockIdx.x * CPB + threadIdx.x / TPC;
-    if (c >= L) return;
-    const int32_t j = cand[c];
-    const float s = column_dot<TPC, VEC4>(X + (int64_t)j * N, r, N, threadIdx.x % TPC, red);
-    if (threadIdx.x % TPC == 0) {
-        const float b = beta[j];
-        const float nb = soft_threshold(s * step + b, lambda * step);
-        zc[c] = s;
-        nbc[c] = nb;
-        dc[c] = nb - b;
-    }
+    cand_dots_block<TPC, VEC4>(X, N, cand, cd, (int)blockIdx.x, red);
 }
 
 // Residual update r <- r - sum_c x_{kept[c]} * delta[c], stage 1.  grid = (row tiles of 1024 rows,
@@ -487,11 +425,27 @@ hipError_t launch_dots_dense(strads_lasso *h)
     return hipGetLastError();
 }
 
+CandDots cand_dots_args(strads_lasso *h)
+{
+    CandDots cd;
+    cd.L = h->L;
+    cd.wide = h->cfg.n > 2048 ? 1 : 0;
+    cd.r = dots_vector(h);
+    cd.lambda = h->cfg.lambda;
+    cd.step = h->step_scale;
+    cd.beta = h->at<float>(h->ws.beta);
+    cd.zc = h->at<float>(h->ws.zc);
+    cd.dc = h->at<float>(h->ws.dc);
+    cd.nbc = h->at<float>(h->ws.nbc);
+    return cd;
+}
+
 hipError_t launch_dots_cand(strads_lasso *h)
 {
     const bool wide = h->cfg.n > 2048;
     const unsigned grid = wide ? (unsigned)h->L : (unsigned)((h->L + 3) / 4);
-#define STRADS_DOTS_CAND(TPC, V) hipLaunchKernelGGL((k_dots_cand<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), h->L, dots_vector(h), h->cfg.lambda, h->step_scale, h->at<float>(h->ws.beta), h->at<float>(h->ws.zc), h->at<float>(h->ws.dc), h->at<float>(h->ws.nbc))
+    const CandDots cd = cand_dots_args(h);
+#define STRADS_DOTS_CAND(TPC, V) hipLaunchKernelGGL((k_dots_cand<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), cd)
     if (wide) { if (h->vec4) STRADS_DOTS_CAND(256, true); else STRADS_DOTS_CAND(256, false); }
     else      { if (h->vec4) STRADS_DOTS_CAND(64, true);  else STRADS_DOTS_CAND(64, false); }
 #undef STRADS_DOTS_CAND

@@ -286,16 +286,18 @@ def test_reduced_configs_teacher_forced(config, kw, rounds):
     print("logged:", log)
 
 
-@pytest.mark.parametrize("fused", [1, 0])
+@pytest.mark.parametrize("ride,fused", [(1, 1), (0, 0), (1, 0), (0, 1)])
 @pytest.mark.parametrize("kw", [
     dict(n=2000, j=6000, nnz=40, l_prime=500),
     dict(n=1003, j=3000, nnz=40, l_prime=1024, lam_frac=0.001, rho=0.9),     # nearly every candidate is kept and moves
     dict(n=61, j=500, nnz=5, l_prime=90, lam_frac=0.001),                    # fewer rows than one workgroup owns
 ])
-def test_residual_update_in_one_kernel_and_in_two_stages(kw, fused):
-    # lists of at most 1024 candidates take the one-kernel update unless "residual_fused" is 0
+def test_short_list_route_and_general_route(kw, ride, fused):
+    # lists of at most 1024 candidates: x_j^T r rides along with the Gram launch and the filter commits B_1
+    # unless "dots_with_gram" is 0; the residual is updated in one kernel unless "residual_fused" is 0
     p = si.make("c2_dense_block_corr", **kw)
     g, o = _pair(p)
+    g.set_tuning("dots_with_gram", ride)
     g.set_tuning("residual_fused", fused)
     log = []
     for _ in range(5):
@@ -307,8 +309,29 @@ def test_residual_update_in_one_kernel_and_in_two_stages(kw, fused):
     delta = _np(g.last_round(want_gram=False)["delta"])
     assert info.n_moved == int(np.count_nonzero(delta))
     assert info.max_abs_delta == np.float32(np.abs(delta).max(initial=0.0))
+    assert info.n_kept == len(_np(g.last_round(want_gram=False)["kept"]))
     if kw["l_prime"] == 1024:
         assert info.n_moved > 200          # every wavefront of the one-kernel update has several columns
+
+
+@pytest.mark.parametrize("loss", ["squared", "logistic"])
+def test_products_taken_with_the_gram_are_the_same_bits(loss):
+    # "dots_with_gram" moves the pass over the candidates' columns, not its arithmetic
+    p = si.make("c2_dense_block_corr", n=3000, j=5000, nnz=40, l_prime=600, lam_frac=0.01)
+    if loss == "logistic":
+        p = si.with_labels(p)
+    a, _ = _pair(p, keep_gram=False)
+    b, _ = _pair(p, keep_gram=False)
+    b.set_tuning("dots_with_gram", 0)
+    for _ in range(6):
+        ia, ib = a.round(want_info=True), b.round(want_info=True)
+        assert (ia.n_kept, ia.n_moved, ia.max_abs_delta) == (ib.n_kept, ib.n_moved, ib.max_abs_delta)
+        la, lb = a.last_round(want_gram=False), b.last_round(want_gram=False)
+        for k in ("kept", "kept_pos", "z", "delta"):
+            assert torch.equal(la[k], lb[k]), k
+    assert ia.n_moved > 0
+    for u, v in zip(a.get_state()[:3], b.get_state()[:3]):
+        assert torch.equal(u, v)
 
 
 @pytest.mark.parametrize("kw,rounds", [
