@@ -166,6 +166,8 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->split_user = 0;
     h->step_scale = cfg->loss == STRADS_LOSS_LOGISTIC ? 4.f : 1.f;
     h->dots_with_gram = 1;
+    h->early_keys = 1;
+    h->next_keys_done = 0;
     h->residual_fused = 1;
     h->jobtab_on = cfg->layout != STRADS_LAYOUT_CSC && cfg->deps != STRADS_DEPS_DYNAMIC ? 1 : 0;
     h->select_cap = kSelectCapDefault;
@@ -288,7 +290,7 @@ static inline int mark(strads_lasso *h, int boundary)
 // with the other shards' work; whatever reads or writes the residual waits for the previous
 // round's residual update, so the updates are applied in round order (Section 3: the schedulers
 // prepare concurrently and take turns to dispatch).
-static int enqueue_round(strads_lasso *top)
+static int enqueue_round(strads_lasso *top, bool more_follows)
 {
     const int32_t S = top->n_lanes;
     strads_lasso *h = top->lanes[top->round % S];
@@ -300,7 +302,8 @@ static int enqueue_round(strads_lasso *top)
     // (the first round after a fork needs no event: the fork itself orders it after everything before)
 #define AFTER_PREVIOUS_ROUND() do { if (S > 1 && top->rounds_since_fork > 0) HIP_TRY(hipStreamWaitEvent(h->stream, prev->ev_resid, 0)); } while (0)
     MARK(STRADS_STAGE_SAMPLER);
-    HIP_TRY(launch_sampler(h));                 // the round index is the shard's device-side counter
+    HIP_TRY(launch_sampler(h, top->next_keys_done != 0));   // the round index is the shard's device-side counter
+    top->next_keys_done = 0;
     MARK(STRADS_STAGE_CAND_DOTS);
     if (dynamic) {
         // every candidate's update from the current residual; the movers; how to tile their Gram
@@ -331,7 +334,12 @@ static int enqueue_round(strads_lasso *top)
     MARK(STRADS_STAGE_RESIDUAL);
     if (csc) HIP_TRY(launch_residual_csc(h));
     else if (geno) HIP_TRY(launch_residual_geno(h));
-    else HIP_TRY(launch_residual_dense(h));
+    else {
+        // the round that follows at once gets its key pass from extra workgroups of this round's last kernel
+        bool done = false;
+        HIP_TRY(launch_residual_dense(h, more_follows && top->early_keys != 0, &done));
+        top->next_keys_done = done ? 1 : 0;
+    }
     MARK(STRADS_N_STAGES);
     if (S > 1) HIP_TRY(hipEventRecord(h->ev_resid, h->stream));
 #undef MARK
@@ -428,7 +436,7 @@ static int record_graph(strads_lasso *h, int32_t first_lane)
         return STRADS_E_UNSUPPORTED;
     }
     int rc = fork_lanes(h);
-    for (int32_t i = 0; i < h->graph_rounds && rc == STRADS_OK; ++i) rc = enqueue_round(h);
+    for (int32_t i = 0; i < h->graph_rounds && rc == STRADS_OK; ++i) rc = enqueue_round(h, i + 1 < h->graph_rounds);
     if (rc == STRADS_OK) rc = join_lanes(h);
     hipGraph_t g = nullptr;
     const hipError_t e = hipStreamEndCapture(h->stream, &g);
@@ -464,7 +472,7 @@ static int enqueue_rounds(strads_lasso *h, int64_t count, int32_t *replays)
     }
     if (count > 0) {
         int rc = fork_lanes(h);
-        for (int64_t i = 0; i < count && rc == STRADS_OK; ++i) rc = enqueue_round(h);
+        for (int64_t i = 0; i < count && rc == STRADS_OK; ++i) rc = enqueue_round(h, i + 1 < count);
         if (rc == STRADS_OK) rc = join_lanes(h);
         if (rc != STRADS_OK) return rc;
     }
@@ -475,7 +483,7 @@ int strads_lasso_round(strads_lasso_t *h, strads_round_info_t *info)
 {
     if (!h) return STRADS_E_INVALID_ARG;
     int rc = fork_lanes(h);
-    if (rc == STRADS_OK) rc = enqueue_round(h);
+    if (rc == STRADS_OK) rc = enqueue_round(h, false);
     if (rc == STRADS_OK) rc = join_lanes(h);
     if (rc != STRADS_OK) return rc;
     if (info) {
@@ -580,6 +588,11 @@ int strads_lasso_get_state(strads_lasso_t *h, float *beta, float *dbeta, float *
 int strads_lasso_set_state(strads_lasso_t *h, const float *beta, const float *dbeta, const float *r, int64_t round)
 {
     if (!h || round < 0) return STRADS_E_INVALID_ARG;
+    if (h->next_keys_done) {
+        // (only after a failed enqueue) a key pass made ahead for the round that did not follow: forget it
+        HIP_TRY(hipMemsetAsync(h->base + h->ws.hist, 0, (size_t)kHistBins * 4, h->stream));
+        h->next_keys_done = 0;
+    }
     if (beta) HIP_TRY(hipMemcpyAsync(h->base + h->ws.beta, beta, (size_t)h->cfg.j * 4, hipMemcpyDeviceToDevice, h->stream));
     if (dbeta) HIP_TRY(hipMemcpyAsync(h->base + h->ws.dbeta, dbeta, (size_t)h->cfg.j * 4, hipMemcpyDeviceToDevice, h->stream));
     if (r) HIP_TRY(hipMemcpyAsync(h->base + h->ws.r, r, (size_t)h->cfg.n * 4, hipMemcpyDeviceToDevice, h->stream));
@@ -698,6 +711,13 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
         HIP_TRY(hipStreamSynchronize(h->stream));
         drop_graphs(h);
         for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->dots_with_gram = (int32_t)value;
+        return STRADS_OK;
+    }
+    if (strcmp(name, "early_keys") == 0) {
+        if (value < 0 || value > 1) return STRADS_E_INVALID_ARG;
+        HIP_TRY(hipStreamSynchronize(h->stream));
+        drop_graphs(h);
+        h->early_keys = (int32_t)value;
         return STRADS_OK;
     }
     if (strcmp(name, "residual_fused") == 0) {

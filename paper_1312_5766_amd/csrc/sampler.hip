@@ -14,78 +14,9 @@
 // strictly above the 22-bit boundary prefix is appended to the output and the few keys on the
 // boundary prefix are resolved and everything is sorted by one workgroup in LDS.
 #include "strads_internal.h"
+#include "keys.h"
 
 namespace strads {
-
-// ---------------------------------------------------------------------------------------------
-// random numbers and the specified log2
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
-                                                        uint32_t k0, uint32_t k1)
-{
-#pragma unroll
-    for (int i = 0; i < 10; ++i) {
-        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-        const uint32_t n0 = hi1 ^ c1 ^ k0;
-        const uint32_t n2 = hi0 ^ c3 ^ k1;
-        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
-    }
-    return c0;
-}
-
-// log2 of a positive normal float: exponent by bit extraction, mantissa folded into
-// [sqrt(1/2), sqrt(2)], then e + f*Q(f) with a fixed degree-8 Q in Horner form.
-__device__ __forceinline__ float log2_spec(float x)
-{
-    const uint32_t bits = __float_as_uint(x);
-    int e = (int)(bits >> 23) - 127;
-    const uint32_t man = bits & 0x007FFFFFu;
-    uint32_t mb;
-    if (man > 0x003504F3u) { mb = man | 0x3F000000u; e += 1; }
-    else                   { mb = man | 0x3F800000u; }
-    const float f = __fsub_rn(__uint_as_float(mb), 1.0f);
-    float q = 0x1.f841dcp-4f;
-    q = __fmaf_rn(q, f, -0x1.a59aeap-3f);
-    q = __fmaf_rn(q, f, 0x1.ba8738p-3f);
-    q = __fmaf_rn(q, f, -0x1.e9d1e6p-3f);
-    q = __fmaf_rn(q, f, 0x1.26d01cp-2f);
-    q = __fmaf_rn(q, f, -0x1.715994p-2f);
-    q = __fmaf_rn(q, f, 0x1.ec73dep-2f);
-    q = __fmaf_rn(q, f, -0x1.715474p-1f);
-    q = __fmaf_rn(q, f, 0x1.715476p+0f);
-    return __fmaf_rn(f, q, (float)e);
-}
-
-// weight of coordinate j in the draw: (delta beta)^2 + eta (Theorem 1), |delta beta| + eta
-// (Algorithm 1 as printed) or 1 (the uniform draw of the comparison schedulers of Section 5.1)
-__device__ __forceinline__ float priority_weight(float dbeta, float eta, int priority)
-{
-    if (priority == STRADS_PRIORITY_LINEAR) return __fadd_rn(fabsf(dbeta), eta);
-    if (priority == STRADS_PRIORITY_UNIFORM) return 1.0f;
-    return __fmaf_rn(dbeta, dbeta, eta);
-}
-
-__device__ __forceinline__ float priority_key(float dbeta, float eta, uint64_t seed, uint64_t t, uint32_t j,
-                                              int priority)
-{
-    const float w = priority_weight(dbeta, eta, priority);
-    const uint32_t x = philox4x32_10_word0(j, 0u, (uint32_t)t, (uint32_t)(t >> 32), (uint32_t)seed,
-                                           (uint32_t)(seed >> 32));
-    const float u = __fmul_rn((float)(2u * (x >> 9) + 1u), 0x1.0p-24f);   // odd multiple of 2^-24, exact
-    const float e = -log2_spec(u);
-    const float key = __fsub_rn(log2_spec(w), log2_spec(e));
-    return __fadd_rn(key, 0.0f);                                          // -0 -> +0
-}
-
-// order-preserving map float -> uint32 (larger float <=> larger integer)
-__device__ __forceinline__ uint32_t orderable(float key)
-{
-    const uint32_t b = __float_as_uint(key);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
 
 // ---------------------------------------------------------------------------------------------
 // block helpers (256-thread workgroups unless stated)
@@ -146,27 +77,9 @@ __device__ __forceinline__ void wave_append(bool flag, uint64_t item, uint64_t *
 // ---------------------------------------------------------------------------------------------
 // pass 1: keys + histogram of the top 11 bits
 // ---------------------------------------------------------------------------------------------
-// Js coordinates of scheduler shard `shard` out of `shards`: position i of the shard is coordinate
-// j = i * shards + shard (one shard: j = i).  Keys are stored by position; the random number and
-// delta beta are those of coordinate j.
-__global__ __launch_bounds__(1024) void k_keys_hist(const float *__restrict__ dbeta, uint32_t Js, uint32_t shards,
-                                                   uint32_t shard, float eta, uint64_t seed,
-                                                   const RoundScalars *__restrict__ sc, int priority,
-                                                   uint32_t *__restrict__ keys, uint32_t *__restrict__ hist0)
+__global__ __launch_bounds__(1024) void k_keys_hist(KeysArgs ka)
 {
-    __shared__ uint32_t lh[kHistBins];
-    const uint64_t t = sc->next_round;          // advanced by the shard's last sampler kernel
-    for (int i = threadIdx.x; i < kHistBins; i += blockDim.x) lh[i] = 0;
-    __syncthreads();
-    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < Js; i += gridDim.x * blockDim.x) {
-        const uint32_t j = i * shards + shard;
-        const uint32_t ok = orderable(priority_key(dbeta[j], eta, seed, t, j, priority));
-        keys[i] = ok;
-        atomicAdd(&lh[ok >> 21], 1u);
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < kHistBins; i += blockDim.x)
-        if (lh[i]) atomicAdd(&hist0[i], lh[i]);
+    keys_hist_block(ka, blockIdx.x, gridDim.x);
 }
 
 __global__ __launch_bounds__(256) void k_keys_only(const float *__restrict__ dbeta, uint32_t J, float eta,
@@ -535,7 +448,23 @@ hipError_t launch_set_next_round(strads_lasso *h, hipStream_t stream, int64_t ne
     return hipGetLastError();
 }
 
-hipError_t launch_sampler(strads_lasso *h)
+KeysArgs keys_args(strads_lasso *h)
+{
+    KeysArgs ka;
+    ka.dbeta = h->at<float>(h->ws.dbeta);
+    ka.Js = (uint32_t)h->Js;
+    ka.shards = (uint32_t)h->n_lanes;
+    ka.shard = (uint32_t)h->lane_id;
+    ka.eta = h->cfg.eta;
+    ka.seed = h->cfg.seed;
+    ka.sc = h->at<RoundScalars>(h->ws.scalars);
+    ka.priority = h->cfg.priority;
+    ka.keys = h->at<uint32_t>(h->ws.keys);
+    ka.hist0 = h->at<uint32_t>(h->ws.hist);
+    return ka;
+}
+
+hipError_t launch_sampler(strads_lasso *h, bool keys_done)
 {
     const uint32_t J = (uint32_t)h->Js, L = (uint32_t)h->L;      // this shard's coordinates
     const uint32_t S = (uint32_t)h->n_lanes, sh = (uint32_t)h->lane_id;
@@ -545,8 +474,8 @@ hipError_t launch_sampler(strads_lasso *h)
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     uint64_t *sel = h->at<uint64_t>(h->ws.sel), *bnd = h->at<uint64_t>(h->ws.bnd);
     const int bt = sampler_threads(h->Js);
-    hipLaunchKernelGGL(k_keys_hist, dim3(g), dim3(bt), 0, h->stream, h->at<float>(h->ws.dbeta), J, S, sh, h->cfg.eta,
-                       h->cfg.seed, sc, h->cfg.priority, keys, hist);
+    // (keys_done: the previous round's last kernel has already made this pass, see launch_residual_dense)
+    if (!keys_done) hipLaunchKernelGGL(k_keys_hist, dim3(g), dim3(bt), 0, h->stream, keys_args(h));
     hipLaunchKernelGGL(k_hist2, dim3(g), dim3(bt), 0, h->stream, keys, J, L, hist, hist + kHistBins, sc);
     const unsigned gc = (unsigned)((h->Js + 256 * kCollectPerThread - 1) / (256 * kCollectPerThread));
     hipLaunchKernelGGL(k_collect, dim3(gc), dim3(256), 0, h->stream, keys, J, S, sh, hist + kHistBins, sc, sel, bnd);

@@ -103,6 +103,9 @@ struct strads_lasso {
     int32_t split_user; // tuning override (0 = automatic)
     int32_t dots_with_gram;  // short lists: every candidate's x_j^T r rides along with the Gram launch and the filter's
                              // workgroup commits B_1 (tuning "dots_with_gram", default 1; see dots_ride_with_gram)
+    int32_t early_keys;      // rounds enqueued back to back: the next round's key pass rides with the one-kernel residual
+                             // update (tuning "early_keys", default 1; one scheduler only)
+    int32_t next_keys_done;  // the round about to be enqueued already has its keys and first histogram
     int32_t residual_fused;  // lists of at most 1024 candidates update the residual in one kernel (tuning "residual_fused", default 1)
     int32_t jobtab_on;  // the Gram workgroups take their jobs from ws.jobtab (tuning "gram_xcd_map", default 1)
     int32_t *jobtab_host;   // shard 0 only: host staging copy of the table
@@ -147,7 +150,7 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
 Workspace workspace_of_lane(const Workspace &w0, int32_t lane);
 
 // Each launcher enqueues on h->stream and returns the hipError_t of the launch.
-hipError_t launch_sampler(strads_lasso *h);                                // Step 1 -> cand[L]; round index from the device
+hipError_t launch_sampler(strads_lasso *h, bool keys_done);                             // Step 1 -> cand[L]; round index from the device
 hipError_t launch_set_next_round(strads_lasso *h, hipStream_t stream, int64_t next_round);
 hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys);  // stage entry
 hipError_t launch_gram_dense(strads_lasso *h, int part);  // Step 2a; part 0: K-slice tiles, part 1: sum + conflict mask
@@ -162,7 +165,10 @@ hipError_t launch_filter_movers(strads_lasso *h);         // greedy walk over th
                                                           // B_1 = non-movers + kept movers; beta, delta beta
 hipError_t launch_scatter_mover_gram(strads_lasso *h, float *out);   // L x L image of the mover Gram
 hipError_t launch_dots_dense(strads_lasso *h);                             // x_j^T r for the kept set + eq. (2) update
-hipError_t launch_residual_dense(strads_lasso *h);                         // r -= X_B delta_B
+struct KeysArgs;
+KeysArgs keys_args(strads_lasso *h);                      // arguments of pass 1 of the selection
+// want_next_keys: another round follows at once; *next_keys_done: its key pass rode along (one scheduler, short lists)
+hipError_t launch_residual_dense(strads_lasso *h, bool want_next_keys, bool *next_keys_done);                         // r -= X_B delta_B
 hipError_t launch_residual_apply(strads_lasso *h, int groups);             // r -= sum of the groups' partial sums
 int residual_groups(int64_t n, int32_t l);
 hipError_t launch_objective(strads_lasso *h);                              // -> objout

@@ -10,6 +10,7 @@
 // reproducible run to run.
 #include "strads_internal.h"
 #include "dots.h"
+#include "keys.h"
 
 namespace strads {
 
@@ -174,12 +175,22 @@ __global__ __launch_bounds__(256) void k_residual_apply(const float *__restrict_
 // from r.  No partial sums leave the chip and one kernel boundary is saved, which is what a round
 // of a small design spends its time on; long lists keep the two-stage path, whose grid grows with
 // the list.
+//
+// Workgroups past res_blocks (there are some when another round follows at once) make the next
+// round's key pass (pass 1 of its selection): it needs delta beta as this round left it, which the
+// kernels before this one have written, and nothing this kernel writes, so the two share a launch
+// and the next round starts one kernel further on.
 constexpr int kFusedResidualMaxL = 1024;
 __global__ __launch_bounds__(1024) void k_residual_fused(const float *__restrict__ X, int64_t N,
                                                          const int32_t *__restrict__ kept,
                                                          const float *__restrict__ delta,
-                                                         RoundScalars *__restrict__ sc, float *__restrict__ r)
+                                                         RoundScalars *__restrict__ sc, float *__restrict__ r,
+                                                         uint32_t res_blocks, KeysArgs next_keys)
 {
+    if (blockIdx.x >= res_blocks) {
+        keys_hist_block(next_keys, blockIdx.x - res_blocks, gridDim.x - res_blocks);
+        return;
+    }
     __shared__ int32_t mcol[kFusedResidualMaxL];
     __shared__ float mdel[kFusedResidualMaxL];
     __shared__ uint32_t wcnt[16];
@@ -462,13 +473,21 @@ int residual_groups(int64_t n, int32_t l)
     return (int)G;
 }
 
-hipError_t launch_residual_dense(strads_lasso *h)
+hipError_t launch_residual_dense(strads_lasso *h, bool want_next_keys, bool *next_keys_done)
 {
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    *next_keys_done = false;
     if (h->residual_fused && h->L <= kFusedResidualMaxL) {
-        hipLaunchKernelGGL(k_residual_fused, dim3((unsigned)((h->cfg.n + 63) / 64)), dim3(1024), 0, h->stream,
+        const unsigned res_blocks = (unsigned)((h->cfg.n + 63) / 64);
+        unsigned key_blocks = 0;
+        if (want_next_keys && h->n_lanes == 1) {
+            key_blocks = (unsigned)((h->Js + 4095) / 4096);         // four keys per thread, at most 256 workgroups
+            if (key_blocks > 256u) key_blocks = 256u;
+            *next_keys_done = true;
+        }
+        hipLaunchKernelGGL(k_residual_fused, dim3(res_blocks + key_blocks), dim3(1024), 0, h->stream,
                            h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc,
-                           h->at<float>(h->ws.r));
+                           h->at<float>(h->ws.r), res_blocks, keys_args(h));
         return hipGetLastError();
     }
     const int G = residual_groups(h->cfg.n, h->L);
