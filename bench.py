@@ -31,8 +31,9 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the Gram tile kernel (read + written), measured offline with two
 # rocprofv3 --pmc runs (FETCH_SIZE x2.00, WRITE_SIZE x1.00 after calibration against a copy kernel of
 # known size); the summary is profiles/hbm_traffic_and_mfma_counters_c2_dense_block_corr.txt.  Workloads
-# that were not measured report null.
-MEASURED_GRAM_TRAFFIC_BYTES = {"c2_dense_block_corr": 70.0e6 + 33.3e6}
+# that were not measured report null.  Two figures: the launch as the default route makes it for a short
+# candidate list (it also carries every candidate's x_j^T r), and the tiles alone.
+MEASURED_GRAM_TRAFFIC_BYTES = {"c2_dense_block_corr": {"with_dots": 110.8e6 + 33.4e6, "tiles_only": 70.0e6 + 33.3e6}}
 
 WORKLOADS = {
     # name -> (config key of synth.lasso_inputs, overrides)
@@ -302,10 +303,16 @@ def main() -> int:
     if (args.profile_level and stage["rounds"] > 0 and stage["gram_tiles"] > 0 and p.layout in ("dense", "geno2")
             and args.deps == "static"):
         ach = gram_flops / (stage["gram_tiles"] * 1e-3) / 1e12
+        # does the launch carry the candidates' dot products?  (the library's rule, see "dots_with_gram")
+        rides = (p.layout == "dense" and args.shards <= 1 and p.l_prime <= 1024
+                 and "dots_with_gram=0" not in [t.replace(" ", "") for t in args.tune])
+        traffic = MEASURED_GRAM_TRAFFIC_BYTES.get(args.workload)
         roofline = {"bound": "mfma", "kernel": "k_gram_tiles", "achieved": round(ach, 3),
                     "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_FP32_PEAK_TFLOPS, 4),
-                    "traffic": MEASURED_GRAM_TRAFFIC_BYTES.get(args.workload), "avg_ms": round(stage["gram_tiles"], 5), "launches": stage["rounds"],
-                    "flops_per_launch": gram_flops}
+                    "traffic": traffic["with_dots" if rides else "tiles_only"] if traffic else None,
+                    "avg_ms": round(stage["gram_tiles"], 5), "launches": stage["rounds"],
+                    "flops_per_launch": gram_flops,
+                    "launch_also_carries": "x_j^T r of every candidate (4*N*L' bytes)" if rides else None}
 
     # for scale: the library route for the same Step 2 (gather the candidate columns, then the vendor
     # GEMM on the panel and its transpose, fp32), timed live on this machine
