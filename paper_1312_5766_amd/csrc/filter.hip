@@ -5,14 +5,16 @@
 // The walk is sequential in the kept set, so the work is arranged to keep the serial chain short.
 // One workgroup of 1024 threads takes the candidates 64 at a time (a "chunk").  `dead` (one bit
 // per candidate, in LDS) marks candidates that conflict with something already kept.
-//   * The chunk's 64 conflict rows (words at or right of the chunk's own word) are staged in LDS.
-//     The mask was written by workgroups all over the chip, so its first read by this workgroup
-//     comes from HBM, about a microsecond away, while a chunk is decided in a fraction of that:
-//     the rows are therefore fetched into registers kFilterAhead chunks ahead of their use.
+//   * The chunk's 64 conflict rows (words at or right of the chunk's own word) live in registers,
+//     spread over the threads.  The mask was written by workgroups all over the chip, so its first
+//     read by this workgroup comes from HBM, about a microsecond away, while a chunk is decided in
+//     a fraction of that: the rows are therefore fetched kFilterAhead chunks ahead of their use.
+//     Only the chunk's 64x64 diagonal block goes to LDS, for wavefront 0.
 //   * Wavefront 0 decides the chunk: candidates that are alive and have no conflict with another
 //     alive candidate of the chunk are kept at once; only the few with an in-chunk conflict are
-//     walked one by one (scalar bit operations on the 64x64 diagonal block).
-//   * All threads then OR the rows of the newly kept candidates into `dead` for later chunks.
+//     walked one by one (scalar bit operations on the diagonal block).
+//   * All threads then OR the words they hold of the newly kept candidates' rows into `dead` for
+//     later chunks.
 // Only bits (a, b) with b in a's 128-tile or right of it are read, matching what the Gram
 // kernel writes.  Bit-exact: the result depends on the conflict bits only.
 #include "strads_internal.h"
@@ -49,11 +51,11 @@ constexpr int32_t kCommitKept = 2;     // Algorithm 1's rule: eq. (2) for the ke
 // Assemble B_1 = (candidates that do not move) + (movers that passed the filter), in draw order,
 // cut at the cap, and commit it: beta_j <- its tentative value, delta beta_j <- |change| (0 for a
 // kept candidate that does not move).  The 1024 threads walk the candidate positions 1024 at a
-// time.  mkept: cm.L bytes of LDS scratch.  mkept_pos[0..nmk): the walk's result, written by this
-// workgroup before a barrier.
+// time.  mkept_pos[0..nmk): the walk's result, written by this workgroup before a barrier.
 __device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_max, const int32_t *mkept_pos,
-                                               int32_t nmk, uint8_t *mkept, RoundScalars *__restrict__ sc)
+                                               int32_t nmk, RoundScalars *__restrict__ sc)
 {
+    __shared__ uint8_t mkept[STRADS_MAX_L_PRIME];       // 1: a mover at this position passed the filter
     __shared__ uint32_t wtot[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int32_t L = cm.L;
@@ -102,13 +104,13 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
                                                            RoundScalars *__restrict__ sc, int32_t *__restrict__ n_out,
                                                            int count_updates, CommitArgs cm)
 {
-    extern __shared__ uint64_t rows[];            // [2][64][W]  (row-major, all W words kept for simplicity)
     if (gdev) { L = gdev->L; W = gdev->Lpad / 64; }   // dynamic dependencies: the movers, counted on the device
     if (L <= 0) {                                      // nothing moves this round
         if (threadIdx.x == 0) *n_out = 0;
-        if (cm.on == kCommitDynamic) commit_dynamic(cm, p_max, kept_pos, 0, reinterpret_cast<uint8_t *>(rows), sc);
+        if (cm.on == kCommitDynamic) commit_dynamic(cm, p_max, kept_pos, 0, sc);
         return;
     }
+    __shared__ uint64_t diag[2][64];              // word c of chunk c's rows, chunks alternating
     __shared__ uint64_t dead[kMaxWords];
     __shared__ uint64_t keptw_s;
     __shared__ int32_t nk_s;
@@ -139,34 +141,31 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
             dst[q] = (c < chunks && w >= c && a < L) ? mask[(int64_t)a * W + w] : 0ull;
         }
     };
-    auto stash = [&](int buf, const uint64_t (&src)[kRowWordsPerThread]) {
+    // the diagonal block of chunk c: every row of the chunk has exactly one holder of its word c
+    auto put_diag = [&](int32_t c, const uint64_t (&src)[kRowWordsPerThread]) {
 #pragma unroll
-        for (int q = 0; q < kRowWordsPerThread; ++q) {
-            const int32_t it = tid + q * kFilterThreads;
-            if (it < items) rows[(size_t)buf * items + it] = src[q];
-        }
+        for (int q = 0; q < kRowWordsPerThread; ++q)
+            if (iword[q] == c) diag[c & 1][irow[q]] = src[q];
     };
 #pragma unroll
     for (int d = 0; d < kFilterAhead; ++d) fetch(d, pre[d]);
-    stash(0, pre[0]);
+    put_diag(0, pre[0]);
     __syncthreads();
 
-    // one chunk; `mine` is the (now free) register set chunk c waited in, `next` holds chunk c+1.
+    // one chunk; `mine` is the register set that holds chunk c, `next` holds chunk c+1.
     // Returns true when the cap on the kept set has been reached.
     auto step = [&](int32_t c, uint64_t (&mine)[kRowWordsPerThread], const uint64_t (&next)[kRowWordsPerThread]) -> bool {
-        const uint64_t *rb = rows + (size_t)(c & 1) * items;
-        fetch(c + kFilterAhead, mine);            // in flight while the next chunks are decided
         if (wave == 0) {
             const int32_t nk0 = nk_s;
             int32_t nk = nk0;
             const uint64_t cur = dead[c];
             const int32_t nvalid = L - c * 64;
             uint64_t alive = ~cur & (nvalid >= 64 ? ~0ull : ((1ull << nvalid) - 1ull));
-            const uint64_t diag = rb[lane * W + c];
+            const uint64_t dg = diag[c & 1][lane];
             uint64_t keptw = 0;
             if (nk < cap) {
                 // lanes whose row meets another alive candidate of this chunk need the serial walk
-                const uint64_t tangled = __ballot((diag & alive) != 0) & alive;
+                const uint64_t tangled = __ballot((dg & alive) != 0) & alive;
                 const uint64_t freeb = alive & ~tangled;
                 if (tangled == 0 && nk + __popcll(freeb) <= cap) {
                     keptw = freeb;
@@ -188,7 +187,7 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
                         keptw |= 1ull << l;
                         ++nk;
                         todo &= ~(1ull << l);
-                        todo &= ~readlane64(diag, l);
+                        todo &= ~readlane64(dg, l);
                     }
                 }
             }
@@ -207,12 +206,13 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
             for (int q = 0; q < kRowWordsPerThread; ++q) {
                 const int32_t w = iword[q];
                 if (w > c && ((keptw >> irow[q]) & 1ull)) {
-                    const uint64_t v = rb[tid + q * kFilterThreads];
+                    const uint64_t v = mine[q];
                     if (v) atomicOr((unsigned long long *)&dead[w], (unsigned long long)v);
                 }
             }
         }
-        if (c + 1 < chunks) stash((c + 1) & 1, next);
+        if (c + 1 < chunks) put_diag(c + 1, next);
+        fetch(c + kFilterAhead, mine);            // chunk c is done with its registers; in flight for the next chunks
         __syncthreads();
         return full;
     };
@@ -229,10 +229,8 @@ __global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__res
     // a memory round trip on the serial chain of every chunk)
     const int32_t nk = nk_s;
     if (cm.on == kCommitDynamic) {
-        // the rows are done with (every thread is past the loop's last barrier): their LDS, sized by the
-        // host for the padded candidate count (16 bytes per candidate), serves as the commit's scratch
         if (tid == 0) *n_out = nk;
-        commit_dynamic(cm, p_max, kept_pos, nk, reinterpret_cast<uint8_t *>(rows), sc);
+        commit_dynamic(cm, p_max, kept_pos, nk, sc);
         return;
     }
     if (cm.on == kCommitKept) {
@@ -261,8 +259,7 @@ static hipError_t launch_filter_kernel(strads_lasso *h, int32_t l, int32_t W, co
                                        const int32_t *cand, int32_t *kept_pos, int32_t *kept, int32_t *n_out,
                                        bool count_updates, const CommitArgs &cm)
 {
-    const size_t lds = (size_t)2 * 64 * W * sizeof(uint64_t);
-#define STRADS_FILTER(IPT) hipLaunchKernelGGL(k_filter<IPT>, dim3(1), dim3(kFilterThreads), lds, h->stream, h->at<uint64_t>(h->ws.mask), l, W, gdev, p_max, cand, kept_pos, kept, h->at<RoundScalars>(h->ws.scalars), n_out, count_updates ? 1 : 0, cm)
+#define STRADS_FILTER(IPT) hipLaunchKernelGGL(k_filter<IPT>, dim3(1), dim3(kFilterThreads), 0, h->stream, h->at<uint64_t>(h->ws.mask), l, W, gdev, p_max, cand, kept_pos, kept, h->at<RoundScalars>(h->ws.scalars), n_out, count_updates ? 1 : 0, cm)
     if (W <= 16) STRADS_FILTER(1);
     else if (W <= 32) STRADS_FILTER(2);
     else if (W <= 64) STRADS_FILTER(4);
@@ -334,14 +331,6 @@ hipError_t launch_keep_all(strads_lasso *h)
     return hipGetLastError();
 }
 
-hipError_t filter_prepare()
-{
-    const int lds = 2 * 64 * kMaxWords * (int)sizeof(uint64_t);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_filter<1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_filter<2>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_filter<4>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_filter<8>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    return e;
-}
+hipError_t filter_prepare() { return hipSuccess; }   // static LDS only
 
 } // namespace strads
