@@ -29,8 +29,8 @@ __device__ __forceinline__ uint64_t readlane64(uint64_t v, int l)
 }
 
 constexpr int kMaxWords = STRADS_MAX_L_PRIME / 64;   // mask words per row (128)
-constexpr int kFilterThreads = 1024;
-constexpr int kFilterAhead = 4;                     // chunks whose rows are in flight from memory
+constexpr int kFilterMaxThreads = 576;              // wavefront 0 decides, four or eight wavefronts hold the conflict rows
+constexpr int kFilterMaxWaves = kFilterMaxThreads / 64;
 
 // Dynamic dependencies: what the walk over the movers is followed by, in the same workgroup (a
 // kernel of its own would cost a launch boundary, a good part of a short round).
@@ -50,22 +50,23 @@ constexpr int32_t kCommitKept = 2;     // Algorithm 1's rule: eq. (2) for the ke
 
 // Assemble B_1 = (candidates that do not move) + (movers that passed the filter), in draw order,
 // cut at the cap, and commit it: beta_j <- its tentative value, delta beta_j <- |change| (0 for a
-// kept candidate that does not move).  The 1024 threads walk the candidate positions 1024 at a
+// kept candidate that does not move).  The workgroup walks the candidate positions blockDim.x at a
 // time.  mkept_pos[0..nmk): the walk's result, written by this workgroup before a barrier.
 __device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_max, const int32_t *mkept_pos,
                                                int32_t nmk, RoundScalars *__restrict__ sc)
 {
     __shared__ uint8_t mkept[STRADS_MAX_L_PRIME];       // 1: a mover at this position passed the filter
-    __shared__ uint32_t wtot[16];
+    __shared__ uint32_t wtot[kFilterMaxWaves];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nthreads = blockDim.x, nwaves = nthreads >> 6;
     const int32_t L = cm.L;
     const int32_t cap = p_max > 0 ? p_max : L;
-    for (int32_t a = tid; a < L; a += kFilterThreads) mkept[a] = 0;
+    for (int32_t a = tid; a < L; a += nthreads) mkept[a] = 0;
     __syncthreads();
-    for (int32_t i = tid; i < nmk; i += kFilterThreads) mkept[cm.mpos[mkept_pos[i]]] = 1;
+    for (int32_t i = tid; i < nmk; i += nthreads) mkept[cm.mpos[mkept_pos[i]]] = 1;
     __syncthreads();
     uint32_t base = 0;
-    for (int32_t a0 = 0; a0 < L; a0 += kFilterThreads) {
+    for (int32_t a0 = 0; a0 < L; a0 += nthreads) {
         const int32_t a = a0 + tid;
         const float d = a < L ? cm.dc[a] : 0.f;
         const bool keep = a < L && (d == 0.f || mkept[a]);
@@ -74,7 +75,7 @@ __device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_m
         __syncthreads();
         uint32_t before = 0, total = 0;
 #pragma unroll
-        for (int w = 0; w < 16; ++w) { const uint32_t v = wtot[w]; if (w < wave) before += v; total += v; }
+        for (int w = 0; w < nwaves; ++w) { const uint32_t v = wtot[w]; if (w < wave) before += v; total += v; }
         const int32_t idx = (int32_t)(base + before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull)));
         if (keep && idx < cap) {
             const int32_t j = cm.cand[a];
@@ -95,162 +96,223 @@ __device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_m
     }
 }
 
-// IPT = words of a chunk's 64 rows handled per thread = ceil(64 * W / 1024): 1, 2, 4 or 8.
-template <int kRowWordsPerThread>
-__global__ __launch_bounds__(kFilterThreads) void k_filter(const uint64_t *__restrict__ mask, int32_t L, int32_t W,
+#ifdef STRADS_FILTER_TIMING
+// lab builds only: shader-clock stamps of wavefront 0 (start, after the first loads, after every chunk, end)
+__device__ unsigned long long g_filter_stamps[160];
+#define STRADS_STAMP(i) do { if (threadIdx.x == 0) g_filter_stamps[(i)] = clock64(); } while (0)
+#else
+#define STRADS_STAMP(i) do { } while (0)
+#endif
+
+// TPR = holder threads per row of a chunk (4; 8 for rows of more than 64 words), IPT = words of a row per
+// holder thread = ceil(W / TPR): 4, 8 or 16.  A = chunks whose words a thread has in registers or on
+// their way there (chunk c waits in set c mod A).
+//
+// The workgroup is five (nine) wavefronts, one to three per SIMD: with sixteen the chunk loop was bound
+// by instruction issue, four wavefronts taking turns on every SIMD for a few dozen instructions each.
+// Roles, one barrier per chunk c:
+//   wavefront 0 decides chunk c.  The dead bits of the chunk are dead[c]: what the rows kept in chunks
+//     <= c-2 do to word c was ORed in by the holders, what the rows kept in chunk c-1 do to it by
+//     wavefront 0 itself when it decided c-1 (its lanes hold word c of those rows; LDS operations of
+//     one wavefront complete in order).  Lane l loads words c and c+1 of row 64c + l itself, A chunks
+//     early, so a chunk costs it one LDS round trip and a few dozen instructions, which is what the
+//     whole walk is bound by: a single wavefront issues an instruction every four to five cycles.
+//   holders (the other wavefronts; TPR threads per row of a chunk, thread j of a row owning words j, j+TPR, ...):
+//     OR the words they hold of the rows kept in chunk c-1 into dead[w], w > c, and refill those
+//     registers with chunk c-1+A.
+// Each role runs its own loop (same trip count, same barriers), every load in it is unconditional,
+// from an address clamped into the mask, and sits at a fixed place of the unrolled body: only then
+// does the compiler wait for the load it needs rather than for all outstanding ones, which would put
+// a memory round trip into every chunk.  Nothing is stored to global memory inside the loop for the
+// same reason.  Rows at or past L and words at or right of a row's diagonal word are written by the
+// mask kernel for every row below Lpad; words left of the diagonal are never used.
+template <int IPT, int A, int TPR>
+__global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__restrict__ mask, int32_t L, int32_t W,
                                                            const GramShape *__restrict__ gdev,
                                                            int32_t p_max, const int32_t *__restrict__ cand,
                                                            int32_t *kept_pos, int32_t *__restrict__ kept,
                                                            RoundScalars *__restrict__ sc, int32_t *__restrict__ n_out,
                                                            int count_updates, CommitArgs cm)
 {
+    STRADS_STAMP(0);
     if (gdev) { L = gdev->L; W = gdev->Lpad / 64; }   // dynamic dependencies: the movers, counted on the device
     if (L <= 0) {                                      // nothing moves this round
         if (threadIdx.x == 0) *n_out = 0;
         if (cm.on == kCommitDynamic) commit_dynamic(cm, p_max, kept_pos, 0, sc);
         return;
     }
-    __shared__ uint64_t diag[2][64];              // word c of chunk c's rows, chunks alternating
     __shared__ uint64_t dead[kMaxWords];
-    __shared__ uint64_t keptw_s;
-    __shared__ int32_t nk_s;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ uint64_t keptw_all[kMaxWords];     // [c]: the candidates kept in chunk c
+    __shared__ int32_t nkb[kMaxWords + 1];        // [c]: kept before chunk c.  (Positions go to global memory
+                                                  // after the walk.)
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int32_t cap = (p_max > 0 && cm.on != kCommitDynamic) ? p_max : L;   // the movers' walk has no cap: commit_dynamic applies it
     const int32_t chunks = (L + 63) / 64;
-    const int32_t items = 64 * W;                 // words of one chunk's rows
+    const int64_t chunk_stride = (int64_t)64 * W; // words from a chunk's rows to the next chunk's
+    const int32_t c_max = W - 1;                  // chunk index up to which a chunk's rows lie inside the mask (chunks <= W)
 
-    for (int i = tid; i < W; i += kFilterThreads) dead[i] = 0;
-    if (tid == 0) nk_s = 0;
-
-    // this thread's share of a chunk's 64 x W words: the (row, word) of item tid + q*1024 does not
-    // depend on the chunk, so the divisions are done once
-    int16_t irow[kRowWordsPerThread], iword[kRowWordsPerThread];
-#pragma unroll
-    for (int q = 0; q < kRowWordsPerThread; ++q) {
-        const int32_t it = tid + q * kFilterThreads;
-        const int32_t rw = it / W;
-        irow[q] = (int16_t)rw;
-        iword[q] = it < items ? (int16_t)(it - rw * W) : (int16_t)-1;     // -1: no such item
-    }
-    // register sets of the chunks in flight: chunk c waits in set c % kFilterAhead
-    uint64_t pre[kFilterAhead][kRowWordsPerThread];
-    auto fetch = [&](int32_t c, uint64_t (&dst)[kRowWordsPerThread]) {
-#pragma unroll
-        for (int q = 0; q < kRowWordsPerThread; ++q) {
-            const int32_t a = c * 64 + irow[q], w = iword[q];
-            dst[q] = (c < chunks && w >= c && a < L) ? mask[(int64_t)a * W + w] : 0ull;
-        }
-    };
-    // the diagonal block of chunk c: every row of the chunk has exactly one holder of its word c
-    auto put_diag = [&](int32_t c, const uint64_t (&src)[kRowWordsPerThread]) {
-#pragma unroll
-        for (int q = 0; q < kRowWordsPerThread; ++q)
-            if (iword[q] == c) diag[c & 1][irow[q]] = src[q];
-    };
-#pragma unroll
-    for (int d = 0; d < kFilterAhead; ++d) fetch(d, pre[d]);
-    put_diag(0, pre[0]);
+    constexpr int kThreads = 64 + 64 * TPR;
+    for (int i = tid; i < W; i += kThreads) dead[i] = 0;
+    if (tid == 0) nkb[0] = 0;
     __syncthreads();
 
-    // one chunk; `mine` is the register set that holds chunk c, `next` holds chunk c+1.
-    // Returns true when the cap on the kept set has been reached.
-    auto step = [&](int32_t c, uint64_t (&mine)[kRowWordsPerThread], const uint64_t (&next)[kRowWordsPerThread]) -> bool {
-        if (wave == 0) {
-            const int32_t nk0 = nk_s;
-            int32_t nk = nk0;
-            const uint64_t cur = dead[c];
-            const int32_t nvalid = L - c * 64;
-            uint64_t alive = ~cur & (nvalid >= 64 ? ~0ull : ((1ull << nvalid) - 1ull));
-            const uint64_t dg = diag[c & 1][lane];
-            uint64_t keptw = 0;
-            if (nk < cap) {
-                // lanes whose row meets another alive candidate of this chunk need the serial walk
-                const uint64_t tangled = __ballot((dg & alive) != 0) & alive;
-                const uint64_t freeb = alive & ~tangled;
-                if (tangled == 0 && nk + __popcll(freeb) <= cap) {
-                    keptw = freeb;
-                    nk += __popcll(freeb);
-                } else {
-                    uint64_t todo = alive;
-                    while (todo != 0 && nk < cap) {       // uniform across the wavefront
-                        // free candidates before the next tangled one are kept in one step
-                        const uint64_t tn = todo & tangled;
-                        const int l = tn ? __ffsll((long long)tn) - 1 : 64;
-                        uint64_t run = todo & (l >= 64 ? ~0ull : ((1ull << l) - 1ull));
-                        int32_t nrun = __popcll(run);
-                        if (nk + nrun > cap) {            // the cap cuts the run: keep its first cap-nk bits
-                            while (nrun > cap - nk) { run &= ~(1ull << (63 - __builtin_clzll(run))); --nrun; }
-                            keptw |= run; nk += nrun; todo = 0; break;
+    int32_t n_done = 0;                           // chunks decided
+    if (wave == 0) {
+        // ---- the decider ----
+        // words c and c+1 of row 64c + lane
+        uint64_t dgq[A], nxq[A];
+        // chunks are fetched in order, so the address is carried along: from chunk to chunk the
+        // diagonal word moves 64 rows down and one word right; past the last chunk inside the mask
+        // the pointer stays (the values are not used)
+        const uint64_t *dptr = mask + (int64_t)lane * W;
+        int32_t c_next = 0;                       // the chunk dptr points at
+        auto fetch_diag = [&](uint64_t &d0, uint64_t &d1) {
+            d0 = dptr[0];
+            d1 = dptr[c_next < c_max ? 1 : 0];
+            if (c_next < c_max) { dptr += chunk_stride + 1; ++c_next; }
+        };
+#pragma unroll
+        for (int d = 0; d < A; ++d) fetch_diag(dgq[d], nxq[d]);
+        STRADS_STAMP(1);
+        int32_t nk = 0;                           // kept so far
+        const uint32_t lane_lo = lane < 32 ? 1u << lane : 0u, lane_hi = lane >= 32 ? 1u << (lane - 32) : 0u;
+        const uint64_t last_valid = (L & 63) ? (1ull << (L & 63)) - 1ull : ~0ull;     // live lanes of the last chunk
+        for (int32_t c0 = 0; c0 < chunks; c0 += A) {
+            bool stop = false;
+#pragma unroll
+            for (int d = 0; d < A; ++d) {
+                const int32_t c = c0 + d;
+                if (stop || c >= chunks) break;
+                const uint64_t cur = dead[c];
+                const uint64_t dgv = dgq[d], nxv = nxq[d];
+                fetch_diag(dgq[d], nxq[d]);
+                const uint64_t alive = ~cur & (c + 1 < chunks ? ~0ull : last_valid);
+                uint64_t keptw = 0;
+                if (nk < cap) {
+                    // lanes whose row meets another alive candidate of this chunk need the serial walk
+                    const uint64_t tangled = __ballot((dgv & alive) != 0) & alive;
+                    const uint64_t freeb = alive & ~tangled;
+                    if (tangled == 0 && nk + __popcll(freeb) <= cap) {
+                        keptw = freeb;
+                        nk += __popcll(freeb);
+                    } else {
+                        uint64_t todo = alive;
+                        while (todo != 0 && nk < cap) {       // uniform across the wavefront
+                            // free candidates before the next tangled one are kept in one step
+                            const uint64_t tn = todo & tangled;
+                            const int l = tn ? __ffsll((long long)tn) - 1 : 64;
+                            uint64_t run = todo & (l >= 64 ? ~0ull : ((1ull << l) - 1ull));
+                            int32_t nrun = __popcll(run);
+                            if (nk + nrun > cap) {            // the cap cuts the run: keep its first cap-nk bits
+                                while (nrun > cap - nk) { run &= ~(1ull << (63 - __builtin_clzll(run))); --nrun; }
+                                keptw |= run; nk += nrun; todo = 0; break;
+                            }
+                            keptw |= run; nk += nrun; todo &= ~run;
+                            if (l >= 64 || nk >= cap) break;
+                            keptw |= 1ull << l;
+                            ++nk;
+                            todo &= ~(1ull << l);
+                            todo &= ~readlane64(dgv, l);
                         }
-                        keptw |= run; nk += nrun; todo &= ~run;
-                        if (l >= 64 || nk >= cap) break;
-                        keptw |= 1ull << l;
-                        ++nk;
-                        todo &= ~(1ull << l);
-                        todo &= ~readlane64(dg, l);
                     }
                 }
+                if (lane == 0) { keptw_all[c] = keptw; nkb[c + 1] = nk; }
+                // what this chunk's kept rows do to the next chunk's word
+                const bool mine = (((uint32_t)keptw & lane_lo) | ((uint32_t)(keptw >> 32) & lane_hi)) != 0u;
+                if (mine && nxv != 0 && c + 1 < chunks)
+                    atomicOr((unsigned long long *)&dead[c + 1], (unsigned long long)nxv);
+                __syncthreads();
+                STRADS_STAMP(2 + c);
+                n_done = c + 1;
+                stop = nk >= cap;
             }
-            if ((keptw >> lane) & 1ull) {
-                const int32_t idx = nk0 + __popcll(keptw & ((1ull << lane) - 1ull));
-                kept_pos[idx] = c * 64 + lane;
-            }
-            if (lane == 0) { keptw_s = keptw; nk_s = nk; }
+            if (stop) break;
         }
-        __syncthreads();
-        const uint64_t keptw = keptw_s;
-        const bool full = nk_s >= cap;
-        // OR the kept rows into dead[w], w > c
-        if (!full && keptw != 0) {
+    } else {
+        // ---- the holders ----
+        const int hid = tid - 64;
+        const int row = hid / TPR, j = hid % TPR; // the thread's row of every chunk; it owns words j + TPR q
+        const uint32_t row_lo = row < 32 ? 1u << row : 0u, row_hi = row >= 32 ? 1u << (row - 32) : 0u;
+        uint64_t pre[A][IPT];
+        // chunk c's words of this thread are at mask + (64 c + row) W + j + 4 q; chunks are fetched in
+        // order, so the row pointer is carried along (it stays on the last chunk inside the mask)
+        const uint64_t *rowp = mask + (int64_t)row * W;
+        int32_t c_next = 0;
+        int32_t wq[IPT];                          // j + TPR q, clamped into the row
 #pragma unroll
-            for (int q = 0; q < kRowWordsPerThread; ++q) {
-                const int32_t w = iword[q];
-                if (w > c && ((keptw >> irow[q]) & 1ull)) {
-                    const uint64_t v = mine[q];
-                    if (v) atomicOr((unsigned long long *)&dead[w], (unsigned long long)v);
+        for (int q = 0; q < IPT; ++q) wq[q] = j + TPR * q < W ? j + TPR * q : W - 1;
+        auto fetch = [&](uint64_t (&dst)[IPT]) {
+#pragma unroll
+            for (int q = 0; q < IPT; ++q) dst[q] = rowp[wq[q]];
+            if (c_next < c_max) { rowp += chunk_stride; ++c_next; }
+        };
+#pragma unroll
+        for (int d = 0; d < A; ++d) fetch(pre[d]);
+        for (int32_t c0 = 0; c0 < chunks; c0 += A) {
+            bool stop = false;
+#pragma unroll
+            for (int d = 0; d < A; ++d) {
+                const int32_t c = c0 + d;
+                if (stop || c >= chunks) break;
+                if (c > 0) {
+                    // the rows kept in chunk c-1 -> dead[w], w > c
+                    uint64_t (&prev)[IPT] = pre[(d + A - 1) % A];
+                    const uint64_t keptw = keptw_all[c - 1];
+                    if ((((uint32_t)keptw & row_lo) | ((uint32_t)(keptw >> 32) & row_hi)) != 0u) {
+#pragma unroll
+                        for (int q = 0; q < IPT; ++q) {
+                            const int32_t w = j + TPR * q;
+                            const uint64_t v = prev[q];
+                            if (w > c && w < W && v != 0)
+                                atomicOr((unsigned long long *)&dead[w], (unsigned long long)v);
+                        }
+                    }
+                    fetch(prev);                  // chunk c-1 is done with its registers: they take chunk c-1+A
                 }
+                __syncthreads();
+                n_done = c + 1;
+                stop = nkb[c + 1] >= cap;
             }
+            if (stop) break;
         }
-        if (c + 1 < chunks) put_diag(c + 1, next);
-        fetch(c + kFilterAhead, mine);            // chunk c is done with its registers; in flight for the next chunks
-        __syncthreads();
-        return full;
-    };
+    }
+    __syncthreads();
+    n_done = __builtin_amdgcn_readfirstlane(n_done);
 
-    for (int32_t c0 = 0; c0 < chunks; c0 += kFilterAhead) {
-        bool stop = false;
-#pragma unroll
-        for (int d = 0; d < kFilterAhead; ++d) {
-            if (!stop && c0 + d < chunks) stop = step(c0 + d, pre[d], pre[(d + 1) % kFilterAhead]);
-        }
-        if (stop) break;
-    }
-    // kept column ids, gathered once at the end (a global load inside the loop above would put
-    // a memory round trip on the serial chain of every chunk)
-    const int32_t nk = nk_s;
-    if (cm.on == kCommitDynamic) {
-        if (tid == 0) *n_out = nk;
-        commit_dynamic(cm, p_max, kept_pos, nk, sc);
-        return;
-    }
-    if (cm.on == kCommitKept) {
-        // eq. (2) and Step 4 for B_1, from the update every candidate was found to make when the Gram was formed
-        for (int32_t i = tid; i < nk; i += kFilterThreads) {
-            const int32_t a = kept_pos[i], j = cand[a];
+    // The kept positions, in order, from the per-chunk words: candidate a is number
+    // nkb[a / 64] + (kept candidates of its chunk before it); with them the column ids and, where the
+    // candidates' updates are already known, eq. (2) and Step 4 for B_1.
+    const int32_t nkf = nkb[n_done];
+    const int32_t a_end = n_done * 64 < L ? n_done * 64 : L;
+    for (int32_t a = tid; a < a_end; a += kThreads) {
+        const uint64_t w = keptw_all[a >> 6];
+        if (!((w >> (a & 63)) & 1ull)) continue;
+        const int32_t i = nkb[a >> 6] + __popcll(w & ((1ull << (a & 63)) - 1ull));
+        kept_pos[i] = a;
+        if (cm.on == kCommitKept) {
+            const int32_t j = cand[a];
             const float d = cm.dc[a];
             kept[i] = j;
             cm.z[i] = cm.zc[a];
             cm.delta[i] = d;
             cm.beta[j] = cm.nbc[a];
             cm.dbeta[j] = fabsf(d);
+        } else if (cm.on != kCommitDynamic) {
+            kept[i] = cand[a];
         }
-    } else {
-        for (int32_t i = tid; i < nk; i += kFilterThreads) kept[i] = cand[kept_pos[i]];
+    }
+    if (cm.on == kCommitDynamic) {
+        if (tid == 0) *n_out = nkf;
+        __syncthreads();                          // kept_pos is read back by other threads
+        commit_dynamic(cm, p_max, kept_pos, nkf, sc);
+        return;
     }
     if (tid == 0) {
-        *n_out = nk;
-        if (count_updates) sc->updates_total += (unsigned long long)nk;
+        *n_out = nkf;
+        if (count_updates) sc->updates_total += (unsigned long long)nkf;
     }
+    STRADS_STAMP(2 + kMaxWords);
 }
 
 // Launch for row width W (words); with gdev the kernel takes the actual length and width from
@@ -259,11 +321,12 @@ static hipError_t launch_filter_kernel(strads_lasso *h, int32_t l, int32_t W, co
                                        const int32_t *cand, int32_t *kept_pos, int32_t *kept, int32_t *n_out,
                                        bool count_updates, const CommitArgs &cm)
 {
-#define STRADS_FILTER(IPT) hipLaunchKernelGGL(k_filter<IPT>, dim3(1), dim3(kFilterThreads), 0, h->stream, h->at<uint64_t>(h->ws.mask), l, W, gdev, p_max, cand, kept_pos, kept, h->at<RoundScalars>(h->ws.scalars), n_out, count_updates ? 1 : 0, cm)
-    if (W <= 16) STRADS_FILTER(1);
-    else if (W <= 32) STRADS_FILTER(2);
-    else if (W <= 64) STRADS_FILTER(4);
-    else STRADS_FILTER(8);
+#define STRADS_FILTER(IPT, A, TPR) hipLaunchKernelGGL((k_filter<IPT, A, TPR>), dim3(1), dim3(64 + 64 * TPR), 0, h->stream, h->at<uint64_t>(h->ws.mask), l, W, gdev, p_max, cand, kept_pos, kept, h->at<RoundScalars>(h->ws.scalars), n_out, count_updates ? 1 : 0, cm)
+    // words of a row per holder thread = ceil(W / threads per row); short rows can afford more chunks in flight
+    if (W <= 16) STRADS_FILTER(4, 8, 4);
+    else if (W <= 32) STRADS_FILTER(8, 6, 4);
+    else if (W <= 64) STRADS_FILTER(16, 4, 4);
+    else STRADS_FILTER(16, 3, 8);
 #undef STRADS_FILTER
     return hipGetLastError();
 }
