@@ -96,14 +96,6 @@ __device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_m
     }
 }
 
-#ifdef STRADS_FILTER_TIMING
-// lab builds only: shader-clock stamps of wavefront 0 (start, after the first loads, after every chunk, end)
-__device__ unsigned long long g_filter_stamps[160];
-#define STRADS_STAMP(i) do { if (threadIdx.x == 0) g_filter_stamps[(i)] = clock64(); } while (0)
-#else
-#define STRADS_STAMP(i) do { } while (0)
-#endif
-
 // TPR = holder threads per row of a chunk (4; 8 for rows of more than 64 words), IPT = words of a row per
 // holder thread = ceil(W / TPR): 4, 8 or 16.  A = chunks whose words a thread has in registers or on
 // their way there (chunk c waits in set c mod A).
@@ -134,7 +126,6 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
                                                            RoundScalars *__restrict__ sc, int32_t *__restrict__ n_out,
                                                            int count_updates, CommitArgs cm)
 {
-    STRADS_STAMP(0);
     if (gdev) { L = gdev->L; W = gdev->Lpad / 64; }   // dynamic dependencies: the movers, counted on the device
     if (L <= 0) {                                      // nothing moves this round
         if (threadIdx.x == 0) *n_out = 0;
@@ -174,7 +165,6 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
         };
 #pragma unroll
         for (int d = 0; d < A; ++d) fetch_diag(dgq[d], nxq[d]);
-        STRADS_STAMP(1);
         int32_t nk = 0;                           // kept so far
         const uint32_t lane_lo = lane < 32 ? 1u << lane : 0u, lane_hi = lane >= 32 ? 1u << (lane - 32) : 0u;
         const uint64_t last_valid = (L & 63) ? (1ull << (L & 63)) - 1ull : ~0ull;     // live lanes of the last chunk
@@ -223,7 +213,6 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
                 if (mine && nxv != 0 && c + 1 < chunks)
                     atomicOr((unsigned long long *)&dead[c + 1], (unsigned long long)nxv);
                 __syncthreads();
-                STRADS_STAMP(2 + c);
                 n_done = c + 1;
                 stop = nk >= cap;
             }
@@ -312,7 +301,6 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
         *n_out = nkf;
         if (count_updates) sc->updates_total += (unsigned long long)nkf;
     }
-    STRADS_STAMP(2 + kMaxWords);
 }
 
 // Launch for row width W (words); with gdev the kernel takes the actual length and width from
