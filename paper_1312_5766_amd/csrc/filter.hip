@@ -107,8 +107,10 @@ __device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_m
 //     <= c-2 do to word c was ORed in by the holders, what the rows kept in chunk c-1 do to it by
 //     wavefront 0 itself when it decided c-1 (its lanes hold word c of those rows; LDS operations of
 //     one wavefront complete in order).  Lane l loads words c and c+1 of row 64c + l itself, A chunks
-//     early, so a chunk costs it one LDS round trip and a few dozen instructions, which is what the
-//     whole walk is bound by: a single wavefront issues an instruction every four to five cycles.
+//     early, so a chunk costs it one LDS round trip and a few dozen instructions.  That chain is what
+//     the walk is bound by (measured: some 500 cycles from the barrier to the chunk's dead word in a
+//     scalar register, 250 for the quick decision, 250 to get the results into LDS; a lone wavefront
+//     spends about ten cycles per instruction of a dependent chain with its branches).
 //   holders (the other wavefronts; TPR threads per row of a chunk, thread j of a row owning words j, j+TPR, ...):
 //     OR the words they hold of the rows kept in chunk c-1 into dead[w], w > c, and refill those
 //     registers with chunk c-1+A.
