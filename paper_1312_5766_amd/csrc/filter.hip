@@ -29,8 +29,6 @@ __device__ __forceinline__ uint64_t readlane64(uint64_t v, int l)
 }
 
 constexpr int kMaxWords = STRADS_MAX_L_PRIME / 64;   // mask words per row (128)
-constexpr int kFilterMaxThreads = 576;              // wavefront 0 decides, four or eight wavefronts hold the conflict rows
-constexpr int kFilterMaxWaves = kFilterMaxThreads / 64;
 
 // Dynamic dependencies: what the walk over the movers is followed by, in the same workgroup (a
 // kernel of its own would cost a launch boundary, a good part of a short round).
@@ -50,47 +48,58 @@ constexpr int32_t kCommitKept = 2;     // Algorithm 1's rule: eq. (2) for the ke
 
 // Assemble B_1 = (candidates that do not move) + (movers that passed the filter), in draw order,
 // cut at the cap, and commit it: beta_j <- its tentative value, delta beta_j <- |change| (0 for a
-// kept candidate that does not move).  The workgroup walks the candidate positions blockDim.x at a
-// time.  mkept_pos[0..nmk): the walk's result, written by this workgroup before a barrier.
-__device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_max, const int32_t *mkept_pos,
-                                               int32_t nmk, RoundScalars *__restrict__ sc)
+// kept candidate that does not move).  mkept[a] (LDS, one byte per candidate position) says whether a
+// mover at position a passed the filter.  Three phases with a barrier between them, whatever the
+// length of the list: one keep bit per candidate, gathered into 64-bit words by wavefront ballots;
+// the number of kept candidates before every word (one wavefront); the writes.
+__device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_max, const uint8_t *mkept,
+                                               RoundScalars *__restrict__ sc)
 {
-    __shared__ uint8_t mkept[STRADS_MAX_L_PRIME];       // 1: a mover at this position passed the filter
-    __shared__ uint32_t wtot[kFilterMaxWaves];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nthreads = blockDim.x, nwaves = nthreads >> 6;
+    __shared__ uint64_t keepw[kMaxWords];
+    __shared__ int32_t before[kMaxWords + 1];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int nthreads = blockDim.x;
     const int32_t L = cm.L;
     const int32_t cap = p_max > 0 ? p_max : L;
-    for (int32_t a = tid; a < L; a += nthreads) mkept[a] = 0;
-    __syncthreads();
-    for (int32_t i = tid; i < nmk; i += nthreads) mkept[cm.mpos[mkept_pos[i]]] = 1;
-    __syncthreads();
-    uint32_t base = 0;
-    for (int32_t a0 = 0; a0 < L; a0 += nthreads) {
+    const int32_t nwords = (L + 63) / 64;
+    for (int32_t a0 = 0; a0 < nwords * 64; a0 += nthreads) {       // whole wavefronts: nthreads is a multiple of 64
         const int32_t a = a0 + tid;
-        const float d = a < L ? cm.dc[a] : 0.f;
-        const bool keep = a < L && (d == 0.f || mkept[a]);
+        const bool keep = a < L && (cm.dc[a] == 0.f || mkept[a]);
         const uint64_t m = __ballot(keep);
-        if (lane == 0) wtot[wave] = (uint32_t)__popcll(m);
-        __syncthreads();
-        uint32_t before = 0, total = 0;
+        if (lane == 0 && a < nwords * 64) keepw[a >> 6] = m;
+    }
+    __syncthreads();
+    if (tid < 64) {                                                 // at most 128 words: two per lane
+        const int32_t w0 = 2 * lane, w1 = 2 * lane + 1;
+        const int32_t c0 = w0 < nwords ? __popcll(keepw[w0]) : 0, c1 = w1 < nwords ? __popcll(keepw[w1]) : 0;
+        int32_t incl = c0 + c1;
 #pragma unroll
-        for (int w = 0; w < nwaves; ++w) { const uint32_t v = wtot[w]; if (w < wave) before += v; total += v; }
-        const int32_t idx = (int32_t)(base + before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull)));
-        if (keep && idx < cap) {
-            const int32_t j = cm.cand[a];
-            cm.kept_pos[idx] = a;
-            cm.kept[idx] = j;
-            cm.z[idx] = cm.zc[a];
-            cm.delta[idx] = d;
-            cm.beta[j] = cm.nbc[a];
-            cm.dbeta[j] = fabsf(d);
+        for (int d = 1; d < 64; d <<= 1) {
+            const int32_t v = __shfl_up(incl, d);
+            if (lane >= d) incl += v;
         }
-        base += total;
-        __syncthreads();
+        if (w0 < nwords) before[w0] = incl - c0 - c1;
+        if (w1 < nwords) before[w1] = incl - c1;
+        if (lane == 63) before[kMaxWords] = incl;
+    }
+    __syncthreads();
+    for (int32_t a = tid; a < L; a += nthreads) {
+        const uint64_t w = keepw[a >> 6];
+        if (!((w >> (a & 63)) & 1ull)) continue;
+        const int32_t idx = before[a >> 6] + __popcll(w & ((1ull << (a & 63)) - 1ull));
+        if (idx >= cap) continue;
+        const int32_t j = cm.cand[a];
+        const float d = cm.dc[a];
+        cm.kept_pos[idx] = a;
+        cm.kept[idx] = j;
+        cm.z[idx] = cm.zc[a];
+        cm.delta[idx] = d;
+        cm.beta[j] = cm.nbc[a];
+        cm.dbeta[j] = fabsf(d);
     }
     if (tid == 0) {
-        const int32_t nk = (int32_t)base < cap ? (int32_t)base : cap;
+        const int32_t total = before[kMaxWords];
+        const int32_t nk = total < cap ? total : cap;
         sc->n_kept = nk;
         sc->updates_total += (unsigned long long)nk;
     }
@@ -128,10 +137,17 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
                                                            RoundScalars *__restrict__ sc, int32_t *__restrict__ n_out,
                                                            int count_updates, CommitArgs cm)
 {
+    constexpr int kThreads = 64 + 64 * TPR;
+    __shared__ uint8_t mkept[STRADS_MAX_L_PRIME];       // dynamic dependencies: 1 = a mover at this candidate position was kept
     if (gdev) { L = gdev->L; W = gdev->Lpad / 64; }   // dynamic dependencies: the movers, counted on the device
+    if (cm.on == kCommitDynamic)
+        for (int32_t a = threadIdx.x; a < cm.L; a += kThreads) mkept[a] = 0;      // (the barriers below order it)
     if (L <= 0) {                                      // nothing moves this round
         if (threadIdx.x == 0) *n_out = 0;
-        if (cm.on == kCommitDynamic) commit_dynamic(cm, p_max, kept_pos, 0, sc);
+        if (cm.on == kCommitDynamic) {
+            __syncthreads();
+            commit_dynamic(cm, p_max, mkept, sc);
+        }
         return;
     }
     __shared__ uint64_t dead[kMaxWords];
@@ -145,7 +161,6 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
     const int64_t chunk_stride = (int64_t)64 * W; // words from a chunk's rows to the next chunk's
     const int32_t c_max = W - 1;                  // chunk index up to which a chunk's rows lie inside the mask (chunks <= W)
 
-    constexpr int kThreads = 64 + 64 * TPR;
     for (int i = tid; i < W; i += kThreads) dead[i] = 0;
     if (tid == 0) nkb[0] = 0;
     __syncthreads();
@@ -289,14 +304,16 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
             cm.delta[i] = d;
             cm.beta[j] = cm.nbc[a];
             cm.dbeta[j] = fabsf(d);
-        } else if (cm.on != kCommitDynamic) {
+        } else if (cm.on == kCommitDynamic) {
+            mkept[cm.mpos[a]] = 1;                // a is a position in the mover list here
+        } else {
             kept[i] = cand[a];
         }
     }
     if (cm.on == kCommitDynamic) {
         if (tid == 0) *n_out = nkf;
-        __syncthreads();                          // kept_pos is read back by other threads
-        commit_dynamic(cm, p_max, kept_pos, nkf, sc);
+        __syncthreads();
+        commit_dynamic(cm, p_max, mkept, sc);
         return;
     }
     if (tid == 0) {
