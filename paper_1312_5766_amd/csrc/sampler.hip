@@ -97,12 +97,27 @@ __global__ __launch_bounds__(1024) void k_hist2(const uint32_t *__restrict__ key
 {
     __shared__ uint32_t lh[kHistBins];
     __shared__ uint32_t tmp[258];
+    // The thread's first keys are requested before the boundary bin is looked up (which takes a trip to
+    // memory for the histogram and two barriers), so that the two latencies overlap.
+    constexpr int kEarly = 4;
+    const uint32_t stride = gridDim.x * blockDim.x;
+    uint32_t early[kEarly];
+#pragma unroll
+    for (int q = 0; q < kEarly; ++q) {
+        const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x + q * stride;
+        early[q] = j < J ? keys[j] : 0u;
+    }
     uint32_t b0, above;
     find_bin_desc(hist0, L, tmp, b0, above);
     if (blockIdx.x == 0 && threadIdx.x == 0) { sc->bin0 = b0; sc->rem1 = L - above; }
     for (int i = threadIdx.x; i < kHistBins; i += blockDim.x) lh[i] = 0;
     __syncthreads();
-    for (uint32_t j = blockIdx.x * blockDim.x + threadIdx.x; j < J; j += gridDim.x * blockDim.x) {
+#pragma unroll
+    for (int q = 0; q < kEarly; ++q) {
+        const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x + q * stride;
+        if (j < J && (early[q] >> 21) == b0) atomicAdd(&lh[(early[q] >> 10) & 0x7FFu], 1u);
+    }
+    for (uint32_t j = blockIdx.x * blockDim.x + threadIdx.x + kEarly * stride; j < J; j += stride) {
         const uint32_t ok = keys[j];
         if ((ok >> 21) == b0) atomicAdd(&lh[(ok >> 10) & 0x7FFu], 1u);
     }
@@ -128,19 +143,24 @@ __global__ __launch_bounds__(256) void k_collect(const uint32_t *__restrict__ ke
 {
     __shared__ uint32_t tmp[258];
     __shared__ uint32_t wtot[2][4], wbase[2][4];
+    const int lane = __lane_id(), wave = threadIdx.x >> 6;
+    const uint32_t base = (blockIdx.x * 256u + (threadIdx.x & ~63u)) * kCollectPerThread + (threadIdx.x & 63u);
+    // the keys are requested before the boundary prefix is looked up, so that the two trips to memory overlap
+    uint32_t okv[kCollectPerThread];
+#pragma unroll
+    for (int q = 0; q < kCollectPerThread; ++q) {
+        const uint32_t j = base + q * 64u;
+        okv[q] = j < J ? keys[j] : 0u;
+    }
     const uint32_t b0 = sc->bin0, rem1 = sc->rem1;
     uint32_t b1, above;
     find_bin_desc(hist1, rem1, tmp, b1, above);
     const uint32_t p22 = (b0 << 11) | b1;
     if (blockIdx.x == 0 && threadIdx.x == 0) { sc->prefix22 = p22; sc->rem2 = rem1 - above; }
-    const int lane = __lane_id(), wave = threadIdx.x >> 6;
-    const uint32_t base = (blockIdx.x * 256u + (threadIdx.x & ~63u)) * kCollectPerThread + (threadIdx.x & 63u);
-    uint32_t okv[kCollectPerThread];
     uint32_t n_gt = 0, n_eq = 0;
 #pragma unroll
     for (int q = 0; q < kCollectPerThread; ++q) {
         const uint32_t j = base + q * 64u;
-        okv[q] = j < J ? keys[j] : 0u;
         const uint32_t p = okv[q] >> 10;
         n_gt += (j < J && p > p22) ? 1u : 0u;
         n_eq += (j < J && p == p22) ? 1u : 0u;
@@ -301,6 +321,10 @@ __global__ __launch_bounds__(1024) void k_finalize(RoundScalars *__restrict__ sc
     __shared__ uint32_t pick[2];
     const uint32_t tid = threadIdx.x;
     uint32_t n_sel = sc->n_sel, nb = sc->n_bnd, need = sc->rem2;
+    // what the collect pass selected outright is final: this thread's item of it is requested now, so that
+    // its trip to memory overlaps the work on the boundary list (steps A and B only append behind it)
+    const uint32_t n_sel_collected = n_sel;
+    const uint64_t early_item = sel[tid];         // (any value past the collected part; the buffer holds 2 x 8192 items)
 
     // A. (rare) boundary list longer than the LDS sort can hold: peel 8-bit digits below the
     //    22-bit prefix until it fits.  Items are distinct, so this always terminates.
@@ -368,7 +392,8 @@ __global__ __launch_bounds__(1024) void k_finalize(RoundScalars *__restrict__ sc
 
     // C. sort the L selected items: descending item = draw order
     if (L <= kRegSortMax) {
-        const uint64_t v = bitonic_sort_desc_1024(tid < L ? sel[tid] : 0ull, lds);
+        const uint64_t mine = tid < n_sel_collected ? early_item : (tid < L ? sel[tid] : 0ull);
+        const uint64_t v = bitonic_sort_desc_1024(mine, lds);
         if (tid < Lpad) cand[tid] = tid < L ? (int32_t)(0xFFFFFFFFu - (uint32_t)v) : 0;
     }
     // longer lists are put in order by k_sort_chunks + k_merge_rank, spread over many workgroups
