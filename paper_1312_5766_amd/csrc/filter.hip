@@ -150,6 +150,19 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
         }
         return;
     }
+    // Short and medium lists that end with eq. (2) for the kept candidates: what that needs of the
+    // thread's first candidates is requested now, and has arrived long before the walk is over.
+    constexpr int kEarly = IPT <= 8 ? 4 : 0;
+    int32_t e_cand[kEarly > 0 ? kEarly : 1];
+    float e_dc[kEarly > 0 ? kEarly : 1], e_zc[kEarly > 0 ? kEarly : 1], e_nbc[kEarly > 0 ? kEarly : 1];
+    if (cm.on == kCommitKept) {
+#pragma unroll
+        for (int k = 0; k < kEarly; ++k) {
+            const int32_t a = (int32_t)threadIdx.x + k * kThreads;
+            const int32_t at = a < L ? a : 0;
+            e_cand[k] = cand[at]; e_dc[k] = cm.dc[at]; e_zc[k] = cm.zc[at]; e_nbc[k] = cm.nbc[at];
+        }
+    }
     __shared__ uint64_t dead[kMaxWords];
     __shared__ uint64_t keptw_all[kMaxWords];     // [c]: the candidates kept in chunk c
     __shared__ int32_t nkb[kMaxWords + 1];        // [c]: kept before chunk c.  (Positions go to global memory
@@ -291,7 +304,28 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
     // candidates' updates are already known, eq. (2) and Step 4 for B_1.
     const int32_t nkf = nkb[n_done];
     const int32_t a_end = n_done * 64 < L ? n_done * 64 : L;
-    for (int32_t a = tid; a < a_end; a += kThreads) {
+    int32_t a_first = tid;
+    if (cm.on == kCommitKept) {
+#pragma unroll
+        for (int k = 0; k < kEarly; ++k) {      // the candidates whose values were requested at the start
+            const int32_t a = tid + k * kThreads;
+            if (a < a_end) {
+                const uint64_t w = keptw_all[a >> 6];
+                if ((w >> (a & 63)) & 1ull) {
+                    const int32_t i = nkb[a >> 6] + __popcll(w & ((1ull << (a & 63)) - 1ull));
+                    const int32_t j = e_cand[k];
+                    kept_pos[i] = a;
+                    kept[i] = j;
+                    cm.z[i] = e_zc[k];
+                    cm.delta[i] = e_dc[k];
+                    cm.beta[j] = e_nbc[k];
+                    cm.dbeta[j] = fabsf(e_dc[k]);
+                }
+            }
+        }
+        a_first = tid + kEarly * kThreads;
+    }
+    for (int32_t a = a_first; a < a_end; a += kThreads) {
         const uint64_t w = keptw_all[a >> 6];
         if (!((w >> (a & 63)) & 1ull)) continue;
         const int32_t i = nkb[a >> 6] + __popcll(w & ((1ull << (a & 63)) - 1ull));

@@ -185,7 +185,7 @@ __global__ __launch_bounds__(1024) void k_residual_fused(const float *__restrict
                                                          const int32_t *__restrict__ kept,
                                                          const float *__restrict__ delta,
                                                          RoundScalars *__restrict__ sc, float *__restrict__ r,
-                                                         uint32_t res_blocks, KeysArgs next_keys)
+                                                         int32_t lpad, uint32_t res_blocks, KeysArgs next_keys)
 {
     if (blockIdx.x >= res_blocks) {
         keys_hist_block(next_keys, blockIdx.x - res_blocks, gridDim.x - res_blocks);
@@ -196,9 +196,17 @@ __global__ __launch_bounds__(1024) void k_residual_fused(const float *__restrict
     __shared__ uint32_t wcnt[16];
     __shared__ float red[16][64];
     __shared__ float wmax[16];
-    const int k = sc->n_kept;                   // <= candidates per round <= kFusedResidualMaxL
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const float d = tid < k ? delta[tid] : 0.f;
+    // everything this thread will want from memory whatever the kept count turns out to be is requested
+    // at once (entry tid of the kept list, its row of r), so that the trips overlap instead of following
+    // one another: the count, then the list, then the columns
+    const int64_t i = (int64_t)blockIdx.x * 64 + lane;
+    const int slot = tid < lpad ? tid : 0;      // the lists have lpad entries
+    const float d_slot = delta[slot];
+    const int32_t col_slot = kept[slot];
+    const float r_old = (wave == 0 && i < N) ? r[i] : 0.f;
+    const int k = sc->n_kept;                   // <= candidates per round <= kFusedResidualMaxL
+    const float d = tid < k ? d_slot : 0.f;
     const bool mv = d != 0.f;
     const uint64_t m = __ballot(mv);
     if (lane == 0) wcnt[wave] = (uint32_t)__popcll(m);
@@ -208,12 +216,11 @@ __global__ __launch_bounds__(1024) void k_residual_fused(const float *__restrict
     for (int w = 0; w < 16; ++w) { const uint32_t v = wcnt[w]; if (w < wave) before += v; tot += v; }
     if (mv) {
         const uint32_t p = before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-        mcol[p] = kept[tid];
+        mcol[p] = col_slot;
         mdel[p] = d;
     }
     __syncthreads();
 
-    const int64_t i = (int64_t)blockIdx.x * 64 + lane;
     float acc = 0.f;
     if (i < N) {
         uint32_t q = (uint32_t)wave;
@@ -239,7 +246,7 @@ __global__ __launch_bounds__(1024) void k_residual_fused(const float *__restrict
         float t = 0.f;
 #pragma unroll
         for (int w = 0; w < 16; ++w) t += red[w][lane];
-        r[i] -= t;
+        r[i] = r_old - t;
     }
     if (blockIdx.x == 0 && tid == 0) {
         float mx = 0.f;
@@ -487,7 +494,7 @@ hipError_t launch_residual_dense(strads_lasso *h, bool want_next_keys, bool *nex
         }
         hipLaunchKernelGGL(k_residual_fused, dim3(res_blocks + key_blocks), dim3(1024), 0, h->stream,
                            h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc,
-                           h->at<float>(h->ws.r), res_blocks, keys_args(h));
+                           h->at<float>(h->ws.r), h->Lpad, res_blocks, keys_args(h));
         return hipGetLastError();
     }
     const int G = residual_groups(h->cfg.n, h->L);
