@@ -52,8 +52,12 @@ constexpr int32_t kCommitKept = 2;     // Algorithm 1's rule: eq. (2) for the ke
 // mover at position a passed the filter.  Three phases with a barrier between them, whatever the
 // length of the list: one keep bit per candidate, gathered into 64-bit words by wavefront ballots;
 // the number of kept candidates before every word (one wavefront); the writes.
+//
+// e_*: what the caller requested early of candidates tid + k * blockDim.x, k < K (see k_filter).
+template <int K>
 __device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_max, const uint8_t *mkept,
-                                               RoundScalars *__restrict__ sc)
+                                               RoundScalars *__restrict__ sc, const int32_t *e_cand,
+                                               const float *e_dc, const float *e_zc, const float *e_nbc)
 {
     __shared__ uint64_t keepw[kMaxWords];
     __shared__ int32_t before[kMaxWords + 1];
@@ -62,7 +66,16 @@ __device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_m
     const int32_t L = cm.L;
     const int32_t cap = p_max > 0 ? p_max : L;
     const int32_t nwords = (L + 63) / 64;
-    for (int32_t a0 = 0; a0 < nwords * 64; a0 += nthreads) {       // whole wavefronts: nthreads is a multiple of 64
+#pragma unroll
+    for (int k = 0; k < K; ++k) {                                   // whole wavefronts: nthreads is a multiple of 64
+        const int32_t a = tid + k * nthreads;
+        if (k * nthreads < nwords * 64) {
+            const bool keep = a < L && (e_dc[k] == 0.f || mkept[a]);
+            const uint64_t m = __ballot(keep);
+            if (lane == 0 && a < nwords * 64) keepw[a >> 6] = m;
+        }
+    }
+    for (int32_t a0 = K * nthreads; a0 < nwords * 64; a0 += nthreads) {
         const int32_t a = a0 + tid;
         const bool keep = a < L && (cm.dc[a] == 0.f || mkept[a]);
         const uint64_t m = __ballot(keep);
@@ -83,7 +96,23 @@ __device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_m
         if (lane == 63) before[kMaxWords] = incl;
     }
     __syncthreads();
-    for (int32_t a = tid; a < L; a += nthreads) {
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int32_t a = tid + k * nthreads;
+        if (a >= L) continue;
+        const uint64_t w = keepw[a >> 6];
+        if (!((w >> (a & 63)) & 1ull)) continue;
+        const int32_t idx = before[a >> 6] + __popcll(w & ((1ull << (a & 63)) - 1ull));
+        if (idx >= cap) continue;
+        const int32_t j = e_cand[k];
+        cm.kept_pos[idx] = a;
+        cm.kept[idx] = j;
+        cm.z[idx] = e_zc[k];
+        cm.delta[idx] = e_dc[k];
+        cm.beta[j] = e_nbc[k];
+        cm.dbeta[j] = fabsf(e_dc[k]);
+    }
+    for (int32_t a = tid + K * nthreads; a < L; a += nthreads) {
         const uint64_t w = keepw[a >> 6];
         if (!((w >> (a & 63)) & 1ull)) continue;
         const int32_t idx = before[a >> 6] + __popcll(w & ((1ull << (a & 63)) - 1ull));
@@ -142,26 +171,27 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
     if (gdev) { L = gdev->L; W = gdev->Lpad / 64; }   // dynamic dependencies: the movers, counted on the device
     if (cm.on == kCommitDynamic)
         for (int32_t a = threadIdx.x; a < cm.L; a += kThreads) mkept[a] = 0;      // (the barriers below order it)
+    // Short and medium lists that end with eq. (2) for kept candidates: what that needs of the
+    // thread's first candidates (positions in the round's candidate list) is requested now, and has
+    // arrived long before the walk is over.
+    constexpr int kEarly = IPT <= 8 ? 4 : 0;
+    int32_t e_cand[kEarly > 0 ? kEarly : 1];
+    float e_dc[kEarly > 0 ? kEarly : 1], e_zc[kEarly > 0 ? kEarly : 1], e_nbc[kEarly > 0 ? kEarly : 1];
+    if (cm.on != 0) {
+#pragma unroll
+        for (int k = 0; k < kEarly; ++k) {
+            const int32_t a = (int32_t)threadIdx.x + k * kThreads;
+            const int32_t at = a < cm.L ? a : 0;
+            e_cand[k] = cm.cand[at]; e_dc[k] = cm.dc[at]; e_zc[k] = cm.zc[at]; e_nbc[k] = cm.nbc[at];
+        }
+    }
     if (L <= 0) {                                      // nothing moves this round
         if (threadIdx.x == 0) *n_out = 0;
         if (cm.on == kCommitDynamic) {
             __syncthreads();
-            commit_dynamic(cm, p_max, mkept, sc);
+            commit_dynamic<kEarly>(cm, p_max, mkept, sc, e_cand, e_dc, e_zc, e_nbc);
         }
         return;
-    }
-    // Short and medium lists that end with eq. (2) for the kept candidates: what that needs of the
-    // thread's first candidates is requested now, and has arrived long before the walk is over.
-    constexpr int kEarly = IPT <= 8 ? 4 : 0;
-    int32_t e_cand[kEarly > 0 ? kEarly : 1];
-    float e_dc[kEarly > 0 ? kEarly : 1], e_zc[kEarly > 0 ? kEarly : 1], e_nbc[kEarly > 0 ? kEarly : 1];
-    if (cm.on == kCommitKept) {
-#pragma unroll
-        for (int k = 0; k < kEarly; ++k) {
-            const int32_t a = (int32_t)threadIdx.x + k * kThreads;
-            const int32_t at = a < L ? a : 0;
-            e_cand[k] = cand[at]; e_dc[k] = cm.dc[at]; e_zc[k] = cm.zc[at]; e_nbc[k] = cm.nbc[at];
-        }
     }
     __shared__ uint64_t dead[kMaxWords];
     __shared__ uint64_t keptw_all[kMaxWords];     // [c]: the candidates kept in chunk c
@@ -347,7 +377,7 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
     if (cm.on == kCommitDynamic) {
         if (tid == 0) *n_out = nkf;
         __syncthreads();
-        commit_dynamic(cm, p_max, mkept, sc);
+        commit_dynamic<kEarly>(cm, p_max, mkept, sc, e_cand, e_dc, e_zc, e_nbc);
         return;
     }
     if (tid == 0) {
