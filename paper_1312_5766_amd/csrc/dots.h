@@ -78,9 +78,9 @@ __device__ __forceinline__ void cand_dots_block(const float *__restrict__ X, int
     const int c = block * CPB + (int)threadIdx.x / TPC;
     if (c >= cd.L) return;                      // TPC = 256: whole workgroup; TPC = 64: whole wavefront
     const int32_t j = cand[c];
+    const float b = cd.beta[j];                 // requested with the column, not after the reduction
     const float s = column_dot<TPC, VEC4>(X + (int64_t)j * N, cd.r, N, (int)threadIdx.x % TPC, red);
     if (threadIdx.x % TPC == 0) {
-        const float b = cd.beta[j];
         const float nb = soft_threshold(s * cd.step + b, cd.lambda * cd.step);
         cd.zc[c] = s;
         cd.nbc[c] = nb;

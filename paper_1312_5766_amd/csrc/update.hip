@@ -38,9 +38,9 @@ __global__ __launch_bounds__(256) void k_dots_update(const float *__restrict__ X
     const int c = blockIdx.x * CPB + threadIdx.x / TPC;
     if (c >= sc->n_kept) return;                // TPC = 256: whole workgroup; TPC = 64: whole wavefront
     const int32_t j = kept[c];
+    const float b = beta[j];                    // requested with the column, not after the reduction
     const float s = column_dot<TPC, VEC4>(X + (int64_t)j * N, r, N, threadIdx.x % TPC, red);
     if (threadIdx.x % TPC == 0) {
-        const float b = beta[j];
         const float nb = soft_threshold(s * step + b, lambda * step);     // step = 1: eq. (2) as printed
         const float d = nb - b;
         z[c] = s;
