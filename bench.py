@@ -244,7 +244,7 @@ def main() -> int:
     streams = None
     if args.profile_level and args.shards == 1 and args.deps == "static" and p.layout == "dense":
         v = fresh()
-        short = p.l_prime <= 1024
+        short = p.l_prime <= 4096
         if short:
             v.set_tuning("dots_with_gram", 0)
             v.set_tuning("residual_fused", 0)
@@ -312,7 +312,7 @@ def main() -> int:
             and args.deps == "static"):
         ach = gram_flops / (stage["gram_tiles"] * 1e-3) / 1e12
         # does the launch carry the candidates' dot products?  (the library's rule, see "dots_with_gram")
-        rides = (p.layout == "dense" and args.shards <= 1 and p.l_prime <= 1024
+        rides = (p.layout == "dense" and args.shards <= 1 and p.l_prime <= 4096
                  and "dots_with_gram=0" not in [t.replace(" ", "") for t in args.tune])
         traffic = MEASURED_GRAM_TRAFFIC_BYTES.get(args.workload)
         roofline = {"bound": "mfma", "kernel": "k_gram_tiles", "achieved": round(ach, 3),

@@ -183,7 +183,7 @@ inline const float *dots_vector(const strads_lasso *h)
 // made for all candidates by extra workgroups of the Gram launch (CandDots), and the filter's
 // workgroup applies eq. (2) to the ones it kept.  (With several schedulers the Gram of a round is
 // formed before the previous round's residual exists, so its products cannot be taken there.)
-constexpr int kShortList = 1024;
+constexpr int kShortList = 4096;
 inline bool dots_ride_with_gram(const strads_lasso *h)
 {
     return h->dots_with_gram && h->cfg.deps == STRADS_DEPS_STATIC && h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR &&

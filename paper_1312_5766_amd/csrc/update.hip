@@ -180,7 +180,7 @@ __global__ __launch_bounds__(256) void k_residual_apply(const float *__restrict_
 // round's key pass (pass 1 of its selection): it needs delta beta as this round left it, which the
 // kernels before this one have written, and nothing this kernel writes, so the two share a launch
 // and the next round starts one kernel further on.
-constexpr int kFusedResidualMaxL = 1024;
+constexpr int kFusedResidualMaxL = 4096;
 __global__ __launch_bounds__(1024) void k_residual_fused(const float *__restrict__ X, int64_t N,
                                                          const int32_t *__restrict__ kept,
                                                          const float *__restrict__ delta,
@@ -206,20 +206,28 @@ __global__ __launch_bounds__(1024) void k_residual_fused(const float *__restrict
     const int32_t col_slot = kept[slot];
     const float r_old = (wave == 0 && i < N) ? r[i] : 0.f;
     const int k = sc->n_kept;                   // <= candidates per round <= kFusedResidualMaxL
-    const float d = tid < k ? d_slot : 0.f;
-    const bool mv = d != 0.f;
-    const uint64_t m = __ballot(mv);
-    if (lane == 0) wcnt[wave] = (uint32_t)__popcll(m);
-    __syncthreads();
-    uint32_t before = 0, tot = 0;
+    // the movers (delta != 0) of the kept list, in list order, 1024 entries at a time
+    uint32_t tot = 0;
+    float dmax = 0.f;
+    for (int c0 = 0; c0 < k; c0 += 1024) {
+        const int a = c0 + tid;
+        const float d = a < k ? (c0 == 0 ? d_slot : delta[a]) : 0.f;
+        const bool mv = d != 0.f;
+        const uint64_t m = __ballot(mv);
+        if (lane == 0) wcnt[wave] = (uint32_t)__popcll(m);
+        __syncthreads();
+        uint32_t before = 0, here = 0;
 #pragma unroll
-    for (int w = 0; w < 16; ++w) { const uint32_t v = wcnt[w]; if (w < wave) before += v; tot += v; }
-    if (mv) {
-        const uint32_t p = before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-        mcol[p] = col_slot;
-        mdel[p] = d;
+        for (int w = 0; w < 16; ++w) { const uint32_t v = wcnt[w]; if (w < wave) before += v; here += v; }
+        if (mv) {
+            const uint32_t p = tot + before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            mcol[p] = c0 == 0 ? col_slot : kept[a];
+            mdel[p] = d;
+        }
+        tot += here;
+        dmax = fmaxf(dmax, fabsf(d));
+        __syncthreads();
     }
-    __syncthreads();
 
     float acc = 0.f;
     if (i < N) {
@@ -236,7 +244,7 @@ __global__ __launch_bounds__(1024) void k_residual_fused(const float *__restrict
     }
     red[wave][lane] = acc;
     if (blockIdx.x == 0) {                      // round summary for strads_lasso_round's info
-        float mx = fabsf(d);
+        float mx = dmax;
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_down(mx, off));
         if (lane == 0) wmax[wave] = mx;
