@@ -291,9 +291,10 @@ def test_reduced_configs_teacher_forced(config, kw, rounds):
     dict(n=2000, j=6000, nnz=40, l_prime=500),
     dict(n=1003, j=3000, nnz=40, l_prime=1024, lam_frac=0.001, rho=0.9),     # nearly every candidate is kept and moves
     dict(n=61, j=500, nnz=5, l_prime=90, lam_frac=0.001),                    # fewer rows than one workgroup owns
+    dict(n=403, j=9000, nnz=40, l_prime=2500, lam_frac=0.001, rho=0.9),      # more than 1024 movers: the kept list is compacted in pieces
 ])
 def test_short_list_route_and_general_route(kw, ride, fused):
-    # lists of at most 1024 candidates: x_j^T r rides along with the Gram launch and the filter commits B_1
+    # lists of at most 4096 candidates: x_j^T r rides along with the Gram launch and the filter commits B_1
     # unless "dots_with_gram" is 0; the residual is updated in one kernel unless "residual_fused" is 0
     p = si.make("c2_dense_block_corr", **kw)
     g, o = _pair(p)
@@ -310,6 +311,8 @@ def test_short_list_route_and_general_route(kw, ride, fused):
     assert info.n_moved == int(np.count_nonzero(delta))
     assert info.max_abs_delta == np.float32(np.abs(delta).max(initial=0.0))
     assert info.n_kept == len(_np(g.last_round(want_gram=False)["kept"]))
+    if kw["l_prime"] == 2500:
+        assert info.n_moved > 1024
     if kw["l_prime"] == 1024:
         assert info.n_moved > 200          # every wavefront of the one-kernel update has several columns
 
