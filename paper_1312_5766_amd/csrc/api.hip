@@ -333,11 +333,12 @@ static int enqueue_round(strads_lasso *top, bool more_follows)
     else HIP_TRY(launch_dots_dense(h));
     MARK(STRADS_STAGE_RESIDUAL);
     if (csc) HIP_TRY(launch_residual_csc(h));
-    else if (geno) HIP_TRY(launch_residual_geno(h));
     else {
         // the round that follows at once gets its key pass from extra workgroups of this round's last kernel
         bool done = false;
-        HIP_TRY(launch_residual_dense(h, more_follows && top->early_keys != 0, &done));
+        const bool want = more_follows && top->early_keys != 0;
+        if (geno) HIP_TRY(launch_residual_geno(h, want, &done));
+        else HIP_TRY(launch_residual_dense(h, want, &done));
         top->next_keys_done = done ? 1 : 0;
     }
     MARK(STRADS_N_STAGES);

@@ -400,7 +400,7 @@ hipError_t launch_kkt_geno(strads_lasso *h, float *g_or_null)
 }
 #undef STRADS_GENO_DOTS
 
-hipError_t launch_residual_geno(strads_lasso *h)
+hipError_t launch_residual_geno(strads_lasso *h, bool want_next_keys, bool *next_keys_done)
 {
     const int64_t words = geno_words(h->cfg.n);
     const int G = residual_groups(16 * words / 4, h->L);    // row blocks here hold 4096 rows, the dense ones 1024
@@ -410,7 +410,7 @@ hipError_t launch_residual_geno(strads_lasso *h)
                        h->cfg.col_mean, h->cfg.col_scale, h->Npad, h->at<int32_t>(h->ws.kept),
                        h->at<float>(h->ws.delta), h->at<RoundScalars>(h->ws.scalars), part);
     const hipError_t e = hipGetLastError();
-    return e != hipSuccess ? e : launch_residual_apply(h, G);     // stage 2 is shared with the dense path
+    return e != hipSuccess ? e : launch_residual_apply(h, G, want_next_keys, next_keys_done);     // stage 2 is shared with the dense path
 }
 
 } // namespace strads

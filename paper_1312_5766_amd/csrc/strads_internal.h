@@ -103,8 +103,8 @@ struct strads_lasso {
     int32_t split_user; // tuning override (0 = automatic)
     int32_t dots_with_gram;  // short lists: every candidate's x_j^T r rides along with the Gram launch and the filter's
                              // workgroup commits B_1 (tuning "dots_with_gram", default 1; see dots_ride_with_gram)
-    int32_t early_keys;      // rounds enqueued back to back: the next round's key pass rides with the one-kernel residual
-                             // update (tuning "early_keys", default 1; one scheduler only)
+    int32_t early_keys;      // rounds enqueued back to back: the next round's key pass rides with the last kernel of the
+                             // residual update (tuning "early_keys", default 1; one scheduler, dense and packed designs)
     int32_t next_keys_done;  // the round about to be enqueued already has its keys and first histogram
     int32_t residual_fused;  // lists of at most 1024 candidates update the residual in one kernel (tuning "residual_fused", default 1)
     int32_t jobtab_on;  // the Gram workgroups take their jobs from ws.jobtab (tuning "gram_xcd_map", default 1)
@@ -169,7 +169,7 @@ struct KeysArgs;
 KeysArgs keys_args(strads_lasso *h);                      // arguments of pass 1 of the selection
 // want_next_keys: another round follows at once; *next_keys_done: its key pass rode along (one scheduler, short lists)
 hipError_t launch_residual_dense(strads_lasso *h, bool want_next_keys, bool *next_keys_done);                         // r -= X_B delta_B
-hipError_t launch_residual_apply(strads_lasso *h, int groups);             // r -= sum of the groups' partial sums
+hipError_t launch_residual_apply(strads_lasso *h, int groups, bool want_next_keys, bool *next_keys_done);   // r -= sum of the groups' partial sums
 int residual_groups(int64_t n, int32_t l);
 hipError_t launch_objective(strads_lasso *h);                              // -> objout
 hipError_t launch_logistic_weights(strads_lasso *h);                       // r (= -X beta) -> w
@@ -202,7 +202,7 @@ hipError_t filter_prepare();
 inline int64_t geno_words(int64_t n) { return (n + 63) / 64 * 4; }   // 32-bit words per column
 hipError_t launch_dots_geno(strads_lasso *h);
 hipError_t launch_dots_cand_geno(strads_lasso *h);
-hipError_t launch_residual_geno(strads_lasso *h);
+hipError_t launch_residual_geno(strads_lasso *h, bool want_next_keys, bool *next_keys_done);
 hipError_t launch_kkt_geno(strads_lasso *h, float *g_or_null);
 // CSC design
 hipError_t launch_gram_csc(strads_lasso *h);

@@ -151,9 +151,16 @@ __global__ __launch_bounds__(256) void k_residual_partial(const float *__restric
 
 // stage 2: r[i] -= sum_g part[g][i], groups in order (a kernel boundary, not an in-kernel fence,
 // makes the partial sums visible: a device-wide fence would write back every L2 of the 8 dies)
+//
+// Workgroups past res_blocks (there are some when another round follows at once, one scheduler) make
+// the next round's key pass, as in k_residual_fused.
 __global__ __launch_bounds__(256) void k_residual_apply(const float *__restrict__ part, int G, int64_t N, int64_t Npad,
-                                                        float *__restrict__ r)
+                                                        float *__restrict__ r, uint32_t res_blocks, KeysArgs next_keys)
 {
+    if (blockIdx.x >= res_blocks) {
+        keys_hist_block(next_keys, blockIdx.x - res_blocks, gridDim.x - res_blocks);
+        return;
+    }
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= N) return;
     float s = 0.f;
@@ -515,13 +522,22 @@ hipError_t launch_residual_dense(strads_lasso *h, bool want_next_keys, bool *nex
         hipLaunchKernelGGL(k_residual_partial<false>, grid, dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->Npad,
                            h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc, part);
     const hipError_t e = hipGetLastError();
-    return e != hipSuccess ? e : launch_residual_apply(h, G);
+    return e != hipSuccess ? e : launch_residual_apply(h, G, want_next_keys, next_keys_done);
 }
 
-hipError_t launch_residual_apply(strads_lasso *h, int groups)
+hipError_t launch_residual_apply(strads_lasso *h, int groups, bool want_next_keys, bool *next_keys_done)
 {
-    hipLaunchKernelGGL(k_residual_apply, dim3((unsigned)((h->cfg.n + 255) / 256)), dim3(256), 0, h->stream,
-                       h->at<float>(h->ws.rpart), groups, h->cfg.n, h->Npad, h->at<float>(h->ws.r));
+    const unsigned res_blocks = (unsigned)((h->cfg.n + 255) / 256);
+    unsigned key_blocks = 0;
+    *next_keys_done = false;
+    if (want_next_keys && h->n_lanes == 1) {
+        key_blocks = (unsigned)((h->Js + 1023) / 1024);             // four keys per thread, at most 256 workgroups
+        if (key_blocks > 256u) key_blocks = 256u;
+        *next_keys_done = true;
+    }
+    hipLaunchKernelGGL(k_residual_apply, dim3(res_blocks + key_blocks), dim3(256), 0, h->stream,
+                       h->at<float>(h->ws.rpart), groups, h->cfg.n, h->Npad, h->at<float>(h->ws.r), res_blocks,
+                       keys_args(h));
     return hipGetLastError();
 }
 
