@@ -250,8 +250,8 @@ int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, i
  *                   launch, and the filter's workgroup applies eq. (2) to the kept ones; 0: a kernel
  *                   after the filter takes the products for the kept set only.  Identical results.
  *   "early_keys"     1 (default): when rounds are enqueued back to back (strads_lasso_run) with one scheduler,
- *                   the launch of the round's last kernel (the residual update of a dense or packed
- *                   design) also carries the next round's key pass; 0: every round starts with its own
+ *                   the launch of the round's last kernel (of the residual update) also carries the next
+ *                   round's key pass; 0: every round starts with its own
  *                   key pass.  Identical results.
  *   "residual_fused" 1 (default): dense designs with l_prime <= 4096 apply r -= X_B delta_B in one
  *                   kernel; 0: always the two-stage update (partial sums per column group, then their

@@ -332,12 +332,12 @@ static int enqueue_round(strads_lasso *top, bool more_follows)
     else if (geno) HIP_TRY(launch_dots_geno(h));
     else HIP_TRY(launch_dots_dense(h));
     MARK(STRADS_STAGE_RESIDUAL);
-    if (csc) HIP_TRY(launch_residual_csc(h));
-    else {
+    {
         // the round that follows at once gets its key pass from extra workgroups of this round's last kernel
         bool done = false;
         const bool want = more_follows && top->early_keys != 0;
-        if (geno) HIP_TRY(launch_residual_geno(h, want, &done));
+        if (csc) HIP_TRY(launch_residual_csc(h, want, &done));
+        else if (geno) HIP_TRY(launch_residual_geno(h, want, &done));
         else HIP_TRY(launch_residual_dense(h, want, &done));
         top->next_keys_done = done ? 1 : 0;
     }

@@ -15,6 +15,7 @@
 //
 //   dots / KKT       one wavefront per column: 8 bytes per nonzero streamed, r gathered from L2.
 #include "strads_internal.h"
+#include "keys.h"
 
 namespace strads {
 
@@ -313,9 +314,16 @@ __global__ __launch_bounds__(256) void k_csc_residual_acc(const float *__restric
         atomicAdd((unsigned long long *)&racc[row_idx[p]], (unsigned long long)fix40(val[p], d));
 }
 
+// Workgroups past res_blocks (there are some when another round follows at once, one scheduler) make the
+// next round's key pass: it needs delta beta as this round leaves it and nothing this kernel writes.
 __global__ __launch_bounds__(256) void k_csc_residual_apply(long long *__restrict__ racc, int64_t N,
-                                                            float *__restrict__ r)
+                                                            float *__restrict__ r, uint32_t res_blocks,
+                                                            KeysArgs next_keys)
 {
+    if (blockIdx.x >= res_blocks) {
+        keys_hist_block(next_keys, blockIdx.x - res_blocks, gridDim.x - res_blocks);
+        return;
+    }
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= N) return;
     const long long v = racc[i];
@@ -409,14 +417,22 @@ hipError_t launch_dots_csc(strads_lasso *h)
     return hipGetLastError();
 }
 
-hipError_t launch_residual_csc(strads_lasso *h)
+hipError_t launch_residual_csc(strads_lasso *h, bool want_next_keys, bool *next_keys_done)
 {
     const CscScratch s = csc_carve(h);
     hipLaunchKernelGGL(k_csc_residual_acc, dim3((h->L + 3) / 4), dim3(256), 0, h->stream, h->cfg.x, h->cfg.row_idx,
                        h->cfg.col_ptr, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta),
                        h->at<RoundScalars>(h->ws.scalars), s.racc);
-    hipLaunchKernelGGL(k_csc_residual_apply, dim3((unsigned)((h->cfg.n + 255) / 256)), dim3(256), 0, h->stream, s.racc,
-                       h->cfg.n, h->at<float>(h->ws.r));
+    const unsigned res_blocks = (unsigned)((h->cfg.n + 255) / 256);
+    unsigned key_blocks = 0;
+    *next_keys_done = false;
+    if (want_next_keys && h->n_lanes == 1) {
+        key_blocks = (unsigned)((h->Js + 1023) / 1024);             // four keys per thread, at most 256 workgroups
+        if (key_blocks > 256u) key_blocks = 256u;
+        *next_keys_done = true;
+    }
+    hipLaunchKernelGGL(k_csc_residual_apply, dim3(res_blocks + key_blocks), dim3(256), 0, h->stream, s.racc,
+                       h->cfg.n, h->at<float>(h->ws.r), res_blocks, keys_args(h));
     return hipGetLastError();
 }
 

@@ -104,7 +104,7 @@ struct strads_lasso {
     int32_t dots_with_gram;  // short lists: every candidate's x_j^T r rides along with the Gram launch and the filter's
                              // workgroup commits B_1 (tuning "dots_with_gram", default 1; see dots_ride_with_gram)
     int32_t early_keys;      // rounds enqueued back to back: the next round's key pass rides with the last kernel of the
-                             // residual update (tuning "early_keys", default 1; one scheduler, dense and packed designs)
+                             // residual update (tuning "early_keys", default 1; one scheduler)
     int32_t next_keys_done;  // the round about to be enqueued already has its keys and first histogram
     int32_t residual_fused;  // lists of at most 1024 candidates update the residual in one kernel (tuning "residual_fused", default 1)
     int32_t jobtab_on;  // the Gram workgroups take their jobs from ws.jobtab (tuning "gram_xcd_map", default 1)
@@ -208,7 +208,7 @@ hipError_t launch_kkt_geno(strads_lasso *h, float *g_or_null);
 hipError_t launch_gram_csc(strads_lasso *h);
 hipError_t launch_dots_csc(strads_lasso *h);
 hipError_t launch_dots_cand_csc(strads_lasso *h);         // dynamic dependencies: all candidates, nothing committed
-hipError_t launch_residual_csc(strads_lasso *h);
+hipError_t launch_residual_csc(strads_lasso *h, bool want_next_keys, bool *next_keys_done);
 hipError_t launch_kkt_csc(strads_lasso *h, float *g_or_null);
 size_t csc_scratch_bytes(int64_t n, int32_t l, int32_t max_col_nnz);
 hipError_t csc_prepare();
