@@ -14,9 +14,7 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;                                   // lane 0 holds the sum
 }
 
-// dot product of one column with r by TPC threads (TPC = 64: one wavefront, 128: half a workgroup,
-// 256: a workgroup).  TPC > 64: every thread of the workgroup must make the call (there is a barrier
-// inside), and red is the group's own TPC/64 floats.
+// dot product of one column with r by TPC threads (TPC = 64: one wavefront, 256: a workgroup)
 template <int TPC, bool VEC4>
 __device__ __forceinline__ float column_dot(const float *__restrict__ x, const float *__restrict__ r, int64_t N,
                                             int t, float *red /* TPC/64 floats of LDS, TPC > 64 only */)
@@ -64,7 +62,7 @@ __device__ __forceinline__ float soft_threshold(float a, float lambda)
 // candidates per workgroup `block`.
 struct CandDots {
     int32_t L;                  // candidates; 0: none wanted
-    int32_t wide;               // 0: a wavefront per candidate, 1: a workgroup, 2: half a workgroup
+    int32_t wide;               // 1: a workgroup per candidate, 0: a wavefront per candidate
     const float *r;
     float lambda, step;
     const float *beta;
@@ -77,20 +75,12 @@ __device__ __forceinline__ void cand_dots_block(const float *__restrict__ X, int
                                                 float *red)
 {
     constexpr int CPB = 256 / TPC;
-    const int group = (int)threadIdx.x / TPC;
-    int c = block * CPB + group;
-    bool live = true;
-    if (TPC == 128) {                           // the other half of the workgroup meets the barrier: no early exit
-        live = c < cd.L;
-        c = live ? c : cd.L - 1;
-    } else if (c >= cd.L) {
-        return;                                 // TPC = 256: whole workgroup; TPC = 64: whole wavefront
-    }
+    const int c = block * CPB + (int)threadIdx.x / TPC;
+    if (c >= cd.L) return;                      // TPC = 256: whole workgroup; TPC = 64: whole wavefront
     const int32_t j = cand[c];
     const float b = cd.beta[j];                 // requested with the column, not after the reduction
-    const float s = column_dot<TPC, VEC4>(X + (int64_t)j * N, cd.r, N, (int)threadIdx.x % TPC,
-                                          red + group * (TPC / 64));
-    if (threadIdx.x % TPC == 0 && live) {
+    const float s = column_dot<TPC, VEC4>(X + (int64_t)j * N, cd.r, N, (int)threadIdx.x % TPC, red);
+    if (threadIdx.x % TPC == 0) {
         const float nb = soft_threshold(s * cd.step + b, cd.lambda * cd.step);
         cd.zc[c] = s;
         cd.nbc[c] = nb;

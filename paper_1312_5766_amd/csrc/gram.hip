@@ -509,8 +509,7 @@ __global__ __launch_bounds__(256, kGramOcc) void k_gram_tiles(const float *__res
     if ((int32_t)blockIdx.x >= n_jobs) {
         if constexpr (LOAD != kLoadGeno2) {
             const int block = (int)blockIdx.x - n_jobs;
-            if (cd.wide == 2) cand_dots_block<128, LOAD == kLoadVec4>(X, N, cand, cd, block, smem);
-            else if (cd.wide) cand_dots_block<256, LOAD == kLoadVec4>(X, N, cand, cd, block, smem);
+            if (cd.wide) cand_dots_block<256, LOAD == kLoadVec4>(X, N, cand, cd, block, smem);
             else cand_dots_block<64, LOAD == kLoadVec4>(X, N, cand, cd, block, smem);
         }
         return;
@@ -868,7 +867,7 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
     unsigned extra = 0;
     if (dots_ride_with_gram(h)) {
         cd = cand_dots_args(h);
-        extra = dots_blocks(cd.wide, cd.L);
+        extra = cd.wide ? (unsigned)cd.L : (unsigned)((cd.L + 3) / 4);
     }
     const dim3 grid((unsigned)n_jobs + extra);
     const int32_t *jobtab = h->jobtab_on ? reinterpret_cast<const int32_t *>(h->base + h->ws.jobtab) : nullptr;

@@ -189,15 +189,6 @@ inline bool dots_ride_with_gram(const strads_lasso *h)
     return h->dots_with_gram && h->cfg.deps == STRADS_DEPS_STATIC && h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR &&
            h->n_lanes == 1 && h->L <= kShortList;
 }
-// How many threads take one column's dot product with r: a wavefront for short columns (mode 0), half a
-// workgroup for columns of moderate length (mode 2: a list of 1000 then fits the chip's 512 slots of
-// the Gram launch in one go, and that is what its extra workgroups add to the launch), a workgroup
-// for long ones (mode 1).  The same rule everywhere, so that the routes give the same bits.
-inline int dots_mode(int64_t n) { return n <= 2048 ? 0 : n <= 16384 ? 2 : 1; }
-inline unsigned dots_blocks(int mode, int32_t l)
-{
-    return mode == 2 ? (unsigned)((l + 1) / 2) : mode == 1 ? (unsigned)l : (unsigned)((l + 3) / 4);
-}
 struct CandDots;
 CandDots cand_dots_args(strads_lasso *h);                 // arguments of the candidates' tentative updates
 hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null);            // -> scalars.kkt_max_bits

@@ -35,21 +35,12 @@ __global__ __launch_bounds__(256) void k_dots_update(const float *__restrict__ X
 {
     __shared__ float red[4];
     constexpr int CPB = 256 / TPC;              // columns per workgroup
-    const int group = threadIdx.x / TPC;
-    const int nk = sc->n_kept;
-    int c = blockIdx.x * CPB + group;
-    bool live = true;
-    if (TPC == 128) {                           // the other half of the workgroup meets the barrier: no early exit
-        if (blockIdx.x * CPB >= nk) return;     // (the whole workgroup)
-        live = c < nk;
-        c = live ? c : nk - 1;
-    } else if (c >= nk) {
-        return;                                 // TPC = 256: whole workgroup; TPC = 64: whole wavefront
-    }
+    const int c = blockIdx.x * CPB + threadIdx.x / TPC;
+    if (c >= sc->n_kept) return;                // TPC = 256: whole workgroup; TPC = 64: whole wavefront
     const int32_t j = kept[c];
     const float b = beta[j];                    // requested with the column, not after the reduction
-    const float s = column_dot<TPC, VEC4>(X + (int64_t)j * N, r, N, threadIdx.x % TPC, red + group * (TPC / 64));
-    if (threadIdx.x % TPC == 0 && live) {
+    const float s = column_dot<TPC, VEC4>(X + (int64_t)j * N, r, N, threadIdx.x % TPC, red);
+    if (threadIdx.x % TPC == 0) {
         const float nb = soft_threshold(s * step + b, lambda * step);     // step = 1: eq. (2) as printed
         const float d = nb - b;
         z[c] = s;
@@ -458,12 +449,11 @@ hipError_t launch_dots_dense(strads_lasso *h)
     const RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     const float *r = dots_vector(h);
     const int32_t *kept = h->at<int32_t>(h->ws.kept);
-    const int mode = dots_mode(h->cfg.n);
-    const unsigned grid = dots_blocks(mode, h->L);
+    const bool wide = h->cfg.n > 2048;
+    const unsigned grid = wide ? (unsigned)h->L : (unsigned)((h->L + 3) / 4);
 #define STRADS_DOTS(TPC, V) hipLaunchKernelGGL((k_dots_update<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, kept, sc, r, h->cfg.lambda, h->step_scale, h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.z), h->at<float>(h->ws.delta))
-    if (mode == 2)      { if (h->vec4) STRADS_DOTS(128, true); else STRADS_DOTS(128, false); }
-    else if (mode == 1) { if (h->vec4) STRADS_DOTS(256, true); else STRADS_DOTS(256, false); }
-    else                { if (h->vec4) STRADS_DOTS(64, true);  else STRADS_DOTS(64, false); }
+    if (wide) { if (h->vec4) STRADS_DOTS(256, true); else STRADS_DOTS(256, false); }
+    else      { if (h->vec4) STRADS_DOTS(64, true);  else STRADS_DOTS(64, false); }
 #undef STRADS_DOTS
     return hipGetLastError();
 }
@@ -472,7 +462,7 @@ CandDots cand_dots_args(strads_lasso *h)
 {
     CandDots cd;
     cd.L = h->L;
-    cd.wide = dots_mode(h->cfg.n);
+    cd.wide = h->cfg.n > 2048 ? 1 : 0;
     cd.r = dots_vector(h);
     cd.lambda = h->cfg.lambda;
     cd.step = h->step_scale;
@@ -485,12 +475,12 @@ CandDots cand_dots_args(strads_lasso *h)
 
 hipError_t launch_dots_cand(strads_lasso *h)
 {
+    const bool wide = h->cfg.n > 2048;
+    const unsigned grid = wide ? (unsigned)h->L : (unsigned)((h->L + 3) / 4);
     const CandDots cd = cand_dots_args(h);
-    const unsigned grid = dots_blocks(cd.wide, h->L);
 #define STRADS_DOTS_CAND(TPC, V) hipLaunchKernelGGL((k_dots_cand<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), cd)
-    if (cd.wide == 2)  { if (h->vec4) STRADS_DOTS_CAND(128, true); else STRADS_DOTS_CAND(128, false); }
-    else if (cd.wide)  { if (h->vec4) STRADS_DOTS_CAND(256, true); else STRADS_DOTS_CAND(256, false); }
-    else               { if (h->vec4) STRADS_DOTS_CAND(64, true);  else STRADS_DOTS_CAND(64, false); }
+    if (wide) { if (h->vec4) STRADS_DOTS_CAND(256, true); else STRADS_DOTS_CAND(256, false); }
+    else      { if (h->vec4) STRADS_DOTS_CAND(64, true);  else STRADS_DOTS_CAND(64, false); }
 #undef STRADS_DOTS_CAND
     return hipGetLastError();
 }
