@@ -3,18 +3,18 @@
 // one iff it conflicts with nothing kept so far.
 //
 // The walk is sequential in the kept set, so the work is arranged to keep the serial chain short.
-// One workgroup of 1024 threads takes the candidates 64 at a time (a "chunk").  `dead` (one bit
-// per candidate, in LDS) marks candidates that conflict with something already kept.
-//   * The chunk's 64 conflict rows (words at or right of the chunk's own word) live in registers,
-//     spread over the threads.  The mask was written by workgroups all over the chip, so its first
-//     read by this workgroup comes from HBM, about a microsecond away, while a chunk is decided in
-//     a fraction of that: the rows are therefore fetched kFilterAhead chunks ahead of their use.
-//     Only the chunk's 64x64 diagonal block goes to LDS, for wavefront 0.
+// One small workgroup takes the candidates 64 at a time (a "chunk").  `dead` (one bit per candidate,
+// in LDS) marks candidates that conflict with something already kept.
 //   * Wavefront 0 decides the chunk: candidates that are alive and have no conflict with another
 //     alive candidate of the chunk are kept at once; only the few with an in-chunk conflict are
-//     walked one by one (scalar bit operations on the diagonal block).
-//   * All threads then OR the words they hold of the newly kept candidates' rows into `dead` for
-//     later chunks.
+//     walked one by one (scalar bit operations on the chunk's 64x64 diagonal block, which its lanes
+//     load themselves).
+//   * The other wavefronts hold the chunks' conflict rows (words right of the chunk's own word) in
+//     registers and OR the rows of the newly kept candidates into `dead` for later chunks.  The mask
+//     was written by workgroups all over the chip, so its first read by this workgroup comes from
+//     memory, a microsecond or more away, while a chunk is decided in a fraction of that: the rows
+//     are fetched several chunks ahead of their use.
+// The details, and what they are there to avoid, are at k_filter.
 // Only bits (a, b) with b in a's 128-tile or right of it are read, matching what the Gram
 // kernel writes.  Bit-exact: the result depends on the conflict bits only.
 #include "strads_internal.h"
