@@ -176,7 +176,7 @@ __global__ __launch_bounds__(256) void k_residual_apply(const float *__restrict_
     r[i] -= s;
 }
 
-// The same update in one kernel, for candidate lists of at most 1024: a workgroup of 16 wavefronts
+// The same update in one kernel, for candidate lists of at most 4096: a workgroup of 16 wavefronts
 // owns 64 rows (one per lane).  Wavefront w sums the movers w, w+16, ... of the kept list in list
 // order, the 16 sums meet in LDS in wavefront order, and the first wavefront subtracts the total
 // from r.  No partial sums leave the chip and one kernel boundary is saved, which is what a round
