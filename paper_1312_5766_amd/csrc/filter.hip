@@ -75,11 +75,25 @@ __device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_m
             if (lane == 0 && a < nwords * 64) keepw[a >> 6] = m;
         }
     }
-    for (int32_t a0 = K * nthreads; a0 < nwords * 64; a0 += nthreads) {
-        const int32_t a = a0 + tid;
-        const bool keep = a < L && (cm.dc[a] == 0.f || mkept[a]);
-        const uint64_t m = __ballot(keep);
-        if (lane == 0 && a < nwords * 64) keepw[a >> 6] = m;
+    // (the rest of a long list four positions per thread at a time, their loads requested together: one
+    // trip to memory per four positions instead of one per position)
+    constexpr int kBatch = 4;
+    for (int32_t a0 = K * nthreads; a0 < nwords * 64; a0 += kBatch * nthreads) {
+        float d4[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int32_t a = a0 + u * nthreads + tid;
+            d4[u] = a < L ? cm.dc[a] : 1.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int32_t a = a0 + u * nthreads + tid;
+            if (a0 + u * nthreads < nwords * 64) {                  // whole wavefronts
+                const bool keep = a < L && (d4[u] == 0.f || mkept[a]);
+                const uint64_t m = __ballot(keep);
+                if (lane == 0 && a < nwords * 64) keepw[a >> 6] = m;
+            }
+        }
     }
     __syncthreads();
     if (tid < 64) {                                                 // at most 128 words: two per lane
@@ -112,19 +126,29 @@ __device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_m
         cm.beta[j] = e_nbc[k];
         cm.dbeta[j] = fabsf(e_dc[k]);
     }
-    for (int32_t a = tid + K * nthreads; a < L; a += nthreads) {
-        const uint64_t w = keepw[a >> 6];
-        if (!((w >> (a & 63)) & 1ull)) continue;
-        const int32_t idx = before[a >> 6] + __popcll(w & ((1ull << (a & 63)) - 1ull));
-        if (idx >= cap) continue;
-        const int32_t j = cm.cand[a];
-        const float d = cm.dc[a];
-        cm.kept_pos[idx] = a;
-        cm.kept[idx] = j;
-        cm.z[idx] = cm.zc[a];
-        cm.delta[idx] = d;
-        cm.beta[j] = cm.nbc[a];
-        cm.dbeta[j] = fabsf(d);
+    for (int32_t a0 = tid + K * nthreads; a0 < L; a0 += kBatch * nthreads) {
+        int32_t j4[kBatch];
+        float d4[kBatch], z4[kBatch], nb4[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int32_t a = a0 + u * nthreads, at = a < L ? a : 0;
+            j4[u] = cm.cand[at]; d4[u] = cm.dc[at]; z4[u] = cm.zc[at]; nb4[u] = cm.nbc[at];
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int32_t a = a0 + u * nthreads;
+            if (a >= L) continue;
+            const uint64_t w = keepw[a >> 6];
+            if (!((w >> (a & 63)) & 1ull)) continue;
+            const int32_t idx = before[a >> 6] + __popcll(w & ((1ull << (a & 63)) - 1ull));
+            if (idx >= cap) continue;
+            cm.kept_pos[idx] = a;
+            cm.kept[idx] = j4[u];
+            cm.z[idx] = z4[u];
+            cm.delta[idx] = d4[u];
+            cm.beta[j4[u]] = nb4[u];
+            cm.dbeta[j4[u]] = fabsf(d4[u]);
+        }
     }
     if (tid == 0) {
         const int32_t total = before[kMaxWords];
@@ -355,23 +379,36 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
         }
         a_first = tid + kEarly * kThreads;
     }
-    for (int32_t a = a_first; a < a_end; a += kThreads) {
-        const uint64_t w = keptw_all[a >> 6];
-        if (!((w >> (a & 63)) & 1ull)) continue;
-        const int32_t i = nkb[a >> 6] + __popcll(w & ((1ull << (a & 63)) - 1ull));
-        kept_pos[i] = a;
-        if (cm.on == kCommitKept) {
-            const int32_t j = cand[a];
-            const float d = cm.dc[a];
-            kept[i] = j;
-            cm.z[i] = cm.zc[a];
-            cm.delta[i] = d;
-            cm.beta[j] = cm.nbc[a];
-            cm.dbeta[j] = fabsf(d);
-        } else if (cm.on == kCommitDynamic) {
-            mkept[cm.mpos[a]] = 1;                // a is a position in the mover list here
-        } else {
-            kept[i] = cand[a];
+    // (four positions per thread at a time, their loads requested together)
+    constexpr int kBatch = 4;
+    for (int32_t a0 = a_first; a0 < a_end; a0 += kBatch * kThreads) {
+        int32_t j4[kBatch];                       // the candidate's column; dynamic dependencies: its place in the candidate list
+        float d4[kBatch], z4[kBatch], nb4[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int32_t a = a0 + u * kThreads, at = a < a_end ? a : 0;
+            j4[u] = cm.on == kCommitDynamic ? cm.mpos[at] : cand[at];
+            if (cm.on == kCommitKept) { d4[u] = cm.dc[at]; z4[u] = cm.zc[at]; nb4[u] = cm.nbc[at]; }
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int32_t a = a0 + u * kThreads;
+            if (a >= a_end) continue;
+            const uint64_t w = keptw_all[a >> 6];
+            if (!((w >> (a & 63)) & 1ull)) continue;
+            const int32_t i = nkb[a >> 6] + __popcll(w & ((1ull << (a & 63)) - 1ull));
+            kept_pos[i] = a;
+            if (cm.on == kCommitKept) {
+                kept[i] = j4[u];
+                cm.z[i] = z4[u];
+                cm.delta[i] = d4[u];
+                cm.beta[j4[u]] = nb4[u];
+                cm.dbeta[j4[u]] = fabsf(d4[u]);
+            } else if (cm.on == kCommitDynamic) {
+                mkept[j4[u]] = 1;                 // a is a position in the mover list here
+            } else {
+                kept[i] = j4[u];
+            }
         }
     }
     if (cm.on == kCommitDynamic) {
