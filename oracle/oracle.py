@@ -66,6 +66,10 @@ def lib():
         L.oracle_draw.restype = i32
         L.oracle_gram_dense.argtypes = [i64, vp, vp, i32, vp]
         L.oracle_gram_dense.restype = None
+        L.oracle_gram_rows_dense.argtypes = [i64, vp, vp, i32, vp, i32, vp]
+        L.oracle_gram_rows_dense.restype = None
+        L.oracle_gram_pairs_dense.argtypes = [i64, vp, vp, vp, vp, i64, vp]
+        L.oracle_gram_pairs_dense.restype = None
         L.oracle_gram_csc.argtypes = [vp, vp, vp, vp, i32, vp]
         L.oracle_gram_csc.restype = None
         L.oracle_filter.argtypes = [i32, vp, f32, i32, vp]
@@ -153,6 +157,24 @@ def gram_dense(x_cols, cand) -> np.ndarray:
     return G
 
 
+def gram_rows_dense(x_cols, cand, rows) -> np.ndarray:
+    """Rows `rows` (positions into cand) of the candidate Gram: (len(rows), len(cand)) fp32."""
+    x, c, rw = _arr(x_cols, np.float32), _arr(cand, np.int32), _arr(rows, np.int32)
+    out = np.empty((rw.shape[0], c.shape[0]), np.float32)
+    lib().oracle_gram_rows_dense(x.shape[1], _p(x), _p(c), c.shape[0], _p(rw), rw.shape[0], _p(out))
+    return out
+
+
+def gram_pairs_dense(x_cols, cand, pa, pb) -> np.ndarray:
+    """Entries (pa[t], pb[t]) (positions into cand) of the candidate Gram."""
+    x, c = _arr(x_cols, np.float32), _arr(cand, np.int32)
+    a, b = _arr(pa, np.int32), _arr(pb, np.int32)
+    assert a.shape == b.shape
+    out = np.empty(a.shape[0], np.float32)
+    lib().oracle_gram_pairs_dense(x.shape[1], _p(x), _p(c), _p(a), _p(b), a.shape[0], _p(out))
+    return out
+
+
 def gram_csc(values, row_idx, col_ptr, cand) -> np.ndarray:
     v, ri, cp, c = _arr(values, np.float32), _arr(row_idx, np.int32), _arr(col_ptr, np.int64), _arr(cand, np.int32)
     L = c.shape[0]
@@ -167,6 +189,59 @@ def greedy_filter(G, rho, p_max=0) -> np.ndarray:
     kept = np.empty(max(L, 1), np.int32)
     k = lib().oracle_filter(L, _p(g), np.float32(rho), int(p_max), _p(kept))
     return kept[:k].copy()
+
+
+def dots_dense(x_cols, cols, r) -> np.ndarray:
+    """x_j^T r (fp64) for the listed columns of a dense design; x_cols: (J, N) fp32, row j = covariate x_j."""
+    x, c, rr = _arr(x_cols, np.float32), _arr(cols, np.int32), _arr(r, np.float32)
+    z = np.empty(c.shape[0], np.float64)
+    lib().oracle_dots_dense(x.shape[1], _p(x), _p(c), c.shape[0], _p(rr), _p(z))
+    return z
+
+
+def dots_csc(values, row_idx, col_ptr, cols, r) -> np.ndarray:
+    v, ri, cp = _arr(values, np.float32), _arr(row_idx, np.int32), _arr(col_ptr, np.int64)
+    c, rr = _arr(cols, np.int32), _arr(r, np.float32)
+    z = np.empty(c.shape[0], np.float64)
+    lib().oracle_dots_csc(_p(v), _p(ri), _p(cp), _p(c), c.shape[0], _p(rr), _p(z))
+    return z
+
+
+def update(cols, z, lam, beta, dbeta, inv_kappa: float = 1.0) -> np.ndarray:
+    """eq. (2) and Step 4 for the listed coordinates, in place on beta and dbeta (fp32 arrays that must be
+    C-contiguous); returns the changes (fp64).  inv_kappa: 1 for the squared loss, 4 for the logistic loss."""
+    c, zz = _arr(cols, np.int32), _arr(z, np.float64)
+    assert beta.dtype == np.float32 and dbeta.dtype == np.float32 and beta.flags.c_contiguous and dbeta.flags.c_contiguous
+    delta = np.empty(c.shape[0], np.float64)
+    lib().oracle_update(c.shape[0], _p(c), _p(zz), np.float32(lam), float(inv_kappa), _p(beta), _p(dbeta), _p(delta))
+    return delta
+
+
+def residual_dense(x_cols, cols, delta, r) -> None:
+    """r <- r - sum_c x_{cols[c]} delta[c], in place on r (fp32, C-contiguous)."""
+    x, c, d = _arr(x_cols, np.float32), _arr(cols, np.int32), _arr(delta, np.float64)
+    assert r.dtype == np.float32 and r.flags.c_contiguous and r.shape[0] == x.shape[1]
+    lib().oracle_residual_dense(x.shape[1], _p(x), _p(c), c.shape[0], _p(d), _p(r))
+
+
+def residual_csc(values, row_idx, col_ptr, cols, delta, r) -> None:
+    v, ri, cp = _arr(values, np.float32), _arr(row_idx, np.int32), _arr(col_ptr, np.int64)
+    c, d = _arr(cols, np.int32), _arr(delta, np.float64)
+    assert r.dtype == np.float32 and r.flags.c_contiguous
+    lib().oracle_residual_csc(r.shape[0], _p(v), _p(ri), _p(cp), _p(c), c.shape[0], _p(d), _p(r))
+
+
+def logistic_weights(y, v) -> np.ndarray:
+    """w_i = y_i / (1 + exp(-y_i v_i)) from the state vector v = -X beta."""
+    yy, vv = _arr(y, np.float32), _arr(v, np.float32)
+    w = np.empty(yy.shape[0], np.float32)
+    lib().oracle_logistic_weights(yy.shape[0], _p(yy), _p(vv), _p(w))
+    return w
+
+
+def objective_logistic(y, v, beta, lam) -> float:
+    yy, vv, b = _arr(y, np.float32), _arr(v, np.float32), _arr(beta, np.float32)
+    return float(lib().oracle_objective_logistic(yy.shape[0], _p(yy), _p(vv), b.shape[0], _p(b), np.float32(lam)))
 
 
 def soft_threshold(a: float, lam: float) -> float:

@@ -196,6 +196,37 @@ void oracle_gram_dense(int64_t N, const float *X, const int32_t *cand, int32_t L
     }
 }
 
+/* The same dependencies for chosen rows of G only (row rows[t] against every candidate; out is
+ * n_rows x L, row-major), and for chosen pairs (out[t] = x_{cand[pa[t]]}^T x_{cand[pb[t]]}): the same
+ * definition, for candidate sets whose whole Gram would take the CPU minutes. */
+void oracle_gram_rows_dense(int64_t N, const float *X, const int32_t *cand, int32_t L,
+                            const int32_t *rows, int32_t n_rows, float *out)
+{
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int32_t t = 0; t < n_rows; ++t) {
+        for (int32_t b = 0; b < L; ++b) {
+            const float *xa = X + (int64_t)cand[rows[t]] * N;
+            const float *xb = X + (int64_t)cand[b] * N;
+            double s = 0.0;
+            for (int64_t i = 0; i < N; ++i) s += (double)xa[i] * (double)xb[i];
+            out[(int64_t)t * L + b] = (float)s;
+        }
+    }
+}
+
+void oracle_gram_pairs_dense(int64_t N, const float *X, const int32_t *cand, const int32_t *pa,
+                             const int32_t *pb, int64_t n_pairs, float *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n_pairs; ++t) {
+        const float *xa = X + (int64_t)cand[pa[t]] * N;
+        const float *xb = X + (int64_t)cand[pb[t]] * N;
+        double s = 0.0;
+        for (int64_t i = 0; i < N; ++i) s += (double)xa[i] * (double)xb[i];
+        out[t] = (float)s;
+    }
+}
+
 /* CSC design: column j holds rows row_idx[col_ptr[j] .. col_ptr[j+1]) in
  * increasing order with the matching values. */
 void oracle_gram_csc(const float *val, const int32_t *row_idx, const int64_t *col_ptr,

@@ -34,6 +34,22 @@ def test_gram_is_not_transposed_or_shifted(oracle_mod):
     assert np.allclose(G, ref, atol=1e-7)
 
 
+def test_gram_rows_and_pairs_are_the_same_numbers_as_the_whole_gram(oracle_mod):
+    p = si.make("c5_dense_duplicates", n=300, j=400, nnz=10, l_prime=50)
+    x = p.x.numpy()
+    rng = np.random.default_rng(4)
+    cand = rng.permutation(p.j)[:83].astype(np.int32)
+    G = oracle_mod.gram_dense(x, cand)
+    rows = np.array([82, 0, 17, 17, 40], np.int32)
+    R = oracle_mod.gram_rows_dense(x, cand, rows)
+    assert R.shape == (5, 83) and np.array_equal(R, G[rows])
+    pa, pb = rng.integers(0, 83, 500).astype(np.int32), rng.integers(0, 83, 500).astype(np.int32)
+    assert np.array_equal(oracle_mod.gram_pairs_dense(x, cand, pa, pb), G[pa, pb])
+    # and against an fp64 matmul, so that a transposed or shifted index in the row variant shows
+    xs = x[cand].astype(np.float64)
+    assert np.abs(R - (xs[rows] @ xs.T)).max() < 1e-7
+
+
 def test_gram_csc_equals_dense(oracle_mod):
     p = si.make("c4_sparse_csc", n=300, j=500, nnz_per_col=12, nnz=10, l_prime=40)
     xd = si.csc_to_dense(p).numpy()

@@ -219,3 +219,70 @@ def test_forced_decisions_are_followed():
     out = s.round(forced_cand=np.array([5, 3, 9], np.int32), forced_kept_pos=np.array([0, 2], np.int32))
     assert out["cand"].tolist() == [5, 3, 9] and out["kept"].tolist() == [5, 9]
     assert s.dbeta[3] == np.float32(1e6)
+
+
+# ---- the stage functions called one by one (as the full-size GPU parity tests call them) --------
+def test_stage_functions_one_by_one_equal_the_whole_round_and_the_closed_forms():
+    from oracle import oracle as o
+    p = si.make("c5_dense_duplicates", n=150, j=240, nnz=8, l_prime=60, lam_frac=0.02)
+    x, y = p.x.numpy(), p.y.numpy()
+    s = _solver(p)
+    for _ in range(3):
+        beta0, dbeta0, r0 = s.beta.copy(), s.dbeta.copy(), s.r.copy()
+        out = s.round()
+        kept = out["kept"]
+        # dots: against an fp64 matmul with the columns as rows (a transposed or shifted operand fails it)
+        z = o.dots_dense(x, kept, r0)
+        assert np.array_equal(z, out["z"])
+        assert np.abs(z - x[kept].astype(np.float64) @ r0.astype(np.float64)).max() < 1e-12
+        # update: closed form of the soft-threshold per coordinate, nothing else touched
+        b, d = beta0.copy(), dbeta0.copy()
+        delta = o.update(kept, z, p.lam, b, d)
+        assert np.array_equal(delta, out["delta"]) and np.array_equal(b, s.beta) and np.array_equal(d, s.dbeta)
+        for c, j in enumerate(kept):
+            a = z[c] + float(beta0[j])
+            want = np.float32(math.copysign(max(abs(a) - float(np.float32(p.lam)), 0.0), a))
+            assert b[j] == want and d[j] == np.float32(abs(float(want) - float(beta0[j])))
+        untouched = np.ones(p.j, bool)
+        untouched[kept] = False
+        assert np.array_equal(b[untouched], beta0[untouched]) and np.array_equal(d[untouched], dbeta0[untouched])
+        # residual: r - X_B delta, and the invariant r = y - X beta
+        r = r0.copy()
+        o.residual_dense(x, kept, delta, r)
+        assert np.array_equal(r, s.r)
+        assert np.abs(r - (r0.astype(np.float64) - delta @ x[kept].astype(np.float64))).max() < 1e-6
+        assert np.abs(r - (y.astype(np.float64) - b.astype(np.float64) @ x.astype(np.float64))).max() < 1e-5
+    assert np.count_nonzero(s.beta) > 0
+
+
+def test_stage_functions_csc_equal_dense_and_logistic_wrappers():
+    from oracle import oracle as o
+    p = si.make("c4_sparse_csc", n=200, j=300, nnz_per_col=9, nnz=6, l_prime=40)
+    xd = si.csc_to_dense(p).numpy()
+    v, ri, cp = p.values.numpy(), p.row_idx.numpy(), p.col_ptr.numpy()
+    rng = np.random.default_rng(1)
+    cols = rng.permutation(p.j)[:37].astype(np.int32)
+    r = rng.normal(size=p.n).astype(np.float32)
+    z_s, z_d = o.dots_csc(v, ri, cp, cols, r), o.dots_dense(xd, cols, r)
+    assert np.abs(z_s - z_d).max() < 1e-12
+    delta = rng.normal(size=37)
+    r1, r2 = r.copy(), r.copy()
+    o.residual_csc(v, ri, cp, cols, delta, r1)
+    o.residual_dense(xd, cols, delta, r2)
+    assert np.abs(r1.astype(np.float64) - r2).max() < 1e-6
+    # logistic weights and objective: the textbook expressions in fp64
+    yl = np.where(rng.random(p.n) < 0.5, -1.0, 1.0).astype(np.float32)
+    w = o.logistic_weights(yl, r)
+    assert np.abs(w - yl / (1.0 + np.exp(-yl.astype(np.float64) * r))).max() < 1e-7
+    beta = rng.normal(size=p.j).astype(np.float32)
+    f = o.objective_logistic(yl, r, beta, 0.3)
+    assert f == pytest.approx(float(np.logaddexp(0.0, yl.astype(np.float64) * r).sum())
+                              + float(np.float32(0.3)) * float(np.abs(beta.astype(np.float64)).sum()), rel=1e-12)
+    # update with the logistic step (1 / curvature = 4): S(beta + 4 z, 4 lambda)
+    b, d = beta.copy(), np.zeros_like(beta)
+    zz = rng.normal(size=37) * 0.2
+    dl = o.update(cols, zz, 0.3, b, d, inv_kappa=4.0)
+    for c, j in enumerate(cols):
+        a = 4.0 * zz[c] + float(beta[j])
+        want = np.float32(math.copysign(max(abs(a) - 4.0 * float(np.float32(0.3)), 0.0), a))
+        assert b[j] == want and dl[c] == float(want) - float(beta[j])
