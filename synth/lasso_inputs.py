@@ -47,6 +47,7 @@ class LassoProblem:
     col_mean: Optional[torch.Tensor] = None   # geno2: (j,) fp32
     col_scale: Optional[torch.Tensor] = None  # geno2: (j,) fp32; x_ij = fl(fl(g_ij - mean_j) * scale_j)
     loss: str = "squared"                   # "squared" | "logistic" (then y holds labels in {-1, +1})
+    dup_src: Optional[torch.Tensor] = None  # config 5: (j,) int64, the column a duplicate was copied from, -1 elsewhere
 
     def to(self, device) -> "LassoProblem":
         kw = {}
@@ -287,7 +288,9 @@ def dense_duplicates(n=50000, j=1000000, dup_frac=0.3, dup_corr=0.9, nnz=2000, s
         e = _standardize_rows_(e)
         blk = c * x[src_of[di]].to(torch.float64) + d * e
         x[di] = _standardize_rows_(blk).to(torch.float32)
-    return _finish_dense(name, x, nnz, 0.5, 1.5, sigma, lam_frac, rho, eta, l_prime, rounds, seed, g)
+    p = _finish_dense(name, x, nnz, 0.5, 1.5, sigma, lam_frac, rho, eta, l_prime, rounds, seed, g)
+    p.dup_src = src_of
+    return p
 
 
 def sparse_csc(n=100000, j=1000000, nnz_per_col=100, nnz=1000, sigma=0.1, lam_frac=0.02,

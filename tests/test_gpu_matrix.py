@@ -1,8 +1,10 @@
 """Every combination of design layout, dependency rule, priority, shard count and loss on a small
 problem: a few teacher-forced rounds each.  The candidate list must be the oracle's own draw, bit
-for bit; the oracle then follows the GPU's (elsewhere verified) keep / mover decisions and all
-floating-point state is compared after every round.  The stage-by-stage checks of the Gram and of
-the greedy walk live in the per-feature test files; this one is about the options working together.
+for bit; the GPU's mover and keep decisions must be the oracle's own or admissible variants of them
+(a tentative change within the dot-product tolerance of zero; a Gram entry within the Gram tolerance
+of rho, tests/parity_rules.py); the oracle then follows them and all floating-point state is compared
+after every round.  The entry-by-entry checks of the Gram live in the per-feature test files; this one
+is about the options working together.
 """
 import dataclasses
 import itertools
@@ -11,7 +13,9 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import oracle as orc
 from oracle.oracle import OracleLasso
+from parity_rules import check_kept_against_oracle
 from synth import lasso_inputs as si
 from test_gpu_parity import BETA_RTOL, DOT_RTOL, OBJ_RTOL, _assert_close, _gpu, _np, _ref_candidates
 
@@ -80,14 +84,30 @@ def test_options_work_together(layout, deps, priority, shards, loss):
         lr = g.last_round()
         cand = _np(lr["cand"])
         assert np.array_equal(cand, _ref_candidates(o, dbeta0, t0)), f"candidate list (round {t})"
-        forced = dict(forced_cand=cand, forced_kept_pos=_np(lr["kept_pos"]))
-        if deps == "dynamic":
-            forced["forced_mover"] = (_np(g.last_candidates()["delta_cand"]) != 0).astype(np.uint8)
+        kept_pos = _np(lr["kept_pos"])
+        forced = dict(forced_cand=cand, forced_kept_pos=kept_pos)
+        scale = 4.0 if loss == "logistic" else 1.0
+        if deps != "none":
+            # the index decisions the oracle is about to follow are its own, or admissible variants
+            Gref = orc.gram_csc(o.x, o.row_idx, o.col_ptr, cand) if o.csc else orc.gram_dense(o.x, cand)
+            if deps == "dynamic":
+                d_gpu = _np(g.last_candidates()["delta_cand"])
+                mover_gpu = d_gpu != 0
+                dv = o.dots_vector()
+                z_ref = orc.dots_csc(o.x, o.row_idx, o.col_ptr, cand, dv) if o.csc else orc.dots_dense(o.x, cand, dv)
+                d_ref = orc.update(cand, z_ref, o.lam, o.beta.copy(), o.dbeta.copy(), inv_kappa=scale)
+                differ = mover_gpu != (d_ref != 0)
+                tol = DOT_RTOL * np.abs(z_ref[differ]) * scale + 2e-6 * scale * wn
+                assert np.all(np.abs(d_ref[differ]) <= tol) and np.all(np.abs(d_gpu[differ]) <= tol), "mover decision"
+                Gref[~mover_gpu, :] = 0
+                Gref[:, ~mover_gpu] = 0
+                forced["forced_mover"] = mover_gpu.astype(np.uint8)
+            check_kept_against_oracle(Gref, kept_pos, orc.greedy_filter(Gref, o.rho, o.p_max), o.rho, o.p_max, [],
+                                      f"round {t}")
         out = o.round(**forced)
         assert np.array_equal(_np(lr["kept"]), out["kept"])
         beta, dbeta, r, tt = g.get_state()
         assert tt == o.t
-        scale = 4.0 if loss == "logistic" else 1.0
         _assert_close(_np(lr["z"]), out["z"], DOT_RTOL, 1e-6 * wn, f"dots (round {t})")
         _assert_close(_np(beta), o.beta, BETA_RTOL, 2e-6 * scale * wn, f"beta (round {t})")
         _assert_close(_np(dbeta), o.dbeta, BETA_RTOL, 2e-6 * scale * wn, f"delta beta (round {t})")
