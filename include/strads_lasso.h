@@ -49,6 +49,7 @@ extern "C" {
 #define STRADS_E_HIP                 -3   /* a HIP runtime call or kernel launch failed */
 #define STRADS_E_DIVERGED            -4   /* objective is not finite (rho too large can do this) */
 #define STRADS_E_UNSUPPORTED         -5
+#define STRADS_E_TOO_LARGE           -6   /* a size exceeds the fixed maximum of an entry point that allocates nothing */
 
 #define STRADS_LAYOUT_DENSE_COLMAJOR  0   /* x[j*n + i] = X_ij, fp32, leading dimension n */
 #define STRADS_LAYOUT_CSC             1   /* values / row_idx / col_ptr */
@@ -230,6 +231,26 @@ int strads_lasso_stage_keys(strads_lasso_t *h, int64_t round, float *keys_out);
  * overwrites the handle's last-round filter outputs.  Synchronises. */
 int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, int32_t *kept_pos,
                               int32_t *n_kept);
+
+/* For callers that cannot allocate device memory or let a library do it (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid it): the dependency filter of strads_lasso_stage_filter without a
+ * handle and without a workspace.  The conflict bitmask and the other scratch of its kernels live in a
+ * file-scope device array inside the library, STRADS_FILTER_STATIC_MAX_L^2 / 8 bytes + 64 KiB + 256 bytes
+ * (8.06 MiB), which every GPU the library runs on holds until the process ends.  The call makes no
+ * allocation of any kind and does not synchronise: it enqueues three kernels on `stream` and returns.
+ *   gram      DEVICE, l*l floats row-major, symmetric (only |gram[a][b]| < rho is looked at, a != b)
+ *   l         1 .. STRADS_FILTER_STATIC_MAX_L; larger: STRADS_E_TOO_LARGE, nothing enqueued
+ *   rho       > 0; p_max >= 0 (0 = no cap)
+ *   kept_pos  DEVICE, room for l ints: receives the kept positions in increasing order
+ *   n_kept    DEVICE, one int: how many
+ *   stream    hipStream_t of the caller (NULL = the default stream); outputs are valid once the work
+ *             enqueued on it has finished
+ * All calls on one GPU share that GPU's array: calls that overlap in time on the same GPU (different
+ * streams or threads) race and must be serialised by the caller.  The first call on a device looks up the
+ * array's address there (make it outside a graph capture).  On error no output is written. */
+#define STRADS_FILTER_STATIC_MAX_L 8192
+int strads_lasso_filter_static(const float *gram, int32_t l, float rho, int32_t p_max, int32_t *kept_pos,
+                               int32_t *n_kept, void *stream);
 
 /* Launch-shape knobs for measurement sweeps (never change results except the
  * fp32 summation order of the Gram when split_k changes, and of the residual update):

@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libstrads_lasso.so")
 
 STRADS_OK = 0
-E_INVALID_ARG, E_WORKSPACE_TOO_SMALL, E_HIP, E_DIVERGED, E_UNSUPPORTED = -1, -2, -3, -4, -5
+E_INVALID_ARG, E_WORKSPACE_TOO_SMALL, E_HIP, E_DIVERGED, E_UNSUPPORTED, E_TOO_LARGE = -1, -2, -3, -4, -5, -6
+FILTER_STATIC_MAX_L = 8192
 LAYOUT_DENSE, LAYOUT_CSC, LAYOUT_GENO2 = 0, 1, 2
 LOSS = {"squared": 0, "logistic": 1}
 MAX_L_PRIME = 8192
@@ -31,7 +32,7 @@ EXPORTS = [
     "strads_lasso_objective", "strads_lasso_kkt", "strads_lasso_get_state", "strads_lasso_set_state",
     "strads_lasso_last_round", "strads_lasso_last_candidates", "strads_lasso_stage_keys", "strads_lasso_stage_filter",
     "strads_lasso_set_tuning", "strads_lasso_stage_times", "strads_lasso_last_kkt_ms", "strads_lasso_destroy",
-    "strads_lasso_strerror",
+    "strads_lasso_strerror", "strads_lasso_filter_static",
 ]
 
 
@@ -84,6 +85,7 @@ def load():
     L.strads_lasso_stage_filter.argtypes = [vp, vp, C.c_int32, vp, C.POINTER(C.c_int32)]
     L.strads_lasso_set_tuning.argtypes = [vp, C.c_char_p, C.c_int64]
     L.strads_lasso_stage_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+    L.strads_lasso_filter_static.argtypes = [vp, C.c_int32, C.c_float, C.c_int32, vp, vp, vp]
     L.strads_lasso_destroy.argtypes = [vp]
     L.strads_lasso_destroy.restype = None
     L.strads_lasso_strerror.argtypes = [C.c_int]
@@ -115,6 +117,21 @@ def strads_lasso_workspace_bytes(n, j, l_prime, layout=LAYOUT_DENSE, keep_gram=F
     cfg = Config(n=n, j=j, layout=layout, l_prime=l_prime, keep_gram=int(keep_gram), max_col_nnz=int(max_col_nnz),
                  deps=DEPS_DYNAMIC if dynamic else DEPS_STATIC)
     return int(load().strads_lasso_workspace_bytes(C.byref(cfg)))
+
+
+def strads_lasso_filter_static(gram: torch.Tensor, rho: float, p_max: int, kept_pos: torch.Tensor,
+                               n_kept: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """The dependency filter on a caller-supplied Gram without handle or workspace.  Every tensor is the
+    caller's (gram: l x l fp32; kept_pos: >= l int32; n_kept: >= 1 int32, all on the GPU); nothing is
+    allocated and nothing is waited for."""
+    assert gram.is_cuda and gram.dtype == torch.float32 and gram.is_contiguous() and gram.dim() == 2
+    l = gram.shape[0]
+    assert gram.shape[1] == l and kept_pos.dtype == torch.int32 and n_kept.dtype == torch.int32
+    assert kept_pos.is_cuda and n_kept.is_cuda and kept_pos.numel() >= l and n_kept.numel() >= 1
+    s = stream if stream is not None else torch.cuda.current_stream(gram.device)
+    with torch.cuda.device(gram.device):
+        _check(load().strads_lasso_filter_static(_ptr(gram), l, float(rho), int(p_max), _ptr(kept_pos), _ptr(n_kept),
+                                                 s.cuda_stream), "strads_lasso_filter_static")
 
 
 class StradsLasso:

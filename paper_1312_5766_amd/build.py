@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libstrads_lasso.so")
-SOURCES = ["api.hip", "sampler.hip", "gram.hip", "filter.hip", "update.hip", "csc.hip", "geno.hip"]
+SOURCES = ["api.hip", "sampler.hip", "gram.hip", "filter.hip", "update.hip", "csc.hip", "geno.hip", "noalloc.hip"]
 
 
 def build(verbose: bool = False) -> str:

@@ -796,6 +796,7 @@ const char *strads_lasso_strerror(int code)
     case STRADS_E_HIP: return "HIP runtime error";
     case STRADS_E_DIVERGED: return "objective is not finite";
     case STRADS_E_UNSUPPORTED: return "not supported";
+    case STRADS_E_TOO_LARGE: return "size exceeds the fixed maximum of this entry point";
     default: return "unknown error";
     }
 }

@@ -17,6 +17,8 @@
 // The details, and what they are there to avoid, are at k_filter.
 // Only bits (a, b) with b in a's 128-tile or right of it are read, matching what the Gram
 // kernel writes.  Bit-exact: the result depends on the conflict bits only.
+#include <string.h>
+
 #include "strads_internal.h"
 
 namespace strads {
@@ -425,11 +427,12 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
 
 // Launch for row width W (words); with gdev the kernel takes the actual length and width from
 // device memory (they can only be smaller).
-static hipError_t launch_filter_kernel(strads_lasso *h, int32_t l, int32_t W, const GramShape *gdev, int32_t p_max,
+static hipError_t launch_filter_kernel(hipStream_t stream, const uint64_t *mask, RoundScalars *sc, int32_t l, int32_t W,
+                                       const GramShape *gdev, int32_t p_max,
                                        const int32_t *cand, int32_t *kept_pos, int32_t *kept, int32_t *n_out,
                                        bool count_updates, const CommitArgs &cm)
 {
-#define STRADS_FILTER(IPT, A, TPR) hipLaunchKernelGGL((k_filter<IPT, A, TPR>), dim3(1), dim3(64 + 64 * TPR), 0, h->stream, h->at<uint64_t>(h->ws.mask), l, W, gdev, p_max, cand, kept_pos, kept, h->at<RoundScalars>(h->ws.scalars), n_out, count_updates ? 1 : 0, cm)
+#define STRADS_FILTER(IPT, A, TPR) hipLaunchKernelGGL((k_filter<IPT, A, TPR>), dim3(1), dim3(64 + 64 * TPR), 0, stream, mask, l, W, gdev, p_max, cand, kept_pos, kept, sc, n_out, count_updates ? 1 : 0, cm)
     // words of a row per holder thread = ceil(W / threads per row); short rows can afford more chunks in flight
     if (W <= 16) STRADS_FILTER(4, 8, 4);
     else if (W <= 32) STRADS_FILTER(8, 6, 4);
@@ -461,7 +464,8 @@ static CommitArgs commit_args(strads_lasso *h, int32_t mode)
 hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates, bool commit)
 {
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
-    return launch_filter_kernel(h, l, h->Lpad / 64, nullptr, h->cfg.p_max, h->at<int32_t>(h->ws.cand),
+    return launch_filter_kernel(h->stream, h->at<uint64_t>(h->ws.mask), sc, l, h->Lpad / 64, nullptr, h->cfg.p_max,
+                                h->at<int32_t>(h->ws.cand),
                                 h->at<int32_t>(h->ws.kept_pos), h->at<int32_t>(h->ws.kept), &sc->n_kept, count_updates,
                                 commit_args(h, commit ? kCommitKept : 0));
 }
@@ -473,9 +477,20 @@ hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates, bool co
 hipError_t launch_filter_movers(strads_lasso *h)
 {
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
-    return launch_filter_kernel(h, h->L, h->Lpad / 64, h->at<GramShape>(h->ws.dshape), h->cfg.p_max,
+    return launch_filter_kernel(h->stream, h->at<uint64_t>(h->ws.mask), sc, h->L, h->Lpad / 64,
+                                h->at<GramShape>(h->ws.dshape), h->cfg.p_max,
                                 h->at<int32_t>(h->ws.mcand), h->at<int32_t>(h->ws.mkept_pos),
                                 h->at<int32_t>(h->ws.kept), &sc->n_mkept, false, commit_args(h, kCommitDynamic));
+}
+
+// The greedy walk alone, on buffers named one by one (no handle): mask holds lpad rows of lpad / 64 words as
+// k_mask_from_gram writes them, cand l column ids, kept_pos and kept room for l entries, n_out one int.
+hipError_t launch_filter_plain(hipStream_t stream, const uint64_t *mask, int32_t l, int32_t lpad, int32_t p_max,
+                               const int32_t *cand, int32_t *kept_pos, int32_t *kept, RoundScalars *sc, int32_t *n_out)
+{
+    CommitArgs cm;
+    memset(&cm, 0, sizeof(cm));
+    return launch_filter_kernel(stream, mask, sc, l, lpad / 64, nullptr, p_max, cand, kept_pos, kept, n_out, false, cm);
 }
 
 // No dependency check (the Shotgun scheduler of Section 5.1): B_1 is the head of the draw.

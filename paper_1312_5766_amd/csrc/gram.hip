@@ -879,11 +879,16 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
     return hipGetLastError();
 }
 
+hipError_t launch_mask_from_gram_plain(hipStream_t stream, const float *gram, int32_t l, int32_t lpad, float rho,
+                                       uint64_t *mask)
+{
+    hipLaunchKernelGGL(k_mask_from_gram, dim3((lpad + 255) / 256, lpad), dim3(256), 0, stream, gram, l, lpad, rho, mask);
+    return hipGetLastError();
+}
+
 hipError_t launch_mask_from_gram(strads_lasso *h, const float *gram, int32_t l)
 {
-    hipLaunchKernelGGL(k_mask_from_gram, dim3((h->Lpad + 255) / 256, h->Lpad), dim3(256), 0, h->stream, gram, l,
-                       h->Lpad, h->cfg.rho, h->at<uint64_t>(h->ws.mask));
-    return hipGetLastError();
+    return launch_mask_from_gram_plain(h->stream, gram, l, h->Lpad, h->cfg.rho, h->at<uint64_t>(h->ws.mask));
 }
 
 hipError_t gram_prepare()

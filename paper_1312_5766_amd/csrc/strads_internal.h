@@ -155,6 +155,12 @@ hipError_t launch_set_next_round(strads_lasso *h, hipStream_t stream, int64_t ne
 hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys);  // stage entry
 hipError_t launch_gram_dense(strads_lasso *h, int part);  // Step 2a; part 0: K-slice tiles, part 1: sum + conflict mask
 hipError_t launch_mask_from_gram(strads_lasso *h, const float *gram, int32_t l);
+// the same two steps on buffers named one by one (no handle): conflict bits of an l x l Gram into lpad rows of
+// lpad / 64 words, then the greedy walk over them
+hipError_t launch_mask_from_gram_plain(hipStream_t stream, const float *gram, int32_t l, int32_t lpad, float rho,
+                                       uint64_t *mask);
+hipError_t launch_filter_plain(hipStream_t stream, const uint64_t *mask, int32_t l, int32_t lpad, int32_t p_max,
+                               const int32_t *cand, int32_t *kept_pos, int32_t *kept, RoundScalars *sc, int32_t *n_out);
 hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates, bool commit);       // Step 2b -> kept_pos, kept, n_kept;
                                                           // commit: and eq. (2) for B_1 from the candidates' tentative updates
 hipError_t launch_keep_all(strads_lasso *h);              // no dependency check: B_1 = first p_max candidates
