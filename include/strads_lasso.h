@@ -47,7 +47,8 @@ extern "C" {
 #define STRADS_E_INVALID_ARG         -1
 #define STRADS_E_WORKSPACE_TOO_SMALL -2
 #define STRADS_E_HIP                 -3   /* a HIP runtime call or kernel launch failed */
-#define STRADS_E_DIVERGED            -4   /* objective is not finite (rho too large can do this) */
+#define STRADS_E_DIVERGED            -4   /* objective is not finite: updating correlated coordinates together (rho too
+                                             large, or no dependency check) can make the iteration blow up */
 #define STRADS_E_UNSUPPORTED         -5
 #define STRADS_E_TOO_LARGE           -6   /* a size exceeds the fixed maximum of an entry point that allocates nothing */
 
@@ -113,7 +114,11 @@ typedef struct {
     int32_t        layout;        /* STRADS_LAYOUT_* */
     const float   *x;             /* DEVICE. dense: n*j values, column-major; CSC: nnz values;
                                      GENO2: the packed words (cast), 16-byte aligned */
-    const int32_t *row_idx;       /* DEVICE, CSC only: nnz row indices, increasing within a column */
+    const int32_t *row_idx;       /* DEVICE, CSC only: nnz row indices, increasing within a column.  CSC sums are kept in
+                                     2^-40 fixed point: |x_a^T x_b| must stay below 2^22 and every |value * change of
+                                     beta_j| of a round below 2^22 / |B_1| (at least 512; unit-norm columns and a
+                                     converging iteration are far inside); a residual update that leaves the range
+                                     writes NaN into r, which strads_lasso_run reports as STRADS_E_DIVERGED */
     const int64_t *col_ptr;       /* DEVICE, CSC only: j+1 offsets, col_ptr[0] = 0 */
     const float   *col_mean;      /* DEVICE, GENO2 only: j column means */
     const float   *col_scale;     /* DEVICE, GENO2 only: j column scales (1 / l2 norm of the centred column) */
@@ -162,8 +167,8 @@ typedef struct {
     int32_t graph_replays;        /* HIP-graph launches this call made (each = "graph_rounds" rounds) */
 } strads_run_info_t;
 
-/* Bytes of workspace a configuration needs (depends on n, j, layout, l_prime, keep_gram, deps and,
- * for CSC, max_col_nnz only; pointers in cfg are ignored).  Makes no device call.
+/* Bytes of workspace a configuration needs (depends on n, j, layout, l_prime, keep_gram, deps, n_shards
+ * and, for CSC, max_col_nnz only; pointers in cfg are ignored).  Makes no device call.
  * Returns 0 if cfg is NULL or a size field is invalid. */
 size_t strads_lasso_workspace_bytes(const strads_lasso_config_t *cfg);
 
@@ -297,6 +302,13 @@ int strads_lasso_stage_times(strads_lasso_t *h, float *avg_ms, int32_t *rounds_t
 int strads_lasso_last_kkt_ms(strads_lasso_t *h, float *ms);
 
 void strads_lasso_destroy(strads_lasso_t *h);
+
+/* 1 if the library was built as a debug build (-DSTRADS_DEBUG_SYNC), else 0.  A debug build waits for the
+ * stream and checks the error state after every kernel launch, so that a failing kernel is reported by the
+ * call that launched it (every call then synchronises; "graph_rounds" is refused), and
+ * strads_lasso_create checks the unit-norm precondition: a design with a column whose l2 norm differs from
+ * 1 by more than 1e-3 is rejected with STRADS_E_INVALID_ARG (one pass over the design). */
+int strads_lasso_debug_build(void);
 
 const char *strads_lasso_strerror(int code);
 

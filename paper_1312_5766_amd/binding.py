@@ -14,7 +14,10 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libstrads_lasso.so")
+# STRADS_LASSO_DEBUG=1 selects the debug build (waits and checks after every launch; checks unit norms at create)
+# STRADS_LASSO_LIB=<path> loads another build of the same library (measurements of kernel variants)
+LIB_PATH = os.environ.get("STRADS_LASSO_LIB") or os.path.join(
+    _HERE, "libstrads_lasso_debug.so" if os.environ.get("STRADS_LASSO_DEBUG") == "1" else "libstrads_lasso.so")
 
 STRADS_OK = 0
 E_INVALID_ARG, E_WORKSPACE_TOO_SMALL, E_HIP, E_DIVERGED, E_UNSUPPORTED, E_TOO_LARGE = -1, -2, -3, -4, -5, -6
@@ -32,7 +35,7 @@ EXPORTS = [
     "strads_lasso_objective", "strads_lasso_kkt", "strads_lasso_get_state", "strads_lasso_set_state",
     "strads_lasso_last_round", "strads_lasso_last_candidates", "strads_lasso_stage_keys", "strads_lasso_stage_filter",
     "strads_lasso_set_tuning", "strads_lasso_stage_times", "strads_lasso_last_kkt_ms", "strads_lasso_destroy",
-    "strads_lasso_strerror", "strads_lasso_filter_static",
+    "strads_lasso_strerror", "strads_lasso_filter_static", "strads_lasso_debug_build",
 ]
 
 
@@ -86,6 +89,7 @@ def load():
     L.strads_lasso_set_tuning.argtypes = [vp, C.c_char_p, C.c_int64]
     L.strads_lasso_stage_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     L.strads_lasso_filter_static.argtypes = [vp, C.c_int32, C.c_float, C.c_int32, vp, vp, vp]
+    L.strads_lasso_debug_build.argtypes = []
     L.strads_lasso_destroy.argtypes = [vp]
     L.strads_lasso_destroy.restype = None
     L.strads_lasso_strerror.argtypes = [C.c_int]

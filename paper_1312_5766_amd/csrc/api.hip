@@ -235,6 +235,10 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
             if (launch_csc_init(&tmp, &h->at<RoundScalars>(ln->ws.scalars)->bad_input) != hipSuccess) rc = STRADS_E_HIP;
         }
     }
+#ifdef STRADS_DEBUG_SYNC
+    // debug build: the unit-norm precondition of eq. (2)'s update is checked, one pass over the design
+    if (rc == STRADS_OK && launch_check_unit_norm(h) != hipSuccess) rc = STRADS_E_HIP;
+#endif
     if (rc == STRADS_OK) {
         RoundScalars sc;
         if (hipMemcpyAsync(&sc, h->base + ws.scalars, sizeof(sc), hipMemcpyDeviceToHost, h->stream) != hipSuccess ||
@@ -681,6 +685,9 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
     if (!h || !name) return STRADS_E_INVALID_ARG;
     if (strcmp(name, "graph_rounds") == 0) {
         if (value < 0 || value > 4096) return STRADS_E_INVALID_ARG;
+#ifdef STRADS_DEBUG_SYNC
+        if (value > 0) return STRADS_E_UNSUPPORTED;     // a debug build waits after every launch; a capture cannot
+#endif
         HIP_TRY(hipStreamSynchronize(h->stream));
         drop_graphs(h);
         h->graph_rounds = (int32_t)value;
@@ -785,6 +792,15 @@ int strads_lasso_last_kkt_ms(strads_lasso_t *h, float *ms)
     if (!h || !ms) return STRADS_E_INVALID_ARG;
     *ms = h->last_kkt_ms;
     return STRADS_OK;
+}
+
+int strads_lasso_debug_build(void)
+{
+#ifdef STRADS_DEBUG_SYNC
+    return 1;
+#else
+    return 0;
+#endif
 }
 
 const char *strads_lasso_strerror(int code)

@@ -21,6 +21,7 @@ namespace strads {
 
 constexpr double kFixScale = 1099511627776.0;          // 2^40
 constexpr double kFixInv = 1.0 / 1099511627776.0;
+constexpr double kFixTermLimit = 4194304.0;            // 2^22; a residual update of k columns accepts |value * change| < 2^22 / k
 
 __device__ __forceinline__ long long fix40(float a, float b)
 {
@@ -310,15 +311,23 @@ __global__ __launch_bounds__(256) void k_csc_residual_acc(const float *__restric
     if (d == 0.f) return;
     const int32_t j = kept[c];
     const int64_t p0 = col_ptr[j], p1 = col_ptr[j + 1];
-    for (int64_t p = p0 + (threadIdx.x & 63); p < p1; p += 64)
-        atomicAdd((unsigned long long *)&racc[row_idx[p]], (unsigned long long)fix40(val[p], d));
+    bool out_of_range = false;
+    const double term_limit = kFixTermLimit / (double)k;
+    for (int64_t p = p0 + (threadIdx.x & 63); p < p1; p += 64) {
+        const float v = val[p];
+        // the accumulator holds sums below 2^23 in magnitude and up to k terms can land on one row: a term at or
+        // above 2^22 / k (or not finite: the iteration has blown up) is reported instead of being allowed to wrap
+        if (!(fabs((double)v * (double)d) < term_limit)) { out_of_range = true; continue; }
+        atomicAdd((unsigned long long *)&racc[row_idx[p]], (unsigned long long)fix40(v, d));
+    }
+    if (out_of_range) atomicOr(&sc->overflow, 1u);
 }
 
 // Workgroups past res_blocks (there are some when another round follows at once, one scheduler) make the
 // next round's key pass: it needs delta beta as this round leaves it and nothing this kernel writes.
 __global__ __launch_bounds__(256) void k_csc_residual_apply(long long *__restrict__ racc, int64_t N,
                                                             float *__restrict__ r, uint32_t res_blocks,
-                                                            KeysArgs next_keys)
+                                                            KeysArgs next_keys, const RoundScalars *__restrict__ sc)
 {
     if (blockIdx.x >= res_blocks) {
         keys_hist_block(next_keys, blockIdx.x - res_blocks, gridDim.x - res_blocks);
@@ -327,6 +336,13 @@ __global__ __launch_bounds__(256) void k_csc_residual_apply(long long *__restric
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= N) return;
     const long long v = racc[i];
+    if (sc->overflow) {
+        // a product left the accumulator's range (set by the kernel before this one): the sums are not
+        // trustworthy, and the residual says so: the objective and the optimality test then read as not finite
+        r[i] = __int_as_float(0x7fc00000);
+        if (v != 0) racc[i] = 0;
+        return;
+    }
     if (v != 0) {
         r[i] = (float)((double)r[i] - (double)v * kFixInv);
         racc[i] = 0;
@@ -372,7 +388,7 @@ hipError_t launch_csc_init(strads_lasso *h, uint32_t *bad_dev)
     hipLaunchKernelGGL(k_csc_zero, dim3(1024), dim3(256), 0, h->stream, s.cnt, s.racc, h->cfg.n, bad_dev);
     hipLaunchKernelGGL(k_csc_check, dim3(1024), dim3(256), 0, h->stream, h->cfg.col_ptr, h->cfg.j,
                        h->cfg.max_col_nnz, bad_dev);
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_gram_csc(strads_lasso *h)
@@ -396,7 +412,7 @@ hipError_t launch_gram_csc(strads_lasso *h)
                        h->cfg.row_idx, h->cfg.x, s.row_start, s.entries, h->L, h->Lpad, h->cfg.rho,
                        h->at<uint64_t>(h->ws.mask), h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr,
                        &sc->near_rho_pairs);
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_dots_cand_csc(strads_lasso *h)
@@ -405,7 +421,7 @@ hipError_t launch_dots_cand_csc(strads_lasso *h)
                        h->cfg.col_ptr, h->at<int32_t>(h->ws.cand), h->L, dots_vector(h), h->cfg.lambda, h->step_scale,
                        h->at<float>(h->ws.beta), h->at<float>(h->ws.zc), h->at<float>(h->ws.dc),
                        h->at<float>(h->ws.nbc));
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_dots_csc(strads_lasso *h)
@@ -414,7 +430,7 @@ hipError_t launch_dots_csc(strads_lasso *h)
                        h->cfg.col_ptr, h->at<int32_t>(h->ws.kept), h->at<RoundScalars>(h->ws.scalars),
                        dots_vector(h), h->cfg.lambda, h->step_scale, h->at<float>(h->ws.beta),
                        h->at<float>(h->ws.dbeta), h->at<float>(h->ws.z), h->at<float>(h->ws.delta));
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_residual_csc(strads_lasso *h, bool want_next_keys, bool *next_keys_done)
@@ -432,8 +448,9 @@ hipError_t launch_residual_csc(strads_lasso *h, bool want_next_keys, bool *next_
         *next_keys_done = true;
     }
     hipLaunchKernelGGL(k_csc_residual_apply, dim3(res_blocks + key_blocks), dim3(256), 0, h->stream, s.racc,
-                       h->cfg.n, h->at<float>(h->ws.r), res_blocks, keys_args(h));
-    return hipGetLastError();
+                       h->cfg.n, h->at<float>(h->ws.r), res_blocks, keys_args(h),
+                       h->at<RoundScalars>(h->ws.scalars));
+    return launch_status(h->stream);
 }
 
 hipError_t launch_kkt_csc(strads_lasso *h, float *g_or_null)
@@ -444,7 +461,7 @@ hipError_t launch_kkt_csc(strads_lasso *h, float *g_or_null)
     hipLaunchKernelGGL(k_csc_kkt, dim3((unsigned)((h->cfg.j + 3) / 4 < 256 * 16 ? (h->cfg.j + 3) / 4 : 256 * 16)), dim3(256), 0, h->stream, h->cfg.x,
                        h->cfg.row_idx, h->cfg.col_ptr, h->cfg.j, dots_vector(h), h->at<float>(h->ws.beta),
                        h->cfg.lambda, g_or_null, sc);
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 } // namespace strads

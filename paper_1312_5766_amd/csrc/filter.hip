@@ -439,7 +439,7 @@ static hipError_t launch_filter_kernel(hipStream_t stream, const uint64_t *mask,
     else if (W <= 64) STRADS_FILTER(16, 4, 4);
     else STRADS_FILTER(16, 3, 8);
 #undef STRADS_FILTER
-    return hipGetLastError();
+    return launch_status(stream);
 }
 
 static CommitArgs commit_args(strads_lasso *h, int32_t mode)
@@ -514,7 +514,7 @@ hipError_t launch_keep_all(strads_lasso *h)
     hipLaunchKernelGGL(k_keep_all, dim3((h->L + 255) / 256), dim3(256), 0, h->stream, h->at<int32_t>(h->ws.cand),
                        h->L, h->cfg.p_max, h->at<int32_t>(h->ws.kept_pos), h->at<int32_t>(h->ws.kept),
                        h->at<RoundScalars>(h->ws.scalars));
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t filter_prepare() { return hipSuccess; }   // static LDS only

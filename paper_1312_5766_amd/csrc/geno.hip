@@ -371,14 +371,14 @@ hipError_t launch_dots_geno(strads_lasso *h)
     // the grid covers all L candidates; workgroups past the kept count (known on the device) leave at once
     STRADS_GENO_DOTS(kGenoCommit, h->at<int32_t>(h->ws.kept), (int64_t)h->L, h->at<float>(h->ws.z),
                      h->at<float>(h->ws.delta), (float *)nullptr);
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_dots_cand_geno(strads_lasso *h)
 {
     STRADS_GENO_DOTS(kGenoTentative, h->at<int32_t>(h->ws.cand), (int64_t)h->L, h->at<float>(h->ws.zc),
                      h->at<float>(h->ws.dc), h->at<float>(h->ws.nbc));
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_kkt_geno(strads_lasso *h, float *g_or_null)
@@ -393,10 +393,10 @@ hipError_t launch_kkt_geno(strads_lasso *h, float *g_or_null)
                            geno_words(h->cfg.n), h->cfg.col_mean, h->cfg.col_scale, h->cfg.j,
                            h->at<RoundScalars>(h->ws.scalars), dots_vector(h), h->cfg.lambda,
                            h->at<float>(h->ws.beta), g_or_null);
-        return hipGetLastError();
+        return launch_status(h->stream);
     }
     STRADS_GENO_DOTS(kGenoAll, (const int32_t *)nullptr, h->cfg.j, g_or_null, (float *)nullptr, (float *)nullptr);
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 #undef STRADS_GENO_DOTS
 

@@ -27,6 +27,7 @@
 #include "strads_internal.h"
 #include "dots.h"
 #include <algorithm>
+#include <type_traits>
 #include <utility>
 #include <vector>
 
@@ -314,15 +315,24 @@ __device__ __forceinline__ void gram_tile_off(const float *__restrict__ X, int64
             mfma32(acc[1][1], av1[c], bv1[c]);
         }
     };
-    // multiply stage `buf` out of LDS, its first operands already in `first`; `between` runs after
-    // the MFMAs of the first K step have been issued (the next stage's LDS writes and global loads:
-    // whatever they wait for is then waited for behind a full matrix pipe)
-    auto compute = [&](int buf, Ops first, auto between) {
-        Ops cur = first;
+    // One stage: multiply stage `buf` out of LDS.  Its first operands are in `cur` already; `between` runs
+    // after the MFMAs of the first K step have been issued (the next stage's LDS writes and the global
+    // loads of the stage after: whatever they wait for is then waited for behind a full matrix pipe).
+    // The stage's one barrier sits before its LAST K step, not after it: by then every wavefront has
+    // written its share of the next stage (and nobody reads that buffer any more: its last operands
+    // were requested a step earlier), so the first operands of the next stage are requested right
+    // after the barrier and arrive while the last step's 16 MFMAs run: neither the barrier nor the LDS
+    // round trip after it is waited for with an empty matrix pipe.  `more`: another stage follows.
+    auto stage = [&](int buf, Ops &cur, bool more, auto between) {
 #pragma unroll
         for (int ks = 0; ks < kGramKT / 8; ++ks) {
             Ops next = cur;
-            if (ks + 1 < kGramKT / 8) next = read_ops(buf, ks + 1);
+            if (ks + 1 < kGramKT / 8) {
+                next = read_ops(buf, ks + 1);
+            } else if (more) {
+                __syncthreads();
+                next = read_ops(buf ^ 1, 0);
+            }
             mma(cur);
             if (ks == 0) between();
             cur = next;
@@ -333,21 +343,17 @@ __device__ __forceinline__ void gram_tile_off(const float *__restrict__ X, int64
     stash(0);
     if (nstage > 1) fetch(1);
     __syncthreads();
+    Ops cur = read_ops(0, 0);
     int st = 0;
-    for (; st + 2 < nfull; ++st) {              // steady state
-        compute(st & 1, read_ops(st & 1, 0), [&] { stash_full((st + 1) & 1); fetch_full(st + 2); });
-        __syncthreads();
-    }
-    for (; st + 2 < nstage; ++st) {             // a ragged last stage is fetched with clamping
-        compute(st & 1, read_ops(st & 1, 0), [&] { stash((st + 1) & 1); fetch(st + 2); });
-        __syncthreads();
-    }
+    for (; st + 2 < nfull; ++st)                // steady state
+        stage(st & 1, cur, true, [&] { stash_full((st + 1) & 1); fetch_full(st + 2); });
+    for (; st + 2 < nstage; ++st)               // a ragged last stage is fetched with clamping
+        stage(st & 1, cur, true, [&] { stash((st + 1) & 1); fetch(st + 2); });
     if (st + 1 < nstage) {
-        compute(st & 1, read_ops(st & 1, 0), [&] { stash((st + 1) & 1); });
-        __syncthreads();
+        stage(st & 1, cur, true, [&] { stash((st + 1) & 1); });
         ++st;
     }
-    compute(st & 1, read_ops(st & 1, 0), [] {});
+    stage(st & 1, cur, false, [] {});
     mfma_drain();
 
     float *out = P + (int64_t)s * g.Lpad * g.Lpad;
@@ -398,63 +404,73 @@ __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int6
     const int offp = (gp * 32 + li) * kRow + lh * 4;
     const int offq = (gq * 32 + li) * kRow + lh * 4;
     const int offr = (gr * 32 + li) * kRow + lh * 4;
-    auto compute = [&](int buf) {
-        const float *base = smem + buf * 2 * kPanel;
-        if (sym) {
+    // The whole pipeline once for the wavefronts with a symmetric share (SYM) and once for the others: the
+    // two use the accumulators and operands differently, and a choice made inside the K loop would cost
+    // register moves in every step.
+    auto run = [&](auto symc) {
+        constexpr bool SYM = decltype(symc)::value;
+        // operands of one 8-row K step: 4 K values of this lane's column in groups p, q (and r)
+        struct Ops { float4 p, q, r; };
+        auto read_ops = [&](int buf, int ks) {
+            const float *base = smem + buf * 2 * kPanel + ks * 8;
+            Ops o;
+            o.p = *reinterpret_cast<const float4 *>(base + offp);
+            o.q = *reinterpret_cast<const float4 *>(base + offq);
+            if (SYM) o.r = o.q;
+            else o.r = *reinterpret_cast<const float4 *>(base + offr);
+            return o;
+        };
+        auto mma = [&](const Ops &o) {
+            const float pv[4] = {o.p.x, o.p.y, o.p.z, o.p.w}, qv[4] = {o.q.x, o.q.y, o.q.z, o.q.w};
+            const float rv[4] = {o.r.x, o.r.y, o.r.z, o.r.w};
 #pragma unroll
-            for (int ks = 0; ks < kGramKT / 8; ++ks) {
-                const float4 p4 = *reinterpret_cast<const float4 *>(base + offp + ks * 8);
-                const float4 q4 = *reinterpret_cast<const float4 *>(base + offq + ks * 8);
-                const float pv[4] = {p4.x, p4.y, p4.z, p4.w}, qv[4] = {q4.x, q4.y, q4.z, q4.w};
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
+            for (int c = 0; c < 4; ++c) {
+                if (SYM) {
                     mfma32(acc[0], pv[c], pv[c]);
                     mfma32(acc[1], pv[c], qv[c]);
                     mfma32(acc[2], qv[c], qv[c]);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int ks = 0; ks < kGramKT / 8; ++ks) {
-                const float4 p4 = *reinterpret_cast<const float4 *>(base + offp + ks * 8);
-                const float4 q4 = *reinterpret_cast<const float4 *>(base + offq + ks * 8);
-                const float4 r4 = *reinterpret_cast<const float4 *>(base + offr + ks * 8);
-                const float pv[4] = {p4.x, p4.y, p4.z, p4.w}, qv[4] = {q4.x, q4.y, q4.z, q4.w};
-                const float rv[4] = {r4.x, r4.y, r4.z, r4.w};
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
+                } else {
                     mfma32(acc[0], pv[c], qv[c]);
                     mfma32(acc[1], pv[c], rv[c]);
                 }
             }
-        }
-    };
+        };
+        // one stage, as in gram_tile_off: operands one K step ahead, the stage's barrier before its last step
+        auto stage = [&](int buf, Ops &cur, bool more, auto between) {
+#pragma unroll
+            for (int ks = 0; ks < kGramKT / 8; ++ks) {
+                Ops next = cur;
+                if (ks + 1 < kGramKT / 8) {
+                    next = read_ops(buf, ks + 1);
+                } else if (more) {
+                    __syncthreads();
+                    next = read_ops(buf ^ 1, 0);
+                }
+                mma(cur);
+                if (ks == 0) between();
+                cur = next;
+            }
+        };
 
-    fetch(0);
-    stash(0);
-    if (nstage > 1) fetch(1);
-    __syncthreads();
-    int st = 0;
-    for (; st + 2 < nfull; ++st) {
-        stash_full((st + 1) & 1);
-        fetch_full(st + 2);
-        compute(st & 1);
+        fetch(0);
+        stash(0);
+        if (nstage > 1) fetch(1);
         __syncthreads();
-    }
-    for (; st + 2 < nstage; ++st) {
-        stash((st + 1) & 1);
-        fetch(st + 2);
-        compute(st & 1);
-        __syncthreads();
-    }
-    if (st + 1 < nstage) {
-        stash((st + 1) & 1);
-        compute(st & 1);
-        __syncthreads();
-        ++st;
-    }
-    compute(st & 1);
-    mfma_drain();
+        Ops cur = read_ops(0, 0);
+        int st = 0;
+        for (; st + 2 < nfull; ++st)
+            stage(st & 1, cur, true, [&] { stash_full((st + 1) & 1); fetch_full(st + 2); });
+        for (; st + 2 < nstage; ++st)
+            stage(st & 1, cur, true, [&] { stash((st + 1) & 1); fetch(st + 2); });
+        if (st + 1 < nstage) {
+            stage(st & 1, cur, true, [&] { stash((st + 1) & 1); });
+            ++st;
+        }
+        stage(st & 1, cur, false, [] {});
+        mfma_drain();
+    };
+    if (sym) run(std::true_type{});
+    else run(std::false_type{});
 
     float *out = P + (int64_t)s * g.Lpad * g.Lpad;
     const int t0 = ta * kGramTile;
@@ -716,34 +732,55 @@ static GramShape gram_shape(const strads_lasso *h)
 }
 
 // Which job the workgroup with a given blockIdx.x takes.  Workgroups are dealt to the chip's eight XCDs
-// in turn (workgroup b runs on XCD b mod 8), each XCD has its own L2, and all jobs of one K-slice read
-// the same rows of the same few panels.  Numbering the jobs tile by tile would spread every slice over
-// all eight L2s, and every panel row would cross the fabric eight times.  Instead the jobs are put in
-// order of their first row (then by tile) and every XCD gets a consecutive eighth of that order: the
-// workgroups that share an L2 then work on the same one or two K-slices.
+// in turn (workgroup b runs on XCD b mod 8), each XCD has its own L2, and a job streams the rows of its
+// K-slice of two 128-column panels (one for a diagonal tile).  What two jobs can share in an L2 is a panel
+// they have in common, read at about the same time over the same rows.  So the jobs are put in an order in
+// which neighbours share as much as possible, and every XCD gets a consecutive eighth of that order (the
+// 64 workgroups it holds at a time are then neighbours):
+//   * first by the first row of the job's K-slice: with many slices (a short candidate list) an XCD then
+//     works on one or two slices of all tiles, and a panel row crosses the fabric once or twice, not eight times;
+//   * within a slice by blocks of 8 x 8 tiles (block row, block column, then tile row, tile column; a
+//     diagonal tile sits where its row and column meet): the 64 tiles of a block need 16 panels between
+//     them, where 64 consecutive tiles of one tile row need 65.  For a long candidate list (one slice,
+//     thousands of tiles) this is what keeps most panel reads inside the L2.
 size_t gram_job_table_entries(int64_t n, int32_t lpad)
 {
     const size_t T = (size_t)(lpad / kGramTile);
     return (T * (T - 1) / 2 + T) * (size_t)gram_split_choose(n, lpad);      // any smaller slice count fits
 }
 
+constexpr int32_t kJobBlock = 8;     // tiles per side of a block of jobs that share panels in one L2
+
 int32_t gram_job_table(const strads_lasso *h, int32_t *out)
 {
     const GramShape g = gram_shape(h);
     const int32_t n_off = g.T * (g.T - 1) / 2 * g.split_off;
     const int32_t total = n_off + g.T * g.split_diag;
-    std::vector<std::pair<int64_t, int32_t>> order((size_t)total);
-    for (int32_t job = 0; job < total; ++job) {
-        const int64_t kbeg = job < n_off ? (int64_t)(job % g.split_off) * g.kchunk_off
-                                         : (int64_t)((job - n_off) % g.split_diag) * g.kchunk_diag;
-        order[(size_t)job] = std::make_pair(kbeg, job);
+    struct Key { int64_t kbeg; int32_t bi, bj, ta, tb, job; };
+    std::vector<Key> order((size_t)total);
+    {
+        int32_t job = 0;
+        for (int32_t ta = 0; ta < g.T; ++ta)                 // the numbering gram_job decodes
+            for (int32_t tb = ta + 1; tb < g.T; ++tb)
+                for (int32_t sl = 0; sl < g.split_off; ++sl, ++job)
+                    order[(size_t)job] = Key{(int64_t)sl * g.kchunk_off, ta / kJobBlock, tb / kJobBlock, ta, tb, job};
+        for (int32_t ta = 0; ta < g.T; ++ta)
+            for (int32_t sl = 0; sl < g.split_diag; ++sl, ++job)
+                order[(size_t)job] = Key{(int64_t)sl * g.kchunk_diag, ta / kJobBlock, ta / kJobBlock, ta, ta, job};
     }
-    std::sort(order.begin(), order.end());
+    std::sort(order.begin(), order.end(), [](const Key &a, const Key &b) {
+        if (a.kbeg != b.kbeg) return a.kbeg < b.kbeg;
+        if (a.bi != b.bi) return a.bi < b.bi;
+        if (a.bj != b.bj) return a.bj < b.bj;
+        if (a.ta != b.ta) return a.ta < b.ta;
+        if (a.tb != b.tb) return a.tb < b.tb;
+        return a.job < b.job;
+    });
     const int32_t kXcds = 8, base = total / kXcds, rem = total % kXcds;
     for (int32_t b = 0; b < total; ++b) {
         const int32_t x = b % kXcds, q = b / kXcds;
         const int32_t first = x * base + (x < rem ? x : rem);               // jobs of the XCDs before x
-        out[b] = order[(size_t)(first + q)].second;
+        out[b] = order[(size_t)(first + q)].job;
     }
     return total;
 }
@@ -807,7 +844,7 @@ hipError_t launch_movers(strads_lasso *h)
                        tiled ? 0 : h->Lpad, h->at<int32_t>(h->ws.mpos),
                        h->at<int32_t>(h->ws.mcand), h->at<RoundScalars>(h->ws.scalars),
                        h->at<GramShape>(h->ws.dshape));
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 // L x L image (row-major) of the mover Gram for parity checks: x_a^T x_b where both candidate
@@ -829,7 +866,7 @@ hipError_t launch_scatter_mover_gram(strads_lasso *h, float *out)
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_scatter_mover_gram, dim3(4, 1024), dim3(256), 0, h->stream, h->at<float>(h->ws.gram),
                        h->at<GramShape>(h->ws.dshape), h->at<int32_t>(h->ws.mpos), h->L, out);
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_gram_dense(strads_lasso *h, int part)
@@ -846,7 +883,7 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
         hipLaunchKernelGGL(k_gram_mask, grid, dim3(256), 0, h->stream, P, g, gdev, h->cfg.rho,
                            h->at<uint64_t>(h->ws.mask), h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr,
                            &sc->near_rho_pairs);
-        return hipGetLastError();
+        return launch_status(h->stream);
     }
     const int load = h->cfg.layout == STRADS_LAYOUT_GENO2 ? kLoadGeno2 : (h->vec4 ? kLoadVec4 : kLoadScalar);
     GenoCols gc;
@@ -860,7 +897,7 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
         else if (load == kLoadVec4) STRADS_GRAM_DYN(kLoadVec4);
         else STRADS_GRAM_DYN(kLoadScalar);
 #undef STRADS_GRAM_DYN
-        return hipGetLastError();
+        return launch_status(h->stream);
     }
     const int32_t n_jobs = g.T * (g.T - 1) / 2 * g.split_off + g.T * g.split_diag;
     CandDots cd = {};
@@ -876,14 +913,14 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
     else if (load == kLoadVec4) STRADS_GRAM(kLoadVec4);
     else STRADS_GRAM(kLoadScalar);
 #undef STRADS_GRAM
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_mask_from_gram_plain(hipStream_t stream, const float *gram, int32_t l, int32_t lpad, float rho,
                                        uint64_t *mask)
 {
     hipLaunchKernelGGL(k_mask_from_gram, dim3((lpad + 255) / 256, lpad), dim3(256), 0, stream, gram, l, lpad, rho, mask);
-    return hipGetLastError();
+    return launch_status(stream);
 }
 
 hipError_t launch_mask_from_gram(strads_lasso *h, const float *gram, int32_t l)

@@ -72,7 +72,7 @@ extern "C" int strads_lasso_filter_static(const float *gram, int32_t l, float rh
     int32_t *kept = reinterpret_cast<int32_t *>(base + kOffKept);
     RoundScalars *sc = reinterpret_cast<RoundScalars *>(base + kOffScalars);
     hipLaunchKernelGGL(k_iota, dim3((l + 255) / 256), dim3(256), 0, s, ids, l);
-    if (hipGetLastError() != hipSuccess) return STRADS_E_HIP;
+    if (launch_status(s) != hipSuccess) return STRADS_E_HIP;
     if (launch_mask_from_gram_plain(s, gram, l, lpad, rho, mask) != hipSuccess) return STRADS_E_HIP;
     if (launch_filter_plain(s, mask, l, lpad, p_max, ids, kept_pos, kept, sc, n_kept) != hipSuccess) return STRADS_E_HIP;
     return STRADS_OK;

@@ -464,13 +464,14 @@ static inline int sampler_grid(int64_t J)
     return (int)b;
 }
 
-__global__ void k_set_next_round(RoundScalars *sc, unsigned long long t) { sc->next_round = t; }
+// (also run whenever the solver state is set from outside: a CSC range error reported for the old state is dropped)
+__global__ void k_set_next_round(RoundScalars *sc, unsigned long long t) { sc->next_round = t; sc->overflow = 0u; }
 
 hipError_t launch_set_next_round(strads_lasso *h, hipStream_t stream, int64_t next_round)
 {
     hipLaunchKernelGGL(k_set_next_round, dim3(1), dim3(1), 0, stream, h->at<RoundScalars>(h->ws.scalars),
                        (unsigned long long)next_round);
-    return hipGetLastError();
+    return launch_status(stream);
 }
 
 KeysArgs keys_args(strads_lasso *h)
@@ -520,7 +521,7 @@ hipError_t launch_sampler(strads_lasso *h, bool keys_done)
         hipLaunchKernelGGL(k_merge_rank, dim3(n_chunks * 4u), dim3(256), (size_t)n_chunks * 1024u * 8u, h->stream,
                            sorted, L, (uint32_t)h->Lpad, n_chunks, h->at<int32_t>(h->ws.cand));
     }
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys)
@@ -528,7 +529,7 @@ hipError_t launch_keys_only(strads_lasso *h, int64_t round, float *keys)
     hipLaunchKernelGGL(k_keys_only, dim3(sampler_grid(h->cfg.j)), dim3(256), 0, h->stream,
                        h->at<float>(h->ws.dbeta), (uint32_t)h->cfg.j, h->cfg.eta, h->cfg.seed, (uint64_t)round,
                        h->cfg.priority, keys);
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t sampler_prepare()

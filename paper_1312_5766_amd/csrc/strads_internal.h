@@ -43,6 +43,8 @@ struct RoundScalars {
     uint32_t bad_input;    // set by the create-time check of a CSC design
     int32_t n_movers;      // dynamic dependencies: candidates whose update is not zero
     int32_t n_mkept;       // dynamic dependencies: movers that passed the filter
+    uint32_t overflow;     // CSC designs: a product left the range of the fixed-point accumulators (sticky until
+                           // the state is set again); the residual is then written as NaN
 };
 
 // Decomposition of a candidate Gram into workgroup jobs (see gram.hip).  With dynamic
@@ -140,6 +142,28 @@ struct strads_lasso {
 
 namespace strads {
 
+// Status of the launches a launcher has just made.  A debug build (-DSTRADS_DEBUG_SYNC) also waits for
+// them and reports what the kernels themselves ran into, so that a failure is pinned to the launcher that
+// caused it instead of surfacing at some later call.  (Not while the stream is being captured into a
+// graph: nothing runs then.)
+inline hipError_t launch_status(hipStream_t stream)
+{
+    hipError_t e = hipGetLastError();
+#ifdef STRADS_DEBUG_SYNC
+    if (e == hipSuccess) {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(stream, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusNone; }
+        if (cs == hipStreamCaptureStatusNone) {
+            e = hipStreamSynchronize(stream);
+            if (e == hipSuccess) e = hipGetLastError();
+        }
+    }
+#else
+    (void)stream;
+#endif
+    return e;
+}
+
 int gram_split_auto(int64_t n, int32_t lpad);
 size_t gram_partial_floats(int64_t n, int32_t lpad, bool dynamic);   // floats of K-slice partial tiles to reserve
 void gram_shape_table(int64_t n, int32_t lpad, GramShape *out);      // out[t], t = 0 .. lpad/kGramTile
@@ -199,6 +223,7 @@ struct CandDots;
 CandDots cand_dots_args(strads_lasso *h);                 // arguments of the candidates' tentative updates
 hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null);            // -> scalars.kkt_max_bits
 hipError_t launch_init_state(strads_lasso *h);
+hipError_t launch_check_unit_norm(strads_lasso *h);       // sets bit 1 of scalars.bad_input if a column's l2 norm is not 1
 hipError_t launch_init_lane(strads_lasso *h);             // zero a shard's histograms and round scalars
 hipError_t launch_clear_kkt(strads_lasso *h);
 hipError_t sampler_prepare();

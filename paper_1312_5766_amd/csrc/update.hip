@@ -455,7 +455,7 @@ hipError_t launch_dots_dense(strads_lasso *h)
     if (wide) { if (h->vec4) STRADS_DOTS(256, true); else STRADS_DOTS(256, false); }
     else      { if (h->vec4) STRADS_DOTS(64, true);  else STRADS_DOTS(64, false); }
 #undef STRADS_DOTS
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 CandDots cand_dots_args(strads_lasso *h)
@@ -482,7 +482,7 @@ hipError_t launch_dots_cand(strads_lasso *h)
     if (wide) { if (h->vec4) STRADS_DOTS_CAND(256, true); else STRADS_DOTS_CAND(256, false); }
     else      { if (h->vec4) STRADS_DOTS_CAND(64, true);  else STRADS_DOTS_CAND(64, false); }
 #undef STRADS_DOTS_CAND
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 int residual_groups(int64_t n, int32_t l)
@@ -510,7 +510,7 @@ hipError_t launch_residual_dense(strads_lasso *h, bool want_next_keys, bool *nex
         hipLaunchKernelGGL(k_residual_fused, dim3(res_blocks + key_blocks), dim3(1024), 0, h->stream,
                            h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc,
                            h->at<float>(h->ws.r), h->Lpad, res_blocks, keys_args(h));
-        return hipGetLastError();
+        return launch_status(h->stream);
     }
     const int G = residual_groups(h->cfg.n, h->L);
     const dim3 grid((unsigned)((h->cfg.n + 1023) / 1024), (unsigned)G);
@@ -538,7 +538,7 @@ hipError_t launch_residual_apply(strads_lasso *h, int groups, bool want_next_key
     hipLaunchKernelGGL(k_residual_apply, dim3(res_blocks + key_blocks), dim3(256), 0, h->stream,
                        h->at<float>(h->ws.rpart), groups, h->cfg.n, h->Npad, h->at<float>(h->ws.r), res_blocks,
                        keys_args(h));
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_objective(strads_lasso *h)
@@ -553,7 +553,7 @@ hipError_t launch_objective(strads_lasso *h)
                            h->cfg.n, h->at<float>(h->ws.beta), h->cfg.j, (double)h->cfg.lambda, part);
     hipLaunchKernelGGL(k_objective_final, dim3(1), dim3(256), 0, h->stream, part, kObjBlocks,
                        h->at<double>(h->ws.objout));
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null)
@@ -572,7 +572,7 @@ hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null)
         else if (nr <= 12) STRADS_KKT_STREAM(12);
         else STRADS_KKT_STREAM(16);
 #undef STRADS_KKT_STREAM
-        return hipGetLastError();
+        return launch_status(h->stream);
     }
     int64_t gk = wide ? h->cfg.j : (h->cfg.j + 3) / 4;
     if (gk > 256 * 16) gk = 256 * 16;           // persistent: a few workgroups per compute unit
@@ -581,20 +581,20 @@ hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null)
     if (wide) { if (h->vec4) STRADS_KKT(256, true); else STRADS_KKT(256, false); }
     else      { if (h->vec4) STRADS_KKT(64, true);  else STRADS_KKT(64, false); }
 #undef STRADS_KKT
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_logistic_weights(strads_lasso *h)
 {
     hipLaunchKernelGGL(k_logistic_weights, dim3((unsigned)((h->Npad + 255) / 256)), dim3(256), 0, h->stream, h->cfg.y,
                        h->at<float>(h->ws.r), h->cfg.n, h->Npad, h->at<float>(h->ws.w));
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_clear_kkt(strads_lasso *h)
 {
     hipLaunchKernelGGL(k_clear_kkt, dim3(1), dim3(1), 0, h->stream, h->at<RoundScalars>(h->ws.scalars));
-    return hipGetLastError();
+    return launch_status(h->stream);
 }
 
 hipError_t launch_init_state(strads_lasso *h)
@@ -603,7 +603,49 @@ hipError_t launch_init_state(strads_lasso *h)
                        h->cfg.c_init, h->cfg.loss == STRADS_LOSS_LOGISTIC ? 1 : 0,
                        h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.r),
                        h->at<uint32_t>(h->ws.hist), h->at<uint32_t>(h->ws.scalars), (int)(sizeof(RoundScalars) / 4));
-    return hipGetLastError();
+    return launch_status(h->stream);
+}
+
+// The update of eq. (2) has no 1 / ||x_j||^2 factor because columns are standardised to unit l2 norm: a
+// precondition the library states and, in a debug build, checks when a handle is created.  One wavefront
+// per column (grid-stride), the sum of squares in fp32 (fp64 across the wavefront); a column off by more
+// than 1e-3 sets bit 1 of bad_input.
+__global__ __launch_bounds__(256) void k_check_unit_norm(int32_t layout, const float *__restrict__ x, int64_t N, int64_t J,
+                                                         const int32_t *__restrict__ row_idx,
+                                                         const int64_t *__restrict__ col_ptr,
+                                                         const float *__restrict__ col_mean,
+                                                         const float *__restrict__ col_scale, uint32_t *__restrict__ bad)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t words = (N + 63) / 64 * 4;
+    for (int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); j < J; j += (int64_t)gridDim.x * 4) {
+        double s = 0.0;
+        if (layout == STRADS_LAYOUT_DENSE_COLMAJOR) {
+            const float *c = x + j * N;
+            for (int64_t i = lane; i < N; i += 64) s += (double)c[i] * (double)c[i];
+        } else if (layout == STRADS_LAYOUT_CSC) {
+            for (int64_t p = col_ptr[j] + lane; p < col_ptr[j + 1]; p += 64) s += (double)x[p] * (double)x[p];
+        } else {
+            const uint32_t *w = reinterpret_cast<const uint32_t *>(x) + j * words;
+            const float m = col_mean[j], sc = col_scale[j];
+            for (int64_t i = lane; i < N; i += 64) {
+                const float v = __fmul_rn(__fsub_rn((float)((w[i >> 4] >> (2 * (i & 15))) & 3u), m), sc);
+                s += (double)v * (double)v;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off);
+        if (lane == 0 && !(fabs(s - 1.0) <= 1e-3)) atomicOr(bad, 2u);
+    }
+}
+
+hipError_t launch_check_unit_norm(strads_lasso *h)
+{
+    const int64_t want = (h->cfg.j + 3) / 4;
+    hipLaunchKernelGGL(k_check_unit_norm, dim3((unsigned)(want < 8192 ? want : 8192)), dim3(256), 0, h->stream,
+                       h->cfg.layout, h->cfg.x, h->cfg.n, h->cfg.j, h->cfg.row_idx, h->cfg.col_ptr, h->cfg.col_mean,
+                       h->cfg.col_scale, &h->at<RoundScalars>(h->ws.scalars)->bad_input);
+    return launch_status(h->stream);
 }
 
 } // namespace strads

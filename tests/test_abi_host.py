@@ -118,3 +118,24 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         b.load()
+
+
+def test_debug_build_exports_the_same_symbols_and_says_what_it_is():
+    path = os.path.join(ROOT, "paper_1312_5766_amd", "libstrads_lasso_debug.so")
+    assert os.path.exists(path), "build it with `python -m paper_1312_5766_amd.build --debug`"
+    dbg = C.CDLL(path)
+    for n in _declared_functions():
+        assert hasattr(dbg, n), n
+    assert dbg.strads_lasso_debug_build() == 1
+    assert pk.load().strads_lasso_debug_build() == (1 if os.environ.get("STRADS_LASSO_DEBUG") == "1" else 0)
+
+
+def test_static_filter_rejects_bad_arguments_before_any_device_call():
+    lib = pk.load()
+    f = lib.strads_lasso_filter_static
+    assert f(None, 2, 0.1, 0, 1, 1, None) == b.E_INVALID_ARG
+    assert f(1, 0, 0.1, 0, 1, 1, None) == b.E_INVALID_ARG
+    assert f(1, 2, float("nan"), 0, 1, 1, None) == b.E_INVALID_ARG
+    assert f(1, 2, 0.1, -1, 1, 1, None) == b.E_INVALID_ARG
+    assert f(1, b.FILTER_STATIC_MAX_L + 1, 0.1, 0, 1, 1, None) == b.E_TOO_LARGE
+    assert b"maximum" in lib.strads_lasso_strerror(b.E_TOO_LARGE)

@@ -286,3 +286,29 @@ def test_stage_functions_csc_equal_dense_and_logistic_wrappers():
         a = 4.0 * zz[c] + float(beta[j])
         want = np.float32(math.copysign(max(abs(a) - 4.0 * float(np.float32(0.3)), 0.0), a))
         assert b[j] == want and dl[c] == float(want) - float(beta[j])
+
+
+def test_unchecked_updates_of_copies_of_one_column_diverge():
+    # Section 2's remark: updating correlated variables in parallel can diverge.  64 copies of one unit
+    # column updated together overshoot 63-fold per round; the dependency check (rho = 0.1) lets one copy
+    # through per round and the objective falls.
+    rng = np.random.default_rng(0)
+    col = rng.normal(size=256)
+    col -= col.mean()
+    col /= np.linalg.norm(col)
+    x = np.tile(col.astype(np.float32), (64, 1))
+    y = (3.0 * col + 0.01 * rng.normal(size=256)).astype(np.float32)
+    wild = OracleLasso(x=x, y=y, lam=0.01, rho=0.1, eta=1e-6, l_prime=64, no_deps=True, priority="uniform")
+    f0 = wild.objective()
+    for _ in range(6):
+        out = wild.round()
+        assert len(out["kept"]) == 64
+    assert wild.objective() > 1e15 * f0
+    with np.errstate(all="ignore"):
+        for _ in range(40):
+            wild.round()
+    assert not np.isfinite(wild.objective())
+    tame = OracleLasso(x=x, y=y, lam=0.01, rho=0.1, eta=1e-6, l_prime=64)
+    for _ in range(5):
+        assert len(tame.round()["kept"]) == 1
+    assert tame.objective() < 0.01 * f0
