@@ -279,9 +279,10 @@ int strads_lasso_filter_static(const float *gram, int32_t l, float rho, int32_t 
  *                   the launch of the round's last kernel (of the residual update) also carries the next
  *                   round's key pass; 0: every round starts with its own
  *                   key pass.  Identical results.
- *   "residual_fused" 1 (default): dense designs with l_prime <= 4096 apply r -= X_B delta_B in one
- *                   kernel; 0: always the two-stage update (partial sums per column group, then their
- *                   sum).  The two differ in fp32 summation order only.
+ *   "residual_fused" 1 (default): dense designs apply r -= X_B delta_B in one kernel where one exists for the
+ *                   shape (l_prime <= 4096; longer lists over 16-byte aligned columns of at least 4096 rows);
+ *                   0: always the two-stage update (partial sums per column group, then their sum).  The
+ *                   routes differ in fp32 summation order only.
  *   "profile_level", "profile_rounds"   see strads_lasso_stage_times
  * Returns STRADS_E_INVALID_ARG for an unknown name or a value out of range. */
 int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value);

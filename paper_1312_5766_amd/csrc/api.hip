@@ -184,6 +184,7 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->lanes[0] = h;
     int rc = STRADS_OK;
     if (sampler_prepare() != hipSuccess || gram_prepare() != hipSuccess || filter_prepare() != hipSuccess ||
+        update_prepare() != hipSuccess ||
         (cfg->layout == STRADS_LAYOUT_CSC && csc_prepare() != hipSuccess))
         rc = STRADS_E_HIP;
     // the other scheduler shards: same problem, own per-shard block of the workspace, own stream

@@ -50,6 +50,52 @@ __device__ __forceinline__ float column_dot(const float *__restrict__ x, const f
     return s;                                   // valid in thread 0 of the group
 }
 
+// Two columns at once by a workgroup of 256 threads: every piece of r is loaded once and used for both
+// columns, which takes a third off the requests to the L2 (r lives there; X comes from HBM).  Each
+// column's sum is formed exactly as column_dot<256, VEC4> forms it (same partial sums, same order), so
+// the two routes give the same bits.  Results in sa, sb, valid in thread 0.
+template <bool VEC4>
+__device__ __forceinline__ void column_dot2(const float *__restrict__ xa, const float *__restrict__ xb,
+                                            const float *__restrict__ r, int64_t N, int t, float (*red)[4],
+                                            float &sa, float &sb)
+{
+    constexpr int TPC = 256;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f, b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
+    if (VEC4) {
+        const float4 *xa4 = reinterpret_cast<const float4 *>(xa);
+        const float4 *xb4 = reinterpret_cast<const float4 *>(xb);
+        const float4 *r4 = reinterpret_cast<const float4 *>(r);
+        const int64_t n4 = N >> 2;
+        int64_t i = t;
+        for (; i + 3 * TPC < n4; i += 4 * TPC) {
+            const float4 p0 = xa4[i], p1 = xa4[i + TPC], p2 = xa4[i + 2 * TPC], p3 = xa4[i + 3 * TPC];
+            const float4 q0 = xb4[i], q1 = xb4[i + TPC], q2 = xb4[i + 2 * TPC], q3 = xb4[i + 3 * TPC];
+            const float4 v0 = r4[i], v1 = r4[i + TPC], v2 = r4[i + 2 * TPC], v3 = r4[i + 3 * TPC];
+            a0 += p0.x * v0.x + p0.y * v0.y + p0.z * v0.z + p0.w * v0.w;
+            a1 += p1.x * v1.x + p1.y * v1.y + p1.z * v1.z + p1.w * v1.w;
+            a2 += p2.x * v2.x + p2.y * v2.y + p2.z * v2.z + p2.w * v2.w;
+            a3 += p3.x * v3.x + p3.y * v3.y + p3.z * v3.z + p3.w * v3.w;
+            b0 += q0.x * v0.x + q0.y * v0.y + q0.z * v0.z + q0.w * v0.w;
+            b1 += q1.x * v1.x + q1.y * v1.y + q1.z * v1.z + q1.w * v1.w;
+            b2 += q2.x * v2.x + q2.y * v2.y + q2.z * v2.z + q2.w * v2.w;
+            b3 += q3.x * v3.x + q3.y * v3.y + q3.z * v3.z + q3.w * v3.w;
+        }
+        for (; i < n4; i += TPC) {
+            const float4 p = xa4[i], q = xb4[i], v = r4[i];
+            a0 += p.x * v.x + p.y * v.y + p.z * v.z + p.w * v.w;
+            b0 += q.x * v.x + q.y * v.y + q.z * v.z + q.w * v.w;
+        }
+    } else {
+        for (int64_t i = t; i < N; i += TPC) { const float v = r[i]; a0 += xa[i] * v; b0 += xb[i] * v; }
+    }
+    const float wa = wave_sum((a0 + a1) + (a2 + a3)), wb = wave_sum((b0 + b1) + (b2 + b3));
+    if ((t & 63) == 0) { red[0][t >> 6] = wa; red[1][t >> 6] = wb; }
+    __syncthreads();
+    sa = sb = 0.f;
+    if (t == 0)
+        for (int w = 0; w < TPC / 64; ++w) { sa += red[0][w]; sb += red[1][w]; }
+}
+
 __device__ __forceinline__ float soft_threshold(float a, float lambda)
 {
     const float m = fabsf(a) - lambda;
@@ -85,6 +131,33 @@ __device__ __forceinline__ void cand_dots_block(const float *__restrict__ X, int
         cd.zc[c] = s;
         cd.nbc[c] = nb;
         cd.dc[c] = nb - b;
+    }
+}
+
+// The same for candidate positions 2*block and 2*block + 1 by one workgroup (long columns, stand-alone kernel).
+template <bool VEC4>
+__device__ __forceinline__ void cand_dots_pair(const float *__restrict__ X, int64_t N,
+                                               const int32_t *__restrict__ cand, const CandDots &cd, int block,
+                                               float (*red)[4])
+{
+    const int c0 = 2 * block;
+    if (c0 >= cd.L) return;
+    const bool two = c0 + 1 < cd.L;
+    const int32_t ja = cand[c0], jb = cand[two ? c0 + 1 : c0];
+    const float ba = cd.beta[ja], bb = cd.beta[jb];
+    float sa, sb;
+    column_dot2<VEC4>(X + (int64_t)ja * N, X + (int64_t)jb * N, cd.r, N, (int)threadIdx.x, red, sa, sb);
+    if (threadIdx.x == 0) {
+        const float na = soft_threshold(sa * cd.step + ba, cd.lambda * cd.step);
+        cd.zc[c0] = sa;
+        cd.nbc[c0] = na;
+        cd.dc[c0] = na - ba;
+        if (two) {
+            const float nb = soft_threshold(sb * cd.step + bb, cd.lambda * cd.step);
+            cd.zc[c0 + 1] = sb;
+            cd.nbc[c0 + 1] = nb;
+            cd.dc[c0 + 1] = nb - bb;
+        }
     }
 }
 

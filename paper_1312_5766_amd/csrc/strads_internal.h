@@ -229,6 +229,7 @@ hipError_t launch_clear_kkt(strads_lasso *h);
 hipError_t sampler_prepare();
 hipError_t gram_prepare();
 hipError_t filter_prepare();
+hipError_t update_prepare();
 // packed genotype design (STRADS_LAYOUT_GENO2); the Gram uses launch_gram_dense with a decoding loader
 inline int64_t geno_words(int64_t n) { return (n + 63) / 64 * 4; }   // 32-bit words per column
 hipError_t launch_dots_geno(strads_lasso *h);

@@ -50,6 +50,48 @@ __global__ __launch_bounds__(256) void k_dots_update(const float *__restrict__ X
     }
 }
 
+// Long columns (a workgroup per column pays one pass over r per column): kept positions 2b and 2b + 1 by
+// workgroup b, r read once for both.  Same arithmetic per column as k_dots_update<256, VEC4>.
+template <bool VEC4>
+__global__ __launch_bounds__(256) void k_dots_update_pair(const float *__restrict__ X, int64_t N,
+                                                          const int32_t *__restrict__ kept,
+                                                          const RoundScalars *__restrict__ sc,
+                                                          const float *__restrict__ r, float lambda, float step,
+                                                          float *__restrict__ beta, float *__restrict__ dbeta,
+                                                          float *__restrict__ z, float *__restrict__ delta)
+{
+    __shared__ float red[2][4];
+    const int c0 = 2 * (int)blockIdx.x, k = sc->n_kept;
+    if (c0 >= k) return;
+    const bool two = c0 + 1 < k;
+    const int32_t ja = kept[c0], jb = kept[two ? c0 + 1 : c0];
+    const float ba = beta[ja], bb = beta[jb];   // requested with the columns, not after the reduction
+    float sa, sb;
+    column_dot2<VEC4>(X + (int64_t)ja * N, X + (int64_t)jb * N, r, N, (int)threadIdx.x, red, sa, sb);
+    if (threadIdx.x == 0) {
+        const float na = soft_threshold(sa * step + ba, lambda * step);
+        z[c0] = sa;
+        delta[c0] = na - ba;
+        beta[ja] = na;
+        dbeta[ja] = fabsf(na - ba);
+        if (two) {
+            const float nb = soft_threshold(sb * step + bb, lambda * step);
+            z[c0 + 1] = sb;
+            delta[c0 + 1] = nb - bb;
+            beta[jb] = nb;
+            dbeta[jb] = fabsf(nb - bb);
+        }
+    }
+}
+
+template <bool VEC4>
+__global__ __launch_bounds__(256) void k_dots_cand_pair(const float *__restrict__ X, int64_t N,
+                                                        const int32_t *__restrict__ cand, CandDots cd)
+{
+    __shared__ float red[2][4];
+    cand_dots_pair<VEC4>(X, N, cand, cd, (int)blockIdx.x, red);
+}
+
 // Dynamic dependencies: the update every candidate would make from the current residual.  For
 // candidate position c < L: zc[c] = x_j^T r, nbc[c] = S(zc + beta_j, lambda), dc[c] = nbc - beta_j.
 // Nothing of the solver state is written: which candidates are committed is decided later.
@@ -271,6 +313,114 @@ __global__ __launch_bounds__(1024) void k_residual_fused(const float *__restrict
     }
 }
 
+// Long candidate lists (more than kFusedResidualMaxL) over 16-byte aligned columns: the same one-kernel
+// scheme with 256 rows per workgroup, four per lane, so that a wavefront takes 1 KB of a column at a
+// time and has eight columns in flight.  Nothing but X is streamed: no partial sums go through HBM and no
+// second kernel adds them up.  Wavefront w sums movers w, w+16, ... in list order, the 16 sums are added
+// in wavefront order: the result does not depend on how the launch is laid out.
+__global__ __launch_bounds__(1024) void k_residual_rows(const float *__restrict__ X, int64_t N,
+                                                        const int32_t *__restrict__ kept,
+                                                        const float *__restrict__ delta,
+                                                        RoundScalars *__restrict__ sc, float *__restrict__ r,
+                                                        int32_t lpad, uint32_t res_blocks, KeysArgs next_keys)
+{
+    if (blockIdx.x >= res_blocks) {
+        keys_hist_block(next_keys, blockIdx.x - res_blocks, gridDim.x - res_blocks);
+        return;
+    }
+    extern __shared__ int32_t rows_lds[];       // [lpad] mover columns, then [lpad] their changes (8 * lpad bytes)
+    int32_t *mcol = rows_lds;
+    float *mdel = reinterpret_cast<float *>(rows_lds + lpad);
+    __shared__ uint32_t wcnt[16];
+    __shared__ float4 red[16][64];
+    __shared__ float wmax[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t i = ((int64_t)blockIdx.x * 64 + lane) * 4;        // N is a multiple of 4 here
+    // everything this thread will want of the kept list whatever its length turns out to be (entries
+    // tid, tid + 1024, ... of the lpad-entry lists) and its rows of r are requested at once, before the
+    // count is known: one trip to memory instead of one per 1024 entries
+    constexpr int kMaxPass = STRADS_MAX_L_PRIME / 1024;
+    float dq[kMaxPass];
+    int32_t cq[kMaxPass];
+#pragma unroll
+    for (int p = 0; p < kMaxPass; ++p) {
+        const int a = p * 1024 + tid;
+        const int at = a < lpad ? a : 0;
+        dq[p] = delta[at];
+        cq[p] = kept[at];
+    }
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float4 r_old = (wave == 0 && i < N) ? *reinterpret_cast<const float4 *>(r + i) : zero4;
+    const int k = sc->n_kept;
+    uint32_t tot = 0;
+    float dmax = 0.f;
+#pragma unroll
+    for (int p = 0; p < kMaxPass; ++p) {        // the movers (delta != 0) of the kept list, in list order
+        if (p * 1024 >= k) break;               // uniform
+        const int a = p * 1024 + tid;
+        const float d = a < k ? dq[p] : 0.f;
+        const bool mv = d != 0.f;
+        const uint64_t m = __ballot(mv);
+        if (lane == 0) wcnt[wave] = (uint32_t)__popcll(m);
+        __syncthreads();
+        uint32_t before = 0, here = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) { const uint32_t v = wcnt[w]; if (w < wave) before += v; here += v; }
+        if (mv) {
+            const uint32_t pos = tot + before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            mcol[pos] = cq[p];
+            mdel[pos] = d;
+        }
+        tot += here;
+        dmax = fmaxf(dmax, fabsf(d));
+        __syncthreads();
+    }
+
+    float4 acc = zero4;
+    if (i < N) {
+        const float *xi = X + i;
+        uint32_t q = (uint32_t)wave;
+        for (; q + 112u < tot; q += 128u) {     // eight columns in flight
+            float4 v[8];
+            float dd[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                v[u] = *reinterpret_cast<const float4 *>(xi + (int64_t)mcol[q + 16u * u] * N);
+                dd[u] = mdel[q + 16u * u];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                acc.x += v[u].x * dd[u]; acc.y += v[u].y * dd[u]; acc.z += v[u].z * dd[u]; acc.w += v[u].w * dd[u];
+            }
+        }
+        for (; q < tot; q += 16u) {
+            const float4 v = *reinterpret_cast<const float4 *>(xi + (int64_t)mcol[q] * N);
+            const float dd = mdel[q];
+            acc.x += v.x * dd; acc.y += v.y * dd; acc.z += v.z * dd; acc.w += v.w * dd;
+        }
+    }
+    red[wave][lane] = acc;
+    if (blockIdx.x == 0) {                      // round summary for strads_lasso_round's info
+        float mx = dmax;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_down(mx, off));
+        if (lane == 0) wmax[wave] = mx;
+    }
+    __syncthreads();
+    if (wave == 0 && i < N) {
+        float4 t = zero4;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) { const float4 p = red[w][lane]; t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w; }
+        *reinterpret_cast<float4 *>(r + i) = make_float4(r_old.x - t.x, r_old.y - t.y, r_old.z - t.z, r_old.w - t.w);
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        float mx = 0.f;
+        for (int w = 0; w < 16; ++w) mx = fmaxf(mx, wmax[w]);
+        sc->n_moved = (int32_t)tot;
+        sc->max_abs_delta = mx;
+    }
+}
+
 // eq. (1): 1/2 sum r_i^2 + lambda sum |beta_j|, fp64 accumulation, two fixed-order stages
 __global__ __launch_bounds__(256) void k_objective_partial(const float *__restrict__ r, int64_t N,
                                                            const float *__restrict__ beta, int64_t J, double lambda,
@@ -450,11 +600,16 @@ hipError_t launch_dots_dense(strads_lasso *h)
     const float *r = dots_vector(h);
     const int32_t *kept = h->at<int32_t>(h->ws.kept);
     const bool wide = h->cfg.n > 2048;
-    const unsigned grid = wide ? (unsigned)h->L : (unsigned)((h->L + 3) / 4);
-#define STRADS_DOTS(TPC, V) hipLaunchKernelGGL((k_dots_update<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, kept, sc, r, h->cfg.lambda, h->step_scale, h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.z), h->at<float>(h->ws.delta))
-    if (wide) { if (h->vec4) STRADS_DOTS(256, true); else STRADS_DOTS(256, false); }
-    else      { if (h->vec4) STRADS_DOTS(64, true);  else STRADS_DOTS(64, false); }
-#undef STRADS_DOTS
+    const unsigned grid = wide ? (unsigned)((h->L + 1) / 2) : (unsigned)((h->L + 3) / 4);
+#define STRADS_DOTS_ARGS dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, kept, sc, r, h->cfg.lambda, h->step_scale, h->at<float>(h->ws.beta), h->at<float>(h->ws.dbeta), h->at<float>(h->ws.z), h->at<float>(h->ws.delta)
+    if (wide) {
+        if (h->vec4) hipLaunchKernelGGL((k_dots_update_pair<true>), STRADS_DOTS_ARGS);
+        else hipLaunchKernelGGL((k_dots_update_pair<false>), STRADS_DOTS_ARGS);
+    } else {
+        if (h->vec4) hipLaunchKernelGGL((k_dots_update<64, true>), STRADS_DOTS_ARGS);
+        else hipLaunchKernelGGL((k_dots_update<64, false>), STRADS_DOTS_ARGS);
+    }
+#undef STRADS_DOTS_ARGS
     return launch_status(h->stream);
 }
 
@@ -476,12 +631,17 @@ CandDots cand_dots_args(strads_lasso *h)
 hipError_t launch_dots_cand(strads_lasso *h)
 {
     const bool wide = h->cfg.n > 2048;
-    const unsigned grid = wide ? (unsigned)h->L : (unsigned)((h->L + 3) / 4);
+    const unsigned grid = wide ? (unsigned)((h->L + 1) / 2) : (unsigned)((h->L + 3) / 4);
     const CandDots cd = cand_dots_args(h);
-#define STRADS_DOTS_CAND(TPC, V) hipLaunchKernelGGL((k_dots_cand<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), cd)
-    if (wide) { if (h->vec4) STRADS_DOTS_CAND(256, true); else STRADS_DOTS_CAND(256, false); }
-    else      { if (h->vec4) STRADS_DOTS_CAND(64, true);  else STRADS_DOTS_CAND(64, false); }
-#undef STRADS_DOTS_CAND
+#define STRADS_DOTS_CAND_ARGS dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), cd
+    if (wide) {
+        if (h->vec4) hipLaunchKernelGGL((k_dots_cand_pair<true>), STRADS_DOTS_CAND_ARGS);
+        else hipLaunchKernelGGL((k_dots_cand_pair<false>), STRADS_DOTS_CAND_ARGS);
+    } else {
+        if (h->vec4) hipLaunchKernelGGL((k_dots_cand<64, true>), STRADS_DOTS_CAND_ARGS);
+        else hipLaunchKernelGGL((k_dots_cand<64, false>), STRADS_DOTS_CAND_ARGS);
+    }
+#undef STRADS_DOTS_CAND_ARGS
     return launch_status(h->stream);
 }
 
@@ -508,6 +668,20 @@ hipError_t launch_residual_dense(strads_lasso *h, bool want_next_keys, bool *nex
             *next_keys_done = true;
         }
         hipLaunchKernelGGL(k_residual_fused, dim3(res_blocks + key_blocks), dim3(1024), 0, h->stream,
+                           h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc,
+                           h->at<float>(h->ws.r), h->Lpad, res_blocks, keys_args(h));
+        return launch_status(h->stream);
+    }
+    if (h->residual_fused && h->vec4 && h->cfg.n >= 4096) {
+        // a long list over long, 16-byte aligned columns: one kernel, 256 rows per workgroup
+        const unsigned res_blocks = (unsigned)((h->cfg.n / 4 + 63) / 64);
+        unsigned key_blocks = 0;
+        if (want_next_keys && h->n_lanes == 1) {
+            key_blocks = (unsigned)((h->Js + 4095) / 4096);
+            if (key_blocks > 256u) key_blocks = 256u;
+            *next_keys_done = true;
+        }
+        hipLaunchKernelGGL(k_residual_rows, dim3(res_blocks + key_blocks), dim3(1024), (size_t)h->Lpad * 8, h->stream,
                            h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc,
                            h->at<float>(h->ws.r), h->Lpad, res_blocks, keys_args(h));
         return launch_status(h->stream);
@@ -637,6 +811,13 @@ __global__ __launch_bounds__(256) void k_check_unit_norm(int32_t layout, const f
         for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off);
         if (lane == 0 && !(fabs(s - 1.0) <= 1e-3)) atomicOr(bad, 2u);
     }
+}
+
+hipError_t update_prepare()
+{
+    // the long-list residual kernel keeps the mover list (up to 8192 columns and changes) in dynamic LDS
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_residual_rows),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, STRADS_MAX_L_PRIME * 8);
 }
 
 hipError_t launch_check_unit_norm(strads_lasso *h)
