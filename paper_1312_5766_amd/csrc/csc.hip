@@ -5,7 +5,12 @@
 //   candidate Gram   A dense MFMA Gram of gathered sparse columns would multiply zeros.  Instead an
 //                    inverted index of the candidate set is built per round (row -> list of
 //                    (candidate, value)); candidate a then walks its own rows and, for every other
-//                    candidate met in a row, adds the product into an LDS row G[a][*].
+//                    candidate met in a row, adds the product into an LDS row G[a][*].  The index is
+//                    one kernel: every row owns a bucket of fixed capacity (a few times the expected
+//                    load), an entry takes the next free slot of its row's bucket with one atomic, and
+//                    the few entries that find their bucket full go to one overflow list that every
+//                    reader scans too; no counting pass, no scan over the rows, no second pass over
+//                    the columns.
 //   residual update  r -= sum_j x_j * change_j scatters into rows that several columns may share.
 //
 // Both accumulate through integer atomics on a 2^-40 fixed-point image of each product (the fp64
@@ -29,39 +34,51 @@ __device__ __forceinline__ long long fix40(float a, float b)
 }
 
 struct CscEntry { int32_t cand; float val; };
+struct CscOverflow { int32_t row, cand; float val; };
 
 struct CscScratch {
-    uint32_t *cnt;          // [N]   per-row entry count (returns to zero after the fill pass)
-    uint32_t *row_start;    // [N+1] exclusive scan of cnt
-    uint32_t *chunk_total;  // [ceil(N/4096)] scan scratch
-    CscEntry *entries;      // [L * max_col_nnz]
+    uint32_t *cnt;          // [N]   entries that asked for a slot of the row's bucket (zeroed again by the round's last kernel)
+    uint32_t *ovf_cnt;      // [1]   entries in the overflow list (likewise)
+    CscEntry *bucket;       // [N * cap]  row i owns bucket[i * cap .. +cap)
+    CscOverflow *ovf;       // [L * max_col_nnz]  entries whose bucket was full
     long long *racc;        // [N]   fixed-point residual accumulator (returns to zero after apply)
+    int32_t cap;            // bucket capacity
 };
+
+// Bucket capacity: four times the expected number of candidate entries per row plus 8, rounded up to a
+// power of two, between 8 and 64 (N = 10^5, 4000 candidates of 100 nonzeros: load 4, capacity 32, a bucket
+// is two cache lines; a row that gets more sends the rest to the overflow list).
+static int32_t csc_bucket_cap(int64_t n, int32_t l, int32_t max_col_nnz)
+{
+    const double load = (double)l * (double)(max_col_nnz > 0 ? max_col_nnz : 1) / (double)(n > 0 ? n : 1);
+    int32_t cap = 8;
+    while (cap < 64 && (double)cap < 4.0 * load + 8.0) cap *= 2;
+    return cap;
+}
+
+static size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 
 static CscScratch csc_carve(const strads_lasso *h)
 {
     char *p = h->base + h->ws.csc_scratch;
     const size_t n = (size_t)h->cfg.n;
-    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
     CscScratch s;
-    s.cnt = (uint32_t *)p;               p += up(n * 4);
-    s.row_start = (uint32_t *)p;         p += up((n + 1) * 4);
-    s.chunk_total = (uint32_t *)p;       p += up(((n + 4095) / 4096 + 1) * 4);
-    s.racc = (long long *)p;             p += up(n * 8);
-    s.entries = (CscEntry *)p;
+    s.cap = csc_bucket_cap(h->cfg.n, h->L, h->cfg.max_col_nnz);
+    s.cnt = (uint32_t *)p;               p += up256(n * 4);
+    s.ovf_cnt = (uint32_t *)p;           p += 256;
+    s.racc = (long long *)p;             p += up256(n * 8);
+    s.bucket = (CscEntry *)p;            p += up256(n * (size_t)s.cap * sizeof(CscEntry));
+    s.ovf = (CscOverflow *)p;
     return s;
 }
 
 size_t csc_scratch_bytes(int64_t n, int32_t l, int32_t max_col_nnz)
 {
-    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
-    return up((size_t)n * 4) + up(((size_t)n + 1) * 4) + up((((size_t)n + 4095) / 4096 + 1) * 4) + up((size_t)n * 8) +
-           up((size_t)l * (size_t)(max_col_nnz > 0 ? max_col_nnz : 1) * sizeof(CscEntry));
+    const size_t cap = (size_t)csc_bucket_cap(n, l, max_col_nnz);
+    return up256((size_t)n * 4) + 256 + up256((size_t)n * 8) + up256((size_t)n * cap * sizeof(CscEntry)) +
+           up256((size_t)l * (size_t)(max_col_nnz > 0 ? max_col_nnz : 1) * sizeof(CscOverflow));
 }
 
-// ---------------------------------------------------------------------------------------------
-// create-time check: col_ptr non-decreasing, starts at 0, no column longer than max_col_nnz
-// ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_csc_check(const int64_t *__restrict__ col_ptr, int64_t J, int32_t max_col_nnz,
                                                    uint32_t *__restrict__ bad)
 {
@@ -73,97 +90,51 @@ __global__ __launch_bounds__(256) void k_csc_check(const int64_t *__restrict__ c
 }
 
 __global__ __launch_bounds__(256) void k_csc_zero(uint32_t *__restrict__ cnt, long long *__restrict__ racc, int64_t N,
-                                                  uint32_t *__restrict__ bad)
+                                                  uint32_t *__restrict__ bad, uint32_t *__restrict__ ovf_cnt)
 {
     const int64_t stride = (int64_t)gridDim.x * 256;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < N; i += stride) { cnt[i] = 0u; racc[i] = 0; }
-    if (blockIdx.x == 0 && threadIdx.x == 0) *bad = 0u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) { *bad = 0u; *ovf_cnt = 0u; }
 }
 
 // ---------------------------------------------------------------------------------------------
 // inverted index of the candidate set
 // ---------------------------------------------------------------------------------------------
-// n_dev != NULL (dynamic dependencies): the list is the movers, counted on the device; workgroups
+// n_dev != NULL (dynamic dependencies): the list is the movers, counted on the device; wavefronts
 // past the count have nothing to do.
-__global__ __launch_bounds__(64) void k_csc_count(const int32_t *__restrict__ cand, const GramShape *__restrict__ n_dev,
-                                                  const int64_t *__restrict__ col_ptr,
-                                                  const int32_t *__restrict__ row_idx, uint32_t *__restrict__ cnt)
+//
+// One wavefront per candidate a: every nonzero (row, value) of its column takes the next slot of the
+// row's bucket (cnt[row] counts the requests, so it may pass the capacity); past the capacity the entry
+// goes to the overflow list.  The order of the entries in a bucket depends on which atomic lands first;
+// nothing downstream depends on it (the products are summed in fixed point).
+__global__ __launch_bounds__(256) void k_csc_build(const int32_t *__restrict__ cand, const GramShape *__restrict__ n_dev,
+                                                   int32_t L, const int64_t *__restrict__ col_ptr,
+                                                   const int32_t *__restrict__ row_idx, const float *__restrict__ val,
+                                                   uint32_t *__restrict__ cnt, CscEntry *__restrict__ bucket, int32_t cap,
+                                                   uint32_t *__restrict__ ovf_cnt, CscOverflow *__restrict__ ovf)
 {
-    if (n_dev && (int32_t)blockIdx.x >= n_dev->L) return;
-    const int32_t j = cand[blockIdx.x];
-    const int64_t p0 = col_ptr[j], p1 = col_ptr[j + 1];
-    for (int64_t p = p0 + threadIdx.x; p < p1; p += 64) atomicAdd(&cnt[row_idx[p]], 1u);
-}
-
-// exclusive scan of cnt[0..N) in two kernels.  (1) every workgroup scans its own 4096 rows and
-// leaves the chunk total; (2) every workgroup adds the totals of the chunks before it.
-constexpr int kScanChunk = 4096;
-
-__global__ __launch_bounds__(1024) void k_csc_scan_local(const uint32_t *__restrict__ cnt, int64_t N,
-                                                         uint32_t *__restrict__ row_start,
-                                                         uint32_t *__restrict__ chunk_total)
-{
-    __shared__ uint32_t wsum[16];
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int64_t i0 = (int64_t)blockIdx.x * kScanChunk + (int64_t)t * 4;
-    uint32_t v[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) v[q] = i0 + q < N ? cnt[i0 + q] : 0u;
-    const uint32_t mine = v[0] + v[1] + v[2] + v[3];
-    uint32_t inc = mine;                                   // inclusive scan across the wavefront
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) { const uint32_t u = __shfl_up(inc, d); if (lane >= d) inc += u; }
-    if (lane == 63) wsum[wave] = inc;
-    __syncthreads();
-    uint32_t before = 0, total = 0;
-#pragma unroll
-    for (int w = 0; w < 16; ++w) { const uint32_t u = wsum[w]; if (w < wave) before += u; total += u; }
-    uint32_t run = before + inc - mine;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) { if (i0 + q < N) row_start[i0 + q] = run; run += v[q]; }
-    if (t == 0) chunk_total[blockIdx.x] = total;
-}
-
-__global__ __launch_bounds__(1024) void k_csc_scan_add(int64_t N, int32_t n_chunks, uint32_t *__restrict__ row_start,
-                                                       const uint32_t *__restrict__ chunk_total)
-{
-    __shared__ uint32_t part[16];
-    __shared__ uint32_t base_s;
-    const int t = threadIdx.x;
-    uint32_t s = 0;
-    for (int c = t; c < (int)blockIdx.x; c += 1024) s += chunk_total[c];
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off);
-    if ((t & 63) == 0) part[t >> 6] = s;
-    __syncthreads();
-    if (t == 0) { uint32_t b = 0; for (int w = 0; w < 16; ++w) b += part[w]; base_s = b; }
-    __syncthreads();
-    const uint32_t base = base_s;
-    const int64_t i0 = (int64_t)blockIdx.x * kScanChunk + (int64_t)t * 4;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) if (i0 + q < N) row_start[i0 + q] += base;
-    if ((int)blockIdx.x == n_chunks - 1 && t == 0) row_start[N] = base + chunk_total[blockIdx.x];
-}
-
-// place (candidate, value) into its row's bucket; the count doubles as a countdown cursor, so it is
-// back at zero when the pass ends
-__global__ __launch_bounds__(64) void k_csc_fill(const int32_t *__restrict__ cand, const GramShape *__restrict__ n_dev,
-                                                 const int64_t *__restrict__ col_ptr,
-                                                 const int32_t *__restrict__ row_idx, const float *__restrict__ val,
-                                                 const uint32_t *__restrict__ row_start, uint32_t *__restrict__ cnt,
-                                                 CscEntry *__restrict__ entries)
-{
-    if (n_dev && (int32_t)blockIdx.x >= n_dev->L) return;
-    const int32_t a = blockIdx.x;
+    if (n_dev) L = n_dev->L;
+    const int32_t a = (int32_t)blockIdx.x * 4 + (int32_t)(threadIdx.x >> 6);
+    if (a >= L) return;
     const int32_t j = cand[a];
     const int64_t p0 = col_ptr[j], p1 = col_ptr[j + 1];
-    for (int64_t p = p0 + threadIdx.x; p < p1; p += 64) {
+    for (int64_t p = p0 + (threadIdx.x & 63); p < p1; p += 64) {
         const int32_t row = row_idx[p];
-        const uint32_t slot = atomicSub(&cnt[row], 1u) - 1u;
-        CscEntry e;
-        e.cand = a;
-        e.val = val[p];
-        entries[row_start[row] + slot] = e;
+        const float v = val[p];
+        const uint32_t slot = atomicAdd(&cnt[row], 1u);
+        if (slot < (uint32_t)cap) {
+            CscEntry e;
+            e.cand = a;
+            e.val = v;
+            bucket[(int64_t)row * cap + slot] = e;
+        } else {
+            const uint32_t o = atomicAdd(ovf_cnt, 1u);
+            CscOverflow e;
+            e.row = row;
+            e.cand = a;
+            e.val = v;
+            ovf[o] = e;
+        }
     }
 }
 
@@ -171,8 +142,9 @@ __global__ __launch_bounds__(64) void k_csc_fill(const int32_t *__restrict__ can
 __global__ __launch_bounds__(256) void k_csc_gram(const int32_t *__restrict__ cand, const GramShape *__restrict__ n_dev,
                                                   const int64_t *__restrict__ col_ptr,
                                                   const int32_t *__restrict__ row_idx, const float *__restrict__ val,
-                                                  const uint32_t *__restrict__ row_start,
-                                                  const CscEntry *__restrict__ entries, int32_t L, int32_t Lpad,
+                                                  const uint32_t *__restrict__ cnt, const CscEntry *__restrict__ bucket,
+                                                  int32_t cap, const uint32_t *__restrict__ ovf_cnt,
+                                                  const CscOverflow *__restrict__ ovf, int32_t L, int32_t Lpad,
                                                   float rho, uint64_t *__restrict__ mask, float *__restrict__ gram,
                                                   int32_t *__restrict__ near_pairs)
 {
@@ -187,14 +159,24 @@ __global__ __launch_bounds__(256) void k_csc_gram(const int32_t *__restrict__ ca
     if (a < L) {
         const int32_t j = cand[a];
         const int64_t p0 = col_ptr[j], p1 = col_ptr[j + 1];
+        const uint32_t n_ovf = *ovf_cnt;
         for (int64_t p = p0 + tid; p < p1; p += 256) {
             const int32_t row = row_idx[p];
             const float v = val[p];
-            const uint32_t s = row_start[row], e = row_start[row + 1];
-            for (uint32_t q = s; q < e; ++q) {
-                const CscEntry en = entries[q];
+            const uint32_t asked = cnt[row];
+            const uint32_t m = asked < (uint32_t)cap ? asked : (uint32_t)cap;
+            const CscEntry *b = bucket + (int64_t)row * cap;
+            for (uint32_t q = 0; q < m; ++q) {
+                const CscEntry en = b[q];
                 if (en.cand >= first || gram)
                     atomicAdd((unsigned long long *)&acc[en.cand], (unsigned long long)fix40(v, en.val));
+            }
+            if (asked > (uint32_t)cap) {          // the rest of this row's entries are somewhere in the overflow list
+                for (uint32_t q = 0; q < n_ovf; ++q) {
+                    const CscOverflow en = ovf[q];
+                    if (en.row == row && (en.cand >= first || gram))
+                        atomicAdd((unsigned long long *)&acc[en.cand], (unsigned long long)fix40(v, en.val));
+                }
             }
         }
     }
@@ -327,14 +309,17 @@ __global__ __launch_bounds__(256) void k_csc_residual_acc(const float *__restric
 // next round's key pass: it needs delta beta as this round leaves it and nothing this kernel writes.
 __global__ __launch_bounds__(256) void k_csc_residual_apply(long long *__restrict__ racc, int64_t N,
                                                             float *__restrict__ r, uint32_t res_blocks,
-                                                            KeysArgs next_keys, const RoundScalars *__restrict__ sc)
+                                                            KeysArgs next_keys, const RoundScalars *__restrict__ sc,
+                                                            uint32_t *__restrict__ cnt, uint32_t *__restrict__ ovf_cnt)
 {
     if (blockIdx.x >= res_blocks) {
         keys_hist_block(next_keys, blockIdx.x - res_blocks, gridDim.x - res_blocks);
         return;
     }
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i == 0) *ovf_cnt = 0u;                    // the round's inverted index is done with: empty it for the next round
     if (i >= N) return;
+    if (cnt[i] != 0u) cnt[i] = 0u;
     const long long v = racc[i];
     if (sc->overflow) {
         // a product left the accumulator's range (set by the kernel before this one): the sums are not
@@ -385,7 +370,7 @@ hipError_t csc_prepare()
 hipError_t launch_csc_init(strads_lasso *h, uint32_t *bad_dev)
 {
     const CscScratch s = csc_carve(h);
-    hipLaunchKernelGGL(k_csc_zero, dim3(1024), dim3(256), 0, h->stream, s.cnt, s.racc, h->cfg.n, bad_dev);
+    hipLaunchKernelGGL(k_csc_zero, dim3(1024), dim3(256), 0, h->stream, s.cnt, s.racc, h->cfg.n, bad_dev, s.ovf_cnt);
     hipLaunchKernelGGL(k_csc_check, dim3(1024), dim3(256), 0, h->stream, h->cfg.col_ptr, h->cfg.j,
                        h->cfg.max_col_nnz, bad_dev);
     return launch_status(h->stream);
@@ -399,17 +384,10 @@ hipError_t launch_gram_csc(strads_lasso *h)
     const int32_t *cand = dynamic ? h->at<int32_t>(h->ws.mcand) : h->at<int32_t>(h->ws.cand);
     const GramShape *n_dev = dynamic ? h->at<GramShape>(h->ws.dshape) : nullptr;
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
-    hipLaunchKernelGGL(k_csc_count, dim3(h->L), dim3(64), 0, h->stream, cand, n_dev, h->cfg.col_ptr, h->cfg.row_idx,
-                       s.cnt);
-    const int32_t n_chunks = (int32_t)((h->cfg.n + kScanChunk - 1) / kScanChunk);
-    hipLaunchKernelGGL(k_csc_scan_local, dim3(n_chunks), dim3(1024), 0, h->stream, s.cnt, h->cfg.n, s.row_start,
-                       s.chunk_total);
-    hipLaunchKernelGGL(k_csc_scan_add, dim3(n_chunks), dim3(1024), 0, h->stream, h->cfg.n, n_chunks, s.row_start,
-                       s.chunk_total);
-    hipLaunchKernelGGL(k_csc_fill, dim3(h->L), dim3(64), 0, h->stream, cand, n_dev, h->cfg.col_ptr, h->cfg.row_idx,
-                       h->cfg.x, s.row_start, s.cnt, s.entries);
+    hipLaunchKernelGGL(k_csc_build, dim3((h->L + 3) / 4), dim3(256), 0, h->stream, cand, n_dev, h->L, h->cfg.col_ptr,
+                       h->cfg.row_idx, h->cfg.x, s.cnt, s.bucket, s.cap, s.ovf_cnt, s.ovf);
     hipLaunchKernelGGL(k_csc_gram, dim3(h->L), dim3(256), (size_t)h->Lpad * 8, h->stream, cand, n_dev, h->cfg.col_ptr,
-                       h->cfg.row_idx, h->cfg.x, s.row_start, s.entries, h->L, h->Lpad, h->cfg.rho,
+                       h->cfg.row_idx, h->cfg.x, s.cnt, s.bucket, s.cap, s.ovf_cnt, s.ovf, h->L, h->Lpad, h->cfg.rho,
                        h->at<uint64_t>(h->ws.mask), h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr,
                        &sc->near_rho_pairs);
     return launch_status(h->stream);
@@ -449,7 +427,7 @@ hipError_t launch_residual_csc(strads_lasso *h, bool want_next_keys, bool *next_
     }
     hipLaunchKernelGGL(k_csc_residual_apply, dim3(res_blocks + key_blocks), dim3(256), 0, h->stream, s.racc,
                        h->cfg.n, h->at<float>(h->ws.r), res_blocks, keys_args(h),
-                       h->at<RoundScalars>(h->ws.scalars));
+                       h->at<RoundScalars>(h->ws.scalars), s.cnt, s.ovf_cnt);
     return launch_status(h->stream);
 }
 

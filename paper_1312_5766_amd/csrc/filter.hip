@@ -435,8 +435,8 @@ static hipError_t launch_filter_kernel(hipStream_t stream, const uint64_t *mask,
 #define STRADS_FILTER(IPT, A, TPR) hipLaunchKernelGGL((k_filter<IPT, A, TPR>), dim3(1), dim3(64 + 64 * TPR), 0, stream, mask, l, W, gdev, p_max, cand, kept_pos, kept, sc, n_out, count_updates ? 1 : 0, cm)
     // words of a row per holder thread = ceil(W / threads per row); short rows can afford more chunks in flight
     if (W <= 16) STRADS_FILTER(4, 8, 4);
-    else if (W <= 32) STRADS_FILTER(8, 6, 4);
-    else if (W <= 64) STRADS_FILTER(16, 4, 4);
+    else if (W <= 32) STRADS_FILTER(4, 6, 8);
+    else if (W <= 64) STRADS_FILTER(8, 4, 8);
     else STRADS_FILTER(16, 3, 8);
 #undef STRADS_FILTER
     return launch_status(stream);
