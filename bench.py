@@ -254,7 +254,9 @@ def run_sweep(args) -> int:
     the dot products of the kept set and the residual update (HBM streams).  Each point is a synthetic
     i.i.d. design with exactly L' columns (every column is a candidate in every round), a threshold no
     pair reaches (every candidate is kept) and lambda = 0 (every kept coordinate moves): k = k1 = L'.
-    Kernel times are the library's per-stage HIP events averaged over the timed rounds."""
+    Kernel times are the library's per-stage HIP events averaged over the timed rounds.  The dot products
+    are taken by their own kernel for every list length (a short list would otherwise fold them into the
+    Gram launch); the residual update takes the route the library picks for the shape."""
     import torch
     import paper_1312_5766_amd as pk
     pk.load()
@@ -271,6 +273,7 @@ def run_sweep(args) -> int:
             x /= x.norm(dim=1, keepdim=True)
             y = torch.randn(n, generator=gen, device=dev, dtype=torch.float32)
             s = pk.StradsLasso(x=x, y=y, lam=0.0, rho=2.0, eta=1e-6, l_prime=l, seed=0)
+            s.set_tuning("dots_with_gram", 0)      # the kept-set dot products as a kernel of their own, so that they can be timed
             for t in args.tune:
                 name, value = t.split("=")
                 s.set_tuning(name, int(value))

@@ -280,7 +280,8 @@ int strads_lasso_filter_static(const float *gram, int32_t l, float rho, int32_t 
  *                   round's key pass; 0: every round starts with its own
  *                   key pass.  Identical results.
  *   "residual_fused" 1 (default): dense designs apply r -= X_B delta_B in one kernel where one exists for the
- *                   shape (l_prime <= 4096; longer lists over 16-byte aligned columns of at least 4096 rows);
+ *                   shape (l_prime <= 4096; more than 1024 candidates over 16-byte aligned columns of at least
+ *                   32768 rows);
  *                   0: always the two-stage update (partial sums per column group, then their sum).  The
  *                   routes differ in fp32 summation order only.
  *   "profile_level", "profile_rounds"   see strads_lasso_stage_times

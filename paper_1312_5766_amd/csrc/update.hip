@@ -659,31 +659,26 @@ hipError_t launch_residual_dense(strads_lasso *h, bool want_next_keys, bool *nex
 {
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     *next_keys_done = false;
-    if (h->residual_fused && h->L <= kFusedResidualMaxL) {
-        const unsigned res_blocks = (unsigned)((h->cfg.n + 63) / 64);
+    // one kernel where one fits the shape: long, 16-byte aligned columns and more than 1024 candidates take
+    // 256 rows per workgroup (it needs N / 256 workgroups to be enough to fill the chip); lists of at most
+    // 4096 take 64 rows per workgroup; what is left (long lists over short columns) is done in two stages
+    const bool rows = h->vec4 && h->cfg.n >= 32768 && h->L > 1024;
+    if (h->residual_fused && (rows || h->L <= kFusedResidualMaxL)) {
+        const unsigned res_blocks = rows ? (unsigned)((h->cfg.n / 4 + 63) / 64) : (unsigned)((h->cfg.n + 63) / 64);
         unsigned key_blocks = 0;
         if (want_next_keys && h->n_lanes == 1) {
             key_blocks = (unsigned)((h->Js + 4095) / 4096);         // four keys per thread, at most 256 workgroups
             if (key_blocks > 256u) key_blocks = 256u;
             *next_keys_done = true;
         }
-        hipLaunchKernelGGL(k_residual_fused, dim3(res_blocks + key_blocks), dim3(1024), 0, h->stream,
-                           h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc,
-                           h->at<float>(h->ws.r), h->Lpad, res_blocks, keys_args(h));
-        return launch_status(h->stream);
-    }
-    if (h->residual_fused && h->vec4 && h->cfg.n >= 4096) {
-        // a long list over long, 16-byte aligned columns: one kernel, 256 rows per workgroup
-        const unsigned res_blocks = (unsigned)((h->cfg.n / 4 + 63) / 64);
-        unsigned key_blocks = 0;
-        if (want_next_keys && h->n_lanes == 1) {
-            key_blocks = (unsigned)((h->Js + 4095) / 4096);
-            if (key_blocks > 256u) key_blocks = 256u;
-            *next_keys_done = true;
-        }
-        hipLaunchKernelGGL(k_residual_rows, dim3(res_blocks + key_blocks), dim3(1024), (size_t)h->Lpad * 8, h->stream,
-                           h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc,
-                           h->at<float>(h->ws.r), h->Lpad, res_blocks, keys_args(h));
+        if (rows)
+            hipLaunchKernelGGL(k_residual_rows, dim3(res_blocks + key_blocks), dim3(1024), (size_t)h->Lpad * 8, h->stream,
+                               h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc,
+                               h->at<float>(h->ws.r), h->Lpad, res_blocks, keys_args(h));
+        else
+            hipLaunchKernelGGL(k_residual_fused, dim3(res_blocks + key_blocks), dim3(1024), 0, h->stream,
+                               h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.kept), h->at<float>(h->ws.delta), sc,
+                               h->at<float>(h->ws.r), h->Lpad, res_blocks, keys_args(h));
         return launch_status(h->stream);
     }
     const int G = residual_groups(h->cfg.n, h->L);

@@ -269,6 +269,9 @@ def test_config1_free_run_objective_trajectory():
     ("c3_genotype", dict(n=500, j=20000, nnz=20, l_prime=700), 6),
     ("c5_dense_duplicates", dict(n=3000, j=5000, nnz=30, l_prime=400), 8),
     ("c1_dense_iid", dict(n=1003, j=900, nnz=10, l_prime=150), 6),        # N not a multiple of 4
+    # long columns, a list between 1024 and 4096: x_j^T r two columns per workgroup (ragged: odd kept counts occur),
+    # the residual update in one kernel with 256 rows per workgroup and a ragged last workgroup
+    ("c5_dense_duplicates", dict(n=33004, j=2600, nnz=30, l_prime=1300, lam_frac=0.01), 3),
 ])
 def test_reduced_configs_teacher_forced(config, kw, rounds):
     p = si.make(config, **kw)
