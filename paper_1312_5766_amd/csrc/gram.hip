@@ -741,8 +741,10 @@ static GramShape gram_shape(const strads_lasso *h)
 //     works on one or two slices of all tiles, and a panel row crosses the fabric once or twice, not eight times;
 //   * within a slice by blocks of 8 x 8 tiles (block row, block column, then tile row, tile column; a
 //     diagonal tile sits where its row and column meet): the 64 tiles of a block need 16 panels between
-//     them, where 64 consecutive tiles of one tile row need 65.  For a long candidate list (one slice,
-//     thousands of tiles) this is what keeps most panel reads inside the L2.
+//     them, where 64 consecutive tiles of one tile row need 65.  What this buys is modest, because the
+//     workgroups of an XCD do not stay in step over the thousands of stages of a long slice: for 8000
+//     candidates over 50000 rows the L2 miss rate of the launch falls from 45 % to 36 % of requests, and the
+//     kernel, which is bound by the matrix pipe, takes the same time.
 size_t gram_job_table_entries(int64_t n, int32_t lpad)
 {
     const size_t T = (size_t)(lpad / kGramTile);
