@@ -63,7 +63,7 @@ extern "C" {
                                              16 times fewer bytes than fp32 for every pass over X. */
 
 #define STRADS_MAX_L_PRIME         8192   /* largest supported candidate count per round */
-/* Loss function of eq. (1) (Section 2.1: "squared-loss or logistic-loss").
+/* Loss function of eq. (1) (Section 2.1 allows the squared and the logistic loss).
  *   SQUARED   L = 1/2 ||y - X beta||^2; the state vector r kept between rounds is the residual
  *             y - X beta, and eq. (2) is beta_j <- S(x_j^T r + beta_j, lambda).
  *   LOGISTIC  L = sum_i log(1 + exp(-y_i x_i^T beta)) with labels y_i in {-1, +1} (not checked).  The
@@ -126,7 +126,7 @@ typedef struct {
     float          lambda;        /* regularisation weight of eq. (1), >= 0, finite */
     float          rho;           /* dependency threshold of Step 2, > 0 */
     float          eta;           /* priority floor of Algorithm 1, >= 1e-30 */
-    float          c_init;        /* Algorithm 1's "very large constant" C: initial delta beta (> 0) */
+    float          c_init;        /* Algorithm 1's large initial constant C: initial delta beta (> 0) */
     int32_t        l_prime;       /* P': candidates per round, 1..STRADS_MAX_L_PRIME; clamped to j */
     int32_t        p_max;         /* P: cap on the kept set; 0 = keep every admissible candidate */
     uint64_t       seed;          /* keys the counter-based random stream with (round, j) */

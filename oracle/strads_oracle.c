@@ -353,8 +353,8 @@ double oracle_objective(int64_t N, const float *r, int64_t J, const float *beta,
 }
 
 /* --------------------------------------------------------------------------
- * Logistic loss.  Section 2.1 lets L in eq. (1) be "squared-loss or logistic-loss" and says the
- * latter is handled "using the same approach" as in the parallel coordinate descent work it cites;
+ * Logistic loss.  Section 2.1 lets L in eq. (1) be the squared or the logistic loss and says the
+ * latter is handled in the same way as in the parallel coordinate descent work it cites;
  * no formula is given.  Taken here: labels y_i in {-1, +1},
  *      L(beta) = sum_i log(1 + exp(-y_i m_i)),   m = X beta,
  * whose derivative along coordinate j is -x_j^T w with w_i = y_i / (1 + exp(y_i m_i)), and whose

@@ -1,5 +1,5 @@
-// Step 2 of SAP for the Lasso, second half (Algorithm 1: "choose a set B_1 of <= P coefficients
-// from U such that |x_j^T x_k| < rho for all pairs"): walk the candidates in draw order and keep
+// Step 2 of SAP for the Lasso, second half (Algorithm 1's choice of B_1: at most P of the drawn
+// candidates, every pair of them correlated below rho): walk the candidates in draw order and keep
 // one iff it conflicts with nothing kept so far.
 //
 // The walk is sequential in the kept set, so the work is arranged to keep the serial chain short.

@@ -1,5 +1,5 @@
-// Step 1 of SAP for the Lasso (Section 2.1, Step 1; Algorithm 1's "draw a set U of P'
-// coefficients"; Theorem 1's weight): draw P' distinct coordinates with probability
+// Step 1 of SAP for the Lasso (Section 2.1, Step 1; Algorithm 1's draw of the set U of P'
+// coefficients; Theorem 1's weight): draw P' distinct coordinates with probability
 // proportional to w_j = (delta beta_j)^2 + eta.
 //
 // Successive sampling without replacement is done with the Gumbel-top-k identity: the P'
