@@ -35,7 +35,7 @@ EXPORTS = [
     "strads_lasso_objective", "strads_lasso_kkt", "strads_lasso_get_state", "strads_lasso_set_state",
     "strads_lasso_last_round", "strads_lasso_last_candidates", "strads_lasso_stage_keys", "strads_lasso_stage_filter",
     "strads_lasso_set_tuning", "strads_lasso_stage_times", "strads_lasso_last_kkt_ms", "strads_lasso_destroy",
-    "strads_lasso_strerror", "strads_lasso_filter_static", "strads_lasso_debug_build",
+    "strads_lasso_strerror", "strads_lasso_filter_static", "strads_lasso_debug_build", "strads_lasso_gram256_plan",
 ]
 
 
@@ -90,6 +90,7 @@ def load():
     L.strads_lasso_stage_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     L.strads_lasso_filter_static.argtypes = [vp, C.c_int32, C.c_float, C.c_int32, vp, vp, vp]
     L.strads_lasso_debug_build.argtypes = []
+    L.strads_lasso_gram256_plan.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.POINTER(C.c_int32), vp, vp]
     L.strads_lasso_destroy.argtypes = [vp]
     L.strads_lasso_destroy.restype = None
     L.strads_lasso_strerror.argtypes = [C.c_int]
@@ -117,10 +118,26 @@ def _ptr(t: Optional[torch.Tensor]):
 
 
 def strads_lasso_workspace_bytes(n, j, l_prime, layout=LAYOUT_DENSE, keep_gram=False, max_col_nnz=0,
-                                 dynamic=False) -> int:
+                                 dynamic=False, n_shards=0) -> int:
     cfg = Config(n=n, j=j, layout=layout, l_prime=l_prime, keep_gram=int(keep_gram), max_col_nnz=int(max_col_nnz),
-                 deps=DEPS_DYNAMIC if dynamic else DEPS_STATIC)
+                 deps=DEPS_DYNAMIC if dynamic else DEPS_STATIC, n_shards=int(n_shards))
     return int(load().strads_lasso_workspace_bytes(C.byref(cfg)))
+
+
+GRAM256_MAX_PIECES = 8
+
+
+def strads_lasso_gram256_plan(n: int, l: int, planes_cap: int):
+    """Host only.  (workgroups, pieces, planes): pieces is an int32 array [256][GRAM256_MAX_PIECES][5] of
+    (tile row, tile column, first stage, end stage, plane), planes an int32 array [T][T], T = ceil(l / 256)."""
+    import numpy as np
+    wgs = C.c_int32(0)
+    t = (l + 255) // 256
+    pieces = np.zeros((256, GRAM256_MAX_PIECES, 5), np.int32)
+    planes = np.zeros((t, t), np.int32)
+    _check(load().strads_lasso_gram256_plan(int(n), int(l), int(planes_cap), C.byref(wgs), pieces.ctypes.data,
+                                            planes.ctypes.data), "strads_lasso_gram256_plan")
+    return wgs.value, pieces, planes
 
 
 def strads_lasso_filter_static(gram: torch.Tensor, rho: float, p_max: int, kept_pos: torch.Tensor,

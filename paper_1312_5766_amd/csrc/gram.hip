@@ -26,6 +26,7 @@
 // results do not depend on scheduling.
 #include "strads_internal.h"
 #include "dots.h"
+#include <string.h>
 #include <algorithm>
 #include <type_traits>
 #include <utility>
@@ -487,6 +488,232 @@ __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int6
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Long candidate lists over 16-byte aligned fp32 columns: 256 x 256 output tiles.
+//
+// A global load instruction costs the matrix pipe the same however little it brings (measured: the 128 x 128
+// kernel above takes 12 % less time when its loads are left out, whether they would have hit the L2 or not),
+// and a 256 x 256 tile needs half as many of them per MFMA.  A workgroup of 8 wavefronts (two per SIMD, one
+// workgroup per compute unit: two LDS stages of 512 columns take 144 KB) owns the tile; wavefront (wr, wc)
+// holds rows 128 wr .. +127 and columns 64 wc .. +63 of it as 4 x 2 MFMA accumulators (128 AGPRs).
+//
+// With one workgroup per compute unit and a few hundred tiles the work is dealt out as a stream: the
+// (tile, stage) pairs are laid end to end and every workgroup takes an equal run of them, which covers the
+// end of one tile, whole tiles, and the start of another.  A tile therefore arrives in up to a few pieces
+// (two when there are more tiles than workgroups); piece p of a tile is written to partial plane p and the mask
+// kernel adds a tile's planes in order, so the sum does not depend on timing.  The runs are computed on the
+// host when the handle is created (BigPiece table).
+//
+// A tile on the diagonal stages its 256 columns once and multiplies only the 36 of its 64 32 x 32 blocks on or
+// above the diagonal, dealt out to the wavefronts so that no SIMD gets more than 10 (an off-diagonal tile: 16);
+// the stream counts a stage of a diagonal tile as 10/16 of a stage accordingly.  Blocks above the diagonal
+// of a 128 x 128 diagonal square are also stored mirrored, as the mask kernel expects that square complete.
+constexpr int kBigTile = 256;
+constexpr int32_t kJobBlock = 8;                        // tiles per side of a block of jobs that share panels in one L2
+constexpr int kBigThreads = 512;
+constexpr int kBigPanel = kBigTile * kRow;              // floats per 256-column operand panel per stage
+constexpr int kBigColsPerPass = kBigThreads / kKQ;      // columns the 512 threads stage in one pass
+constexpr int kBigPasses = kBigTile / kBigColsPerPass;  // passes per panel
+constexpr int kBigMaxPieces = 8;                        // pieces per workgroup the table has room for
+
+struct BigPiece {
+    int32_t ta, tb;         // tile (256-column groups), ta <= tb
+    int32_t sbeg, send;     // stages [sbeg, send) of kGramKT rows each; send <= sbeg: no piece
+    int32_t plane;          // partial plane the piece is written to
+    int32_t pad_[3];
+};
+
+// BOTH, RIGHT: which of the wavefront's blocks are multiplied (see below); compile-time, because a choice made
+// at run time around the MFMA statements makes the compiler copy accumulators between registers right behind
+// them, and it does not know how long their results take.
+template <bool DIAG, uint32_t BOTH, uint32_t RIGHT>
+__device__ __forceinline__ void gram_piece256(const float *__restrict__ X, int64_t N,
+                                              const int32_t *__restrict__ cand, int32_t L, int32_t Lpad,
+                                              const BigPiece pc, int ra, int cb, float *__restrict__ P, float *smem)
+{
+    constexpr int NPAN = DIAG ? 1 : 2;
+    constexpr int NLD = NPAN * kBigPasses;
+    constexpr int kStage = NPAN * kBigPanel;            // floats per LDS stage
+    const int tid = threadIdx.x;
+    const int64_t kbeg = (int64_t)pc.sbeg * kGramKT;
+    const int64_t kend = (int64_t)pc.send * kGramKT < N ? (int64_t)pc.send * kGramKT : N;
+    const int nstage = pc.send - pc.sbeg;
+    const int nfull = (int)((kend - kbeg) / kGramKT);
+
+    // staging: thread -> column (it * 64 + tid / 8) of each panel, floats (tid % 8) * 4 .. +3 of the stage
+    const int crow = tid / kKQ, kq = (tid % kKQ) * 4;
+    const float *col[NLD];
+    float4 R[NLD];
+#pragma unroll
+    for (int p = 0; p < NPAN; ++p)
+#pragma unroll
+        for (int it = 0; it < kBigPasses; ++it) {
+            int i = (p == 0 ? pc.ta : pc.tb) * kBigTile + it * kBigColsPerPass + crow;
+            i = i < L ? i : L - 1;                      // columns past the list: clamped, their products are never read
+            col[p * kBigPasses + it] = X + (int64_t)cand[i] * N;
+        }
+    auto fetch = [&](int st) {
+        const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) R[i] = load_k4<true>(col[i], k, kend);
+    };
+    auto fetch_full = [&](int st) {
+        const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) R[i] = *reinterpret_cast<const float4 *>(col[i] + k);
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < NPAN; ++p)
+#pragma unroll
+            for (int it = 0; it < kBigPasses; ++it)
+                *reinterpret_cast<float4 *>(smem + buf * kStage + p * kBigPanel +
+                                            (it * kBigColsPerPass + crow) * kRow + kq) = R[p * kBigPasses + it];
+    };
+
+    const int lane = tid & 63;
+    const int li = lane & 31, lh = lane >> 5;
+    // The wavefront's blocks: rows 32 (ra + a) .. +31, columns 32 (cb + b) .. +31 of the tile, a < 4, b < 2.
+    // BOTH = rows a whose two blocks are multiplied, RIGHT = rows a of which only the block b = 1 is.
+    constexpr uint32_t both = DIAG ? BOTH : 0xFu, right = DIAG ? RIGHT : 0u;
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    const int offa = (ra * 32 + li) * kRow + lh * 4;
+    const int offb = (DIAG ? 0 : kBigPanel) + (cb * 32 + li) * kRow + lh * 4;
+    // Operands of one 8-row K step: lane (li, lh) holds k = 8*ks + 4*lh .. +3 of its four A rows and two B
+    // columns.  The 32 MFMAs of a step go A row by A row; as soon as a row's eight are issued its registers
+    // take the same row of the next step, and the next step's B columns are requested at the start of the
+    // step: 32 operand registers instead of 48, every LDS read at least eight MFMAs ahead of its use.
+    struct Ops { float4 a[4], b[2]; };
+    auto lds_ops = [&](int buf, int ks) { return smem + buf * kStage + ks * 8; };
+    auto read_a = [&](const float *base, int a) {
+        return *reinterpret_cast<const float4 *>(base + offa + a * 32 * kRow);
+    };
+    auto read_b = [&](const float *base, int b) {
+        return *reinterpret_cast<const float4 *>(base + offb + b * 32 * kRow);
+    };
+    auto mma_row = [&](int a, const float4 &av4, const float4 (&bv4)[2]) {
+        const float av[4] = {av4.x, av4.y, av4.z, av4.w};
+        const float b0[4] = {bv4[0].x, bv4[0].y, bv4[0].z, bv4[0].w}, b1[4] = {bv4[1].x, bv4[1].y, bv4[1].z, bv4[1].w};
+        if (both >> a & 1u) {                           // a is a constant once the loops are unrolled
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                mfma32(acc[a][0], av[c], b0[c]);
+                mfma32(acc[a][1], av[c], b1[c]);
+            }
+        } else if (right >> a & 1u) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) mfma32(acc[a][1], av[c], b1[c]);
+        }
+    };
+    // One stage: multiply stage `buf` out of LDS; `cur` holds the operands of its first K step.  `between`
+    // (the next stage's LDS writes, the global loads of the stage after) runs behind the first eight MFMAs.
+    // The stage's one barrier sits before its last K step: by then every wavefront has written its share of
+    // the next stage and nobody reads that buffer any more, so the last step can already request the next
+    // stage's first operands.  `more`: another stage follows.
+    auto stage = [&](int buf, Ops &cur, bool more, auto between) {
+#pragma unroll
+        for (int ks = 0; ks < kGramKT / 8; ++ks) {
+            const bool last = ks + 1 == kGramKT / 8;
+            if (last && more) __syncthreads();
+            const bool ahead = !last || more;
+            const float *nb = last ? lds_ops(buf ^ 1, 0) : lds_ops(buf, ks + 1);
+            float4 bn[2] = {cur.b[0], cur.b[1]};
+            if (ahead) { bn[0] = read_b(nb, 0); bn[1] = read_b(nb, 1); }
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                mma_row(a, cur.a[a], cur.b);
+                if (ahead) cur.a[a] = read_a(nb, a);
+                if (ks == 0 && a == 0) between();
+            }
+            cur.b[0] = bn[0];
+            cur.b[1] = bn[1];
+        }
+    };
+    auto read_ops = [&](int buf, int ks) {
+        const float *base = lds_ops(buf, ks);
+        Ops o;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) o.a[a] = read_a(base, a);
+#pragma unroll
+        for (int b = 0; b < 2; ++b) o.b[b] = read_b(base, b);
+        return o;
+    };
+
+    fetch(0);
+    stash(0);
+    if (nstage > 1) fetch(1);
+    __syncthreads();
+    Ops cur = read_ops(0, 0);
+    int st = 0;
+    for (; st + 2 < nfull; ++st)                // steady state
+        stage(st & 1, cur, true, [&] { stash((st + 1) & 1); fetch_full(st + 2); });
+    for (; st + 2 < nstage; ++st)               // a ragged last stage is fetched with clamping
+        stage(st & 1, cur, true, [&] { stash((st + 1) & 1); fetch(st + 2); });
+    if (st + 1 < nstage) {
+        stage(st & 1, cur, true, [&] { stash((st + 1) & 1); });
+        ++st;
+    }
+    stage(st & 1, cur, false, [] {});
+    mfma_drain();
+
+    float *out = P + (int64_t)pc.plane * Lpad * Lpad;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int rb = ra + a, cbk = cb + b;        // row and column block inside the tile
+            const int row0 = pc.ta * kBigTile + rb * 32, col0 = pc.tb * kBigTile + cbk * 32;
+            const bool mine = (both >> a & 1u) || (b == 1 && (right >> a & 1u));
+            if (!mine || row0 >= Lpad || col0 >= Lpad) continue;
+            store_block(out, Lpad, row0, col0, acc[a][b], li, lh);
+            // inside a diagonal 128 x 128 square the mask kernel expects both triangles
+            if (DIAG && rb != cbk && rb / 4 == cbk / 4) store_block_t(out, Lpad, row0, col0, acc[a][b], li, lh);
+        }
+}
+
+__global__ __launch_bounds__(kBigThreads, 1) void k_gram_tiles256(const float *__restrict__ X, int64_t N,
+                                                                  const int32_t *__restrict__ cand, int32_t L,
+                                                                  int32_t Lpad, const BigPiece *__restrict__ pieces,
+                                                                  float *__restrict__ P)
+{
+    extern __shared__ float smem[];             // [2 stages][A panel | B panel]
+    const BigPiece *mine = pieces + (size_t)blockIdx.x * kBigMaxPieces;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    for (int i = 0; i < kBigMaxPieces; ++i) {
+        const BigPiece pc = mine[i];
+        if (pc.send <= pc.sbeg) break;          // uniform: the table is the same for every thread
+        if (pc.ta != pc.tb) {
+            // wavefront (wr, wc) = (wave / 4, wave % 4): rows 128 wr .. +127, columns 64 wc .. +63, all eight blocks
+            gram_piece256<false, 0xFu, 0u>(X, N, cand, L, Lpad, pc, (wave >> 2) * 4, (wave & 3) * 2, P, smem);
+        } else {
+            // On the diagonal only the 36 blocks with row block <= column block are needed; they are dealt out so
+            // that the two wavefronts of a SIMD (w and w + 4) have 8, 8, 10 and 10 of them between them:
+            //   w0 / w4: rows 0-3 x cols 6,7 (a = 0,1 / a = 2,3)      w1 / w5: rows 0-3 x cols 4,5 (a = 0,1 / a = 2,3)
+            //   w2: rows 4-7 x cols 6,7 (7 blocks)   w6: rows 4-7 x cols 4,5 (3)
+            //   w3: rows 0-3 x cols 2,3 (7 blocks)   w7: rows 0-3 x cols 0,1 (3)
+            switch (wave) {
+            case 0: gram_piece256<true, 0x3u, 0u>(X, N, cand, L, Lpad, pc, 0, 6, P, smem); break;
+            case 1: gram_piece256<true, 0x3u, 0u>(X, N, cand, L, Lpad, pc, 0, 4, P, smem); break;
+            case 4: gram_piece256<true, 0xCu, 0u>(X, N, cand, L, Lpad, pc, 0, 6, P, smem); break;
+            case 5: gram_piece256<true, 0xCu, 0u>(X, N, cand, L, Lpad, pc, 0, 4, P, smem); break;
+            case 2: gram_piece256<true, 0x7u, 0x8u>(X, N, cand, L, Lpad, pc, 4, 6, P, smem); break;
+            case 3: gram_piece256<true, 0x7u, 0x8u>(X, N, cand, L, Lpad, pc, 0, 2, P, smem); break;
+            case 6: gram_piece256<true, 0x1u, 0x2u>(X, N, cand, L, Lpad, pc, 4, 4, P, smem); break;
+            default: gram_piece256<true, 0x1u, 0x2u>(X, N, cand, L, Lpad, pc, 0, 0, P, smem); break;
+            }
+        }
+        __syncthreads();                        // the next piece reuses the LDS stages
+    }
+}
+
 // One job = one (tile, K-slice) pair.  Jobs are numbered with the off-diagonal tiles of the upper
 // triangle first (K-slice fastest), then the diagonal tiles.
 template <int LOAD>
@@ -566,11 +793,13 @@ __device__ __forceinline__ uint64_t spread_every_4th(uint64_t x)
 // A thread owns 4 consecutive columns b of one row a (16-byte loads of every slice), a wavefront
 // 256 columns = four 64-bit mask words, assembled from one ballot per column-in-thread; only
 // columns in the tiles at or right of a's diagonal tile exist.  gdev != NULL: the shape is read
-// from device memory (dynamic dependencies) and the grid strides over it.
+// from device memory (dynamic dependencies) and the grid strides over it.  planes256 != NULL: the tiles
+// were written by k_gram_tiles256, and a tile's slice count is looked up there.
 __global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, GramShape gh,
                                                    const GramShape *__restrict__ gdev, float rho,
                                                    uint64_t *__restrict__ mask, float *__restrict__ gram,
-                                                   int32_t *__restrict__ near_pairs)
+                                                   int32_t *__restrict__ near_pairs,
+                                                   const int32_t *__restrict__ planes256, int32_t T2)
 {
     const GramShape g = gdev ? *gdev : gh;
     const int32_t L = g.L, Lpad = g.Lpad;
@@ -586,7 +815,9 @@ __global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, 
             const bool have = b >= first && b < Lpad;
             float v[4] = {0.f, 0.f, 0.f, 0.f};
             if (have) {
-                const int32_t split = b < first + kGramTile ? g.split_diag : g.split_off;
+                // 256-wide tiles: planes256[tile] partial planes hold pieces of tile (a / 256, b / 256)
+                const int32_t split = planes256 ? planes256[(a / kBigTile) * T2 + b / kBigTile]
+                                                : (b < first + kGramTile ? g.split_diag : g.split_off);
                 const float *p = P + (int64_t)a * Lpad + b;
                 int32_t s = 0;
                 for (; s + 7 < split; s += 8) {             // eight slices in flight, added in slice order
@@ -715,9 +946,117 @@ __host__ __device__ static inline GramShape gram_shape_for(int64_t n, int32_t L,
     return g;
 }
 
+// The stream of (tile, stage) pairs of the 256-wide route, cut into equal runs for `wgs` workgroups.
+// Tiles are ordered in blocks of 8 x 8 (an XCD's workgroups then work on neighbouring tiles, which share
+// panels in its L2), and workgroup b, which runs on XCD b mod 8, takes run (b mod 8) * wgs / 8 + b / 8.
+// Returns the number of partial planes the cut needs (the most pieces any tile falls into), 0 if a workgroup
+// would get more than kBigMaxPieces pieces.  pieces ([wgs][kBigMaxPieces]) and planes ([T2 * T2]) may be NULL.
+static int32_t gram256_cut(int64_t n, int32_t lpad, int32_t wgs, BigPiece *pieces, int32_t *planes)
+{
+    const int32_t T2 = (lpad + kBigTile - 1) / kBigTile;
+    const int64_t S = (n + kGramKT - 1) / kGramKT;
+    struct Tile { int32_t ta, tb; };
+    std::vector<Tile> tiles;
+    for (int32_t bi = 0; bi * kJobBlock < T2; ++bi)
+        for (int32_t bj = bi; bj * kJobBlock < T2; ++bj)
+            for (int32_t ta = bi * kJobBlock; ta < (bi + 1) * kJobBlock && ta < T2; ++ta)
+                for (int32_t tb = bj * kJobBlock; tb < (bj + 1) * kJobBlock && tb < T2; ++tb)
+                    if (ta <= tb) tiles.push_back(Tile{ta, tb});
+    // a stage of a diagonal tile keeps the busiest SIMD busy for 10 MFMA blocks, of any other tile for 16
+    auto weight = [](const Tile &t) { return t.ta == t.tb ? (int64_t)10 : (int64_t)16; };
+    std::vector<int64_t> begin(tiles.size() + 1, 0);    // weighted position at which a tile starts
+    for (size_t t = 0; t < tiles.size(); ++t) begin[t + 1] = begin[t] + weight(tiles[t]) * S;
+    const int64_t U = begin[tiles.size()];
+    // the cut before run q falls on the stage boundary at or below U * q / wgs, as (tile, stage)
+    auto cut = [&](int32_t q, size_t *tile, int64_t *stage) {
+        if (q >= wgs) { *tile = tiles.size(); *stage = 0; return; }
+        const int64_t pos = U / wgs * q + U % wgs * q / wgs;
+        size_t t = (size_t)(std::upper_bound(begin.begin(), begin.end(), pos) - begin.begin()) - 1;
+        *tile = t;
+        *stage = (pos - begin[t]) / weight(tiles[t]);
+    };
+    std::vector<int32_t> count((size_t)T2 * T2, 0);
+    if (pieces) memset(pieces, 0, sizeof(BigPiece) * 256 * kBigMaxPieces);
+    for (int32_t q = 0; q < wgs; ++q) {
+        const int32_t b = (q % (wgs / 8)) * 8 + q / (wgs / 8);      // the workgroup that takes run q
+        size_t t, t1;
+        int64_t s0, e1;
+        cut(q, &t, &s0);
+        cut(q + 1, &t1, &e1);
+        int32_t np = 0;
+        while (t < t1 || (t == t1 && s0 < e1)) {
+            const int64_t s1 = t < t1 ? S : e1;
+            if (s1 > s0) {
+                if (np == kBigMaxPieces) return 0;
+                int32_t &c = count[(size_t)tiles[t].ta * T2 + tiles[t].tb];
+                if (pieces) {
+                    BigPiece &pc = pieces[(size_t)b * kBigMaxPieces + np];
+                    pc.ta = tiles[t].ta; pc.tb = tiles[t].tb;
+                    pc.sbeg = (int32_t)s0; pc.send = (int32_t)s1; pc.plane = c;
+                }
+                ++c; ++np;
+            }
+            if (t == t1) break;
+            ++t; s0 = 0;
+        }
+    }
+    int32_t most = 0;
+    for (int32_t c : count) most = c > most ? c : most;
+    if (planes) memcpy(planes, count.data(), sizeof(int32_t) * count.size());
+    return most;
+}
+
+// Workgroups for the 256-wide route: as many as there are compute units, fewer (a multiple of 8) when the
+// cut would otherwise need more partial planes than planes_cap.  0: no cut fits.
+int32_t gram256_workgroups(int64_t n, int32_t lpad, int32_t planes_cap)
+{
+    for (int32_t wgs = 256; wgs >= 8; wgs -= 8) {
+        const int32_t need = gram256_cut(n, lpad, wgs, nullptr, nullptr);
+        if (need > 0 && need <= planes_cap) return wgs;
+    }
+    return 0;
+}
+
+// Shapes that take the 256-wide route by default (fp32 columns, Algorithm 1's dependency rule; the caller
+// checks the 16-byte alignment of X): lists longer than the short-list route serves, columns long enough
+// that a workgroup's run is thousands of MFMAs.
+bool gram256_default(int64_t n, int32_t lpad, int32_t layout, int32_t deps)
+{
+    return layout == STRADS_LAYOUT_DENSE_COLMAJOR && deps == STRADS_DEPS_STATIC && lpad > kShortList && n >= 4096 &&
+           n % 4 == 0;
+}
+
+int32_t gram256_plan_host(int64_t n, int32_t lpad, int32_t wgs, int32_t *pieces5, int32_t *planes)
+{
+    std::vector<BigPiece> pc((size_t)256 * kBigMaxPieces);
+    const int32_t need = gram256_cut(n, lpad, wgs, pc.data(), planes);
+    for (size_t i = 0; i < pc.size(); ++i) {
+        pieces5[5 * i + 0] = pc[i].ta; pieces5[5 * i + 1] = pc[i].tb; pieces5[5 * i + 2] = pc[i].sbeg;
+        pieces5[5 * i + 3] = pc[i].send; pieces5[5 * i + 4] = pc[i].plane;
+    }
+    return need;
+}
+
+size_t gram256_table_bytes() { return sizeof(BigPiece) * 256 * kBigMaxPieces + sizeof(int32_t) * 32 * 32; }
+
+// Fill the host image of the route's tables ([256][kBigMaxPieces] pieces, then [T2 * T2] plane counts).
+int32_t gram256_tables(const strads_lasso *h, int32_t wgs, void *out)
+{
+    BigPiece *pieces = reinterpret_cast<BigPiece *>(out);
+    int32_t *planes = reinterpret_cast<int32_t *>(pieces + 256 * kBigMaxPieces);
+    return gram256_cut(h->cfg.n, h->Lpad, wgs, pieces, planes);
+}
+
 size_t gram_partial_floats(int64_t n, int32_t lpad, bool dynamic)
 {
-    if (!dynamic) return (size_t)gram_split_choose(n, lpad) * lpad * lpad;
+    if (!dynamic) {
+        int32_t planes = gram_split_choose(n, lpad);
+        if (gram256_default(n, lpad, STRADS_LAYOUT_DENSE_COLMAJOR, STRADS_DEPS_STATIC)) {
+            const int32_t need = gram256_cut(n, lpad, 256, nullptr, nullptr);     // 0: never for these shapes
+            if (need > planes) planes = need;
+        }
+        return (size_t)planes * lpad * lpad;
+    }
     size_t most = 0;                                        // any mover count up to lpad
     for (int32_t l = kGramTile; l <= lpad; l += kGramTile) {
         const size_t need = (size_t)gram_split_choose(n, l) * l * l;
@@ -750,8 +1089,6 @@ size_t gram_job_table_entries(int64_t n, int32_t lpad)
     const size_t T = (size_t)(lpad / kGramTile);
     return (T * (T - 1) / 2 + T) * (size_t)gram_split_choose(n, lpad);      // any smaller slice count fits
 }
-
-constexpr int32_t kJobBlock = 8;     // tiles per side of a block of jobs that share panels in one L2
 
 int32_t gram_job_table(const strads_lasso *h, int32_t *out)
 {
@@ -878,13 +1215,23 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
     const GramShape *gdev = dynamic ? h->at<GramShape>(h->ws.dshape) : nullptr;
     const size_t lds = 2 * 2 * kPanel * sizeof(float);
     float *P = h->at<float>(h->ws.partial);
+    const bool big = !dynamic && h->big_wgs > 0;            // 256-wide tiles (see k_gram_tiles256)
+    const BigPiece *pieces = reinterpret_cast<const BigPiece *>(h->base + h->ws.big_tables);
     if (part == 1) {
         RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
         dim3 grid((h->Lpad + 1023) / 1024, h->Lpad);       // 1024 columns of one row per workgroup
         if (dynamic) { if (grid.x > 2) grid.x = 2; if (grid.y > 2048) grid.y = 2048; }
         hipLaunchKernelGGL(k_gram_mask, grid, dim3(256), 0, h->stream, P, g, gdev, h->cfg.rho,
                            h->at<uint64_t>(h->ws.mask), h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr,
-                           &sc->near_rho_pairs);
+                           &sc->near_rho_pairs,
+                           big ? reinterpret_cast<const int32_t *>(pieces + 256 * kBigMaxPieces) : nullptr,
+                           (h->Lpad + kBigTile - 1) / kBigTile);
+        return launch_status(h->stream);
+    }
+    if (big) {
+        hipLaunchKernelGGL(k_gram_tiles256, dim3((unsigned)h->big_wgs), dim3(kBigThreads),
+                           2 * 2 * kBigPanel * sizeof(float), h->stream, h->cfg.x, h->cfg.n,
+                           h->at<int32_t>(h->ws.cand), h->L, h->Lpad, pieces, P);
         return launch_status(h->stream);
     }
     const int load = h->cfg.layout == STRADS_LAYOUT_GENO2 ? kLoadGeno2 : (h->vec4 ? kLoadVec4 : kLoadScalar);
@@ -943,7 +1290,8 @@ hipError_t gram_prepare()
         const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
     }
-    return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(k_gram_tiles256),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 2 * kBigPanel * (int)sizeof(float));
 }
 
 } // namespace strads

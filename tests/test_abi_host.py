@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "strads_lasso.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(strads_lasso_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(strads_lasso_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -139,3 +139,71 @@ def test_static_filter_rejects_bad_arguments_before_any_device_call():
     assert f(1, 2, 0.1, -1, 1, 1, None) == b.E_INVALID_ARG
     assert f(1, b.FILTER_STATIC_MAX_L + 1, 0.1, 0, 1, 1, None) == b.E_TOO_LARGE
     assert b"maximum" in lib.strads_lasso_strerror(b.E_TOO_LARGE)
+
+
+# ---------------------------------------------------------------------------------------------
+# host logic of the tile kernel for long candidate lists: the stream of (tile, stage) pairs cut into runs
+# ---------------------------------------------------------------------------------------------
+def _plan_facts(n, l, cap):
+    import numpy as np
+    wgs, pieces, planes = pk.strads_lasso_gram256_plan(n, l, cap)
+    stages, t = (n + 31) // 32, (l + 255) // 256
+    cover = np.zeros((t, t, stages), np.int32)
+    seen, load = set(), np.zeros(256)
+    for w in range(256):
+        ended = False
+        for i in range(pk.GRAM256_MAX_PIECES):
+            ta, tb, s0, s1, plane = (int(v) for v in pieces[w, i])
+            if s1 <= s0:
+                ended = True
+                continue
+            assert not ended, "pieces of a workgroup are listed without gaps"
+            assert w < wgs and 0 <= ta <= tb < t and 0 <= s0 < s1 <= stages
+            cover[ta, tb, s0:s1] += 1
+            assert (ta, tb, plane) not in seen, "two pieces of a tile share a plane"
+            seen.add((ta, tb, plane))
+            load[w] += (s1 - s0) * (10 if ta == tb else 16)
+    return wgs, planes, cover, seen, load[:wgs], t
+
+
+@pytest.mark.parametrize("n,l,cap", [(50000, 8000, 2), (50000, 8192, 2), (4096, 4300, 4), (1000, 700, 16),
+                                     (5000, 513, 30), (4096, 128, 64), (260, 1100, 4), (8, 257, 1),
+                                     (33, 300, 2)])
+def test_gram256_plan_covers_every_tile_stage_once(n, l, cap):
+    import numpy as np
+    wgs, planes, cover, seen, load, t = _plan_facts(n, l, cap)
+    assert 8 <= wgs <= 256 and wgs % 8 == 0
+    for a in range(t):
+        for b_ in range(t):
+            if a <= b_:
+                assert (cover[a, b_] == 1).all(), (a, b_)
+                assert planes[a, b_] == sum(1 for (x, y, _) in seen if (x, y) == (a, b_))
+                # a tile's planes are numbered 0 .. count-1 without gaps
+                assert {p for (x, y, p) in seen if (x, y) == (a, b_)} == set(range(int(planes[a, b_])))
+            else:
+                assert cover[a, b_].sum() == 0 and planes[a, b_] == 0
+    assert planes.max() <= cap
+    # equal runs: no workgroup's share (in MFMA blocks on the busiest SIMD) differs from another's by more
+    # than one stage of the heavier kind of tile
+    assert load.max() - load.min() <= 16 + 10
+
+
+def test_gram256_plan_at_the_bench_shape_needs_two_planes_and_all_compute_units():
+    wgs, planes, cover, seen, load, t = _plan_facts(50000, 8000, 2)
+    assert wgs == 256 and t == 32 and planes.max() == 2
+    assert len(seen) <= 528 + 256           # every cut adds at most one piece
+
+
+def test_gram256_plan_rejects_bad_arguments_and_impossible_caps():
+    wgs = C.c_int32(7)
+    buf = (C.c_int32 * (256 * 8 * 5))()
+    pl = (C.c_int32 * 1024)()
+    lib = pk.load()
+    assert lib.strads_lasso_gram256_plan(0, 100, 1, C.byref(wgs), buf, pl) == pk.E_INVALID_ARG
+    assert lib.strads_lasso_gram256_plan(100, 0, 1, C.byref(wgs), buf, pl) == pk.E_INVALID_ARG
+    assert lib.strads_lasso_gram256_plan(100, pk.MAX_L_PRIME + 1, 1, C.byref(wgs), buf, pl) == pk.E_INVALID_ARG
+    assert lib.strads_lasso_gram256_plan(100, 100, 0, C.byref(wgs), buf, pl) == pk.E_INVALID_ARG
+    assert lib.strads_lasso_gram256_plan(100, 100, 1, None, buf, pl) == pk.E_INVALID_ARG
+    # 15 tiles of 9 stages cannot be dealt to 8 or more workgroups in whole tiles
+    assert lib.strads_lasso_gram256_plan(260, 1100, 1, C.byref(wgs), buf, pl) == pk.E_UNSUPPORTED
+    assert wgs.value == 0

@@ -218,6 +218,49 @@ def test_gram_split_k_variants_agree_with_oracle():
         _assert_close(_np(lr["G"]), Gref, DOT_RTOL, 1e-6, f"gram split {split}")
 
 
+@pytest.mark.parametrize("n,j,l_prime", [(1000, 900, 700), (5000, 700, 513), (1004, 600, 300), (4096, 300, 128),
+                                         (260, 1200, 1100), (8, 300, 257)])
+def test_gram_in_256_wide_tiles_matches_oracle(n, j, l_prime):
+    """The tile kernel for long lists (256 x 256 tiles, work dealt out as a stream of (tile, stage) pairs),
+    forced onto short lists: whole Gram against the oracle, including a ragged last tile, a ragged last K
+    stage, a single diagonal tile and pieces of one stage."""
+    p = si.make("c2_dense_block_corr", n=n, j=j, nnz=5, l_prime=l_prime)
+    g, o = _pair(p)
+    g.set_tuning("gram_tile256", 2)
+    for _ in range(2):                                  # twice: stale partial planes must not leak into a round
+        g.round()
+        lr = g.last_round(want_gram=True)
+        cand = _np(lr["cand"])
+        Gref = orc.gram_dense(o.x, cand)
+        _assert_close(_np(lr["G"]), Gref, DOT_RTOL, 1e-6, "gram")
+        assert np.array_equal(_np(lr["G"]), _np(lr["G"]).T)
+        kept = _np(lr["kept_pos"])
+        assert np.array_equal(kept, orc.greedy_filter(_np(lr["G"]), o.rho, o.p_max))
+
+
+def test_gram_of_a_long_list_takes_the_256_wide_route_and_matches_oracle_rows():
+    """A list longer than 4096 over columns of at least 4096 rows takes the 256-wide tiles by default: sampled
+    rows of the Gram against the oracle, the rest against the 128-wide kernel's result on the same candidates."""
+    p = si.make("c5_dense_duplicates", n=4096, j=4500, nnz=20, l_prime=4300)
+    g, o = _pair(p)
+    g.round()
+    lr = g.last_round(want_gram=True)
+    cand, G = _np(lr["cand"]), _np(lr["G"])
+    rows = np.unique(np.concatenate([[0, 127, 128, 255, 256, 4095, 4096, 4223, 4299],
+                                     np.random.default_rng(5).integers(0, 4300, 24)])).astype(np.int32)
+    ref = orc.gram_rows_dense(o.x, cand, rows)
+    _assert_close(G[rows], ref, DOT_RTOL, 1e-6, "gram rows")
+    assert np.array_equal(G, G.T)
+    g2, _ = _pair(p)
+    g2.set_tuning("gram_tile256", 0)
+    g2.round()
+    lr2 = g2.last_round(want_gram=True)
+    assert np.array_equal(_np(lr2["cand"]), cand)
+    _assert_close(_np(lr2["G"]), G, 2e-5, 2e-6, "128-wide against 256-wide tiles")
+    assert np.array_equal(_np(lr2["kept_pos"]), orc.greedy_filter(_np(lr2["G"]), o.rho, o.p_max))
+    assert np.array_equal(_np(lr["kept_pos"]), orc.greedy_filter(G, o.rho, o.p_max))
+
+
 @pytest.mark.parametrize("L", [1, 2, 63, 64, 65, 200, 1000, 2500, 4100, 8192])
 def test_filter_is_bit_exact_on_given_gram(L):
     p = si.make("c1_dense_iid", n=8, j=max(L, 2), nnz=1, l_prime=L)
