@@ -273,10 +273,10 @@ int strads_lasso_filter_static(const float *gram, int32_t l, float rho, int32_t 
  *                   identical.  Dense and packed designs with static or no dependencies only.
  *   "gram_tile256"  how Step 2's Gram is tiled.  1 (default): lists of more than 4096 candidates over 16-byte
  *                   aligned fp32 columns of at least 4096 rows, under Algorithm 1's dependency rule, are
- *                   multiplied in 256 x 256 tiles dealt out as a stream (strads_lasso_gram256_plan); every other
- *                   shape in 128 x 128 tiles with K-slices.  0: always 128 x 128.  2: 256 x 256 wherever
+ *                   multiplied in 256 x 256 tiles handed out from a queue (strads_lasso_gram256_plan); every
+ *                   other shape in 128 x 128 tiles with K-slices.  0: always 128 x 128.  2: 256 x 256 wherever
  *                   the design is fp32, aligned and the rule static (STRADS_E_UNSUPPORTED if the workspace
- *                   lacks the partial planes).  The routes differ in fp32 summation order only.
+ *                   lacks room for the tile slots).  The routes differ in fp32 summation order only.
  *   "dots_with_gram" 1 (default): fp32 dense designs with l_prime <= 4096, Algorithm 1's dependency rule and
  *                   one scheduler take x_j^T r for every candidate in extra workgroups of the Gram
  *                   launch, and the filter's workgroup applies eq. (2) to the kept ones; 0: a kernel
@@ -294,19 +294,18 @@ int strads_lasso_filter_static(const float *gram, int32_t l, float rho, int32_t 
  * Returns STRADS_E_INVALID_ARG for an unknown name or a value out of range. */
 int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value);
 
-/* Host only, no GPU call: how the tile kernel for long candidate lists (Section 2.1, Step 2: the pairwise
- * dependencies of the P' candidates; see "gram_tile256") deals the Gram of l candidates over n rows out to its
- * workgroups.  The (tile, stage) pairs -- tiles of 256 x 256 entries of the upper triangle, stages of 32 rows --
- * are laid end to end and cut into equal runs, one per workgroup; a tile that falls into several runs is
- * written as that many partial planes.  planes_cap: the most planes a tile may need.
- *   wgs_out  HOST int32: workgroups used (a multiple of 8, at most 256)
- *   pieces   HOST int32 [256][STRADS_GRAM256_MAX_PIECES][5]: (tile row, tile column, first stage, end stage,
- *            plane) of each piece of each workgroup; end <= first: no piece
- *   planes   HOST int32 [T][T], T = ceil(l / 256): planes of each tile (0 below the diagonal)
- * Returns STRADS_E_UNSUPPORTED (wgs_out = 0) if no cut fits planes_cap. */
-#define STRADS_GRAM256_MAX_PIECES 8
-int strads_lasso_gram256_plan(int64_t n, int32_t l, int32_t planes_cap, int32_t *wgs_out, int32_t *pieces,
-                              int32_t *planes);
+/* Host only, no GPU call: the work queue of the tile kernel for long candidate lists (Section 2.1, Step 2: the
+ * pairwise dependencies of the P' candidates; see "gram_tile256") for l candidates over n rows.  The Gram's upper
+ * triangle is cut into tiles of 256 x 256 entries and every tile's n rows into stages of 32; an item of the
+ * queue is a stage range of one tile.  Items shrink as the queue empties (whole tiles first, 32 stages at the
+ * end) and workgroups take them in order as they become free; each item is written to a tile slot of its own
+ * and a tile's slots are consecutive, in row order.
+ *   n_items     HOST int32: number of items (= tile slots)
+ *   items       HOST int32 [items_cap][5]: (tile row, tile column, first stage, end stage, slot) of the first
+ *               items_cap items in queue order; may be NULL if items_cap is 0
+ *   first_slot, n_slots   HOST int32 [T][T], T = ceil(l / 256): slot range of each tile (0, 0 below the diagonal) */
+int strads_lasso_gram256_plan(int64_t n, int32_t l, int32_t items_cap, int32_t *n_items, int32_t *items,
+                              int32_t *first_slot, int32_t *n_slots);
 
 /* Average duration in milliseconds of each stage (HOST array of STRADS_N_STAGES floats) over the
  * rounds enqueued since profiling was switched on or since the last call, measured with HIP events

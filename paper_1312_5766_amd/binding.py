@@ -90,7 +90,7 @@ def load():
     L.strads_lasso_stage_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     L.strads_lasso_filter_static.argtypes = [vp, C.c_int32, C.c_float, C.c_int32, vp, vp, vp]
     L.strads_lasso_debug_build.argtypes = []
-    L.strads_lasso_gram256_plan.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.POINTER(C.c_int32), vp, vp]
+    L.strads_lasso_gram256_plan.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.POINTER(C.c_int32), vp, vp, vp]
     L.strads_lasso_destroy.argtypes = [vp]
     L.strads_lasso_destroy.restype = None
     L.strads_lasso_strerror.argtypes = [C.c_int]
@@ -124,20 +124,19 @@ def strads_lasso_workspace_bytes(n, j, l_prime, layout=LAYOUT_DENSE, keep_gram=F
     return int(load().strads_lasso_workspace_bytes(C.byref(cfg)))
 
 
-GRAM256_MAX_PIECES = 8
-
-
-def strads_lasso_gram256_plan(n: int, l: int, planes_cap: int):
-    """Host only.  (workgroups, pieces, planes): pieces is an int32 array [256][GRAM256_MAX_PIECES][5] of
-    (tile row, tile column, first stage, end stage, plane), planes an int32 array [T][T], T = ceil(l / 256)."""
+def strads_lasso_gram256_plan(n: int, l: int):
+    """Host only.  (items, first_slot, n_slots): items is an int32 array [n_items][5] of (tile row, tile column,
+    first stage, end stage, slot) in queue order; first_slot and n_slots are int32 arrays [T][T], T = ceil(l / 256)."""
     import numpy as np
-    wgs = C.c_int32(0)
     t = (l + 255) // 256
-    pieces = np.zeros((256, GRAM256_MAX_PIECES, 5), np.int32)
-    planes = np.zeros((t, t), np.int32)
-    _check(load().strads_lasso_gram256_plan(int(n), int(l), int(planes_cap), C.byref(wgs), pieces.ctypes.data,
-                                            planes.ctypes.data), "strads_lasso_gram256_plan")
-    return wgs.value, pieces, planes
+    first, count = np.zeros((t, t), np.int32), np.zeros((t, t), np.int32)
+    n_items = C.c_int32(0)
+    _check(load().strads_lasso_gram256_plan(int(n), int(l), 0, C.byref(n_items), None, first.ctypes.data,
+                                            count.ctypes.data), "strads_lasso_gram256_plan")
+    items = np.zeros((max(1, n_items.value), 5), np.int32)
+    _check(load().strads_lasso_gram256_plan(int(n), int(l), n_items.value, C.byref(n_items), items.ctypes.data,
+                                            first.ctypes.data, count.ctypes.data), "strads_lasso_gram256_plan")
+    return items[:n_items.value], first, count
 
 
 def strads_lasso_filter_static(gram: torch.Tensor, rho: float, p_max: int, kept_pos: torch.Tensor,

@@ -28,7 +28,7 @@ Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gr
     w.w = take((size_t)npad * 4);
     w.jobtab = take(layout != STRADS_LAYOUT_CSC && deps != STRADS_DEPS_DYNAMIC
                         ? gram_job_table_entries(n, (int32_t)lpad) * 4 : 256);
-    w.big_tables = take(layout == STRADS_LAYOUT_DENSE_COLMAJOR ? gram256_table_bytes() : 256);
+    w.big_tables = take(layout == STRADS_LAYOUT_DENSE_COLMAJOR ? gram256_table_bytes(n, (int32_t)lpad) : 256);
     w.objpart = take((size_t)kObjBlocks * 8);
     w.objout = take(8);
     // once per shard
@@ -125,26 +125,29 @@ static int upload_job_table(strads_lasso *h)
     return STRADS_OK;
 }
 
-// Choose between the two Gram tile kernels (h->tile256, the shape, the planes the workspace holds) and, for
-// the 256-wide one, build its tables and copy them to the workspace.  Waits for the copy.
+// Choose between the two Gram tile kernels (h->tile256, the shape, the partial storage the workspace holds)
+// and, for the 256-wide one, build its tables and copy them to the workspace.  Waits for the copy.
 static int choose_gram_route(strads_lasso *h)
 {
-    int32_t wgs = 0;
+    int32_t items = 0;
     const bool can = h->vec4 && h->cfg.deps == STRADS_DEPS_STATIC && h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR;
     if (can && (h->tile256 == 2 ||
-                (h->tile256 == 1 && gram256_default(h->cfg.n, h->Lpad, h->cfg.layout, h->cfg.deps))))
-        wgs = gram256_workgroups(h->cfg.n, h->Lpad, h->split_max);
-    if (wgs > 0) {
-        void *img = malloc(gram256_table_bytes());
+                (h->tile256 == 1 && gram256_default(h->cfg.n, h->Lpad, h->cfg.layout, h->cfg.deps)))) {
+        items = gram256_items(h->cfg.n, h->Lpad);
+        // one 256 x 256 slot per item must fit the partial storage
+        if ((size_t)items * 256 * 256 > h->partial_floats) items = 0;
+    }
+    if (items > 0) {
+        void *img = malloc(gram256_table_bytes(h->cfg.n, h->Lpad));
         if (!img) return STRADS_E_INVALID_ARG;
-        gram256_tables(h, wgs, img);
-        const hipError_t e1 = hipMemcpyAsync(h->base + h->ws.big_tables, img, gram256_table_bytes(),
+        gram256_tables(h->cfg.n, h->Lpad, img);
+        const hipError_t e1 = hipMemcpyAsync(h->base + h->ws.big_tables, img, gram256_table_bytes(h->cfg.n, h->Lpad),
                                              hipMemcpyHostToDevice, h->stream);
         const hipError_t e2 = hipStreamSynchronize(h->stream);
         free(img);
         if (e1 != hipSuccess || e2 != hipSuccess) return STRADS_E_HIP;
     }
-    for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->big_wgs = wgs;
+    for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->big_items = items;
     return STRADS_OK;
 }
 
@@ -186,9 +189,9 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->L = L;
     h->Lpad = (L + kGramTile - 1) / kGramTile * kGramTile;
     h->Npad = (cfg->n + 63) / 64 * 64;
-    h->split_max = cfg->layout != STRADS_LAYOUT_CSC && cfg->deps != STRADS_DEPS_DYNAMIC
-                       ? (int32_t)(gram_partial_floats(cfg->n, h->Lpad, false) / ((size_t)h->Lpad * h->Lpad))
-                       : (cfg->layout != STRADS_LAYOUT_CSC ? gram_split_auto(cfg->n, h->Lpad) : 1);
+    h->split_max = cfg->layout != STRADS_LAYOUT_CSC ? gram_split_auto(cfg->n, h->Lpad) : 1;
+    h->partial_floats = cfg->layout != STRADS_LAYOUT_CSC
+                            ? gram_partial_floats(cfg->n, h->Lpad, cfg->deps == STRADS_DEPS_DYNAMIC) : 0;
     h->split_user = 0;
     h->step_scale = cfg->loss == STRADS_LOSS_LOGISTIC ? 4.f : 1.f;
     h->dots_with_gram = 1;
@@ -197,7 +200,7 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->residual_fused = 1;
     h->jobtab_on = cfg->layout != STRADS_LAYOUT_CSC && cfg->deps != STRADS_DEPS_DYNAMIC ? 1 : 0;
     h->tile256 = 1;
-    h->big_wgs = 0;
+    h->big_items = 0;
     h->select_cap = kSelectCapDefault;
     h->round = 0;
     h->profile_level = 0;
@@ -710,16 +713,14 @@ int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, i
     return STRADS_OK;
 }
 
-int strads_lasso_gram256_plan(int64_t n, int32_t l, int32_t planes_cap, int32_t *wgs_out, int32_t *pieces,
-                              int32_t *planes)
+int strads_lasso_gram256_plan(int64_t n, int32_t l, int32_t items_cap, int32_t *n_items, int32_t *items,
+                              int32_t *first_slot, int32_t *n_slots)
 {
-    if (n < 1 || l < 1 || l > STRADS_MAX_L_PRIME || planes_cap < 1 || !wgs_out || !pieces || !planes)
+    if (n < 1 || l < 1 || l > STRADS_MAX_L_PRIME || items_cap < 0 || !n_items || (items_cap > 0 && !items) ||
+        !first_slot || !n_slots)
         return STRADS_E_INVALID_ARG;
     const int32_t lpad = (l + kGramTile - 1) / kGramTile * kGramTile;
-    const int32_t wgs = gram256_workgroups(n, lpad, planes_cap);
-    *wgs_out = wgs;
-    if (wgs == 0) return STRADS_E_UNSUPPORTED;
-    gram256_plan_host(n, lpad, wgs, pieces, planes);
+    *n_items = gram256_plan_host(n, lpad, items_cap, items, first_slot, n_slots);
     return STRADS_OK;
 }
 
@@ -764,7 +765,7 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
         for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->tile256 = (int32_t)value;
         const int rc = choose_gram_route(h);
         if (rc != STRADS_OK) return rc;
-        return value == 2 && h->big_wgs == 0 ? STRADS_E_UNSUPPORTED : STRADS_OK;
+        return value == 2 && h->big_items == 0 ? STRADS_E_UNSUPPORTED : STRADS_OK;
     }
     if (strcmp(name, "dots_with_gram") == 0) {
         if (value < 0 || value > 1) return STRADS_E_INVALID_ARG;

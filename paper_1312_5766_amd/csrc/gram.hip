@@ -497,12 +497,15 @@ __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int6
 // workgroup per compute unit: two LDS stages of 512 columns take 144 KB) owns the tile; wavefront (wr, wc)
 // holds rows 128 wr .. +127 and columns 64 wc .. +63 of it as 4 x 2 MFMA accumulators (128 AGPRs).
 //
-// With one workgroup per compute unit and a few hundred tiles the work is dealt out as a stream: the
-// (tile, stage) pairs are laid end to end and every workgroup takes an equal run of them, which covers the
-// end of one tile, whole tiles, and the start of another.  A tile therefore arrives in up to a few pieces
-// (two when there are more tiles than workgroups); piece p of a tile is written to partial plane p and the mask
-// kernel adds a tile's planes in order, so the sum does not depend on timing.  The runs are computed on the
-// host when the handle is created (BigPiece table).
+// Work is handed out from a queue.  One workgroup per compute unit and a few hundred tiles of 1500 stages
+// do not divide evenly, and the eight XCDs of one chip do not run at the same speed (measured: up to 5 %
+// between the slowest and the fastest under this load, differently from box to box), so equal shares would
+// leave most of the chip waiting for its slowest part.  The (tile, stage range) items of the queue shrink as
+// the queue empties -- whole tiles while more than a tile per workgroup is left, then a 256th of what is left,
+// down to 32 stages -- and a workgroup that has finished an item takes the next with one atomic increment
+// (guided self-scheduling).  An item is written to a tile slot of its own (256 x 256 floats); the slots of a
+// tile are consecutive, in K order, and the mask kernel adds them in that order, so the sum does not depend
+// on which workgroup computed what or when.  The queue is computed on the host when the handle is created.
 //
 // A tile on the diagonal stages its 256 columns once and multiplies only the 36 of its 64 32 x 32 blocks on or
 // above the diagonal, dealt out to the wavefronts so that no SIMD gets more than 10 (an off-diagonal tile: 16);
@@ -514,12 +517,14 @@ constexpr int kBigThreads = 512;
 constexpr int kBigPanel = kBigTile * kRow;              // floats per 256-column operand panel per stage
 constexpr int kBigColsPerPass = kBigThreads / kKQ;      // columns the 512 threads stage in one pass
 constexpr int kBigPasses = kBigTile / kBigColsPerPass;  // passes per panel
-constexpr int kBigMaxPieces = 8;                        // pieces per workgroup the table has room for
+constexpr int kBigSlot = kBigTile * kBigTile;           // floats per tile slot
+constexpr int kBigWorkgroups = 256;                     // one per compute unit
+constexpr int kBigMinStages = 32;                       // shortest item of the queue
 
 struct BigPiece {
     int32_t ta, tb;         // tile (256-column groups), ta <= tb
-    int32_t sbeg, send;     // stages [sbeg, send) of kGramKT rows each; send <= sbeg: no piece
-    int32_t plane;          // partial plane the piece is written to
+    int32_t sbeg, send;     // stages [sbeg, send) of kGramKT rows each
+    int32_t slot;           // tile slot the item is written to
     int32_t pad_[3];
 };
 
@@ -575,7 +580,7 @@ __device__ __forceinline__ void gram_piece256(const float *__restrict__ X, int64
     const int li = lane & 31, lh = lane >> 5;
     // The wavefront's blocks: rows 32 (ra + a) .. +31, columns 32 (cb + b) .. +31 of the tile, a < 4, b < 2.
     // BOTH = rows a whose two blocks are multiplied, RIGHT = rows a of which only the block b = 1 is.
-    constexpr uint32_t both = DIAG ? BOTH : 0xFu, right = DIAG ? RIGHT : 0u;
+    constexpr uint32_t both = BOTH, right = RIGHT;
 
     floatx16 acc[4][2];
 #pragma unroll
@@ -664,35 +669,53 @@ __device__ __forceinline__ void gram_piece256(const float *__restrict__ X, int64
     stage(st & 1, cur, false, [] {});
     mfma_drain();
 
-    float *out = P + (int64_t)pc.plane * Lpad * Lpad;
+    float *out = P + (int64_t)pc.slot * kBigSlot;       // the item's own 256 x 256 slot
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
             const int rb = ra + a, cbk = cb + b;        // row and column block inside the tile
-            const int row0 = pc.ta * kBigTile + rb * 32, col0 = pc.tb * kBigTile + cbk * 32;
             const bool mine = (both >> a & 1u) || (b == 1 && (right >> a & 1u));
-            if (!mine || row0 >= Lpad || col0 >= Lpad) continue;
-            store_block(out, Lpad, row0, col0, acc[a][b], li, lh);
+            // blocks past the padded list are never read
+            if (!mine || pc.ta * kBigTile + rb * 32 >= Lpad || pc.tb * kBigTile + cbk * 32 >= Lpad) continue;
+            store_block(out, kBigTile, rb * 32, cbk * 32, acc[a][b], li, lh);
             // inside a diagonal 128 x 128 square the mask kernel expects both triangles
-            if (DIAG && rb != cbk && rb / 4 == cbk / 4) store_block_t(out, Lpad, row0, col0, acc[a][b], li, lh);
+            if (DIAG && rb != cbk && rb / 4 == cbk / 4) store_block_t(out, kBigTile, rb * 32, cbk * 32, acc[a][b], li, lh);
         }
 }
 
 __global__ __launch_bounds__(kBigThreads, 1) void k_gram_tiles256(const float *__restrict__ X, int64_t N,
                                                                   const int32_t *__restrict__ cand, int32_t L,
-                                                                  int32_t Lpad, const BigPiece *__restrict__ pieces,
+                                                                  int32_t Lpad, const BigPiece *__restrict__ items,
+                                                                  int32_t n_items, uint32_t *__restrict__ next,
                                                                   float *__restrict__ P)
 {
-    extern __shared__ float smem[];             // [2 stages][A panel | B panel]
-    const BigPiece *mine = pieces + (size_t)blockIdx.x * kBigMaxPieces;
+    // [2 stages][A panel | B panel]; aligned for 16-byte LDS accesses whatever else the kernel keeps in LDS
+    extern __shared__ __align__(16) float smem[];
+    __shared__ uint32_t taken;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    for (int i = 0; i < kBigMaxPieces; ++i) {
-        const BigPiece pc = mine[i];
-        if (pc.send <= pc.sbeg) break;          // uniform: the table is the same for every thread
-        if (pc.ta != pc.tb) {
+    // every workgroup ends by drawing an index past the queue: the counter stops at n_items + gridDim.x and
+    // the mask kernel, which runs next on the stream, puts it back to zero
+    for (;;) {
+        if (threadIdx.x == 0) taken = atomicAdd(next, 1u);
+        __syncthreads();
+        const uint32_t it = taken;              // uniform
+        if (it >= (uint32_t)n_items) break;
+        const BigPiece pc = items[it];
+        // the last tile row / column holds 256 or 128 columns of the (128-padded) list
+        const bool half = (pc.tb + 1) * kBigTile > Lpad;
+        if (pc.ta != pc.tb && !half) {
             // wavefront (wr, wc) = (wave / 4, wave % 4): rows 128 wr .. +127, columns 64 wc .. +63, all eight blocks
             gram_piece256<false, 0xFu, 0u>(X, N, cand, L, Lpad, pc, (wave >> 2) * 4, (wave & 3) * 2, P, smem);
+        } else if (pc.ta != pc.tb) {
+            // 256 rows x 128 columns: wavefront (wave / 2, wave % 2) takes rows 64 (wave / 2) .. +63 and columns
+            // 64 (wave % 2) .. +63, four blocks each
+            gram_piece256<false, 0x3u, 0u>(X, N, cand, L, Lpad, pc, (wave >> 1) * 2, (wave & 1) * 2, P, smem);
+        } else if (half) {
+            // the corner tile with 128 columns: one diagonal 128 x 128 square, 10 blocks
+            if (wave == 3) gram_piece256<true, 0x7u, 0x8u>(X, N, cand, L, Lpad, pc, 0, 2, P, smem);
+            else if (wave == 7) gram_piece256<true, 0x1u, 0x2u>(X, N, cand, L, Lpad, pc, 0, 0, P, smem);
+            else gram_piece256<true, 0u, 0u>(X, N, cand, L, Lpad, pc, 0, 0, P, smem);
         } else {
             // On the diagonal only the 36 blocks with row block <= column block are needed; they are dealt out so
             // that the two wavefronts of a SIMD (w and w + 4) have 8, 8, 10 and 10 of them between them:
@@ -710,7 +733,7 @@ __global__ __launch_bounds__(kBigThreads, 1) void k_gram_tiles256(const float *_
             default: gram_piece256<true, 0x1u, 0x2u>(X, N, cand, L, Lpad, pc, 0, 0, P, smem); break;
             }
         }
-        __syncthreads();                        // the next piece reuses the LDS stages
+        __syncthreads();                        // the next item reuses the LDS stages, and `taken`
     }
 }
 
@@ -793,17 +816,19 @@ __device__ __forceinline__ uint64_t spread_every_4th(uint64_t x)
 // A thread owns 4 consecutive columns b of one row a (16-byte loads of every slice), a wavefront
 // 256 columns = four 64-bit mask words, assembled from one ballot per column-in-thread; only
 // columns in the tiles at or right of a's diagonal tile exist.  gdev != NULL: the shape is read
-// from device memory (dynamic dependencies) and the grid strides over it.  planes256 != NULL: the tiles
-// were written by k_gram_tiles256, and a tile's slice count is looked up there.
+// from device memory (dynamic dependencies) and the grid strides over it.  slots256 != NULL: the tiles
+// were written by k_gram_tiles256 into tile slots; first slot and slot count per tile are looked up there,
+// and queue_next, that kernel's queue position, is put back to zero.
 __global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, GramShape gh,
                                                    const GramShape *__restrict__ gdev, float rho,
                                                    uint64_t *__restrict__ mask, float *__restrict__ gram,
                                                    int32_t *__restrict__ near_pairs,
-                                                   const int32_t *__restrict__ planes256, int32_t T2)
+                                                   const int32_t *__restrict__ slots256, int32_t T2,
+                                                   uint32_t *__restrict__ queue_next)
 {
+    if (queue_next && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *queue_next = 0u;   // for the next round
     const GramShape g = gdev ? *gdev : gh;
     const int32_t L = g.L, Lpad = g.Lpad;
-    const int64_t plane = (int64_t)Lpad * Lpad;
     const int lane = threadIdx.x & 63;
     for (int32_t a = blockIdx.y; a < Lpad; a += gridDim.y) {
         const int32_t first = (a / kGramTile) * kGramTile;  // first column of a's diagonal tile
@@ -815,10 +840,16 @@ __global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, 
             const bool have = b >= first && b < Lpad;
             float v[4] = {0.f, 0.f, 0.f, 0.f};
             if (have) {
-                // 256-wide tiles: planes256[tile] partial planes hold pieces of tile (a / 256, b / 256)
-                const int32_t split = planes256 ? planes256[(a / kBigTile) * T2 + b / kBigTile]
-                                                : (b < first + kGramTile ? g.split_diag : g.split_off);
+                int32_t split = b < first + kGramTile ? g.split_diag : g.split_off;
                 const float *p = P + (int64_t)a * Lpad + b;
+                int64_t plane = (int64_t)Lpad * Lpad;
+                if (slots256) {
+                    // 256-wide tiles: the items of tile (a / 256, b / 256) lie in consecutive tile slots
+                    const int32_t tile = (a / kBigTile) * T2 + b / kBigTile;
+                    split = slots256[T2 * T2 + tile];
+                    p = P + (int64_t)slots256[tile] * kBigSlot + (a % kBigTile) * kBigTile + b % kBigTile;
+                    plane = kBigSlot;
+                }
                 int32_t s = 0;
                 for (; s + 7 < split; s += 8) {             // eight slices in flight, added in slice order
                     float4 q[8];
@@ -946,116 +977,101 @@ __host__ __device__ static inline GramShape gram_shape_for(int64_t n, int32_t L,
     return g;
 }
 
-// The stream of (tile, stage) pairs of the 256-wide route, cut into equal runs for `wgs` workgroups.
-// Tiles are ordered in blocks of 8 x 8 (an XCD's workgroups then work on neighbouring tiles, which share
-// panels in its L2), and workgroup b, which runs on XCD b mod 8, takes run (b mod 8) * wgs / 8 + b / 8.
-// Returns the number of partial planes the cut needs (the most pieces any tile falls into), 0 if a workgroup
-// would get more than kBigMaxPieces pieces.  pieces ([wgs][kBigMaxPieces]) and planes ([T2 * T2]) may be NULL.
-static int32_t gram256_cut(int64_t n, int32_t lpad, int32_t wgs, BigPiece *pieces, int32_t *planes)
+// The queue of the 256-wide route: the tiles of the upper triangle in blocks of 8 x 8 (neighbours in the queue
+// share panels), each cut into equal items, shorter from tile to tile.  An item is at most a 256th (one
+// workgroup's share) of the work that comes after its tile in the queue, measured in off-diagonal stages (a
+// stage of a diagonal tile keeps the busiest SIMD busy for 10 MFMA blocks, of a tile in a last tile column of
+// 128 columns for 8, of any other for 16), but at least kBigMinStages stages and at most the tile.  Slots are
+// numbered in queue order, so a tile's items have consecutive slots in K order.
+// first / count ([T2 * T2], may be NULL): first slot and number of slots of every tile.
+static std::vector<BigPiece> gram256_queue(int64_t n, int32_t lpad, int32_t *first, int32_t *count)
 {
     const int32_t T2 = (lpad + kBigTile - 1) / kBigTile;
     const int64_t S = (n + kGramKT - 1) / kGramKT;
-    struct Tile { int32_t ta, tb; };
-    std::vector<Tile> tiles;
+    const bool half_last = T2 * kBigTile > lpad;
+    auto weight = [&](int32_t ta, int32_t tb) {
+        return ta == tb ? (int64_t)10 : (half_last && tb == T2 - 1 ? (int64_t)8 : (int64_t)16);
+    };
+    std::vector<BigPiece> tiles;
+    int64_t left = 0;                                   // what is left of the job, in 16ths of an off-diagonal stage
     for (int32_t bi = 0; bi * kJobBlock < T2; ++bi)
         for (int32_t bj = bi; bj * kJobBlock < T2; ++bj)
             for (int32_t ta = bi * kJobBlock; ta < (bi + 1) * kJobBlock && ta < T2; ++ta)
                 for (int32_t tb = bj * kJobBlock; tb < (bj + 1) * kJobBlock && tb < T2; ++tb)
-                    if (ta <= tb) tiles.push_back(Tile{ta, tb});
-    // a stage of a diagonal tile keeps the busiest SIMD busy for 10 MFMA blocks, of any other tile for 16
-    auto weight = [](const Tile &t) { return t.ta == t.tb ? (int64_t)10 : (int64_t)16; };
-    std::vector<int64_t> begin(tiles.size() + 1, 0);    // weighted position at which a tile starts
-    for (size_t t = 0; t < tiles.size(); ++t) begin[t + 1] = begin[t] + weight(tiles[t]) * S;
-    const int64_t U = begin[tiles.size()];
-    // the cut before run q falls on the stage boundary at or below U * q / wgs, as (tile, stage)
-    auto cut = [&](int32_t q, size_t *tile, int64_t *stage) {
-        if (q >= wgs) { *tile = tiles.size(); *stage = 0; return; }
-        const int64_t pos = U / wgs * q + U % wgs * q / wgs;
-        size_t t = (size_t)(std::upper_bound(begin.begin(), begin.end(), pos) - begin.begin()) - 1;
-        *tile = t;
-        *stage = (pos - begin[t]) / weight(tiles[t]);
-    };
-    std::vector<int32_t> count((size_t)T2 * T2, 0);
-    if (pieces) memset(pieces, 0, sizeof(BigPiece) * 256 * kBigMaxPieces);
-    for (int32_t q = 0; q < wgs; ++q) {
-        const int32_t b = (q % (wgs / 8)) * 8 + q / (wgs / 8);      // the workgroup that takes run q
-        size_t t, t1;
-        int64_t s0, e1;
-        cut(q, &t, &s0);
-        cut(q + 1, &t1, &e1);
-        int32_t np = 0;
-        while (t < t1 || (t == t1 && s0 < e1)) {
-            const int64_t s1 = t < t1 ? S : e1;
-            if (s1 > s0) {
-                if (np == kBigMaxPieces) return 0;
-                int32_t &c = count[(size_t)tiles[t].ta * T2 + tiles[t].tb];
-                if (pieces) {
-                    BigPiece &pc = pieces[(size_t)b * kBigMaxPieces + np];
-                    pc.ta = tiles[t].ta; pc.tb = tiles[t].tb;
-                    pc.sbeg = (int32_t)s0; pc.send = (int32_t)s1; pc.plane = c;
-                }
-                ++c; ++np;
-            }
-            if (t == t1) break;
-            ++t; s0 = 0;
+                    if (ta <= tb) {
+                        tiles.push_back(BigPiece{ta, tb, 0, 0, 0, {0, 0, 0}});
+                        left += weight(ta, tb) * S;
+                    }
+    if (first) for (int32_t i = 0; i < T2 * T2; ++i) first[i] = count[i] = 0;
+    std::vector<BigPiece> queue;
+    for (const BigPiece &t : tiles) {
+        const int64_t w = weight(t.ta, t.tb);
+        if (first) first[t.ta * T2 + t.tb] = (int32_t)queue.size();
+        // items of this tile: equal parts no longer than a 256th of what will be left after the tile
+        int64_t len = (left - w * S) / kBigWorkgroups / w;
+        if (len < kBigMinStages) len = kBigMinStages;
+        const int64_t parts = (S + len - 1) / len;
+        for (int64_t k = 0; k < parts; ++k) {
+            const int64_t s0 = S * k / parts, s1 = S * (k + 1) / parts;
+            queue.push_back(BigPiece{t.ta, t.tb, (int32_t)s0, (int32_t)s1, (int32_t)queue.size(), {0, 0, 0}});
+            if (count) ++count[t.ta * T2 + t.tb];
         }
+        left -= w * S;
     }
-    int32_t most = 0;
-    for (int32_t c : count) most = c > most ? c : most;
-    if (planes) memcpy(planes, count.data(), sizeof(int32_t) * count.size());
-    return most;
+    return queue;
 }
 
-// Workgroups for the 256-wide route: as many as there are compute units, fewer (a multiple of 8) when the
-// cut would otherwise need more partial planes than planes_cap.  0: no cut fits.
-int32_t gram256_workgroups(int64_t n, int32_t lpad, int32_t planes_cap)
-{
-    for (int32_t wgs = 256; wgs >= 8; wgs -= 8) {
-        const int32_t need = gram256_cut(n, lpad, wgs, nullptr, nullptr);
-        if (need > 0 && need <= planes_cap) return wgs;
-    }
-    return 0;
-}
+int32_t gram256_items(int64_t n, int32_t lpad) { return (int32_t)gram256_queue(n, lpad, nullptr, nullptr).size(); }
 
 // Shapes that take the 256-wide route by default (fp32 columns, Algorithm 1's dependency rule; the caller
 // checks the 16-byte alignment of X): lists longer than the short-list route serves, columns long enough
-// that a workgroup's run is thousands of MFMAs.
+// that an item is thousands of MFMAs.
 bool gram256_default(int64_t n, int32_t lpad, int32_t layout, int32_t deps)
 {
     return layout == STRADS_LAYOUT_DENSE_COLMAJOR && deps == STRADS_DEPS_STATIC && lpad > kShortList && n >= 4096 &&
            n % 4 == 0;
 }
 
-int32_t gram256_plan_host(int64_t n, int32_t lpad, int32_t wgs, int32_t *pieces5, int32_t *planes)
+// Bytes of the route's tables in the workspace: the queue, then first slot and slot count per tile.
+size_t gram256_table_bytes(int64_t n, int32_t lpad)
 {
-    std::vector<BigPiece> pc((size_t)256 * kBigMaxPieces);
-    const int32_t need = gram256_cut(n, lpad, wgs, pc.data(), planes);
-    for (size_t i = 0; i < pc.size(); ++i) {
-        pieces5[5 * i + 0] = pc[i].ta; pieces5[5 * i + 1] = pc[i].tb; pieces5[5 * i + 2] = pc[i].sbeg;
-        pieces5[5 * i + 3] = pc[i].send; pieces5[5 * i + 4] = pc[i].plane;
-    }
-    return need;
+    const size_t T2 = (size_t)((lpad + kBigTile - 1) / kBigTile);
+    return sizeof(BigPiece) * (size_t)gram256_items(n, lpad) + 2 * sizeof(int32_t) * T2 * T2;
 }
 
-size_t gram256_table_bytes() { return sizeof(BigPiece) * 256 * kBigMaxPieces + sizeof(int32_t) * 32 * 32; }
-
-// Fill the host image of the route's tables ([256][kBigMaxPieces] pieces, then [T2 * T2] plane counts).
-int32_t gram256_tables(const strads_lasso *h, int32_t wgs, void *out)
+// Host image of those tables; returns the number of items.
+int32_t gram256_tables(int64_t n, int32_t lpad, void *out)
 {
-    BigPiece *pieces = reinterpret_cast<BigPiece *>(out);
-    int32_t *planes = reinterpret_cast<int32_t *>(pieces + 256 * kBigMaxPieces);
-    return gram256_cut(h->cfg.n, h->Lpad, wgs, pieces, planes);
+    const int32_t T2 = (lpad + kBigTile - 1) / kBigTile;
+    std::vector<int32_t> first((size_t)T2 * T2), count((size_t)T2 * T2);
+    const std::vector<BigPiece> q = gram256_queue(n, lpad, first.data(), count.data());
+    char *o = reinterpret_cast<char *>(out);
+    memcpy(o, q.data(), sizeof(BigPiece) * q.size());
+    memcpy(o + sizeof(BigPiece) * q.size(), first.data(), sizeof(int32_t) * first.size());
+    memcpy(o + sizeof(BigPiece) * q.size() + sizeof(int32_t) * first.size(), count.data(), sizeof(int32_t) * count.size());
+    return (int32_t)q.size();
+}
+
+// The queue as plain integers for the host-side plan call: items5[i] = (ta, tb, sbeg, send, slot).
+int32_t gram256_plan_host(int64_t n, int32_t lpad, int32_t cap, int32_t *items5, int32_t *first, int32_t *count)
+{
+    const std::vector<BigPiece> q = gram256_queue(n, lpad, first, count);
+    for (size_t i = 0; i < q.size() && i < (size_t)cap; ++i) {
+        items5[5 * i + 0] = q[i].ta; items5[5 * i + 1] = q[i].tb; items5[5 * i + 2] = q[i].sbeg;
+        items5[5 * i + 3] = q[i].send; items5[5 * i + 4] = q[i].slot;
+    }
+    return (int32_t)q.size();
 }
 
 size_t gram_partial_floats(int64_t n, int32_t lpad, bool dynamic)
 {
     if (!dynamic) {
-        int32_t planes = gram_split_choose(n, lpad);
+        size_t need = (size_t)gram_split_choose(n, lpad) * lpad * lpad;
         if (gram256_default(n, lpad, STRADS_LAYOUT_DENSE_COLMAJOR, STRADS_DEPS_STATIC)) {
-            const int32_t need = gram256_cut(n, lpad, 256, nullptr, nullptr);     // 0: never for these shapes
-            if (need > planes) planes = need;
+            const size_t slots = (size_t)gram256_items(n, lpad) * kBigSlot;      // one tile slot per queue item
+            if (slots > need) need = slots;
         }
-        return (size_t)planes * lpad * lpad;
+        return need;
     }
     size_t most = 0;                                        // any mover count up to lpad
     for (int32_t l = kGramTile; l <= lpad; l += kGramTile) {
@@ -1215,23 +1231,24 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
     const GramShape *gdev = dynamic ? h->at<GramShape>(h->ws.dshape) : nullptr;
     const size_t lds = 2 * 2 * kPanel * sizeof(float);
     float *P = h->at<float>(h->ws.partial);
-    const bool big = !dynamic && h->big_wgs > 0;            // 256-wide tiles (see k_gram_tiles256)
-    const BigPiece *pieces = reinterpret_cast<const BigPiece *>(h->base + h->ws.big_tables);
+    const bool big = !dynamic && h->big_items > 0;          // 256-wide tiles (see k_gram_tiles256)
+    const BigPiece *items = reinterpret_cast<const BigPiece *>(h->base + h->ws.big_tables);
+    RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     if (part == 1) {
-        RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
         dim3 grid((h->Lpad + 1023) / 1024, h->Lpad);       // 1024 columns of one row per workgroup
         if (dynamic) { if (grid.x > 2) grid.x = 2; if (grid.y > 2048) grid.y = 2048; }
         hipLaunchKernelGGL(k_gram_mask, grid, dim3(256), 0, h->stream, P, g, gdev, h->cfg.rho,
                            h->at<uint64_t>(h->ws.mask), h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr,
                            &sc->near_rho_pairs,
-                           big ? reinterpret_cast<const int32_t *>(pieces + 256 * kBigMaxPieces) : nullptr,
-                           (h->Lpad + kBigTile - 1) / kBigTile);
+                           big ? reinterpret_cast<const int32_t *>(items + h->big_items) : nullptr,
+                           (h->Lpad + kBigTile - 1) / kBigTile, big ? &sc->gram_next : nullptr);
         return launch_status(h->stream);
     }
     if (big) {
-        hipLaunchKernelGGL(k_gram_tiles256, dim3((unsigned)h->big_wgs), dim3(kBigThreads),
-                           2 * 2 * kBigPanel * sizeof(float), h->stream, h->cfg.x, h->cfg.n,
-                           h->at<int32_t>(h->ws.cand), h->L, h->Lpad, pieces, P);
+        const unsigned wgs = h->big_items < kBigWorkgroups ? (unsigned)h->big_items : (unsigned)kBigWorkgroups;
+        hipLaunchKernelGGL(k_gram_tiles256, dim3(wgs), dim3(kBigThreads), 2 * 2 * kBigPanel * sizeof(float), h->stream,
+                           h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), h->L, h->Lpad, items, h->big_items,
+                           &sc->gram_next, P);
         return launch_status(h->stream);
     }
     const int load = h->cfg.layout == STRADS_LAYOUT_GENO2 ? kLoadGeno2 : (h->vec4 ? kLoadVec4 : kLoadScalar);

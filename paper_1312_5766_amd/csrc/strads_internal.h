@@ -43,6 +43,7 @@ struct RoundScalars {
     uint32_t bad_input;    // set by the create-time check of a CSC design
     int32_t n_movers;      // dynamic dependencies: candidates whose update is not zero
     int32_t n_mkept;       // dynamic dependencies: movers that passed the filter
+    uint32_t gram_next;    // 256-wide Gram tiles: next item of the kernel's queue (zero between rounds)
     uint32_t overflow;     // CSC designs: a product left the range of the fixed-point accumulators (sticky until
                            // the state is set again); the residual is then written as NaN
 };
@@ -62,7 +63,7 @@ struct Workspace {
     size_t beta, dbeta, r;
     size_t w;               // float [Npad]: logistic loss, the weights eq. (2)'s dot products are taken with
     size_t jobtab;          // int32 [jobs]: static dependencies, dense/packed: job of each Gram workgroup
-    size_t big_tables;      // dense fp32 designs: piece table and per-tile plane counts of the 256-wide Gram tiles
+    size_t big_tables;      // dense fp32 designs: queue and per-tile slot ranges of the 256-wide Gram tiles
     size_t keys;            // uint32 [J]
     size_t hist;            // uint32 [2][kHistBins]
     size_t scalars;         // RoundScalars
@@ -104,6 +105,7 @@ struct strads_lasso {
     float step_scale;   // 1 / curvature of the coordinate step: 1 (squared loss), 4 (logistic loss)
     int32_t split_max;  // K-slices the workspace was sized for
     int32_t split_user; // tuning override (0 = automatic)
+    size_t partial_floats;   // floats of ws.partial
     int32_t dots_with_gram;  // short lists: every candidate's x_j^T r rides along with the Gram launch and the filter's
                              // workgroup commits B_1 (tuning "dots_with_gram", default 1; see dots_ride_with_gram)
     int32_t early_keys;      // rounds enqueued back to back: the next round's key pass rides with the last kernel of the
@@ -114,7 +116,7 @@ struct strads_lasso {
     int32_t *jobtab_host;   // shard 0 only: host staging copy of the table
     int32_t tile256;    // Gram of long lists in 256 x 256 tiles: 0 never, 1 where it is the default, 2 wherever the
                         // workspace has the partial planes for it (tuning "gram_tile256", default 1)
-    int32_t big_wgs;    // workgroups of that route; 0: the 128 x 128 kernel is used
+    int32_t big_items;  // items in that route's queue; 0: the 128 x 128 kernel is used
     int32_t select_cap;
     int64_t round;
     bool vec4;          // dense columns are 16-byte aligned (N % 4 == 0 and x aligned)
@@ -171,11 +173,11 @@ inline hipError_t launch_status(hipStream_t stream)
 int gram_split_auto(int64_t n, int32_t lpad);
 size_t gram_partial_floats(int64_t n, int32_t lpad, bool dynamic);   // floats of K-slice partial tiles to reserve
 void gram_shape_table(int64_t n, int32_t lpad, GramShape *out);      // out[t], t = 0 .. lpad/kGramTile
-int32_t gram256_workgroups(int64_t n, int32_t lpad, int32_t planes_cap);   // 0: the 256-wide route does not fit
 bool gram256_default(int64_t n, int32_t lpad, int32_t layout, int32_t deps);
-size_t gram256_table_bytes();
-int32_t gram256_plan_host(int64_t n, int32_t lpad, int32_t wgs, int32_t *pieces5, int32_t *planes);
-int32_t gram256_tables(const strads_lasso *h, int32_t wgs, void *out);      // host image of ws.big_tables
+int32_t gram256_items(int64_t n, int32_t lpad);                      // items (= tile slots) of the 256-wide route's queue
+size_t gram256_table_bytes(int64_t n, int32_t lpad);
+int32_t gram256_tables(int64_t n, int32_t lpad, void *out);          // host image of ws.big_tables
+int32_t gram256_plan_host(int64_t n, int32_t lpad, int32_t cap, int32_t *items5, int32_t *first, int32_t *count);
 size_t gram_job_table_entries(int64_t n, int32_t lpad);              // capacity needed for gram_job_table
 int32_t gram_job_table(const strads_lasso *h, int32_t *out);         // out[blockIdx.x] = job; returns the job count
 Workspace carve(int64_t n, int64_t j, int32_t layout, int32_t l, int32_t keep_gram, int32_t max_col_nnz, int32_t deps,
@@ -226,7 +228,7 @@ constexpr int kShortList = 4096;
 inline bool dots_ride_with_gram(const strads_lasso *h)
 {
     return h->dots_with_gram && h->cfg.deps == STRADS_DEPS_STATIC && h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR &&
-           h->n_lanes == 1 && h->L <= kShortList && h->big_wgs == 0;
+           h->n_lanes == 1 && h->L <= kShortList && h->big_items == 0;
 }
 struct CandDots;
 CandDots cand_dots_args(strads_lasso *h);                 // arguments of the candidates' tentative updates

@@ -142,68 +142,72 @@ def test_static_filter_rejects_bad_arguments_before_any_device_call():
 
 
 # ---------------------------------------------------------------------------------------------
-# host logic of the tile kernel for long candidate lists: the stream of (tile, stage) pairs cut into runs
+# host logic of the tile kernel for long candidate lists: the queue of (tile, stage range) items
 # ---------------------------------------------------------------------------------------------
-def _plan_facts(n, l, cap):
+def _weight(ta, tb, t, half_last):
+    return 10 if ta == tb else (8 if half_last and tb == t - 1 else 16)
+
+
+@pytest.mark.parametrize("n,l", [(50000, 8000), (50000, 8192), (4096, 4300), (1000, 700), (5000, 513), (4096, 128),
+                                 (260, 1100), (8, 257), (33, 300), (100000, 6000)])
+def test_gram256_queue_covers_every_tile_stage_once_in_shrinking_items(n, l):
     import numpy as np
-    wgs, pieces, planes = pk.strads_lasso_gram256_plan(n, l, cap)
+    items, first, count = pk.strads_lasso_gram256_plan(n, l)
     stages, t = (n + 31) // 32, (l + 255) // 256
+    half_last = t * 256 > (l + 127) // 128 * 128        # the last tile column holds 128 columns of the padded list
     cover = np.zeros((t, t, stages), np.int32)
-    seen, load = set(), np.zeros(256)
-    for w in range(256):
-        ended = False
-        for i in range(pk.GRAM256_MAX_PIECES):
-            ta, tb, s0, s1, plane = (int(v) for v in pieces[w, i])
-            if s1 <= s0:
-                ended = True
-                continue
-            assert not ended, "pieces of a workgroup are listed without gaps"
-            assert w < wgs and 0 <= ta <= tb < t and 0 <= s0 < s1 <= stages
-            cover[ta, tb, s0:s1] += 1
-            assert (ta, tb, plane) not in seen, "two pieces of a tile share a plane"
-            seen.add((ta, tb, plane))
-            load[w] += (s1 - s0) * (10 if ta == tb else 16)
-    return wgs, planes, cover, seen, load[:wgs], t
-
-
-@pytest.mark.parametrize("n,l,cap", [(50000, 8000, 2), (50000, 8192, 2), (4096, 4300, 4), (1000, 700, 16),
-                                     (5000, 513, 30), (4096, 128, 64), (260, 1100, 4), (8, 257, 1),
-                                     (33, 300, 2)])
-def test_gram256_plan_covers_every_tile_stage_once(n, l, cap):
-    import numpy as np
-    wgs, planes, cover, seen, load, t = _plan_facts(n, l, cap)
-    assert 8 <= wgs <= 256 and wgs % 8 == 0
+    assert np.array_equal(items[:, 4], np.arange(len(items)))          # slots are numbered in queue order
+    total = sum(_weight(a, b_, t, half_last) * stages for a in range(t) for b_ in range(a, t))
+    left, prev_tile, prev_end, limit = total, None, 0, 0
+    for ta, tb, s0, s1, slot in (tuple(int(v) for v in row) for row in items):
+        assert 0 <= ta <= tb < t and 0 <= s0 < s1 <= stages
+        cover[ta, tb, s0:s1] += 1
+        w = _weight(ta, tb, t, half_last)
+        # a tile's items are consecutive in the queue and in row order, so its slots are too
+        if (ta, tb) != prev_tile:
+            assert s0 == 0 and first[ta, tb] == slot and (prev_tile is None or prev_end == stages)
+            left -= w * stages
+            # guided sizes: no item is worth more than a 256th of the work queued behind its tile (32 stages
+            # at least), so that the queue ends in short items whatever the workgroups' speeds
+            limit = max(left // 256 // w, 32)
+        else:
+            assert s0 == prev_end
+        prev_tile, prev_end = (ta, tb), s1
+        assert first[ta, tb] <= slot < first[ta, tb] + count[ta, tb]
+        assert s1 - s0 <= limit and (s1 - s0 >= limit // 2 or s1 - s0 == stages or limit == 32)
+    assert left == 0 and prev_end == stages
     for a in range(t):
         for b_ in range(t):
             if a <= b_:
                 assert (cover[a, b_] == 1).all(), (a, b_)
-                assert planes[a, b_] == sum(1 for (x, y, _) in seen if (x, y) == (a, b_))
-                # a tile's planes are numbered 0 .. count-1 without gaps
-                assert {p for (x, y, p) in seen if (x, y) == (a, b_)} == set(range(int(planes[a, b_])))
+                assert count[a, b_] >= 1
             else:
-                assert cover[a, b_].sum() == 0 and planes[a, b_] == 0
-    assert planes.max() <= cap
-    # equal runs: no workgroup's share (in MFMA blocks on the busiest SIMD) differs from another's by more
-    # than one stage of the heavier kind of tile
-    assert load.max() - load.min() <= 16 + 10
+                assert cover[a, b_].sum() == 0 and count[a, b_] == 0 and first[a, b_] == 0
+    assert int(count.sum()) == len(items)
 
 
-def test_gram256_plan_at_the_bench_shape_needs_two_planes_and_all_compute_units():
-    wgs, planes, cover, seen, load, t = _plan_facts(50000, 8000, 2)
-    assert wgs == 256 and t == 32 and planes.max() == 2
-    assert len(seen) <= 528 + 256           # every cut adds at most one piece
+def test_gram256_queue_at_the_bench_shape():
+    items, first, count = pk.strads_lasso_gram256_plan(50000, 8000)
+    lens = items[:, 3] - items[:, 2]
+    assert len(count) == 32 and count.max() <= 1563 // 32 + 1
+    assert (lens[:240] == 1563).all()               # the queue starts with whole tiles, about one per workgroup
+    assert lens[-200:].max() <= 32                  # the queue ends in short items
+    assert 900 <= len(items) <= 2000                # tile slots: 256 KB each
+    assert lens.min() >= 31
 
 
-def test_gram256_plan_rejects_bad_arguments_and_impossible_caps():
-    wgs = C.c_int32(7)
-    buf = (C.c_int32 * (256 * 8 * 5))()
-    pl = (C.c_int32 * 1024)()
+def test_gram256_plan_rejects_bad_arguments():
+    n_items = C.c_int32(7)
+    buf = (C.c_int32 * 5)()
+    tt = (C.c_int32 * 1024)()
     lib = pk.load()
-    assert lib.strads_lasso_gram256_plan(0, 100, 1, C.byref(wgs), buf, pl) == pk.E_INVALID_ARG
-    assert lib.strads_lasso_gram256_plan(100, 0, 1, C.byref(wgs), buf, pl) == pk.E_INVALID_ARG
-    assert lib.strads_lasso_gram256_plan(100, pk.MAX_L_PRIME + 1, 1, C.byref(wgs), buf, pl) == pk.E_INVALID_ARG
-    assert lib.strads_lasso_gram256_plan(100, 100, 0, C.byref(wgs), buf, pl) == pk.E_INVALID_ARG
-    assert lib.strads_lasso_gram256_plan(100, 100, 1, None, buf, pl) == pk.E_INVALID_ARG
-    # 15 tiles of 9 stages cannot be dealt to 8 or more workgroups in whole tiles
-    assert lib.strads_lasso_gram256_plan(260, 1100, 1, C.byref(wgs), buf, pl) == pk.E_UNSUPPORTED
-    assert wgs.value == 0
+    assert lib.strads_lasso_gram256_plan(0, 100, 0, C.byref(n_items), None, tt, tt) == pk.E_INVALID_ARG
+    assert lib.strads_lasso_gram256_plan(100, 0, 0, C.byref(n_items), None, tt, tt) == pk.E_INVALID_ARG
+    assert lib.strads_lasso_gram256_plan(100, pk.MAX_L_PRIME + 1, 0, C.byref(n_items), None, tt, tt) == pk.E_INVALID_ARG
+    assert lib.strads_lasso_gram256_plan(100, 100, -1, C.byref(n_items), buf, tt, tt) == pk.E_INVALID_ARG
+    assert lib.strads_lasso_gram256_plan(100, 100, 1, C.byref(n_items), None, tt, tt) == pk.E_INVALID_ARG
+    assert lib.strads_lasso_gram256_plan(100, 100, 0, None, None, tt, tt) == pk.E_INVALID_ARG
+    assert lib.strads_lasso_gram256_plan(100, 100, 0, C.byref(n_items), None, None, tt) == pk.E_INVALID_ARG
+    assert n_items.value == 7
+    assert lib.strads_lasso_gram256_plan(100, 100, 1, C.byref(n_items), buf, tt, tt) == pk.STRADS_OK
+    assert n_items.value == 1 and list(buf) == [0, 0, 0, 4, 0]

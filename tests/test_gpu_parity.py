@@ -219,11 +219,11 @@ def test_gram_split_k_variants_agree_with_oracle():
 
 
 @pytest.mark.parametrize("n,j,l_prime", [(1000, 900, 700), (5000, 700, 513), (1004, 600, 300), (4096, 300, 128),
-                                         (260, 1200, 1100), (8, 300, 257)])
+                                         (260, 1200, 1100), (8, 600, 511)])
 def test_gram_in_256_wide_tiles_matches_oracle(n, j, l_prime):
-    """The tile kernel for long lists (256 x 256 tiles, work dealt out as a stream of (tile, stage) pairs),
-    forced onto short lists: whole Gram against the oracle, including a ragged last tile, a ragged last K
-    stage, a single diagonal tile and pieces of one stage."""
+    """The tile kernel for long lists (256 x 256 tiles, stage ranges of tiles handed out from a queue), forced
+    onto short lists: whole Gram against the oracle, including a last tile column of 128 columns, a ragged
+    last K stage, a single diagonal tile and one-stage items."""
     p = si.make("c2_dense_block_corr", n=n, j=j, nnz=5, l_prime=l_prime)
     g, o = _pair(p)
     g.set_tuning("gram_tile256", 2)
