@@ -394,11 +394,12 @@ def kkt_pass(g, p, shards, torch):
     return out, viol
 
 
-def gram_roofline(p, L, stage, workload, rides):
+def gram_roofline(p, L, stage, workload, rides, tile_edge=128):
     gram_flops = float(p.n) * L * (L - 1)          # algorithmic: every unordered pair once, 2 flops per row
     ach = gram_flops / (stage["gram_tiles"] * 1e-3) / 1e12
-    tr = measured_traffic("k_gram_tiles", workload, "with_dots" if rides else "tiles_only")
-    return {"bound": "mfma", "kernel": "k_gram_tiles", "achieved": round(ach, 3),
+    kernel = "k_gram_tiles256" if tile_edge == 256 else "k_gram_tiles"
+    tr = measured_traffic(kernel, workload, "with_dots" if rides else "tiles_only")
+    return {"bound": "mfma", "kernel": kernel, "achieved": round(ach, 3),
             "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_FP32_PEAK_TFLOPS, 4),
             "traffic": tr["bytes"] if tr else None, "traffic_source": tr["source"] if tr else None,
             "avg_ms": round(stage["gram_tiles"], 5), "launches": stage["rounds"], "flops_per_launch": gram_flops,
@@ -634,6 +635,7 @@ def main() -> int:
     print("bench.py: warm-up done", file=sys.stderr, flush=True)
 
     g = fresh()
+    tile_edge = g.gram_tile_edge()
     if args.graph_rounds > 0:
         g.set_tuning("graph_rounds", args.graph_rounds)
     f0 = g.objective()
@@ -713,7 +715,8 @@ def main() -> int:
         # does the launch carry the candidates' dot products?  (the library's rule, see "dots_with_gram")
         rides = (p.layout == "dense" and args.shards <= 1 and p.l_prime <= 4096
                  and "dots_with_gram=0" not in [t.replace(" ", "") for t in args.tune])
-        roofline = gram_roofline(p, L, stage, workload_name, rides)
+        rides = rides and tile_edge != 256
+        roofline = gram_roofline(p, L, stage, workload_name, rides, tile_edge)
 
     # for scale: the library route for the same Step 2 (gather the candidate columns, then the vendor
     # GEMM on the panel and its transpose, fp32), timed live on this machine

@@ -307,6 +307,11 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value);
 int strads_lasso_gram256_plan(int64_t n, int32_t l, int32_t items_cap, int32_t *n_items, int32_t *items,
                               int32_t *first_slot, int32_t *n_slots);
 
+/* Which tile kernel forms Step 2's Gram for this handle as it is tuned now: edge (HOST int32) = 256 (tiles of
+ * 256 x 256 from a queue, see "gram_tile256"), 128 (tiles of 128 x 128 with K-slices), or 0 (a sparse design or
+ * no dependency check: no tile kernel). */
+int strads_lasso_gram_tile_edge(strads_lasso_t *h, int32_t *edge);
+
 /* Average duration in milliseconds of each stage (HOST array of STRADS_N_STAGES floats) over the
  * rounds enqueued since profiling was switched on or since the last call, measured with HIP events
  * recorded on the handle's stream.  Switch on with strads_lasso_set_tuning(h, "profile_level", v):

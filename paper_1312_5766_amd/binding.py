@@ -36,6 +36,7 @@ EXPORTS = [
     "strads_lasso_last_round", "strads_lasso_last_candidates", "strads_lasso_stage_keys", "strads_lasso_stage_filter",
     "strads_lasso_set_tuning", "strads_lasso_stage_times", "strads_lasso_last_kkt_ms", "strads_lasso_destroy",
     "strads_lasso_strerror", "strads_lasso_filter_static", "strads_lasso_debug_build", "strads_lasso_gram256_plan",
+    "strads_lasso_gram_tile_edge",
 ]
 
 
@@ -90,6 +91,7 @@ def load():
     L.strads_lasso_stage_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     L.strads_lasso_filter_static.argtypes = [vp, C.c_int32, C.c_float, C.c_int32, vp, vp, vp]
     L.strads_lasso_debug_build.argtypes = []
+    L.strads_lasso_gram_tile_edge.argtypes = [vp, C.POINTER(C.c_int32)]
     L.strads_lasso_gram256_plan.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.POINTER(C.c_int32), vp, vp, vp]
     L.strads_lasso_destroy.argtypes = [vp]
     L.strads_lasso_destroy.restype = None
@@ -321,6 +323,11 @@ class StradsLasso:
         ms = C.c_float()
         _check(load().strads_lasso_last_kkt_ms(self._h, C.byref(ms)), "strads_lasso_last_kkt_ms")
         return float(ms.value)
+
+    def gram_tile_edge(self) -> int:
+        edge = C.c_int32(-1)
+        _check(load().strads_lasso_gram_tile_edge(self._h, C.byref(edge)), "strads_lasso_gram_tile_edge")
+        return edge.value
 
     def set_tuning(self, name: str, value: int):
         _check(load().strads_lasso_set_tuning(self._h, name.encode(), int(value)), "strads_lasso_set_tuning")

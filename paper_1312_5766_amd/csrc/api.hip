@@ -724,6 +724,14 @@ int strads_lasso_gram256_plan(int64_t n, int32_t l, int32_t items_cap, int32_t *
     return STRADS_OK;
 }
 
+int strads_lasso_gram_tile_edge(strads_lasso_t *h, int32_t *edge)
+{
+    if (!h || !edge) return STRADS_E_INVALID_ARG;
+    if (h->cfg.layout == STRADS_LAYOUT_CSC || h->cfg.deps == STRADS_DEPS_NONE) { *edge = 0; return STRADS_OK; }
+    *edge = h->cfg.deps == STRADS_DEPS_STATIC && h->big_items > 0 ? 256 : kGramTile;
+    return STRADS_OK;
+}
+
 int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
 {
     if (!h || !name) return STRADS_E_INVALID_ARG;

@@ -211,3 +211,9 @@ def test_gram256_plan_rejects_bad_arguments():
     assert n_items.value == 7
     assert lib.strads_lasso_gram256_plan(100, 100, 1, C.byref(n_items), buf, tt, tt) == pk.STRADS_OK
     assert n_items.value == 1 and list(buf) == [0, 0, 0, 4, 0]
+
+
+def test_gram_tile_edge_rejects_null_arguments():
+    edge = C.c_int32(5)
+    assert pk.load().strads_lasso_gram_tile_edge(None, C.byref(edge)) == pk.E_INVALID_ARG
+    assert edge.value == 5

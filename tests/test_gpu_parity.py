@@ -226,8 +226,10 @@ def test_gram_in_256_wide_tiles_matches_oracle(n, j, l_prime):
     last K stage, a single diagonal tile and one-stage items."""
     p = si.make("c2_dense_block_corr", n=n, j=j, nnz=5, l_prime=l_prime)
     g, o = _pair(p)
+    assert g.gram_tile_edge() == 128
     g.set_tuning("gram_tile256", 2)
-    for _ in range(2):                                  # twice: stale partial planes must not leak into a round
+    assert g.gram_tile_edge() == 256
+    for _ in range(2):                                  # twice: stale tile slots must not leak into a round
         g.round()
         lr = g.last_round(want_gram=True)
         cand = _np(lr["cand"])
@@ -243,6 +245,7 @@ def test_gram_of_a_long_list_takes_the_256_wide_route_and_matches_oracle_rows():
     rows of the Gram against the oracle, the rest against the 128-wide kernel's result on the same candidates."""
     p = si.make("c5_dense_duplicates", n=4096, j=4500, nnz=20, l_prime=4300)
     g, o = _pair(p)
+    assert g.gram_tile_edge() == 256
     g.round()
     lr = g.last_round(want_gram=True)
     cand, G = _np(lr["cand"]), _np(lr["G"])
@@ -253,6 +256,7 @@ def test_gram_of_a_long_list_takes_the_256_wide_route_and_matches_oracle_rows():
     assert np.array_equal(G, G.T)
     g2, _ = _pair(p)
     g2.set_tuning("gram_tile256", 0)
+    assert g2.gram_tile_edge() == 128
     g2.round()
     lr2 = g2.last_round(want_gram=True)
     assert np.array_equal(_np(lr2["cand"]), cand)
