@@ -261,7 +261,7 @@ def run_sweep(args) -> int:
     import paper_1312_5766_amd as pk
     pk.load()
     dev = torch.device("cuda:0")
-    print(f"{'N':>6} {'L=k':>5} | {'gram us':>9} {'TFLOP/s':>8} {'frac':>5} | {'dots MB':>8} {'us':>7} {'GB/s':>6} "
+    print(f"{'N':>6} {'L=k':>5} | {'gram us':>9} {'TFLOP/s':>8} {'frac':>5} {'tile':>4} {'mask us':>7} | {'dots MB':>8} {'us':>7} {'GB/s':>6} "
           f"{'frac':>5} | {'resid us':>8} {'GB/s':>6} {'frac':>5}", flush=True)
     for n in args.sweep_rows:
         for l in args.sweep_l_prime:
@@ -276,7 +276,11 @@ def run_sweep(args) -> int:
             s.set_tuning("dots_with_gram", 0)      # the kept-set dot products as a kernel of their own, so that they can be timed
             for t in args.tune:
                 name, value = t.split("=")
-                s.set_tuning(name, int(value))
+                try:
+                    s.set_tuning(name, int(value))
+                except pk.StradsError as e:            # a route the shape has no room for: the point keeps the default
+                    print(f"# N={n} L'={l}: {name}={value} refused ({e})", flush=True)
+            edge = s.gram_tile_edge()
             for _ in range(2):
                 s.round()
             # every round starts from the same state, so the values stay finite whatever Jacobi does with L' columns
@@ -296,7 +300,8 @@ def run_sweep(args) -> int:
             gram_tf = n * l * (l - 1) / (st["gram_tiles"] * 1e-3) / 1e12 if st["gram_tiles"] > 0 else 0.0
             dots_gb = 4.0 * n * (k + 1) / (st["update"] * 1e-3) / 1e9 if st["update"] > 0 else 0.0
             res_gb = (4.0 * n * k1 + 8.0 * n) / (st["residual"] * 1e-3) / 1e9
-            print(f"{n:>6} {l:>5} | {st['gram_tiles'] * 1e3:>9.1f} {gram_tf:>8.1f} {gram_tf / MFMA_FP32_PEAK_TFLOPS:>5.3f} | "
+            print(f"{n:>6} {l:>5} | {st['gram_tiles'] * 1e3:>9.1f} {gram_tf:>8.1f} {gram_tf / MFMA_FP32_PEAK_TFLOPS:>5.3f} "
+                  f"{edge:>4} {st['gram_mask'] * 1e3:>7.1f} | "
                   f"{4e-6 * n * (k + 1):>8.1f} {st['update'] * 1e3:>7.1f} {dots_gb:>6.0f} {dots_gb / HBM_PEAK_GBPS:>5.3f} | "
                   f"{st['residual'] * 1e3:>8.1f} {res_gb:>6.0f} {res_gb / HBM_PEAK_GBPS:>5.3f}", flush=True)
             del x, y, s
