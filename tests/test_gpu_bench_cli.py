@@ -64,7 +64,9 @@ def test_size_sweep_mode_prints_one_row_per_point():
     assert len(lines) == 3 and lines[0].split()[0] == "N"
     for l in lines[1:]:
         f = l.replace("|", " ").split()
-        assert int(f[0]) == 3000 and float(f[2]) > 0 and float(f[6]) > 0 and float(f[9]) > 0
+        # N, L', gram us, TFLOP/s, frac, tile kernel, mask us | dots MB, us, GB/s, frac | residual us, GB/s, frac
+        assert len(f) == 14 and int(f[0]) == 3000 and int(f[5]) == 128
+        assert float(f[2]) > 0 and float(f[6]) > 0 and float(f[8]) > 0 and float(f[11]) > 0
 
 
 def test_scheduler_comparison_mode_prints_one_line_per_scheduler():
