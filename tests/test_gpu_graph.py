@@ -17,9 +17,12 @@ def _gpu():
 
 
 @pytest.mark.parametrize("kw", [dict(), dict(n_shards=3), dict(dynamic=True), dict(n_shards=2, dynamic=True),
-                                dict(priority="uniform", no_deps=True, p_max=64)])
+                                dict(priority="uniform", no_deps=True, p_max=64), dict(tile256=True),
+                                dict(tile256=True, n_shards=2)])
 def test_graph_replays_equal_eager_rounds(kw):
     pk = _gpu()
+    kw = dict(kw)
+    tile256 = kw.pop("tile256", False)      # the Gram in 256-wide tiles from a queue, whose position the mask kernel resets
     dev = torch.device("cuda:0")
     p = si.make("c2_dense_block_corr", n=1000, j=3000, nnz=20, l_prime=300)
     side = torch.cuda.Stream(dev)               # the legacy default stream cannot be captured
@@ -27,6 +30,10 @@ def test_graph_replays_equal_eager_rounds(kw):
         base = dict(x=p.x.to(dev), y=p.y.to(dev), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
         g = pk.StradsLasso(**base, **kw)        # replays graphs of 4 rounds
         e = pk.StradsLasso(**base, **kw)        # never uses graphs
+        if tile256:
+            g.set_tuning("gram_tile256", 2)
+            e.set_tuning("gram_tile256", 2)
+            assert g.gram_tile_edge() == e.gram_tile_edge() == 256
         g.set_tuning("graph_rounds", 4)
         e.set_tuning("graph_rounds", 0)
         total = 0

@@ -57,13 +57,20 @@ def test_one_coordinate_per_shard_is_cyclic_coordinate_descent():
         assert np.abs(_np(g.get_state()[0]) - b).max() < 1e-5
 
 
-@pytest.mark.parametrize("kw", [dict(n_shards=2), dict(n_shards=4), dict(n_shards=3, dynamic=True)])
+@pytest.mark.parametrize("kw", [dict(n_shards=2), dict(n_shards=4), dict(n_shards=3, dynamic=True),
+                                dict(n_shards=2, tile256=True)])
 def test_overlapped_run_equals_serialised_rounds_and_tracks_the_oracle(kw):
     pk = _gpu()
     dev = torch.device("cuda:0")
+    kw = dict(kw)
+    tile256 = kw.pop("tile256", False)      # the shards' Gram kernels in 256-wide tiles, each with a queue of its own
     p = si.make("c2_dense_block_corr", n=2000, j=8000, nnz=40, l_prime=500)
     base = dict(x=p.x.to(dev), y=p.y.to(dev), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
     a, b, c = (pk.StradsLasso(**base, **kw) for _ in range(3))
+    if tile256:
+        for h in (a, b, c):
+            h.set_tuning("gram_tile256", 2)
+            assert h.gram_tile_edge() == 256
     o = OracleLasso(x=p.x.numpy(), y=p.y.numpy(), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed, **kw)
     R = 40
     ia = a.run(R)                           # one call: the shards overlap
