@@ -702,9 +702,13 @@ __global__ __launch_bounds__(kBigThreads, 1) void k_gram_tiles256(const float *_
         const uint32_t it = taken;              // uniform
         if (it >= (uint32_t)n_items) break;
         const BigPiece pc = items[it];
-        // the last tile row / column holds 256 or 128 columns of the (128-padded) list
-        const bool half = (pc.tb + 1) * kBigTile > Lpad;
-        if (pc.ta != pc.tb && !half) {
+        // 32-column blocks of tile column tb that hold candidates: 8, fewer in the last tile column
+        const int nbv = L - pc.tb * kBigTile >= kBigTile ? 8 : (L - pc.tb * kBigTile + 31) / 32;
+        const bool half = nbv <= 4;
+        if (pc.ta != pc.tb && nbv <= 2) {
+            // 256 rows x 64 columns: wavefront w takes rows 32 w .. +31, two blocks
+            gram_piece256<false, 0x1u, 0u>(X, N, cand, L, Lpad, pc, wave, 0, P, smem);
+        } else if (pc.ta != pc.tb && !half) {
             // wavefront (wr, wc) = (wave / 4, wave % 4): rows 128 wr .. +127, columns 64 wc .. +63, all eight blocks
             gram_piece256<false, 0xFu, 0u>(X, N, cand, L, Lpad, pc, (wave >> 2) * 4, (wave & 3) * 2, P, smem);
         } else if (pc.ta != pc.tb) {
@@ -712,8 +716,8 @@ __global__ __launch_bounds__(kBigThreads, 1) void k_gram_tiles256(const float *_
             // 64 (wave % 2) .. +63, four blocks each
             gram_piece256<false, 0x3u, 0u>(X, N, cand, L, Lpad, pc, (wave >> 1) * 2, (wave & 1) * 2, P, smem);
         } else if (half) {
-            // the corner tile with 128 columns: one diagonal 128 x 128 square, 10 blocks
-            if (wave == 3) gram_piece256<true, 0x7u, 0x8u>(X, N, cand, L, Lpad, pc, 0, 2, P, smem);
+            // the corner tile with at most 128 columns: one diagonal 128 x 128 square, 10 blocks (3 if 64 columns)
+            if (wave == 3 && nbv > 2) gram_piece256<true, 0x7u, 0x8u>(X, N, cand, L, Lpad, pc, 0, 2, P, smem);
             else if (wave == 7) gram_piece256<true, 0x1u, 0x2u>(X, N, cand, L, Lpad, pc, 0, 0, P, smem);
             else gram_piece256<true, 0u, 0u>(X, N, cand, L, Lpad, pc, 0, 0, P, smem);
         } else {
