@@ -531,7 +531,8 @@ struct BigPiece {
 // BOTH, RIGHT: which of the wavefront's blocks are multiplied (see below); compile-time, because a choice made
 // at run time around the MFMA statements makes the compiler copy accumulators between registers right behind
 // them, and it does not know how long their results take.
-template <bool DIAG, uint32_t BOTH, uint32_t RIGHT>
+// LATE: the K step of a stage (0 .. 2) behind whose first eight MFMAs the wavefront stages the next data.
+template <bool DIAG, uint32_t BOTH, uint32_t RIGHT, int LATE = 0>
 __device__ __forceinline__ void gram_piece256(const float *__restrict__ X, int64_t N,
                                               const int32_t *__restrict__ cand, int32_t L, int32_t Lpad,
                                               const BigPiece pc, int ra, int cb, float *__restrict__ P, float *smem)
@@ -619,7 +620,8 @@ __device__ __forceinline__ void gram_piece256(const float *__restrict__ X, int64
         }
     };
     // One stage: multiply stage `buf` out of LDS; `cur` holds the operands of its first K step.  `between`
-    // (the next stage's LDS writes, the global loads of the stage after) runs behind the first eight MFMAs.
+    // (the next stage's LDS writes, the global loads of the stage after) runs behind the first eight MFMAs of
+    // K step LATE (before the stage's barrier in any case).
     // The stage's one barrier sits before its last K step: by then every wavefront has written its share of
     // the next stage and nobody reads that buffer any more, so the last step can already request the next
     // stage's first operands.  `more`: another stage follows.
@@ -636,7 +638,7 @@ __device__ __forceinline__ void gram_piece256(const float *__restrict__ X, int64
             for (int a = 0; a < 4; ++a) {
                 mma_row(a, cur.a[a], cur.b);
                 if (ahead) cur.a[a] = read_a(nb, a);
-                if (ks == 0 && a == 0) between();
+                if (ks == LATE && a == 0) between();
             }
             cur.b[0] = bn[0];
             cur.b[1] = bn[1];
@@ -710,7 +712,10 @@ __global__ __launch_bounds__(kBigThreads, 1) void k_gram_tiles256(const float *_
             gram_piece256<false, 0x1u, 0u>(X, N, cand, L, Lpad, pc, wave, 0, P, smem);
         } else if (pc.ta != pc.tb && !half) {
             // wavefront (wr, wc) = (wave / 4, wave % 4): rows 128 wr .. +127, columns 64 wc .. +63, all eight blocks
-            gram_piece256<false, 0xFu, 0u>(X, N, cand, L, Lpad, pc, (wave >> 2) * 4, (wave & 3) * 2, P, smem);
+            // The two wavefronts of a SIMD (w and w + 4) stage at different K steps of a stage, so that one of them
+            // feeds the matrix pipe while the other issues its LDS writes and global loads (-1.4 %).
+            if (wave < 4) gram_piece256<false, 0xFu, 0u, 0>(X, N, cand, L, Lpad, pc, 0, wave * 2, P, smem);
+            else gram_piece256<false, 0xFu, 0u, 2>(X, N, cand, L, Lpad, pc, 4, (wave & 3) * 2, P, smem);
         } else if (pc.ta != pc.tb) {
             // 256 rows x 128 columns: wavefront (wave / 2, wave % 2) takes rows 64 (wave / 2) .. +63 and columns
             // 64 (wave % 2) .. +63, four blocks each
@@ -816,85 +821,101 @@ __device__ __forceinline__ uint64_t spread_every_4th(uint64_t x)
     return x;
 }
 
-// Sum the K-slices in slice order and emit the conflict bits (and, optionally, the fp32 Gram).
-// A thread owns 4 consecutive columns b of one row a (16-byte loads of every slice), a wavefront
-// 256 columns = four 64-bit mask words, assembled from one ballot per column-in-thread; only
-// columns in the tiles at or right of a's diagonal tile exist.  gdev != NULL: the shape is read
-// from device memory (dynamic dependencies) and the grid strides over it.  slots256 != NULL: the tiles
-// were written by k_gram_tiles256 into tile slots; first slot and slot count per tile are looked up there,
-// and queue_next, that kernel's queue position, is put back to zero.
+// Sum the K-slices in slice order and emit the conflict bits (and, optionally, the fp32 Gram) for one
+// wavefront's share: 256 columns b0 .. b0+255 of row a.  A thread owns 4 consecutive columns (16-byte loads of
+// every slice), the wavefront's four 64-bit mask words are assembled from one ballot per column-in-thread;
+// only columns in the tiles at or right of a's diagonal tile exist.  slots256 != NULL: the tiles were written
+// by k_gram_tiles256 into tile slots; first slot and slot count per tile are looked up there.
+__device__ __forceinline__ void mask_segment(const float *__restrict__ P, const GramShape &g, float rho,
+                                             uint64_t *__restrict__ mask, float *__restrict__ gram,
+                                             int32_t *__restrict__ near_pairs, const int32_t *__restrict__ slots256,
+                                             int32_t T2, int32_t a, int32_t b0, int lane)
+{
+    const int32_t L = g.L, Lpad = g.Lpad;
+    const int32_t first = (a / kGramTile) * kGramTile;      // first column of a's diagonal tile
+    // Lpad is a multiple of 128, so a wavefront is either fully inside or half inside (its first 128 columns)
+    if (b0 + 256 <= first) return;                          // uniform per wavefront
+    const int32_t b = b0 + 4 * lane;
+    const bool have = b >= first && b < Lpad;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (have) {
+        int32_t split = b < first + kGramTile ? g.split_diag : g.split_off;
+        const float *p = P + (int64_t)a * Lpad + b;
+        int64_t plane = (int64_t)Lpad * Lpad;
+        if (slots256) {
+            // 256-wide tiles: the items of tile (a / 256, b / 256) lie in consecutive tile slots
+            const int32_t tile = (a / kBigTile) * T2 + b / kBigTile;
+            split = slots256[T2 * T2 + tile];
+            p = P + (int64_t)slots256[tile] * kBigSlot + (a % kBigTile) * kBigTile + b % kBigTile;
+            plane = kBigSlot;
+        }
+        int32_t s = 0;
+        for (; s + 7 < split; s += 8) {                     // eight slices in flight, added in slice order
+            float4 q[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) q[u] = *reinterpret_cast<const float4 *>(p + (s + u) * plane);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { v[0] += q[u].x; v[1] += q[u].y; v[2] += q[u].z; v[3] += q[u].w; }
+        }
+        for (; s < split; ++s) {
+            const float4 q = *reinterpret_cast<const float4 *>(p + s * plane);
+            v[0] += q.x; v[1] += q.y; v[2] += q.z; v[3] += q.w;
+        }
+    }
+    uint64_t B[4];
+    uint32_t n_near = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const bool live = have && a < L && b + c < L && a != b + c;
+        const float ag = fabsf(v[c]);
+        B[c] = __ballot(live && !(ag < rho));
+        if (near_pairs) n_near += (uint32_t)__popcll(__ballot(live && b + c > a && fabsf(ag - rho) <= 1e-6f));
+    }
+    if (lane < 4) {
+        const int32_t wb = b0 + 64 * lane;                  // first column of mask word `lane` of this wavefront
+        if (wb >= first && wb < Lpad) {
+            uint64_t w = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) w |= spread_every_4th((B[c] >> (16 * lane)) & 0xFFFFull) << c;
+            mask[(int64_t)a * (Lpad / 64) + (wb >> 6)] = w;
+        }
+    }
+    if (near_pairs && n_near && lane == 0) atomicAdd(near_pairs, (int32_t)n_near);
+    if (gram && have) {
+        *reinterpret_cast<float4 *>(gram + (int64_t)a * Lpad + b) = make_float4(v[0], v[1], v[2], v[3]);
+        if (b >= first + kGramTile) {                       // mirror the tiles right of the diagonal
+#pragma unroll
+            for (int c = 0; c < 4; ++c) gram[(int64_t)(b + c) * Lpad + a] = v[c];
+        }
+    }
+}
+
+// K-slice planes (128-wide tiles): a workgroup takes 1024 columns of one row.  gdev != NULL: the shape is read
+// from device memory (dynamic dependencies) and the grid strides over it.
 __global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, GramShape gh,
                                                    const GramShape *__restrict__ gdev, float rho,
                                                    uint64_t *__restrict__ mask, float *__restrict__ gram,
-                                                   int32_t *__restrict__ near_pairs,
-                                                   const int32_t *__restrict__ slots256, int32_t T2,
-                                                   uint32_t *__restrict__ queue_next)
+                                                   int32_t *__restrict__ near_pairs)
 {
-    if (queue_next && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *queue_next = 0u;   // for the next round
     const GramShape g = gdev ? *gdev : gh;
-    const int32_t L = g.L, Lpad = g.Lpad;
     const int lane = threadIdx.x & 63;
-    for (int32_t a = blockIdx.y; a < Lpad; a += gridDim.y) {
-        const int32_t first = (a / kGramTile) * kGramTile;  // first column of a's diagonal tile
-        for (int32_t b0 = (blockIdx.x * 256 + (threadIdx.x & ~63)) * 4; b0 < Lpad; b0 += gridDim.x * 1024) {
-            // b0: first column of this wavefront's 256; Lpad is a multiple of 128, so a wavefront is
-            // either fully inside or half inside (its first 128 columns)
-            if (b0 + 256 <= first) continue;                // uniform per wavefront
-            const int32_t b = b0 + 4 * lane;
-            const bool have = b >= first && b < Lpad;
-            float v[4] = {0.f, 0.f, 0.f, 0.f};
-            if (have) {
-                int32_t split = b < first + kGramTile ? g.split_diag : g.split_off;
-                const float *p = P + (int64_t)a * Lpad + b;
-                int64_t plane = (int64_t)Lpad * Lpad;
-                if (slots256) {
-                    // 256-wide tiles: the items of tile (a / 256, b / 256) lie in consecutive tile slots
-                    const int32_t tile = (a / kBigTile) * T2 + b / kBigTile;
-                    split = slots256[T2 * T2 + tile];
-                    p = P + (int64_t)slots256[tile] * kBigSlot + (a % kBigTile) * kBigTile + b % kBigTile;
-                    plane = kBigSlot;
-                }
-                int32_t s = 0;
-                for (; s + 7 < split; s += 8) {             // eight slices in flight, added in slice order
-                    float4 q[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) q[u] = *reinterpret_cast<const float4 *>(p + (s + u) * plane);
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) { v[0] += q[u].x; v[1] += q[u].y; v[2] += q[u].z; v[3] += q[u].w; }
-                }
-                for (; s < split; ++s) {
-                    const float4 q = *reinterpret_cast<const float4 *>(p + s * plane);
-                    v[0] += q.x; v[1] += q.y; v[2] += q.z; v[3] += q.w;
-                }
-            }
-            uint64_t B[4];
-            uint32_t n_near = 0;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const bool live = have && a < L && b + c < L && a != b + c;
-                const float ag = fabsf(v[c]);
-                B[c] = __ballot(live && !(ag < rho));
-                if (near_pairs) n_near += (uint32_t)__popcll(__ballot(live && b + c > a && fabsf(ag - rho) <= 1e-6f));
-            }
-            if (lane < 4) {
-                const int32_t wb = b0 + 64 * lane;          // first column of mask word `lane` of this wavefront
-                if (wb >= first && wb < Lpad) {
-                    uint64_t w = 0;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) w |= spread_every_4th((B[c] >> (16 * lane)) & 0xFFFFull) << c;
-                    mask[(int64_t)a * (Lpad / 64) + (wb >> 6)] = w;
-                }
-            }
-            if (near_pairs && n_near && lane == 0) atomicAdd(near_pairs, (int32_t)n_near);
-            if (gram && have) {
-                *reinterpret_cast<float4 *>(gram + (int64_t)a * Lpad + b) = make_float4(v[0], v[1], v[2], v[3]);
-                if (b >= first + kGramTile) {               // mirror the tiles right of the diagonal
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) gram[(int64_t)(b + c) * Lpad + a] = v[c];
-                }
-            }
-        }
-    }
+    for (int32_t a = blockIdx.y; a < g.Lpad; a += gridDim.y)
+        for (int32_t b0 = (blockIdx.x * 256 + (threadIdx.x & ~63)) * 4; b0 < g.Lpad; b0 += gridDim.x * 1024)
+            mask_segment(P, g, rho, mask, gram, near_pairs, nullptr, 0, a, b0, lane);
+}
+
+// Tile slots (256-wide tiles): a workgroup takes four consecutive rows of one tile, which are 4 KB in a row in
+// every slot of the tile.  It also puts the tile kernel's queue position back to zero for the next round.
+__global__ __launch_bounds__(256) void k_gram_mask256(const float *__restrict__ P, GramShape g, float rho,
+                                                      uint64_t *__restrict__ mask, float *__restrict__ gram,
+                                                      int32_t *__restrict__ near_pairs,
+                                                      const int32_t *__restrict__ slots256, int32_t T2,
+                                                      uint32_t *__restrict__ queue_next)
+{
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *queue_next = 0u;
+    const int32_t a = (int32_t)blockIdx.y * 4 + (int32_t)(threadIdx.x >> 6);
+    if (a >= g.Lpad) return;                                // whole wavefronts
+    mask_segment(P, g, rho, mask, gram, near_pairs, slots256, T2, a, (int32_t)blockIdx.x * kBigTile, threadIdx.x & 63);
 }
 
 // Conflict bits from a caller-supplied full Gram (stage entry for parity tests).
@@ -1239,13 +1260,18 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
     const BigPiece *items = reinterpret_cast<const BigPiece *>(h->base + h->ws.big_tables);
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     if (part == 1) {
+        float *gram = h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr;
+        if (big) {
+            const int32_t T2 = (h->Lpad + kBigTile - 1) / kBigTile;
+            hipLaunchKernelGGL(k_gram_mask256, dim3((unsigned)T2, (unsigned)(h->Lpad + 3) / 4), dim3(256), 0, h->stream, P, g,
+                               h->cfg.rho, h->at<uint64_t>(h->ws.mask), gram, &sc->near_rho_pairs,
+                               reinterpret_cast<const int32_t *>(items + h->big_items), T2, &sc->gram_next);
+            return launch_status(h->stream);
+        }
         dim3 grid((h->Lpad + 1023) / 1024, h->Lpad);       // 1024 columns of one row per workgroup
         if (dynamic) { if (grid.x > 2) grid.x = 2; if (grid.y > 2048) grid.y = 2048; }
         hipLaunchKernelGGL(k_gram_mask, grid, dim3(256), 0, h->stream, P, g, gdev, h->cfg.rho,
-                           h->at<uint64_t>(h->ws.mask), h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr,
-                           &sc->near_rho_pairs,
-                           big ? reinterpret_cast<const int32_t *>(items + h->big_items) : nullptr,
-                           (h->Lpad + kBigTile - 1) / kBigTile, big ? &sc->gram_next : nullptr);
+                           h->at<uint64_t>(h->ws.mask), gram, &sc->near_rho_pairs);
         return launch_status(h->stream);
     }
     if (big) {
