@@ -219,7 +219,7 @@ def test_gram_split_k_variants_agree_with_oracle():
 
 
 @pytest.mark.parametrize("n,j,l_prime", [(1000, 900, 700), (5000, 700, 513), (1004, 600, 300), (4096, 300, 128),
-                                         (260, 1200, 1100), (8, 600, 511)])
+                                         (260, 1200, 1100), (8, 600, 511), (996, 800, 512), (2052, 900, 768)])
 def test_gram_in_256_wide_tiles_matches_oracle(n, j, l_prime):
     """The tile kernel for long lists (256 x 256 tiles, stage ranges of tiles handed out from a queue), forced
     onto short lists: whole Gram against the oracle, including a last tile column of 128 columns, a ragged
