@@ -850,7 +850,14 @@ __device__ __forceinline__ void mask_segment(const float *__restrict__ P, const 
             plane = kBigSlot;
         }
         int32_t s = 0;
-        for (; s + 7 < split; s += 8) {                     // eight slices in flight, added in slice order
+        for (; s + 15 < split; s += 16) {                   // sixteen slices in flight, added in slice order
+            float4 q[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) q[u] = *reinterpret_cast<const float4 *>(p + (s + u) * plane);
+#pragma unroll
+            for (int u = 0; u < 16; ++u) { v[0] += q[u].x; v[1] += q[u].y; v[2] += q[u].z; v[3] += q[u].w; }
+        }
+        for (; s + 7 < split; s += 8) {                     // eight
             float4 q[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) q[u] = *reinterpret_cast<const float4 *>(p + (s + u) * plane);
@@ -913,7 +920,8 @@ __global__ __launch_bounds__(256) void k_gram_mask256(const float *__restrict__ 
                                                       uint32_t *__restrict__ queue_next)
 {
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *queue_next = 0u;
-    const int32_t a = (int32_t)blockIdx.y * 4 + (int32_t)(threadIdx.x >> 6);
+    // last rows first: the tiles at the end of the queue are the ones cut into the most items
+    const int32_t a = (int32_t)(gridDim.y - 1 - blockIdx.y) * 4 + (int32_t)(threadIdx.x >> 6);
     if (a >= g.Lpad) return;                                // whole wavefronts
     mask_segment(P, g, rho, mask, gram, near_pairs, slots256, T2, a, (int32_t)blockIdx.x * kBigTile, threadIdx.x & 63);
 }
