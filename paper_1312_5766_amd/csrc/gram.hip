@@ -780,7 +780,7 @@ __global__ __launch_bounds__(256, kGramOcc) void k_gram_tiles(const float *__res
                                                        GenoCols gc, const int32_t *__restrict__ jobtab,
                                                        float *__restrict__ P, int32_t n_jobs, CandDots cd)
 {
-    extern __shared__ float smem[];             // [2 stages][A panel | B panel]
+    extern __shared__ __align__(16) float smem[];             // [2 stages][A panel | B panel]
     if ((int32_t)blockIdx.x >= n_jobs) {
         if constexpr (LOAD != kLoadGeno2) {
             const int block = (int)blockIdx.x - n_jobs;
@@ -802,7 +802,7 @@ __global__ __launch_bounds__(256, kGramOcc) void k_gram_tiles_dyn(const float *_
                                                            const GramShape *__restrict__ gdev, GenoCols gc,
                                                            float *__restrict__ P)
 {
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     const GramShape g = *gdev;
     const int32_t total = g.T * (g.T - 1) / 2 * g.split_off + g.T * g.split_diag;
     for (int32_t job = blockIdx.x; job < total; job += gridDim.x) {
