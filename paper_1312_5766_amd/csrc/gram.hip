@@ -493,9 +493,11 @@ __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int6
 //
 // A global load instruction costs the matrix pipe the same however little it brings (measured: the 128 x 128
 // kernel above takes 12 % less time when its loads are left out, whether they would have hit the L2 or not),
-// and a 256 x 256 tile needs half as many of them per MFMA.  A workgroup of 8 wavefronts (two per SIMD, one
-// workgroup per compute unit: two LDS stages of 512 columns take 144 KB) owns the tile; wavefront (wr, wc)
-// holds rows 128 wr .. +127 and columns 64 wc .. +63 of it as 4 x 2 MFMA accumulators (128 AGPRs).
+// and a 256 x 256 tile needs half as many of them per MFMA; they also write LDS themselves
+// (global_load_lds_dwordx4), so that no data passes through the vector registers on its way there.  A workgroup
+// of 8 wavefronts (two per SIMD, one workgroup per compute unit: two LDS stages of 512 columns take 128 KB)
+// owns the tile; wavefront (wr, wc) holds rows 128 wr .. +127 and columns 64 wc .. +63 of it as 4 x 2 MFMA
+// accumulators (128 AGPRs).
 //
 // Work is handed out from a queue.  One workgroup per compute unit and a few hundred tiles of 1500 stages
 // do not divide evenly, and the eight XCDs of one chip do not run at the same speed (measured: up to 5 %
@@ -514,7 +516,7 @@ __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int6
 constexpr int kBigTile = 256;
 constexpr int32_t kJobBlock = 8;                        // tiles per side of a block of jobs that share panels in one L2
 constexpr int kBigThreads = 512;
-constexpr int kBigPanel = kBigTile * kRow;              // floats per 256-column operand panel per stage
+constexpr int kBigLdsBytes = 2 * 2 * kBigTile * kGramKT * (int)sizeof(float);   // two stages of two 256-column panels
 constexpr int kBigColsPerPass = kBigThreads / kKQ;      // columns the 512 threads stage in one pass
 constexpr int kBigPasses = kBigTile / kBigColsPerPass;  // passes per panel
 constexpr int kBigSlot = kBigTile * kBigTile;           // floats per tile slot
@@ -528,59 +530,86 @@ struct BigPiece {
     int32_t pad_[3];
 };
 
-// BOTH, RIGHT: which of the wavefront's blocks are multiplied (see below); compile-time, because a choice made
-// at run time around the MFMA statements makes the compiler copy accumulators between registers right behind
-// them, and it does not know how long their results take.
-// LATE: the K step of a stage (0 .. 2) behind whose first eight MFMAs the wavefront stages the next data.
+// 16 bytes per lane from global memory straight into LDS: lane l's piece lands at lds + 16 l (lds: the same for
+// the whole wavefront).  Issued as an assembly statement so that the compiler does not serialise the pipeline
+// around it (it would wait for every such load before any later LDS read); the waits are placed by hand.
+__device__ __forceinline__ void dma16(const float *g, const float *lds_uniform)
+{
+    const uint32_t l = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const float *)lds_uniform;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(l), "v"(g) : "memory", "m0");
+}
+__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// One item of the queue: stages [sbeg, send) of tile (ta, tb), written to the item's tile slot.
+// The panels come from global memory straight into LDS.  An LDS stage is [panel][256 columns][32 floats],
+// unpadded (a wavefront's 64 pieces of one load instruction are 8 columns x 128 bytes in a row); the 16-byte quads
+// of a column are stored permuted, quad q of column c at position q ^ (c & 7), so that the 32 lanes that read the
+// same quad of 32 consecutive columns spread over all banks.  Two stages are in LDS (128 KB); a stage's loads are
+// requested as early as its buffer is free, a whole stage before they are needed.
+// BOTH, RIGHT: which of the wavefront's blocks are multiplied (see k_gram_tiles256); compile-time, because a
+// choice made at run time around the MFMA statements makes the compiler copy accumulators between registers
+// right behind them, and it does not know how long their results take.
+// LATE: when the wavefront requests its share of the next data.  0: stage st+2 into the buffer of stage st right
+// after stage st's barrier; otherwise stage st+1 into the other buffer behind the first MFMAs of stage st.  The
+// two wavefronts of a SIMD differ in this, so that one of them feeds the matrix pipe while the other issues its
+// loads (all at once: +2.5 %; a K step later than this: +0.3 %; two K steps later: +2.5 %, the data then arrive
+// late for the barrier).
 template <bool DIAG, uint32_t BOTH, uint32_t RIGHT, int LATE = 0>
 __device__ __forceinline__ void gram_piece256(const float *__restrict__ X, int64_t N,
-                                              const int32_t *__restrict__ cand, int32_t L, int32_t Lpad,
-                                              const BigPiece pc, int ra, int cb, float *__restrict__ P, float *smem)
+                                                  const int32_t *__restrict__ cand, int32_t L, int32_t Lpad,
+                                                  const BigPiece pc, int ra, int cb, float *__restrict__ P, float *smem)
 {
     constexpr int NPAN = DIAG ? 1 : 2;
     constexpr int NLD = NPAN * kBigPasses;
-    constexpr int kStage = NPAN * kBigPanel;            // floats per LDS stage
+    constexpr int kRowD = kGramKT;                      // floats per column per stage, no padding
+    constexpr int kPanelD = kBigTile * kRowD;
+    constexpr int kStageD = NPAN * kPanelD;
+    constexpr bool EARLY = LATE == 0;
     const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t kbeg = (int64_t)pc.sbeg * kGramKT;
     const int64_t kend = (int64_t)pc.send * kGramKT < N ? (int64_t)pc.send * kGramKT : N;
     const int nstage = pc.send - pc.sbeg;
     const int nfull = (int)((kend - kbeg) / kGramKT);
 
-    // staging: thread -> column (it * 64 + tid / 8) of each panel, floats (tid % 8) * 4 .. +3 of the stage
-    const int crow = tid / kKQ, kq = (tid % kKQ) * 4;
+    // staging: thread -> column (it * 64 + tid / 8) of each panel; it brings the quad that belongs at position
+    // tid % 8 of that column
+    const int crow = tid / kKQ, pq = tid % kKQ;
+    const int kq = (pq ^ (crow & 7)) * 4;
     const float *col[NLD];
-    float4 R[NLD];
 #pragma unroll
     for (int p = 0; p < NPAN; ++p)
 #pragma unroll
         for (int it = 0; it < kBigPasses; ++it) {
             int i = (p == 0 ? pc.ta : pc.tb) * kBigTile + it * kBigColsPerPass + crow;
-            i = i < L ? i : L - 1;                      // columns past the list: clamped, their products are never read
+            i = i < L ? i : L - 1;
             col[p * kBigPasses + it] = X + (int64_t)cand[i] * N;
         }
-    auto fetch = [&](int st) {
+    auto dma = [&](int st, int buf) {                   // a stage that lies entirely inside the item's rows
         const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) R[i] = load_k4<true>(col[i], k, kend);
-    };
-    auto fetch_full = [&](int st) {
-        const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) R[i] = *reinterpret_cast<const float4 *>(col[i] + k);
-    };
-    auto stash = [&](int buf) {
 #pragma unroll
         for (int p = 0; p < NPAN; ++p)
 #pragma unroll
             for (int it = 0; it < kBigPasses; ++it)
-                *reinterpret_cast<float4 *>(smem + buf * kStage + p * kBigPanel +
-                                            (it * kBigColsPerPass + crow) * kRow + kq) = R[p * kBigPasses + it];
+                dma16(col[p * kBigPasses + it] + k,
+                      smem + buf * kStageD + p * kPanelD + (it * kBigColsPerPass + wave * 8) * kRowD);
+    };
+    auto bring = [&](int st, int buf) {                 // any stage: a ragged one goes through registers
+        if (st < nfull) { dma(st, buf); return; }
+        const int64_t k = kbeg + (int64_t)st * kGramKT + kq;
+        float4 R[NLD];
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) R[i] = load_k4<true>(col[i], k, kend);
+#pragma unroll
+        for (int p = 0; p < NPAN; ++p)
+#pragma unroll
+            for (int it = 0; it < kBigPasses; ++it)
+                *reinterpret_cast<float4 *>(smem + buf * kStageD + p * kPanelD +
+                                            (it * kBigColsPerPass + crow) * kRowD + pq * 4) = R[p * kBigPasses + it];
     };
 
     const int lane = tid & 63;
     const int li = lane & 31, lh = lane >> 5;
-    // The wavefront's blocks: rows 32 (ra + a) .. +31, columns 32 (cb + b) .. +31 of the tile, a < 4, b < 2.
-    // BOTH = rows a whose two blocks are multiplied, RIGHT = rows a of which only the block b = 1 is.
     constexpr uint32_t both = BOTH, right = RIGHT;
 
     floatx16 acc[4][2];
@@ -591,24 +620,24 @@ __device__ __forceinline__ void gram_piece256(const float *__restrict__ X, int64
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    const int offa = (ra * 32 + li) * kRow + lh * 4;
-    const int offb = (DIAG ? 0 : kBigPanel) + (cb * 32 + li) * kRow + lh * 4;
-    // Operands of one 8-row K step: lane (li, lh) holds k = 8*ks + 4*lh .. +3 of its four A rows and two B
-    // columns.  The 32 MFMAs of a step go A row by A row; as soon as a row's eight are issued its registers
-    // take the same row of the next step, and the next step's B columns are requested at the start of the
-    // step: 32 operand registers instead of 48, every LDS read at least eight MFMAs ahead of its use.
+    // where lane (li, lh) finds k = 8 ks + 4 lh .. +3 of column (32 r + li): quad 2 ks + lh sits at position
+    // (2 ks + lh) ^ (li & 7)
+    int sw[kGramKT / 8];
+#pragma unroll
+    for (int ks = 0; ks < kGramKT / 8; ++ks) sw[ks] = ((2 * ks + lh) ^ (li & 7)) * 4;
+    const int offa = (ra * 32 + li) * kRowD;
+    const int offb = (DIAG ? 0 : kPanelD) + (cb * 32 + li) * kRowD;
     struct Ops { float4 a[4], b[2]; };
-    auto lds_ops = [&](int buf, int ks) { return smem + buf * kStage + ks * 8; };
-    auto read_a = [&](const float *base, int a) {
-        return *reinterpret_cast<const float4 *>(base + offa + a * 32 * kRow);
+    auto read_a = [&](int buf, int ks, int a) {
+        return *reinterpret_cast<const float4 *>(smem + buf * kStageD + offa + a * 32 * kRowD + sw[ks]);
     };
-    auto read_b = [&](const float *base, int b) {
-        return *reinterpret_cast<const float4 *>(base + offb + b * 32 * kRow);
+    auto read_b = [&](int buf, int ks, int b) {
+        return *reinterpret_cast<const float4 *>(smem + buf * kStageD + offb + b * 32 * kRowD + sw[ks]);
     };
     auto mma_row = [&](int a, const float4 &av4, const float4 (&bv4)[2]) {
         const float av[4] = {av4.x, av4.y, av4.z, av4.w};
         const float b0[4] = {bv4[0].x, bv4[0].y, bv4[0].z, bv4[0].w}, b1[4] = {bv4[1].x, bv4[1].y, bv4[1].z, bv4[1].w};
-        if (both >> a & 1u) {                           // a is a constant once the loops are unrolled
+        if (both >> a & 1u) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 mfma32(acc[a][0], av[c], b0[c]);
@@ -619,69 +648,58 @@ __device__ __forceinline__ void gram_piece256(const float *__restrict__ X, int64
             for (int c = 0; c < 4; ++c) mfma32(acc[a][1], av[c], b1[c]);
         }
     };
-    // One stage: multiply stage `buf` out of LDS; `cur` holds the operands of its first K step.  `between`
-    // (the next stage's LDS writes, the global loads of the stage after) runs behind the first eight MFMAs of
-    // K step LATE (before the stage's barrier in any case).
-    // The stage's one barrier sits before its last K step: by then every wavefront has written its share of
-    // the next stage and nobody reads that buffer any more, so the last step can already request the next
-    // stage's first operands.  `more`: another stage follows.
+    // One stage.  Its barrier sits before its last K step; a wavefront arrives there with its own loads into
+    // the next stage's buffer landed.  `between` runs behind the first eight MFMAs of the last K step (early
+    // wavefronts: the barrier has just freed this stage's buffer) or of K step 1 (late ones).
     auto stage = [&](int buf, Ops &cur, bool more, auto between) {
 #pragma unroll
         for (int ks = 0; ks < kGramKT / 8; ++ks) {
             const bool last = ks + 1 == kGramKT / 8;
-            if (last && more) __syncthreads();
+            if (last && more) { dma_wait(); __syncthreads(); }
             const bool ahead = !last || more;
-            const float *nb = last ? lds_ops(buf ^ 1, 0) : lds_ops(buf, ks + 1);
+            const int nbuf = last ? buf ^ 1 : buf, nks = last ? 0 : ks + 1;
             float4 bn[2] = {cur.b[0], cur.b[1]};
-            if (ahead) { bn[0] = read_b(nb, 0); bn[1] = read_b(nb, 1); }
+            if (ahead) { bn[0] = read_b(nbuf, nks, 0); bn[1] = read_b(nbuf, nks, 1); }
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
                 mma_row(a, cur.a[a], cur.b);
-                if (ahead) cur.a[a] = read_a(nb, a);
-                if (ks == LATE && a == 0) between();
+                if (ahead) cur.a[a] = read_a(nbuf, nks, a);
+                if (ks == (EARLY ? kGramKT / 8 - 1 : 0) && a == 0) between();
             }
             cur.b[0] = bn[0];
             cur.b[1] = bn[1];
         }
     };
-    auto read_ops = [&](int buf, int ks) {
-        const float *base = lds_ops(buf, ks);
-        Ops o;
-#pragma unroll
-        for (int a = 0; a < 4; ++a) o.a[a] = read_a(base, a);
-#pragma unroll
-        for (int b = 0; b < 2; ++b) o.b[b] = read_b(base, b);
-        return o;
-    };
 
-    fetch(0);
-    stash(0);
-    if (nstage > 1) fetch(1);
+    bring(0, 0);
+    if (EARLY && nstage > 1) bring(1, 1);
+    dma_wait();
     __syncthreads();
-    Ops cur = read_ops(0, 0);
+    Ops cur;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) cur.a[a] = read_a(0, 0, a);
+#pragma unroll
+    for (int b = 0; b < 2; ++b) cur.b[b] = read_b(0, 0, b);
     int st = 0;
     for (; st + 2 < nfull; ++st)                // steady state
-        stage(st & 1, cur, true, [&] { stash((st + 1) & 1); fetch_full(st + 2); });
-    for (; st + 2 < nstage; ++st)               // a ragged last stage is fetched with clamping
-        stage(st & 1, cur, true, [&] { stash((st + 1) & 1); fetch(st + 2); });
-    if (st + 1 < nstage) {
-        stage(st & 1, cur, true, [&] { stash((st + 1) & 1); });
-        ++st;
-    }
+        stage(st & 1, cur, true, [&] { if (EARLY) dma(st + 2, st & 1); else dma(st + 1, (st & 1) ^ 1); });
+    for (; st + 1 < nstage; ++st)               // the last stages: what is left to bring may be ragged or nothing
+        stage(st & 1, cur, true, [&] {
+            if (EARLY) { if (st + 2 < nstage) bring(st + 2, st & 1); }
+            else bring(st + 1, (st & 1) ^ 1);
+        });
     stage(st & 1, cur, false, [] {});
     mfma_drain();
 
-    float *out = P + (int64_t)pc.slot * kBigSlot;       // the item's own 256 x 256 slot
+    float *out = P + (int64_t)pc.slot * kBigSlot;
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
-            const int rb = ra + a, cbk = cb + b;        // row and column block inside the tile
+            const int rb = ra + a, cbk = cb + b;
             const bool mine = (both >> a & 1u) || (b == 1 && (right >> a & 1u));
-            // blocks past the padded list are never read
             if (!mine || pc.ta * kBigTile + rb * 32 >= Lpad || pc.tb * kBigTile + cbk * 32 >= Lpad) continue;
             store_block(out, kBigTile, rb * 32, cbk * 32, acc[a][b], li, lh);
-            // inside a diagonal 128 x 128 square the mask kernel expects both triangles
             if (DIAG && rb != cbk && rb / 4 == cbk / 4) store_block_t(out, kBigTile, rb * 32, cbk * 32, acc[a][b], li, lh);
         }
 }
@@ -1284,7 +1302,7 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
     }
     if (big) {
         const unsigned wgs = h->big_items < kBigWorkgroups ? (unsigned)h->big_items : (unsigned)kBigWorkgroups;
-        hipLaunchKernelGGL(k_gram_tiles256, dim3(wgs), dim3(kBigThreads), 2 * 2 * kBigPanel * sizeof(float), h->stream,
+        hipLaunchKernelGGL(k_gram_tiles256, dim3(wgs), dim3(kBigThreads), kBigLdsBytes, h->stream,
                            h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), h->L, h->Lpad, items, h->big_items,
                            &sc->gram_next, P);
         return launch_status(h->stream);
@@ -1346,7 +1364,7 @@ hipError_t gram_prepare()
         if (e != hipSuccess) return e;
     }
     return hipFuncSetAttribute(reinterpret_cast<const void *>(k_gram_tiles256),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 2 * kBigPanel * (int)sizeof(float));
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
 }
 
 } // namespace strads
