@@ -272,7 +272,9 @@ int strads_lasso_filter_static(const float *gram, int32_t l, float rho, int32_t 
  *                   L2 (one of the eight XCDs) work on the same K-slices; 0: tile by tile.  Results are
  *                   identical.  Dense and packed designs with static or no dependencies only.
  *   "gram_tile256"  how Step 2's Gram is tiled.  1 (default): lists of more than 4096 candidates over 16-byte
- *                   aligned fp32 columns of at least 4096 rows, under Algorithm 1's dependency rule, are
+ *                   aligned fp32 columns of at least 4096 rows, under Algorithm 1's dependency rule (and shorter
+ *                   lists over columns long enough that every compute unit gets at least 180 stages of 32
+ *                   rows of a tile to multiply), are
  *                   multiplied in 256 x 256 tiles handed out from a queue (strads_lasso_gram256_plan); every
  *                   other shape in 128 x 128 tiles with K-slices.  0: always 128 x 128.  2: 256 x 256 wherever
  *                   the design is fp32, aligned and the rule static (STRADS_E_UNSUPPORTED if the workspace

@@ -1076,12 +1076,17 @@ static std::vector<BigPiece> gram256_queue(int64_t n, int32_t lpad, int32_t *fir
 int32_t gram256_items(int64_t n, int32_t lpad) { return (int32_t)gram256_queue(n, lpad, nullptr, nullptr).size(); }
 
 // Shapes that take the 256-wide route by default (fp32 columns, Algorithm 1's dependency rule; the caller
-// checks the 16-byte alignment of X): lists longer than the short-list route serves, columns long enough
-// that an item is thousands of MFMAs.
+// checks the 16-byte alignment of X): lists longer than the short-list route serves, and shorter ones whose Gram
+// gives every workgroup at least 180 stages' worth of work (measured: 4096 candidates over 50000 rows 6.0 ms
+// against 6.4 ms with 128-wide tiles, 2048 candidates 1.63 against 1.71 ms; 4096 over 10000 rows a tie; below
+// that the 128-wide kernel with its K-slices wins).
 bool gram256_default(int64_t n, int32_t lpad, int32_t layout, int32_t deps)
 {
-    return layout == STRADS_LAYOUT_DENSE_COLMAJOR && deps == STRADS_DEPS_STATIC && lpad > kShortList && n >= 4096 &&
-           n % 4 == 0;
+    if (layout != STRADS_LAYOUT_DENSE_COLMAJOR || deps != STRADS_DEPS_STATIC || n < 4096 || n % 4 != 0) return false;
+    if (lpad > kShortList) return true;
+    const int64_t T2 = (lpad + kBigTile - 1) / kBigTile, S = (n + kGramKT - 1) / kGramKT;
+    const int64_t work = (T2 * (T2 - 1) / 2 * 16 + T2 * 10) * S / 16;      // in stages of an off-diagonal tile
+    return work >= (int64_t)180 * kBigWorkgroups;
 }
 
 // Bytes of the route's tables in the workspace: the queue, then first slot and slot count per tile.
