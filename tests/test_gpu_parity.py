@@ -240,18 +240,19 @@ def test_gram_in_256_wide_tiles_matches_oracle(n, j, l_prime):
         assert np.array_equal(kept, orc.greedy_filter(_np(lr["G"]), o.rho, o.p_max))
 
 
-@pytest.mark.parametrize("j,l_prime", [(4500, 4300), (8192, 8192)])
-def test_gram_of_a_long_list_takes_the_256_wide_route_and_matches_oracle_rows(j, l_prime):
-    """A list longer than 4096 over columns of at least 4096 rows takes the 256-wide tiles by default: sampled
-    rows of the Gram against the oracle, the rest against the 128-wide kernel's result on the same candidates.
+@pytest.mark.parametrize("n,j,l_prime", [(4096, 4500, 4300), (4096, 8192, 8192), (45056, 2100, 2048)])
+def test_gram_of_a_long_list_takes_the_256_wide_route_and_matches_oracle_rows(n, j, l_prime):
+    """A list longer than 4096 over columns of at least 4096 rows takes the 256-wide tiles by default, and so does
+    a shorter list over columns long enough (2048 candidates over 45056 rows): sampled rows of the Gram against
+    the oracle, the rest against the 128-wide kernel's result on the same candidates.
     (8192 is the longest list the library takes: every column is a candidate, 32 x 32 tiles, nothing padded.)"""
-    p = si.make("c5_dense_duplicates", n=4096, j=j, nnz=20, l_prime=l_prime)
+    p = si.make("c5_dense_duplicates", n=n, j=j, nnz=20, l_prime=l_prime)
     g, o = _pair(p)
     assert g.gram_tile_edge() == 256
     g.round()
     lr = g.last_round(want_gram=True)
     cand, G = _np(lr["cand"]), _np(lr["G"])
-    rows = np.unique(np.concatenate([[0, 127, 128, 255, 256, 4095, 4096, 4223, l_prime - 1],
+    rows = np.unique(np.concatenate([np.minimum([0, 127, 128, 255, 256, 4095, 4096, 4223, l_prime - 1], l_prime - 1),
                                      np.random.default_rng(5).integers(0, l_prime, 24)])).astype(np.int32)
     ref = orc.gram_rows_dense(o.x, cand, rows)
     _assert_close(G[rows], ref, DOT_RTOL, 1e-6, "gram rows")
