@@ -400,7 +400,9 @@ __global__ __launch_bounds__(1024) void k_finalize(RoundScalars *__restrict__ sc
 
     // D. leave the histograms and per-round scalars clean for the next round
     for (uint32_t i = tid; i < 2u * kHistBins; i += 1024u) hist[i] = 0;
-    if (tid == 0) { sc->n_sel = 0; sc->n_bnd = 0; sc->near_rho_pairs = 0; sc->next_round += shards; }
+    // (gram_next: the 256-wide tile kernel's queue position; the kernel that adds its tile slots resets it as
+    // well, this covers a round that was cut short between the two)
+    if (tid == 0) { sc->n_sel = 0; sc->n_bnd = 0; sc->near_rho_pairs = 0; sc->gram_next = 0u; sc->next_round += shards; }
 }
 
 // Draw order for lists longer than 1024 items, in two kernels.  (1) every workgroup sorts one
