@@ -268,6 +268,28 @@ def test_gram_of_a_long_list_takes_the_256_wide_route_and_matches_oracle_rows(n,
     assert np.array_equal(_np(lr["kept_pos"]), orc.greedy_filter(G, o.rho, o.p_max))
 
 
+def test_rounds_with_256_wide_tiles_repeat_bit_for_bit():
+    """Which workgroup takes which item of the tile queue differs from launch to launch; the results must not.
+    Two handles run the same 25 rounds with the 256-wide tiles (forced onto a list of 1500, so that the queue has
+    several items per tile): every round's Gram and the final state are bit-identical, and the objective
+    follows the 128-wide kernel's within the parity tolerance."""
+    p = si.make("c5_dense_duplicates", n=6000, j=4000, nnz=20, l_prime=1500)
+    (a, _), (b, _), (c, _) = _pair(p), _pair(p), _pair(p)
+    a.set_tuning("gram_tile256", 2)
+    b.set_tuning("gram_tile256", 2)
+    assert a.gram_tile_edge() == b.gram_tile_edge() == 256 and c.gram_tile_edge() == 128
+    for t in range(25):
+        a.round(); b.round(); c.round()
+        if t % 6 == 0:
+            ga, gb = a.last_round(want_gram=True), b.last_round(want_gram=True)
+            assert torch.equal(ga["cand"], gb["cand"]) and torch.equal(ga["G"], gb["G"]), t
+            assert torch.equal(ga["kept_pos"], gb["kept_pos"])
+    for u, v in zip(a.get_state()[:3], b.get_state()[:3]):
+        assert torch.equal(u, v)
+    assert a.objective() == b.objective()
+    assert a.objective() == pytest.approx(c.objective(), rel=1e-4)
+
+
 @pytest.mark.parametrize("L", [1, 2, 63, 64, 65, 200, 1000, 2500, 4100, 8192])
 def test_filter_is_bit_exact_on_given_gram(L):
     p = si.make("c1_dense_iid", n=8, j=max(L, 2), nnz=1, l_prime=L)
