@@ -511,7 +511,7 @@ __device__ __forceinline__ void gram_tile_diag(const float *__restrict__ X, int6
 //
 // A tile on the diagonal stages its 256 columns once and multiplies only the 36 of its 64 32 x 32 blocks on or
 // above the diagonal, dealt out to the wavefronts so that no SIMD gets more than 10 (an off-diagonal tile: 16);
-// the stream counts a stage of a diagonal tile as 10/16 of a stage accordingly.  Blocks above the diagonal
+// the queue's item sizes count a stage of a diagonal tile as 10/16 of a stage accordingly.  Blocks above the diagonal
 // of a 128 x 128 diagonal square are also stored mirrored, as the mask kernel expects that square complete.
 constexpr int kBigTile = 256;
 constexpr int32_t kJobBlock = 8;                        // tiles per side of a block of jobs that share panels in one L2
