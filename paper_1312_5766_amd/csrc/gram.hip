@@ -840,11 +840,10 @@ __device__ __forceinline__ uint64_t spread_every_4th(uint64_t x)
     return x;
 }
 
-// Sum the K-slices in slice order and emit the conflict bits (and, optionally, the fp32 Gram) for one
-// wavefront's share: 256 columns b0 .. b0+255 of row a.  A thread owns 4 consecutive columns (16-byte loads of
-// every slice), the wavefront's four 64-bit mask words are assembled from one ballot per column-in-thread;
-// only columns in the tiles at or right of a's diagonal tile exist.  slots256 != NULL: the tiles were written
-// by k_gram_tiles256 into tile slots; first slot and slot count per tile are looked up there.
+// Conflict bits (and, optionally, the fp32 Gram) from the tile slots the 256-wide tile kernel wrote, for one
+// wavefront's share: 256 columns b0 .. b0+255 of row a, i.e. one row of one tile; a thread owns 4 consecutive
+// columns and the wavefront's four 64-bit mask words are assembled from one ballot per column-in-thread.  First slot and slot count of the tile are looked up in
+// slots256 ([T2 * T2] first slots, then [T2 * T2] counts); up to sixteen slots are in flight per thread.
 __device__ __forceinline__ void mask_segment(const float *__restrict__ P, const GramShape &g, float rho,
                                              uint64_t *__restrict__ mask, float *__restrict__ gram,
                                              int32_t *__restrict__ near_pairs, const int32_t *__restrict__ slots256,
@@ -858,18 +857,13 @@ __device__ __forceinline__ void mask_segment(const float *__restrict__ P, const 
     const bool have = b >= first && b < Lpad;
     float v[4] = {0.f, 0.f, 0.f, 0.f};
     if (have) {
-        int32_t split = b < first + kGramTile ? g.split_diag : g.split_off;
-        const float *p = P + (int64_t)a * Lpad + b;
-        int64_t plane = (int64_t)Lpad * Lpad;
-        if (slots256) {
-            // 256-wide tiles: the items of tile (a / 256, b / 256) lie in consecutive tile slots
-            const int32_t tile = (a / kBigTile) * T2 + b / kBigTile;
-            split = slots256[T2 * T2 + tile];
-            p = P + (int64_t)slots256[tile] * kBigSlot + (a % kBigTile) * kBigTile + b % kBigTile;
-            plane = kBigSlot;
-        }
+        // the items of tile (a / 256, b / 256) lie in consecutive tile slots
+        const int32_t tile = (a / kBigTile) * T2 + b / kBigTile;
+        const int32_t split = slots256[T2 * T2 + tile];
+        const float *p = P + (int64_t)slots256[tile] * kBigSlot + (a % kBigTile) * kBigTile + b % kBigTile;
+        constexpr int64_t plane = kBigSlot;
         int32_t s = 0;
-        for (; s + 15 < split; s += 16) {                   // sixteen slices in flight, added in slice order
+        for (; s + 15 < split; s += 16) {                   // sixteen slots in flight, added in slot order
             float4 q[16];
 #pragma unroll
             for (int u = 0; u < 16; ++u) q[u] = *reinterpret_cast<const float4 *>(p + (s + u) * plane);
@@ -916,7 +910,10 @@ __device__ __forceinline__ void mask_segment(const float *__restrict__ P, const 
     }
 }
 
-// K-slice planes (128-wide tiles): a workgroup takes 1024 columns of one row.  gdev != NULL: the shape is read
+// Sum the K-slices in slice order and emit the conflict bits (and, optionally, the fp32 Gram).
+// A thread owns 4 consecutive columns b of one row a (16-byte loads of every slice), a wavefront
+// 256 columns = four 64-bit mask words, assembled from one ballot per column-in-thread; only
+// columns in the tiles at or right of a's diagonal tile exist.  gdev != NULL: the shape is read
 // from device memory (dynamic dependencies) and the grid strides over it.
 __global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, GramShape gh,
                                                    const GramShape *__restrict__ gdev, float rho,
@@ -924,15 +921,67 @@ __global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, 
                                                    int32_t *__restrict__ near_pairs)
 {
     const GramShape g = gdev ? *gdev : gh;
+    const int32_t L = g.L, Lpad = g.Lpad;
+    const int64_t plane = (int64_t)Lpad * Lpad;
     const int lane = threadIdx.x & 63;
-    for (int32_t a = blockIdx.y; a < g.Lpad; a += gridDim.y)
-        for (int32_t b0 = (blockIdx.x * 256 + (threadIdx.x & ~63)) * 4; b0 < g.Lpad; b0 += gridDim.x * 1024)
-            mask_segment(P, g, rho, mask, gram, near_pairs, nullptr, 0, a, b0, lane);
+    for (int32_t a = blockIdx.y; a < Lpad; a += gridDim.y) {
+        const int32_t first = (a / kGramTile) * kGramTile;  // first column of a's diagonal tile
+        for (int32_t b0 = (blockIdx.x * 256 + (threadIdx.x & ~63)) * 4; b0 < Lpad; b0 += gridDim.x * 1024) {
+            // b0: first column of this wavefront's 256; Lpad is a multiple of 128, so a wavefront is
+            // either fully inside or half inside (its first 128 columns)
+            if (b0 + 256 <= first) continue;                // uniform per wavefront
+            const int32_t b = b0 + 4 * lane;
+            const bool have = b >= first && b < Lpad;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (have) {
+                const int32_t split = b < first + kGramTile ? g.split_diag : g.split_off;
+                const float *p = P + (int64_t)a * Lpad + b;
+                int32_t s = 0;
+                for (; s + 7 < split; s += 8) {             // eight slices in flight, added in slice order
+                    float4 q[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) q[u] = *reinterpret_cast<const float4 *>(p + (s + u) * plane);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) { v[0] += q[u].x; v[1] += q[u].y; v[2] += q[u].z; v[3] += q[u].w; }
+                }
+                for (; s < split; ++s) {
+                    const float4 q = *reinterpret_cast<const float4 *>(p + s * plane);
+                    v[0] += q.x; v[1] += q.y; v[2] += q.z; v[3] += q.w;
+                }
+            }
+            uint64_t B[4];
+            uint32_t n_near = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bool live = have && a < L && b + c < L && a != b + c;
+                const float ag = fabsf(v[c]);
+                B[c] = __ballot(live && !(ag < rho));
+                if (near_pairs) n_near += (uint32_t)__popcll(__ballot(live && b + c > a && fabsf(ag - rho) <= 1e-6f));
+            }
+            if (lane < 4) {
+                const int32_t wb = b0 + 64 * lane;          // first column of mask word `lane` of this wavefront
+                if (wb >= first && wb < Lpad) {
+                    uint64_t w = 0;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) w |= spread_every_4th((B[c] >> (16 * lane)) & 0xFFFFull) << c;
+                    mask[(int64_t)a * (Lpad / 64) + (wb >> 6)] = w;
+                }
+            }
+            if (near_pairs && n_near && lane == 0) atomicAdd(near_pairs, (int32_t)n_near);
+            if (gram && have) {
+                *reinterpret_cast<float4 *>(gram + (int64_t)a * Lpad + b) = make_float4(v[0], v[1], v[2], v[3]);
+                if (b >= first + kGramTile) {               // mirror the tiles right of the diagonal
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) gram[(int64_t)(b + c) * Lpad + a] = v[c];
+                }
+            }
+        }
+    }
 }
 
 // Tile slots (256-wide tiles): a workgroup takes four consecutive rows of one tile, which are 4 KB in a row in
 // every slot of the tile.  It also puts the tile kernel's queue position back to zero for the next round.
-__global__ __launch_bounds__(256) void k_gram_mask256(const float *__restrict__ P, GramShape g, float rho,
+__global__ __launch_bounds__(256, 8) void k_gram_mask256(const float *__restrict__ P, GramShape g, float rho,
                                                       uint64_t *__restrict__ mask, float *__restrict__ gram,
                                                       int32_t *__restrict__ near_pairs,
                                                       const int32_t *__restrict__ slots256, int32_t T2,
