@@ -557,8 +557,8 @@ __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" :
 // late for the barrier).
 template <bool DIAG, uint32_t BOTH, uint32_t RIGHT, int LATE = 0>
 __device__ __forceinline__ void gram_piece256(const float *__restrict__ X, int64_t N,
-                                                  const int32_t *__restrict__ cand, int32_t L, int32_t Lpad,
-                                                  const BigPiece pc, int ra, int cb, float *__restrict__ P, float *smem)
+                                              const int32_t *__restrict__ cand, int32_t L, int32_t Lpad,
+                                              const BigPiece pc, int ra, int cb, float *__restrict__ P, float *smem)
 {
     constexpr int NPAN = DIAG ? 1 : 2;
     constexpr int NLD = NPAN * kBigPasses;
