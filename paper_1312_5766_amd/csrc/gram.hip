@@ -814,19 +814,27 @@ __global__ __launch_bounds__(256, kGramOcc) void k_gram_tiles(const float *__res
 
 // Dynamic dependencies: the Gram of the movers only.  Their number is known on the device alone,
 // so the launch has a fixed number of resident workgroups, which read the decomposition the mover
-// kernel chose and share its jobs round-robin.
+// kernel chose.  Each takes the job with its own number first; when there are more jobs than workgroups the
+// rest are taken in order from a counter (`next`, zeroed by the mover kernel), because the XCDs of a chip do
+// not run at the same speed and equal shares would wait for the slowest.
 template <int LOAD>
 __global__ __launch_bounds__(256, kGramOcc) void k_gram_tiles_dyn(const float *__restrict__ X, int64_t N,
                                                            const int32_t *__restrict__ mcand,
                                                            const GramShape *__restrict__ gdev, GenoCols gc,
-                                                           float *__restrict__ P)
+                                                           float *__restrict__ P, uint32_t *__restrict__ next)
 {
     extern __shared__ __align__(16) float smem[];
+    __shared__ uint32_t taken;
     const GramShape g = *gdev;
     const int32_t total = g.T * (g.T - 1) / 2 * g.split_off + g.T * g.split_diag;
-    for (int32_t job = blockIdx.x; job < total; job += gridDim.x) {
+    int32_t job = blockIdx.x;
+    while (job < total) {
         gram_job<LOAD>(X, N, mcand, g, gc, job, P, smem);
-        __syncthreads();                        // the next job reuses the LDS panels
+        if (total <= (int32_t)gridDim.x) break; // every job had a workgroup of its own
+        if (threadIdx.x == 0) taken = atomicAdd(next, 1u);
+        __syncthreads();                        // also: the next job reuses the LDS panels
+        job = (int32_t)gridDim.x + (int32_t)taken;
+        __syncthreads();                        // `taken` is written again after the next job
     }
 }
 
@@ -1288,6 +1296,7 @@ __global__ __launch_bounds__(1024) void k_movers(const float *__restrict__ dc, c
         }
         g.L = (int32_t)base;
         sc->n_movers = (int32_t)base;
+        sc->gram_next = 0u;                     // the mover Gram's job counter (k_gram_tiles_dyn)
         *gout = g;
     }
 }
@@ -1369,7 +1378,7 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
     gc.words = geno_words(h->cfg.n);
     if (dynamic) {
         const int32_t *mcand = h->at<int32_t>(h->ws.mcand);
-#define STRADS_GRAM_DYN(LD) hipLaunchKernelGGL(k_gram_tiles_dyn<LD>, dim3(kGramSlots), dim3(256), lds, h->stream, h->cfg.x, h->cfg.n, mcand, gdev, gc, P)
+#define STRADS_GRAM_DYN(LD) hipLaunchKernelGGL(k_gram_tiles_dyn<LD>, dim3(kGramSlots), dim3(256), lds, h->stream, h->cfg.x, h->cfg.n, mcand, gdev, gc, P, &sc->gram_next)
         if (load == kLoadGeno2) STRADS_GRAM_DYN(kLoadGeno2);
         else if (load == kLoadVec4) STRADS_GRAM_DYN(kLoadVec4);
         else STRADS_GRAM_DYN(kLoadScalar);
