@@ -744,7 +744,12 @@ hipError_t launch_kkt_dense(strads_lasso *h, float *g_or_null)
         return launch_status(h->stream);
     }
     int64_t gk = wide ? h->cfg.j : (h->cfg.j + 3) / 4;
-    if (gk > 256 * 16) gk = 256 * 16;           // persistent: a few workgroups per compute unit
+    // Long columns: about 16 columns per workgroup, dispatched as compute units become free (32 workgroups' worth
+    // of columns per resident workgroup: the XCDs of a chip do not work through them at the same speed, and with
+    // two workgroups per slot, 244 columns each, the pass took 2 % longer).  Short columns: a few workgroups per
+    // compute unit, each striding over the columns.
+    const int64_t cap = wide ? 256 * 256 : 256 * 16;
+    if (gk > cap) gk = cap;
     const unsigned grid = (unsigned)gk;
 #define STRADS_KKT(TPC, V) hipLaunchKernelGGL((k_kkt<TPC, V>), dim3(grid), dim3(256), 0, h->stream, h->cfg.x, h->cfg.n, h->cfg.j, dots_vector(h), h->at<float>(h->ws.beta), h->cfg.lambda, g_or_null, sc)
     if (wide) { if (h->vec4) STRADS_KKT(256, true); else STRADS_KKT(256, false); }
