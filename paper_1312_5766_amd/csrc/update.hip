@@ -335,7 +335,13 @@ __global__ __launch_bounds__(1024) void k_residual_rows(const float *__restrict_
     __shared__ float4 red[16][64];
     __shared__ float wmax[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t i = ((int64_t)blockIdx.x * 64 + lane) * 4;        // N is a multiple of 4 here
+    // Workgroup b runs on XCD b mod 8 and each XCD has its own L2.  A column's 1024-byte piece of one row
+    // block does not start on a 128-byte line whenever 4 N is not a multiple of 128, so neighbouring row
+    // blocks share a line of every such column: each XCD takes consecutive row blocks, and the shared line
+    // comes from memory once per XCD instead of once per block.
+    const uint32_t xcd = blockIdx.x & 7u, per = res_blocks >> 3, rem = res_blocks & 7u;
+    const uint32_t blk = xcd * per + (xcd < rem ? xcd : rem) + (blockIdx.x >> 3);
+    const int64_t i = ((int64_t)blk * 64 + lane) * 4;               // N is a multiple of 4 here
     // everything this thread will want of the kept list whatever its length turns out to be (entries
     // tid, tid + 1024, ... of the lpad-entry lists) and its rows of r are requested at once, before the
     // count is known: one trip to memory instead of one per 1024 entries
