@@ -848,76 +848,6 @@ __device__ __forceinline__ uint64_t spread_every_4th(uint64_t x)
     return x;
 }
 
-// Conflict bits (and, optionally, the fp32 Gram) from the tile slots the 256-wide tile kernel wrote, for one
-// wavefront's share: 256 columns b0 .. b0+255 of row a, i.e. one row of one tile; a thread owns 4 consecutive
-// columns and the wavefront's four 64-bit mask words are assembled from one ballot per column-in-thread.  First slot and slot count of the tile are looked up in
-// slots256 ([T2 * T2] first slots, then [T2 * T2] counts); up to sixteen slots are in flight per thread.
-__device__ __forceinline__ void mask_segment(const float *__restrict__ P, const GramShape &g, float rho,
-                                             uint64_t *__restrict__ mask, float *__restrict__ gram,
-                                             int32_t *__restrict__ near_pairs, const int32_t *__restrict__ slots256,
-                                             int32_t T2, int32_t a, int32_t b0, int lane)
-{
-    const int32_t L = g.L, Lpad = g.Lpad;
-    const int32_t first = (a / kGramTile) * kGramTile;      // first column of a's diagonal tile
-    // Lpad is a multiple of 128, so a wavefront is either fully inside or half inside (its first 128 columns)
-    if (b0 + 256 <= first) return;                          // uniform per wavefront
-    const int32_t b = b0 + 4 * lane;
-    const bool have = b >= first && b < Lpad;
-    float v[4] = {0.f, 0.f, 0.f, 0.f};
-    if (have) {
-        // the items of tile (a / 256, b / 256) lie in consecutive tile slots
-        const int32_t tile = (a / kBigTile) * T2 + b / kBigTile;
-        const int32_t split = slots256[T2 * T2 + tile];
-        const float *p = P + (int64_t)slots256[tile] * kBigSlot + (a % kBigTile) * kBigTile + b % kBigTile;
-        constexpr int64_t plane = kBigSlot;
-        int32_t s = 0;
-        for (; s + 15 < split; s += 16) {                   // sixteen slots in flight, added in slot order
-            float4 q[16];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) q[u] = *reinterpret_cast<const float4 *>(p + (s + u) * plane);
-#pragma unroll
-            for (int u = 0; u < 16; ++u) { v[0] += q[u].x; v[1] += q[u].y; v[2] += q[u].z; v[3] += q[u].w; }
-        }
-        for (; s + 7 < split; s += 8) {                     // eight
-            float4 q[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) q[u] = *reinterpret_cast<const float4 *>(p + (s + u) * plane);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) { v[0] += q[u].x; v[1] += q[u].y; v[2] += q[u].z; v[3] += q[u].w; }
-        }
-        for (; s < split; ++s) {
-            const float4 q = *reinterpret_cast<const float4 *>(p + s * plane);
-            v[0] += q.x; v[1] += q.y; v[2] += q.z; v[3] += q.w;
-        }
-    }
-    uint64_t B[4];
-    uint32_t n_near = 0;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const bool live = have && a < L && b + c < L && a != b + c;
-        const float ag = fabsf(v[c]);
-        B[c] = __ballot(live && !(ag < rho));
-        if (near_pairs) n_near += (uint32_t)__popcll(__ballot(live && b + c > a && fabsf(ag - rho) <= 1e-6f));
-    }
-    if (lane < 4) {
-        const int32_t wb = b0 + 64 * lane;                  // first column of mask word `lane` of this wavefront
-        if (wb >= first && wb < Lpad) {
-            uint64_t w = 0;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) w |= spread_every_4th((B[c] >> (16 * lane)) & 0xFFFFull) << c;
-            mask[(int64_t)a * (Lpad / 64) + (wb >> 6)] = w;
-        }
-    }
-    if (near_pairs && n_near && lane == 0) atomicAdd(near_pairs, (int32_t)n_near);
-    if (gram && have) {
-        *reinterpret_cast<float4 *>(gram + (int64_t)a * Lpad + b) = make_float4(v[0], v[1], v[2], v[3]);
-        if (b >= first + kGramTile) {                       // mirror the tiles right of the diagonal
-#pragma unroll
-            for (int c = 0; c < 4; ++c) gram[(int64_t)(b + c) * Lpad + a] = v[c];
-        }
-    }
-}
-
 // Sum the K-slices in slice order and emit the conflict bits (and, optionally, the fp32 Gram).
 // A thread owns 4 consecutive columns b of one row a (16-byte loads of every slice), a wavefront
 // 256 columns = four 64-bit mask words, assembled from one ballot per column-in-thread; only
@@ -987,19 +917,103 @@ __global__ __launch_bounds__(256) void k_gram_mask(const float *__restrict__ P, 
     }
 }
 
-// Tile slots (256-wide tiles): a workgroup takes four consecutive rows of one tile, which are 4 KB in a row in
-// every slot of the tile.  It also puts the tile kernel's queue position back to zero for the next round.
-__global__ __launch_bounds__(256, 8) void k_gram_mask256(const float *__restrict__ P, GramShape g, float rho,
+// Rows per wavefront of k_gram_mask256 (measured at 8000 candidates, 470 MB of tile slots: 2 rows 80 us, 4 rows
+// 86 us, 8 rows 106 us; one row per wavefront, with workgroups for the tiles left of the diagonal too, 212 us).
+constexpr int kMaskRows = 2;
+constexpr int kMaskGroups = kBigTile / (4 * kMaskRows);     // workgroups per tile
+
+// Conflict bits (and, optionally, the fp32 Gram) from the tile slots the 256-wide tile kernel wrote.  A
+// workgroup takes 4 * kMaskRows consecutive rows of one tile on or right of the diagonal (they are consecutive
+// in every slot of the tile), a wavefront kMaskRows of them, a thread 4 consecutive columns of each; the
+// slots are added in slot order, those of four slots and all the wavefront's rows in flight at once, and a row's
+// four 64-bit mask words are assembled from one ballot per column-in-thread.  First slot and slot count of a
+// tile are looked up in slots256 ([T2 * T2] first slots, then [T2 * T2] counts).  The kernel also puts the tile
+// kernel's queue position back to zero for the next round, and marks the chunks of 64 rows that have a conflict
+// bit in a word the greedy walk's row holders use (chunk_nz, see k_filter).
+__global__ __launch_bounds__(256) void k_gram_mask256(const float *__restrict__ P, GramShape g, float rho,
                                                       uint64_t *__restrict__ mask, float *__restrict__ gram,
                                                       int32_t *__restrict__ near_pairs,
                                                       const int32_t *__restrict__ slots256, int32_t T2,
-                                                      uint32_t *__restrict__ queue_next)
+                                                      uint32_t *__restrict__ queue_next, uint32_t *__restrict__ chunk_nz)
 {
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *queue_next = 0u;
-    // last rows first: the tiles at the end of the queue are the ones cut into the most items
-    const int32_t a = (int32_t)(gridDim.y - 1 - blockIdx.y) * 4 + (int32_t)(threadIdx.x >> 6);
-    if (a >= g.Lpad) return;                                // whole wavefronts
-    mask_segment(P, g, rho, mask, gram, near_pairs, slots256, T2, a, (int32_t)blockIdx.x * kBigTile, threadIdx.x & 63);
+    constexpr int R = kMaskRows;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *queue_next = 0u;
+    // last tile row first (the tiles at the end of the queue are the ones cut into the most items): tile row
+    // T2 - 1 has one tile on or right of the diagonal, tile row tr has T2 - tr
+    int32_t u = (int32_t)blockIdx.x / kMaskGroups, tr = T2 - 1;
+    for (int32_t n = 1; u >= n; ++n) { u -= n; --tr; }      // uniform
+    const int32_t tc = tr + u;
+    const int lane = threadIdx.x & 63;
+    const int32_t a0 = tr * kBigTile + (((int32_t)blockIdx.x % kMaskGroups) * 4 + (int32_t)(threadIdx.x >> 6)) * R;
+    const int32_t L = g.L, Lpad = g.Lpad;
+    if (a0 >= Lpad) return;                                 // whole wavefronts: R divides 128, and so does Lpad's step
+    const int32_t first = (a0 / kGramTile) * kGramTile;     // first column of these rows' 128-wide diagonal tile
+    const int32_t b0 = tc * kBigTile, b = b0 + 4 * lane;
+    const bool have = b >= first && b < Lpad;
+    float4 v[R];
+#pragma unroll
+    for (int i = 0; i < R; ++i) v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (have) {
+        const int32_t tile = tr * T2 + tc;
+        const int32_t split = slots256[T2 * T2 + tile];
+        const float *p = P + (int64_t)slots256[tile] * kBigSlot + (a0 % kBigTile) * kBigTile + 4 * lane;
+        constexpr int64_t plane = kBigSlot;
+        int32_t s = 0;
+        for (; s + 3 < split; s += 4) {
+            float4 q[4][R];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int i = 0; i < R; ++i)
+                    q[t][i] = *reinterpret_cast<const float4 *>(p + (s + t) * plane + i * kBigTile);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int i = 0; i < R; ++i) {
+                    v[i].x += q[t][i].x; v[i].y += q[t][i].y; v[i].z += q[t][i].z; v[i].w += q[t][i].w;
+                }
+        }
+        for (; s < split; ++s) {
+            float4 q[R];
+#pragma unroll
+            for (int i = 0; i < R; ++i) q[i] = *reinterpret_cast<const float4 *>(p + s * plane + i * kBigTile);
+#pragma unroll
+            for (int i = 0; i < R; ++i) { v[i].x += q[i].x; v[i].y += q[i].y; v[i].z += q[i].z; v[i].w += q[i].w; }
+        }
+    }
+    uint32_t n_near = 0;
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const int32_t a = a0 + i;
+        const float vc[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+        uint64_t B[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const bool live = have && a < L && b + c < L && a != b + c;
+            const float ag = fabsf(vc[c]);
+            B[c] = __ballot(live && !(ag < rho));
+            if (near_pairs) n_near += (uint32_t)__popcll(__ballot(live && b + c > a && fabsf(ag - rho) <= 1e-6f));
+        }
+        if (lane < 4) {
+            const int32_t wb = b0 + 64 * lane;              // first column of mask word `lane` of this row
+            if (wb >= first && wb < Lpad) {
+                uint64_t w = 0;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) w |= spread_every_4th((B[c] >> (16 * lane)) & 0xFFFFull) << c;
+                mask[(int64_t)a * (Lpad / 64) + (wb >> 6)] = w;
+                // a word that the greedy walk's row holders use (see k_filter): mark the row's chunk of 64
+                if (w != 0 && (wb >> 6) >= (a >> 6) + 2) chunk_nz[a >> 6] = 1u;
+            }
+        }
+        if (gram && have) {
+            *reinterpret_cast<float4 *>(gram + (int64_t)a * Lpad + b) = v[i];
+            if (b >= first + kGramTile) {                   // mirror the tiles right of the diagonal
+#pragma unroll
+                for (int c = 0; c < 4; ++c) gram[(int64_t)(b + c) * Lpad + a] = vc[c];
+            }
+        }
+    }
+    if (near_pairs && n_near && lane == 0) atomicAdd(near_pairs, (int32_t)n_near);
 }
 
 // Conflict bits from a caller-supplied full Gram (stage entry for parity tests).
@@ -1353,9 +1367,9 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
         float *gram = h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr;
         if (big) {
             const int32_t T2 = (h->Lpad + kBigTile - 1) / kBigTile;
-            hipLaunchKernelGGL(k_gram_mask256, dim3((unsigned)T2, (unsigned)(h->Lpad + 3) / 4), dim3(256), 0, h->stream, P, g,
+            hipLaunchKernelGGL(k_gram_mask256, dim3((unsigned)(T2 * (T2 + 1) / 2 * kMaskGroups)), dim3(256), 0, h->stream, P, g,
                                h->cfg.rho, h->at<uint64_t>(h->ws.mask), gram, &sc->near_rho_pairs,
-                               reinterpret_cast<const int32_t *>(items + h->big_items), T2, &sc->gram_next);
+                               reinterpret_cast<const int32_t *>(items + h->big_items), T2, &sc->gram_next, sc->chunk_nz);
             return launch_status(h->stream);
         }
         dim3 grid((h->Lpad + 1023) / 1024, h->Lpad);       // 1024 columns of one row per workgroup
