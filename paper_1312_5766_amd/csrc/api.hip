@@ -360,7 +360,7 @@ static int enqueue_round(strads_lasso *top, bool more_follows)
     MARK(STRADS_STAGE_FILTER);
     if (unchecked) HIP_TRY(launch_keep_all(h));
     else if (dynamic) HIP_TRY(launch_filter_movers(h));
-    else HIP_TRY(launch_filter(h, h->L, true, ride));
+    else HIP_TRY(launch_filter(h, h->L, true, ride, !csc && h->big_items > 0));   // (the 256-wide tiles' mask kernel marks chunks)
     MARK(STRADS_STAGE_UPDATE);
     if (!dynamic) AFTER_PREVIOUS_ROUND();
     if (!dynamic && !ride && h->cfg.loss == STRADS_LOSS_LOGISTIC) HIP_TRY(launch_logistic_weights(h));
@@ -700,7 +700,7 @@ int strads_lasso_stage_filter(strads_lasso_t *h, const float *gram, int32_t l, i
 {
     if (!h || !gram || !kept_pos || !n_kept || l < 1 || l > h->L) return STRADS_E_INVALID_ARG;
     HIP_TRY(launch_mask_from_gram(h, gram, l));
-    HIP_TRY(launch_filter(h, l, false, false));
+    HIP_TRY(launch_filter(h, l, false, false, false));
     RoundScalars sc;
     const int rs = read_scalars(h, &sc);
     if (rs != STRADS_OK) return rs;

@@ -184,7 +184,13 @@ __device__ __forceinline__ void commit_dynamic(const CommitArgs &cm, int32_t p_m
 // a memory round trip into every chunk.  Nothing is stored to global memory inside the loop for the
 // same reason.  Rows at or past L and words at or right of a row's diagonal word are written by the
 // mask kernel for every row below Lpad; words left of the diagonal are never used.
-template <int IPT, int A, int TPR>
+//
+// FLAGS: the mask kernel has marked the chunks (sc->chunk_nz) any of whose rows has a nonzero word two or more
+// words right of its diagonal word, which are the words the holders use.  The holders neither fetch nor look at
+// the rows of an unmarked chunk: with few conflicts (a long list drawn from nearly orthogonal columns) the walk
+// is otherwise bound by one compute unit reading the whole mask, 8 MB for 8000 candidates.  The marks are read
+// once at the start, and cleared for the next round at the end.
+template <int IPT, int A, int TPR, bool FLAGS>
 __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__restrict__ mask, int32_t L, int32_t W,
                                                            const GramShape *__restrict__ gdev,
                                                            int32_t p_max, const int32_t *__restrict__ cand,
@@ -230,7 +236,12 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
     const int64_t chunk_stride = (int64_t)64 * W; // words from a chunk's rows to the next chunk's
     const int32_t c_max = W - 1;                  // chunk index up to which a chunk's rows lie inside the mask (chunks <= W)
 
-    for (int i = tid; i < W; i += kThreads) dead[i] = 0;
+    __shared__ uint8_t nzc[FLAGS ? kMaxWords : 1];  // [c]: the holders have something to do for chunk c
+    for (int i = tid; i < W; i += kThreads) {
+        dead[i] = 0;
+        // (the first A chunks are fetched before the marks have arrived)
+        if constexpr (FLAGS) nzc[i] = (i < A || sc->chunk_nz[i] != 0u) ? 1 : 0;
+    }
     if (tid == 0) nkb[0] = 0;
     __syncthreads();
 
@@ -317,13 +328,26 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
         int32_t wq[IPT];                          // j + TPR q, clamped into the row
 #pragma unroll
         for (int q = 0; q < IPT; ++q) wq[q] = j + TPR * q < W ? j + TPR * q : W - 1;
-        auto fetch = [&](uint64_t (&dst)[IPT]) {
+        auto fetch = [&](uint64_t (&dst)[IPT], bool on) {
+            if (on) {                           // (uniform; always true without FLAGS)
 #pragma unroll
-            for (int q = 0; q < IPT; ++q) dst[q] = rowp[wq[q]];
+                for (int q = 0; q < IPT; ++q) {
+                    if constexpr (FLAGS) {      // (the clamped word index computed here: registers are short)
+                        const int32_t w = j + TPR * q;
+                        dst[q] = rowp[w < W ? w : W - 1];
+                    } else {
+                        dst[q] = rowp[wq[q]];
+                    }
+                }
+            }
             if (c_next < c_max) { rowp += chunk_stride; ++c_next; }
         };
+        auto marked = [&](int32_t c) -> bool {    // uniform
+            if constexpr (FLAGS) return c < chunks && __builtin_amdgcn_readfirstlane((int)nzc[c]) != 0;
+            return true;
+        };
 #pragma unroll
-        for (int d = 0; d < A; ++d) fetch(pre[d]);
+        for (int d = 0; d < A; ++d) fetch(pre[d], true);
         for (int32_t c0 = 0; c0 < chunks; c0 += A) {
             bool stop = false;
 #pragma unroll
@@ -334,7 +358,7 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
                     // the rows kept in chunk c-1 -> dead[w], w > c
                     uint64_t (&prev)[IPT] = pre[(d + A - 1) % A];
                     const uint64_t keptw = keptw_all[c - 1];
-                    if ((((uint32_t)keptw & row_lo) | ((uint32_t)(keptw >> 32) & row_hi)) != 0u) {
+                    if ((((uint32_t)keptw & row_lo) | ((uint32_t)(keptw >> 32) & row_hi)) != 0u && marked(c - 1)) {
 #pragma unroll
                         for (int q = 0; q < IPT; ++q) {
                             const int32_t w = j + TPR * q;
@@ -343,7 +367,7 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
                                 atomicOr((unsigned long long *)&dead[w], (unsigned long long)v);
                         }
                     }
-                    fetch(prev);                  // chunk c-1 is done with its registers: they take chunk c-1+A
+                    fetch(prev, marked(c - 1 + A));   // chunk c-1 is done with its registers: they take chunk c-1+A
                 }
                 __syncthreads();
                 n_done = c + 1;
@@ -354,6 +378,8 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
     }
     __syncthreads();
     n_done = __builtin_amdgcn_readfirstlane(n_done);
+    if constexpr (FLAGS)
+        for (int i = tid; i < W; i += kThreads) sc->chunk_nz[i] = 0u;
 
     // The kept positions, in order, from the per-chunk words: candidate a is number
     // nkb[a / 64] + (kept candidates of its chunk before it); with them the column ids and, where the
@@ -427,17 +453,18 @@ __global__ __launch_bounds__(64 + 64 * TPR) void k_filter(const uint64_t *__rest
 
 // Launch for row width W (words); with gdev the kernel takes the actual length and width from
 // device memory (they can only be smaller).
+// marked: the mask was written this round by the kernel that marks chunks in sc->chunk_nz (see k_filter).
 static hipError_t launch_filter_kernel(hipStream_t stream, const uint64_t *mask, RoundScalars *sc, int32_t l, int32_t W,
                                        const GramShape *gdev, int32_t p_max,
                                        const int32_t *cand, int32_t *kept_pos, int32_t *kept, int32_t *n_out,
-                                       bool count_updates, const CommitArgs &cm)
+                                       bool count_updates, const CommitArgs &cm, bool marked)
 {
-#define STRADS_FILTER(IPT, A, TPR) hipLaunchKernelGGL((k_filter<IPT, A, TPR>), dim3(1), dim3(64 + 64 * TPR), 0, stream, mask, l, W, gdev, p_max, cand, kept_pos, kept, sc, n_out, count_updates ? 1 : 0, cm)
+#define STRADS_FILTER(IPT, A, TPR, FLAGS) hipLaunchKernelGGL((k_filter<IPT, A, TPR, FLAGS>), dim3(1), dim3(64 + 64 * TPR), 0, stream, mask, l, W, gdev, p_max, cand, kept_pos, kept, sc, n_out, count_updates ? 1 : 0, cm)
     // words of a row per holder thread = ceil(W / threads per row); short rows can afford more chunks in flight
-    if (W <= 16) STRADS_FILTER(4, 8, 4);
-    else if (W <= 32) STRADS_FILTER(4, 6, 8);
-    else if (W <= 64) STRADS_FILTER(8, 4, 8);
-    else STRADS_FILTER(16, 3, 8);
+    if (W <= 16) STRADS_FILTER(4, 8, 4, false);
+    else if (W <= 32) STRADS_FILTER(4, 6, 8, false);
+    else if (W <= 64) { if (marked) STRADS_FILTER(8, 4, 8, true); else STRADS_FILTER(8, 4, 8, false); }
+    else { if (marked) STRADS_FILTER(16, 3, 8, true); else STRADS_FILTER(16, 3, 8, false); }
 #undef STRADS_FILTER
     return launch_status(stream);
 }
@@ -461,13 +488,13 @@ static CommitArgs commit_args(strads_lasso *h, int32_t mode)
     return cm;
 }
 
-hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates, bool commit)
+hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates, bool commit, bool marked)
 {
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
     return launch_filter_kernel(h->stream, h->at<uint64_t>(h->ws.mask), sc, l, h->Lpad / 64, nullptr, h->cfg.p_max,
                                 h->at<int32_t>(h->ws.cand),
                                 h->at<int32_t>(h->ws.kept_pos), h->at<int32_t>(h->ws.kept), &sc->n_kept, count_updates,
-                                commit_args(h, commit ? kCommitKept : 0));
+                                commit_args(h, commit ? kCommitKept : 0), marked);
 }
 
 // Dynamic dependencies: the walk runs over the movers only (their conflict mask has the row
@@ -480,7 +507,7 @@ hipError_t launch_filter_movers(strads_lasso *h)
     return launch_filter_kernel(h->stream, h->at<uint64_t>(h->ws.mask), sc, h->L, h->Lpad / 64,
                                 h->at<GramShape>(h->ws.dshape), h->cfg.p_max,
                                 h->at<int32_t>(h->ws.mcand), h->at<int32_t>(h->ws.mkept_pos),
-                                h->at<int32_t>(h->ws.kept), &sc->n_mkept, false, commit_args(h, kCommitDynamic));
+                                h->at<int32_t>(h->ws.kept), &sc->n_mkept, false, commit_args(h, kCommitDynamic), false);
 }
 
 // The greedy walk alone, on buffers named one by one (no handle): mask holds lpad rows of lpad / 64 words as
@@ -490,7 +517,7 @@ hipError_t launch_filter_plain(hipStream_t stream, const uint64_t *mask, int32_t
 {
     CommitArgs cm;
     memset(&cm, 0, sizeof(cm));
-    return launch_filter_kernel(stream, mask, sc, l, lpad / 64, nullptr, p_max, cand, kept_pos, kept, n_out, false, cm);
+    return launch_filter_kernel(stream, mask, sc, l, lpad / 64, nullptr, p_max, cand, kept_pos, kept, n_out, false, cm, false);
 }
 
 // No dependency check (the Shotgun scheduler of Section 5.1): B_1 is the head of the draw.

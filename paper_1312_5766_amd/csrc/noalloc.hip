@@ -22,8 +22,8 @@ constexpr size_t kOffMask = 0;                                                  
 constexpr size_t kOffIds = kOffMask + (size_t)kStaticMaxL * (kStaticMaxL / 64) * 8;   // int32 [l]: 0, 1, 2, ...
 constexpr size_t kOffKept = kOffIds + (size_t)kStaticMaxL * 4;                        // int32 [l]: ids of the kept ones
 constexpr size_t kOffScalars = kOffKept + (size_t)kStaticMaxL * 4;                    // RoundScalars
-constexpr size_t kScratchBytes = kOffScalars + 256;                                   // 8 MiB + 64 KiB + 256 B
-static_assert(sizeof(RoundScalars) <= 256, "scalars block");
+constexpr size_t kScratchBytes = kOffScalars + 1024;                                  // 8 MiB + 64 KiB + 1 KiB
+static_assert(sizeof(RoundScalars) <= 1024, "scalars block");
 
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 

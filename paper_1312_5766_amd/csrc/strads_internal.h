@@ -46,6 +46,9 @@ struct RoundScalars {
     uint32_t gram_next;    // 256-wide Gram tiles: next item of the kernel's queue (zero between rounds)
     uint32_t overflow;     // CSC designs: a product left the range of the fixed-point accumulators (sticky until
                            // the state is set again); the residual is then written as NaN
+    uint32_t chunk_nz[STRADS_MAX_L_PRIME / 64];    // 256-wide Gram tiles: [c] != 0: a row of candidates 64c .. 64c+63
+                           // has a conflict bit in mask word c + 2 or beyond (set by the mask kernel, cleared by the
+                           // greedy walk; a mark too many costs time only)
 };
 
 // Decomposition of a candidate Gram into workgroup jobs (see gram.hip).  With dynamic
@@ -196,7 +199,7 @@ hipError_t launch_mask_from_gram_plain(hipStream_t stream, const float *gram, in
                                        uint64_t *mask);
 hipError_t launch_filter_plain(hipStream_t stream, const uint64_t *mask, int32_t l, int32_t lpad, int32_t p_max,
                                const int32_t *cand, int32_t *kept_pos, int32_t *kept, RoundScalars *sc, int32_t *n_out);
-hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates, bool commit);       // Step 2b -> kept_pos, kept, n_kept;
+hipError_t launch_filter(strads_lasso *h, int32_t l, bool count_updates, bool commit, bool marked);       // Step 2b -> kept_pos, kept, n_kept;
                                                           // commit: and eq. (2) for B_1 from the candidates' tentative updates
 hipError_t launch_keep_all(strads_lasso *h);              // no dependency check: B_1 = first p_max candidates
 // dynamic dependencies

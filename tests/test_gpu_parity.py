@@ -290,6 +290,26 @@ def test_rounds_with_256_wide_tiles_repeat_bit_for_bit():
     assert a.objective() == pytest.approx(c.objective(), rel=1e-4)
 
 
+@pytest.mark.parametrize("j,l_prime,p_max", [(3000, 2500, 0), (6000, 5000, 0), (6000, 5000, 1800), (8192, 8192, 0)])
+def test_greedy_walk_after_256_wide_tiles_with_many_conflicts(j, l_prime, p_max):
+    """With the 256-wide tiles the mask kernel marks the chunks of 64 candidates whose rows the greedy walk has
+    to read, and the walk skips the others.  Block-correlated columns put conflicts in most chunks (the
+    near-duplicate designs of the other tests in few): the kept set is the oracle's greedy walk on the same
+    Gram, in three rounds in a row (the marks of one round must not leak into the next, nor be missed)."""
+    p = si.make("c2_dense_block_corr", n=260, j=j, nnz=5, l_prime=l_prime)
+    g, o = _pair(p, p_max=p_max)
+    g.set_tuning("gram_tile256", 2)
+    assert g.gram_tile_edge() == 256
+    rejected = 0
+    for _ in range(3):
+        g.round()
+        lr = g.last_round(want_gram=True)
+        G, kept = _np(lr["G"]), _np(lr["kept_pos"])
+        assert np.array_equal(kept, orc.greedy_filter(G, o.rho, o.p_max))
+        rejected += l_prime - len(kept)
+    assert rejected > 0
+
+
 @pytest.mark.parametrize("L", [1, 2, 63, 64, 65, 200, 1000, 2500, 4100, 8192])
 def test_filter_is_bit_exact_on_given_gram(L):
     p = si.make("c1_dense_iid", n=8, j=max(L, 2), nnz=1, l_prime=L)
