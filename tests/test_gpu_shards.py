@@ -58,13 +58,16 @@ def test_one_coordinate_per_shard_is_cyclic_coordinate_descent():
 
 
 @pytest.mark.parametrize("kw", [dict(n_shards=2), dict(n_shards=4), dict(n_shards=3, dynamic=True),
-                                dict(n_shards=2, tile256=True)])
+                                dict(n_shards=2, tile256=True), dict(n_shards=2, tile256=True, shape=(400, 8000, 2600))])
 def test_overlapped_run_equals_serialised_rounds_and_tracks_the_oracle(kw):
     pk = _gpu()
     dev = torch.device("cuda:0")
     kw = dict(kw)
     tile256 = kw.pop("tile256", False)      # the shards' Gram kernels in 256-wide tiles, each with a queue of its own
-    p = si.make("c2_dense_block_corr", n=2000, j=8000, nnz=40, l_prime=500)
+    # (2600 candidates: 41 mask words per row, where the greedy walk skips the chunks of candidates that the
+    # shard's own slot sum has not marked; the marks of overlapping shards must not mix)
+    n, j, l_prime = kw.pop("shape", (2000, 8000, 500))
+    p = si.make("c2_dense_block_corr", n=n, j=j, nnz=40, l_prime=l_prime)
     base = dict(x=p.x.to(dev), y=p.y.to(dev), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
     a, b, c = (pk.StradsLasso(**base, **kw) for _ in range(3))
     if tile256:
