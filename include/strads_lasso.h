@@ -279,6 +279,13 @@ int strads_lasso_filter_static(const float *gram, int32_t l, float rho, int32_t 
  *                   other shape in 128 x 128 tiles with K-slices.  0: always 128 x 128.  2: 256 x 256 wherever
  *                   the design is fp32, aligned and the rule static (STRADS_E_UNSUPPORTED if the workspace
  *                   lacks room for the tile slots).  The routes differ in fp32 summation order only.
+ *   "gram_direct"   1 (default): under Algorithm 1's dependency rule, the Gram of a long list over short columns
+ *                   (at most 1024 rows and at least 1024 candidates, or at most 2048 rows and at least 3072
+ *                   candidates; dense fp32 or packed designs) is multiplied in 64 x 64 tiles that run over all
+ *                   rows and write the conflict bits themselves: no K-slices and no second kernel that sums
+ *                   them.  0: never.  2: for every list of such a design (STRADS_E_UNSUPPORTED where the rule is
+ *                   not Algorithm 1's, the design is sparse, the 256 x 256 tiles are in use or "gram_split_k"
+ *                   is set).  The routes differ in fp32 summation order only.
  *   "dots_with_gram" 1 (default): fp32 dense designs with l_prime <= 4096, Algorithm 1's dependency rule and
  *                   one scheduler take x_j^T r for every candidate in extra workgroups of the Gram
  *                   launch, and the filter's workgroup applies eq. (2) to the kept ones; 0: a kernel
@@ -310,8 +317,8 @@ int strads_lasso_gram256_plan(int64_t n, int32_t l, int32_t items_cap, int32_t *
                               int32_t *first_slot, int32_t *n_slots);
 
 /* Which tile kernel forms Step 2's Gram for this handle as it is tuned now: edge (HOST int32) = 256 (tiles of
- * 256 x 256 from a queue, see "gram_tile256"), 128 (tiles of 128 x 128 with K-slices), or 0 (a sparse design or
- * no dependency check: no tile kernel). */
+ * 256 x 256 from a queue, see "gram_tile256"), 128 (tiles of 128 x 128 with K-slices), 64 (tiles of 64 x 64 over
+ * all rows, see "gram_direct"), or 0 (a sparse design or no dependency check: no tile kernel). */
 int strads_lasso_gram_tile_edge(strads_lasso_t *h, int32_t *edge);
 
 /* Average duration in milliseconds of each stage (HOST array of STRADS_N_STAGES floats) over the

@@ -201,6 +201,7 @@ int strads_lasso_create(const strads_lasso_config_t *cfg, strads_lasso_t **out)
     h->jobtab_on = cfg->layout != STRADS_LAYOUT_CSC && cfg->deps != STRADS_DEPS_DYNAMIC ? 1 : 0;
     h->tile256 = 1;
     h->big_items = 0;
+    h->direct = 1;
     h->select_cap = kSelectCapDefault;
     h->round = 0;
     h->profile_level = 0;
@@ -728,7 +729,7 @@ int strads_lasso_gram_tile_edge(strads_lasso_t *h, int32_t *edge)
 {
     if (!h || !edge) return STRADS_E_INVALID_ARG;
     if (h->cfg.layout == STRADS_LAYOUT_CSC || h->cfg.deps == STRADS_DEPS_NONE) { *edge = 0; return STRADS_OK; }
-    *edge = h->cfg.deps == STRADS_DEPS_STATIC && h->big_items > 0 ? 256 : kGramTile;
+    *edge = h->cfg.deps == STRADS_DEPS_STATIC && h->big_items > 0 ? 256 : (gram_direct_on(h) ? 64 : kGramTile);
     return STRADS_OK;
 }
 
@@ -774,6 +775,13 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value)
         const int rc = choose_gram_route(h);
         if (rc != STRADS_OK) return rc;
         return value == 2 && h->big_items == 0 ? STRADS_E_UNSUPPORTED : STRADS_OK;
+    }
+    if (strcmp(name, "gram_direct") == 0) {
+        if (value < 0 || value > 2) return STRADS_E_INVALID_ARG;
+        HIP_TRY(hipStreamSynchronize(h->stream));
+        drop_graphs(h);
+        for (int32_t s = 0; s < h->n_lanes; ++s) h->lanes[s]->direct = (int32_t)value;
+        return value == 2 && !gram_direct_on(h) ? STRADS_E_UNSUPPORTED : STRADS_OK;
     }
     if (strcmp(name, "dots_with_gram") == 0) {
         if (value < 0 || value > 1) return STRADS_E_INVALID_ARG;

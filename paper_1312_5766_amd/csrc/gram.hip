@@ -812,6 +812,212 @@ __global__ __launch_bounds__(256, kGramOcc) void k_gram_tiles(const float *__res
     gram_job<LOAD>(X, N, cand, g, gc, job, P, smem);
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Short columns under a long candidate list (e.g. 2000 candidates over 500 rows): 64 x 64 tiles over the whole
+// row range, conflict bits straight from the accumulators.
+//
+// With few rows there is little to split along K, and the 128 x 128 tiles of such a list are fewer than the
+// chip's compute units: the K-slices that fill the chip then cost a partial tile per slice and a second kernel
+// that sums them.  Here a workgroup of 4 wavefronts owns a 64 x 64 tile of the upper triangle (diagonal tiles in
+// full) for all N rows, each wavefront one 32 x 32 block in a single MFMA accumulator (consecutive MFMAs into the
+// same accumulator issue back to back), and writes the tile's conflict bits itself: a wavefront ballot over an
+// accumulator register is 32 columns of two rows, i.e. two halves of 64-bit mask words.  The sums run over K
+// in one order, so nothing depends on scheduling here either.  The staging, the operand reads one K step ahead
+// and the place of the stage's barrier are those of the 128 x 128 kernel.
+// (Measured at 2000 candidates over 500 rows, 528 tiles: 37 us, of which 8 us are launch, first fetch and the
+// epilogue; with no loads, LDS traffic or barriers in the loop it is 31 us, because 528 equal workgroups leave some
+// SIMDs three wavefronts to run where most have two.  The tile kernel with K-slices plus the sum of the slices
+// takes 50 us there.)
+constexpr int kDirTile = 64;
+constexpr int kDirPanel = kDirTile * kRow;                      // floats per operand panel per stage
+constexpr int kDirLdsBytes = 2 * 2 * kDirPanel * (int)sizeof(float);
+
+// Staging of the two 64-column panels of a tile, one stage of kGramKT rows at a time (see PanelLoader).
+//   fp32 designs: a thread holds two float4 per panel: column (it * 32 + tid / 8), floats (tid % 8) * 4 .. +3.
+//   packed genotypes: threads 0..127 stage the first panel, the others the second; a thread holds one 32-bit
+//     word (16 rows): column (tid % 128) / 2, rows 16 * (tid % 2) .. +15 of the stage.
+template <int LOAD>
+struct DirectLoader {
+    int64_t kend;
+    const float *col[4];
+    float4 R[4];
+    int crow, kq;
+    const uint32_t *wp;
+    uint32_t W;
+    int valid, gpanel, gcol, ghalf;
+    float mean, scale;
+
+    __device__ __forceinline__ void init(const float *__restrict__ X, int64_t N, const int32_t *__restrict__ cand,
+                                         int32_t L, int32_t ta, int32_t tb, const GenoCols &gc)
+    {
+        kend = N;
+        const int tid = threadIdx.x;
+        if (LOAD == kLoadGeno2) {
+            gpanel = tid >> 7; gcol = (tid & 127) >> 1; ghalf = tid & 1;
+            int i = (gpanel ? tb : ta) * kDirTile + gcol;
+            i = i < L ? i : L - 1;
+            const int64_t j = cand[i];
+            wp = reinterpret_cast<const uint32_t *>(X) + j * gc.words + ghalf;
+            mean = gc.mean[j];
+            scale = gc.scale[j];
+            W = 0u;
+            valid = 0;
+        } else {
+            crow = tid >> 3;
+            kq = (tid & 7) * 4;
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int it = 0; it < 2; ++it) {
+                    int i = (p ? tb : ta) * kDirTile + it * 32 + crow;
+                    i = i < L ? i : L - 1;
+                    col[p * 2 + it] = X + (int64_t)cand[i] * N;
+                }
+        }
+    }
+
+    __device__ __forceinline__ void fetch(int st)
+    {
+        if (LOAD == kLoadGeno2) {
+            const int64_t left = kend - ((int64_t)st * kGramKT + 16 * ghalf);     // rows of this word inside the column
+            valid = left >= 16 ? 16 : (left > 0 ? (int)left : 0);
+            W = valid > 0 ? wp[2 * st] : 0u;
+        } else {
+            const int64_t k = (int64_t)st * kGramKT + kq;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) R[i] = load_k4<LOAD == kLoadVec4>(col[i], k, kend);
+        }
+    }
+
+    __device__ __forceinline__ void stash(float *stage) const
+    {
+        if (LOAD == kLoadGeno2) {
+            float *dst = stage + gpanel * kDirPanel + gcol * kRow + 16 * ghalf;
+            float x[16];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {       // entries q, q+4, q+8, q+12 of a word are the bytes of (word >> 2q) & 0x03030303
+                const uint32_t t = (W >> (2 * q)) & 0x03030303u;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float g = (float)((t >> (8 * c)) & 0xFFu);
+                    const float val = __fmul_rn(__fsub_rn(g, mean), scale);
+                    x[4 * c + q] = 4 * c + q < valid ? val : 0.f;
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float4 *>(dst + 4 * q) = make_float4(x[4 * q], x[4 * q + 1], x[4 * q + 2], x[4 * q + 3]);
+        } else {
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int it = 0; it < 2; ++it)
+                    *reinterpret_cast<float4 *>(stage + p * kDirPanel + (it * 32 + crow) * kRow + kq) = R[p * 2 + it];
+        }
+    }
+};
+
+// Workgroups past n_jobs take the candidates' x_j^T r, as in k_gram_tiles.
+template <int LOAD>
+__global__ __launch_bounds__(256) void k_gram_direct(const float *__restrict__ X, int64_t N,
+                                                     const int32_t *__restrict__ cand, int32_t L, int32_t Lpad,
+                                                     GenoCols gc, float rho, uint64_t *__restrict__ mask,
+                                                     float *__restrict__ gram, int32_t *__restrict__ near_pairs,
+                                                     int32_t n_jobs, CandDots cd)
+{
+    extern __shared__ __align__(16) float smem[];             // [2 stages][A panel | B panel]
+    if ((int32_t)blockIdx.x >= n_jobs) {
+        if constexpr (LOAD != kLoadGeno2) {
+            const int block = (int)blockIdx.x - n_jobs;
+            if (cd.wide) cand_dots_block<256, LOAD == kLoadVec4>(X, N, cand, cd, block, smem);
+            else cand_dots_block<64, LOAD == kLoadVec4>(X, N, cand, cd, block, smem);
+        }
+        return;
+    }
+    // tile (ta, tb), ta <= tb, of the upper triangle in row-major order
+    const int32_t T = Lpad / kDirTile;
+    int32_t u = (int32_t)blockIdx.x, ta = 0;
+    for (int32_t n = T; u >= n; --n) { u -= n; ++ta; }         // uniform
+    const int32_t tb = ta + u;
+    const int tid = threadIdx.x;
+    const int nstage = (int)((N + kGramKT - 1) / kGramKT);
+
+    DirectLoader<LOAD> ld;
+    ld.init(X, N, cand, L, ta, tb, gc);
+
+    const int wave = tid >> 6, lane = tid & 63;
+    const int wr = wave >> 1, wc = wave & 1;    // 32 x 32 block of this wavefront
+    const int li = lane & 31, lh = lane >> 5;
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    const int offa = (wr * 32 + li) * kRow + lh * 4;
+    const int offb = kDirPanel + (wc * 32 + li) * kRow + lh * 4;
+    struct Ops { float4 a, b; };
+    auto read_ops = [&](int buf, int ks) {
+        Ops o;
+        o.a = *reinterpret_cast<const float4 *>(smem + buf * 2 * kDirPanel + offa + ks * 8);
+        o.b = *reinterpret_cast<const float4 *>(smem + buf * 2 * kDirPanel + offb + ks * 8);
+        return o;
+    };
+    auto mma = [&](const Ops &o) {
+        mfma32(acc, o.a.x, o.b.x);
+        mfma32(acc, o.a.y, o.b.y);
+        mfma32(acc, o.a.z, o.b.z);
+        mfma32(acc, o.a.w, o.b.w);
+    };
+    auto stage = [&](int buf, Ops &cur, bool more, auto between) {
+#pragma unroll
+        for (int ks = 0; ks < kGramKT / 8; ++ks) {
+            Ops next = cur;
+            if (ks + 1 < kGramKT / 8) {
+                next = read_ops(buf, ks + 1);
+            } else if (more) {
+                __syncthreads();
+                next = read_ops(buf ^ 1, 0);
+            }
+            mma(cur);
+            if (ks == 0) between();
+            cur = next;
+        }
+    };
+    ld.fetch(0);
+    ld.stash(smem);
+    if (nstage > 1) ld.fetch(1);
+    __syncthreads();
+    Ops cur = read_ops(0, 0);
+    int st = 0;
+    for (; st + 2 < nstage; ++st)
+        stage(st & 1, cur, true, [&] { ld.stash(smem + ((st + 1) & 1) * 2 * kDirPanel); ld.fetch(st + 2); });
+    if (st + 1 < nstage) {
+        stage(st & 1, cur, true, [&] { ld.stash(smem + ((st + 1) & 1) * 2 * kDirPanel); });
+        ++st;
+    }
+    stage(st & 1, cur, false, [] {});
+    mfma_drain();
+
+    // register v of lane (li, lh) holds row 8 * (v / 4) + 4 * lh + (v % 4), column li of the block: the ballot
+    // over register v is columns 0..31 of row 8 * (v / 4) + (v % 4) in its low half and of the row 4 below in
+    // its high half
+    const int32_t row0 = ta * kDirTile + wr * 32, b = tb * kDirTile + wc * 32 + li;
+    uint32_t *m32 = reinterpret_cast<uint32_t *>(mask);       // (little-endian halves of the 64-bit words)
+    uint32_t n_near = 0;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int32_t a = row0 + 8 * (v >> 2) + 4 * lh + (v & 3);
+        const bool live = a < L && b < L && a != b;
+        const float ag = fabsf(acc[v]);
+        const uint64_t bal = __ballot(live && !(ag < rho));
+        if (near_pairs) n_near += (uint32_t)__popcll(__ballot(live && b > a && fabsf(ag - rho) <= 1e-6f));
+        if (li == 0) m32[((int64_t)a * (Lpad / 64) + tb) * 2 + wc] = lh ? (uint32_t)(bal >> 32) : (uint32_t)bal;
+    }
+    if (near_pairs && n_near && lane == 0) atomicAdd(near_pairs, (int32_t)n_near);
+    if (gram) {
+        store_block(gram, Lpad, row0, tb * kDirTile + wc * 32, acc, li, lh);
+        if (ta != tb) store_block_t(gram, Lpad, row0, tb * kDirTile + wc * 32, acc, li, lh);
+    }
+}
+
 // Dynamic dependencies: the Gram of the movers only.  Their number is known on the device alone,
 // so the launch has a fixed number of resident workgroups, which read the decomposition the mover
 // kernel chose.  Each takes the job with its own number first; when there are more jobs than workgroups the
@@ -1160,6 +1366,17 @@ bool gram256_default(int64_t n, int32_t lpad, int32_t layout, int32_t deps)
     return work >= (int64_t)180 * kBigWorkgroups;
 }
 
+// Where the 64 x 64 tiles that write the conflict bits themselves (k_gram_direct) are the default: columns short
+// enough that a tile's whole row range is a short job, and a list long enough that such tiles fill the chip.
+// (Measured, tiles + sum of the K-slices against this kernel, in us: 256 rows x 1024 candidates 22 / 13, x 4096
+// 95 / 54; 500 x 1024 27 / 18, x 2000 50 / 36, x 4096 134 / 93; 1000 x 1024 35 / 29, x 1536 49 / 46, x 4096 217 / 172;
+// 2000 x 1024 44 / 50, x 2000 113 / 117, x 3072 214 / 188, x 4096 362 / 324.)
+bool gram_direct_default(int64_t n, int32_t lpad)
+{
+    const int64_t T = lpad / kDirTile;
+    return (n <= 1024 && T >= 16) || (n <= 2048 && T >= 48);
+}
+
 // Bytes of the route's tables in the workspace: the queue, then first slot and slot count per tile.
 size_t gram256_table_bytes(int64_t n, int32_t lpad)
 {
@@ -1363,8 +1580,10 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
     const bool big = !dynamic && h->big_items > 0;          // 256-wide tiles (see k_gram_tiles256)
     const BigPiece *items = reinterpret_cast<const BigPiece *>(h->base + h->ws.big_tables);
     RoundScalars *sc = h->at<RoundScalars>(h->ws.scalars);
+    const bool direct = !dynamic && gram_direct_on(h);      // 64 x 64 tiles straight to conflict bits (see k_gram_direct)
     if (part == 1) {
         float *gram = h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr;
+        if (direct) return hipSuccess;                      // the tile kernel has written the mask
         if (big) {
             const int32_t T2 = (h->Lpad + kBigTile - 1) / kBigTile;
             hipLaunchKernelGGL(k_gram_mask256, dim3((unsigned)(T2 * (T2 + 1) / 2 * kMaskGroups)), dim3(256), 0, h->stream, P, g,
@@ -1399,13 +1618,23 @@ hipError_t launch_gram_dense(strads_lasso *h, int part)
 #undef STRADS_GRAM_DYN
         return launch_status(h->stream);
     }
-    const int32_t n_jobs = g.T * (g.T - 1) / 2 * g.split_off + g.T * g.split_diag;
     CandDots cd = {};
     unsigned extra = 0;
     if (dots_ride_with_gram(h)) {
         cd = cand_dots_args(h);
         extra = cd.wide ? (unsigned)cd.L : (unsigned)((cd.L + 3) / 4);
     }
+    if (direct) {
+        const int32_t T = h->Lpad / kDirTile, n_tiles = T * (T + 1) / 2;
+        float *gram = h->cfg.keep_gram ? h->at<float>(h->ws.gram) : nullptr;
+#define STRADS_GRAM_DIRECT(LD) hipLaunchKernelGGL(k_gram_direct<LD>, dim3((unsigned)n_tiles + extra), dim3(256), kDirLdsBytes, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), h->L, h->Lpad, gc, h->cfg.rho, h->at<uint64_t>(h->ws.mask), gram, &sc->near_rho_pairs, n_tiles, cd)
+        if (load == kLoadGeno2) STRADS_GRAM_DIRECT(kLoadGeno2);
+        else if (load == kLoadVec4) STRADS_GRAM_DIRECT(kLoadVec4);
+        else STRADS_GRAM_DIRECT(kLoadScalar);
+#undef STRADS_GRAM_DIRECT
+        return launch_status(h->stream);
+    }
+    const int32_t n_jobs = g.T * (g.T - 1) / 2 * g.split_off + g.T * g.split_diag;
     const dim3 grid((unsigned)n_jobs + extra);
     const int32_t *jobtab = h->jobtab_on ? reinterpret_cast<const int32_t *>(h->base + h->ws.jobtab) : nullptr;
 #define STRADS_GRAM(LD) hipLaunchKernelGGL(k_gram_tiles<LD>, grid, dim3(256), lds, h->stream, h->cfg.x, h->cfg.n, h->at<int32_t>(h->ws.cand), g, gc, jobtab, P, n_jobs, cd)

@@ -120,6 +120,8 @@ struct strads_lasso {
     int32_t tile256;    // Gram of long lists in 256 x 256 tiles: 0 never, 1 where it is the default, 2 wherever the
                         // workspace has the partial planes for it (tuning "gram_tile256", default 1)
     int32_t big_items;  // items in that route's queue; 0: the 128 x 128 kernel is used
+    int32_t direct;     // Gram of a long list over short columns in 64 x 64 tiles that write the conflict bits themselves:
+                        // 0 never, 1 where it is the default, 2 wherever it applies (tuning "gram_direct", default 1)
     int32_t select_cap;
     int64_t round;
     bool vec4;          // dense columns are 16-byte aligned (N % 4 == 0 and x aligned)
@@ -178,6 +180,7 @@ size_t gram_partial_floats(int64_t n, int32_t lpad, bool dynamic);   // floats o
 void gram_shape_table(int64_t n, int32_t lpad, GramShape *out);      // out[t], t = 0 .. lpad/kGramTile
 bool gram256_default(int64_t n, int32_t lpad, int32_t layout, int32_t deps);
 int32_t gram256_items(int64_t n, int32_t lpad);                      // items (= tile slots) of the 256-wide route's queue
+bool gram_direct_default(int64_t n, int32_t lpad);                   // see k_gram_direct
 size_t gram256_table_bytes(int64_t n, int32_t lpad);
 int32_t gram256_tables(int64_t n, int32_t lpad, void *out);          // host image of ws.big_tables
 int32_t gram256_plan_host(int64_t n, int32_t lpad, int32_t cap, int32_t *items5, int32_t *first, int32_t *count);
@@ -232,6 +235,14 @@ inline bool dots_ride_with_gram(const strads_lasso *h)
 {
     return h->dots_with_gram && h->cfg.deps == STRADS_DEPS_STATIC && h->cfg.layout == STRADS_LAYOUT_DENSE_COLMAJOR &&
            h->n_lanes == 1 && h->L <= kShortList && h->big_items == 0;
+}
+// Whether Step 2's Gram goes straight to conflict bits in 64 x 64 tiles (k_gram_direct): Algorithm 1's rule, a dense
+// or packed design, the automatic K decomposition, and the 256-wide tiles not in use.
+inline bool gram_direct_on(const strads_lasso *h)
+{
+    if (h->cfg.deps != STRADS_DEPS_STATIC || h->cfg.layout == STRADS_LAYOUT_CSC || h->big_items > 0 || h->split_user > 0)
+        return false;
+    return h->direct == 2 || (h->direct == 1 && gram_direct_default(h->cfg.n, h->Lpad));
 }
 struct CandDots;
 CandDots cand_dots_args(strads_lasso *h);                 // arguments of the candidates' tentative updates

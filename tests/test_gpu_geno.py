@@ -40,6 +40,24 @@ def test_teacher_forced_rounds(kw, rounds):
     print("logged:", log)
 
 
+@pytest.mark.parametrize("kw,forced", [(dict(n=500, j=2300, nnz=20, l_prime=2000), False),
+                                       (dict(n=463, j=3000, nnz=10, l_prime=300), True),
+                                       (dict(n=17, j=300, nnz=4, l_prime=130), True),
+                                       (dict(n=5, j=7, nnz=2, l_prime=7), True)])
+def test_rounds_with_the_gram_in_64_wide_tiles(kw, forced):
+    """The tile kernel for long lists over short columns (64 x 64 tiles that write the conflict bits themselves)
+    on the packed design: by default at the third configuration's list length, forced onto shorter lists."""
+    p = si.make("c3_genotype_packed", **kw)
+    g, o = _pair(p)
+    if forced:
+        g.set_tuning("gram_direct", 2)
+    assert g.gram_tile_edge() == 64
+    log = []
+    for _ in range(4):
+        assert _check_round(g, o, log, teacher_forced=True)
+    print("logged:", log)
+
+
 def test_same_trajectory_as_the_decoded_fp32_design():
     # the decoded matrix given as a dense fp32 design: identical candidate lists and kept sets,
     # beta and r equal up to summation order

@@ -226,7 +226,7 @@ def test_gram_in_256_wide_tiles_matches_oracle(n, j, l_prime):
     last K stage, a single diagonal tile and one-stage items."""
     p = si.make("c2_dense_block_corr", n=n, j=j, nnz=5, l_prime=l_prime)
     g, o = _pair(p)
-    assert g.gram_tile_edge() == 128
+    assert g.gram_tile_edge() == (64 if (n, l_prime) == (260, 1100) else 128)   # (1100 candidates over 260 rows: 64-wide)
     g.set_tuning("gram_tile256", 2)
     assert g.gram_tile_edge() == 256
     for _ in range(2):                                  # twice: stale tile slots must not leak into a round
@@ -238,6 +238,37 @@ def test_gram_in_256_wide_tiles_matches_oracle(n, j, l_prime):
         assert np.array_equal(_np(lr["G"]), _np(lr["G"]).T)
         kept = _np(lr["kept_pos"])
         assert np.array_equal(kept, orc.greedy_filter(_np(lr["G"]), o.rho, o.p_max))
+
+
+@pytest.mark.parametrize("n,j,l_prime,forced", [(500, 2300, 2000, False), (1000, 1700, 1600, False),
+                                                (1000, 900, 700, True), (1001, 500, 300, True), (37, 300, 260, True),
+                                                (3, 200, 130, True), (64, 90, 64, True), (8, 3, 2, True)])
+def test_gram_in_64_wide_tiles_matches_oracle(n, j, l_prime, forced):
+    """A long list over short columns is multiplied in 64 x 64 tiles that run over all rows and write the conflict
+    bits themselves (no K-slices, no slot sum).  Whole Gram against the oracle and the kept set against the greedy
+    walk on it: the shapes that take the route by default, and the route forced onto short lists (unaligned
+    columns, a single ragged K stage, one tile)."""
+    p = si.make("c2_dense_block_corr", n=n, j=j, nnz=5, l_prime=l_prime)
+    g, o = _pair(p)
+    if forced:
+        assert g.gram_tile_edge() == 128
+        g.set_tuning("gram_direct", 2)
+    assert g.gram_tile_edge() == 64
+    for _ in range(2):
+        g.round()
+        lr = g.last_round(want_gram=True)
+        cand, G = _np(lr["cand"]), _np(lr["G"])
+        _assert_close(G, orc.gram_dense(o.x, cand), DOT_RTOL, 1e-6, "gram")
+        assert np.array_equal(G, G.T)
+        assert np.array_equal(_np(lr["kept_pos"]), orc.greedy_filter(G, o.rho, o.p_max))
+    h, o2 = _pair(p)                                   # and whole rounds against the oracle, stage by stage
+    if forced:
+        h.set_tuning("gram_direct", 2)
+    log = []
+    for _ in range(3):
+        assert _check_round(h, o2, log, teacher_forced=True)
+    g.set_tuning("gram_direct", 0)
+    assert g.gram_tile_edge() == 128
 
 
 @pytest.mark.parametrize("n,j,l_prime", [(4096, 4500, 4300), (4096, 8192, 8192), (45056, 2100, 2048)])
