@@ -18,11 +18,12 @@ def _gpu():
 
 @pytest.mark.parametrize("kw", [dict(), dict(n_shards=3), dict(dynamic=True), dict(n_shards=2, dynamic=True),
                                 dict(priority="uniform", no_deps=True, p_max=64), dict(tile256=True),
-                                dict(tile256=True, n_shards=2)])
+                                dict(tile256=True, n_shards=2), dict(direct=True), dict(direct=True, n_shards=2)])
 def test_graph_replays_equal_eager_rounds(kw):
     pk = _gpu()
     kw = dict(kw)
     tile256 = kw.pop("tile256", False)      # the Gram in 256-wide tiles from a queue, whose position the mask kernel resets
+    direct = kw.pop("direct", False)        # the Gram in 64-wide tiles that write the conflict bits themselves
     dev = torch.device("cuda:0")
     p = si.make("c2_dense_block_corr", n=1000, j=3000, nnz=20, l_prime=300)
     side = torch.cuda.Stream(dev)               # the legacy default stream cannot be captured
@@ -34,6 +35,10 @@ def test_graph_replays_equal_eager_rounds(kw):
             g.set_tuning("gram_tile256", 2)
             e.set_tuning("gram_tile256", 2)
             assert g.gram_tile_edge() == e.gram_tile_edge() == 256
+        if direct:
+            g.set_tuning("gram_direct", 2)
+            e.set_tuning("gram_direct", 2)
+            assert g.gram_tile_edge() == e.gram_tile_edge() == 64
         g.set_tuning("graph_rounds", 4)
         e.set_tuning("graph_rounds", 0)
         total = 0

@@ -58,7 +58,8 @@ def test_one_coordinate_per_shard_is_cyclic_coordinate_descent():
 
 
 @pytest.mark.parametrize("kw", [dict(n_shards=2), dict(n_shards=4), dict(n_shards=3, dynamic=True),
-                                dict(n_shards=2, tile256=True), dict(n_shards=2, tile256=True, shape=(400, 8000, 2600))])
+                                dict(n_shards=2, tile256=True), dict(n_shards=2, tile256=True, shape=(400, 8000, 2600)),
+                                dict(n_shards=2, shape=(400, 8000, 2600), edge=64)])
 def test_overlapped_run_equals_serialised_rounds_and_tracks_the_oracle(kw):
     pk = _gpu()
     dev = torch.device("cuda:0")
@@ -67,6 +68,7 @@ def test_overlapped_run_equals_serialised_rounds_and_tracks_the_oracle(kw):
     # (2600 candidates: 41 mask words per row, where the greedy walk skips the chunks of candidates that the
     # shard's own slot sum has not marked; the marks of overlapping shards must not mix)
     n, j, l_prime = kw.pop("shape", (2000, 8000, 500))
+    edge = kw.pop("edge", 0)                # (the last case: short columns under a long list, 64-wide tiles by default)
     p = si.make("c2_dense_block_corr", n=n, j=j, nnz=40, l_prime=l_prime)
     base = dict(x=p.x.to(dev), y=p.y.to(dev), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed)
     a, b, c = (pk.StradsLasso(**base, **kw) for _ in range(3))
@@ -74,6 +76,8 @@ def test_overlapped_run_equals_serialised_rounds_and_tracks_the_oracle(kw):
         for h in (a, b, c):
             h.set_tuning("gram_tile256", 2)
             assert h.gram_tile_edge() == 256
+    if edge:
+        assert a.gram_tile_edge() == edge
     o = OracleLasso(x=p.x.numpy(), y=p.y.numpy(), lam=p.lam, rho=p.rho, eta=p.eta, l_prime=p.l_prime, seed=p.seed, **kw)
     R = 40
     ia = a.run(R)                           # one call: the shards overlap
