@@ -331,7 +331,7 @@ __global__ __launch_bounds__(1024) void k_residual_rows(const float *__restrict_
     extern __shared__ int32_t rows_lds[];       // [lpad] mover columns, then [lpad] their changes (8 * lpad bytes)
     int32_t *mcol = rows_lds;
     float *mdel = reinterpret_cast<float *>(rows_lds + lpad);
-    __shared__ uint32_t wcnt[16];
+    __shared__ uint32_t wcnt[128];
     __shared__ float4 red[16][64];
     __shared__ float wmax[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -358,29 +358,42 @@ __global__ __launch_bounds__(1024) void k_residual_rows(const float *__restrict_
     const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
     const float4 r_old = (wave == 0 && i < N) ? *reinterpret_cast<const float4 *>(r + i) : zero4;
     const int k = sc->n_kept;
-    uint32_t tot = 0;
+    // The movers (delta != 0) of the kept list, in list order.  Entry p * 1024 + tid belongs to group p * 16 + wave
+    // (64 consecutive entries); the groups' mover counts meet in LDS once, every wavefront takes their running sum
+    // itself (two groups per lane), and each mover's place is its group's offset plus its rank in the group:
+    // two barriers whatever the length of the list.
+    static_assert(kMaxPass * 16 == 128, "two groups per lane");
     float dmax = 0.f;
+    uint64_t ms[kMaxPass];
 #pragma unroll
-    for (int p = 0; p < kMaxPass; ++p) {        // the movers (delta != 0) of the kept list, in list order
-        if (p * 1024 >= k) break;               // uniform
+    for (int p = 0; p < kMaxPass; ++p) {
         const int a = p * 1024 + tid;
-        const float d = a < k ? dq[p] : 0.f;
-        const bool mv = d != 0.f;
-        const uint64_t m = __ballot(mv);
-        if (lane == 0) wcnt[wave] = (uint32_t)__popcll(m);
-        __syncthreads();
-        uint32_t before = 0, here = 0;
-#pragma unroll
-        for (int w = 0; w < 16; ++w) { const uint32_t v = wcnt[w]; if (w < wave) before += v; here += v; }
-        if (mv) {
-            const uint32_t pos = tot + before + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-            mcol[pos] = cq[p];
-            mdel[pos] = d;
-        }
-        tot += here;
-        dmax = fmaxf(dmax, fabsf(d));
-        __syncthreads();
+        if (a >= k) dq[p] = 0.f;
+        ms[p] = __ballot(dq[p] != 0.f);
+        if (lane == 0) wcnt[p * 16 + wave] = (uint32_t)__popcll(ms[p]);
+        dmax = fmaxf(dmax, fabsf(dq[p]));
     }
+    __syncthreads();
+    const uint32_t c0 = wcnt[2 * lane], c1 = wcnt[2 * lane + 1];
+    uint32_t incl = c0 + c1;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t v = __shfl_up(incl, off);
+        if (lane >= off) incl += v;
+    }
+    const uint32_t before0 = incl - c0 - c1, before1 = incl - c1;     // movers before groups 2 * lane and 2 * lane + 1
+    const uint32_t tot = __shfl(incl, 63);
+#pragma unroll
+    for (int p = 0; p < kMaxPass; ++p) {
+        const int grp = p * 16 + wave;
+        const uint32_t e0 = __shfl(before0, grp >> 1), e1 = __shfl(before1, grp >> 1);
+        if (dq[p] != 0.f) {
+            const uint32_t pos = ((grp & 1) ? e1 : e0) + (uint32_t)__popcll(ms[p] & ((1ull << lane) - 1ull));
+            mcol[pos] = cq[p];
+            mdel[pos] = dq[p];
+        }
+    }
+    __syncthreads();
 
     float4 acc = zero4;
     if (i < N) {
