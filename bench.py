@@ -402,7 +402,7 @@ def kkt_pass(g, p, shards, torch):
 def gram_roofline(p, L, stage, workload, rides, tile_edge=128):
     gram_flops = float(p.n) * L * (L - 1)          # algorithmic: every unordered pair once, 2 flops per row
     ach = gram_flops / (stage["gram_tiles"] * 1e-3) / 1e12
-    kernel = "k_gram_tiles256" if tile_edge == 256 else "k_gram_tiles"
+    kernel = {256: "k_gram_tiles256", 64: "k_gram_direct"}.get(tile_edge, "k_gram_tiles")
     tr = measured_traffic(kernel, workload, "with_dots" if rides else "tiles_only")
     return {"bound": "mfma", "kernel": kernel, "achieved": round(ach, 3),
             "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_FP32_PEAK_TFLOPS, 4),
