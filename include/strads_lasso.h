@@ -316,6 +316,14 @@ int strads_lasso_set_tuning(strads_lasso_t *h, const char *name, int64_t value);
 int strads_lasso_gram256_plan(int64_t n, int32_t l, int32_t items_cap, int32_t *n_items, int32_t *items,
                               int32_t *first_slot, int32_t *n_slots);
 
+/* Host only, no GPU call: the tile kernel that Step 2's Gram (Section 2.1, Step 2: the pairwise dependencies of
+ * the P' candidates) of l candidates over n rows takes by default, for a design of the given layout
+ * (STRADS_LAYOUT_*) under the given dependency rule (STRADS_DEPS_*): edge (HOST int32) as
+ * strads_lasso_gram_tile_edge reports it.  A handle may differ: fp32 columns that are not 16-byte aligned never
+ * take the 256 x 256 tiles, and tunings ("gram_tile256", "gram_direct", "gram_split_k") override the default.
+ * STRADS_E_INVALID_ARG for n < 1, l outside 1 .. STRADS_MAX_L_PRIME, an unknown layout or rule, or a NULL edge. */
+int strads_lasso_gram_default_tile_edge(int64_t n, int32_t l, int32_t layout, int32_t deps, int32_t *edge);
+
 /* Which tile kernel forms Step 2's Gram for this handle as it is tuned now: edge (HOST int32) = 256 (tiles of
  * 256 x 256 from a queue, see "gram_tile256"), 128 (tiles of 128 x 128 with K-slices), 64 (tiles of 64 x 64 over
  * all rows, see "gram_direct"), or 0 (a sparse design or no dependency check: no tile kernel). */

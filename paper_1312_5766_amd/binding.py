@@ -36,7 +36,7 @@ EXPORTS = [
     "strads_lasso_last_round", "strads_lasso_last_candidates", "strads_lasso_stage_keys", "strads_lasso_stage_filter",
     "strads_lasso_set_tuning", "strads_lasso_stage_times", "strads_lasso_last_kkt_ms", "strads_lasso_destroy",
     "strads_lasso_strerror", "strads_lasso_filter_static", "strads_lasso_debug_build", "strads_lasso_gram256_plan",
-    "strads_lasso_gram_tile_edge",
+    "strads_lasso_gram_tile_edge", "strads_lasso_gram_default_tile_edge",
 ]
 
 
@@ -92,6 +92,7 @@ def load():
     L.strads_lasso_filter_static.argtypes = [vp, C.c_int32, C.c_float, C.c_int32, vp, vp, vp]
     L.strads_lasso_debug_build.argtypes = []
     L.strads_lasso_gram_tile_edge.argtypes = [vp, C.POINTER(C.c_int32)]
+    L.strads_lasso_gram_default_tile_edge.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
     L.strads_lasso_gram256_plan.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.POINTER(C.c_int32), vp, vp, vp]
     L.strads_lasso_destroy.argtypes = [vp]
     L.strads_lasso_destroy.restype = None
@@ -124,6 +125,14 @@ def strads_lasso_workspace_bytes(n, j, l_prime, layout=LAYOUT_DENSE, keep_gram=F
     cfg = Config(n=n, j=j, layout=layout, l_prime=l_prime, keep_gram=int(keep_gram), max_col_nnz=int(max_col_nnz),
                  deps=DEPS_DYNAMIC if dynamic else DEPS_STATIC, n_shards=int(n_shards))
     return int(load().strads_lasso_workspace_bytes(C.byref(cfg)))
+
+
+def strads_lasso_gram_default_tile_edge(n: int, l: int, layout: int = LAYOUT_DENSE, deps: int = DEPS_STATIC) -> int:
+    """Host only.  Edge of the tiles Step 2's Gram of l candidates over n rows takes by default (256, 128, 64, or 0)."""
+    edge = C.c_int32(-1)
+    _check(load().strads_lasso_gram_default_tile_edge(int(n), int(l), int(layout), int(deps), C.byref(edge)),
+           "strads_lasso_gram_default_tile_edge")
+    return int(edge.value)
 
 
 def strads_lasso_gram256_plan(n: int, l: int):

@@ -725,6 +725,19 @@ int strads_lasso_gram256_plan(int64_t n, int32_t l, int32_t items_cap, int32_t *
     return STRADS_OK;
 }
 
+int strads_lasso_gram_default_tile_edge(int64_t n, int32_t l, int32_t layout, int32_t deps, int32_t *edge)
+{
+    if (n < 1 || l < 1 || l > STRADS_MAX_L_PRIME || !edge || layout < STRADS_LAYOUT_DENSE_COLMAJOR ||
+        layout > STRADS_LAYOUT_GENO2 || deps < STRADS_DEPS_STATIC || deps > STRADS_DEPS_NONE)
+        return STRADS_E_INVALID_ARG;
+    const int32_t lpad = (l + kGramTile - 1) / kGramTile * kGramTile;
+    if (layout == STRADS_LAYOUT_CSC || deps == STRADS_DEPS_NONE) *edge = 0;
+    else if (gram256_default(n, lpad, layout, deps)) *edge = 256;
+    else if (deps == STRADS_DEPS_STATIC && gram_direct_default(n, lpad)) *edge = 64;
+    else *edge = kGramTile;
+    return STRADS_OK;
+}
+
 int strads_lasso_gram_tile_edge(strads_lasso_t *h, int32_t *edge)
 {
     if (!h || !edge) return STRADS_E_INVALID_ARG;

@@ -213,6 +213,30 @@ def test_gram256_plan_rejects_bad_arguments():
     assert n_items.value == 1 and list(buf) == [0, 0, 0, 4, 0]
 
 
+def test_default_tile_kernel_by_shape():
+    """Which tile kernel forms Step 2's Gram by default (host-side rule, no GPU): the five configurations, the
+    borders of the rules, and the layouts and dependency rules that have no choice."""
+    edge = pk.strads_lasso_gram_default_tile_edge
+    assert edge(50000, 8000) == 256                  # long list over long columns: 256-wide tiles from a queue
+    assert edge(10000, 1000) == 128 and edge(1000, 200) == 128
+    assert edge(500, 2000) == 64                     # short columns under a long list: 64-wide tiles, no K-slices
+    assert edge(500, 2000, pk.LAYOUT_GENO2) == 64
+    assert edge(4096, 4097) == 256 and edge(4096, 4096) == 128 and edge(4092, 8000) == 128
+    assert edge(4094, 8000) == 128                   # columns of a length that is no multiple of 4 floats
+    assert edge(50000, 2048) == 256 and edge(50000, 1024) == 128     # enough stages of work per compute unit or not
+    assert edge(1024, 1024) == 64 and edge(1024, 896) == 128 and edge(1025, 1024) == 128
+    assert edge(2048, 3072) == 64 and edge(2048, 2944) == 128 and edge(2049, 3072) == 128
+    assert edge(500, 2000, pk.LAYOUT_DENSE, pk.DEPS_DYNAMIC) == 128  # the movers' Gram is tiled on the device
+    assert edge(500, 2000, pk.LAYOUT_CSC) == 0 and edge(500, 2000, pk.LAYOUT_DENSE, pk.DEPS_NONE) == 0
+    assert edge(50000, 8000, pk.LAYOUT_GENO2) == 128
+    lib, out = pk.load(), C.c_int32(7)
+    for bad in ((0, 10, 0, 0), (10, 0, 0, 0), (10, pk.MAX_L_PRIME + 1, 0, 0), (10, 10, 3, 0), (10, 10, -1, 0),
+                (10, 10, 0, 3), (10, 10, 0, -1)):
+        assert lib.strads_lasso_gram_default_tile_edge(*bad, C.byref(out)) == pk.E_INVALID_ARG
+    assert lib.strads_lasso_gram_default_tile_edge(10, 10, 0, 0, None) == pk.E_INVALID_ARG
+    assert out.value == 7
+
+
 def test_gram_tile_edge_rejects_null_arguments():
     edge = C.c_int32(5)
     assert pk.load().strads_lasso_gram_tile_edge(None, C.byref(edge)) == pk.E_INVALID_ARG
